@@ -1,0 +1,194 @@
+/*
+ * libco3 -- the per-iteration CO3 gradient codec on one AMD MI355X (gfx950).
+ *
+ * C ABI of the hot path of "Communication-Efficient Federated DNN Training: Convert,
+ * Compress, Correct" (arXiv 2204.08211): error correction with memory decay, fp conversion,
+ * element-wise Huffman coding, and the parameter server's decode + average.  U users are a
+ * batch dimension on one GPU.  All the arithmetic runs in HIP kernels; there is no CPU
+ * fallback.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are plain
+ *     host memory read (or written) before the call returns.
+ *   - `stream` is a hipStream_t passed as void*; every kernel is enqueued on it and no call
+ *     synchronises unless its comment says so.
+ *   - every function returns a co3_status; data-dependent conditions (non-finite inputs,
+ *     clamped inputs, symbols without a code, stream capacity, corrupt streams) are ADDED to
+ *     the caller's device counter block `status` (CO3_STATUS_WORDS x uint64), which the caller
+ *     clears and reads.
+ *   - notation follows the paper: g gradient, m memory, gamma memory-decay coefficient,
+ *     [sgn,exp,mant] float format, b = h_Hf(ghat) the binary string, r its length.
+ */
+#ifndef CO3_H
+#define CO3_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CO3_CHUNK 4096u           /* elements per chunk (32-bit aligned unit of the stream) */
+#define CO3_SUB 64u               /* elements per sub-chunk (unit one decoder lane owns)    */
+#define CO3_SUBS_PER_CHUNK 64u
+#define CO3_MAX_CODE_LEN 64
+#define CO3_STATUS_WORDS 8
+
+typedef enum {
+    CO3_OK = 0,
+    CO3_ERR_ARG = -1,       /* null pointer, bad size, misaligned buffer                    */
+    CO3_ERR_FORMAT = -2,    /* [sgn,exp,mant] / bias outside what the library supports      */
+    CO3_ERR_CAPACITY = -3,  /* workspace or stream buffer too small (host-detectable part)  */
+    CO3_ERR_CODELEN = -4,   /* a Huffman code would need more than CO3_MAX_CODE_LEN bits     */
+    CO3_ERR_CORRUPT = -5,
+    CO3_ERR_HIP = -6        /* a HIP runtime call failed                                    */
+} co3_status;
+
+/* indices into the device counter block */
+enum {
+    CO3_STAT_NONFINITE = 0, /* inputs v = g + gamma m that are NaN or +-Inf                  */
+    CO3_STAT_CLAMPED = 1,   /* finite inputs with |v| above the largest representative      */
+    CO3_STAT_NOCODE = 2,    /* symbols met by the encoder that have no codeword             */
+    CO3_STAT_CAPACITY = 3,  /* chunks not written because the stream buffer is too small    */
+    CO3_STAT_CODELEN = 4,   /* code tables built on the device that needed > 64 bits        */
+    CO3_STAT_CORRUPT = 5    /* sub-chunks the decoder could not decode consistently         */
+};
+
+/* Float format of Q_fp: one sign bit, exp_bits exponent bits, mant_bits mantissa bits
+ * (Sec. IV-A (i); the sets M and E of Sec. V-B).  Requires exp_bits >= 2 and
+ * 1 + exp_bits + mant_bits <= 8 (a symbol is one byte).                                    */
+typedef struct {
+    int32_t exp_bits;
+    int32_t mant_bits;
+} co3_format;
+
+/* One DNN layer of the flat gradient (Sec. II-D: layers are independent and differently
+ * distributed; Sec. IV-A (ii): one code per layer).  Segments must be contiguous, in order,
+ * and cover [0, d).  `codebook` selects the code table within a code-table set.            */
+typedef struct {
+    uint64_t offset;
+    uint64_t length;
+    int32_t codebook;
+    int32_t reserved;
+} co3_segment;
+
+typedef struct co3_plan co3_plan;           /* layout of one round: library-owned           */
+typedef struct co3_codebook co3_codebook;   /* a set of Huffman code tables: library-owned  */
+
+/* ---- plan: problem statement of Sec. II-B (U users, d-dimensional gradients, the float
+ * format and, per user and layer, the exponent bias) ------------------------------------
+ * bias is host memory, [U][nseg]: the value exponent of exponent field f is f - bias, i.e.
+ * the paper's c_scale = 2^b has b = (2^(exp_bits-1) - 1) - bias.  Required: bias <= 127 (the
+ * smallest normal magnitude is a normal fp32) and (2^exp_bits - 2) - bias <= 100.  segments == NULL means one segment covering [0, d) with
+ * codebook 0.  per_user_books != 0 gives every user its own tables (table index
+ * u * books_per_user + segment.codebook) instead of one table per layer shared by all users.
+ * Allocates small device tables; synchronises the device.  Not on the per-iteration path:
+ * the paper holds the bias for several epochs (Sec. VI).                                   */
+int co3_plan_create(co3_format format, uint32_t U, uint64_t d, uint32_t nseg,
+                    const co3_segment *segments, const int32_t *bias, int32_t per_user_books,
+                    co3_plan **out);
+/* Replace the [U][nseg] bias table (host memory).  Synchronises `stream`.                  */
+int co3_plan_set_bias(co3_plan *plan, const int32_t *bias, void *stream);
+void co3_plan_destroy(co3_plan *plan);
+uint64_t co3_plan_num_chunks(const co3_plan *plan);     /* chunks per user                  */
+uint32_t co3_plan_num_books(const co3_plan *plan);      /* tables in a matching set         */
+uint32_t co3_plan_alphabet(const co3_plan *plan);       /* A = 2^(1+exp_bits+mant_bits)     */
+/* bytes of the `symbols` buffer of co3_encode_args / co3_decode_args (U*d plus padding)    */
+size_t co3_plan_symbols_bytes(const co3_plan *plan);
+/* bytes of the `workspace` buffer of co3_encode_args                                       */
+size_t co3_plan_workspace_bytes(const co3_plan *plan);
+/* words per user that hold any stream whose longest codeword has max_code_len bits         */
+uint64_t co3_plan_stream_words(const co3_plan *plan, uint32_t max_code_len);
+
+/* ---- code tables: h_Hf of Sec. IV-A (ii) ------------------------------------------------
+ * co3_build_codebook: Huffman codes for nbooks tables from integer weights (host memory,
+ * [nbooks][A], weight 0 = symbol has no code); weights == NULL only allocates the set, to be
+ * filled by co3_build_codebook_device.  Ties are broken by (weight, key) with leaf key =
+ * symbol and internal key = A + creation order; codes are canonical by (length, symbol).
+ * Runs on the host, uploads the tables, synchronises the device.
+ * Errors: CO3_ERR_CODELEN if a code would exceed 64 bits, CO3_ERR_ARG if a table's weights
+ * sum to 2^64 or more.                                                                     */
+int co3_build_codebook(co3_format format, uint32_t nbooks, const uint64_t *weights,
+                       co3_codebook **out);
+/* Rebuild every table of `books` on the device from device weights [nbooks][A] (e.g. the
+ * histogram co3_encode wrote), with no host round trip.  Tables needing more than 64 bits
+ * are left empty and counted in status[CO3_STAT_CODELEN].                                  */
+int co3_build_codebook_device(co3_codebook *books, const uint64_t *weights, uint64_t *status,
+                              void *stream);
+/* Copy one table to host memory (len[A], code[A]) for inspection.  Synchronises `stream`.  */
+int co3_codebook_export(const co3_codebook *books, uint32_t book, uint8_t *len, uint64_t *code,
+                        void *stream);
+uint32_t co3_codebook_num_books(const co3_codebook *books);
+void co3_codebook_destroy(co3_codebook *books);
+
+/* ---- user side: Algorithm 1 lines 8-10 for all U users -----------------------------------
+ * v = g + gamma m (eq. (f_error_fb)), ghat = Q_fp(v), m' = v - ghat, b = h_Hf(ghat).
+ * mode CO3_BOOK_FIXED encodes with `books` as they are (a code designed beforehand, e.g. from
+ * the GenNorm model); CO3_BOOK_EMPIRICAL first rebuilds `books` on the device from this
+ * round's symbol histogram.                                                                */
+enum { CO3_BOOK_FIXED = 0, CO3_BOOK_EMPIRICAL = 1 };
+
+typedef struct {
+    const float *g;          /* device [U][row_stride] gradients; 16-byte aligned            */
+    const float *m;          /* device [U][row_stride] memory m_{t-1}                        */
+    float *m_out;            /* device [U][row_stride] memory m_t; may equal m               */
+    uint64_t row_stride;     /* elements between users, >= d, multiple of 4                  */
+    float gamma;             /* memory-decay coefficient                                     */
+    int32_t mode;            /* CO3_BOOK_FIXED or CO3_BOOK_EMPIRICAL                         */
+    co3_codebook *books;     /* set with co3_plan_num_books() tables                         */
+    uint8_t *symbols;        /* device, co3_plan_symbols_bytes(): [U][d] symbols (out)       */
+    uint64_t *hist;          /* device [num_books][A] symbol counts (out; cleared here)      */
+    uint32_t *words;         /* device [U][words_stride] streams (out)                       */
+    uint64_t words_stride;   /* capacity of one user's stream in 32-bit words                */
+    uint64_t *chunk_offset;  /* device [U][num_chunks+1] bit offsets of the chunks (out)     */
+    uint16_t *sub_bits;      /* device [U][num_chunks*64] bits per sub-chunk (out)           */
+    uint64_t *payload_bits;  /* device [U]: r = sum of codeword lengths (out)                */
+    uint64_t *status;        /* device [CO3_STATUS_WORDS] counters (added to)                */
+    void *workspace;         /* device, co3_plan_workspace_bytes()                           */
+    size_t workspace_bytes;
+} co3_encode_args;
+
+/* Enqueues the whole user side on `stream`.  Stream words beyond a user's last chunk are not
+ * written.  A chunk that does not fit words_stride is skipped and counted.                  */
+int co3_encode(const co3_plan *plan, const co3_encode_args *args, void *stream);
+
+/* ---- PS side: Algorithm 1 lines 13-14 ----------------------------------------------------*/
+typedef struct {
+    const uint32_t *words;        /* device [U][words_stride]                                */
+    uint64_t words_stride;
+    const uint64_t *chunk_offset; /* device [U][num_chunks+1]                                */
+    const uint16_t *sub_bits;     /* device [U][num_chunks*64]                               */
+    const co3_codebook *books;
+    uint8_t *symbols;             /* device, co3_plan_symbols_bytes(), or NULL (out)         */
+    float *q;                     /* device [U][q_stride] reconstructed ghat, or NULL (out)  */
+    uint64_t q_stride;
+    uint64_t *status;
+} co3_decode_args;
+
+/* h_Hf^-1 (Sec. II-B (iii): the mapping h is invertible): symbols and/or values of every
+ * user's stream.  Never reads outside [0, words_stride) of a user's stream; inconsistent
+ * sub-chunks are counted in status[CO3_STAT_CORRUPT] and their outputs are unspecified.     */
+int co3_decode(const co3_plan *plan, const co3_decode_args *args, void *stream);
+
+typedef struct {
+    const uint32_t *words;
+    uint64_t words_stride;
+    const uint64_t *chunk_offset;
+    const uint16_t *sub_bits;
+    const co3_codebook *books;
+    float *out;                   /* device [d]: (1/U) sum_u ghat^(u)                         */
+    uint64_t *status;
+} co3_aggregate_args;
+
+/* Decode all U streams and average them (eq. (aggregate hat) without the learning rate):
+ * out[i] = fl32((sum over u = 0..U-1, in fp64, of ghat_i^(u)) * (1.0 / U)).                 */
+int co3_ps_aggregate(const co3_plan *plan, const co3_aggregate_args *args, void *stream);
+
+/* Human-readable name of a status code.                                                     */
+const char *co3_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CO3_H */

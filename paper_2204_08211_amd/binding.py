@@ -1,0 +1,261 @@
+"""Thin ctypes binding of libco3.so (include/co3.h): argument marshalling only.
+
+torch is used for device memory and streams; every step of the codec runs in the HIP
+kernels of the library.  There is no CPU fallback: loading fails loudly when the library has
+not been built (python -m paper_2204_08211_amd.build).
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libco3.so")
+
+CHUNK = 4096
+SUB = 64
+SUBS_PER_CHUNK = 64
+STATUS_WORDS = 8
+(STAT_NONFINITE, STAT_CLAMPED, STAT_NOCODE, STAT_CAPACITY, STAT_CODELEN, STAT_CORRUPT) = range(6)
+BOOK_FIXED, BOOK_EMPIRICAL = 0, 1
+OK, ERR_ARG, ERR_FORMAT, ERR_CAPACITY, ERR_CODELEN, ERR_CORRUPT, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
+
+EXPORTS = [
+    "co3_plan_create", "co3_plan_set_bias", "co3_plan_destroy", "co3_plan_num_chunks", "co3_plan_num_books",
+    "co3_plan_alphabet", "co3_plan_symbols_bytes", "co3_plan_workspace_bytes", "co3_plan_stream_words",
+    "co3_build_codebook", "co3_build_codebook_device", "co3_codebook_export", "co3_codebook_num_books",
+    "co3_codebook_destroy", "co3_encode", "co3_decode", "co3_ps_aggregate", "co3_status_string",
+]
+
+
+class Format(C.Structure):
+    _fields_ = [("exp_bits", C.c_int32), ("mant_bits", C.c_int32)]
+
+
+class Segment(C.Structure):
+    _fields_ = [("offset", C.c_uint64), ("length", C.c_uint64), ("codebook", C.c_int32), ("reserved", C.c_int32)]
+
+
+class EncodeArgs(C.Structure):
+    _fields_ = [("g", C.c_void_p), ("m", C.c_void_p), ("m_out", C.c_void_p), ("row_stride", C.c_uint64),
+                ("gamma", C.c_float), ("mode", C.c_int32), ("books", C.c_void_p), ("symbols", C.c_void_p),
+                ("hist", C.c_void_p), ("words", C.c_void_p), ("words_stride", C.c_uint64),
+                ("chunk_offset", C.c_void_p), ("sub_bits", C.c_void_p), ("payload_bits", C.c_void_p),
+                ("status", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+class DecodeArgs(C.Structure):
+    _fields_ = [("words", C.c_void_p), ("words_stride", C.c_uint64), ("chunk_offset", C.c_void_p),
+                ("sub_bits", C.c_void_p), ("books", C.c_void_p), ("symbols", C.c_void_p), ("q", C.c_void_p),
+                ("q_stride", C.c_uint64), ("status", C.c_void_p)]
+
+
+class AggregateArgs(C.Structure):
+    _fields_ = [("words", C.c_void_p), ("words_stride", C.c_uint64), ("chunk_offset", C.c_void_p),
+                ("sub_bits", C.c_void_p), ("books", C.c_void_p), ("out", C.c_void_p), ("status", C.c_void_p)]
+
+
+class Co3Error(RuntimeError):
+    def __init__(self, where, code):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} ({code})")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library.  Raises if it has not been built: there is no fallback path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2204_08211_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        L.co3_plan_create.argtypes = [Format, C.c_uint32, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p,
+                                      C.c_int32, C.POINTER(C.c_void_p)]
+        L.co3_plan_set_bias.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.co3_plan_destroy.argtypes = [C.c_void_p]
+        L.co3_plan_destroy.restype = None
+        for name, rt in [("co3_plan_num_chunks", C.c_uint64), ("co3_plan_num_books", C.c_uint32),
+                         ("co3_plan_alphabet", C.c_uint32), ("co3_plan_symbols_bytes", C.c_size_t),
+                         ("co3_plan_workspace_bytes", C.c_size_t)]:
+            getattr(L, name).argtypes = [C.c_void_p]
+            getattr(L, name).restype = rt
+        L.co3_plan_stream_words.argtypes = [C.c_void_p, C.c_uint32]
+        L.co3_plan_stream_words.restype = C.c_uint64
+        L.co3_build_codebook.argtypes = [Format, C.c_uint32, C.c_void_p, C.POINTER(C.c_void_p)]
+        L.co3_build_codebook_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.co3_codebook_export.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.co3_codebook_num_books.argtypes = [C.c_void_p]
+        L.co3_codebook_num_books.restype = C.c_uint32
+        L.co3_codebook_destroy.argtypes = [C.c_void_p]
+        L.co3_codebook_destroy.restype = None
+        L.co3_encode.argtypes = [C.c_void_p, C.POINTER(EncodeArgs), C.c_void_p]
+        L.co3_decode.argtypes = [C.c_void_p, C.POINTER(DecodeArgs), C.c_void_p]
+        L.co3_ps_aggregate.argtypes = [C.c_void_p, C.POINTER(AggregateArgs), C.c_void_p]
+        L.co3_status_string.argtypes = [C.c_int]
+        L.co3_status_string.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def status_string(code):
+    return lib().co3_status_string(int(code)).decode()
+
+
+def _check(where, rc):
+    if rc != OK:
+        raise Co3Error(where, rc)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+class Plan:
+    """co3_plan: U users, d elements, [sgn,exp,mant] format, layers and per-(user, layer) bias."""
+
+    def __init__(self, E, M, U, d, bias, seg_len=None, seg_book=None, per_user_books=False):
+        self.E, self.M, self.U, self.d = int(E), int(M), int(U), int(d)
+        self.seg_len = [int(d)] if seg_len is None else [int(x) for x in seg_len]
+        self.nseg = len(self.seg_len)
+        self.seg_book = [0] * self.nseg if seg_book is None else [int(x) for x in seg_book]
+        self.per_user_books = bool(per_user_books)
+        bias = np.ascontiguousarray(np.broadcast_to(np.asarray(bias, dtype=np.int32), (self.U, self.nseg)))
+        segs = (Segment * self.nseg)()
+        off = 0
+        for k, (n, b) in enumerate(zip(self.seg_len, self.seg_book)):
+            segs[k] = Segment(off, n, b, 0)
+            off += n
+        h = C.c_void_p()
+        _check("co3_plan_create", lib().co3_plan_create(Format(self.E, self.M), self.U, self.d, self.nseg,
+                                                        C.cast(segs, C.c_void_p), bias.ctypes.data_as(C.c_void_p),
+                                                        int(self.per_user_books), C.byref(h)))
+        self.handle = h
+        self.bias = bias
+        self.num_chunks = int(lib().co3_plan_num_chunks(h))
+        self.num_books = int(lib().co3_plan_num_books(h))
+        self.A = int(lib().co3_plan_alphabet(h))
+        self.symbols_bytes = int(lib().co3_plan_symbols_bytes(h))
+        self.workspace_bytes = int(lib().co3_plan_workspace_bytes(h))
+        self.sym_stride = (self.d + 15) // 16 * 16
+
+    def set_bias(self, bias, stream=None):
+        bias = np.ascontiguousarray(np.broadcast_to(np.asarray(bias, dtype=np.int32), (self.U, self.nseg)))
+        _check("co3_plan_set_bias", lib().co3_plan_set_bias(self.handle, bias.ctypes.data_as(C.c_void_p), _stream(stream)))
+        self.bias = bias
+
+    def stream_words(self, max_code_len=64):
+        return int(lib().co3_plan_stream_words(self.handle, int(max_code_len)))
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib().co3_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Codebook:
+    """co3_codebook: a set of Huffman code tables living on the device."""
+
+    def __init__(self, handle, E, M, nbooks):
+        self.handle, self.E, self.M, self.nbooks = handle, E, M, nbooks
+        self.A = 1 << (1 + E + M)
+
+    def export(self, book=0, stream=None):
+        length = np.zeros(self.A, np.uint8)
+        code = np.zeros(self.A, np.uint64)
+        _check("co3_codebook_export", lib().co3_codebook_export(self.handle, int(book), length.ctypes.data_as(C.c_void_p),
+                                                                code.ctypes.data_as(C.c_void_p), _stream(stream)))
+        return length, code
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib().co3_codebook_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def co3_build_codebook(E, M, nbooks, weights=None):
+    """Huffman tables from host integer weights [nbooks][A] (None: empty set for device builds)."""
+    h = C.c_void_p()
+    wp = None
+    if weights is not None:
+        weights = np.ascontiguousarray(weights, dtype=np.uint64).reshape(nbooks, 1 << (1 + E + M))
+        wp = weights.ctypes.data_as(C.c_void_p)
+    _check("co3_build_codebook", lib().co3_build_codebook(Format(E, M), int(nbooks), wp, C.byref(h)))
+    return Codebook(h, E, M, nbooks)
+
+
+def co3_build_codebook_device(books, weights, status, stream=None):
+    """Rebuild the set from device weights (uint64 viewed as an int64 tensor [nbooks][A])."""
+    _check("co3_build_codebook_device",
+           lib().co3_build_codebook_device(books.handle, _ptr(weights), _ptr(status), _stream(stream)))
+
+
+class RoundBuffers:
+    """Device buffers of one round, allocated with torch (plumbing only)."""
+
+    def __init__(self, plan, device="cuda:0", words_stride=None, max_code_len=32):
+        import torch
+        self.plan = plan
+        U, nch = plan.U, plan.num_chunks
+        self.words_stride = int(words_stride) if words_stride is not None else plan.stream_words(max_code_len)
+        dev = torch.device(device)
+        self.symbols = torch.zeros(plan.symbols_bytes, dtype=torch.uint8, device=dev)
+        self.hist = torch.zeros((plan.num_books, plan.A), dtype=torch.int64, device=dev)
+        self.words = torch.zeros((U, self.words_stride), dtype=torch.int32, device=dev)
+        self.chunk_offset = torch.zeros((U, nch + 1), dtype=torch.int64, device=dev)
+        self.sub_bits = torch.zeros((U, nch * SUBS_PER_CHUNK), dtype=torch.int16, device=dev)
+        self.payload_bits = torch.zeros(U, dtype=torch.int64, device=dev)
+        self.status = torch.zeros(STATUS_WORDS, dtype=torch.int64, device=dev)
+        self.workspace = torch.zeros(plan.workspace_bytes, dtype=torch.uint8, device=dev)
+
+    def symbols_2d(self):
+        p = self.plan
+        return self.symbols[:p.U * p.sym_stride].view(p.U, p.sym_stride)[:, :p.d]
+
+
+def co3_encode(plan, books, g, m, m_out, gamma, buf, mode=BOOK_EMPIRICAL, stream=None):
+    """User side of one round for all U users (Algorithm 1 lines 8-10).  g, m, m_out are float32
+    device tensors [U][row_stride]; outputs land in `buf` (RoundBuffers)."""
+    assert g.dim() == 2 and g.shape == m.shape == m_out.shape and g.stride(1) == 1
+    assert g.stride(0) == m.stride(0) == m_out.stride(0)
+    a = EncodeArgs(g.data_ptr(), m.data_ptr(), m_out.data_ptr(), g.stride(0), float(np.float32(gamma)), int(mode),
+                   books.handle, buf.symbols.data_ptr(), buf.hist.data_ptr(), buf.words.data_ptr(),
+                   buf.words_stride, buf.chunk_offset.data_ptr(), buf.sub_bits.data_ptr(),
+                   buf.payload_bits.data_ptr(), buf.status.data_ptr(), buf.workspace.data_ptr(),
+                   buf.workspace.numel())
+    _check("co3_encode", lib().co3_encode(plan.handle, C.byref(a), _stream(stream)))
+
+
+def co3_decode(plan, books, buf, symbols=None, q=None, stream=None):
+    """Invert the streams in `buf` into symbols (uint8, plan.symbols_bytes) and/or values q [U][stride]."""
+    a = DecodeArgs(buf.words.data_ptr(), buf.words_stride, buf.chunk_offset.data_ptr(), buf.sub_bits.data_ptr(),
+                   books.handle, None if symbols is None else symbols.data_ptr(),
+                   None if q is None else q.data_ptr(), 0 if q is None else q.stride(0), buf.status.data_ptr())
+    _check("co3_decode", lib().co3_decode(plan.handle, C.byref(a), _stream(stream)))
+
+
+def co3_ps_aggregate(plan, books, buf, out, stream=None):
+    """PS side: out[d] = (1/U) sum_u ghat^(u) decoded from the streams in `buf`."""
+    assert out.numel() >= plan.d
+    a = AggregateArgs(buf.words.data_ptr(), buf.words_stride, buf.chunk_offset.data_ptr(), buf.sub_bits.data_ptr(),
+                      books.handle, out.data_ptr(), buf.status.data_ptr())
+    _check("co3_ps_aggregate", lib().co3_ps_aggregate(plan.handle, C.byref(a), _stream(stream)))

@@ -1,0 +1,287 @@
+// Host side of the C ABI declared in include/co3.h: argument checks, plans, code-table sets and
+// the launch sequences.  No codec arithmetic happens here except the host Huffman builder that
+// co3_build_codebook exposes.
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "co3_internal.h"
+#include "quantize_math.h"
+
+using namespace co3;
+
+namespace {
+
+struct DeviceGuard {
+    int prev = 0;
+    bool switched = false;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) == hipSuccess && prev != dev) switched = hipSetDevice(dev) == hipSuccess;
+    }
+    ~DeviceGuard()
+    {
+        if (switched) (void)hipSetDevice(prev);
+    }
+};
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_bias_table(const co3_format &f, const int32_t *bias, size_t n)
+{
+    for (size_t i = 0; i < n; ++i)
+        if (!format_supported(f.exp_bits, f.mant_bits, bias[i])) return CO3_ERR_FORMAT;
+    return CO3_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *co3_status_string(int status)
+{
+    switch (status) {
+        case CO3_OK: return "CO3_OK";
+        case CO3_ERR_ARG: return "CO3_ERR_ARG";
+        case CO3_ERR_FORMAT: return "CO3_ERR_FORMAT";
+        case CO3_ERR_CAPACITY: return "CO3_ERR_CAPACITY";
+        case CO3_ERR_CODELEN: return "CO3_ERR_CODELEN";
+        case CO3_ERR_CORRUPT: return "CO3_ERR_CORRUPT";
+        case CO3_ERR_HIP: return "CO3_ERR_HIP";
+        default: return "CO3_ERR_UNKNOWN";
+    }
+}
+
+int co3_plan_create(co3_format format, uint32_t U, uint64_t d, uint32_t nseg, const co3_segment *segments,
+                    const int32_t *bias, int32_t per_user_books, co3_plan **out)
+{
+    if (!out || !bias || U == 0) return CO3_ERR_ARG;
+    *out = nullptr;
+    if (format.exp_bits < 2 || format.mant_bits < 0 || 1 + format.exp_bits + format.mant_bits > 8)
+        return CO3_ERR_FORMAT;
+    co3_segment whole = {0, d, 0, 0};
+    if (!segments) { segments = &whole; nseg = 1; }
+    if (nseg == 0 || nseg > (1u << 20)) return CO3_ERR_ARG;
+    std::vector<SegDev> segs(nseg + 1);
+    uint64_t off = 0, chunks = 0;
+    int32_t max_book = 0;
+    for (uint32_t k = 0; k < nseg; ++k) {
+        if (segments[k].offset != off || segments[k].codebook < 0 || segments[k].codebook >= (1 << 16))
+            return CO3_ERR_ARG;
+        if (off + segments[k].length < off) return CO3_ERR_ARG;
+        segs[k] = {off, segments[k].length, chunks, segments[k].codebook, 0};
+        off += segments[k].length;
+        chunks += (segments[k].length + kChunk - 1) / kChunk;
+        if (segments[k].codebook > max_book) max_book = segments[k].codebook;
+    }
+    if (off != d) return CO3_ERR_ARG;
+    if (chunks >= (1ull << 31)) return CO3_ERR_ARG;  // one workgroup per chunk in grid.x
+    segs[nseg] = {d, 0, chunks, 0, 0};
+    int rc = check_bias_table(format, bias, (size_t)U * nseg);
+    if (rc != CO3_OK) return rc;
+
+    co3_plan *p = new (std::nothrow) co3_plan;
+    if (!p) return CO3_ERR_ARG;
+    if (hipGetDevice(&p->device) != hipSuccess) { delete p; return CO3_ERR_HIP; }
+    if (hipMalloc(&p->d_segs, sizeof(SegDev) * (nseg + 1)) != hipSuccess ||
+        hipMalloc(&p->d_bias, sizeof(int32_t) * (size_t)U * nseg) != hipSuccess ||
+        hipMemcpy(p->d_segs, segs.data(), sizeof(SegDev) * (nseg + 1), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(p->d_bias, bias, sizeof(int32_t) * (size_t)U * nseg, hipMemcpyHostToDevice) != hipSuccess) {
+        co3_plan_destroy(p);
+        return CO3_ERR_HIP;
+    }
+    Layout &l = p->lay;
+    l.U = U; l.nseg = nseg; l.d = d; l.nchunks = chunks;
+    l.E = format.exp_bits; l.M = format.mant_bits;
+    l.A = 1u << (1 + format.exp_bits + format.mant_bits);
+    l.books_per_user = (uint32_t)max_book + 1;
+    l.per_user_books = per_user_books ? 1u : 0u;
+    l.nbooks = l.books_per_user * (per_user_books ? U : 1u);
+    l.segs = p->d_segs;
+    l.bias = p->d_bias;
+    *out = p;
+    return CO3_OK;
+}
+
+int co3_plan_set_bias(co3_plan *plan, const int32_t *bias, void *stream)
+{
+    if (!plan || !bias) return CO3_ERR_ARG;
+    const size_t n = (size_t)plan->lay.U * plan->lay.nseg;
+    co3_format f = {plan->lay.E, plan->lay.M};
+    int rc = check_bias_table(f, bias, n);
+    if (rc != CO3_OK) return rc;
+    DeviceGuard guard(plan->device);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(plan->d_bias, bias, sizeof(int32_t) * n, hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        return CO3_ERR_HIP;
+    return CO3_OK;
+}
+
+void co3_plan_destroy(co3_plan *plan)
+{
+    if (!plan) return;
+    DeviceGuard guard(plan->device);
+    if (plan->d_segs) (void)hipFree(plan->d_segs);
+    if (plan->d_bias) (void)hipFree(plan->d_bias);
+    delete plan;
+}
+
+uint64_t co3_plan_num_chunks(const co3_plan *plan) { return plan ? plan->lay.nchunks : 0; }
+uint32_t co3_plan_num_books(const co3_plan *plan) { return plan ? plan->lay.nbooks : 0; }
+uint32_t co3_plan_alphabet(const co3_plan *plan) { return plan ? plan->lay.A : 0; }
+
+size_t co3_plan_symbols_bytes(const co3_plan *plan)
+{
+    if (!plan) return 0;
+    const uint64_t stride = (plan->lay.d + 15) & ~(uint64_t)15;
+    return (size_t)(stride * plan->lay.U + 16);
+}
+
+size_t co3_plan_workspace_bytes(const co3_plan *plan)
+{
+    if (!plan) return 0;
+    return (size_t)(plan->lay.nchunks * plan->lay.U * sizeof(uint32_t) + 256);
+}
+
+uint64_t co3_plan_stream_words(const co3_plan *plan, uint32_t max_code_len)
+{
+    if (!plan) return 0;
+    if (max_code_len > CO3_MAX_CODE_LEN) max_code_len = CO3_MAX_CODE_LEN;
+    // every chunk rounds up to a whole word
+    return (plan->lay.d * max_code_len + 31) / 32 + plan->lay.nchunks + 1;
+}
+
+int co3_build_codebook(co3_format format, uint32_t nbooks, const uint64_t *weights, co3_codebook **out)
+{
+    if (!out || nbooks == 0) return CO3_ERR_ARG;
+    *out = nullptr;
+    if (format.exp_bits < 2 || format.mant_bits < 0 || 1 + format.exp_bits + format.mant_bits > 8)
+        return CO3_ERR_FORMAT;
+    const uint32_t A = 1u << (1 + format.exp_bits + format.mant_bits);
+    std::vector<BookDev> host(nbooks);
+    std::memset(host.data(), 0, sizeof(BookDev) * nbooks);
+    if (weights) {
+        for (uint32_t b = 0; b < nbooks; ++b) {
+            int rc = build_book_host(weights + (size_t)b * A, A, &host[b]);
+            if (rc != CO3_OK) return rc;
+        }
+    }
+    co3_codebook *cb = new (std::nothrow) co3_codebook;
+    if (!cb) return CO3_ERR_ARG;
+    cb->format = format;
+    cb->nbooks = nbooks;
+    cb->A = A;
+    if (hipGetDevice(&cb->device) != hipSuccess ||
+        hipMalloc(&cb->d_books, sizeof(BookDev) * nbooks) != hipSuccess ||
+        hipMemcpy(cb->d_books, host.data(), sizeof(BookDev) * nbooks, hipMemcpyHostToDevice) != hipSuccess) {
+        co3_codebook_destroy(cb);
+        return CO3_ERR_HIP;
+    }
+    *out = cb;
+    return CO3_OK;
+}
+
+int co3_build_codebook_device(co3_codebook *books, const uint64_t *weights, uint64_t *status, void *stream)
+{
+    if (!books || !weights || !status) return CO3_ERR_ARG;
+    DeviceGuard guard(books->device);
+    hipError_t e = launch_build_books(books->d_books, books->nbooks, books->A, weights, status,
+                                      static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CO3_OK : CO3_ERR_HIP;
+}
+
+int co3_codebook_export(const co3_codebook *books, uint32_t book, uint8_t *len, uint64_t *code, void *stream)
+{
+    if (!books || book >= books->nbooks || !len || !code) return CO3_ERR_ARG;
+    DeviceGuard guard(books->device);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    BookDev *h = new (std::nothrow) BookDev;
+    if (!h) return CO3_ERR_ARG;
+    int rc = CO3_OK;
+    if (hipMemcpyAsync(h, books->d_books + book, sizeof(BookDev), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        rc = CO3_ERR_HIP;
+    else {
+        std::memcpy(len, h->len, books->A);
+        std::memcpy(code, h->code, sizeof(uint64_t) * books->A);
+    }
+    delete h;
+    return rc;
+}
+
+uint32_t co3_codebook_num_books(const co3_codebook *books) { return books ? books->nbooks : 0; }
+
+void co3_codebook_destroy(co3_codebook *books)
+{
+    if (!books) return;
+    DeviceGuard guard(books->device);
+    if (books->d_books) (void)hipFree(books->d_books);
+    delete books;
+}
+
+static int check_books(const co3_plan *plan, const co3_codebook *books)
+{
+    if (!books) return CO3_ERR_ARG;
+    if (books->nbooks != plan->lay.nbooks || books->A != plan->lay.A) return CO3_ERR_ARG;
+    if (books->device != plan->device) return CO3_ERR_ARG;
+    return CO3_OK;
+}
+
+int co3_encode(const co3_plan *plan, const co3_encode_args *a, void *stream)
+{
+    if (!plan || !a) return CO3_ERR_ARG;
+    const Layout &lay = plan->lay;
+    if (!a->g || !a->m || !a->m_out || !a->symbols || !a->hist || !a->words || !a->chunk_offset ||
+        !a->sub_bits || !a->payload_bits || !a->status || !a->workspace)
+        return CO3_ERR_ARG;
+    if (!aligned16(a->g) || !aligned16(a->m) || !aligned16(a->m_out) || !aligned16(a->symbols) ||
+        (a->row_stride & 3u) || a->row_stride < lay.d)
+        return CO3_ERR_ARG;
+    if (a->mode != CO3_BOOK_FIXED && a->mode != CO3_BOOK_EMPIRICAL) return CO3_ERR_ARG;
+    int rc = check_books(plan, a->books);
+    if (rc != CO3_OK) return rc;
+    if (a->workspace_bytes < co3_plan_workspace_bytes(plan)) return CO3_ERR_CAPACITY;
+    if (!(a->gamma == a->gamma)) return CO3_ERR_ARG;
+
+    DeviceGuard guard(plan->device);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    EncodeWs ws;
+    ws.chunk_bits = reinterpret_cast<uint32_t *>((reinterpret_cast<uintptr_t>(a->workspace) + 255u) & ~(uintptr_t)255u);
+
+    if (launch_zero_u64(a->hist, (uint64_t)lay.nbooks * lay.A, s) != hipSuccess) return CO3_ERR_HIP;
+    if (launch_quantize(lay, *a, s) != hipSuccess) return CO3_ERR_HIP;
+    if (a->mode == CO3_BOOK_EMPIRICAL &&
+        launch_build_books(a->books->d_books, lay.nbooks, lay.A, a->hist, a->status, s) != hipSuccess)
+        return CO3_ERR_HIP;
+    if (launch_pack(lay, *a, a->books->d_books, ws, s) != hipSuccess) return CO3_ERR_HIP;
+    return CO3_OK;
+}
+
+int co3_decode(const co3_plan *plan, const co3_decode_args *a, void *stream)
+{
+    if (!plan || !a) return CO3_ERR_ARG;
+    const Layout &lay = plan->lay;
+    if (!a->words || !a->chunk_offset || !a->sub_bits || !a->status || (!a->symbols && !a->q)) return CO3_ERR_ARG;
+    if (a->q && a->q_stride < lay.d) return CO3_ERR_ARG;
+    int rc = check_books(plan, a->books);
+    if (rc != CO3_OK) return rc;
+    DeviceGuard guard(plan->device);
+    return launch_decode(lay, *a, a->books->d_books, static_cast<hipStream_t>(stream)) == hipSuccess ? CO3_OK
+                                                                                                  : CO3_ERR_HIP;
+}
+
+int co3_ps_aggregate(const co3_plan *plan, const co3_aggregate_args *a, void *stream)
+{
+    if (!plan || !a) return CO3_ERR_ARG;
+    const Layout &lay = plan->lay;
+    if (!a->words || !a->chunk_offset || !a->sub_bits || !a->status || !a->out) return CO3_ERR_ARG;
+    int rc = check_books(plan, a->books);
+    if (rc != CO3_OK) return rc;
+    DeviceGuard guard(plan->device);
+    return launch_aggregate(lay, *a, a->books->d_books, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? CO3_OK
+               : CO3_ERR_HIP;
+}
+
+}  // extern "C"

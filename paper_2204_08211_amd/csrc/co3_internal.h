@@ -1,0 +1,96 @@
+// Internal declarations shared by the host API and the HIP kernels of libco3.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "co3.h"
+
+namespace co3 {
+
+constexpr int kChunk = CO3_CHUNK;
+constexpr int kSub = CO3_SUB;
+constexpr int kSubsPerChunk = CO3_SUBS_PER_CHUNK;
+constexpr int kMaxA = 256;          // symbols are bytes
+constexpr int kDecBits = 11;        // prefix width of the direct decode table
+constexpr int kDecEntries = 1 << kDecBits;
+constexpr int kFastLen = 24;        // longest code held in the 32-bit encode entry
+constexpr uint32_t kFastSlow = 0xFFu;  // length field marking "use the 64-bit table"
+
+// One Huffman code table as the kernels read it.
+struct BookDev {
+    uint64_t code[kMaxA];        // right-aligned codeword of each symbol
+    uint64_t first[65];          // first[L]: first canonical code of length L (L = 1..64)
+    uint32_t fast[kMaxA];        // (len << 24) | code for len <= 24; len field 0xFF: long code; 0: no code
+    uint32_t count[65];          // count[L]: symbols with length L
+    uint32_t offset[65];         // offset[L]: index of the first length-L symbol in sorted[]
+    uint16_t dec[kDecEntries];   // prefix -> (len << 8) | symbol for len <= 11, else 0
+    uint8_t len[kMaxA];          // codeword length, 0 = no code
+    uint8_t sorted[kMaxA];       // symbols ordered by (length, symbol)
+    uint32_t maxlen;
+    uint32_t nactive;
+    uint32_t pad[2];
+};
+
+// One layer of the flat vector as the kernels read it.
+struct SegDev {
+    uint64_t offset;       // first element
+    uint64_t length;
+    uint64_t chunk_start;  // index of the segment's first chunk within a user
+    int32_t book;          // code table id within a user's (or the shared) set
+    int32_t pad;
+};
+
+// Constants of Q_fp for one (format, bias), derived on the device from E, M and bias.
+struct Layout {
+    uint32_t U;
+    uint32_t nseg;
+    uint64_t d;
+    uint64_t nchunks;          // per user
+    int32_t E, M;
+    uint32_t A;
+    uint32_t books_per_user;   // 1 + max segment.codebook
+    uint32_t per_user_books;
+    uint32_t nbooks;           // tables in a set
+    const SegDev *segs;        // device [nseg + 1] (last entry: offset = d, chunk_start = nchunks)
+    const int32_t *bias;       // device [U][nseg]
+};
+
+}  // namespace co3
+
+struct co3_plan {
+    co3::Layout lay;
+    co3::SegDev *d_segs = nullptr;
+    int32_t *d_bias = nullptr;
+    int device = 0;
+};
+
+struct co3_codebook {
+    co3_format format;
+    uint32_t nbooks = 0;
+    uint32_t A = 0;
+    co3::BookDev *d_books = nullptr;
+    int device = 0;
+};
+
+namespace co3 {
+
+// Host Huffman builder (host_codebook.cpp): fills one table; returns a co3_status.
+int build_book_host(const uint64_t *weights, uint32_t A, BookDev *out);
+
+// Kernel launchers (one per .hip file).  All return a hipError_t from hipGetLastError().
+struct EncodeWs {
+    uint32_t *chunk_bits;   // [U][nchunks]
+};
+
+hipError_t launch_zero_u64(uint64_t *p, uint64_t n, hipStream_t s);
+hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, hipStream_t s);
+hipError_t launch_build_books(BookDev *books, uint32_t nbooks, uint32_t A, const uint64_t *weights,
+                              uint64_t *status, hipStream_t s);
+hipError_t launch_pack(const Layout &lay, const co3_encode_args &a, const BookDev *books,
+                       const EncodeWs &ws, hipStream_t s);
+hipError_t launch_decode(const Layout &lay, const co3_decode_args &a, const BookDev *books, hipStream_t s);
+hipError_t launch_aggregate(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
+                            hipStream_t s);
+
+}  // namespace co3

@@ -1,0 +1,106 @@
+// Host construction of one Huffman code table (Sec. IV-A (ii): element-wise Huffman coding of
+// the quantized gradient; optimal for a known source, Sec. II-E).
+//
+// Tie rule: nodes are ordered by (weight, key); a leaf's key is its symbol, an internal node's
+// key is A + its creation order; the two smallest are merged.  With the leaves sorted once by
+// (weight, symbol) and the internal nodes kept in creation order (their weights never
+// decrease), the smallest node is always at the head of one of the two lists, and on equal
+// weight the leaf comes first because every leaf key is below every internal key.
+#include <algorithm>
+#include <cstring>
+#include <vector>
+
+#include "co3_internal.h"
+
+namespace co3 {
+
+// Fill every derived table of `b` from b->len[] (lengths) for alphabet size A.
+static void finish_tables(BookDev *b, uint32_t A)
+{
+    std::memset(b->count, 0, sizeof(b->count));
+    std::memset(b->first, 0, sizeof(b->first));
+    std::memset(b->offset, 0, sizeof(b->offset));
+    std::memset(b->code, 0, sizeof(b->code));
+    std::memset(b->fast, 0, sizeof(b->fast));
+    std::memset(b->dec, 0, sizeof(b->dec));
+    std::memset(b->sorted, 0, sizeof(b->sorted));
+    b->maxlen = 0;
+    b->nactive = 0;
+    for (uint32_t s = 0; s < A; ++s) {
+        if (!b->len[s]) continue;
+        b->count[b->len[s]]++;
+        b->nactive++;
+        if (b->len[s] > b->maxlen) b->maxlen = b->len[s];
+    }
+    // canonical codes: first[L] = (first[L-1] + count[L-1]) << 1
+    uint64_t code = 0;
+    uint32_t off = 0;
+    for (int L = 1; L <= 64; ++L) {
+        code = (code + b->count[L - 1]) << 1;
+        b->first[L] = code;
+        b->offset[L] = off;
+        off += b->count[L];
+    }
+    uint32_t next[65];
+    std::memset(next, 0, sizeof(next));
+    for (uint32_t s = 0; s < A; ++s) {  // ascending symbol within each length
+        const int L = b->len[s];
+        if (!L) continue;
+        const uint32_t rank = next[L]++;
+        b->code[s] = b->first[L] + rank;
+        b->sorted[b->offset[L] + rank] = (uint8_t)s;
+        if (L <= kFastLen) b->fast[s] = ((uint32_t)L << 24) | (uint32_t)b->code[s];
+        else b->fast[s] = kFastSlow << 24;
+        if (L <= kDecBits) {
+            const uint32_t lo = (uint32_t)b->code[s] << (kDecBits - L);
+            const uint32_t n = 1u << (kDecBits - L);
+            for (uint32_t i = 0; i < n; ++i) b->dec[lo + i] = (uint16_t)((L << 8) | s);
+        }
+    }
+}
+
+int build_book_host(const uint64_t *w, uint32_t A, BookDev *b)
+{
+    std::memset(b, 0, sizeof(*b));
+    struct Leaf { uint64_t w; uint32_t s; };
+    std::vector<Leaf> leaves;
+    uint64_t total = 0;
+    for (uint32_t s = 0; s < A; ++s) {
+        if (!w[s]) continue;
+        if (total + w[s] < total) return CO3_ERR_ARG;
+        total += w[s];
+        leaves.push_back({w[s], s});
+    }
+    const int n = (int)leaves.size();
+    if (n == 0) { finish_tables(b, A); return CO3_OK; }
+    if (n == 1) { b->len[leaves[0].s] = 1; finish_tables(b, A); return CO3_OK; }
+    std::sort(leaves.begin(), leaves.end(),
+              [](const Leaf &x, const Leaf &y) { return x.w != y.w ? x.w < y.w : x.s < y.s; });
+    // nodes 0..n-1: sorted leaves; n..2n-2: internal nodes in creation order
+    std::vector<uint64_t> nw(2 * n - 1);
+    std::vector<int> parent(2 * n - 1, -1);
+    for (int i = 0; i < n; ++i) nw[i] = leaves[i].w;
+    int li = 0, ii = n, made = n;
+    for (int step = 0; step < n - 1; ++step) {
+        int pick[2];
+        for (int r = 0; r < 2; ++r) {
+            const bool have_leaf = li < n, have_int = ii < made;
+            if (have_leaf && (!have_int || nw[li] <= nw[ii])) pick[r] = li++;
+            else pick[r] = ii++;
+        }
+        nw[made] = nw[pick[0]] + nw[pick[1]];
+        parent[pick[0]] = made;
+        parent[pick[1]] = made;
+        ++made;
+    }
+    for (int i = 0; i < n; ++i) {
+        int depth = 0;
+        for (int p = parent[i]; p >= 0; p = parent[p]) ++depth;
+        if (depth > CO3_MAX_CODE_LEN) return CO3_ERR_CODELEN;
+        b->len[leaves[i].s] = (uint8_t)depth;
+    }
+    finish_tables(b, A);
+    return CO3_OK;
+}
+
+}  // namespace co3

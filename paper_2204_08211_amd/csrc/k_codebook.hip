@@ -1,0 +1,144 @@
+// Huffman code tables built on the device from symbol counts (Sec. IV-A (ii)), one workgroup
+// per table, so that an encoder using this round's histogram needs no host round trip.
+//
+// Same tie rule and canonical form as the host builder: leaves sorted by (weight, symbol),
+// internal nodes in creation order, merge the two smallest with leaves first on equal weight.
+#include "co3_internal.h"
+
+namespace co3 {
+
+constexpr int kCbThreads = 256;
+
+__global__ __launch_bounds__(kCbThreads) void k_build_books(BookDev *__restrict__ books, uint32_t A,
+                                                           const uint64_t *__restrict__ weights,
+                                                           uint64_t *__restrict__ status)
+{
+    BookDev &B = books[blockIdx.x];
+    const uint64_t *w = weights + (uint64_t)blockIdx.x * A;
+    const int t = threadIdx.x;
+
+    __shared__ uint64_t lw[kMaxA];        // weight of symbol t
+    __shared__ uint64_t nw[2 * kMaxA];    // node weights: sorted leaves, then internal nodes
+    __shared__ int parent[2 * kMaxA];
+    __shared__ uint32_t leaf_sym[kMaxA];  // sorted leaf -> symbol
+    __shared__ uint32_t slen[kMaxA];      // symbol -> length
+    __shared__ uint32_t cnt[65], off[65];
+    __shared__ uint64_t first[65];
+    __shared__ uint32_t sorted[kMaxA];
+    __shared__ int err;
+
+    const uint64_t myw = (t < (int)A) ? w[t] : 0;
+    lw[t] = myw;
+    slen[t] = 0;
+    parent[t] = -1;
+    parent[t + kMaxA] = -1;
+    if (t < 65) { cnt[t] = 0; off[t] = 0; first[t] = 0; }
+    if (t == 0) err = 0;
+    const int n = __syncthreads_count(myw > 0);
+
+    // rank of this leaf in (weight, symbol) order among the active symbols
+    if (myw > 0) {
+        int rank = 0;
+        for (int j = 0; j < (int)A; ++j) {
+            const uint64_t wj = lw[j];
+            rank += (wj > 0 && (wj < myw || (wj == myw && j < t))) ? 1 : 0;
+        }
+        nw[rank] = myw;
+        leaf_sym[rank] = t;
+    }
+    __syncthreads();
+
+    if (t == 0 && n >= 2) {
+        int li = 0, ii = n, made = n;
+        for (int step = 0; step < n - 1; ++step) {
+            int pick[2];
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const bool have_leaf = li < n, have_int = ii < made;
+                if (have_leaf && (!have_int || nw[li] <= nw[ii])) pick[r] = li++;
+                else pick[r] = ii++;
+            }
+            const uint64_t s = nw[pick[0]] + nw[pick[1]];
+            if (s < nw[pick[1]]) err = 1;  // the weights of this table sum to 2^64 or more
+            nw[made] = s;
+            parent[pick[0]] = made;
+            parent[pick[1]] = made;
+            ++made;
+        }
+    }
+    __syncthreads();
+
+    if (t < n) {
+        int depth = 0;
+        if (n == 1) depth = 1;
+        for (int p = parent[t]; p >= 0 && depth <= CO3_MAX_CODE_LEN; p = parent[p]) ++depth;
+        if (depth > CO3_MAX_CODE_LEN) err = 1;
+        else slen[leaf_sym[t]] = (uint32_t)depth;
+    }
+    __syncthreads();
+    const bool bad = err != 0;
+    if (bad) {
+        slen[t] = 0;
+        if (t == 0) atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CODELEN), 1ull);
+    }
+    __syncthreads();
+
+    const uint32_t L = slen[t];
+    if (L) atomicAdd(&cnt[L], 1u);
+    __syncthreads();
+    if (t == 0) {
+        uint64_t code = 0;
+        uint32_t o = 0, mx = 0;
+        for (int l = 1; l <= 64; ++l) {
+            code = (code + cnt[l - 1]) << 1;
+            first[l] = code;
+            off[l] = o;
+            o += cnt[l];
+            if (cnt[l]) mx = l;
+        }
+        B.maxlen = mx;
+        B.nactive = bad ? 0 : (uint32_t)n;
+        B.pad[0] = B.pad[1] = 0;
+    }
+    __syncthreads();
+
+    uint64_t code = 0;
+    uint32_t fast = 0;
+    if (L) {
+        uint32_t rank = 0;
+        for (int j = 0; j < t; ++j) rank += (slen[j] == L) ? 1u : 0u;
+        code = first[L] + rank;
+        sorted[off[L] + rank] = (uint32_t)t;
+        fast = (L <= (uint32_t)kFastLen) ? ((L << 24) | (uint32_t)code) : (kFastSlow << 24);
+    }
+    B.code[t] = code;
+    B.fast[t] = fast;
+    B.len[t] = (uint8_t)L;
+    if (t < 65) { B.first[t] = first[t]; B.count[t] = cnt[t]; B.offset[t] = off[t]; }
+    __syncthreads();
+    B.sorted[t] = (t < n && !bad) ? (uint8_t)sorted[t] : 0;
+
+    // direct decode table: every kDecBits-bit prefix whose code is at most kDecBits long
+    for (int idx = t; idx < kDecEntries; idx += kCbThreads) {
+        uint16_t e = 0;
+        for (int l = 1; l <= kDecBits; ++l) {
+            const uint32_t c = (uint32_t)idx >> (kDecBits - l);
+            const uint32_t f = (uint32_t)first[l];
+            if (cnt[l] && c >= f && c - f < cnt[l]) {
+                e = (uint16_t)((l << 8) | sorted[off[l] + (c - f)]);
+                break;
+            }
+        }
+        B.dec[idx] = e;
+    }
+}
+
+hipError_t launch_build_books(BookDev *books, uint32_t nbooks, uint32_t A, const uint64_t *weights,
+                              uint64_t *status, hipStream_t s)
+{
+    if (nbooks == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_build_books, dim3(nbooks), dim3(kCbThreads), 0, s, books, A, weights, status);
+    return hipGetLastError();
+}
+
+}  // namespace co3

@@ -1,0 +1,186 @@
+"""GPU-vs-oracle parity through the C ABI (pytest -m gpu).  Bit-exact for symbols, histograms,
+codebooks, bit offsets, bitstreams and the fp32 error memory; 1e-6 relative for the PS average."""
+import numpy as np
+import pytest
+
+import co3_synth as syn
+from oracle import co3_oracle as orc
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+BOOK_FIXED, BOOK_EMPIRICAL = 0, 1
+
+
+def make_inputs(rng, U, d, E, M, bias, beta=1.0, alpha=1e-3, specials=0.2, mem_scale=0.5):
+    g = np.stack([syn.gennorm_numpy(rng, d, beta, alpha) for _ in range(U)])
+    m = np.stack([syn.gennorm_numpy(rng, d, beta, alpha * mem_scale) for _ in range(U)])
+    if specials:
+        for u in range(U):
+            idx = rng.choice(d, int(d * specials), replace=False)
+            g[u, idx] = gu.special_values(E, M, bias, rng, idx.size)
+            m[u, idx[: idx.size // 2]] = 0
+    return g, m
+
+
+@pytest.mark.parametrize("E,M,d", [(3, 0, 5 * 2048 + 123), (4, 1, 4096 * 3 + 70), (4, 3, 40000), (3, 2, 4095),
+                                   (5, 2, 2049), (2, 1, 64), (2, 5, 10000), (7, 0, 9000)])
+def test_single_user_adversarial(E, M, d):
+    print(f"case E={E} M={M} d={d}", flush=True)
+    rng = np.random.default_rng(E * 1000 + M * 10 + d)
+    bias = min((2 ** E - 2) + 9, 100)          # top binade 2^-9 (2^26 for the 7-bit exponent)
+    g, m = make_inputs(rng, 1, d, E, M, bias)
+    kw = dict(E=E, M=M, U=1, d=d, bias=[[bias]])
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL)
+    ref = gu.oracle_round(kw, g, m, 0.9)
+    gu.compare_round(gpu, ref, d)
+
+
+def test_nonfinite_inputs():
+    E, M, d, bias = 4, 3, 7000, 20
+    rng = np.random.default_rng(1)
+    g, m = make_inputs(rng, 2, d, E, M, bias)
+    g[0, [0, 5, 4096, 6999]] = [np.nan, np.inf, -np.inf, np.nan]
+    m[1, [17, 18]] = [np.inf, np.nan]
+    kw = dict(E=E, M=M, U=2, d=d, bias=[[bias], [bias]])
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL)
+    ref = gu.oracle_round(kw, g, m, 0.9)
+    assert int(ref["counters"][0]) == 6
+    gu.compare_round(gpu, ref, d)
+
+
+def test_extreme_bias_denormal_range():
+    # smallest supported scale: the subnormal row of the format lies in fp32's denormal range
+    E, M, d, bias = 4, 3, 20000, 127
+    rng = np.random.default_rng(2)
+    top = orc.grid(E, M, bias)[-1]
+    g = (rng.standard_normal((1, d)) * top / 3).astype(np.float32)
+    g[0, :4000] = gu.special_values(E, M, bias, rng, 4000)
+    m = (rng.standard_normal((1, d)) * top / 8).astype(np.float32)
+    kw = dict(E=E, M=M, U=1, d=d, bias=[[bias]])
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL)
+    ref = gu.oracle_round(kw, g, m, 0.9)
+    gu.compare_round(gpu, ref, d)
+    # and the largest supported scale
+    bias = (2 ** E - 2) - 100
+    top = orc.grid(E, M, bias)[-1]
+    g = (rng.standard_normal((1, d)) * top / 3).astype(np.float32)
+    m = (rng.standard_normal((1, d)) * top / 8).astype(np.float32)
+    kw = dict(E=E, M=M, U=1, d=d, bias=[[bias]])
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL)
+    gu.compare_round(gpu, gu.oracle_round(kw, g, m, 0.9), d)
+
+
+@pytest.mark.parametrize("per_user", [False, True])
+def test_multi_user_multi_segment(per_user):
+    E, M, U = 3, 2, 3
+    seg_len = [1, 63, 4097, 0, 2048 * 3 + 5, 64, 9001, 4096]
+    seg_book = [0, 1, 2, 0, 1, 3, 2, 0]
+    d = sum(seg_len)
+    rng = np.random.default_rng(7 + per_user)
+    bias = rng.integers(8, 20, (U, len(seg_len))).astype(np.int32)
+    g = np.empty((U, d), np.float32); m = np.empty((U, d), np.float32)
+    off = 0
+    for k, n in enumerate(seg_len):
+        for u in range(U):
+            top = orc.grid(E, M, int(bias[u, k]))[-1]
+            g[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, top / 8)
+            m[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, top / 30)
+        off += n
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias, seg_len=seg_len, seg_book=seg_book, per_user_books=per_user)
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL)
+    ref = gu.oracle_round(kw, g, m, 0.9)
+    gu.compare_round(gpu, ref, d)
+
+
+def test_fixed_model_codebook():
+    # code designed from the GenNorm model (Sec. IV-A (ii)); weights come from the oracle's model
+    E, M, U, d = 4, 3, 2, 30000
+    rng = np.random.default_rng(11)
+    g = np.stack([syn.gennorm_numpy(rng, d, 0.9, 1e-3) for _ in range(U)])
+    m = np.zeros_like(g)
+    bias = syn.bias_for_max(np.abs(g).max(), E)
+    w, _, _ = orc.gennorm_weights(E, M, bias, 0.0, 1e-3, 0.9)
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[bias]] * U)
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=w[None, :], max_code_len=64)
+    ref = gu.oracle_round(kw, g, m, 0.9, weights=w[None, :])
+    gu.compare_round(gpu, ref, d)
+    assert ref["lens"].max() > 11
+
+
+def test_long_codes_slow_paths():
+    # weights 1, 1, 2, 4, ... give codes of up to 63 bits: exercises the 64-bit encode and the
+    # canonical-search decode paths
+    E, M, U, d = 4, 1, 1, 6000
+    A = 64
+    nm = orc.num_magnitudes(E, M)
+    emit = np.array([s for s in range(A) if (s & 31) < nm and s != 32])
+    w = np.zeros(A, np.uint64)
+    w[emit] = np.array([1] + [1 << i for i in range(emit.size - 1)], np.uint64)
+    rng = np.random.default_rng(13)
+    bias = 16
+    grid = orc.grid(E, M, bias)
+    k = rng.integers(0, nm, d)
+    g = (grid[k] * rng.choice([-1.0, 1.0], d)).astype(np.float32)[None, :]
+    m = np.zeros_like(g)
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[bias]])
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=w[None, :], max_code_len=64)
+    ref = gu.oracle_round(kw, g, m, 0.9, weights=w[None, :])
+    assert ref["lens"].max() >= 57
+    gu.compare_round(gpu, ref, d)
+
+
+def test_iterations_carry_memory_cfg1_recipe():
+    # workload 1 at reduced d: fresh gradient per iteration, memory carried, bias per iteration
+    w = syn.WORKLOADS["cfg1"].scaled(d=3 * 4096 + 999)
+    m = np.zeros((1, w.d), np.float32)
+    for it in range(w.iters):
+        g = syn.user_gradient_numpy(w, it, 0)[None, :]
+        v = g + np.float32(w.gamma) * m
+        bias = syn.bias_for_max(np.abs(v).max(), w.E)
+        kw = dict(E=w.E, M=w.M, U=1, d=w.d, bias=[[bias]])
+        gpu, _ = gu.gpu_round(kw, g, m, w.gamma, BOOK_EMPIRICAL)
+        ref = gu.oracle_round(kw, g, m, w.gamma)
+        gu.compare_round(gpu, ref, w.d)
+        m = ref["m_new"]
+
+
+def test_in_place_and_determinism():
+    E, M, U, d, bias = 4, 3, 4, 50000, 18
+    rng = np.random.default_rng(17)
+    g, m = make_inputs(rng, U, d, E, M, bias, specials=0.05)
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[bias]] * U)
+    a, _ = gu.gpu_round(kw, g, m, 0.5, BOOK_EMPIRICAL)
+    b, _ = gu.gpu_round(kw, g, m, 0.5, BOOK_EMPIRICAL)
+    for key in ("sym", "m_new", "hist", "words", "chunk_offset", "sub_bits", "avg"):
+        gu.assert_bits_equal(a[key], b[key], key)
+
+
+def test_error_paths_capacity_nocode_corrupt():
+    import torch
+    from paper_2204_08211_amd import binding as B
+    E, M, U, d, bias = 4, 1, 1, 20000, 16
+    rng = np.random.default_rng(19)
+    g = syn.gennorm_numpy(rng, d, 1.0, 2.0 ** -12)[None, :]
+    m = np.zeros_like(g)
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[bias]])
+    ref = gu.oracle_round(kw, g, m, 0.9)
+    need = ref["words"][0].size
+    # stream buffer two chunks short: the last chunks are skipped and counted, nothing is written past it
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL, words_stride=need - 700, want_decode=False)
+    assert int(gpu["status_encode"][B.STAT_CAPACITY]) >= 1
+    gu.assert_bits_equal(gpu["chunk_offset"], ref["chunk_offset"], "offsets still exact")
+    # fixed code that lacks symbols which occur
+    w = ref["hist"][0].copy(); w[np.argsort(w)[-3]] = 0
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=w[None, :], want_decode=False)
+    assert int(gpu["status_encode"][B.STAT_NOCODE]) == int(ref["hist"][0][np.argsort(ref["hist"][0])[-3]])
+    # corrupt stream / index: the decoder flags it and stays inside the buffers
+    gpu, (plan, books, buf, gt, mt) = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL)
+    assert int(gpu["status"][B.STAT_CORRUPT]) == 0
+    buf.sub_bits[0, 5] += 3
+    buf.words[0, 100:140] = -1
+    buf.status.zero_()
+    out = torch.zeros(d, dtype=torch.float32, device="cuda:0")
+    B.co3_ps_aggregate(plan, books, buf, out)
+    torch.cuda.synchronize()
+    assert int(buf.status[B.STAT_CORRUPT].item()) >= 1
