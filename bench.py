@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""CO3 codec benchmark on one MI355X.
+
+One "step" = one whole CO3 round for all U users: co3_encode (error correction, fp conversion,
+memory update, histogram, code table, lengths, scan, bit-pack) followed by co3_ps_aggregate
+(decode all streams, dequantize, average).  Inputs are synthetic GenNorm gradients resident in
+HBM before the timed region; the memory m is carried from step to step and the gradients rotate
+through a small pre-generated pool.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--book empirical|model]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=20)
+    p.add_argument("--warmup", type=int, default=3)
+    p.add_argument("--workload", default="cfg3", help="cfg1..cfg5 of BASELINE.json (default: the one the target is quoted on)")
+    p.add_argument("--book", default="empirical", choices=["empirical", "model"])
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--pool", type=int, default=2, help="pre-generated gradient sets to rotate through")
+    return p.parse_args()
+
+
+def cpu_baseline(w, it0_host, bias_host, seconds_target=15.0):
+    """The oracle as it stands, single thread, on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import co3_round as oround
+    g = it0_host
+    U, d = g.shape
+    m = np.zeros_like(g)
+    tm = {}
+    t0 = time.perf_counter()
+    enc = oround.encode_round(g, m, w.gamma, w.E, w.M, w.seg_len, list(range(len(w.seg_len))) if w.nseg > 1 else [0],
+                              bias_host[:U], False, None, tm)
+    t_enc = time.perf_counter() - t0
+    oround.ps_round(enc, w.E, w.M, w.seg_len, list(range(len(w.seg_len))) if w.nseg > 1 else [0], bias_host[:U], False, tm)
+    t_all = time.perf_counter() - t0
+    return dict(value=U * d / t_all / 1e9, unit="GElem/s", cores=1, kind="oracle",
+                sample=f"users 0..{U - 1} of {w.U} at full d={d}, one round (encode+decode+average), "
+                       f"{t_all:.1f} s; encode alone {U * d / t_enc / 1e6:.2f} MElem/s",
+                stages_s={k: round(v, 3) for k, v in tm.items()})
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU (users are a batch on that GPU); --gpus {a.gpus} is not supported",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import co3_synth as syn
+    from paper_2204_08211_amd import binding as B
+
+    w = syn.WORKLOADS[a.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    U, d = w.U, w.d
+    stride = (d + 3) // 4 * 4
+    nseg = len(w.seg_len)
+    seg_book = list(range(nseg)) if nseg > 1 else [0]
+
+    # inputs: pool of gradient sets, memory starts at zero (m_0 = 0)
+    pool = []
+    for it in range(a.pool):
+        g = torch.zeros((U, stride), dtype=torch.float32, device=dev)
+        for u in range(U):
+            syn.user_gradient_torch(w, it, u, dev, out=g[u, :d])
+        pool.append(g)
+    m = torch.zeros((U, stride), dtype=torch.float32, device=dev)
+
+    # exponent bias: the workload's rule on iteration 0 (v = g since m_0 = 0), per user and segment;
+    # held for the whole run like the paper holds b_t for several epochs
+    mx = np.zeros((U, nseg))
+    off = 0
+    for k, n in enumerate(w.seg_len):
+        mx[:, k] = pool[0][:, off:off + n].abs().amax(dim=1).cpu().numpy()
+        off += n
+    bias = syn.bias_table(mx, w.E)
+
+    plan = B.Plan(w.E, w.M, U, d, bias, seg_len=w.seg_len, seg_book=seg_book, per_user_books=w.per_user_books)
+    if a.book == "model":
+        from oracle import co3_oracle as orc   # model weights are an input prepared off the timed path
+        raise SystemExit("--book model needs per-book GenNorm parameters; use the empirical book for the headline")
+    books = B.co3_build_codebook(w.E, w.M, plan.num_books, None)
+    buf = B.RoundBuffers(plan, dev, max_code_len=16)
+    out = torch.zeros(d, dtype=torch.float32, device=dev)
+    mode = B.BOOK_EMPIRICAL
+
+    def step(i):
+        B.co3_encode(plan, books, pool[i % a.pool], m, m, w.gamma, buf, mode=mode)
+        B.co3_ps_aggregate(plan, books, buf, out)
+
+    for i in range(a.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    buf.status.zero_()
+    torch.cuda.synchronize()
+
+    B.profile_begin()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(a.steps):
+        step(a.warmup + i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    dev_ms = ev0.elapsed_time(ev1)
+    kt = B.profile_end()
+
+    ms_per_step = max(wall_ms, dev_ms) / a.steps
+    elems = U * d
+    payload = buf.payload_bits.cpu().numpy().astype(np.float64)
+    container_bits = float(buf.chunk_offset[:, -1].cpu().numpy().astype(np.float64).sum()) \
+        + 64.0 * U * (plan.num_chunks + 1) + 16.0 * U * plan.num_chunks * 64
+    bpe = float(payload.sum()) / elems
+    status = buf.status.cpu().numpy().tolist()
+    if status[B.STAT_CAPACITY] or status[B.STAT_NOCODE] or status[B.STAT_CORRUPT] or status[B.STAT_CODELEN]:
+        print(f"bench.py: codec reported errors: status={status}", file=sys.stderr)
+        sys.exit(1)
+
+    per_launch = {k: v[0] / v[1] for k, v in kt.items()}
+    enc_kernels = ["k_zero_u64", "k_quantize", "k_build_books", "k_chunk_bits", "k_scan_chunks", "k_pack"]
+    enc_ms = sum(kt[k][0] for k in enc_kernels if k in kt) / a.steps
+    dec_ms = kt["k_aggregate"][0] / a.steps
+    # dominant kernel: the fused error-correction / fp-conversion / histogram sweep
+    dom = max(per_launch, key=lambda k: kt[k][0])
+    alg_bytes = {  # algorithmic bytes per element of each kernel ("Kernels")
+        "k_quantize": 13.0,            # read g, read m, write m', write symbol
+        "k_chunk_bits": 1.0,
+        "k_pack": 1.0 + bpe / 8.0,
+        "k_aggregate": bpe / 8.0 + 4.0 / U,
+    }
+    ach = alg_bytes.get(dom, 0.0) * elems / (per_launch[dom] * 1e-3) / 1e9
+    roof = dict(bound="hbm", kernel=dom, achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                frac=round(ach / HBM_PEAK_GBS, 4), traffic=None,
+                bytes_per_element=alg_bytes.get(dom), avg_launch_ms=round(per_launch[dom], 4))
+    enc_alg = (12.0 + bpe / 8.0) * elems
+    res = {
+        "metric": "CO3 encode+decode GElem/s and % HBM roofline on 1 MI355X; bits/element",
+        "value": round(elems / (ms_per_step * 1e-3) / 1e9, 3), "unit": "GElem/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32+u8",
+        "data": "synthetic GenNorm gradients (torch device generator), see DESIGN.md",
+        "config": {"workload": f"{w.name}: U={U} d={d} [1,{w.E},{w.M}] gamma={w.gamma} nseg={nseg} book={a.book} "
+                               f"(pooled over users)", "elements_per_step": elems},
+        "roofline": roof,
+        "encode": {"ms": round(enc_ms, 4), "gelem_s": round(elems / enc_ms / 1e6, 2),
+                   "hbm_frac_algorithmic": round(enc_alg / (enc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                   "bytes_per_element_algorithmic": round(12.0 + bpe / 8.0, 3)},
+        "decode_average": {"ms": round(dec_ms, 4), "gelem_s": round(elems / dec_ms / 1e6, 2),
+                           "hbm_frac_algorithmic": round((bpe / 8.0 + 4.0 / U) * elems / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "bits_per_element": {"payload": round(bpe, 4), "container": round(container_bits / elems, 4)},
+        "kernel_ms_per_launch": {k: round(v, 4) for k, v in per_launch.items()},
+        "status": status,
+    }
+    if not a.no_cpu_baseline:
+        ns = min(U, max(1, int(100e6 // d)))
+        host = pool[0][:ns, :d].cpu().numpy()
+        res["cpu_baseline"] = cpu_baseline(w, host, bias)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -80,8 +80,8 @@ typedef struct co3_codebook co3_codebook;   /* a set of Huffman code tables: lib
  * format and, per user and layer, the exponent bias) ------------------------------------
  * bias is host memory, [U][nseg]: the value exponent of exponent field f is f - bias, i.e.
  * the paper's c_scale = 2^b has b = (2^(exp_bits-1) - 1) - bias.  Required: bias <= 127 (the
- * smallest normal magnitude is a normal fp32) and (2^exp_bits - 2) - bias <= 100.  segments == NULL means one segment covering [0, d) with
- * codebook 0.  per_user_books != 0 gives every user its own tables (table index
+ * smallest normal magnitude is a normal fp32) and (2^exp_bits - 2) - bias <= 100.
+ * segments == NULL means one segment covering [0, d) with codebook 0.  per_user_books != 0 gives every user its own tables (table index
  * u * books_per_user + segment.codebook) instead of one table per layer shared by all users.
  * Allocates small device tables; synchronises the device.  Not on the per-iteration path:
  * the paper holds the bias for several epochs (Sec. VI).                                   */
@@ -184,6 +184,19 @@ typedef struct {
 /* Decode all U streams and average them (eq. (aggregate hat) without the learning rate):
  * out[i] = fl32((sum over u = 0..U-1, in fp64, of ghat_i^(u)) * (1.0 / U)).                 */
 int co3_ps_aggregate(const co3_plan *plan, const co3_aggregate_args *args, void *stream);
+
+/* ---- measurement aid ---------------------------------------------------------------------
+ * Between co3_profile_begin() and co3_profile_end() every kernel the library launches is
+ * bracketed by two HIP events recorded on the stream it is launched on.  co3_profile_end
+ * synchronises the device and returns, per kernel name, the summed elapsed time and the
+ * number of launches (at most `capacity` entries; *count gets the number written).         */
+typedef struct {
+    char name[32];
+    double total_ms;
+    uint64_t launches;
+} co3_kernel_time;
+int co3_profile_begin(void);
+int co3_profile_end(co3_kernel_time *out, uint32_t capacity, uint32_t *count);
 
 /* Human-readable name of a status code.                                                     */
 const char *co3_status_string(int status);

@@ -25,6 +25,7 @@ EXPORTS = [
     "co3_plan_alphabet", "co3_plan_symbols_bytes", "co3_plan_workspace_bytes", "co3_plan_stream_words",
     "co3_build_codebook", "co3_build_codebook_device", "co3_codebook_export", "co3_codebook_num_books",
     "co3_codebook_destroy", "co3_encode", "co3_decode", "co3_ps_aggregate", "co3_status_string",
+    "co3_profile_begin", "co3_profile_end",
 ]
 
 
@@ -53,6 +54,10 @@ class DecodeArgs(C.Structure):
 class AggregateArgs(C.Structure):
     _fields_ = [("words", C.c_void_p), ("words_stride", C.c_uint64), ("chunk_offset", C.c_void_p),
                 ("sub_bits", C.c_void_p), ("books", C.c_void_p), ("out", C.c_void_p), ("status", C.c_void_p)]
+
+
+class KernelTime(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("total_ms", C.c_double), ("launches", C.c_uint64)]
 
 
 class Co3Error(RuntimeError):
@@ -93,10 +98,23 @@ def lib():
         L.co3_encode.argtypes = [C.c_void_p, C.POINTER(EncodeArgs), C.c_void_p]
         L.co3_decode.argtypes = [C.c_void_p, C.POINTER(DecodeArgs), C.c_void_p]
         L.co3_ps_aggregate.argtypes = [C.c_void_p, C.POINTER(AggregateArgs), C.c_void_p]
+        L.co3_profile_end.argtypes = [C.POINTER(KernelTime), C.c_uint32, C.POINTER(C.c_uint32)]
         L.co3_status_string.argtypes = [C.c_int]
         L.co3_status_string.restype = C.c_char_p
         _lib = L
     return _lib
+
+
+def profile_begin():
+    _check("co3_profile_begin", lib().co3_profile_begin())
+
+
+def profile_end():
+    """{kernel name: (total ms, launches)} for the launches since profile_begin()."""
+    arr = (KernelTime * 16)()
+    n = C.c_uint32(0)
+    _check("co3_profile_end", lib().co3_profile_end(arr, 16, C.byref(n)))
+    return {arr[i].name.decode(): (arr[i].total_ms, int(arr[i].launches)) for i in range(n.value)}
 
 
 def status_string(code):

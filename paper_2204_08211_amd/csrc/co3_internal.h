@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdio.h>
 
 #include "co3.h"
 
@@ -14,6 +15,7 @@ constexpr int kSubsPerChunk = CO3_SUBS_PER_CHUNK;
 constexpr int kMaxA = 256;          // symbols are bytes
 constexpr int kDecBits = 11;        // prefix width of the direct decode table
 constexpr int kDecEntries = 1 << kDecBits;
+constexpr int kLongSlots = 64 - kDecBits;  // lengths kDecBits+1 .. 64
 constexpr int kFastLen = 24;        // longest code held in the 32-bit encode entry
 constexpr uint32_t kFastSlow = 0xFFu;  // length field marking "use the 64-bit table"
 
@@ -29,7 +31,14 @@ struct BookDev {
     uint8_t sorted[kMaxA];       // symbols ordered by (length, symbol)
     uint32_t maxlen;
     uint32_t nactive;
-    uint32_t pad[2];
+    // Lengths above kDecBits that occur, ascending.  A 64-bit left-aligned window w whose code is
+    // longer than kDecBits has the first listed length with w <= long_last[k]; its symbol is
+    // sorted[(uint32_t)(w >> (64 - len)) + long_base[k]].
+    uint32_t nlong;
+    uint32_t pad;
+    uint64_t long_last[kLongSlots];   // left-aligned last code of the length, low bits all ones
+    uint32_t long_base[kLongSlots];   // offset[len] - first[len] (mod 2^32)
+    uint32_t long_len[kLongSlots];
 };
 
 // One layer of the flat vector as the kernels read it.
@@ -74,6 +83,20 @@ struct co3_codebook {
 };
 
 namespace co3 {
+
+// Per-kernel event timing (profile.cpp).  A ProfScope around a launch records two events on
+// the stream when profiling is on, and does nothing otherwise.
+enum KernelId { K_ZERO = 0, K_QUANTIZE, K_BUILD_BOOKS, K_CHUNK_BITS, K_SCAN, K_PACK, K_DECODE, K_AGGREGATE, K_COUNT };
+bool profile_enabled();
+class ProfScope {
+public:
+    ProfScope(int kid, hipStream_t s);
+    ~ProfScope();
+private:
+    int kid_;
+    hipStream_t s_;
+    hipEvent_t start_;
+};
 
 // Host Huffman builder (host_codebook.cpp): fills one table; returns a co3_status.
 int build_book_host(const uint64_t *weights, uint32_t A, BookDev *out);

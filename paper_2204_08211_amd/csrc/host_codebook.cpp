@@ -41,6 +41,21 @@ static void finish_tables(BookDev *b, uint32_t A)
         b->offset[L] = off;
         off += b->count[L];
     }
+    // search list for codes longer than the direct table
+    b->nlong = 0;
+    b->pad = 0;
+    std::memset(b->long_last, 0, sizeof(b->long_last));
+    std::memset(b->long_base, 0, sizeof(b->long_base));
+    std::memset(b->long_len, 0, sizeof(b->long_len));
+    for (int L = kDecBits + 1; L <= 64; ++L) {
+        if (!b->count[L]) continue;
+        const uint32_t k = b->nlong++;
+        const uint64_t end_code = b->first[L] + b->count[L];                  // 2^L when the code is complete
+        const uint64_t end_la = (L == 64) ? end_code : (end_code << (64 - L));  // wraps to 0 then
+        b->long_last[k] = end_la - 1;
+        b->long_base[k] = b->offset[L] - (uint32_t)b->first[L];
+        b->long_len[k] = (uint32_t)L;
+    }
     uint32_t next[65];
     std::memset(next, 0, sizeof(next));
     for (uint32_t s = 0; s < A; ++s) {  // ascending symbol within each length

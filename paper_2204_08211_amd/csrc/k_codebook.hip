@@ -88,17 +88,31 @@ __global__ __launch_bounds__(kCbThreads) void k_build_books(BookDev *__restrict_
     __syncthreads();
     if (t == 0) {
         uint64_t code = 0;
-        uint32_t o = 0, mx = 0;
+        uint32_t o = 0, mx = 0, nlong = 0;
         for (int l = 1; l <= 64; ++l) {
             code = (code + cnt[l - 1]) << 1;
             first[l] = code;
             off[l] = o;
+            if (cnt[l]) {
+                mx = l;
+                if (l > kDecBits) {  // search list for codes longer than the direct table
+                    const uint64_t end_code = code + cnt[l];
+                    const uint64_t end_la = (l == 64) ? end_code : (end_code << (64 - l));
+                    B.long_last[nlong] = end_la - 1;
+                    B.long_base[nlong] = o - (uint32_t)code;
+                    B.long_len[nlong] = (uint32_t)l;
+                    ++nlong;
+                }
+            }
             o += cnt[l];
-            if (cnt[l]) mx = l;
+        }
+        for (uint32_t k = nlong; k < (uint32_t)kLongSlots; ++k) {
+            B.long_last[k] = 0; B.long_base[k] = 0; B.long_len[k] = 0;
         }
         B.maxlen = mx;
         B.nactive = bad ? 0 : (uint32_t)n;
-        B.pad[0] = B.pad[1] = 0;
+        B.nlong = nlong;
+        B.pad = 0;
     }
     __syncthreads();
 
@@ -137,6 +151,7 @@ hipError_t launch_build_books(BookDev *books, uint32_t nbooks, uint32_t A, const
                               uint64_t *status, hipStream_t s)
 {
     if (nbooks == 0) return hipSuccess;
+    ProfScope prof(K_BUILD_BOOKS, s);
     hipLaunchKernelGGL(k_build_books, dim3(nbooks), dim3(kCbThreads), 0, s, books, A, weights, status);
     return hipGetLastError();
 }

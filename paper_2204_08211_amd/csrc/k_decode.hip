@@ -1,16 +1,50 @@
 // PS side (Sec. II-B (iv); Algorithm 1 lines 13-14): invert h_Hf for every user's stream and
 // form (1/U) sum_u ghat^(u), eq. (aggregate hat) without the learning rate.
 //
-// One wavefront per chunk; lane j owns sub-chunk j (64 elements), whose start is the chunk's
-// bit offset plus the prefix sum of the sub-chunk bit counts.  Codes of up to kDecBits bits are
-// resolved by one LDS table lookup; longer ones by the canonical first-code search.  Decoded
-// symbols are staged in LDS so that global stores are coalesced across the wave.
+// A wavefront decodes one chunk of one user.  It first copies the chunk's words from HBM into
+// LDS with coalesced loads; then lane j decodes sub-chunk j (64 elements), whose start is the
+// prefix sum of the sub-chunk bit counts.  Codes of up to kDecBits bits are resolved by one LDS
+// table lookup; longer ones by a search over the canonical code's length boundaries.  Decoded
+// symbols are staged in LDS so that global stores (and the accumulation over users) are
+// coalesced.  A chunk whose words do not fit the LDS window is decoded straight from global
+// memory (same code, slower).
+//
+// The work is bound by the serial integer chain of the decoder (table lookup -> shift -> next
+// lookup), not by HBM: it moves about b/8 + 4/U bytes per element.
 #include "co3_internal.h"
 #include "quantize_math.h"
 
 namespace co3 {
 
-constexpr int kStageStride = 17;  // words per staged sub-chunk row (16 + 1: spreads LDS banks)
+constexpr int kStageStride = 17;                            // words per staged sub-chunk row (16 + 1 pad)
+constexpr int kStageWords = kSubsPerChunk * kStageStride;   // one chunk of one user
+constexpr int kPayloadWords = 1152;                         // LDS window for a chunk's words (9 bit/element)
+constexpr int kPayloadPerLane = kPayloadWords / 64;
+
+// Decode tables of one code in LDS.
+struct DecLds {
+    uint16_t dec[kDecEntries];
+    uint64_t long_last[kLongSlots];
+    uint32_t long_base[kLongSlots];
+    uint32_t long_len[kLongSlots];
+    uint8_t sorted[kMaxA];
+    uint32_t nlong;
+    uint32_t pad;
+};
+
+__device__ inline void load_dec_tables(DecLds *T, const BookDev &book, uint32_t t, uint32_t nthreads)
+{
+    for (uint32_t i = t; i < kDecEntries / 2; i += nthreads)
+        reinterpret_cast<uint32_t *>(T->dec)[i] = reinterpret_cast<const uint32_t *>(book.dec)[i];
+    for (uint32_t i = t; i < (uint32_t)kLongSlots; i += nthreads) {
+        T->long_last[i] = book.long_last[i];
+        T->long_base[i] = book.long_base[i];
+        T->long_len[i] = book.long_len[i];
+    }
+    for (uint32_t i = t; i < kMaxA / 4; i += nthreads)
+        reinterpret_cast<uint32_t *>(T->sorted)[i] = reinterpret_cast<const uint32_t *>(book.sorted)[i];
+    if (t == 0) { T->nlong = book.nlong; T->pad = 0; }
+}
 
 __device__ inline uint32_t find_chunk_segment_d(const SegDev *segs, uint32_t nseg, uint64_t chunk)
 {
@@ -34,67 +68,114 @@ __device__ inline uint32_t wave_exclusive_scan_u32(uint32_t x)
     return incl - x;
 }
 
-__device__ inline uint32_t load_word(const uint32_t *w, uint64_t i, uint64_t limit)
+// Word sources of the decoder: index 0 is the chunk's first word.  A well-formed stream never
+// consumes bits beyond its chunk; what a read beyond the end returns only has to be harmless.
+struct LdsWords {
+    const uint32_t *base;   // kPayloadWords allocated words; the chunk's words in front
+    // clamped to the window: one instruction, always inside the allocation
+    __device__ inline uint32_t word(uint32_t i) const
+    {
+        return base[i < (uint32_t)(kPayloadWords - 1) ? i : (uint32_t)(kPayloadWords - 1)];
+    }
+};
+struct GlobalWords {
+    const uint32_t *base;   // chunk's first word in the user's stream
+    uint64_t n;             // words of the chunk
+    __device__ inline uint32_t word(uint32_t i) const { return i < n ? base[i] : 0u; }
+};
+
+// (length << 8) | symbol of the code longer than kDecBits that starts at bit `pos` of the chunk,
+// 0 if none matches.  Left-aligned canonical codes grow with their length, so the code's length
+// is the first listed one whose last code is not below the window.
+template <class Src>
+__device__ __noinline__ uint32_t long_code(Src src, const DecLds *T, uint32_t pos)
 {
-    return i < limit ? w[i] : 0u;
+    const uint32_t i0 = pos >> 5, s0 = pos & 31u;
+    uint64_t full = (((uint64_t)src.word(i0) << 32) | src.word(i0 + 1)) << s0;
+    if (s0) full |= (uint64_t)(src.word(i0 + 2) >> (32u - s0));
+    const uint32_t n = T->nlong;
+    for (uint32_t k = 0; k < n; ++k) {
+        if (full <= T->long_last[k]) {
+            const uint32_t L = T->long_len[k];
+            const uint32_t idx = (uint32_t)(full >> (64u - L)) + T->long_base[k];
+            return (L << 8) | T->sorted[idx & (kMaxA - 1)];
+        }
+    }
+    return 0u;
 }
 
-// Decode `cnt` (<= 64) symbols of one sub-chunk starting at bit `p0` of stream `w`; symbols go
-// to stage_row[0..16] (4 per word).  Returns the number of bits consumed, or ~0u if a prefix
-// matched no codeword.
-__device__ inline uint32_t decode_subchunk(const uint32_t *__restrict__ w, uint64_t limit, uint64_t p0, int cnt,
-                                           const uint16_t *s_dec, const BookDev &book, uint32_t *stage_row)
-{
-    uint64_t wi = p0 >> 5;
-    uint32_t sh = (uint32_t)(p0 & 31u);
-    uint64_t window = (((uint64_t)load_word(w, wi, limit) << 32) | load_word(w, wi + 1, limit)) << sh;
-    uint32_t avail = 64u - sh;
-    wi += 2;
-    uint32_t consumed = 0, packed = 0;
-    for (int j = 0; j < cnt; ++j) {
-        if (avail < 32u) {
-            window |= (uint64_t)load_word(w, wi++, limit) << (32u - avail);
-            avail += 32u;
-        }
-        const uint32_t e = s_dec[window >> (64 - kDecBits)];
-        uint32_t L = e >> 8, s = e & 0xffu;
-        if (L == 0u) {
-            // long code: exact 64-bit window at the current position, canonical search
-            const uint64_t pos = p0 + consumed;
-            const uint64_t i0 = pos >> 5;
-            const uint32_t s0 = (uint32_t)(pos & 31u);
-            uint64_t full = (((uint64_t)load_word(w, i0, limit) << 32) | load_word(w, i0 + 1, limit)) << s0;
-            if (s0) full |= (uint64_t)(load_word(w, i0 + 2, limit) >> (32u - s0));
-            const uint32_t maxlen = book.maxlen;
-            for (uint32_t l = kDecBits + 1; l <= maxlen; ++l) {
-                const uint32_t n_l = book.count[l];
-                if (!n_l) continue;
-                const uint64_t c = full >> (64u - l);
-                const uint64_t f = book.first[l];
-                if (c >= f && c - f < (uint64_t)n_l) {
-                    L = l;
-                    s = book.sorted[book.offset[l] + (uint32_t)(c - f)];
-                    break;
-                }
-            }
-            if (L == 0u) return ~0u;
-            consumed += L;
-            const uint64_t np = pos + L;
-            wi = np >> 5;
-            sh = (uint32_t)(np & 31u);
-            window = (((uint64_t)load_word(w, wi, limit) << 32) | load_word(w, wi + 1, limit)) << sh;
-            avail = 64u - sh;
-            wi += 2;
-        } else {
-            window <<= L;
-            avail -= L;
-            consumed += L;
-        }
-        packed |= s << (8 * (j & 3));
-        if ((j & 3) == 3) { stage_row[j >> 2] = packed; packed = 0; }
+// Sequential bit reader of one lane: `window` holds the next bits left-aligned, of which `avail`
+// are valid; invariant before every table lookup: avail >= 32.
+template <class Src>
+struct Reader {
+    Src src;
+    uint64_t window;
+    uint32_t avail, wi;
+    __device__ inline void seek(uint32_t pos)
+    {
+        wi = pos >> 5;
+        const uint32_t sh = pos & 31u;
+        window = (((uint64_t)src.word(wi) << 32) | src.word(wi + 1)) << sh;
+        avail = 64u - sh;
+        wi += 2;
     }
-    if (cnt & 3) stage_row[cnt >> 2] = packed;
-    return consumed;
+};
+
+// One symbol.  Returns it; `consumed` advances by its length; `bad` is set if nothing matched.
+template <class Src>
+__device__ inline uint32_t decode_symbol(Reader<Src> &r, const DecLds *T, uint32_t p0, uint32_t &consumed, bool &bad)
+{
+    uint32_t nextw = r.src.word(r.wi);                       // both LDS reads are requested
+    uint32_t e = T->dec[r.window >> (64 - kDecBits)];        // before either result is needed
+    asm volatile("" : "+v"(nextw), "+v"(e));
+    uint32_t L = e >> 8, s = e & 0xffu;
+    if (__builtin_expect(L == 0u, 0)) {
+        const uint32_t code = long_code(r.src, T, p0 + consumed);
+        L = code >> 8;
+        s = code & 0xffu;
+        if (L == 0u) { bad = true; L = 1u; }
+        consumed += L;
+        r.seek(p0 + consumed);
+    } else {
+        r.window <<= L;
+        r.avail -= L;
+        consumed += L;
+        const bool take = r.avail < 32u;
+        const uint64_t add = (uint64_t)nextw << ((32u - r.avail) & 31u);
+        r.window |= take ? add : 0ull;
+        r.avail += take ? 32u : 0u;
+        r.wi += take ? 1u : 0u;
+    }
+    return s;
+}
+
+// Decode `cnt` (<= 64) symbols of one sub-chunk starting `p0` bits into the chunk; symbols go to
+// stage_row[0..16] (4 per word).  Returns the number of bits consumed, or ~0u if a prefix matched
+// no codeword.
+template <class Src>
+__device__ inline uint32_t decode_subchunk(Src src, uint32_t p0, int cnt, const DecLds *T, uint32_t *stage_row)
+{
+    Reader<Src> r;
+    r.src = src;
+    r.seek(p0);
+    uint32_t consumed = 0;
+    bool bad = false;
+    if (cnt == kSub) {
+        for (int jj = 0; jj < kSub / 4; ++jj) {
+            uint32_t packed = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) packed |= decode_symbol(r, T, p0, consumed, bad) << (8 * b);
+            stage_row[jj] = packed;
+        }
+    } else {
+        uint32_t packed = 0;
+        for (int j = 0; j < cnt; ++j) {
+            packed |= decode_symbol(r, T, p0, consumed, bad) << (8 * (j & 3));
+            if ((j & 3) == 3) { stage_row[j >> 2] = packed; packed = 0; }
+        }
+        if (cnt & 3) stage_row[cnt >> 2] = packed;
+    }
+    return bad ? ~0u : consumed;
 }
 
 struct ChunkGeom {
@@ -116,22 +197,64 @@ __device__ inline ChunkGeom chunk_geom(const Layout &lay, uint64_t c)
     return g;
 }
 
-// Decode the lane's sub-chunk of user u, chunk c into the LDS stage; flags corrupt sub-chunks.
-__device__ inline void decode_user_chunk(const Layout &lay, const ChunkGeom &g, uint64_t c, uint32_t u,
-                                         const uint32_t *__restrict__ words, uint64_t words_stride,
-                                         const uint64_t *__restrict__ chunk_offset,
-                                         const uint16_t *__restrict__ sub_bits, const BookDev &book,
-                                         const uint16_t *s_dec, uint32_t *s_stage, uint64_t *status)
+// What a wavefront needs to know about chunk c of user u before it can decode it.
+struct ChunkIndex {
+    const uint32_t *w;   // chunk's first word
+    uint32_t nw;         // its words (0 if the index is malformed)
+    uint32_t sb;         // this lane's sub-chunk bit count
+    bool ok;             // 32-bit aligned, ordered, inside the buffer
+    bool in_lds;         // fits the LDS window
+};
+
+__device__ inline ChunkIndex read_index(const Layout &lay, uint64_t c, uint32_t u, const uint32_t *__restrict__ words,
+                                        uint64_t words_stride, const uint64_t *__restrict__ chunk_offset,
+                                        const uint16_t *__restrict__ sub_bits)
 {
+    ChunkIndex ix;
     const uint32_t lane = threadIdx.x & 63;
     const uint64_t off = chunk_offset[(uint64_t)u * (lay.nchunks + 1) + c];
-    const uint32_t sb = sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane];
-    const uint64_t p0 = off + wave_exclusive_scan_u32(sb);
+    const uint64_t end = chunk_offset[(uint64_t)u * (lay.nchunks + 1) + c + 1];
+    ix.sb = sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane];
+    ix.ok = !(off & 31u) && end >= off && (end >> 5) <= words_stride &&
+            ((end - off) >> 5) <= (uint64_t)kChunk * CO3_MAX_CODE_LEN / 32;
+    ix.nw = ix.ok ? (uint32_t)((end - off) >> 5) : 0u;
+    ix.w = words + (uint64_t)u * words_stride + (ix.ok ? (off >> 5) : 0);
+    ix.in_lds = ix.nw <= (uint32_t)kPayloadWords;
+    return ix;
+}
+
+// One wavefront: bring the chunk into s_pay (if it fits), decode it into s_stage.  Every read of
+// the stream stays inside the chunk's words.  Inconsistent sub-chunks are counted in
+// status[CO3_STAT_CORRUPT].  Contains wave-level synchronisation only.
+__device__ inline void decode_user_chunk(const ChunkGeom &g, const ChunkIndex &ix, const DecLds *T,
+                                         uint32_t *s_pay, uint32_t *s_stage, uint64_t *status)
+{
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t p0 = wave_exclusive_scan_u32(ix.sb);
     const int first_elem = (int)lane * kSub;
     const int cnt = (int)g.n - first_elem < 0 ? 0 : ((int)g.n - first_elem > kSub ? kSub : (int)g.n - first_elem);
-    const uint32_t *w = words + (uint64_t)u * words_stride;
-    const uint32_t used = decode_subchunk(w, words_stride, p0, cnt, s_dec, book, s_stage + lane * kStageStride);
-    if (used != sb || (off & 31u) || p0 + sb > words_stride * 32ull)
+    uint32_t used = 0;
+    if (ix.in_lds) {
+        // all loads first, then all LDS stores: one memory latency for the whole chunk
+        uint32_t tmp[kPayloadPerLane];
+#pragma unroll
+        for (int k = 0; k < kPayloadPerLane; ++k) {
+            const uint32_t i = lane + 64u * k;
+            tmp[k] = i < ix.nw ? ix.w[i] : 0u;
+        }
+#pragma unroll
+        for (int k = 0; k < kPayloadPerLane; ++k) {
+            const uint32_t i = lane + 64u * k;
+            if (i < ix.nw) s_pay[i] = tmp[k];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (cnt > 0) used = decode_subchunk(LdsWords{s_pay}, p0, cnt, T, s_stage + lane * kStageStride);
+    } else if (cnt > 0) {
+        used = decode_subchunk(GlobalWords{ix.w, ix.nw}, p0, cnt, T, s_stage + lane * kStageStride);
+    }
+    if (used != ix.sb || !ix.ok)
         atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CORRUPT), 1ull);
 }
 
@@ -142,17 +265,18 @@ __global__ __launch_bounds__(64) void k_decode(Layout lay, const uint32_t *__res
                                                uint64_t sym_stride, float *__restrict__ q, uint64_t q_stride,
                                                uint64_t *__restrict__ status)
 {
-    __shared__ uint16_t s_dec[kDecEntries];
-    __shared__ uint32_t s_stage[kSubsPerChunk * kStageStride];
+    __shared__ DecLds s_tab;
+    __shared__ uint32_t s_stage[kStageWords];
+    __shared__ uint32_t s_pay[kPayloadWords];
     const uint32_t lane = threadIdx.x;
     const uint64_t c = blockIdx.x;
     const uint32_t u = blockIdx.y;
     const ChunkGeom g = chunk_geom(lay, c);
     const BookDev &book = books[(lay.per_user_books ? u * lay.books_per_user : 0u) + (uint32_t)g.book];
-    for (int i = lane; i < kDecEntries / 2; i += 64)
-        reinterpret_cast<uint32_t *>(s_dec)[i] = reinterpret_cast<const uint32_t *>(book.dec)[i];
+    const ChunkIndex ix = read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits);
+    load_dec_tables(&s_tab, book, lane, 64);
     __syncthreads();
-    decode_user_chunk(lay, g, c, u, words, words_stride, chunk_offset, sub_bits, book, s_dec, s_stage, status);
+    decode_user_chunk(g, ix, &s_tab, s_pay, s_stage, status);
     __syncthreads();
     const uint8_t *stage_b = reinterpret_cast<const uint8_t *>(s_stage);
     if (sym) {
@@ -178,53 +302,83 @@ __global__ __launch_bounds__(64) void k_decode(Layout lay, const uint32_t *__res
     }
 }
 
-__global__ __launch_bounds__(64) void k_aggregate(Layout lay, const uint32_t *__restrict__ words,
-                                                  uint64_t words_stride, const uint64_t *__restrict__ chunk_offset,
-                                                  const uint16_t *__restrict__ sub_bits,
-                                                  const BookDev *__restrict__ books, float *__restrict__ out,
-                                                  uint64_t *__restrict__ status)
+// One workgroup per chunk; W wavefronts decode W users at a time into LDS, then every thread
+// sums its elements over those users in ascending user order, in fp64.
+template <int W>
+__global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t *__restrict__ words,
+                                                      uint64_t words_stride,
+                                                      const uint64_t *__restrict__ chunk_offset,
+                                                      const uint16_t *__restrict__ sub_bits,
+                                                      const BookDev *__restrict__ books, float *__restrict__ out,
+                                                      uint64_t *__restrict__ status)
 {
-    __shared__ uint16_t s_dec[kDecEntries];
-    __shared__ uint32_t s_stage[kSubsPerChunk * kStageStride];
-    const uint32_t lane = threadIdx.x;
+    extern __shared__ uint64_t smem64[];
+    DecLds *s_tab = reinterpret_cast<DecLds *>(smem64);   // [per-user books ? W : 1]
+    const uint32_t ntab = lay.per_user_books ? W : 1;
+    DqConst *s_dq = reinterpret_cast<DqConst *>(s_tab + ntab);             // [W]
+    uint32_t *s_stage = reinterpret_cast<uint32_t *>(s_dq + W);            // [W][kStageWords]
+    uint32_t *s_pay = s_stage + W * kStageWords;                           // [W][kPayloadWords]
+    constexpr int T = 64 * W;
+    constexpr int G = (kChunk / 4) / T;  // 4-element groups per thread
+    const uint32_t t = threadIdx.x, wave = t >> 6;
     const uint64_t c = blockIdx.x;
     const ChunkGeom g = chunk_geom(lay, c);
-    double acc[kSub];
+
+    double acc[G][4];
 #pragma unroll
-    for (int i = 0; i < kSub; ++i) acc[i] = 0.0;
-    int loaded_book = -1;
-    for (uint32_t u = 0; u < lay.U; ++u) {
-        const int bi = (int)((lay.per_user_books ? u * lay.books_per_user : 0u) + (uint32_t)g.book);
-        const BookDev &book = books[bi];
-        if (bi != loaded_book) {
-            __syncthreads();
-            for (int i = lane; i < kDecEntries / 2; i += 64)
-                reinterpret_cast<uint32_t *>(s_dec)[i] = reinterpret_cast<const uint32_t *>(book.dec)[i];
-            loaded_book = bi;
+    for (int i = 0; i < G; ++i)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[i][b] = 0.0;
+
+    for (uint32_t u0 = 0; u0 < lay.U; u0 += W) {
+        const uint32_t u = u0 + wave;
+        const bool active = u < lay.U;
+        ChunkIndex ix;
+        if (active) ix = read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits);
+        const DecLds *my_tab = s_tab;
+        if (lay.per_user_books) {
+            my_tab = s_tab + wave;
+            if (active) load_dec_tables(s_tab + wave, books[u * lay.books_per_user + (uint32_t)g.book], t & 63u, 64);
+        } else if (u0 == 0) {
+            load_dec_tables(s_tab, books[(uint32_t)g.book], t, T);
         }
+        if (t < (uint32_t)W && u0 + t < lay.U)
+            s_dq[t] = make_dqconst(lay.E, lay.M, lay.bias[(uint64_t)(u0 + t) * lay.nseg + g.seg]);
         __syncthreads();
-        decode_user_chunk(lay, g, c, u, words, words_stride, chunk_offset, sub_bits, book, s_dec, s_stage, status);
+        if (active) decode_user_chunk(g, ix, my_tab, s_pay + wave * kPayloadWords, s_stage + wave * kStageWords, status);
         __syncthreads();
-        const int bias = lay.bias[(uint64_t)u * lay.nseg + g.seg];
-        // lane owns elements 256*it + 4*lane + b: rows 4*it + lane/16, word lane%16
+        const uint32_t nu = (lay.U - u0 < (uint32_t)W) ? lay.U - u0 : (uint32_t)W;
+        for (uint32_t uu = 0; uu < nu; ++uu) {
+            const DqConst dq = s_dq[uu];
+            const uint32_t *st = s_stage + uu * kStageWords;
 #pragma unroll
-        for (int it = 0; it < 16; ++it) {
-            const uint32_t wv = s_stage[(4 * it + (lane >> 4)) * kStageStride + (lane & 15u)];
+            for (int i = 0; i < G; ++i) {
+                const uint32_t e4 = t + (uint32_t)i * T;  // group of elements 4*e4 .. 4*e4+3
+                const uint32_t wv = st[(e4 >> 4) * kStageStride + (e4 & 15u)];
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const uint32_t s = (wv >> (8 * b)) & 0xffu;
-                acc[4 * it + b] += (double)__uint_as_float(symbol_value_bits(s, lay.E, lay.M, bias));
+                for (int b = 0; b < 4; ++b) {
+                    const uint32_t s = (wv >> (8 * b)) & 0xffu;
+                    acc[i][b] += symbol_value_f64(s, dq);
+                }
             }
         }
+        __syncthreads();
     }
     const double inv_u = 1.0 / (double)lay.U;
     float *dst = out + g.e0;
+    const bool vec_ok = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
 #pragma unroll
-    for (int it = 0; it < 16; ++it) {
+    for (int i = 0; i < G; ++i) {
+        const uint32_t e = 4u * (t + (uint32_t)i * T);
+        float r[4];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const uint32_t e = 256u * it + 4u * lane + b;
-            if (e < g.n) dst[e] = (float)(acc[4 * it + b] * inv_u);
+        for (int b = 0; b < 4; ++b) r[b] = (float)(acc[i][b] * inv_u);
+        if (vec_ok && e + 3 < g.n) {
+            *reinterpret_cast<float4 *>(dst + e) = make_float4(r[0], r[1], r[2], r[3]);
+        } else {
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                if (e + b < g.n) dst[e + b] = r[b];
         }
     }
 }
@@ -233,17 +387,34 @@ hipError_t launch_decode(const Layout &lay, const co3_decode_args &a, const Book
 {
     if (lay.U == 0 || lay.nchunks == 0) return hipSuccess;
     const uint64_t sym_stride = (lay.d + 15) & ~(uint64_t)15;
+    ProfScope prof(K_DECODE, s);
     hipLaunchKernelGGL(k_decode, dim3((uint32_t)lay.nchunks, lay.U), dim3(64), 0, s, lay, a.words, a.words_stride,
                        a.chunk_offset, a.sub_bits, books, a.symbols, sym_stride, a.q, a.q_stride, a.status);
+    return hipGetLastError();
+}
+
+template <int W>
+static hipError_t launch_aggregate_w(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
+                                     hipStream_t s)
+{
+    const size_t lds = (size_t)(lay.per_user_books ? W : 1) * sizeof(DecLds) + (size_t)W * sizeof(DqConst) +
+                       (size_t)W * (kStageWords + kPayloadWords) * 4;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_aggregate<W>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    ProfScope prof(K_AGGREGATE, s);
+    hipLaunchKernelGGL(k_aggregate<W>, dim3((uint32_t)lay.nchunks), dim3(64 * W), lds, s, lay, a.words,
+                       a.words_stride, a.chunk_offset, a.sub_bits, books, a.out, a.status);
     return hipGetLastError();
 }
 
 hipError_t launch_aggregate(const Layout &lay, const co3_aggregate_args &a, const BookDev *books, hipStream_t s)
 {
     if (lay.U == 0 || lay.nchunks == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_aggregate, dim3((uint32_t)lay.nchunks), dim3(64), 0, s, lay, a.words, a.words_stride,
-                       a.chunk_offset, a.sub_bits, books, a.out, a.status);
-    return hipGetLastError();
+    if (lay.U >= 5) return launch_aggregate_w<8>(lay, a, books, s);
+    if (lay.U >= 3) return launch_aggregate_w<4>(lay, a, books, s);
+    if (lay.U == 2) return launch_aggregate_w<2>(lay, a, books, s);
+    return launch_aggregate_w<1>(lay, a, books, s);
 }
 
 }  // namespace co3

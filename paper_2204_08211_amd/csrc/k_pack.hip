@@ -204,13 +204,18 @@ hipError_t launch_pack(const Layout &lay, const co3_encode_args &a, const BookDe
     if (lay.U == 0) return hipSuccess;
     const uint64_t sym_stride = (lay.d + 15) & ~(uint64_t)15;
     if (lay.nchunks) {
+        ProfScope prof(K_CHUNK_BITS, s);
         hipLaunchKernelGGL(k_pack_chunks<false>, dim3((uint32_t)lay.nchunks, lay.U), dim3(kPkThreads), 0, s, lay,
                            a.symbols, sym_stride, books, ws.chunk_bits, a.chunk_offset, a.sub_bits, a.words,
                            a.words_stride, a.status);
     }
+    {
+    ProfScope prof(K_SCAN, s);
     hipLaunchKernelGGL(k_scan_chunks, dim3(lay.U), dim3(kScanThreads), 0, s, lay.nchunks, ws.chunk_bits,
                        a.chunk_offset, a.payload_bits);
+    }
     if (lay.nchunks) {
+        ProfScope prof(K_PACK, s);
         hipLaunchKernelGGL(k_pack_chunks<true>, dim3((uint32_t)lay.nchunks, lay.U), dim3(kPkThreads), 0, s, lay,
                            a.symbols, sym_stride, books, ws.chunk_bits, a.chunk_offset, a.sub_bits, a.words,
                            a.words_stride, a.status);

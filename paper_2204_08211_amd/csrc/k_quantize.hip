@@ -146,6 +146,7 @@ __global__ void k_zero_u64(uint64_t *p, uint64_t n)
 hipError_t launch_zero_u64(uint64_t *p, uint64_t n, hipStream_t s)
 {
     if (n == 0) return hipSuccess;
+    ProfScope prof(K_ZERO, s);
     hipLaunchKernelGGL(k_zero_u64, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0, s, p, n);
     return hipGetLastError();
 }
@@ -161,6 +162,7 @@ hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, hipStrea
     const uint32_t gx = (uint32_t)((ntiles + tiles_per_block - 1) / tiles_per_block);
     const uint64_t sym_stride = (lay.d + 15) & ~(uint64_t)15;
     const size_t lds = (size_t)lay.A * kHistRep * sizeof(uint32_t);
+    ProfScope prof(K_QUANTIZE, s);
     hipLaunchKernelGGL(k_quantize, dim3(gx, lay.U), dim3(kQThreads), lds, s, lay, a.g, a.m, a.m_out,
                        a.symbols, sym_stride, a.row_stride, a.gamma, a.hist, a.status, tiles_per_block);
     return hipGetLastError();
