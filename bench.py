@@ -135,7 +135,8 @@ def main():
         sys.exit(1)
 
     per_launch = {k: v[0] / v[1] for k, v in kt.items()}
-    enc_kernels = ["k_zero_u64", "k_quantize", "k_build_books", "k_chunk_bits", "k_scan_chunks", "k_pack"]
+    enc_kernels = ["k_zero_u64", "k_quantize", "k_reduce_hist", "k_build_books", "k_chunk_bits", "k_scan_chunks",
+                   "k_pack"]
     enc_ms = sum(kt[k][0] for k in enc_kernels if k in kt) / a.steps
     dec_ms = kt["k_aggregate"][0] / a.steps
     # dominant kernel: the fused error-correction / fp-conversion / histogram sweep

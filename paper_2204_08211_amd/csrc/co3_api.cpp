@@ -141,7 +141,9 @@ size_t co3_plan_symbols_bytes(const co3_plan *plan)
 size_t co3_plan_workspace_bytes(const co3_plan *plan)
 {
     if (!plan) return 0;
-    return (size_t)(plan->lay.nchunks * plan->lay.U * sizeof(uint32_t) + 256);
+    const Layout &l = plan->lay;
+    const size_t hist_rep = ((size_t)kHistGlobalRep * l.nbooks * l.A * sizeof(uint64_t) + 255) & ~(size_t)255;
+    return hist_rep + (size_t)(l.nchunks * l.U * sizeof(uint32_t)) + 512;
 }
 
 uint64_t co3_plan_stream_words(const co3_plan *plan, uint32_t max_code_len)
@@ -247,10 +249,13 @@ int co3_encode(const co3_plan *plan, const co3_encode_args *a, void *stream)
     DeviceGuard guard(plan->device);
     hipStream_t s = static_cast<hipStream_t>(stream);
     EncodeWs ws;
-    ws.chunk_bits = reinterpret_cast<uint32_t *>((reinterpret_cast<uintptr_t>(a->workspace) + 255u) & ~(uintptr_t)255u);
+    const uint64_t hist_rep_n = (uint64_t)kHistGlobalRep * lay.nbooks * lay.A;
+    ws.hist_rep = reinterpret_cast<uint64_t *>((reinterpret_cast<uintptr_t>(a->workspace) + 255u) & ~(uintptr_t)255u);
+    ws.chunk_bits = reinterpret_cast<uint32_t *>(
+        (reinterpret_cast<uintptr_t>(ws.hist_rep + hist_rep_n) + 255u) & ~(uintptr_t)255u);
 
-    if (launch_zero_u64(a->hist, (uint64_t)lay.nbooks * lay.A, s) != hipSuccess) return CO3_ERR_HIP;
-    if (launch_quantize(lay, *a, s) != hipSuccess) return CO3_ERR_HIP;
+    if (launch_zero_u64(ws.hist_rep, hist_rep_n, s) != hipSuccess) return CO3_ERR_HIP;
+    if (launch_quantize(lay, *a, ws, s) != hipSuccess) return CO3_ERR_HIP;
     if (a->mode == CO3_BOOK_EMPIRICAL &&
         launch_build_books(a->books->d_books, lay.nbooks, lay.A, a->hist, a->status, s) != hipSuccess)
         return CO3_ERR_HIP;

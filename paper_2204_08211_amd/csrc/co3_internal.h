@@ -16,6 +16,7 @@ constexpr int kMaxA = 256;          // symbols are bytes
 constexpr int kDecBits = 11;        // prefix width of the direct decode table
 constexpr int kDecEntries = 1 << kDecBits;
 constexpr int kLongSlots = 64 - kDecBits;  // lengths kDecBits+1 .. 64
+constexpr int kHistGlobalRep = 64;   // copies of the global symbol-count table the workgroups spread over
 constexpr int kFastLen = 24;        // longest code held in the 32-bit encode entry
 constexpr uint32_t kFastSlow = 0xFFu;  // length field marking "use the 64-bit table"
 
@@ -86,7 +87,7 @@ namespace co3 {
 
 // Per-kernel event timing (profile.cpp).  A ProfScope around a launch records two events on
 // the stream when profiling is on, and does nothing otherwise.
-enum KernelId { K_ZERO = 0, K_QUANTIZE, K_BUILD_BOOKS, K_CHUNK_BITS, K_SCAN, K_PACK, K_DECODE, K_AGGREGATE, K_COUNT };
+enum KernelId { K_ZERO = 0, K_QUANTIZE, K_REDUCE_HIST, K_BUILD_BOOKS, K_CHUNK_BITS, K_SCAN, K_PACK, K_DECODE, K_AGGREGATE, K_COUNT };
 bool profile_enabled();
 class ProfScope {
 public:
@@ -103,11 +104,12 @@ int build_book_host(const uint64_t *weights, uint32_t A, BookDev *out);
 
 // Kernel launchers (one per .hip file).  All return a hipError_t from hipGetLastError().
 struct EncodeWs {
+    uint64_t *hist_rep;     // [kHistGlobalRep][nbooks][A] partial symbol counts
     uint32_t *chunk_bits;   // [U][nchunks]
 };
 
 hipError_t launch_zero_u64(uint64_t *p, uint64_t n, hipStream_t s);
-hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, hipStream_t s);
+hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, const EncodeWs &ws, hipStream_t s);
 hipError_t launch_build_books(BookDev *books, uint32_t nbooks, uint32_t A, const uint64_t *weights,
                               uint64_t *status, hipStream_t s);
 hipError_t launch_pack(const Layout &lay, const co3_encode_args &a, const BookDev *books,

@@ -2,32 +2,25 @@
 // (Algorithm 1 lines 8 and 10; Sec. IV-A (i) and (iii); Sec. V-B for the representative set).
 //
 // Per element:  v = fl32(g + fl32(gamma * m));  q = Q_fp(v);  m' = fl32(v - q);  sym = code of q.
-// HBM traffic per element: read g (4) + read m (4) + write m' (4) + write sym (1).
+// HBM traffic per element: read g (4) + read m (4) + write m' (4) + write sym (1) = 13 bytes.
+//
+// One workgroup of 512 threads per tile of 4096 elements, in memory order, so the tiles in
+// flight at any moment form a compact window of addresses (measured: a grid-stride loop over
+// the same tiles loses a tenth of the bandwidth).  Streaming data is loaded and stored with
+// the nontemporal hint.  Symbol counts go to lane-replicated LDS bins (the peaked symbol
+// distribution would otherwise serialise the atomics), are summed per workgroup and added to
+// one of kHistGlobalRep copies of the global table, so that no address sees every workgroup;
+// k_reduce_hist folds the copies.
 #include "co3_internal.h"
 #include "quantize_math.h"
 
 namespace co3 {
 
-constexpr int kQThreads = 256;
-constexpr int kQTile = kQThreads * 8;   // elements per block iteration (two float4 per thread)
-constexpr int kHistRep = 32;            // lane-replicated copies of every bin (one per LDS bank)
+typedef float f4 __attribute__((ext_vector_type(4)));
 
-// Sum the replicated LDS bins into the global table of one book, then clear them.
-__device__ inline void flush_hist(uint32_t *h_lds, uint32_t A, uint64_t *hist_book)
-{
-    __syncthreads();
-    for (uint32_t bin = threadIdx.x; bin < A; bin += kQThreads) {
-        uint32_t s = 0;
-#pragma unroll
-        for (int r = 0; r < kHistRep; ++r) {
-            uint32_t idx = bin * kHistRep + ((r + bin) & (kHistRep - 1));  // rotate: spread banks
-            s += h_lds[idx];
-            h_lds[idx] = 0;
-        }
-        if (s) atomicAdd(reinterpret_cast<unsigned long long *>(hist_book + bin), (unsigned long long)s);
-    }
-    __syncthreads();
-}
+constexpr int kQThreads = 512;
+constexpr int kQTile = kQThreads * 8;   // two 16-byte vectors of g and of m per thread
+constexpr int kHistRep = 32;            // lane-replicated copies of every LDS bin (one per bank)
 
 __device__ inline uint32_t find_segment(const SegDev *segs, uint32_t nseg, uint64_t elem)
 {
@@ -43,97 +36,106 @@ __device__ inline uint32_t find_segment(const SegDev *segs, uint32_t nseg, uint6
 __global__ __launch_bounds__(kQThreads) void k_quantize(
     Layout lay, const float *__restrict__ g, const float *m, float *m_out,
     uint8_t *__restrict__ sym, uint64_t sym_stride, uint64_t row_stride, float gamma,
-    uint64_t *__restrict__ hist, uint64_t *__restrict__ status, uint32_t tiles_per_block)
+    uint64_t *__restrict__ hist_rep, uint64_t *__restrict__ status)
 {
     extern __shared__ uint32_t h_lds[];  // [A][kHistRep]
     const uint32_t u = blockIdx.y;
     const uint64_t d = lay.d;
-    const uint64_t ntiles = (d + kQTile - 1) / kQTile;
-    const uint64_t t0 = (uint64_t)blockIdx.x * tiles_per_block;
-    const uint64_t t1 = (t0 + tiles_per_block < ntiles) ? t0 + tiles_per_block : ntiles;
-    if (t0 >= t1) return;
-
-    for (uint32_t i = threadIdx.x; i < lay.A * kHistRep; i += kQThreads) h_lds[i] = 0;
-    __syncthreads();
-
+    const uint64_t base = (uint64_t)blockIdx.x * kQTile;
     const float *gu = g + (uint64_t)u * row_stride;
     const float *mu = m + (uint64_t)u * row_stride;
     float *mo = m_out + (uint64_t)u * row_stride;
     uint8_t *su = sym + (uint64_t)u * sym_stride;
-    const uint32_t book_base = lay.per_user_books ? u * lay.books_per_user : 0;
-    const uint32_t lane_rep = threadIdx.x & (kHistRep - 1);
-    const uint32_t sign_shift = lay.E + lay.M;
+    const bool full = base + kQTile <= d;
 
-    uint32_t seg = find_segment(lay.segs, lay.nseg, t0 * kQTile);
-    uint64_t seg_end = lay.segs[seg + 1].offset;
-    QConst qc = make_qconst(lay.E, lay.M, lay.bias[(uint64_t)u * lay.nseg + seg]);
-    uint32_t n_nonfinite = 0, n_clamped = 0;
-
-    for (uint64_t tile = t0; tile < t1; ++tile) {
-        const uint64_t base = tile * kQTile;
-        if (base >= seg_end) {  // block-uniform: the tile starts in a later segment
-            flush_hist(h_lds, lay.A, hist + (uint64_t)(book_base + lay.segs[seg].book) * lay.A);
-            seg = find_segment(lay.segs, lay.nseg, base);
-            seg_end = lay.segs[seg + 1].offset;
-            qc = make_qconst(lay.E, lay.M, lay.bias[(uint64_t)u * lay.nseg + seg]);
-        }
-        if (base + kQTile <= seg_end) {
-            // whole tile inside one segment: vector path
-            float4 gv[2], mv[2];
+    // request the tile before anything else
+    f4 gv[2], mv[2];
+    if (full) {
 #pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                const uint64_t i = base + (uint64_t)k * (kQThreads * 4) + threadIdx.x * 4;
-                gv[k] = *reinterpret_cast<const float4 *>(gu + i);
-                mv[k] = *reinterpret_cast<const float4 *>(mu + i);
-            }
-#pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                const uint64_t i = base + (uint64_t)k * (kQThreads * 4) + threadIdx.x * 4;
-                const float gi[4] = {gv[k].x, gv[k].y, gv[k].z, gv[k].w};
-                const float mi[4] = {mv[k].x, mv[k].y, mv[k].z, mv[k].w};
-                float eo[4];
-                uint32_t packed = 0;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float v = __fadd_rn(gi[j], __fmul_rn(gamma, mi[j]));
-                    uint32_t s, flags;
-                    float q;
-                    quantize(v, qc, sign_shift, s, q, flags);
-                    eo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
-                    n_nonfinite += flags & 1u;
-                    n_clamped += (flags >> 1) & 1u;
-                    packed |= s << (8 * j);
-                    atomicAdd(&h_lds[s * kHistRep + lane_rep], 1u);
-                }
-                *reinterpret_cast<float4 *>(mo + i) = make_float4(eo[0], eo[1], eo[2], eo[3]);
-                *reinterpret_cast<uint32_t *>(su + i) = packed;
-            }
-        } else {
-            // ragged tail of the vector or a tile that crosses a segment boundary: element path
-            for (int k = 0; k < 8; ++k) {
-                const uint64_t i = base + (uint64_t)k * kQThreads + threadIdx.x;
-                if (i >= d) break;
-                uint32_t s_i = seg;
-                while (i >= lay.segs[s_i + 1].offset) ++s_i;
-                const QConst qe = make_qconst(lay.E, lay.M, lay.bias[(uint64_t)u * lay.nseg + s_i]);
-                const float v = __fadd_rn(gu[i], __fmul_rn(gamma, mu[i]));
-                uint32_t s, flags;
-                float q;
-                quantize(v, qe, sign_shift, s, q, flags);
-                mo[i] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
-                n_nonfinite += flags & 1u;
-                n_clamped += (flags >> 1) & 1u;
-                su[i] = (uint8_t)s;
-                atomicAdd(reinterpret_cast<unsigned long long *>(
-                              hist + (uint64_t)(book_base + lay.segs[s_i].book) * lay.A + s), 1ull);
-            }
+        for (int k = 0; k < 2; ++k) {
+            const uint64_t i = base + (uint64_t)k * (kQThreads * 4) + threadIdx.x * 4;
+            gv[k] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(gu + i));
+            mv[k] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(mu + i));
         }
     }
-    flush_hist(h_lds, lay.A, hist + (uint64_t)(book_base + lay.segs[seg].book) * lay.A);
+    for (uint32_t i = threadIdx.x; i < lay.A * kHistRep; i += kQThreads) h_lds[i] = 0;
+
+    const uint32_t book_base = lay.per_user_books ? u * lay.books_per_user : 0;
+    uint64_t *hist = hist_rep + (uint64_t)(blockIdx.x % kHistGlobalRep) * lay.nbooks * lay.A;
+    const uint32_t lane_rep = threadIdx.x & (kHistRep - 1);
+    const uint32_t sign_shift = lay.E + lay.M;
+    const uint32_t seg = find_segment(lay.segs, lay.nseg, base);
+    const uint64_t seg_end = lay.segs[seg + 1].offset;
+    uint32_t n_nonfinite = 0, n_clamped = 0;
+    __syncthreads();
+
+    if (full && base + kQTile <= seg_end) {
+        // whole tile inside one layer: one bias, LDS histogram
+        const QConst qc = make_qconst(lay.E, lay.M, lay.bias[(uint64_t)u * lay.nseg + seg]);
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const uint64_t i = base + (uint64_t)k * (kQThreads * 4) + threadIdx.x * 4;
+            f4 eo;
+            uint32_t packed = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float v = __fadd_rn(gv[k][j], __fmul_rn(gamma, mv[k][j]));
+                uint32_t s, flags;
+                float q;
+                quantize(v, qc, sign_shift, s, q, flags);
+                eo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
+                n_nonfinite += flags & 1u;
+                n_clamped += (flags >> 1) & 1u;
+                packed |= s << (8 * j);
+                atomicAdd(&h_lds[s * kHistRep + lane_rep], 1u);
+            }
+            __builtin_nontemporal_store(eo, reinterpret_cast<f4 *>(mo + i));
+            __builtin_nontemporal_store(packed, reinterpret_cast<uint32_t *>(su + i));
+        }
+        __syncthreads();
+        uint64_t *hist_book = hist + (uint64_t)(book_base + lay.segs[seg].book) * lay.A;
+        for (uint32_t bin = threadIdx.x; bin < lay.A; bin += kQThreads) {
+            uint32_t s = 0;
+#pragma unroll
+            for (int r = 0; r < kHistRep; ++r) s += h_lds[bin * kHistRep + ((r + bin) & (kHistRep - 1))];
+            if (s) atomicAdd(reinterpret_cast<unsigned long long *>(hist_book + bin), (unsigned long long)s);
+        }
+    } else {
+        // ragged tail of the vector or a tile that crosses a layer boundary: element path
+        for (int k = 0; k < 8; ++k) {
+            const uint64_t i = base + (uint64_t)k * kQThreads + threadIdx.x;
+            if (i >= d) break;
+            uint32_t s_i = seg;
+            while (i >= lay.segs[s_i + 1].offset) ++s_i;
+            const QConst qe = make_qconst(lay.E, lay.M, lay.bias[(uint64_t)u * lay.nseg + s_i]);
+            const float v = __fadd_rn(gu[i], __fmul_rn(gamma, mu[i]));
+            uint32_t s, flags;
+            float q;
+            quantize(v, qe, sign_shift, s, q, flags);
+            mo[i] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
+            n_nonfinite += flags & 1u;
+            n_clamped += (flags >> 1) & 1u;
+            su[i] = (uint8_t)s;
+            atomicAdd(reinterpret_cast<unsigned long long *>(
+                          hist + (uint64_t)(book_base + lay.segs[s_i].book) * lay.A + s), 1ull);
+        }
+    }
     if (n_nonfinite)
         atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NONFINITE), (unsigned long long)n_nonfinite);
     if (n_clamped)
         atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CLAMPED), (unsigned long long)n_clamped);
+}
+
+// hist[i] = sum over the kHistGlobalRep copies of hist_rep[r][i]
+__global__ __launch_bounds__(256) void k_reduce_hist(const uint64_t *__restrict__ hist_rep, uint64_t *__restrict__ hist,
+                                                    uint64_t n)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    uint64_t s = 0;
+#pragma unroll 8
+    for (int r = 0; r < kHistGlobalRep; ++r) s += hist_rep[(uint64_t)r * n + i];
+    hist[i] = s;
 }
 
 // Fill kernel used instead of a memset node so that callers may capture the sequence in a graph.
@@ -151,20 +153,20 @@ hipError_t launch_zero_u64(uint64_t *p, uint64_t n, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, hipStream_t s)
+hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, const EncodeWs &ws, hipStream_t s)
 {
     if (lay.d == 0 || lay.U == 0) return hipSuccess;
     const uint64_t ntiles = (lay.d + kQTile - 1) / kQTile;
-    uint64_t bpu = 5120 / lay.U;
-    if (bpu < 1) bpu = 1;
-    if (bpu > ntiles) bpu = ntiles;
-    const uint32_t tiles_per_block = (uint32_t)((ntiles + bpu - 1) / bpu);
-    const uint32_t gx = (uint32_t)((ntiles + tiles_per_block - 1) / tiles_per_block);
     const uint64_t sym_stride = (lay.d + 15) & ~(uint64_t)15;
     const size_t lds = (size_t)lay.A * kHistRep * sizeof(uint32_t);
-    ProfScope prof(K_QUANTIZE, s);
-    hipLaunchKernelGGL(k_quantize, dim3(gx, lay.U), dim3(kQThreads), lds, s, lay, a.g, a.m, a.m_out,
-                       a.symbols, sym_stride, a.row_stride, a.gamma, a.hist, a.status, tiles_per_block);
+    {
+        ProfScope prof(K_QUANTIZE, s);
+        hipLaunchKernelGGL(k_quantize, dim3((uint32_t)ntiles, lay.U), dim3(kQThreads), lds, s, lay, a.g, a.m,
+                           a.m_out, a.symbols, sym_stride, a.row_stride, a.gamma, ws.hist_rep, a.status);
+    }
+    const uint64_t n = (uint64_t)lay.nbooks * lay.A;
+    ProfScope prof(K_REDUCE_HIST, s);
+    hipLaunchKernelGGL(k_reduce_hist, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0, s, ws.hist_rep, a.hist, n);
     return hipGetLastError();
 }
 
