@@ -52,8 +52,7 @@ enum {
     CO3_STAT_NOCODE = 2,    /* symbols met by the encoder that have no codeword             */
     CO3_STAT_CAPACITY = 3,  /* chunks not written because the stream buffer is too small    */
     CO3_STAT_CODELEN = 4,   /* code tables built on the device that needed > 64 bits        */
-    CO3_STAT_CORRUPT = 5,   /* sub-chunks the decoder could not decode consistently         */
-    CO3_STAT_INTERNAL = 6   /* bounded waits inside the library that expired                 */
+    CO3_STAT_CORRUPT = 5    /* sub-chunks the decoder could not decode consistently         */
 };
 
 /* Float format of Q_fp: one sign bit, exp_bits exponent bits, mant_bits mantissa bits
@@ -198,13 +197,6 @@ typedef struct {
 } co3_kernel_time;
 int co3_profile_begin(void);
 int co3_profile_end(co3_kernel_time *out, uint32_t capacity, uint32_t *count);
-
-/* The bit-pack kernel of co3_encode orders its workgroups with tickets and lets each wait for
- * the sizes its predecessors publish; the wait is bounded by `polls` polls per predecessor
- * (default 2^22).  A workgroup whose wait expires adds 1 to status[CO3_STAT_INTERNAL] and goes
- * on, so the kernel always ends; the stream of that call is then invalid.  For tests of this
- * error path only.                                                                          */
-void co3_set_wait_limit(uint32_t polls);
 
 /* Human-readable name of a status code.                                                     */
 const char *co3_status_string(int status);

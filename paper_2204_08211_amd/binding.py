@@ -16,7 +16,7 @@ CHUNK = 4096
 SUB = 64
 SUBS_PER_CHUNK = 64
 STATUS_WORDS = 8
-(STAT_NONFINITE, STAT_CLAMPED, STAT_NOCODE, STAT_CAPACITY, STAT_CODELEN, STAT_CORRUPT, STAT_INTERNAL) = range(7)
+(STAT_NONFINITE, STAT_CLAMPED, STAT_NOCODE, STAT_CAPACITY, STAT_CODELEN, STAT_CORRUPT) = range(6)
 BOOK_FIXED, BOOK_EMPIRICAL = 0, 1
 OK, ERR_ARG, ERR_FORMAT, ERR_CAPACITY, ERR_CODELEN, ERR_CORRUPT, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
@@ -25,7 +25,7 @@ EXPORTS = [
     "co3_plan_alphabet", "co3_plan_symbols_bytes", "co3_plan_workspace_bytes", "co3_plan_stream_words",
     "co3_build_codebook", "co3_build_codebook_device", "co3_codebook_export", "co3_codebook_num_books",
     "co3_codebook_destroy", "co3_encode", "co3_decode", "co3_ps_aggregate", "co3_status_string",
-    "co3_profile_begin", "co3_profile_end", "co3_set_wait_limit",
+    "co3_profile_begin", "co3_profile_end",
 ]
 
 
@@ -99,8 +99,6 @@ def lib():
         L.co3_decode.argtypes = [C.c_void_p, C.POINTER(DecodeArgs), C.c_void_p]
         L.co3_ps_aggregate.argtypes = [C.c_void_p, C.POINTER(AggregateArgs), C.c_void_p]
         L.co3_profile_end.argtypes = [C.POINTER(KernelTime), C.c_uint32, C.POINTER(C.c_uint32)]
-        L.co3_set_wait_limit.argtypes = [C.c_uint32]
-        L.co3_set_wait_limit.restype = None
         L.co3_status_string.argtypes = [C.c_int]
         L.co3_status_string.restype = C.c_char_p
         _lib = L
@@ -117,11 +115,6 @@ def profile_end():
     n = C.c_uint32(0)
     _check("co3_profile_end", lib().co3_profile_end(arr, 16, C.byref(n)))
     return {arr[i].name.decode(): (arr[i].total_ms, int(arr[i].launches)) for i in range(n.value)}
-
-
-def set_wait_limit(polls):
-    """Bound of the pack kernel's wait for a predecessor workgroup (error-path tests only)."""
-    lib().co3_set_wait_limit(C.c_uint32(int(polls)))
 
 
 def status_string(code):

@@ -28,9 +28,6 @@ struct DeviceGuard {
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// polls a pack workgroup may spend on one predecessor before it reports an internal error
-uint32_t g_spin_limit = 1u << 22;
-
 int check_bias_table(const co3_format &f, const int32_t *bias, size_t n)
 {
     for (size_t i = 0; i < n; ++i)
@@ -55,8 +52,6 @@ const char *co3_status_string(int status)
         default: return "CO3_ERR_UNKNOWN";
     }
 }
-
-void co3_set_wait_limit(uint32_t polls) { g_spin_limit = polls; }
 
 int co3_plan_create(co3_format format, uint32_t U, uint64_t d, uint32_t nseg, const co3_segment *segments,
                     const int32_t *bias, int32_t per_user_books, co3_plan **out)
@@ -149,9 +144,7 @@ size_t co3_plan_workspace_bytes(const co3_plan *plan)
     if (!plan) return 0;
     const Layout &l = plan->lay;
     const size_t hist_rep = ((size_t)kHistGlobalRep * l.nbooks * l.A * sizeof(uint64_t) + 255) & ~(size_t)255;
-    const size_t nblk = (size_t)((l.nchunks + kPackChunksPerGroup - 1) / kPackChunksPerGroup);
-    const size_t lookback = ((size_t)l.U * (nblk + 1) * sizeof(uint64_t) + 255) & ~(size_t)255;
-    return hist_rep + lookback + (size_t)l.U * l.nchunks * sizeof(uint32_t) + 768;
+    return hist_rep + (size_t)l.U * l.nchunks * sizeof(uint32_t) + 512;
 }
 
 uint64_t co3_plan_stream_words(const co3_plan *plan, uint32_t max_code_len)
@@ -259,22 +252,15 @@ int co3_encode(const co3_plan *plan, const co3_encode_args *a, void *stream)
     EncodeWs ws;
     const uint64_t hist_rep_n = (uint64_t)kHistGlobalRep * lay.nbooks * lay.A;
     ws.hist_rep = reinterpret_cast<uint64_t *>((reinterpret_cast<uintptr_t>(a->workspace) + 255u) & ~(uintptr_t)255u);
-    ws.lookback = reinterpret_cast<uint64_t *>(
-        (reinterpret_cast<uintptr_t>(ws.hist_rep + hist_rep_n) + 255u) & ~(uintptr_t)255u);
-    ws.spin_limit = g_spin_limit;
-    const uint64_t nblk = (lay.nchunks + kPackChunksPerGroup - 1) / kPackChunksPerGroup;
     ws.chunk_bits = reinterpret_cast<uint32_t *>(
-        (reinterpret_cast<uintptr_t>(ws.lookback + (uint64_t)lay.U * (nblk + 1)) + 255u) & ~(uintptr_t)255u);
+        (reinterpret_cast<uintptr_t>(ws.hist_rep + hist_rep_n) + 255u) & ~(uintptr_t)255u);
 
     if (launch_zero_u64(ws.hist_rep, hist_rep_n, s) != hipSuccess) return CO3_ERR_HIP;
     if (launch_quantize(lay, *a, ws, s) != hipSuccess) return CO3_ERR_HIP;
     if (a->mode == CO3_BOOK_EMPIRICAL &&
         launch_build_books(a->books->d_books, lay.nbooks, lay.A, a->hist, a->status, s) != hipSuccess)
         return CO3_ERR_HIP;
-    static const bool use_lookback = getenv("CO3_TUNE_PACK_LOOKBACK") != nullptr;
-    if ((use_lookback ? launch_pack(lay, *a, a->books->d_books, ws, s)
-                      : launch_pack3(lay, *a, a->books->d_books, ws, s)) != hipSuccess)
-        return CO3_ERR_HIP;
+    if (launch_pack(lay, *a, a->books->d_books, ws, s) != hipSuccess) return CO3_ERR_HIP;
     return CO3_OK;
 }
 

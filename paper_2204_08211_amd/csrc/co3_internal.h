@@ -105,13 +105,8 @@ int build_book_host(const uint64_t *weights, uint32_t A, BookDev *out);
 // Kernel launchers (one per .hip file).  All return a hipError_t from hipGetLastError().
 struct EncodeWs {
     uint64_t *hist_rep;     // [kHistGlobalRep][nbooks][A] partial symbol counts
-    uint64_t *lookback;     // [U] tickets, then [U][ceil(nchunks / 4)] published sizes of the pack kernel
-    uint32_t spin_limit;    // bound of the pack kernel's wait for a predecessor
-    uint32_t *chunk_bits;   // [U][nchunks] (three-kernel pack)
+    uint32_t *chunk_bits;   // [U][nchunks] payload bits of every chunk
 };
-
-// Workgroups of the pack kernel per user (each takes kPackChunksPerGroup consecutive chunks).
-constexpr int kPackChunksPerGroup = 4;
 
 hipError_t launch_zero_u64(uint64_t *p, uint64_t n, hipStream_t s);
 hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, const EncodeWs &ws, hipStream_t s);
@@ -119,8 +114,6 @@ hipError_t launch_build_books(BookDev *books, uint32_t nbooks, uint32_t A, const
                               uint64_t *status, hipStream_t s);
 hipError_t launch_pack(const Layout &lay, const co3_encode_args &a, const BookDev *books,
                        const EncodeWs &ws, hipStream_t s);
-hipError_t launch_pack3(const Layout &lay, const co3_encode_args &a, const BookDev *books,
-                        const EncodeWs &ws, hipStream_t s);
 hipError_t launch_decode(const Layout &lay, const co3_decode_args &a, const BookDev *books, hipStream_t s);
 hipError_t launch_aggregate(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
                             hipStream_t s);

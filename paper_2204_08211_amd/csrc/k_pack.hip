@@ -3,30 +3,29 @@
 // communication overhead counts, is the sum of the codeword lengths.
 //
 // Container: codewords in element order, MSB-first in 32-bit words.  A chunk (4096 elements,
-// restarting at each layer) starts on a 32-bit boundary, so workgroups own disjoint words of
-// the output and no global atomics touch the stream.
+// restarting at each layer) starts on a 32-bit boundary, so wavefronts own disjoint words of the
+// output and no global atomics touch the stream.
 //
-// One kernel, one read of the symbols.  A workgroup takes a ticket (its position in the user's
-// sequence), stages the symbols of kCpb consecutive chunks in LDS, sums their code lengths,
-// publishes the 32-bit-rounded size of its chunks, obtains the bit offset of its first chunk by
-// looking back over the sizes published by its predecessors (decoupled look-back: a predecessor
-// either shows its own size or the running total up to and including itself), and then
-// concatenates the codewords of each chunk in an LDS window and copies the words out coalesced.
-// Tickets make the wait safe: every ticket below a workgroup's own is held by a workgroup that is
-// already running and never waits on a later one.  The wait is bounded; on expiry the workgroup
-// counts an error in status[CO3_STAT_INTERNAL] and goes on.
+// A wavefront owns a chunk and lane j owns sub-chunk j (64 elements), exactly as in the decoder;
+// nothing in these kernels needs a workgroup barrier.  Three steps:
+//   k_pack_wave<false>  code lengths -> bits per sub-chunk (the lane's sum) and per chunk
+//   k_scan_chunks       exclusive scan of the 32-bit-rounded chunk sizes (64-bit offsets)
+//   k_pack_wave<true>   every lane appends its 64 codewords at its bit offset inside an LDS
+//                       window (the offset is the wave prefix sum of the sub-chunk bits), then the
+//                       wavefront copies the window's words out coalesced
+// The symbols of a chunk are staged in LDS in rows of 16 + 1 words so that every lane reads its
+// own row without bank conflicts; once they sit in registers the same LDS words become the
+// output window.
 #include "co3_internal.h"
 
 namespace co3 {
 
-constexpr int kPkThreads = 256;
-constexpr int kPkPerThread = kChunk / kPkThreads;  // 16 symbols per thread and chunk
-constexpr int kCpb = 4;                            // chunks per workgroup
-constexpr int kWinWords = 2048;                    // LDS window of the output (16 bit/element in one pass)
-
-constexpr uint64_t kLbAgg = 1ull << 62;      // value = size of the workgroup's own chunks
-constexpr uint64_t kLbPrefix = 2ull << 62;   // value = total size up to and including the workgroup
-constexpr uint64_t kLbValue = (1ull << 62) - 1;
+constexpr int kPkWaves = 4;                         // wavefronts (chunks) per workgroup
+constexpr int kPkThreads = 64 * kPkWaves;
+constexpr int kRowWords = 17;                       // 16 words of symbols + 1 pad
+constexpr int kStageWords = kSubsPerChunk * kRowWords;  // 1088 words hold a chunk's symbols
+constexpr int kWinWords = 1088;                     // LDS window of the output: 8.5 bit/element per pass
+constexpr int kSymLoads = (kChunk / 4 + 1 + 63) / 64;  // dword loads per lane to stage a chunk (17)
 
 __device__ inline uint32_t find_chunk_segment(const SegDev *segs, uint32_t nseg, uint64_t chunk)
 {
@@ -56,265 +55,189 @@ __device__ inline uint32_t wave_sum(uint32_t x)
     return x;
 }
 
-// 16 consecutive symbol bytes starting at byte `b` of the staged symbols, as four dwords
-__device__ inline void load_symbols16(const uint32_t *s_sym, uint32_t b, uint32_t sb[4])
+__device__ inline void wave_sync_lds()
 {
-    const uint32_t w = b >> 2, sh = 8u * (b & 3u);
-    uint32_t dw[5];
-#pragma unroll
-    for (int k = 0; k < 5; ++k) dw[k] = s_sym[w + k];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) sb[k] = (uint32_t)((((uint64_t)dw[k + 1] << 32) | dw[k]) >> sh);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__global__ __launch_bounds__(kPkThreads) void k_pack(
+template <bool kPack>
+__global__ __launch_bounds__(kPkThreads) void k_pack_wave(
     Layout lay, const uint8_t *__restrict__ sym, uint64_t sym_stride, const BookDev *__restrict__ books,
-    uint32_t *__restrict__ tickets, uint64_t *__restrict__ lb_state, uint32_t nblk,
-    uint64_t *__restrict__ chunk_offset, uint16_t *__restrict__ sub_bits, uint64_t *__restrict__ payload_bits,
-    uint32_t *__restrict__ words, uint64_t words_stride, uint64_t *__restrict__ status, uint32_t spin_limit)
+    uint32_t *__restrict__ chunk_bits, const uint64_t *__restrict__ chunk_offset,
+    uint16_t *__restrict__ sub_bits, uint32_t *__restrict__ words, uint64_t words_stride,
+    uint64_t *__restrict__ status)
 {
-    __shared__ uint32_t s_sym[kCpb * kChunk / 4 + 8];
-    __shared__ uint32_t s_fast[kCpb][kMaxA];
-    __shared__ uint32_t s_bits[kWinWords + 1];
-    __shared__ uint32_t s_part[kCpb][kPkThreads / 64];
-    __shared__ uint32_t s_wave[kPkThreads / 64];
-    __shared__ uint32_t s_cn[kCpb], s_coff[kCpb], s_cbook[kCpb], s_cbits[kCpb];
-    __shared__ uint64_t s_efirst;
-    __shared__ uint64_t s_prefix;
-    __shared__ uint32_t s_ticket;
+    __shared__ uint32_t s_stage_all[kPkWaves][kStageWords + 1];
+    __shared__ uint32_t s_win_all[kPkWaves][kPack ? kWinWords + 1 : 1];
+    __shared__ uint32_t s_fast_all[kPkWaves][kMaxA];
 
-    const uint32_t t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t c = (uint64_t)blockIdx.x * kPkWaves + wave;
     const uint32_t u = blockIdx.y;
-    if (t == 0) s_ticket = atomicAdd(&tickets[u], 1u);
-    __syncthreads();
-    const uint32_t b = s_ticket;                       // position of this workgroup in the user's sequence
-    const uint64_t c0 = (uint64_t)b * kCpb;
-    const uint32_t nck = (lay.nchunks - c0 < (uint64_t)kCpb) ? (uint32_t)(lay.nchunks - c0) : (uint32_t)kCpb;
+    if (c >= lay.nchunks) return;  // whole wavefront; no workgroup barriers below
+    uint32_t *s_stage = s_stage_all[wave];
+    uint32_t *s_win = s_win_all[wave];
+    uint32_t *s_fast = s_fast_all[wave];
 
-    // geometry of the chunks; their elements are contiguous in the user's vector
-    if (t < (uint32_t)kCpb) {
-        uint32_t n = 0, bk = 0;
-        uint64_t e0 = 0;
-        if (t < nck) {
-            const uint64_t c = c0 + t;
-            const uint32_t seg = find_chunk_segment(lay.segs, lay.nseg, c);
-            const SegDev sd = lay.segs[seg];
-            e0 = sd.offset + (c - sd.chunk_start) * kChunk;
-            const uint64_t left = sd.offset + sd.length - e0;
-            n = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
-            bk = (lay.per_user_books ? u * lay.books_per_user : 0u) + (uint32_t)sd.book;
-        }
-        s_cn[t] = n;
-        s_cbook[t] = bk;
-        if (t == 0) s_efirst = e0;
-    }
-    __syncthreads();
-    uint32_t n_elems = 0;
+    const uint32_t seg = find_chunk_segment(lay.segs, lay.nseg, c);
+    const SegDev sd = lay.segs[seg];
+    const uint64_t e0 = sd.offset + (c - sd.chunk_start) * kChunk;
+    const uint64_t left = sd.offset + sd.length - e0;
+    const uint32_t n = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
+    const BookDev &book = books[(lay.per_user_books ? u * lay.books_per_user : 0u) + (uint32_t)sd.book];
+
+    // what the wavefront needs from memory, requested together: table, symbols, (pack) sub-chunk bits
+    uint32_t tab[kMaxA / 64];
 #pragma unroll
-    for (int k = 0; k < kCpb; ++k) {
-        if (t == 0) s_coff[k] = n_elems;
-        n_elems += s_cn[k];
-        if ((uint32_t)k < nck) s_fast[k][t] = books[s_cbook[k]].fast[t];
-    }
-    const uint64_t e_first = s_efirst;
-
-    // stage the symbol bytes as aligned dwords: all loads first, then all LDS stores
-    const uint64_t byte0 = (uint64_t)u * sym_stride + e_first;
+    for (int k = 0; k < kMaxA / 64; ++k) tab[k] = book.fast[lane + 64 * k];
+    const uint64_t byte0 = (uint64_t)u * sym_stride + e0;
     const uint32_t shift = (uint32_t)(byte0 & 3u);
     const uint32_t *src = reinterpret_cast<const uint32_t *>(sym + (byte0 - shift));
-    const uint32_t ndw = (shift + n_elems + 3u) >> 2;
-    {
-        constexpr int kLoads = (kCpb * kChunk / 4 + kPkThreads) / kPkThreads;  // 17
-        uint32_t tmp[kLoads];
+    const uint32_t ndw = (shift + n + 3u) >> 2;
+    uint32_t tmp[kSymLoads];
 #pragma unroll
-        for (int k = 0; k < kLoads; ++k) {
-            const uint32_t i = t + (uint32_t)k * kPkThreads;
-            tmp[k] = i < ndw ? __builtin_nontemporal_load(src + i) : 0u;
-        }
-#pragma unroll
-        for (int k = 0; k < kLoads; ++k) {
-            const uint32_t i = t + (uint32_t)k * kPkThreads;
-            if (i < ndw) s_sym[i] = tmp[k];
-        }
+    for (int k = 0; k < kSymLoads; ++k) {
+        const uint32_t i = lane + 64u * k;
+        tmp[k] = i < ndw ? src[i] : 0u;
     }
-    __syncthreads();
+    uint32_t my_bits = 0;
+    uint64_t off = 0;
+    if (kPack) {
+        my_bits = sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane];
+        off = chunk_offset[(uint64_t)u * (lay.nchunks + 1) + c];
+    }
+#pragma unroll
+    for (int k = 0; k < kMaxA / 64; ++k) s_fast[lane + 64 * k] = tab[k];
+#pragma unroll
+    for (int k = 0; k < kSymLoads; ++k) {
+        const uint32_t i = lane + 64u * k;
+        if (i < kChunk / 4 + 1) s_stage[i + (i >> 4)] = tmp[k];  // rows of 16 words, 17 apart
+    }
+    const int first = (int)lane * kSub;
+    const int cnt = (int)n - first < 0 ? 0 : ((int)n - first > kSub ? kSub : (int)n - first);
+    const uint32_t *row = s_stage + kRowWords * lane;   // words 16*lane .. of the staged bytes; word 16 is row[17]
 
-    // pass A: bits of every chunk
-    uint32_t nocode = 0;
+    if (!kPack) {
+        wave_sync_lds();
+        uint32_t total = 0, nocode = 0;
+        uint32_t cur = row[0];
+#pragma unroll 4
+        for (int jj = 0; jj < kSub / 4; ++jj) {
+            const uint32_t nxt = row[jj + 1 + (jj == kSub / 4 - 1 ? 1 : 0)];
+            const uint32_t w4 = (uint32_t)((((uint64_t)nxt << 32) | cur) >> (8 * shift));
+            cur = nxt;
 #pragma unroll
-    for (int k = 0; k < kCpb; ++k) {
-        uint32_t total = 0;
-        if ((uint32_t)k < nck) {
-            const int first = (int)t * kPkPerThread;
-            const int cn_k = (int)s_cn[k];
-            const int cnt = cn_k - first < 0 ? 0 : (cn_k - first > kPkPerThread ? kPkPerThread : cn_k - first);
-            if (cnt > 0) {
-                uint32_t sb[4];
-                load_symbols16(s_sym, shift + s_coff[k] + (uint32_t)first, sb);
-#pragma unroll
-                for (int j = 0; j < kPkPerThread; ++j) {
-                    const uint32_t s = (sb[j >> 2] >> (8 * (j & 3))) & 0xffu;
-                    uint32_t L = (j < cnt) ? (s_fast[k][s] >> 24) : 0u;
-                    if (L == kFastSlow) L = books[s_cbook[k]].len[s];
-                    if (j < cnt && L == 0u) ++nocode;
-                    total += L;
-                }
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t s = (w4 >> (8 * b)) & 0xffu;
+                const bool in = 4 * jj + b < cnt;
+                uint32_t L = in ? (s_fast[s] >> 24) : 0u;
+                if (__builtin_expect(L == kFastSlow, 0)) L = book.len[s];
+                nocode += (in && L == 0u) ? 1u : 0u;
+                total += L;
             }
         }
-        total = wave_sum(total);
-        if (lane == 0) s_part[k][wave] = total;
-    }
-    __syncthreads();
-    uint64_t own = 0, pay = 0;   // 32-bit-rounded size of this workgroup's chunks; their payload bits
-#pragma unroll
-    for (int k = 0; k < kCpb; ++k) {
-        uint32_t cb = 0;
-#pragma unroll
-        for (int w = 0; w < kPkThreads / 64; ++w) cb += s_part[k][w];
-        if (t == 0) s_cbits[k] = cb;
-        own += (cb + 31u) & ~31u;
-        pay += cb;
-    }
-
-    // publish, look back, publish the running total
-    uint64_t *state = lb_state + (uint64_t)u * nblk;
-    if (wave == 0) {
-        if (lane == 0)
-            __hip_atomic_store(&state[b], (b == 0 ? kLbPrefix : kLbAgg) | own, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        uint64_t prefix = 0;
-        int64_t pos = (int64_t)b - 1;
-        bool timed_out = false;
-        while (pos >= 0) {
-            const int64_t idx = pos - (int64_t)lane;
-            uint64_t v = kLbPrefix;  // before the first workgroup: total 0
-            uint32_t spins = 0;
-            if (idx >= 0) {
-                v = __hip_atomic_load(&state[idx], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-                while ((v >> 62) == 0 && spins < spin_limit) {
-                    __builtin_amdgcn_s_sleep(1);
-                    v = __hip_atomic_load(&state[idx], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-                    ++spins;
-                }
-            }
-            if (__any((v >> 62) == 0)) { timed_out = true; break; }
-            // nearest predecessor is lane 0; sum up to and including the first running total
-            const uint64_t has_prefix = __ballot((v >> 62) == 2);
-            const int stop = has_prefix ? (int)__builtin_ctzll(has_prefix) : 63;
-            uint64_t val = ((int)lane <= stop) ? (v & kLbValue) : 0ull;
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) val += __shfl_xor(val, o, 64);
-            prefix += val;
-            if (has_prefix) break;
-            pos -= 64;
-        }
-        if (lane == 0) {
-            if (timed_out)
-                atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_INTERNAL), 1ull);
-            if (b != 0)
-                __hip_atomic_store(&state[b], kLbPrefix | (prefix + own), __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-            s_prefix = prefix;
-            atomicAdd(reinterpret_cast<unsigned long long *>(payload_bits + u), (unsigned long long)pay);
-        }
-    }
-    if (nocode)
-        atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NOCODE), (unsigned long long)nocode);
-    __syncthreads();
-    uint64_t off = s_prefix;  // bit offset of the first chunk
-
-    // pass B: concatenate the codewords chunk by chunk
-#pragma unroll 1
-    for (uint32_t k = 0; k < nck; ++k) {
-        const uint64_t c = c0 + k;
-        const int first = (int)t * kPkPerThread;
-        const int cn_k = (int)s_cn[k];
-        const int cnt = cn_k - first < 0 ? 0 : (cn_k - first > kPkPerThread ? kPkPerThread : cn_k - first);
-        const BookDev &book = books[s_cbook[k]];
-        uint32_t sb[4] = {0, 0, 0, 0};
-        if (cnt > 0) load_symbols16(s_sym, shift + s_coff[k] + (uint32_t)first, sb);
-        uint32_t ent[kPkPerThread];
-        uint32_t total = 0;
-#pragma unroll
-        for (int j = 0; j < kPkPerThread; ++j) {
-            const uint32_t s = (sb[j >> 2] >> (8 * (j & 3))) & 0xffu;
-            const uint32_t e = (j < cnt) ? s_fast[k][s] : 0u;
-            uint32_t L = e >> 24;
-            if (L == kFastSlow) L = book.len[s];
-            total += L;
-            ent[j] = (e & 0x00ffffffu) | (L << 24);  // exact length (<= 64); code bits valid if L <= 24
-        }
-        const uint32_t incl_w = wave_inclusive_scan(total);
-        if (lane == 63) s_wave[wave] = incl_w;
-        __syncthreads();
-        uint32_t wave_base = 0;
-#pragma unroll
-        for (uint32_t w = 0; w < kPkThreads / 64; ++w)
-            if (w < wave) wave_base += s_wave[w];
-        const uint32_t incl = wave_base + incl_w;
-        const uint32_t excl = incl - total;
-        const uint32_t chunk_total = s_cbits[k];
-
-        // bits of each sub-chunk (4 threads), chunk offset
-        const uint32_t hi = __shfl(incl, (int)(lane | 3u), 64);
-        const uint32_t lo = __shfl(excl, (int)(lane & ~3u), 64);
-        if ((t & 3u) == 0u)
-            sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + (t >> 2)] = (uint16_t)(hi - lo);
-        if (t == 0) {
-            chunk_offset[(uint64_t)u * (lay.nchunks + 1) + c] = off;
-            if (c + 1 == lay.nchunks)
-                chunk_offset[(uint64_t)u * (lay.nchunks + 1) + c + 1] = off + ((chunk_total + 31u) & ~31u);
-        }
-
+        sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane] = (uint16_t)total;
+        const uint32_t chunk_total = wave_sum(total);
+        if (lane == 0) chunk_bits[(uint64_t)u * lay.nchunks + c] = chunk_total;
+        if (nocode)
+            atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NOCODE), (unsigned long long)nocode);
+        return;
+    } else {
+        const uint32_t incl = wave_inclusive_scan(my_bits);
+        const uint32_t excl = incl - my_bits;
+        const uint32_t chunk_total = __shfl(incl, 63, 64);
         const uint32_t nwords = (chunk_total + 31u) >> 5;
         const uint64_t off_words = off >> 5;
-        const bool fits = off_words + nwords <= words_stride;
-        if (!fits && t == 0) atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CAPACITY), 1ull);
+        if (off_words + nwords > words_stride) {
+            if (lane == 0) atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CAPACITY), 1ull);
+            return;
+        }
         uint32_t *dst = words + (uint64_t)u * words_stride + off_words;
 
-        // the chunk's words pass through the LDS window, kWinWords at a time
-        for (uint32_t wbase = 0; wbase < nwords && fits; wbase += kWinWords) {
+        // the chunk's words pass through the LDS window, kWinWords at a time (one pass up to
+        // 8.5 bit/element); every lane ORs its words in, so neighbours may share a word
+        for (uint32_t wbase = 0; wbase < nwords; wbase += kWinWords) {
             const uint32_t wn = nwords - wbase < (uint32_t)kWinWords ? nwords - wbase : (uint32_t)kWinWords;
-            for (uint32_t i = t; i <= wn; i += kPkThreads) s_bits[i] = 0;
-            __syncthreads();
-            uint32_t wi = excl >> 5;        // word receiving the next completed 32 bits
-            uint32_t np = excl & 31u;       // bits pending in acc (the leading np bits belong to earlier threads)
+            for (uint32_t i = lane; i <= wn; i += 64) s_win[i] = 0;
+            wave_sync_lds();
+            uint32_t wi = (excl >> 5) - wbase;  // window word receiving the next completed 32 bits
+            uint32_t np = excl & 31u;           // bits pending in acc (the leading np bits belong to earlier lanes)
             uint64_t acc = 0;
-            bool firstw = true;
-            auto emit = [&](uint32_t w, bool whole) {
-                const uint32_t rel = wi - wbase;
-                if (rel < wn) {  // unsigned: also false below the window
-                    if (firstw || !whole) atomicOr(&s_bits[rel], w);
-                    else s_bits[rel] = w;
-                }
-                firstw = false;
-            };
             auto append = [&](uint64_t code, uint32_t L) {  // L <= 32, np < 32
                 acc = (acc << L) | code;
                 np += L;
                 if (np >= 32u) {
                     np -= 32u;
-                    emit((uint32_t)(acc >> np), true);
+                    if (wi < wn) atomicOr(&s_win[wi], (uint32_t)(acc >> np));  // unsigned: false below the window
                     ++wi;
                 }
             };
+            uint32_t cur = row[0];
+#pragma unroll 2
+            for (int jj = 0; jj < kSub / 4; ++jj) {
+                const uint32_t nxt = row[jj + 1 + (jj == kSub / 4 - 1 ? 1 : 0)];
+                const uint32_t w4 = (uint32_t)((((uint64_t)nxt << 32) | cur) >> (8 * shift));
+                cur = nxt;
 #pragma unroll
-            for (int j = 0; j < kPkPerThread; ++j) {
-                const uint32_t L = ent[j] >> 24;
-                if (L <= (uint32_t)kFastLen) {
-                    if (L) append(ent[j] & 0x00ffffffu, L);
-                } else {
-                    const uint32_t s = (sb[j >> 2] >> (8 * (j & 3))) & 0xffu;
-                    const uint64_t code = book.code[s];
-                    if (L > 32u) { append(code >> 32, L - 32u); append(code & 0xffffffffull, 32u); }
-                    else append(code, L);
+                for (int b = 0; b < 4; ++b) {
+                    const uint32_t s = (w4 >> (8 * b)) & 0xffu;
+                    const uint32_t e = (4 * jj + b < cnt) ? s_fast[s] : 0u;
+                    uint32_t L = e >> 24;
+                    uint64_t code = e & 0x00ffffffu;
+                    if (__builtin_expect(L == kFastSlow, 0)) {
+                        L = book.len[s];
+                        code = book.code[s];
+                        if (L > 32u) {
+                            append(code >> 32, L - 32u);
+                            code &= 0xffffffffull;
+                            L = 32u;
+                        }
+                    }
+                    if (L) append(code, L);
                 }
             }
-            if (np) emit((uint32_t)(acc << (32u - np)), false);
-            __syncthreads();
-            for (uint32_t i = t; i < wn; i += kPkThreads) __builtin_nontemporal_store(s_bits[i], dst + wbase + i);
-            __syncthreads();
+            if (np && wi < wn) atomicOr(&s_win[wi], (uint32_t)(acc << (32u - np)));
+            wave_sync_lds();
+            for (uint32_t i = lane; i < wn; i += 64) __builtin_nontemporal_store(s_win[i], dst + wbase + i);
+            wave_sync_lds();
         }
-        off += (chunk_total + 31u) & ~31u;
     }
+}
+
+// Exclusive scan of the chunks' sizes (rounded up to 32 bits) of one user; payload_bits = r.
+constexpr int kScanThreads = 1024;
+__global__ __launch_bounds__(kScanThreads) void k_scan_chunks(uint64_t nchunks, const uint32_t *__restrict__ chunk_bits,
+                                                            uint64_t *__restrict__ chunk_offset,
+                                                            uint64_t *__restrict__ payload_bits)
+{
+    __shared__ uint32_t s_wave[kScanThreads / 64];
+    __shared__ uint32_t s_pay[kScanThreads / 64];
+    const uint32_t u = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const uint32_t *cb = chunk_bits + (uint64_t)u * nchunks;
+    uint64_t *co = chunk_offset + (uint64_t)u * (nchunks + 1);
+    uint64_t running = 0, payload = 0;
+    for (uint64_t base = 0; base < nchunks; base += kScanThreads) {
+        const uint64_t i = base + t;
+        const uint32_t b = (i < nchunks) ? cb[i] : 0u;
+        const uint32_t a = (b + 31u) & ~31u;
+        const uint32_t incl_w = wave_inclusive_scan(a);
+        const uint32_t pay = wave_sum(b);
+        __syncthreads();  // previous iteration's reads of s_wave are done
+        if (lane == 63) { s_wave[wave] = incl_w; s_pay[wave] = pay; }
+        __syncthreads();
+        uint32_t wave_base = 0, tot = 0, ptot = 0;
+        for (uint32_t k = 0; k < kScanThreads / 64; ++k) {
+            if (k < wave) wave_base += s_wave[k];
+            tot += s_wave[k];
+            ptot += s_pay[k];
+        }
+        if (i < nchunks) co[i] = running + wave_base + incl_w - a;
+        running += tot;
+        payload += ptot;
+    }
+    if (t == 0) { co[nchunks] = running; payload_bits[u] = payload; }
 }
 
 hipError_t launch_pack(const Layout &lay, const co3_encode_args &a, const BookDev *books, const EncodeWs &ws,
@@ -322,17 +245,22 @@ hipError_t launch_pack(const Layout &lay, const co3_encode_args &a, const BookDe
 {
     if (lay.U == 0) return hipSuccess;
     const uint64_t sym_stride = (lay.d + 15) & ~(uint64_t)15;
-    const uint32_t nblk = (uint32_t)((lay.nchunks + kCpb - 1) / kCpb);
-    // tickets [U] (as uint64 slots) + look-back state [U][nblk] + payload_bits [U]
-    if (launch_zero_u64(ws.lookback, (uint64_t)lay.U * (nblk + 1), s) != hipSuccess) return hipGetLastError();
-    if (launch_zero_u64(a.payload_bits, lay.U, s) != hipSuccess) return hipGetLastError();
-    if (lay.nchunks == 0) return launch_zero_u64(a.chunk_offset, lay.U, s);
-    uint32_t *tickets = reinterpret_cast<uint32_t *>(ws.lookback);
-    uint64_t *state = ws.lookback + lay.U;
-    ProfScope prof(K_PACK, s);
-    hipLaunchKernelGGL(k_pack, dim3(nblk, lay.U), dim3(kPkThreads), 0, s, lay, a.symbols, sym_stride, books, tickets,
-                       state, nblk, a.chunk_offset, a.sub_bits, a.payload_bits, a.words, a.words_stride, a.status,
-                       ws.spin_limit);
+    const uint32_t gx = (uint32_t)((lay.nchunks + kPkWaves - 1) / kPkWaves);
+    if (lay.nchunks) {
+        ProfScope prof(K_CHUNK_BITS, s);
+        hipLaunchKernelGGL(k_pack_wave<false>, dim3(gx, lay.U), dim3(kPkThreads), 0, s, lay, a.symbols, sym_stride,
+                           books, ws.chunk_bits, a.chunk_offset, a.sub_bits, a.words, a.words_stride, a.status);
+    }
+    {
+        ProfScope prof(K_SCAN, s);
+        hipLaunchKernelGGL(k_scan_chunks, dim3(lay.U), dim3(kScanThreads), 0, s, lay.nchunks, ws.chunk_bits,
+                           a.chunk_offset, a.payload_bits);
+    }
+    if (lay.nchunks) {
+        ProfScope prof(K_PACK, s);
+        hipLaunchKernelGGL(k_pack_wave<true>, dim3(gx, lay.U), dim3(kPkThreads), 0, s, lay, a.symbols, sym_stride,
+                           books, ws.chunk_bits, a.chunk_offset, a.sub_bits, a.words, a.words_stride, a.status);
+    }
     return hipGetLastError();
 }
 
