@@ -1,0 +1,261 @@
+"""GPU-vs-oracle parity at the full sizes of the five workloads, through the same entry points
+and buffers bench.py uses (pytest -m gpu).
+
+The oracle cannot run a whole round of the large workloads in test time, so:
+  - some users are checked completely (memory, symbols, sub-chunk bits, chunk offsets, payload,
+    and, while the vector is small enough, the whole bitstream);
+  - sampled chunks (first, last, layer boundaries, random; for every user) are checked element
+    by element: memory, symbols, the chunk's words at the offset the GPU reports, and the PS
+    average, which needs every user's symbol of that chunk;
+  - what covers everything is checked through properties: histogram rows equal the symbol counts
+    and sum to the element counts, the code is an optimal prefix code of the histogram (Kraft
+    equality, cost equal to the Huffman cost), chunk offsets are the running sum of the rounded
+    sub-chunk bits, the payload is their sum.
+Where the oracle has every user's symbols (workloads 1-3) the histogram and the code tables are
+compared exactly instead.  Inputs are drawn on the device with the seeded generator and copied to
+the host for the oracle; nothing the oracle computes takes a GPU result as input.
+"""
+import heapq
+import time
+
+import numpy as np
+import pytest
+
+import co3_synth as syn
+from oracle import co3_oracle as orc
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+CHUNK = 4096
+
+
+def chunk_table(seg_len):
+    """(element start, length, segment) of every chunk of one user."""
+    out, off = [], 0
+    for k, n in enumerate(seg_len):
+        for c0 in range(0, n, CHUNK):
+            out.append((off + c0, min(CHUNK, n - c0), k))
+        off += n
+    return out
+
+
+def huffman_cost(w):
+    h = [int(x) for x in w if x > 0]
+    if len(h) == 1:
+        return h[0]
+    heapq.heapify(h)
+    cost = 0
+    while len(h) > 1:
+        a, b = heapq.heappop(h), heapq.heappop(h)
+        cost += a + b
+        heapq.heappush(h, a + b)
+    return cost
+
+
+def check_code_is_optimal(hist, lens, codes):
+    act = hist > 0
+    assert np.array_equal(lens > 0, act)
+    L = lens[act].astype(np.int64)
+    if L.size >= 2:
+        Lmax = int(L.max())
+        assert int(sum(1 << (Lmax - int(l)) for l in L)) == 1 << Lmax          # Kraft equality
+    assert int((hist[act].astype(object) * L.astype(object)).sum()) == huffman_cost(hist)
+    ref = orc.canonical_codes(lens)                                            # canonical form of these lengths
+    assert np.array_equal(ref, codes)
+
+
+def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000, exact_hist=True):
+    import torch
+    from paper_2204_08211_amd import binding as B
+    t_start = time.time()
+    w = syn.WORKLOADS[name]
+    dev = torch.device("cuda:0")
+    U, d, E, M = w.U, w.d, w.E, w.M
+    A = 1 << (1 + E + M)
+    stride = (d + 3) // 4 * 4
+    seg_len = w.seg_len
+    nseg = len(seg_len)
+    seg_book = list(range(nseg)) if nseg > 1 else [0]
+    seg_off = np.concatenate([[0], np.cumsum(seg_len)]).astype(np.int64)
+    print(f"[{name}] U={U} d={d} [1,{E},{M}] nseg={nseg}", flush=True)
+
+    def bias_for(g, m):
+        mx = np.zeros((U, nseg))
+        for k in range(nseg):
+            sl = slice(int(seg_off[k]), int(seg_off[k + 1]))
+            v = g[:, sl] + np.float32(w.gamma) * m[:, sl]
+            mx[:, k] = v.abs().amax(dim=1).cpu().numpy()
+            del v
+        return syn.bias_table(mx, E)
+
+    g = torch.zeros((U, stride), dtype=torch.float32, device=dev)
+    m = torch.zeros((U, stride), dtype=torch.float32, device=dev)
+    out = torch.zeros(d, dtype=torch.float32, device=dev)
+
+    # iteration 0 (m_0 = 0) only produces a realistic memory; iteration 1 is the one checked
+    for u in range(U):
+        syn.user_gradient_torch(w, 0, u, dev, out=g[u, :d])
+    bias = bias_for(g, m)
+    plan = B.Plan(E, M, U, d, bias, seg_len=seg_len, seg_book=seg_book, per_user_books=w.per_user_books)
+    books = B.co3_build_codebook(E, M, plan.num_books, None)
+    buf = B.RoundBuffers(plan, dev, max_code_len=16)
+    B.co3_encode(plan, books, g, m, m, w.gamma, buf, mode=B.BOOK_EMPIRICAL)
+    torch.cuda.synchronize()
+    for u in range(U):
+        syn.user_gradient_torch(w, 1, u, dev, out=g[u, :d])
+    bias = bias_for(g, m)
+    plan.set_bias(bias)
+    m_in = m.clone()
+    buf.status.zero_()
+    B.co3_encode(plan, books, g, m, m, w.gamma, buf, mode=B.BOOK_EMPIRICAL)
+    B.co3_ps_aggregate(plan, books, buf, out)
+    torch.cuda.synchronize()
+    print(f"[{name}] GPU rounds done at {time.time() - t_start:.1f}s", flush=True)
+    status = buf.status.cpu().numpy()
+    assert status[B.STAT_NOCODE] == 0 and status[B.STAT_CAPACITY] == 0 and status[B.STAT_CORRUPT] == 0
+    assert status[B.STAT_NONFINITE] == 0
+
+    nch = plan.num_chunks
+    ctab = chunk_table(seg_len)
+    assert len(ctab) == nch
+    hist = buf.hist.cpu().numpy().view(np.uint64)
+    lc = [books.export(b) for b in range(plan.num_books)]
+    lens = np.stack([x[0] for x in lc]); codes = np.stack([x[1] for x in lc])
+    sub_bits = buf.sub_bits.cpu().numpy().view(np.uint16).reshape(U, nch, 64)
+    chunk_offset = buf.chunk_offset.cpu().numpy().view(np.uint64)
+    payload = buf.payload_bits.cpu().numpy().view(np.uint64)
+    sym_gpu = buf.symbols_2d()
+    bpu = max(seg_book) + 1
+
+    def book_of(u, k):
+        return (u * bpu if w.per_user_books else 0) + seg_book[k]
+
+    # ---- properties that cover everything ------------------------------------------------
+    per_chunk = sub_bits.astype(np.uint64).sum(axis=2)
+    rounded = (per_chunk + np.uint64(31)) & ~np.uint64(31)
+    expect_off = np.concatenate([np.zeros((U, 1), np.uint64), np.cumsum(rounded, axis=1, dtype=np.uint64)], axis=1)
+    assert np.array_equal(chunk_offset, expect_off), "chunk offsets are not the running sum of the rounded sizes"
+    assert np.array_equal(payload, per_chunk.sum(axis=1, dtype=np.uint64))
+    # histogram rows = counts of the symbols the GPU wrote (torch.bincount as a library count)
+    counts = np.zeros_like(hist)
+    for u in range(U):
+        for k in range(nseg):
+            sl = slice(int(seg_off[k]), int(seg_off[k + 1]))
+            counts[book_of(u, k)] += torch.bincount(sym_gpu[u, sl].to(torch.int32), minlength=A).cpu().numpy().astype(np.uint64)
+    assert np.array_equal(hist, counts)
+    assert int(hist.sum()) == U * d
+    for b in range(plan.num_books):
+        check_code_is_optimal(hist[b], lens[b], codes[b])
+    print(f"[{name}] properties ok at {time.time() - t_start:.1f}s; payload {payload.sum() / (U * d):.4f} bit/element, "
+          f"max code length {int(lens.max())}, max offset {int(chunk_offset.max())} bits", flush=True)
+
+    # ---- users checked completely ----------------------------------------------------------
+    oracle_hist = np.zeros_like(hist)
+    clamped = 0
+    full_list = list(range(U)) if exact_hist else list(full_users)
+    for u in full_list:
+        gh = g[u, :d].cpu().numpy(); mh = m_in[u, :d].cpu().numpy()
+        sym_o = np.empty(d, np.uint8)
+        detailed = u in full_users
+        m_gpu = m[u, :d].cpu().numpy() if detailed else None
+        for k in range(nseg):
+            sl = slice(int(seg_off[k]), int(seg_off[k + 1]))
+            mo, so, _, cnt = orc.ef_step(gh[sl], mh[sl], w.gamma, E, M, int(bias[u, k]), want_q=False)
+            sym_o[sl] = so
+            clamped += int(cnt[1])
+            orc.histogram(so, A, oracle_hist[book_of(u, k)])
+            if detailed:
+                assert np.array_equal(mo.view(np.uint32), m_gpu[sl].view(np.uint32)), f"memory of user {u}, layer {k}"
+        if detailed:
+            assert np.array_equal(sym_o, sym_gpu[u].cpu().numpy()), f"symbols of user {u}"
+            # sub-chunk bits from the oracle's symbols and the exported lengths
+            for k in range(nseg):
+                lo, hi = int(seg_off[k]), int(seg_off[k + 1])
+                if hi == lo:
+                    continue
+                L = lens[book_of(u, k)][sym_o[lo:hi]].astype(np.uint32)
+                nck = (hi - lo + CHUNK - 1) // CHUNK
+                pad = np.zeros(nck * CHUNK, np.uint32); pad[:hi - lo] = L
+                c_first = sum((int(n) + CHUNK - 1) // CHUNK for n in seg_len[:k])
+                assert np.array_equal(pad.reshape(nck, 64, 64).sum(axis=2), sub_bits[u, c_first:c_first + nck]), \
+                    f"sub-chunk bits of user {u}, layer {k}"
+            if d <= full_words_limit and exact_hist:
+                pass  # the whole bitstream is compared below, once the oracle's own code is known
+        print(f"[{name}] user {u} {'checked' if detailed else 'counted'} at {time.time() - t_start:.1f}s", flush=True)
+        if detailed and d <= full_words_limit:
+            # whole bitstream of this user with the exported tables (they are checked against the
+            # oracle's own tables below when the oracle has the full histogram)
+            r = orc.pack(sym_o, seg_len, [book_of(u, k) for k in range(nseg)], lens, codes)
+            assert r["rc"] == 0
+            nw = int(r["chunk_offset"][-1]) // 32
+            assert np.array_equal(r["chunk_offset"], chunk_offset[u])
+            assert np.array_equal(r["words"][:nw], buf.words[u, :nw].cpu().numpy().view(np.uint32)), f"bitstream of user {u}"
+            assert r["payload_bits"] == int(payload[u])
+        del gh, mh, sym_o
+    if exact_hist:
+        assert np.array_equal(hist, oracle_hist), "histogram"
+        for b in range(plan.num_books):
+            lo, co = orc.codebook(oracle_hist[b])
+            assert np.array_equal(lo, lens[b]) and np.array_equal(co, codes[b]), f"code table {b}"
+        assert clamped == int(status[B.STAT_CLAMPED])
+
+    # ---- sampled chunks, every user ----------------------------------------------------------
+    rng = np.random.default_rng(syn.seed_for(w.cfg, 999, 0))
+    picks = {0, nch - 1}
+    for k in range(nseg):   # chunks next to layer boundaries
+        c_first = sum((int(n) + CHUNK - 1) // CHUNK for n in seg_len[:k])
+        picks.update({c_first, max(c_first - 1, 0)})
+    picks.update(int(x) for x in rng.integers(0, nch, n_random_chunks))
+    # the chunks of every user that straddle 2^32 stream bits, if any
+    for u in range(U):
+        j = int(np.searchsorted(chunk_offset[u], np.uint64(1 << 32)))
+        if 0 < j < nch:
+            picks.update({j - 1, j})
+    picks = sorted(picks)
+    for c in picks:
+        e0, n, k = ctab[c]
+        syms = np.empty((U, n), np.uint8)
+        for u in range(U):
+            gh = g[u, e0:e0 + n].cpu().numpy(); mh = m_in[u, e0:e0 + n].cpu().numpy()
+            mo, so, _, _ = orc.ef_step(gh, mh, w.gamma, E, M, int(bias[u, k]), want_q=False)
+            assert np.array_equal(mo.view(np.uint32), m[u, e0:e0 + n].cpu().numpy().view(np.uint32)), (c, u)
+            assert np.array_equal(so, sym_gpu[u, e0:e0 + n].cpu().numpy()), (c, u)
+            syms[u] = so
+            bk = book_of(u, k)
+            r = orc.pack(so, [n], [0], lens[bk][None, :], codes[bk][None, :])
+            assert r["rc"] == 0
+            nw = int(r["chunk_offset"][-1]) // 32
+            w0 = int(chunk_offset[u, c]) // 32
+            assert np.array_equal(r["words"][:nw], buf.words[u, w0:w0 + nw].cpu().numpy().view(np.uint32)), (c, u)
+            assert np.array_equal(r["sub_bits"][:64], sub_bits[u, c]), (c, u)
+            assert int(chunk_offset[u, c + 1]) - int(chunk_offset[u, c]) == nw * 32
+        avg = orc.aggregate(syms, [n], bias[:, k:k + 1], E, M)
+        got = out[e0:e0 + n].cpu().numpy()
+        vals = np.stack([np.array([orc.value(s, E, M, int(bias[u, k])) for s in range(A)])[syms[u]] for u in range(U)])
+        scale = np.maximum(np.abs(avg), np.abs(vals).mean(axis=0))
+        assert np.all(np.abs(got.astype(np.float64) - avg) <= 1e-6 * scale), f"PS average in chunk {c}"
+        assert np.array_equal(got.view(np.uint32), avg.view(np.uint32)), f"PS average (bitwise) in chunk {c}"
+    print(f"[{name}] {len(picks)} sampled chunks x {U} users ok at {time.time() - t_start:.1f}s", flush=True)
+
+
+def test_cfg1_full():
+    run_workload("cfg1", full_users=[0], n_random_chunks=24)
+
+
+def test_cfg2_full():
+    run_workload("cfg2", full_users=[0, 9], n_random_chunks=24)
+
+
+def test_cfg3_full():
+    # the workload bench.py times
+    run_workload("cfg3", full_users=[0, 15], n_random_chunks=24)
+
+
+def test_cfg4_full():
+    # 16 layers with their own bias and code table; one user checked completely
+    run_workload("cfg4", full_users=[3], n_random_chunks=16, exact_hist=False, full_words_limit=0)
+
+
+def test_cfg5_full():
+    # more than 2^32 stream bits per user and more than 2^32 elements in the batch
+    run_workload("cfg5", full_users=[], n_random_chunks=24, exact_hist=False, full_words_limit=0)
