@@ -8,9 +8,15 @@ HBM before the timed region; the memory m is carried from step to step and the g
 through a small pre-generated pool.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--book empirical|model]
+
+--book empirical (default, the headline): every round builds its Huffman code on the device from
+that round's pooled symbol histogram.  --book model: the code is designed once, off the timed
+path, from the GenNorm model of g + gamma m and held, as the paper holds its fitted parameters
+for several epochs.  Whichever is not the headline is measured too and reported under "other_book".
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -19,6 +25,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the same counters
+# on a plain copy (profiles/cfg3_hbm_traffic.md); only valid for the workload they were taken on.
+MEASURED_TRAFFIC_BYTES = {("cfg3", "k_quantize"): 5586.2e6, ("cfg3", "k_pack"): 838.7e6,
+                          ("cfg3", "k_chunk_bits"): 425.4e6, ("cfg3", "k_aggregate"): 486.0e6}
 
 
 def parse():
@@ -29,12 +40,28 @@ def parse():
     p.add_argument("--workload", default="cfg3", help="cfg1..cfg5 of BASELINE.json (default: the one the target is quoted on)")
     p.add_argument("--book", default="empirical", choices=["empirical", "model"])
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-other-book", action="store_true", help="measure only the headline code-table mode")
     p.add_argument("--ignore-status", action="store_true", help="tuning runs only: do not stop on codec error counters")
     p.add_argument("--pool", type=int, default=2, help="pre-generated gradient sets to rotate through")
+    p.add_argument("--calibrate-copy", action="store_true",
+                   help="run plain device copies of a known size instead (reference for rocprofv3 --pmc byte counters)")
     return p.parse_args()
 
 
-def cpu_baseline(w, it0_host, bias_host, seconds_target=15.0):
+def calibrate_copy():
+    """Five plain copies of 1 GiB: what FETCH_SIZE / WRITE_SIZE read for 2^30 bytes in, 2^30 out."""
+    import torch
+    n = 1 << 28
+    src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"calibrate_copy": True, "bytes_read_per_copy": 4 * n, "bytes_written_per_copy": 4 * n, "copies": 5}))
+
+
+def cpu_baseline(w, it0_host, bias_host):
     """The oracle as it stands, single thread, on a bounded sample of the same workload."""
     import numpy as np
     from oracle import co3_round as oround
@@ -42,16 +69,19 @@ def cpu_baseline(w, it0_host, bias_host, seconds_target=15.0):
     U, d = g.shape
     m = np.zeros_like(g)
     tm = {}
+    seg_book = list(range(len(w.seg_len))) if w.nseg > 1 else [0]
     t0 = time.perf_counter()
-    enc = oround.encode_round(g, m, w.gamma, w.E, w.M, w.seg_len, list(range(len(w.seg_len))) if w.nseg > 1 else [0],
-                              bias_host[:U], False, None, tm)
+    enc = oround.encode_round(g, m, w.gamma, w.E, w.M, w.seg_len, seg_book, bias_host[:U], False, None, tm)
     t_enc = time.perf_counter() - t0
-    oround.ps_round(enc, w.E, w.M, w.seg_len, list(range(len(w.seg_len))) if w.nseg > 1 else [0], bias_host[:U], False, tm)
+    oround.ps_round(enc, w.E, w.M, w.seg_len, seg_book, bias_host[:U], False, tm)
     t_all = time.perf_counter() - t0
     return dict(value=U * d / t_all / 1e9, unit="GElem/s", cores=1, kind="oracle",
                 sample=f"users 0..{U - 1} of {w.U} at full d={d}, one round (encode+decode+average), "
                        f"{t_all:.1f} s; encode alone {U * d / t_enc / 1e6:.2f} MElem/s",
                 stages_s={k: round(v, 3) for k, v in tm.items()})
+
+
+ENC_KERNELS = ["k_zero_u64", "k_quantize", "k_reduce_hist", "k_build_books", "k_chunk_bits", "k_scan_chunks", "k_pack"]
 
 
 def main():
@@ -60,6 +90,9 @@ def main():
         print(f"bench.py: this build runs on ONE GPU (users are a batch on that GPU); --gpus {a.gpus} is not supported",
               file=sys.stderr)
         sys.exit(2)
+    if a.calibrate_copy:
+        calibrate_copy()
+        return
     import numpy as np
     import torch
     import co3_synth as syn
@@ -72,6 +105,8 @@ def main():
     stride = (d + 3) // 4 * 4
     nseg = len(w.seg_len)
     seg_book = list(range(nseg)) if nseg > 1 else [0]
+    seg_off = np.concatenate([[0], np.cumsum(w.seg_len)]).astype(np.int64)
+    elems = U * d
 
     # inputs: pool of gradient sets, memory starts at zero (m_0 = 0)
     pool = []
@@ -85,93 +120,141 @@ def main():
     # exponent bias: the workload's rule on iteration 0 (v = g since m_0 = 0), per user and segment;
     # held for the whole run like the paper holds b_t for several epochs
     mx = np.zeros((U, nseg))
-    off = 0
-    for k, n in enumerate(w.seg_len):
-        mx[:, k] = pool[0][:, off:off + n].abs().amax(dim=1).cpu().numpy()
-        off += n
+    for k in range(nseg):
+        mx[:, k] = pool[0][:, seg_off[k]:seg_off[k + 1]].abs().amax(dim=1).cpu().numpy()
     bias = syn.bias_table(mx, w.E)
 
     plan = B.Plan(w.E, w.M, U, d, bias, seg_len=w.seg_len, seg_book=seg_book, per_user_books=w.per_user_books)
-    if a.book == "model":
-        from oracle import co3_oracle as orc   # model weights are an input prepared off the timed path
-        raise SystemExit("--book model needs per-book GenNorm parameters; use the empirical book for the headline")
-    books = B.co3_build_codebook(w.E, w.M, plan.num_books, None)
     buf = B.RoundBuffers(plan, dev, max_code_len=16)
     out = torch.zeros(d, dtype=torch.float32, device=dev)
-    mode = B.BOOK_EMPIRICAL
+    counter = [0]
 
-    def step(i):
-        B.co3_encode(plan, books, pool[i % a.pool], m, m, w.gamma, buf, mode=mode)
-        B.co3_ps_aggregate(plan, books, buf, out)
+    def measure(books, mode, label):
+        def step():
+            B.co3_encode(plan, books, pool[counter[0] % a.pool], m, m, w.gamma, buf, mode=mode)
+            B.co3_ps_aggregate(plan, books, buf, out)
+            counter[0] += 1
+        for _ in range(a.warmup):
+            step()
+        torch.cuda.synchronize()
+        buf.status.zero_()
+        torch.cuda.synchronize()
+        B.profile_begin()
+        ev0 = torch.cuda.Event(enable_timing=True)
+        ev1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record()
+        for _ in range(a.steps):
+            step()
+        ev1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        dev_ms = ev0.elapsed_time(ev1)
+        kt = B.profile_end()
+        status = buf.status.cpu().numpy().tolist()
+        if (status[B.STAT_CAPACITY] or status[B.STAT_NOCODE] or status[B.STAT_CORRUPT] or status[B.STAT_CODELEN]) \
+                and not a.ignore_status:
+            print(f"bench.py: codec reported errors ({label}): status={status}", file=sys.stderr)
+            sys.exit(1)
+        ms_per_step = max(wall_ms, dev_ms) / a.steps
+        payload = buf.payload_bits.cpu().numpy().astype(np.float64)
+        container_bits = float(buf.chunk_offset[:, -1].cpu().numpy().astype(np.float64).sum()) \
+            + 64.0 * U * (plan.num_chunks + 1) + 16.0 * U * plan.num_chunks * 64
+        bpe = float(payload.sum()) / elems
+        per_launch = {k: v[0] / v[1] for k, v in kt.items()}
+        enc_ms = sum(kt[k][0] for k in ENC_KERNELS if k in kt) / a.steps
+        dec_ms = kt["k_aggregate"][0] / a.steps
+        enc_alg = (12.0 + bpe / 8.0) * elems
+        return dict(ms_per_step=ms_per_step, kt=kt, per_launch=per_launch, bpe=bpe, status=status,
+                    summary={
+                        "book": label, "ms_per_step": round(ms_per_step, 4),
+                        "gelem_s": round(elems / (ms_per_step * 1e-3) / 1e9, 3),
+                        "encode": {"ms": round(enc_ms, 4), "gelem_s": round(elems / enc_ms / 1e6, 2),
+                                   "hbm_frac_algorithmic": round(enc_alg / (enc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                   "bytes_per_element_algorithmic": round(12.0 + bpe / 8.0, 3)},
+                        "decode_average": {"ms": round(dec_ms, 4), "gelem_s": round(elems / dec_ms / 1e6, 2),
+                                           "hbm_frac_algorithmic": round((bpe / 8.0 + 4.0 / U) * elems / (dec_ms * 1e-3)
+                                                                         / 1e9 / HBM_PEAK_GBS, 4)},
+                        "bits_per_element": {"payload": round(bpe, 4), "container": round(container_bits / elems, 4)},
+                        "kernel_ms_per_launch": {k: round(v, 4) for k, v in per_launch.items()},
+                    })
 
-    for i in range(a.warmup):
-        step(i)
+    def model_books():
+        """Code tables from the GenNorm model of v = g + gamma m (host helper of the library): shape beta
+        of the generator, scale alpha from the measured standard deviation of v, per user and layer;
+        a table shared by several users gets the users' mean cell masses."""
+        wts = np.zeros((plan.num_books, plan.A), dtype=np.float64)
+        cnt = np.zeros(plan.num_books)
+        bpu = max(seg_book) + 1
+        for k in range(nseg):
+            sl = slice(int(seg_off[k]), int(seg_off[k + 1]))
+            v = pool[0][:, sl] + np.float32(w.gamma) * m[:, sl]
+            std = v.double().std(dim=1).cpu().numpy()
+            del v
+            for u in range(U):
+                beta, _ = w.user_params(u)
+                alpha = float(std[u]) * math.sqrt(math.gamma(1.0 / beta) / math.gamma(3.0 / beta))
+                b = (u * bpu if w.per_user_books else 0) + seg_book[k]
+                wts[b] += B.co3_gennorm_weights(w.E, w.M, int(bias[u, k]), 0.0, alpha, beta).astype(np.float64)
+                cnt[b] += 1
+        wts = np.where(wts > 0, np.maximum(1.0, np.floor(wts / np.maximum(cnt, 1)[:, None])), 0.0)
+        return B.co3_build_codebook(w.E, w.M, plan.num_books, wts.astype(np.uint64))
+
+    runs = {}
+    order = ["empirical", "model"] if a.book == "empirical" else ["model", "empirical"]
+    if a.no_other_book:
+        order = order[:1]
+    # the memory m needs a few rounds to reach its steady state before a model of v can be fitted
+    emp_books = B.co3_build_codebook(w.E, w.M, plan.num_books, None)
+    for _ in range(2):
+        B.co3_encode(plan, emp_books, pool[counter[0] % a.pool], m, m, w.gamma, buf, mode=B.BOOK_EMPIRICAL)
+        counter[0] += 1
     torch.cuda.synchronize()
-    buf.status.zero_()
-    torch.cuda.synchronize()
+    for label in order:
+        if label == "empirical":
+            runs[label] = measure(emp_books, B.BOOK_EMPIRICAL, "empirical")
+        else:
+            runs[label] = measure(model_books(), B.BOOK_FIXED, "model")
 
-    B.profile_begin()
-    ev0 = torch.cuda.Event(enable_timing=True)
-    ev1 = torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ev0.record()
-    for i in range(a.steps):
-        step(a.warmup + i)
-    ev1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    dev_ms = ev0.elapsed_time(ev1)
-    kt = B.profile_end()
-
-    ms_per_step = max(wall_ms, dev_ms) / a.steps
-    elems = U * d
-    payload = buf.payload_bits.cpu().numpy().astype(np.float64)
-    container_bits = float(buf.chunk_offset[:, -1].cpu().numpy().astype(np.float64).sum()) \
-        + 64.0 * U * (plan.num_chunks + 1) + 16.0 * U * plan.num_chunks * 64
-    bpe = float(payload.sum()) / elems
-    status = buf.status.cpu().numpy().tolist()
-    if (status[B.STAT_CAPACITY] or status[B.STAT_NOCODE] or status[B.STAT_CORRUPT] or status[B.STAT_CODELEN]) \
-            and not a.ignore_status:
-        print(f"bench.py: codec reported errors: status={status}", file=sys.stderr)
-        sys.exit(1)
-
-    per_launch = {k: v[0] / v[1] for k, v in kt.items()}
-    enc_kernels = ["k_zero_u64", "k_quantize", "k_reduce_hist", "k_build_books", "k_chunk_bits", "k_scan_chunks",
-                   "k_pack"]
-    enc_ms = sum(kt[k][0] for k in enc_kernels if k in kt) / a.steps
-    dec_ms = kt["k_aggregate"][0] / a.steps
-    # dominant kernel: the fused error-correction / fp-conversion / histogram sweep
-    dom = max(per_launch, key=lambda k: kt[k][0])
+    head = runs[a.book]
+    kt, per_launch, bpe = head["kt"], head["per_launch"], head["bpe"]
     alg_bytes = {  # algorithmic bytes per element of each kernel (DESIGN.md, "Kernels")
-        "k_quantize": 13.0,            # read g, read m, write m', write symbol
-        "k_chunk_bits": 1.0,
-        "k_pack": 1.0 + bpe / 8.0,
+        "k_quantize": 13.0,               # read g, read m, write m', write symbol
+        "k_chunk_bits": 1.0,              # read symbol
+        "k_pack": 1.0 + bpe / 8.0,        # read symbol, write codewords
         "k_aggregate": bpe / 8.0 + 4.0 / U,
     }
+    dom = max(per_launch, key=lambda k: kt[k][0])
     ach = alg_bytes.get(dom, 0.0) * elems / (per_launch[dom] * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, dom))
     roof = dict(bound="hbm", kernel=dom, achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                frac=round(ach / HBM_PEAK_GBS, 4), traffic=None,
+                frac=round(ach / HBM_PEAK_GBS, 4), traffic=traffic,
                 bytes_per_element=alg_bytes.get(dom), avg_launch_ms=round(per_launch[dom], 4))
-    enc_alg = (12.0 + bpe / 8.0) * elems
+    if dom == "k_aggregate":
+        roof["note"] = "the decoder is bound by its serial table-lookup chain (integer ALU / LDS latency), not by HBM"
+    roof["kernels"] = {k: {"achieved_GBs": round(alg_bytes[k] * elems / (per_launch[k] * 1e-3) / 1e9, 1),
+                           "frac": round(alg_bytes[k] * elems / (per_launch[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                       for k in alg_bytes if k in per_launch}
     res = {
         "metric": "CO3 encode+decode GElem/s and % HBM roofline on 1 MI355X; bits/element",
-        "value": round(elems / (ms_per_step * 1e-3) / 1e9, 3), "unit": "GElem/s",
-        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 4),
+        "value": head["summary"]["gelem_s"], "unit": "GElem/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": head["summary"]["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32+u8",
         "data": "synthetic GenNorm gradients (torch device generator), see DESIGN.md",
         "config": {"workload": f"{w.name}: U={U} d={d} [1,{w.E},{w.M}] gamma={w.gamma} nseg={nseg} book={a.book} "
-                               f"(pooled over users)", "elements_per_step": elems},
+                               f"({'per-user' if w.per_user_books else 'pooled over users'})",
+                   "elements_per_step": elems},
         "roofline": roof,
-        "encode": {"ms": round(enc_ms, 4), "gelem_s": round(elems / enc_ms / 1e6, 2),
-                   "hbm_frac_algorithmic": round(enc_alg / (enc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                   "bytes_per_element_algorithmic": round(12.0 + bpe / 8.0, 3)},
-        "decode_average": {"ms": round(dec_ms, 4), "gelem_s": round(elems / dec_ms / 1e6, 2),
-                           "hbm_frac_algorithmic": round((bpe / 8.0 + 4.0 / U) * elems / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
-        "bits_per_element": {"payload": round(bpe, 4), "container": round(container_bits / elems, 4)},
-        "kernel_ms_per_launch": {k: round(v, 4) for k, v in per_launch.items()},
-        "status": status,
+        "encode": head["summary"]["encode"],
+        "decode_average": head["summary"]["decode_average"],
+        "bits_per_element": head["summary"]["bits_per_element"],
+        "kernel_ms_per_launch": head["summary"]["kernel_ms_per_launch"],
+        "status": head["status"],
     }
+    others = [runs[k]["summary"] for k in runs if k != a.book]
+    if others:
+        res["other_book"] = others[0]
     if not a.no_cpu_baseline:
         ns = min(U, max(1, int(100e6 // d)))
         host = pool[0][:ns, :d].cpu().numpy()

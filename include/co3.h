@@ -122,6 +122,15 @@ int co3_codebook_export(const co3_codebook *books, uint32_t book, uint8_t *len, 
 uint32_t co3_codebook_num_books(const co3_codebook *books);
 void co3_codebook_destroy(co3_codebook *books);
 
+/* Integer weights for co3_build_codebook when the corrected gradient g + gamma m of a layer is
+ * modelled as GenNorm(mu, alpha, beta) (Sec. III eq. (gennorm); Sec. IV-A (ii): Huffman coding
+ * "using the GenNorm assumption").  weights is host memory, A entries: every symbol Q_fp can
+ * produce gets max(1, floor(p * 2^40)), p the model probability that Q_fp yields it; the other
+ * bit patterns (top exponent field, negative zero) get 0.  Host arithmetic, no GPU involved.
+ * Errors: CO3_ERR_ARG for alpha <= 0, beta <= 0 or a non-finite mu; CO3_ERR_FORMAT.          */
+int co3_gennorm_weights(co3_format format, int32_t bias, double mu, double alpha, double beta,
+                        uint64_t *weights);
+
 /* ---- user side: Algorithm 1 lines 8-10 for all U users -----------------------------------
  * v = g + gamma m (eq. (f_error_fb)), ghat = Q_fp(v), m' = v - ghat, b = h_Hf(ghat).
  * mode CO3_BOOK_FIXED encodes with `books` as they are (a code designed beforehand, e.g. from

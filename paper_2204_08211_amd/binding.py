@@ -25,7 +25,7 @@ EXPORTS = [
     "co3_plan_alphabet", "co3_plan_symbols_bytes", "co3_plan_workspace_bytes", "co3_plan_stream_words",
     "co3_build_codebook", "co3_build_codebook_device", "co3_codebook_export", "co3_codebook_num_books",
     "co3_codebook_destroy", "co3_encode", "co3_decode", "co3_ps_aggregate", "co3_status_string",
-    "co3_profile_begin", "co3_profile_end",
+    "co3_profile_begin", "co3_profile_end", "co3_gennorm_weights",
 ]
 
 
@@ -99,6 +99,7 @@ def lib():
         L.co3_decode.argtypes = [C.c_void_p, C.POINTER(DecodeArgs), C.c_void_p]
         L.co3_ps_aggregate.argtypes = [C.c_void_p, C.POINTER(AggregateArgs), C.c_void_p]
         L.co3_profile_end.argtypes = [C.POINTER(KernelTime), C.c_uint32, C.POINTER(C.c_uint32)]
+        L.co3_gennorm_weights.argtypes = [Format, C.c_int32, C.c_double, C.c_double, C.c_double, C.c_void_p]
         L.co3_status_string.argtypes = [C.c_int]
         L.co3_status_string.restype = C.c_char_p
         _lib = L
@@ -219,6 +220,14 @@ def co3_build_codebook(E, M, nbooks, weights=None):
         wp = weights.ctypes.data_as(C.c_void_p)
     _check("co3_build_codebook", lib().co3_build_codebook(Format(E, M), int(nbooks), wp, C.byref(h)))
     return Codebook(h, E, M, nbooks)
+
+
+def co3_gennorm_weights(E, M, bias, mu, alpha, beta):
+    """uint64[A] Huffman weights of the symbols when g + gamma m is GenNorm(mu, alpha, beta)."""
+    w = np.zeros(1 << (1 + E + M), dtype=np.uint64)
+    _check("co3_gennorm_weights", lib().co3_gennorm_weights(Format(E, M), int(bias), float(mu), float(alpha),
+                                                            float(beta), w.ctypes.data_as(C.c_void_p)))
+    return w
 
 
 def co3_build_codebook_device(books, weights, status, stream=None):
