@@ -108,7 +108,7 @@ uint64_t co3_plan_stream_words(const co3_plan *plan, uint32_t max_code_len);
  * symbol and internal key = A + creation order; codes are canonical by (length, symbol).
  * Runs on the host, uploads the tables, synchronises the device.
  * Errors: CO3_ERR_CODELEN if a code would exceed 64 bits, CO3_ERR_ARG if a table's weights
- * sum to 2^64 or more.                                                                     */
+ * sum to 2^64 - 1 or more.                                                                  */
 int co3_build_codebook(co3_format format, uint32_t nbooks, const uint64_t *weights,
                        co3_codebook **out);
 /* Rebuild every table of `books` on the device from device weights [nbooks][A] (e.g. the

@@ -82,7 +82,7 @@ int build_book_host(const uint64_t *w, uint32_t A, BookDev *b)
     uint64_t total = 0;
     for (uint32_t s = 0; s < A; ++s) {
         if (!w[s]) continue;
-        if (total + w[s] < total) return CO3_ERR_ARG;
+        if (total + w[s] < total || total + w[s] == ~0ull) return CO3_ERR_ARG;
         total += w[s];
         leaves.push_back({w[s], s});
     }

@@ -39,9 +39,10 @@ __global__ __launch_bounds__(kCbThreads) void k_build_books(BookDev *__restrict_
     // rank of this leaf in (weight, symbol) order among the active symbols
     if (myw > 0) {
         int rank = 0;
+#pragma unroll 8
         for (int j = 0; j < (int)A; ++j) {
             const uint64_t wj = lw[j];
-            rank += (wj > 0 && (wj < myw || (wj == myw && j < t))) ? 1 : 0;
+            rank += (int)((wj != 0) & ((wj < myw) | ((wj == myw) & (j < t))));
         }
         nw[rank] = myw;
         leaf_sym[rank] = t;
@@ -49,20 +50,35 @@ __global__ __launch_bounds__(kCbThreads) void k_build_books(BookDev *__restrict_
     __syncthreads();
 
     if (t == 0 && n >= 2) {
+        // the two front entries of each queue live in registers, so that the load refilling a queue
+        // is not needed before the pick after next; an exhausted slot shows the sentinel
+        const uint64_t kNone = ~0ull;
         int li = 0, ii = n, made = n;
+        uint64_t lw0 = nw[0], lw1 = nw[1], iw0 = kNone, iw1 = kNone;
         for (int step = 0; step < n - 1; ++step) {
             int pick[2];
+            uint64_t pw[2];
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
-                const bool have_leaf = li < n, have_int = ii < made;
-                if (have_leaf && (!have_int || nw[li] <= nw[ii])) pick[r] = li++;
-                else pick[r] = ii++;
+                if (lw0 != kNone && (iw0 == kNone || lw0 <= iw0)) {
+                    pick[r] = li; pw[r] = lw0;
+                    ++li;
+                    lw0 = lw1;
+                    lw1 = li + 1 < n ? nw[li + 1] : kNone;
+                } else {
+                    pick[r] = ii; pw[r] = iw0;
+                    ++ii;
+                    iw0 = iw1;
+                    iw1 = ii + 1 < made ? nw[ii + 1] : kNone;
+                }
             }
-            const uint64_t s = nw[pick[0]] + nw[pick[1]];
-            if (s < nw[pick[1]]) err = 1;  // the weights of this table sum to 2^64 or more
+            const uint64_t s = pw[0] + pw[1];
+            if (s < pw[1] || s == kNone) err = 1;  // the weights of this table sum to 2^64 - 1 or more
             nw[made] = s;
             parent[pick[0]] = made;
             parent[pick[1]] = made;
+            if (ii == made) iw0 = s;            // the internal queue was empty: the new node is its head
+            else if (ii + 1 == made) iw1 = s;   // it held one node: the new one is second
             ++made;
         }
     }
@@ -120,7 +136,8 @@ __global__ __launch_bounds__(kCbThreads) void k_build_books(BookDev *__restrict_
     uint32_t fast = 0;
     if (L) {
         uint32_t rank = 0;
-        for (int j = 0; j < t; ++j) rank += (slen[j] == L) ? 1u : 0u;
+#pragma unroll 8
+        for (int j = 0; j < (int)A; ++j) rank += (uint32_t)((j < t) & (slen[j] == L));
         code = first[L] + rank;
         sorted[off[L] + rank] = (uint32_t)t;
         fast = (L <= (uint32_t)kFastLen) ? ((L << 24) | (uint32_t)code) : (kFastSlow << 24);

@@ -11,6 +11,8 @@
 //
 // The work is bound by the serial integer chain of the decoder (table lookup -> shift -> next
 // lookup), not by HBM: it moves about b/8 + 4/U bytes per element.
+#include <cstdlib>
+
 #include "co3_internal.h"
 #include "quantize_math.h"
 
@@ -122,6 +124,9 @@ struct Reader {
 };
 
 // One symbol.  Returns it; `consumed` advances by its length; `bad` is set if nothing matched.
+// A code longer than the direct table is found by comparing the window with the left-aligned
+// last code of every longer length that occurs (they grow with the length).  The window holds at
+// least 32 valid bits, which decides lengths up to 32; longer ones take the exact path.
 template <class Src>
 __device__ inline uint32_t decode_symbol(Reader<Src> &r, const DecLds *T, uint32_t p0, uint32_t &consumed, bool &bad)
 {
@@ -130,22 +135,31 @@ __device__ inline uint32_t decode_symbol(Reader<Src> &r, const DecLds *T, uint32
     asm volatile("" : "+v"(nextw), "+v"(e));
     uint32_t L = e >> 8, s = e & 0xffu;
     if (__builtin_expect(L == 0u, 0)) {
-        const uint32_t code = long_code(r.src, T, p0 + consumed);
-        L = code >> 8;
-        s = code & 0xffu;
-        if (L == 0u) { bad = true; L = 1u; }
-        consumed += L;
-        r.seek(p0 + consumed);
-    } else {
-        r.window <<= L;
-        r.avail -= L;
-        consumed += L;
-        const bool take = r.avail < 32u;
-        const uint64_t add = (uint64_t)nextw << ((32u - r.avail) & 31u);
-        r.window |= take ? add : 0ull;
-        r.avail += take ? 32u : 0u;
-        r.wi += take ? 1u : 0u;
+        const uint32_t n = T->nlong;
+        uint32_t k = 0;
+        while (k < n && r.window > T->long_last[k]) ++k;
+        if (k < n) {
+            L = T->long_len[k];
+            if (L <= 32u) s = T->sorted[((uint32_t)(r.window >> (64u - L)) + T->long_base[k]) & (kMaxA - 1)];
+        }
+        if (__builtin_expect(L == 0u || L > 32u, 0)) {
+            const uint32_t code = long_code(r.src, T, p0 + consumed);  // exact 64-bit window
+            L = code >> 8;
+            s = code & 0xffu;
+            if (L == 0u) { bad = true; L = 1u; }
+            consumed += L;
+            r.seek(p0 + consumed);
+            return s;
+        }
     }
+    r.window <<= L;
+    r.avail -= L;
+    consumed += L;
+    const bool take = r.avail < 32u;
+    const uint64_t add = (uint64_t)nextw << ((32u - r.avail) & 63u);
+    r.window |= take ? add : 0ull;
+    r.avail += take ? 32u : 0u;
+    r.wi += take ? 1u : 0u;
     return s;
 }
 
