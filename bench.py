@@ -39,6 +39,8 @@ def parse():
     p.add_argument("--warmup", type=int, default=3)
     p.add_argument("--workload", default="cfg3", help="cfg1..cfg5 of BASELINE.json (default: the one the target is quoted on)")
     p.add_argument("--book", default="empirical", choices=["empirical", "model"])
+    p.add_argument("--model-encoder", default="sweep", choices=["sweep", "three"],
+                   help="encoder for --book model: the single-sweep kernel (symbols never stored) or the three-step one")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-other-book", action="store_true", help="measure only the headline code-table mode")
     p.add_argument("--ignore-status", action="store_true", help="tuning runs only: do not stop on codec error counters")
@@ -81,7 +83,8 @@ def cpu_baseline(w, it0_host, bias_host):
                 stages_s={k: round(v, 3) for k, v in tm.items()})
 
 
-ENC_KERNELS = ["k_zero_u64", "k_quantize", "k_reduce_hist", "k_build_books", "k_chunk_bits", "k_scan_chunks", "k_pack"]
+ENC_KERNELS = ["k_zero_u64", "k_quantize", "k_reduce_hist", "k_build_books", "k_chunk_bits", "k_scan_chunks", "k_pack",
+               "k_encode_fused"]
 
 
 def main():
@@ -129,9 +132,10 @@ def main():
     out = torch.zeros(d, dtype=torch.float32, device=dev)
     counter = [0]
 
-    def measure(books, mode, label):
+    def measure(books, mode, label, single_sweep=False):
         def step():
-            B.co3_encode(plan, books, pool[counter[0] % a.pool], m, m, w.gamma, buf, mode=mode)
+            B.co3_encode(plan, books, pool[counter[0] % a.pool], m, m, w.gamma, buf, mode=mode,
+                         single_sweep=single_sweep)
             B.co3_ps_aggregate(plan, books, buf, out)
             counter[0] += 1
         for _ in range(a.warmup):
@@ -153,7 +157,8 @@ def main():
         dev_ms = ev0.elapsed_time(ev1)
         kt = B.profile_end()
         status = buf.status.cpu().numpy().tolist()
-        if (status[B.STAT_CAPACITY] or status[B.STAT_NOCODE] or status[B.STAT_CORRUPT] or status[B.STAT_CODELEN]) \
+        if (status[B.STAT_CAPACITY] or status[B.STAT_NOCODE] or status[B.STAT_CORRUPT] or status[B.STAT_CODELEN]
+                or status[B.STAT_STALLED]) \
                 and not a.ignore_status:
             print(f"bench.py: codec reported errors ({label}): status={status}", file=sys.stderr)
             sys.exit(1)
@@ -215,7 +220,7 @@ def main():
         if label == "empirical":
             runs[label] = measure(emp_books, B.BOOK_EMPIRICAL, "empirical")
         else:
-            runs[label] = measure(model_books(), B.BOOK_FIXED, "model")
+            runs[label] = measure(model_books(), B.BOOK_FIXED, "model", single_sweep=a.model_encoder == "sweep")
 
     head = runs[a.book]
     kt, per_launch, bpe = head["kt"], head["per_launch"], head["bpe"]
@@ -224,6 +229,7 @@ def main():
         "k_chunk_bits": 1.0,              # read symbol
         "k_pack": 1.0 + bpe / 8.0,        # read symbol, write codewords
         "k_aggregate": bpe / 8.0 + 4.0 / U,
+        "k_encode_fused": 12.0 + bpe / 8.0,   # read g, read m, write m', write codewords
     }
     dom = max(per_launch, key=lambda k: kt[k][0])
     ach = alg_bytes.get(dom, 0.0) * elems / (per_launch[dom] * 1e-3) / 1e9

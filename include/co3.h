@@ -52,7 +52,10 @@ enum {
     CO3_STAT_NOCODE = 2,    /* symbols met by the encoder that have no codeword             */
     CO3_STAT_CAPACITY = 3,  /* chunks not written because the stream buffer is too small    */
     CO3_STAT_CODELEN = 4,   /* code tables built on the device that needed > 64 bits        */
-    CO3_STAT_CORRUPT = 5    /* sub-chunks the decoder could not decode consistently         */
+    CO3_STAT_CORRUPT = 5,   /* sub-chunks the decoder could not decode consistently         */
+    CO3_STAT_STALLED = 6    /* workgroups of the single-sweep encoder whose bounded wait for
+                             * the sizes of the preceding chunks ran out (their chunks are
+                             * not written)                                                 */
 };
 
 /* Float format of Q_fp: one sign bit, exp_bits exponent bits, mant_bits mantissa bits
@@ -81,8 +84,9 @@ typedef struct co3_codebook co3_codebook;   /* a set of Huffman code tables: lib
  * bias is host memory, [U][nseg]: the value exponent of exponent field f is f - bias, i.e.
  * the paper's c_scale = 2^b has b = (2^(exp_bits-1) - 1) - bias.  Required: bias <= 127 (the
  * smallest normal magnitude is a normal fp32) and (2^exp_bits - 2) - bias <= 100.
- * segments == NULL means one segment covering [0, d) with codebook 0.  per_user_books != 0 gives every user its own tables (table index
- * u * books_per_user + segment.codebook) instead of one table per layer shared by all users.
+ * segments == NULL means one segment covering [0, d) with codebook 0.  per_user_books != 0
+ * gives every user its own tables (table index u * books_per_user + segment.codebook)
+ * instead of one table per layer shared by all users.
  * Allocates small device tables; synchronises the device.  Not on the per-iteration path:
  * the paper holds the bias for several epochs (Sec. VI).                                   */
 int co3_plan_create(co3_format format, uint32_t U, uint64_t d, uint32_t nseg,
@@ -135,7 +139,10 @@ int co3_gennorm_weights(co3_format format, int32_t bias, double mu, double alpha
  * v = g + gamma m (eq. (f_error_fb)), ghat = Q_fp(v), m' = v - ghat, b = h_Hf(ghat).
  * mode CO3_BOOK_FIXED encodes with `books` as they are (a code designed beforehand, e.g. from
  * the GenNorm model); CO3_BOOK_EMPIRICAL first rebuilds `books` on the device from this
- * round's symbol histogram.                                                                */
+ * round's symbol histogram.
+ * In mode CO3_BOOK_FIXED `symbols` and `hist` may both be NULL: neither is produced then, and
+ * the library runs the single-sweep encoder, in which the symbols never reach device memory
+ * (12 bytes of traffic per element plus the stream).                                        */
 enum { CO3_BOOK_FIXED = 0, CO3_BOOK_EMPIRICAL = 1 };
 
 typedef struct {
@@ -148,6 +155,7 @@ typedef struct {
     co3_codebook *books;     /* set with co3_plan_num_books() tables                         */
     uint8_t *symbols;        /* device, co3_plan_symbols_bytes(): [U][d] symbols (out)       */
     uint64_t *hist;          /* device [num_books][A] symbol counts (out; cleared here)      */
+                             /* (symbols, hist: both NULL selects the single-sweep encoder)  */
     uint32_t *words;         /* device [U][words_stride] streams (out)                       */
     uint64_t words_stride;   /* capacity of one user's stream in 32-bit words                */
     uint64_t *chunk_offset;  /* device [U][num_chunks+1] bit offsets of the chunks (out)     */

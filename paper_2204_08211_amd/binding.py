@@ -16,7 +16,7 @@ CHUNK = 4096
 SUB = 64
 SUBS_PER_CHUNK = 64
 STATUS_WORDS = 8
-(STAT_NONFINITE, STAT_CLAMPED, STAT_NOCODE, STAT_CAPACITY, STAT_CODELEN, STAT_CORRUPT) = range(6)
+(STAT_NONFINITE, STAT_CLAMPED, STAT_NOCODE, STAT_CAPACITY, STAT_CODELEN, STAT_CORRUPT, STAT_STALLED) = range(7)
 BOOK_FIXED, BOOK_EMPIRICAL = 0, 1
 OK, ERR_ARG, ERR_FORMAT, ERR_CAPACITY, ERR_CODELEN, ERR_CORRUPT, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
@@ -259,13 +259,16 @@ class RoundBuffers:
         return self.symbols[:p.U * p.sym_stride].view(p.U, p.sym_stride)[:, :p.d]
 
 
-def co3_encode(plan, books, g, m, m_out, gamma, buf, mode=BOOK_EMPIRICAL, stream=None):
+def co3_encode(plan, books, g, m, m_out, gamma, buf, mode=BOOK_EMPIRICAL, stream=None, single_sweep=False):
     """User side of one round for all U users (Algorithm 1 lines 8-10).  g, m, m_out are float32
-    device tensors [U][row_stride]; outputs land in `buf` (RoundBuffers)."""
+    device tensors [U][row_stride]; outputs land in `buf` (RoundBuffers).  single_sweep (fixed code
+    only) passes no symbols and no hist buffer, which selects the library's single-sweep encoder."""
+    assert not single_sweep or mode == BOOK_FIXED
     assert g.dim() == 2 and g.shape == m.shape == m_out.shape and g.stride(1) == 1
     assert g.stride(0) == m.stride(0) == m_out.stride(0)
     a = EncodeArgs(g.data_ptr(), m.data_ptr(), m_out.data_ptr(), g.stride(0), float(np.float32(gamma)), int(mode),
-                   books.handle, buf.symbols.data_ptr(), buf.hist.data_ptr(), buf.words.data_ptr(),
+                   books.handle, None if single_sweep else buf.symbols.data_ptr(),
+                   None if single_sweep else buf.hist.data_ptr(), buf.words.data_ptr(),
                    buf.words_stride, buf.chunk_offset.data_ptr(), buf.sub_bits.data_ptr(),
                    buf.payload_bits.data_ptr(), buf.status.data_ptr(), buf.workspace.data_ptr(),
                    buf.workspace.numel())

@@ -144,7 +144,9 @@ size_t co3_plan_workspace_bytes(const co3_plan *plan)
     if (!plan) return 0;
     const Layout &l = plan->lay;
     const size_t hist_rep = ((size_t)kHistGlobalRep * l.nbooks * l.A * sizeof(uint64_t) + 255) & ~(size_t)255;
-    return hist_rep + (size_t)l.U * l.nchunks * sizeof(uint32_t) + 512;
+    const size_t three_step = hist_rep + (size_t)l.U * l.nchunks * sizeof(uint32_t) + 512;
+    const size_t single_sweep = fused_workspace_bytes(l);
+    return three_step > single_sweep ? three_step : single_sweep;
 }
 
 uint64_t co3_plan_stream_words(const co3_plan *plan, uint32_t max_code_len)
@@ -235,13 +237,16 @@ int co3_encode(const co3_plan *plan, const co3_encode_args *a, void *stream)
 {
     if (!plan || !a) return CO3_ERR_ARG;
     const Layout &lay = plan->lay;
-    if (!a->g || !a->m || !a->m_out || !a->symbols || !a->hist || !a->words || !a->chunk_offset ||
-        !a->sub_bits || !a->payload_bits || !a->status || !a->workspace)
+    if (!a->g || !a->m || !a->m_out || !a->words || !a->chunk_offset || !a->sub_bits || !a->payload_bits ||
+        !a->status || !a->workspace)
         return CO3_ERR_ARG;
+    if (a->mode != CO3_BOOK_FIXED && a->mode != CO3_BOOK_EMPIRICAL) return CO3_ERR_ARG;
+    // symbols and hist come as a pair; without them a fixed code is encoded in a single sweep
+    const bool single_sweep = a->mode == CO3_BOOK_FIXED && !a->symbols && !a->hist;
+    if (!single_sweep && (!a->symbols || !a->hist)) return CO3_ERR_ARG;
     if (!aligned16(a->g) || !aligned16(a->m) || !aligned16(a->m_out) || !aligned16(a->symbols) ||
         (a->row_stride & 3u) || a->row_stride < lay.d)
         return CO3_ERR_ARG;
-    if (a->mode != CO3_BOOK_FIXED && a->mode != CO3_BOOK_EMPIRICAL) return CO3_ERR_ARG;
     int rc = check_books(plan, a->books);
     if (rc != CO3_OK) return rc;
     if (a->workspace_bytes < co3_plan_workspace_bytes(plan)) return CO3_ERR_CAPACITY;
@@ -249,6 +254,8 @@ int co3_encode(const co3_plan *plan, const co3_encode_args *a, void *stream)
 
     DeviceGuard guard(plan->device);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (single_sweep)
+        return launch_encode_fused(lay, *a, a->books->d_books, s) == hipSuccess ? CO3_OK : CO3_ERR_HIP;
     EncodeWs ws;
     const uint64_t hist_rep_n = (uint64_t)kHistGlobalRep * lay.nbooks * lay.A;
     ws.hist_rep = reinterpret_cast<uint64_t *>((reinterpret_cast<uintptr_t>(a->workspace) + 255u) & ~(uintptr_t)255u);

@@ -87,7 +87,7 @@ namespace co3 {
 
 // Per-kernel event timing (profile.cpp).  A ProfScope around a launch records two events on
 // the stream when profiling is on, and does nothing otherwise.
-enum KernelId { K_ZERO = 0, K_QUANTIZE, K_REDUCE_HIST, K_BUILD_BOOKS, K_CHUNK_BITS, K_SCAN, K_PACK, K_DECODE, K_AGGREGATE, K_COUNT };
+enum KernelId { K_ZERO = 0, K_QUANTIZE, K_REDUCE_HIST, K_BUILD_BOOKS, K_CHUNK_BITS, K_SCAN, K_PACK, K_DECODE, K_AGGREGATE, K_FUSED, K_COUNT };
 bool profile_enabled();
 class ProfScope {
 public:
@@ -114,6 +114,9 @@ hipError_t launch_build_books(BookDev *books, uint32_t nbooks, uint32_t A, const
                               uint64_t *status, hipStream_t s);
 hipError_t launch_pack(const Layout &lay, const co3_encode_args &a, const BookDev *books,
                        const EncodeWs &ws, hipStream_t s);
+// single-sweep encoder for a fixed code (k_fused.hip); its workspace need in bytes
+hipError_t launch_encode_fused(const Layout &lay, const co3_encode_args &a, const BookDev *books, hipStream_t s);
+size_t fused_workspace_bytes(const Layout &lay);
 hipError_t launch_decode(const Layout &lay, const co3_decode_args &a, const BookDev *books, hipStream_t s);
 hipError_t launch_aggregate(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
                             hipStream_t s);

@@ -1,0 +1,400 @@
+// The whole user side in one sweep for a code that is held fixed (Algorithm 1 lines 8-10 with
+// the Huffman code designed beforehand, Sec. IV-A (ii)): error correction, fp conversion, memory
+// update and Huffman coding without the symbols ever reaching HBM.
+//
+// HBM traffic per element: read g (4) + read m (4) + write m' (4) + write b (r/d bits).
+//
+// A workgroup of four wavefronts takes four consecutive chunks of one user:
+//   1. all threads quantize the chunks one after the other (the next chunk's g and m are requested
+//      before the current one is computed) and leave the symbols in LDS, in the rows of 16 + 1
+//      words the pack step reads without bank conflicts;
+//   2. wavefront w sums the code lengths of chunk w: lane j owns sub-chunk j;
+//   3. the workgroup's 32-bit-rounded size is published and the sizes of all earlier workgroups of
+//      the user are collected by a decoupled look-back: every workgroup first publishes its own
+//      size, then reads its predecessors' until it meets one that already knows its running total.
+//      Workgroups take their position from a ticket counter, so every predecessor is already
+//      running and publishes without waiting for anyone: the wait always ends.  It is bounded all
+//      the same; a workgroup whose bound runs out marks its entry as stalled, which its successors
+//      inherit instead of waiting, writes no stream words and is counted in the status block.
+//      An entry is one 64-bit word (flag and size together) and carries everything a successor
+//      needs, so it is written and read with relaxed device-scope atomics: ordering fences would
+//      make every workgroup write back and invalidate its L2;
+//   4. wavefront w appends the codewords of chunk w inside an LDS window at the bit offsets given
+//      by the wave prefix sum of the sub-chunk sizes and copies the window out coalesced.
+#include "co3_internal.h"
+#include "quantize_math.h"
+
+namespace co3 {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr int kFuCpb = 4;                            // chunks (= wavefronts) per workgroup
+constexpr int kFuThreads = 64 * kFuCpb;
+constexpr int kFuRow = 17;                           // 16 words of symbols + 1 pad
+constexpr int kFuStage = kSubsPerChunk * kFuRow;     // 1088 words hold a chunk's symbols
+constexpr int kFuWin = 1088;                         // LDS window of the output: 8.5 bit/element per pass
+constexpr int kFuVec = kChunk / 4 / kFuThreads;      // 16-byte vectors of g (and of m) per thread and chunk
+constexpr uint32_t kFuSpinLimit = 1u << 20;          // polls of one predecessor entry before giving up
+
+// look-back entry: flag in the top two bits, size in bits below
+constexpr uint64_t kLbAgg = 1ull << 62;      // size of this workgroup alone
+constexpr uint64_t kLbPrefix = 2ull << 62;   // size of this workgroup and all before it
+constexpr uint64_t kLbStalled = 3ull << 62;
+constexpr uint64_t kLbValue = (1ull << 62) - 1;
+
+static_assert(kFuThreads == kMaxA, "one thread per code-table entry");
+
+__device__ inline uint32_t fu_find_chunk_segment(const SegDev *segs, uint32_t nseg, uint64_t chunk)
+{
+    uint32_t lo = 0, hi = nseg;  // segs[nseg].chunk_start = nchunks > chunk
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (segs[mid].chunk_start <= chunk) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ inline void fu_wave_sync_lds()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__global__ __launch_bounds__(kFuThreads) void k_encode_fused(
+    Layout lay, const float *__restrict__ g, const float *m, float *m_out, uint64_t row_stride, float gamma,
+    const BookDev *__restrict__ books, uint32_t *__restrict__ tickets, uint64_t *lb_state, uint32_t nblk,
+    uint32_t spin_limit, uint64_t *__restrict__ chunk_offset, uint16_t *__restrict__ sub_bits,
+    uint64_t *__restrict__ payload_bits, uint32_t *__restrict__ words, uint64_t words_stride,
+    uint64_t *__restrict__ status)
+{
+    __shared__ uint32_t s_stage[kFuCpb][kFuStage + 1];
+    __shared__ uint32_t s_win[kFuCpb][kFuWin + 1];
+    __shared__ uint32_t s_fast[kFuCpb][kMaxA];
+    __shared__ uint64_t s_e0[kFuCpb];
+    __shared__ uint32_t s_n[kFuCpb], s_book[kFuCpb], s_cbits[kFuCpb];
+    __shared__ int32_t s_bias[kFuCpb];
+    __shared__ uint64_t s_prefix;
+    __shared__ uint32_t s_ticket, s_stalled;
+
+    const uint32_t t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const uint32_t u = blockIdx.y;
+
+    if (t == 0) s_ticket = atomicAdd(&tickets[u], 1u);
+    __syncthreads();
+    const uint32_t b = s_ticket;  // position among the user's workgroups, < nblk = gridDim.x
+    const uint64_t c0 = (uint64_t)b * kFuCpb;
+    const uint32_t nck = lay.nchunks - c0 < (uint64_t)kFuCpb ? (uint32_t)(lay.nchunks - c0) : (uint32_t)kFuCpb;
+
+    if (t < (uint32_t)kFuCpb) {
+        uint64_t e0 = 0;
+        uint32_t n = 0, bk = 0;
+        int32_t bias = 0;
+        if (t < nck) {
+            const uint64_t c = c0 + t;
+            const uint32_t seg = fu_find_chunk_segment(lay.segs, lay.nseg, c);
+            const SegDev sd = lay.segs[seg];
+            e0 = sd.offset + (c - sd.chunk_start) * kChunk;
+            const uint64_t left = sd.offset + sd.length - e0;
+            n = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
+            bk = (lay.per_user_books ? u * lay.books_per_user : 0u) + (uint32_t)sd.book;
+            bias = lay.bias[(uint64_t)u * lay.nseg + seg];
+        }
+        s_e0[t] = e0; s_n[t] = n; s_book[t] = bk; s_bias[t] = bias;
+    }
+    __syncthreads();
+
+    // ---- 1. quantize the chunks, symbols to LDS ------------------------------------------------
+    const float *gu = g + (uint64_t)u * row_stride;
+    const float *mu = m + (uint64_t)u * row_stride;
+    float *mo = m_out + (uint64_t)u * row_stride;
+    const uint32_t sign_shift = lay.E + lay.M;
+    uint32_t n_nonfinite = 0, n_clamped = 0;
+
+    // a whole chunk at a 16-byte aligned position takes the vector path
+    auto vec_ok = [&](uint32_t k) { return k < nck && s_n[k] == (uint32_t)kChunk && (s_e0[k] & 3u) == 0; };
+    f4 gn[kFuVec], mn[kFuVec];
+    if (vec_ok(0)) {
+        const uint64_t e0 = s_e0[0];
+#pragma unroll
+        for (int r = 0; r < kFuVec; ++r) {
+            const uint64_t i = e0 + 4u * (t + (uint32_t)kFuThreads * r);
+            gn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(gu + i));
+            mn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(mu + i));
+        }
+    }
+    // the code-table entries of the chunks, one table per wavefront's chunk
+    for (uint32_t k = 0; k < nck; ++k) s_fast[k][t] = books[s_book[k]].fast[t];
+
+#pragma unroll 1
+    for (uint32_t k = 0; k < nck; ++k) {
+        const bool vk = vec_ok(k);
+        const uint64_t e0 = s_e0[k];
+        const QConst qc = make_qconst(lay.E, lay.M, s_bias[k]);
+        if (vk) {
+            f4 gc[kFuVec], mc[kFuVec];
+#pragma unroll
+            for (int r = 0; r < kFuVec; ++r) { gc[r] = gn[r]; mc[r] = mn[r]; }
+            if (vec_ok(k + 1)) {
+                const uint64_t e1 = s_e0[k + 1];
+#pragma unroll
+                for (int r = 0; r < kFuVec; ++r) {
+                    const uint64_t i = e1 + 4u * (t + (uint32_t)kFuThreads * r);
+                    gn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(gu + i));
+                    mn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(mu + i));
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < kFuVec; ++r) {
+                const uint32_t dw = t + (uint32_t)kFuThreads * r;  // word of the chunk's symbols
+                f4 eo;
+                uint32_t packed = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float v = __fadd_rn(gc[r][j], __fmul_rn(gamma, mc[r][j]));
+                    uint32_t s, flags;
+                    float q;
+                    quantize(v, qc, sign_shift, s, q, flags);
+                    eo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
+                    n_nonfinite += flags & 1u;
+                    n_clamped += (flags >> 1) & 1u;
+                    packed |= s << (8 * j);
+                }
+                __builtin_nontemporal_store(eo, reinterpret_cast<f4 *>(mo + e0 + 4u * dw));
+                s_stage[k][dw + (dw >> 4)] = packed;
+            }
+        } else {
+            // ragged or unaligned chunk: element path; the next chunk is requested afterwards
+            const uint32_t n = s_n[k];
+            uint8_t *stage_bytes = reinterpret_cast<uint8_t *>(s_stage[k]);
+            for (uint32_t j = t; j < n; j += kFuThreads) {
+                const float v = __fadd_rn(gu[e0 + j], __fmul_rn(gamma, mu[e0 + j]));
+                uint32_t s, flags;
+                float q;
+                quantize(v, qc, sign_shift, s, q, flags);
+                mo[e0 + j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
+                n_nonfinite += flags & 1u;
+                n_clamped += (flags >> 1) & 1u;
+                const uint32_t dw = j >> 2;
+                stage_bytes[4u * (dw + (dw >> 4)) + (j & 3u)] = (uint8_t)s;
+            }
+            if (vec_ok(k + 1)) {
+                const uint64_t e1 = s_e0[k + 1];
+#pragma unroll
+                for (int r = 0; r < kFuVec; ++r) {
+                    const uint64_t i = e1 + 4u * (t + (uint32_t)kFuThreads * r);
+                    gn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(gu + i));
+                    mn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(mu + i));
+                }
+            }
+        }
+    }
+    if (n_nonfinite)
+        atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NONFINITE), (unsigned long long)n_nonfinite);
+    if (n_clamped)
+        atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CLAMPED), (unsigned long long)n_clamped);
+    __syncthreads();
+
+    // ---- 2. code lengths: wavefront = chunk, lane = sub-chunk ----------------------------------
+    const bool active = wave < nck;
+    const uint64_t c = c0 + wave;
+    const uint32_t n = active ? s_n[wave] : 0u;
+    const int first = (int)lane * kSub;
+    const int cnt = (int)n - first < 0 ? 0 : ((int)n - first > kSub ? kSub : (int)n - first);
+    const uint32_t *row = s_stage[wave] + kFuRow * lane;
+    const uint32_t *fast = s_fast[wave];
+    const BookDev &book = books[s_book[wave]];
+    uint32_t my_bits = 0;
+    if (active) {
+        uint32_t nocode = 0;
+#pragma unroll 4
+        for (int jj = 0; jj < kSub / 4; ++jj) {
+            const uint32_t w4 = row[jj];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t s = (w4 >> (8 * q)) & 0xffu;
+                const bool in = 4 * jj + q < cnt;
+                uint32_t L = in ? (fast[s] >> 24) : 0u;
+                if (__builtin_expect(L == kFastSlow, 0)) L = book.len[s];
+                nocode += (in && L == 0u) ? 1u : 0u;
+                my_bits += L;
+            }
+        }
+        sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane] = (uint16_t)my_bits;
+        if (nocode)
+            atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NOCODE), (unsigned long long)nocode);
+    }
+    uint32_t incl = my_bits;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t y = __shfl_up(incl, o, 64);
+        if ((int)lane >= o) incl += y;
+    }
+    const uint32_t excl = incl - my_bits;
+    const uint32_t chunk_total = __shfl(incl, 63, 64);
+    if (lane == 0) s_cbits[wave] = chunk_total;  // 0 for a wavefront without a chunk
+    __syncthreads();
+
+    // ---- 3. publish the workgroup's size, look back for the offset -----------------------------
+    uint32_t before = 0;  // 32-bit-rounded sizes of the workgroup's chunks ahead of this wavefront's
+    uint32_t own = 0, pay = 0;
+#pragma unroll
+    for (int k = 0; k < kFuCpb; ++k) {
+        const uint32_t a = (s_cbits[k] + 31u) & ~31u;
+        if ((uint32_t)k < wave) before += a;
+        own += a;
+        pay += s_cbits[k];
+    }
+    uint64_t *state = lb_state + (uint64_t)u * nblk;
+    if (wave == 0) {
+        if (lane == 0)
+            __hip_atomic_store(&state[b], (b == 0 ? kLbPrefix : kLbAgg) | own, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        uint64_t prefix = 0;
+        int64_t pos = (int64_t)b - 1;
+        bool stalled = false;
+        while (pos >= 0) {
+            const int64_t idx = pos - (int64_t)lane;
+            uint64_t v = kLbPrefix;  // before the first workgroup: running total 0
+            if (idx >= 0) {
+                uint32_t spins = 0;
+                v = __hip_atomic_load(&state[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                while ((v >> 62) == 0 && spins < spin_limit) {
+                    __builtin_amdgcn_s_sleep(1);
+                    v = __hip_atomic_load(&state[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ++spins;
+                }
+            }
+            // lane 0 holds the nearest predecessor; sum up to and including the first running total
+            const uint64_t has_prefix = __ballot((v >> 62) == 2);
+            const int stop = has_prefix ? (int)__builtin_ctzll(has_prefix) : 63;
+            const bool bad = (int)lane <= stop && ((v >> 62) == 0 || (v >> 62) == 3);
+            if (__any(bad)) { stalled = true; break; }
+            uint64_t val = ((int)lane <= stop) ? (v & kLbValue) : 0ull;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) val += __shfl_xor(val, o, 64);
+            prefix += val;
+            if (has_prefix) break;
+            pos -= 64;
+        }
+        if (lane == 0) {
+            if (stalled) {
+                __hip_atomic_store(&state[b], kLbStalled, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_STALLED), 1ull);
+            } else if (b != 0) {
+                __hip_atomic_store(&state[b], kLbPrefix | (prefix + own), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+            s_prefix = prefix;
+            s_stalled = stalled ? 1u : 0u;
+            atomicAdd(reinterpret_cast<unsigned long long *>(payload_bits + u), (unsigned long long)pay);
+        }
+    }
+    __syncthreads();
+    if (!active || s_stalled) return;  // whole wavefronts; no workgroup barrier below
+    const uint64_t off = s_prefix + before;
+    if (lane == 0) {
+        uint64_t *co = chunk_offset + (uint64_t)u * (lay.nchunks + 1);
+        co[c] = off;
+        if (c + 1 == lay.nchunks) co[lay.nchunks] = off + ((chunk_total + 31u) & ~31u);
+    }
+
+    // ---- 4. pack chunk `wave` -------------------------------------------------------------------
+    const uint32_t nwords = (chunk_total + 31u) >> 5;
+    const uint64_t off_words = off >> 5;
+    if (off_words + nwords > words_stride) {
+        if (lane == 0) atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CAPACITY), 1ull);
+        return;
+    }
+    uint32_t *dst = words + (uint64_t)u * words_stride + off_words;
+    uint32_t *win = s_win[wave];
+    for (uint32_t wbase = 0; wbase < nwords; wbase += kFuWin) {
+        const uint32_t wn = nwords - wbase < (uint32_t)kFuWin ? nwords - wbase : (uint32_t)kFuWin;
+        for (uint32_t i = lane; i <= wn; i += 64) win[i] = 0;
+        fu_wave_sync_lds();
+        uint32_t wi = (excl >> 5) - wbase;  // window word receiving the next completed 32 bits
+        uint32_t np = excl & 31u;           // bits pending in acc (the leading np bits belong to earlier lanes)
+        uint64_t acc = 0;
+        auto append = [&](uint64_t code, uint32_t L) {  // L <= 32, np < 32
+            acc = (acc << L) | code;
+            np += L;
+            if (np >= 32u) {
+                np -= 32u;
+                if (wi < wn) atomicOr(&win[wi], (uint32_t)(acc >> np));  // unsigned: false below the window
+                ++wi;
+            }
+        };
+#pragma unroll 2
+        for (int jj = 0; jj < kSub / 4; ++jj) {
+            const uint32_t w4 = row[jj];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t s = (w4 >> (8 * q)) & 0xffu;
+                const uint32_t e = (4 * jj + q < cnt) ? fast[s] : 0u;
+                uint32_t L = e >> 24;
+                uint64_t code = e & 0x00ffffffu;
+                if (__builtin_expect(L == kFastSlow, 0)) {
+                    L = book.len[s];
+                    code = book.code[s];
+                    if (L > 32u) {
+                        append(code >> 32, L - 32u);
+                        code &= 0xffffffffull;
+                        L = 32u;
+                    }
+                }
+                if (L) append(code, L);
+            }
+        }
+        if (np && wi < wn) atomicOr(&win[wi], (uint32_t)(acc << (32u - np)));
+        fu_wave_sync_lds();
+        for (uint32_t i = lane; i < wn; i += 64) __builtin_nontemporal_store(win[i], dst + wbase + i);
+        fu_wave_sync_lds();
+    }
+}
+
+// Fill kernel for the look-back state and the payload counters (no memset node, so that callers
+// may capture the sequence in a graph).
+__global__ void k_zero_fused(uint64_t *p, uint64_t n, uint64_t *q, uint64_t nq)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+    if (i < nq) q[i] = 0;
+}
+
+size_t fused_workspace_bytes(const Layout &lay)
+{
+    const uint64_t nblk = (lay.nchunks + kFuCpb - 1) / kFuCpb;
+    // tickets (one 64-bit slot per user) and the look-back entries, plus alignment slack
+    return (size_t)(((uint64_t)lay.U + (uint64_t)lay.U * nblk) * sizeof(uint64_t) + 512);
+}
+
+hipError_t launch_encode_fused(const Layout &lay, const co3_encode_args &a, const BookDev *books, hipStream_t s)
+{
+    if (lay.U == 0) return hipSuccess;
+    const uint64_t nblk = (lay.nchunks + kFuCpb - 1) / kFuCpb;
+    uint64_t *base = reinterpret_cast<uint64_t *>((reinterpret_cast<uintptr_t>(a.workspace) + 255u) & ~(uintptr_t)255u);
+    uint64_t *ticket_slots = base;               // [U], the low 32 bits of each are the counter
+    uint64_t *lb_state = base + lay.U;           // [U][nblk]
+    const uint64_t nz = (uint64_t)lay.U + (uint64_t)lay.U * nblk;
+    {
+        ProfScope prof(K_ZERO, s);
+        const uint64_t nmax = nz > lay.U ? nz : lay.U;
+        hipLaunchKernelGGL(k_zero_fused, dim3((uint32_t)((nmax + 255) / 256)), dim3(256), 0, s, base, nz,
+                           a.payload_bits, (uint64_t)lay.U);
+    }
+    if (lay.nchunks == 0) {
+        // nothing to encode: every user's stream is empty; chunk_offset[u][0] = 0
+        ProfScope prof(K_ZERO, s);
+        hipLaunchKernelGGL(k_zero_fused, dim3((lay.U + 255) / 256), dim3(256), 0, s, a.chunk_offset,
+                           (uint64_t)lay.U, a.chunk_offset, (uint64_t)0);
+        return hipGetLastError();
+    }
+    ProfScope prof(K_FUSED, s);
+    hipLaunchKernelGGL(k_encode_fused, dim3((uint32_t)nblk, lay.U), dim3(kFuThreads), 0, s, lay, a.g, a.m, a.m_out,
+                       a.row_stride, a.gamma, books, reinterpret_cast<uint32_t *>(ticket_slots), lb_state,
+                       (uint32_t)nblk, kFuSpinLimit, a.chunk_offset, a.sub_bits, a.payload_bits, a.words,
+                       a.words_stride, a.status);
+    return hipGetLastError();
+}
+
+}  // namespace co3

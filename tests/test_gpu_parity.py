@@ -184,3 +184,106 @@ def test_error_paths_capacity_nocode_corrupt():
     B.co3_ps_aggregate(plan, books, buf, out)
     torch.cuda.synchronize()
     assert int(buf.status[B.STAT_CORRUPT].item()) >= 1
+
+
+# ---- single-sweep encoder (fixed code, symbols never stored) ------------------------------------
+
+def _single_sweep_case(kw, g, m, gamma, max_code_len=32, weights=None):
+    """Code from the oracle's own histogram of this input (or `weights`), then both sides encode
+    with that fixed code; the GPU side through the single-sweep entry."""
+    if weights is None:
+        weights = gu.oracle_round(kw, g, m, gamma)["hist"]
+    ref = gu.oracle_round(kw, g, m, gamma, weights=weights)
+    gpu, _ = gu.gpu_round(kw, g, m, gamma, BOOK_FIXED, weights=weights, max_code_len=max_code_len,
+                          single_sweep=True)
+    gu.compare_round(gpu, ref, kw["d"], single_sweep=True)
+    return gpu, ref
+
+
+@pytest.mark.parametrize("E,M,d", [(3, 0, 5 * 2048 + 123), (4, 3, 40000), (3, 2, 4095), (2, 1, 1), (4, 3, 4096 * 4),
+                                   (4, 2, 4096 * 9 + 1)])
+def test_single_sweep_single_user(E, M, d):
+    rng = np.random.default_rng(100 + d)
+    bias = 14 if E == 4 else (6 if E == 3 else 2)
+    g, m = make_inputs(rng, 1, d, E, M, bias, alpha=orc.grid(E, M, bias)[-1] / 6)
+    kw = dict(E=E, M=M, U=1, d=d, bias=[[bias]])
+    _single_sweep_case(kw, g, m, 0.9)
+
+
+@pytest.mark.parametrize("per_user", [False, True])
+def test_single_sweep_multi_user_multi_segment(per_user):
+    # layers that start at unaligned elements, empty and tiny layers, several tables
+    E, M, U = 3, 2, 3
+    seg_len = [1, 63, 4097, 0, 2048 * 3 + 5, 64, 9001, 4096, 4096 * 5, 7]
+    seg_book = [0, 1, 2, 0, 1, 3, 2, 0, 1, 3]
+    d = sum(seg_len)
+    rng = np.random.default_rng(27 + per_user)
+    bias = rng.integers(8, 20, (U, len(seg_len))).astype(np.int32)
+    g = np.empty((U, d), np.float32); m = np.empty((U, d), np.float32)
+    off = 0
+    for k, n in enumerate(seg_len):
+        for u in range(U):
+            top = orc.grid(E, M, int(bias[u, k]))[-1]
+            g[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, top / 8)
+            m[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, top / 30)
+        off += n
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias, seg_len=seg_len, seg_book=seg_book, per_user_books=per_user)
+    _single_sweep_case(kw, g, m, 0.9)
+
+
+def test_single_sweep_many_workgroups():
+    # more than 64 workgroups per user, so the look-back walks several windows of entries
+    E, M, U = 4, 3, 2
+    d = 4096 * 4 * 150 + 4096 + 17
+    rng = np.random.default_rng(31)
+    g = np.stack([syn.gennorm_numpy(rng, d, 1.0, 1e-3) for _ in range(U)])
+    m = np.stack([syn.gennorm_numpy(rng, d, 1.0, 3e-4) for _ in range(U)])
+    bias = syn.bias_for_max(np.abs(g + np.float32(0.9) * m).max(), E)
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[bias]] * U)
+    _single_sweep_case(kw, g, m, 0.9)
+
+
+def test_single_sweep_long_codes_and_model_code():
+    E, M, U, d = 4, 1, 1, 6000
+    A = 64
+    nm = orc.num_magnitudes(E, M)
+    emit = np.array([s for s in range(A) if (s & 31) < nm and s != 32])
+    w = np.zeros(A, np.uint64)
+    w[emit] = np.array([1] + [1 << i for i in range(emit.size - 1)], np.uint64)
+    rng = np.random.default_rng(13)
+    bias = 16
+    grid = orc.grid(E, M, bias)
+    k = rng.integers(0, nm, d)
+    g = (grid[k] * rng.choice([-1.0, 1.0], d)).astype(np.float32)[None, :]
+    m = np.zeros_like(g)
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[bias]])
+    _, ref = _single_sweep_case(kw, g, m, 0.9, max_code_len=64, weights=w[None, :])
+    assert ref["lens"].max() >= 57
+    # GenNorm-model code (Sec. IV-A (ii)) on GenNorm data
+    E, M, U, d = 4, 3, 2, 30000
+    g = np.stack([syn.gennorm_numpy(rng, d, 0.9, 1e-3) for _ in range(U)])
+    m = np.zeros_like(g)
+    bias = syn.bias_for_max(np.abs(g).max(), E)
+    w, _, _ = orc.gennorm_weights(E, M, bias, 0.0, 1e-3, 0.9)
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[bias]] * U)
+    _single_sweep_case(kw, g, m, 0.9, max_code_len=64, weights=w[None, :])
+
+
+def test_single_sweep_capacity_and_nocode():
+    E, M, U, d, bias = 4, 3, 2, 4096 * 6 + 100, 18
+    rng = np.random.default_rng(41)
+    g, m = make_inputs(rng, U, d, E, M, bias, specials=0.0, alpha=2e-3)
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[bias]] * U)
+    ref = gu.oracle_round(kw, g, m, 0.5)
+    small = int(ref["chunk_offset"][0][3] // 32) + 5   # room for three chunks and a bit
+    gpu, _ = gu.gpu_round(kw, g, m, 0.5, BOOK_FIXED, weights=ref["hist"], words_stride=small,
+                          want_decode=False, single_sweep=True)
+    assert int(gpu["status_encode"][3]) >= 1
+    gu.assert_bits_equal(gpu["chunk_offset"], ref["chunk_offset"], "chunk offsets")
+    gu.assert_bits_equal(gpu["words"][0, : int(ref["chunk_offset"][0][3] // 32)],
+                         ref["words"][0][: int(ref["chunk_offset"][0][3] // 32)], "chunks that fit")
+    w = ref["hist"].copy()
+    third = np.argsort(ref["hist"][0])[-3]
+    w[0, third] = 0
+    gpu, _ = gu.gpu_round(kw, g, m, 0.5, BOOK_FIXED, weights=w, want_decode=False, single_sweep=True)
+    assert int(gpu["status_encode"][2]) == int(ref["hist"][0][third])
