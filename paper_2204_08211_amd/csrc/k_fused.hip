@@ -20,7 +20,8 @@
 //      needs, so it is written and read with relaxed device-scope atomics: ordering fences would
 //      make every workgroup write back and invalidate its L2;
 //   4. wavefront w appends the codewords of chunk w inside an LDS window at the bit offsets given
-//      by the wave prefix sum of the sub-chunk sizes and copies the window out coalesced.
+//      by the wave prefix sum of the sub-chunk sizes (this needs no stream offset and runs while
+//      the look-back's answers travel) and copies the window out coalesced.
 #include "co3_internal.h"
 #include "quantize_math.h"
 
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
     if (lane == 0) s_cbits[wave] = chunk_total;  // 0 for a wavefront without a chunk
     __syncthreads();
 
-    // ---- 3. publish the workgroup's size, look back for the offset -----------------------------
+    // ---- 3. publish the workgroup's size; pack while the predecessors publish theirs ----------
     uint32_t before = 0;  // 32-bit-rounded sizes of the workgroup's chunks ahead of this wavefront's
     uint32_t own = 0, pay = 0;
 #pragma unroll
@@ -246,10 +247,58 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
         pay += s_cbits[k];
     }
     uint64_t *state = lb_state + (uint64_t)u * nblk;
+    if (t == 0)
+        __hip_atomic_store(&state[b], (b == 0 ? kLbPrefix : kLbAgg) | own, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+
+    // Words [wbase, wbase + wn) of the chunk's codewords, built in the wavefront's LDS window.  A
+    // chunk starts on a word boundary, so the window's content does not depend on where the chunk
+    // lands in the stream.
+    const uint32_t nwords = (chunk_total + 31u) >> 5;
+    uint32_t *win = s_win[wave];
+    auto pack_window = [&](uint32_t wbase, uint32_t wn) {
+        for (uint32_t i = lane; i <= wn; i += 64) win[i] = 0;
+        fu_wave_sync_lds();
+        uint32_t wi = (excl >> 5) - wbase;  // window word receiving the next completed 32 bits
+        uint32_t np = excl & 31u;           // bits pending in acc (the leading np bits belong to earlier lanes)
+        uint64_t acc = 0;
+        auto append = [&](uint64_t code, uint32_t L) {  // L <= 32, np < 32
+            acc = (acc << L) | code;
+            np += L;
+            if (np >= 32u) {
+                np -= 32u;
+                if (wi < wn) atomicOr(&win[wi], (uint32_t)(acc >> np));  // unsigned: false below the window
+                ++wi;
+            }
+        };
+#pragma unroll 2
+        for (int jj = 0; jj < kSub / 4; ++jj) {
+            const uint32_t w4 = row[jj];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t s = (w4 >> (8 * q)) & 0xffu;
+                const uint32_t e = (4 * jj + q < cnt) ? fast[s] : 0u;
+                uint32_t L = e >> 24;
+                uint64_t code = e & 0x00ffffffu;
+                if (__builtin_expect(L == kFastSlow, 0)) {
+                    L = book.len[s];
+                    code = book.code[s];
+                    if (L > 32u) {
+                        append(code >> 32, L - 32u);
+                        code &= 0xffffffffull;
+                        L = 32u;
+                    }
+                }
+                if (L) append(code, L);
+            }
+        }
+        if (np && wi < wn) atomicOr(&win[wi], (uint32_t)(acc << (32u - np)));
+        fu_wave_sync_lds();
+    };
+    const bool one_window = nwords <= (uint32_t)kFuWin;  // up to 8.5 bit/element
+    if (active && one_window) pack_window(0, nwords);
+
     if (wave == 0) {
-        if (lane == 0)
-            __hip_atomic_store(&state[b], (b == 0 ? kLbPrefix : kLbAgg) | own, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
         uint64_t prefix = 0;
         int64_t pos = (int64_t)b - 1;
         bool stalled = false;
@@ -292,63 +341,29 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
     }
     __syncthreads();
     if (!active || s_stalled) return;  // whole wavefronts; no workgroup barrier below
+
+    // ---- 4. the chunk's words go to their place in the stream -----------------------------------
     const uint64_t off = s_prefix + before;
     if (lane == 0) {
         uint64_t *co = chunk_offset + (uint64_t)u * (lay.nchunks + 1);
         co[c] = off;
         if (c + 1 == lay.nchunks) co[lay.nchunks] = off + ((chunk_total + 31u) & ~31u);
     }
-
-    // ---- 4. pack chunk `wave` -------------------------------------------------------------------
-    const uint32_t nwords = (chunk_total + 31u) >> 5;
     const uint64_t off_words = off >> 5;
     if (off_words + nwords > words_stride) {
         if (lane == 0) atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CAPACITY), 1ull);
         return;
     }
     uint32_t *dst = words + (uint64_t)u * words_stride + off_words;
-    uint32_t *win = s_win[wave];
-    for (uint32_t wbase = 0; wbase < nwords; wbase += kFuWin) {
-        const uint32_t wn = nwords - wbase < (uint32_t)kFuWin ? nwords - wbase : (uint32_t)kFuWin;
-        for (uint32_t i = lane; i <= wn; i += 64) win[i] = 0;
-        fu_wave_sync_lds();
-        uint32_t wi = (excl >> 5) - wbase;  // window word receiving the next completed 32 bits
-        uint32_t np = excl & 31u;           // bits pending in acc (the leading np bits belong to earlier lanes)
-        uint64_t acc = 0;
-        auto append = [&](uint64_t code, uint32_t L) {  // L <= 32, np < 32
-            acc = (acc << L) | code;
-            np += L;
-            if (np >= 32u) {
-                np -= 32u;
-                if (wi < wn) atomicOr(&win[wi], (uint32_t)(acc >> np));  // unsigned: false below the window
-                ++wi;
-            }
-        };
-#pragma unroll 2
-        for (int jj = 0; jj < kSub / 4; ++jj) {
-            const uint32_t w4 = row[jj];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t s = (w4 >> (8 * q)) & 0xffu;
-                const uint32_t e = (4 * jj + q < cnt) ? fast[s] : 0u;
-                uint32_t L = e >> 24;
-                uint64_t code = e & 0x00ffffffu;
-                if (__builtin_expect(L == kFastSlow, 0)) {
-                    L = book.len[s];
-                    code = book.code[s];
-                    if (L > 32u) {
-                        append(code >> 32, L - 32u);
-                        code &= 0xffffffffull;
-                        L = 32u;
-                    }
-                }
-                if (L) append(code, L);
-            }
+    if (one_window) {
+        for (uint32_t i = lane; i < nwords; i += 64) __builtin_nontemporal_store(win[i], dst + i);
+    } else {
+        for (uint32_t wbase = 0; wbase < nwords; wbase += kFuWin) {
+            const uint32_t wn = nwords - wbase < (uint32_t)kFuWin ? nwords - wbase : (uint32_t)kFuWin;
+            pack_window(wbase, wn);
+            for (uint32_t i = lane; i < wn; i += 64) __builtin_nontemporal_store(win[i], dst + wbase + i);
+            fu_wave_sync_lds();
         }
-        if (np && wi < wn) atomicOr(&win[wi], (uint32_t)(acc << (32u - np)));
-        fu_wave_sync_lds();
-        for (uint32_t i = lane; i < wn; i += 64) __builtin_nontemporal_store(win[i], dst + wbase + i);
-        fu_wave_sync_lds();
     }
 }
 
