@@ -316,8 +316,12 @@ __global__ __launch_bounds__(64) void k_decode(Layout lay, const uint32_t *__res
     }
 }
 
+constexpr int kMagEntries = kMaxA / 2;  // magnitude codes of a symbol alphabet (the sign bit is on top)
+
 // One workgroup per chunk; W wavefronts decode W users at a time into LDS, then every thread
-// sums its elements over those users in ascending user order, in fp64.
+// sums its elements over those users in ascending user order, in fp64.  The value of a symbol is
+// its magnitude's entry in a per-user LDS table (every representative is an fp32) with the
+// symbol's sign bit moved to bit 31.
 template <int W>
 __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t *__restrict__ words,
                                                       uint64_t words_stride,
@@ -329,14 +333,17 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
     extern __shared__ uint64_t smem64[];
     DecLds *s_tab = reinterpret_cast<DecLds *>(smem64);   // [per-user books ? W : 1]
     const uint32_t ntab = lay.per_user_books ? W : 1;
-    DqConst *s_dq = reinterpret_cast<DqConst *>(s_tab + ntab);             // [W]
-    uint32_t *s_stage = reinterpret_cast<uint32_t *>(s_dq + W);            // [W][kStageWords]
+    uint32_t *s_mag = reinterpret_cast<uint32_t *>(s_tab + ntab);          // [W][kMagEntries] fp32 patterns
+    uint32_t *s_stage = s_mag + W * kMagEntries;                           // [W][kStageWords]
     uint32_t *s_pay = s_stage + W * kStageWords;                           // [W][kPayloadWords]
     constexpr int T = 64 * W;
     constexpr int G = (kChunk / 4) / T;  // 4-element groups per thread
     const uint32_t t = threadIdx.x, wave = t >> 6;
     const uint64_t c = blockIdx.x;
     const ChunkGeom g = chunk_geom(lay, c);
+    const uint32_t sign_shift = (uint32_t)(lay.E + lay.M);
+    const uint32_t mag_mask = (1u << sign_shift) - 1u;
+    const uint32_t sign_up = 31u - sign_shift;
 
     double acc[G][4];
 #pragma unroll
@@ -356,14 +363,17 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
         } else if (u0 == 0) {
             load_dec_tables(s_tab, books[(uint32_t)g.book], t, T);
         }
-        if (t < (uint32_t)W && u0 + t < lay.U)
-            s_dq[t] = make_dqconst(lay.E, lay.M, lay.bias[(uint64_t)(u0 + t) * lay.nseg + g.seg]);
+        for (uint32_t i = t; i < (uint32_t)(W * kMagEntries); i += T) {
+            const uint32_t uu = i / kMagEntries, k = i % kMagEntries;
+            if (u0 + uu < lay.U && k <= mag_mask)
+                s_mag[i] = symbol_value_bits(k, lay.E, lay.M, lay.bias[(uint64_t)(u0 + uu) * lay.nseg + g.seg]);
+        }
         __syncthreads();
         if (active) decode_user_chunk(g, ix, my_tab, s_pay + wave * kPayloadWords, s_stage + wave * kStageWords, status);
         __syncthreads();
         const uint32_t nu = (lay.U - u0 < (uint32_t)W) ? lay.U - u0 : (uint32_t)W;
         for (uint32_t uu = 0; uu < nu; ++uu) {
-            const DqConst dq = s_dq[uu];
+            const uint32_t *mag = s_mag + uu * kMagEntries;
             const uint32_t *st = s_stage + uu * kStageWords;
 #pragma unroll
             for (int i = 0; i < G; ++i) {
@@ -372,7 +382,8 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
                     const uint32_t s = (wv >> (8 * b)) & 0xffu;
-                    acc[i][b] += symbol_value_f64(s, dq);
+                    const uint32_t bits = mag[s & mag_mask] | ((s << sign_up) & 0x80000000u);
+                    acc[i][b] += (double)__uint_as_float(bits);
                 }
             }
         }
@@ -411,8 +422,8 @@ template <int W>
 static hipError_t launch_aggregate_w(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
                                      hipStream_t s)
 {
-    const size_t lds = (size_t)(lay.per_user_books ? W : 1) * sizeof(DecLds) + (size_t)W * sizeof(DqConst) +
-                       (size_t)W * (kStageWords + kPayloadWords) * 4;
+    const size_t lds = (size_t)(lay.per_user_books ? W : 1) * sizeof(DecLds) +
+                       (size_t)W * (kMagEntries + kStageWords + kPayloadWords) * 4;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_aggregate<W>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;

@@ -43,7 +43,7 @@ constexpr uint64_t kLbPrefix = 2ull << 62;   // size of this workgroup and all b
 constexpr uint64_t kLbStalled = 3ull << 62;
 constexpr uint64_t kLbValue = (1ull << 62) - 1;
 
-static_assert(kFuThreads == kMaxA, "one thread per code-table entry");
+static_assert(kChunk % (4 * kFuThreads) == 0, "whole vectors per thread and chunk");
 
 __device__ inline uint32_t fu_find_chunk_segment(const SegDev *segs, uint32_t nseg, uint64_t chunk)
 {
@@ -60,6 +60,16 @@ __device__ inline void fu_wave_sync_lds()
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Workgroup barrier that orders LDS accesses only: unlike __syncthreads() it does not wait for the
+// wavefront's outstanding global stores (the m' vectors just written), which nobody in the
+// workgroup reads.
+__device__ inline void fu_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
@@ -82,7 +92,7 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
     const uint32_t u = blockIdx.y;
 
     if (t == 0) s_ticket = atomicAdd(&tickets[u], 1u);
-    __syncthreads();
+    fu_lds_barrier();
     const uint32_t b = s_ticket;  // position among the user's workgroups, < nblk = gridDim.x
     const uint64_t c0 = (uint64_t)b * kFuCpb;
     const uint32_t nck = lay.nchunks - c0 < (uint64_t)kFuCpb ? (uint32_t)(lay.nchunks - c0) : (uint32_t)kFuCpb;
@@ -103,7 +113,7 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
         }
         s_e0[t] = e0; s_n[t] = n; s_book[t] = bk; s_bias[t] = bias;
     }
-    __syncthreads();
+    fu_lds_barrier();
 
     // ---- 1. quantize the chunks, symbols to LDS ------------------------------------------------
     const float *gu = g + (uint64_t)u * row_stride;
@@ -125,7 +135,8 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
         }
     }
     // the code-table entries of the chunks, one table per wavefront's chunk
-    for (uint32_t k = 0; k < nck; ++k) s_fast[k][t] = books[s_book[k]].fast[t];
+    for (uint32_t i = t; i < nck * (uint32_t)kMaxA; i += kFuThreads)
+        s_fast[i / kMaxA][i % kMaxA] = books[s_book[i / kMaxA]].fast[i % kMaxA];
 
 #pragma unroll 1
     for (uint32_t k = 0; k < nck; ++k) {
@@ -194,7 +205,7 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
         atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NONFINITE), (unsigned long long)n_nonfinite);
     if (n_clamped)
         atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CLAMPED), (unsigned long long)n_clamped);
-    __syncthreads();
+    fu_lds_barrier();
 
     // ---- 2. code lengths: wavefront = chunk, lane = sub-chunk ----------------------------------
     const bool active = wave < nck;
@@ -234,7 +245,7 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
     const uint32_t excl = incl - my_bits;
     const uint32_t chunk_total = __shfl(incl, 63, 64);
     if (lane == 0) s_cbits[wave] = chunk_total;  // 0 for a wavefront without a chunk
-    __syncthreads();
+    fu_lds_barrier();
 
     // ---- 3. publish the workgroup's size; pack while the predecessors publish theirs ----------
     uint32_t before = 0;  // 32-bit-rounded sizes of the workgroup's chunks ahead of this wavefront's
@@ -339,7 +350,7 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
             atomicAdd(reinterpret_cast<unsigned long long *>(payload_bits + u), (unsigned long long)pay);
         }
     }
-    __syncthreads();
+    fu_lds_barrier();
     if (!active || s_stalled) return;  // whole wavefronts; no workgroup barrier below
 
     // ---- 4. the chunk's words go to their place in the stream -----------------------------------

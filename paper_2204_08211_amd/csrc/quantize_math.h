@@ -89,39 +89,4 @@ __device__ inline uint32_t symbol_value_bits(uint32_t sym, int E, int M, int bia
     return bits | (s << 31);
 }
 
-// Branch-free value of a symbol as a double, for the PS-side accumulation.  A code in the
-// subnormal row (exponent field 0) is evaluated as if it had exponent field 1, i.e. with the
-// implicit leading one, and 2^(1 - bias) is subtracted again: exact in fp64.
-struct DqConst {
-    uint32_t rebase;     // (127 - bias) << mant: turns a magnitude code into fp32 exponent|mantissa bits
-    uint32_t shift;      // 23 - mant
-    uint32_t one;        // 1 << mant
-    uint32_t mag_mask;   // (1 << (exp + mant)) - 1
-    uint32_t sign_up;    // 31 - (exp + mant): moves the symbol's sign bit to bit 31
-    double sub_corr;     // 2^(1 - bias)
-};
-
-__device__ inline DqConst make_dqconst(int E, int M, int bias)
-{
-    DqConst c;
-    c.rebase = (uint32_t)(127 - bias) << M;
-    c.shift = (uint32_t)(23 - M);
-    c.one = (uint32_t)1 << M;
-    c.mag_mask = ((uint32_t)1 << (E + M)) - 1u;
-    c.sign_up = (uint32_t)(31 - (E + M));
-    c.sub_corr = __longlong_as_double((long long)(uint64_t)(1 - bias + 1023) << 52);
-    return c;
-}
-
-__device__ inline double symbol_value_f64(uint32_t sym, const DqConst &c)
-{
-    const uint32_t k = sym & c.mag_mask;
-    const bool sub = k < c.one;
-    const uint32_t kk = k + (sub ? c.one : 0u);
-    const uint32_t bits = (kk + c.rebase) << c.shift;
-    const double mag = (double)__uint_as_float(bits) - (sub ? c.sub_corr : 0.0);
-    const uint64_t sign = (uint64_t)((sym << c.sign_up) & 0x80000000u) << 32;
-    return __longlong_as_double((long long)((uint64_t)__double_as_longlong(mag) ^ sign));
-}
-
 }  // namespace co3
