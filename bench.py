@@ -2,17 +2,19 @@
 """CO3 codec benchmark on one MI355X.
 
 One "step" = one whole CO3 round for all U users: co3_encode (error correction, fp conversion,
-memory update, histogram, code table, lengths, scan, bit-pack) followed by co3_ps_aggregate
-(decode all streams, dequantize, average).  Inputs are synthetic GenNorm gradients resident in
+memory update, Huffman coding into the chunked bitstream) followed by co3_ps_aggregate (decode all
+streams, dequantize, average).  Inputs are synthetic GenNorm gradients resident in
 HBM before the timed region; the memory m is carried from step to step and the gradients rotate
 through a small pre-generated pool.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--book empirical|model]
 
---book empirical (default, the headline): every round builds its Huffman code on the device from
-that round's pooled symbol histogram.  --book model: the code is designed once, off the timed
-path, from the GenNorm model of g + gamma m and held, as the paper holds its fitted parameters
-for several epochs.  Whichever is not the headline is measured too and reported under "other_book".
+--book model (default, the headline): the paper's operating mode.  The Huffman code is designed
+once, off the timed path, from the GenNorm model of g + gamma m (Sec. IV-A (ii)) and held, as the
+paper holds its fitted parameters for several epochs; the user side is then the library's
+single-sweep encoder (symbols never reach HBM).  --book empirical: every round builds its code on
+the device from that round's pooled symbol histogram (quantize sweep, code build, coding sweep).
+Whichever is not the headline is measured too and reported under "other_book".
 """
 import argparse
 import json
@@ -28,8 +30,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the same counters
 # on a plain copy (profiles/cfg3_hbm_traffic.md); only valid for the workload they were taken on.
-MEASURED_TRAFFIC_BYTES = {("cfg3", "k_quantize"): 5586.2e6, ("cfg3", "k_pack"): 838.7e6,
-                          ("cfg3", "k_chunk_bits"): 425.4e6, ("cfg3", "k_aggregate"): 486.0e6}
+MEASURED_TRAFFIC_BYTES = {("cfg3", "k_encode_fused"): 5383.9e6, ("cfg3", "k_quantize"): 5586.6e6,
+                          ("cfg3", "k_pack"): 839.7e6, ("cfg3", "k_chunk_bits"): 425.4e6,
+                          ("cfg3", "k_aggregate"): 486.1e6}
 
 
 def parse():
@@ -38,7 +41,7 @@ def parse():
     p.add_argument("--steps", type=int, default=20)
     p.add_argument("--warmup", type=int, default=3)
     p.add_argument("--workload", default="cfg3", help="cfg1..cfg5 of BASELINE.json (default: the one the target is quoted on)")
-    p.add_argument("--book", default="empirical", choices=["empirical", "model"])
+    p.add_argument("--book", default="model", choices=["empirical", "model"])
     p.add_argument("--model-encoder", default="sweep", choices=["sweep", "three"],
                    help="encoder for --book model: the single-sweep kernel (symbols never stored) or the three-step one")
     p.add_argument("--no-cpu-baseline", action="store_true")
