@@ -12,7 +12,9 @@ The oracle cannot run a whole round of the large workloads in test time, so:
     equality, cost equal to the Huffman cost), chunk offsets are the running sum of the rounded
     sub-chunk bits, the payload is their sum.
 Where the oracle has every user's symbols (workloads 1-3) the histogram and the code tables are
-compared exactly instead.  Inputs are drawn on the device with the seeded generator and copied to
+compared exactly instead.  The round is then repeated through the single-sweep encoder (the
+configuration bench.py's headline times) with the code tables held, checked against the oracle
+in the same way, and compared with the first round everywhere.  Inputs are drawn on the device with the seeded generator and copied to
 the host for the oracle; nothing the oracle computes takes a GPU result as input.
 """
 import heapq
@@ -115,127 +117,161 @@ def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000,
     assert status[B.STAT_NOCODE] == 0 and status[B.STAT_CAPACITY] == 0 and status[B.STAT_CORRUPT] == 0
     assert status[B.STAT_NONFINITE] == 0
 
-    nch = plan.num_chunks
-    ctab = chunk_table(seg_len)
-    assert len(ctab) == nch
-    hist = buf.hist.cpu().numpy().view(np.uint64)
-    lc = [books.export(b) for b in range(plan.num_books)]
-    lens = np.stack([x[0] for x in lc]); codes = np.stack([x[1] for x in lc])
-    sub_bits = buf.sub_bits.cpu().numpy().view(np.uint16).reshape(U, nch, 64)
-    chunk_offset = buf.chunk_offset.cpu().numpy().view(np.uint64)
-    payload = buf.payload_bits.cpu().numpy().view(np.uint64)
-    sym_gpu = buf.symbols_2d()
-    bpu = max(seg_book) + 1
+    def verify(m_res, bf, out_res, first):
+        """Check one round's outputs (memory m_res, buffers bf, average out_res) against the oracle.
+        first: the three-step encoder's round, which also has symbols, a histogram and fresh code tables;
+        otherwise the single-sweep encoder's round with those tables held."""
+        label = name if first else name + " single-sweep"
+        nch = plan.num_chunks
+        ctab = chunk_table(seg_len)
+        assert len(ctab) == nch
+        hist = buf.hist.cpu().numpy().view(np.uint64)
+        lc = [books.export(b) for b in range(plan.num_books)]
+        lens = np.stack([x[0] for x in lc]); codes = np.stack([x[1] for x in lc])
+        sub_bits = bf.sub_bits.cpu().numpy().view(np.uint16).reshape(U, nch, 64)
+        chunk_offset = bf.chunk_offset.cpu().numpy().view(np.uint64)
+        payload = bf.payload_bits.cpu().numpy().view(np.uint64)
+        sym_gpu = buf.symbols_2d()
+        bpu = max(seg_book) + 1
 
-    def book_of(u, k):
-        return (u * bpu if w.per_user_books else 0) + seg_book[k]
+        def book_of(u, k):
+            return (u * bpu if w.per_user_books else 0) + seg_book[k]
 
-    # ---- properties that cover everything ------------------------------------------------
-    per_chunk = sub_bits.astype(np.uint64).sum(axis=2)
-    rounded = (per_chunk + np.uint64(31)) & ~np.uint64(31)
-    expect_off = np.concatenate([np.zeros((U, 1), np.uint64), np.cumsum(rounded, axis=1, dtype=np.uint64)], axis=1)
-    assert np.array_equal(chunk_offset, expect_off), "chunk offsets are not the running sum of the rounded sizes"
-    assert np.array_equal(payload, per_chunk.sum(axis=1, dtype=np.uint64))
-    # histogram rows = counts of the symbols the GPU wrote (torch.bincount as a library count)
-    counts = np.zeros_like(hist)
-    for u in range(U):
-        for k in range(nseg):
-            sl = slice(int(seg_off[k]), int(seg_off[k + 1]))
-            counts[book_of(u, k)] += torch.bincount(sym_gpu[u, sl].to(torch.int32), minlength=A).cpu().numpy().astype(np.uint64)
-    assert np.array_equal(hist, counts)
-    assert int(hist.sum()) == U * d
-    for b in range(plan.num_books):
-        check_code_is_optimal(hist[b], lens[b], codes[b])
-    print(f"[{name}] properties ok at {time.time() - t_start:.1f}s; payload {payload.sum() / (U * d):.4f} bit/element, "
-          f"max code length {int(lens.max())}, max offset {int(chunk_offset.max())} bits", flush=True)
+        # ---- properties that cover everything ------------------------------------------------
+        per_chunk = sub_bits.astype(np.uint64).sum(axis=2)
+        rounded = (per_chunk + np.uint64(31)) & ~np.uint64(31)
+        expect_off = np.concatenate([np.zeros((U, 1), np.uint64), np.cumsum(rounded, axis=1, dtype=np.uint64)], axis=1)
+        assert np.array_equal(chunk_offset, expect_off), "chunk offsets are not the running sum of the rounded sizes"
+        assert np.array_equal(payload, per_chunk.sum(axis=1, dtype=np.uint64))
+        # histogram rows = counts of the symbols the GPU wrote (torch.bincount as a library count)
+        if first:
+            counts = np.zeros_like(hist)
+            for u in range(U):
+                for k in range(nseg):
+                    sl = slice(int(seg_off[k]), int(seg_off[k + 1]))
+                    counts[book_of(u, k)] += torch.bincount(sym_gpu[u, sl].to(torch.int32), minlength=A).cpu().numpy().astype(np.uint64)
+            assert np.array_equal(hist, counts)
+            assert int(hist.sum()) == U * d
+            for b in range(plan.num_books):
+                check_code_is_optimal(hist[b], lens[b], codes[b])
+        print(f"[{label}] properties ok at {time.time() - t_start:.1f}s; payload {payload.sum() / (U * d):.4f} bit/element, "
+              f"max code length {int(lens.max())}, max offset {int(chunk_offset.max())} bits", flush=True)
 
-    # ---- users checked completely ----------------------------------------------------------
-    oracle_hist = np.zeros_like(hist)
-    clamped = 0
-    full_list = list(range(U)) if exact_hist else list(full_users)
-    for u in full_list:
-        gh = g[u, :d].cpu().numpy(); mh = m_in[u, :d].cpu().numpy()
-        sym_o = np.empty(d, np.uint8)
-        detailed = u in full_users
-        m_gpu = m[u, :d].cpu().numpy() if detailed else None
-        for k in range(nseg):
-            sl = slice(int(seg_off[k]), int(seg_off[k + 1]))
-            mo, so, _, cnt = orc.ef_step(gh[sl], mh[sl], w.gamma, E, M, int(bias[u, k]), want_q=False)
-            sym_o[sl] = so
-            clamped += int(cnt[1])
-            orc.histogram(so, A, oracle_hist[book_of(u, k)])
-            if detailed:
-                assert np.array_equal(mo.view(np.uint32), m_gpu[sl].view(np.uint32)), f"memory of user {u}, layer {k}"
-        if detailed:
-            assert np.array_equal(sym_o, sym_gpu[u].cpu().numpy()), f"symbols of user {u}"
-            # sub-chunk bits from the oracle's symbols and the exported lengths
+        # ---- users checked completely ----------------------------------------------------------
+        oracle_hist = np.zeros_like(hist)
+        clamped = 0
+        full_list = list(range(U)) if exact_hist and first else list(full_users)
+        for u in full_list:
+            gh = g[u, :d].cpu().numpy(); mh = m_in[u, :d].cpu().numpy()
+            sym_o = np.empty(d, np.uint8)
+            detailed = u in full_users
+            m_gpu = m_res[u, :d].cpu().numpy() if detailed else None
             for k in range(nseg):
-                lo, hi = int(seg_off[k]), int(seg_off[k + 1])
-                if hi == lo:
-                    continue
-                L = lens[book_of(u, k)][sym_o[lo:hi]].astype(np.uint32)
-                nck = (hi - lo + CHUNK - 1) // CHUNK
-                pad = np.zeros(nck * CHUNK, np.uint32); pad[:hi - lo] = L
-                c_first = sum((int(n) + CHUNK - 1) // CHUNK for n in seg_len[:k])
-                assert np.array_equal(pad.reshape(nck, 64, 64).sum(axis=2), sub_bits[u, c_first:c_first + nck]), \
-                    f"sub-chunk bits of user {u}, layer {k}"
-            if d <= full_words_limit and exact_hist:
-                pass  # the whole bitstream is compared below, once the oracle's own code is known
-        print(f"[{name}] user {u} {'checked' if detailed else 'counted'} at {time.time() - t_start:.1f}s", flush=True)
-        if detailed and d <= full_words_limit:
-            # whole bitstream of this user with the exported tables (they are checked against the
-            # oracle's own tables below when the oracle has the full histogram)
-            r = orc.pack(sym_o, seg_len, [book_of(u, k) for k in range(nseg)], lens, codes)
-            assert r["rc"] == 0
-            nw = int(r["chunk_offset"][-1]) // 32
-            assert np.array_equal(r["chunk_offset"], chunk_offset[u])
-            assert np.array_equal(r["words"][:nw], buf.words[u, :nw].cpu().numpy().view(np.uint32)), f"bitstream of user {u}"
-            assert r["payload_bits"] == int(payload[u])
-        del gh, mh, sym_o
-    if exact_hist:
-        assert np.array_equal(hist, oracle_hist), "histogram"
-        for b in range(plan.num_books):
-            lo, co = orc.codebook(oracle_hist[b])
-            assert np.array_equal(lo, lens[b]) and np.array_equal(co, codes[b]), f"code table {b}"
-        assert clamped == int(status[B.STAT_CLAMPED])
+                sl = slice(int(seg_off[k]), int(seg_off[k + 1]))
+                mo, so, _, cnt = orc.ef_step(gh[sl], mh[sl], w.gamma, E, M, int(bias[u, k]), want_q=False)
+                sym_o[sl] = so
+                clamped += int(cnt[1])
+                orc.histogram(so, A, oracle_hist[book_of(u, k)])
+                if detailed:
+                    assert np.array_equal(mo.view(np.uint32), m_gpu[sl].view(np.uint32)), f"memory of user {u}, layer {k}"
+            if detailed:
+                if first:
+                    assert np.array_equal(sym_o, sym_gpu[u].cpu().numpy()), f"symbols of user {u}"
+                # sub-chunk bits from the oracle's symbols and the exported lengths
+                for k in range(nseg):
+                    lo, hi = int(seg_off[k]), int(seg_off[k + 1])
+                    if hi == lo:
+                        continue
+                    L = lens[book_of(u, k)][sym_o[lo:hi]].astype(np.uint32)
+                    nck = (hi - lo + CHUNK - 1) // CHUNK
+                    pad = np.zeros(nck * CHUNK, np.uint32); pad[:hi - lo] = L
+                    c_first = sum((int(n) + CHUNK - 1) // CHUNK for n in seg_len[:k])
+                    assert np.array_equal(pad.reshape(nck, 64, 64).sum(axis=2), sub_bits[u, c_first:c_first + nck]), \
+                        f"sub-chunk bits of user {u}, layer {k}"
+                if d <= full_words_limit and exact_hist:
+                    pass  # the whole bitstream is compared below, once the oracle's own code is known
+            print(f"[{label}] user {u} {'checked' if detailed else 'counted'} at {time.time() - t_start:.1f}s", flush=True)
+            if detailed and d <= full_words_limit:
+                # whole bitstream of this user with the exported tables (they are checked against the
+                # oracle's own tables below when the oracle has the full histogram)
+                r = orc.pack(sym_o, seg_len, [book_of(u, k) for k in range(nseg)], lens, codes)
+                assert r["rc"] == 0
+                nw = int(r["chunk_offset"][-1]) // 32
+                assert np.array_equal(r["chunk_offset"], chunk_offset[u])
+                assert np.array_equal(r["words"][:nw], bf.words[u, :nw].cpu().numpy().view(np.uint32)), f"bitstream of user {u}"
+                assert r["payload_bits"] == int(payload[u])
+            del gh, mh, sym_o
+        if exact_hist and first:
+            assert np.array_equal(hist, oracle_hist), "histogram"
+            for b in range(plan.num_books):
+                lo, co = orc.codebook(oracle_hist[b])
+                assert np.array_equal(lo, lens[b]) and np.array_equal(co, codes[b]), f"code table {b}"
+            assert clamped == int(status[B.STAT_CLAMPED])
 
-    # ---- sampled chunks, every user ----------------------------------------------------------
-    rng = np.random.default_rng(syn.seed_for(w.cfg, 999, 0))
-    picks = {0, nch - 1}
-    for k in range(nseg):   # chunks next to layer boundaries
-        c_first = sum((int(n) + CHUNK - 1) // CHUNK for n in seg_len[:k])
-        picks.update({c_first, max(c_first - 1, 0)})
-    picks.update(int(x) for x in rng.integers(0, nch, n_random_chunks))
-    # the chunks of every user that straddle 2^32 stream bits, if any
-    for u in range(U):
-        j = int(np.searchsorted(chunk_offset[u], np.uint64(1 << 32)))
-        if 0 < j < nch:
-            picks.update({j - 1, j})
-    picks = sorted(picks)
-    for c in picks:
-        e0, n, k = ctab[c]
-        syms = np.empty((U, n), np.uint8)
+        # ---- sampled chunks, every user ----------------------------------------------------------
+        rng = np.random.default_rng(syn.seed_for(w.cfg, 999, 0))
+        picks = {0, nch - 1}
+        for k in range(nseg):   # chunks next to layer boundaries
+            c_first = sum((int(n) + CHUNK - 1) // CHUNK for n in seg_len[:k])
+            picks.update({c_first, max(c_first - 1, 0)})
+        picks.update(int(x) for x in rng.integers(0, nch, n_random_chunks))
+        # the chunks of every user that straddle 2^32 stream bits, if any
         for u in range(U):
-            gh = g[u, e0:e0 + n].cpu().numpy(); mh = m_in[u, e0:e0 + n].cpu().numpy()
-            mo, so, _, _ = orc.ef_step(gh, mh, w.gamma, E, M, int(bias[u, k]), want_q=False)
-            assert np.array_equal(mo.view(np.uint32), m[u, e0:e0 + n].cpu().numpy().view(np.uint32)), (c, u)
-            assert np.array_equal(so, sym_gpu[u, e0:e0 + n].cpu().numpy()), (c, u)
-            syms[u] = so
-            bk = book_of(u, k)
-            r = orc.pack(so, [n], [0], lens[bk][None, :], codes[bk][None, :])
-            assert r["rc"] == 0
-            nw = int(r["chunk_offset"][-1]) // 32
-            w0 = int(chunk_offset[u, c]) // 32
-            assert np.array_equal(r["words"][:nw], buf.words[u, w0:w0 + nw].cpu().numpy().view(np.uint32)), (c, u)
-            assert np.array_equal(r["sub_bits"][:64], sub_bits[u, c]), (c, u)
-            assert int(chunk_offset[u, c + 1]) - int(chunk_offset[u, c]) == nw * 32
-        avg = orc.aggregate(syms, [n], bias[:, k:k + 1], E, M)
-        got = out[e0:e0 + n].cpu().numpy()
-        vals = np.stack([np.array([orc.value(s, E, M, int(bias[u, k])) for s in range(A)])[syms[u]] for u in range(U)])
-        scale = np.maximum(np.abs(avg), np.abs(vals).mean(axis=0))
-        assert np.all(np.abs(got.astype(np.float64) - avg) <= 1e-6 * scale), f"PS average in chunk {c}"
-        assert np.array_equal(got.view(np.uint32), avg.view(np.uint32)), f"PS average (bitwise) in chunk {c}"
-    print(f"[{name}] {len(picks)} sampled chunks x {U} users ok at {time.time() - t_start:.1f}s", flush=True)
+            j = int(np.searchsorted(chunk_offset[u], np.uint64(1 << 32)))
+            if 0 < j < nch:
+                picks.update({j - 1, j})
+        picks = sorted(picks)
+        for c in picks:
+            e0, n, k = ctab[c]
+            syms = np.empty((U, n), np.uint8)
+            for u in range(U):
+                gh = g[u, e0:e0 + n].cpu().numpy(); mh = m_in[u, e0:e0 + n].cpu().numpy()
+                mo, so, _, _ = orc.ef_step(gh, mh, w.gamma, E, M, int(bias[u, k]), want_q=False)
+                assert np.array_equal(mo.view(np.uint32), m_res[u, e0:e0 + n].cpu().numpy().view(np.uint32)), (c, u)
+                if first:
+                    assert np.array_equal(so, sym_gpu[u, e0:e0 + n].cpu().numpy()), (c, u)
+                syms[u] = so
+                bk = book_of(u, k)
+                r = orc.pack(so, [n], [0], lens[bk][None, :], codes[bk][None, :])
+                assert r["rc"] == 0
+                nw = int(r["chunk_offset"][-1]) // 32
+                w0 = int(chunk_offset[u, c]) // 32
+                assert np.array_equal(r["words"][:nw], bf.words[u, w0:w0 + nw].cpu().numpy().view(np.uint32)), (c, u)
+                assert np.array_equal(r["sub_bits"][:64], sub_bits[u, c]), (c, u)
+                assert int(chunk_offset[u, c + 1]) - int(chunk_offset[u, c]) == nw * 32
+            avg = orc.aggregate(syms, [n], bias[:, k:k + 1], E, M)
+            got = out_res[e0:e0 + n].cpu().numpy()
+            vals = np.stack([np.array([orc.value(s, E, M, int(bias[u, k])) for s in range(A)])[syms[u]] for u in range(U)])
+            scale = np.maximum(np.abs(avg), np.abs(vals).mean(axis=0))
+            assert np.all(np.abs(got.astype(np.float64) - avg) <= 1e-6 * scale), f"PS average in chunk {c}"
+            assert np.array_equal(got.view(np.uint32), avg.view(np.uint32)), f"PS average (bitwise) in chunk {c}"
+        print(f"[{label}] {len(picks)} sampled chunks x {U} users ok at {time.time() - t_start:.1f}s", flush=True)
+
+    verify(m, buf, out, True)
+
+    # The same round again through the single-sweep encoder (the configuration bench.py's headline
+    # times) with the code tables held: starts from the same memory, writes to buffers of its own.
+    m2 = m_in.clone()
+    buf2 = B.RoundBuffers(plan, dev, max_code_len=16)
+    out2 = torch.zeros(d, dtype=torch.float32, device=dev)
+    buf2.chunk_offset.fill_(-1); buf2.sub_bits.fill_(-1); buf2.payload_bits.fill_(-1)
+    B.co3_encode(plan, books, g, m2, m2, w.gamma, buf2, mode=B.BOOK_FIXED, single_sweep=True)
+    B.co3_ps_aggregate(plan, books, buf2, out2)
+    torch.cuda.synchronize()
+    status2 = buf2.status.cpu().numpy()
+    assert status2[B.STAT_NOCODE] == 0 and status2[B.STAT_CAPACITY] == 0 and status2[B.STAT_CORRUPT] == 0
+    assert status2[B.STAT_STALLED] == 0 and status2[B.STAT_NONFINITE] == 0
+    assert status2[B.STAT_CLAMPED] == status[B.STAT_CLAMPED]
+    verify(m2, buf2, out2, False)
+    # and, since both encoders were just checked against the oracle where it reaches, everywhere else
+    # against each other
+    assert torch.equal(m2, m) and torch.equal(out2, out)
+    assert torch.equal(buf2.chunk_offset, buf.chunk_offset) and torch.equal(buf2.sub_bits, buf.sub_bits)
+    assert torch.equal(buf2.payload_bits, buf.payload_bits)
+    for u in range(U):
+        nw = int(buf.chunk_offset[u, -1].item()) // 32
+        assert torch.equal(buf2.words[u, :nw], buf.words[u, :nw]), f"stream of user {u}"
+    print(f"[{name}] single-sweep round identical to the three-step round at {time.time() - t_start:.1f}s", flush=True)
 
 
 def test_cfg1_full():
