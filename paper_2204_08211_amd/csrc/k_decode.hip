@@ -20,8 +20,11 @@ namespace co3 {
 
 constexpr int kStageStride = 17;                            // words per staged sub-chunk row (16 + 1 pad)
 constexpr int kStageWords = kSubsPerChunk * kStageStride;   // one chunk of one user
-constexpr int kPayloadWords = 1152;                         // LDS window for a chunk's words (9 bit/element)
+constexpr int kPayloadWords = 1088;                         // a chunk of up to 8.5 bit/element is decoded from LDS
 constexpr int kPayloadPerLane = kPayloadWords / 64;
+// Allocated words of the LDS window.  A lane starts at most at word kPayloadWords, holds two words
+// and takes at most one more per symbol, so its reads end below kPayloadWords + 2 + kSub.
+constexpr int kPayloadAlloc = kPayloadWords + 2 + kSub + 6;
 
 // Decode tables of one code in LDS.
 struct DecLds {
@@ -72,18 +75,22 @@ __device__ inline uint32_t wave_exclusive_scan_u32(uint32_t x)
 
 // Word sources of the decoder: index 0 is the chunk's first word.  A well-formed stream never
 // consumes bits beyond its chunk; what a read beyond the end returns only has to be harmless.
+// word(i): any i.  next(i): the reader's sequential fetch, i below seek_limit + 2 + kSub.
 struct LdsWords {
-    const uint32_t *base;   // kPayloadWords allocated words; the chunk's words in front
-    // clamped to the window: one instruction, always inside the allocation
+    const uint32_t *base;   // kPayloadAlloc allocated words; the chunk's words in front
+    static constexpr uint32_t seek_limit = kPayloadWords;
     __device__ inline uint32_t word(uint32_t i) const
     {
-        return base[i < (uint32_t)(kPayloadWords - 1) ? i : (uint32_t)(kPayloadWords - 1)];
+        return base[i < (uint32_t)(kPayloadAlloc - 1) ? i : (uint32_t)(kPayloadAlloc - 1)];
     }
+    __device__ inline uint32_t next(uint32_t i) const { return base[i]; }
 };
 struct GlobalWords {
     const uint32_t *base;   // chunk's first word in the user's stream
     uint64_t n;             // words of the chunk
+    static constexpr uint32_t seek_limit = 0xffffff00u;
     __device__ inline uint32_t word(uint32_t i) const { return i < n ? base[i] : 0u; }
+    __device__ inline uint32_t next(uint32_t i) const { return word(i); }
 };
 
 // (length << 8) | symbol of the code longer than kDecBits that starts at bit `pos` of the chunk,
@@ -106,59 +113,63 @@ __device__ __noinline__ uint32_t long_code(Src src, const DecLds *T, uint32_t po
     return 0u;
 }
 
-// Sequential bit reader of one lane: `window` holds the next bits left-aligned, of which `avail`
-// are valid; invariant before every table lookup: avail >= 32.
+// Sequential bit reader of one lane: the word that holds the next bit, the word after it, and the
+// bit's offset in the first.  Consuming at most 32 bits moves on by at most one word.
 template <class Src>
 struct Reader {
     Src src;
-    uint64_t window;
-    uint32_t avail, wi;
+    uint32_t w0, w1;   // word with the next bit, following word
+    uint32_t sh;       // offset of the next bit in w0, 0..31
+    uint32_t wi;       // index of the word after w1
     __device__ inline void seek(uint32_t pos)
     {
-        wi = pos >> 5;
-        const uint32_t sh = pos & 31u;
-        window = (((uint64_t)src.word(wi) << 32) | src.word(wi + 1)) << sh;
-        avail = 64u - sh;
-        wi += 2;
+        uint32_t i = pos >> 5;
+        i = i < Src::seek_limit ? i : Src::seek_limit;
+        w0 = src.word(i);
+        w1 = src.word(i + 1);
+        wi = i + 2;
+        sh = pos & 31u;
     }
+    __device__ inline uint32_t pos() const { return (wi - 2u) * 32u + sh; }
+    // the next bits left-aligned: at least 33 are valid, zeros follow
+    __device__ inline uint64_t window() const { return (((uint64_t)w0 << 32) | w1) << sh; }
 };
 
-// One symbol.  Returns it; `consumed` advances by its length; `bad` is set if nothing matched.
-// A code longer than the direct table is found by comparing the window with the left-aligned
-// last code of every longer length that occurs (they grow with the length).  The window holds at
-// least 32 valid bits, which decides lengths up to 32; longer ones take the exact path.
+// One symbol; `bad` is set if nothing matched.  A code longer than the direct table is found by
+// comparing the window with the left-aligned last code of every longer length that occurs (they
+// grow with the length).  The window's valid bits decide lengths up to 32; longer ones take the
+// exact path, which repositions the reader itself.
 template <class Src>
-__device__ inline uint32_t decode_symbol(Reader<Src> &r, const DecLds *T, uint32_t p0, uint32_t &consumed, bool &bad)
+__device__ inline uint32_t decode_symbol(Reader<Src> &r, const DecLds *T, bool &bad)
 {
-    uint32_t nextw = r.src.word(r.wi);                       // both LDS reads are requested
-    uint32_t e = T->dec[r.window >> (64 - kDecBits)];        // before either result is needed
+    const uint64_t win = r.window();
+    uint32_t nextw = r.src.next(r.wi);                       // both LDS reads are requested
+    uint32_t e = T->dec[win >> (64 - kDecBits)];             // before either result is needed
     asm volatile("" : "+v"(nextw), "+v"(e));
     uint32_t L = e >> 8, s = e & 0xffu;
     if (__builtin_expect(L == 0u, 0)) {
         const uint32_t n = T->nlong;
         uint32_t k = 0;
-        while (k < n && r.window > T->long_last[k]) ++k;
+        while (k < n && win > T->long_last[k]) ++k;
         if (k < n) {
             L = T->long_len[k];
-            if (L <= 32u) s = T->sorted[((uint32_t)(r.window >> (64u - L)) + T->long_base[k]) & (kMaxA - 1)];
+            if (L <= 32u) s = T->sorted[((uint32_t)(win >> (64u - L)) + T->long_base[k]) & (kMaxA - 1)];
         }
         if (__builtin_expect(L == 0u || L > 32u, 0)) {
-            const uint32_t code = long_code(r.src, T, p0 + consumed);  // exact 64-bit window
-            L = code >> 8;
+            const uint32_t pos = r.pos();
+            const uint32_t code = long_code(r.src, T, pos);  // exact 64-bit window
+            uint32_t len = code >> 8;
             s = code & 0xffu;
-            if (L == 0u) { bad = true; L = 1u; }
-            consumed += L;
-            r.seek(p0 + consumed);
-            return s;
+            if (len == 0u) { bad = true; len = 1u; }
+            r.seek(pos + len);
+            L = 0u;                                          // the reader stands behind the code already
         }
     }
-    r.window <<= L;
-    r.avail -= L;
-    consumed += L;
-    const bool take = r.avail < 32u;
-    const uint64_t add = (uint64_t)nextw << ((32u - r.avail) & 63u);
-    r.window |= take ? add : 0ull;
-    r.avail += take ? 32u : 0u;
+    const uint32_t t = r.sh + L;
+    const bool take = t >= 32u;
+    r.sh = t & 31u;
+    r.w0 = take ? r.w1 : r.w0;
+    r.w1 = take ? nextw : r.w1;
     r.wi += take ? 1u : 0u;
     return s;
 }
@@ -172,24 +183,23 @@ __device__ inline uint32_t decode_subchunk(Src src, uint32_t p0, int cnt, const 
     Reader<Src> r;
     r.src = src;
     r.seek(p0);
-    uint32_t consumed = 0;
     bool bad = false;
     if (cnt == kSub) {
         for (int jj = 0; jj < kSub / 4; ++jj) {
             uint32_t packed = 0;
 #pragma unroll
-            for (int b = 0; b < 4; ++b) packed |= decode_symbol(r, T, p0, consumed, bad) << (8 * b);
+            for (int b = 0; b < 4; ++b) packed |= decode_symbol(r, T, bad) << (8 * b);
             stage_row[jj] = packed;
         }
     } else {
         uint32_t packed = 0;
         for (int j = 0; j < cnt; ++j) {
-            packed |= decode_symbol(r, T, p0, consumed, bad) << (8 * (j & 3));
+            packed |= decode_symbol(r, T, bad) << (8 * (j & 3));
             if ((j & 3) == 3) { stage_row[j >> 2] = packed; packed = 0; }
         }
         if (cnt & 3) stage_row[cnt >> 2] = packed;
     }
-    return bad ? ~0u : consumed;
+    return bad ? ~0u : r.pos() - p0;
 }
 
 struct ChunkGeom {
@@ -281,7 +291,7 @@ __global__ __launch_bounds__(64) void k_decode(Layout lay, const uint32_t *__res
 {
     __shared__ DecLds s_tab;
     __shared__ uint32_t s_stage[kStageWords];
-    __shared__ uint32_t s_pay[kPayloadWords];
+    __shared__ uint32_t s_pay[kPayloadAlloc];
     const uint32_t lane = threadIdx.x;
     const uint64_t c = blockIdx.x;
     const uint32_t u = blockIdx.y;
@@ -335,7 +345,7 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
     const uint32_t ntab = lay.per_user_books ? W : 1;
     uint32_t *s_mag = reinterpret_cast<uint32_t *>(s_tab + ntab);          // [W][kMagEntries] fp32 patterns
     uint32_t *s_stage = s_mag + W * kMagEntries;                           // [W][kStageWords]
-    uint32_t *s_pay = s_stage + W * kStageWords;                           // [W][kPayloadWords]
+    uint32_t *s_pay = s_stage + W * kStageWords;                           // [W][kPayloadAlloc]
     constexpr int T = 64 * W;
     constexpr int G = (kChunk / 4) / T;  // 4-element groups per thread
     const uint32_t t = threadIdx.x, wave = t >> 6;
@@ -369,7 +379,7 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
                 s_mag[i] = symbol_value_bits(k, lay.E, lay.M, lay.bias[(uint64_t)(u0 + uu) * lay.nseg + g.seg]);
         }
         __syncthreads();
-        if (active) decode_user_chunk(g, ix, my_tab, s_pay + wave * kPayloadWords, s_stage + wave * kStageWords, status);
+        if (active) decode_user_chunk(g, ix, my_tab, s_pay + wave * kPayloadAlloc, s_stage + wave * kStageWords, status);
         __syncthreads();
         const uint32_t nu = (lay.U - u0 < (uint32_t)W) ? lay.U - u0 : (uint32_t)W;
         for (uint32_t uu = 0; uu < nu; ++uu) {
@@ -423,7 +433,7 @@ static hipError_t launch_aggregate_w(const Layout &lay, const co3_aggregate_args
                                      hipStream_t s)
 {
     const size_t lds = (size_t)(lay.per_user_books ? W : 1) * sizeof(DecLds) +
-                       (size_t)W * (kMagEntries + kStageWords + kPayloadWords) * 4;
+                       (size_t)W * (kMagEntries + kStageWords + kPayloadAlloc) * 4;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_aggregate<W>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
