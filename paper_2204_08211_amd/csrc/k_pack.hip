@@ -26,6 +26,7 @@ constexpr int kRowWords = 17;                       // 16 words of symbols + 1 p
 constexpr int kStageWords = kSubsPerChunk * kRowWords;  // 1088 words hold a chunk's symbols
 constexpr int kWinWords = 1088;                     // LDS window of the output: 8.5 bit/element per pass
 constexpr int kSymLoads = (kChunk / 4 + 1 + 63) / 64;  // dword loads per lane to stage a chunk (17)
+constexpr uint32_t kPlainFlag = 1u << 31;              // in chunk_bits: full chunk, every code at most kFastLen bits
 
 __device__ inline uint32_t find_chunk_segment(const SegDev *segs, uint32_t nseg, uint64_t chunk)
 {
@@ -104,9 +105,11 @@ __global__ __launch_bounds__(kPkThreads) void k_pack_wave(
     }
     uint32_t my_bits = 0;
     uint64_t off = 0;
+    bool all_plain = false;
     if (kPack) {
         my_bits = sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane];
         off = chunk_offset[(uint64_t)u * (lay.nchunks + 1) + c];
+        all_plain = (chunk_bits[(uint64_t)u * lay.nchunks + c] & kPlainFlag) != 0u;
     }
 #pragma unroll
     for (int k = 0; k < kMaxA / 64; ++k) s_fast[lane + 64 * k] = tab[k];
@@ -121,28 +124,54 @@ __global__ __launch_bounds__(kPkThreads) void k_pack_wave(
 
     if (!kPack) {
         wave_sync_lds();
-        uint32_t total = 0, nocode = 0;
-        uint32_t cur = row[0];
+        uint32_t total = 0;
+        // A full chunk whose symbols all have codes of at most kFastLen bits needs no per-symbol
+        // checks; bit 31 of chunk_bits tells the pack step so.
+        bool plain = false;
+        if (n == (uint32_t)kChunk) {
+            uint32_t lo = 0xffu, hi = 0u;
+            uint32_t cur = row[0];
 #pragma unroll 4
-        for (int jj = 0; jj < kSub / 4; ++jj) {
-            const uint32_t nxt = row[jj + 1 + (jj == kSub / 4 - 1 ? 1 : 0)];
-            const uint32_t w4 = (uint32_t)((((uint64_t)nxt << 32) | cur) >> (8 * shift));
-            cur = nxt;
+            for (int jj = 0; jj < kSub / 4; ++jj) {
+                const uint32_t nxt = row[jj + 1 + (jj == kSub / 4 - 1 ? 1 : 0)];
+                const uint32_t w4 = (uint32_t)((((uint64_t)nxt << 32) | cur) >> (8 * shift));
+                cur = nxt;
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const uint32_t s = (w4 >> (8 * b)) & 0xffu;
-                const bool in = 4 * jj + b < cnt;
-                uint32_t L = in ? (s_fast[s] >> 24) : 0u;
-                if (__builtin_expect(L == kFastSlow, 0)) L = book.len[s];
-                nocode += (in && L == 0u) ? 1u : 0u;
-                total += L;
+                for (int b = 0; b < 4; ++b) {
+                    const uint32_t L = s_fast[(w4 >> (8 * b)) & 0xffu] >> 24;
+                    total += L;
+                    lo = lo < L ? lo : L;
+                    hi = hi > L ? hi : L;
+                }
             }
+            plain = lo > 0u && hi < kFastSlow;
+        }
+        if (!plain) {
+            uint32_t nocode = 0;
+            total = 0;
+            uint32_t cur = row[0];
+#pragma unroll 4
+            for (int jj = 0; jj < kSub / 4; ++jj) {
+                const uint32_t nxt = row[jj + 1 + (jj == kSub / 4 - 1 ? 1 : 0)];
+                const uint32_t w4 = (uint32_t)((((uint64_t)nxt << 32) | cur) >> (8 * shift));
+                cur = nxt;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const uint32_t s = (w4 >> (8 * b)) & 0xffu;
+                    const bool in = 4 * jj + b < cnt;
+                    uint32_t L = in ? (s_fast[s] >> 24) : 0u;
+                    if (__builtin_expect(L == kFastSlow, 0)) L = book.len[s];
+                    nocode += (in && L == 0u) ? 1u : 0u;
+                    total += L;
+                }
+            }
+            if (nocode)
+                atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NOCODE), (unsigned long long)nocode);
         }
         sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane] = (uint16_t)total;
         const uint32_t chunk_total = wave_sum(total);
-        if (lane == 0) chunk_bits[(uint64_t)u * lay.nchunks + c] = chunk_total;
-        if (nocode)
-            atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NOCODE), (unsigned long long)nocode);
+        const bool all_plain = !__any(!plain);
+        if (lane == 0) chunk_bits[(uint64_t)u * lay.nchunks + c] = chunk_total | (all_plain ? kPlainFlag : 0u);
         return;
     } else {
         const uint32_t incl = wave_inclusive_scan(my_bits);
@@ -175,27 +204,41 @@ __global__ __launch_bounds__(kPkThreads) void k_pack_wave(
                 }
             };
             uint32_t cur = row[0];
+            if (all_plain) {
 #pragma unroll 2
-            for (int jj = 0; jj < kSub / 4; ++jj) {
-                const uint32_t nxt = row[jj + 1 + (jj == kSub / 4 - 1 ? 1 : 0)];
-                const uint32_t w4 = (uint32_t)((((uint64_t)nxt << 32) | cur) >> (8 * shift));
-                cur = nxt;
+                for (int jj = 0; jj < kSub / 4; ++jj) {
+                    const uint32_t nxt = row[jj + 1 + (jj == kSub / 4 - 1 ? 1 : 0)];
+                    const uint32_t w4 = (uint32_t)((((uint64_t)nxt << 32) | cur) >> (8 * shift));
+                    cur = nxt;
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const uint32_t s = (w4 >> (8 * b)) & 0xffu;
-                    const uint32_t e = (4 * jj + b < cnt) ? s_fast[s] : 0u;
-                    uint32_t L = e >> 24;
-                    uint64_t code = e & 0x00ffffffu;
-                    if (__builtin_expect(L == kFastSlow, 0)) {
-                        L = book.len[s];
-                        code = book.code[s];
-                        if (L > 32u) {
-                            append(code >> 32, L - 32u);
-                            code &= 0xffffffffull;
-                            L = 32u;
-                        }
+                    for (int b = 0; b < 4; ++b) {
+                        const uint32_t e = s_fast[(w4 >> (8 * b)) & 0xffu];
+                        append(e & 0x00ffffffu, e >> 24);
                     }
-                    if (L) append(code, L);
+                }
+            } else {
+#pragma unroll 2
+                for (int jj = 0; jj < kSub / 4; ++jj) {
+                    const uint32_t nxt = row[jj + 1 + (jj == kSub / 4 - 1 ? 1 : 0)];
+                    const uint32_t w4 = (uint32_t)((((uint64_t)nxt << 32) | cur) >> (8 * shift));
+                    cur = nxt;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const uint32_t s = (w4 >> (8 * b)) & 0xffu;
+                        const uint32_t e = (4 * jj + b < cnt) ? s_fast[s] : 0u;
+                        uint32_t L = e >> 24;
+                        uint64_t code = e & 0x00ffffffu;
+                        if (__builtin_expect(L == kFastSlow, 0)) {
+                            L = book.len[s];
+                            code = book.code[s];
+                            if (L > 32u) {
+                                append(code >> 32, L - 32u);
+                                code &= 0xffffffffull;
+                                L = 32u;
+                            }
+                        }
+                        if (L) append(code, L);
+                    }
                 }
             }
             if (np && wi < wn) atomicOr(&s_win[wi], (uint32_t)(acc << (32u - np)));
@@ -220,7 +263,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_chunks(uint64_t nchunks, 
     uint64_t running = 0, payload = 0;
     for (uint64_t base = 0; base < nchunks; base += kScanThreads) {
         const uint64_t i = base + t;
-        const uint32_t b = (i < nchunks) ? cb[i] : 0u;
+        const uint32_t b = (i < nchunks) ? (cb[i] & ~kPlainFlag) : 0u;
         const uint32_t a = (b + 31u) & ~31u;
         const uint32_t incl_w = wave_inclusive_scan(a);
         const uint32_t pay = wave_sum(b);
