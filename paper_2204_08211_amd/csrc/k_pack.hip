@@ -205,16 +205,25 @@ __global__ __launch_bounds__(kPkThreads) void k_pack_wave(
             };
             uint32_t cur = row[0];
             if (all_plain) {
-#pragma unroll 2
-                for (int jj = 0; jj < kSub / 4; ++jj) {
+                // the table entries of the next four symbols are requested before the current four
+                // are appended: the appends' LDS atomics keep later look-ups behind them
+                uint32_t en[4];
+                auto lookup4 = [&](int jj) {
                     const uint32_t nxt = row[jj + 1 + (jj == kSub / 4 - 1 ? 1 : 0)];
                     const uint32_t w4 = (uint32_t)((((uint64_t)nxt << 32) | cur) >> (8 * shift));
                     cur = nxt;
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const uint32_t e = s_fast[(w4 >> (8 * b)) & 0xffu];
-                        append(e & 0x00ffffffu, e >> 24);
-                    }
+                    for (int b = 0; b < 4; ++b) en[b] = s_fast[(w4 >> (8 * b)) & 0xffu];
+                };
+                lookup4(0);
+#pragma unroll 2
+                for (int jj = 0; jj < kSub / 4; ++jj) {
+                    uint32_t e[4];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) e[b] = en[b];
+                    if (jj + 1 < kSub / 4) lookup4(jj + 1);
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) append(e[b] & 0x00ffffffu, e[b] >> 24);
                 }
             } else {
 #pragma unroll 2
