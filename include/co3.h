@@ -135,6 +135,28 @@ void co3_codebook_destroy(co3_codebook *books);
 int co3_gennorm_weights(co3_format format, int32_t bias, double mu, double alpha, double beta,
                         uint64_t *weights);
 
+/* ---- the GenNorm model from the data (Sec. III eq. (kurtosis); Sec. IV-A (ii); Sec. VI) -----
+ * co3_gennorm_fit: for every user and layer, the GenNorm(mu, alpha, beta) whose mean, variance
+ * and kurtosis (eq. (kurtosis)) equal those of the sample v = g + gamma m: one read sweep over g
+ * and m (fp64 sums of v, v^2, v^3, v^4 in a fixed order), then beta from the kurtosis by bisection
+ * on [0.1, 64] (clamped) and alpha from the variance.  params is device memory [U][nseg]; an empty
+ * or constant layer (variance below 2^-40 of the mean square) gets alpha = beta = 0.  workspace: device, co3_plan_fit_workspace_bytes().
+ * The paper fits once and holds the parameters for several epochs; so does a caller of this.
+ * co3_model_weights_device: integer Huffman weights (device, [num_books][A]) of the model code
+ * for those parameters: a table's source is the mixture of the quantized models of the (user,
+ * layer) pairs it serves, weighted by their element counts; every symbol Q_fp can produce gets
+ * max(1, floor(p * 2^40)), the others 0.  Feed them to co3_build_codebook_device.             */
+typedef struct {
+    double mu, alpha, beta;
+    double kurtosis;         /* the sample's m4 / m2^2                                        */
+} co3_gennorm_params;
+size_t co3_plan_fit_workspace_bytes(const co3_plan *plan);
+int co3_gennorm_fit(const co3_plan *plan, const float *g, const float *m, uint64_t row_stride,
+                    float gamma, co3_gennorm_params *params, void *workspace,
+                    size_t workspace_bytes, void *stream);
+int co3_model_weights_device(const co3_plan *plan, const co3_gennorm_params *params,
+                             uint64_t *weights, void *stream);
+
 /* ---- user side: Algorithm 1 lines 8-10 for all U users -----------------------------------
  * v = g + gamma m (eq. (f_error_fb)), ghat = Q_fp(v), m' = v - ghat, b = h_Hf(ghat).
  * mode CO3_BOOK_FIXED encodes with `books` as they are (a code designed beforehand, e.g. from

@@ -25,12 +25,17 @@ EXPORTS = [
     "co3_plan_alphabet", "co3_plan_symbols_bytes", "co3_plan_workspace_bytes", "co3_plan_stream_words",
     "co3_build_codebook", "co3_build_codebook_device", "co3_codebook_export", "co3_codebook_num_books",
     "co3_codebook_destroy", "co3_encode", "co3_decode", "co3_ps_aggregate", "co3_status_string",
-    "co3_profile_begin", "co3_profile_end", "co3_gennorm_weights",
+    "co3_profile_begin", "co3_profile_end", "co3_gennorm_weights", "co3_plan_fit_workspace_bytes", "co3_gennorm_fit",
+    "co3_model_weights_device",
 ]
 
 
 class Format(C.Structure):
     _fields_ = [("exp_bits", C.c_int32), ("mant_bits", C.c_int32)]
+
+
+class GennormParams(C.Structure):
+    _fields_ = [("mu", C.c_double), ("alpha", C.c_double), ("beta", C.c_double), ("kurtosis", C.c_double)]
 
 
 class Segment(C.Structure):
@@ -83,7 +88,7 @@ def lib():
         L.co3_plan_destroy.restype = None
         for name, rt in [("co3_plan_num_chunks", C.c_uint64), ("co3_plan_num_books", C.c_uint32),
                          ("co3_plan_alphabet", C.c_uint32), ("co3_plan_symbols_bytes", C.c_size_t),
-                         ("co3_plan_workspace_bytes", C.c_size_t)]:
+                         ("co3_plan_workspace_bytes", C.c_size_t), ("co3_plan_fit_workspace_bytes", C.c_size_t)]:
             getattr(L, name).argtypes = [C.c_void_p]
             getattr(L, name).restype = rt
         L.co3_plan_stream_words.argtypes = [C.c_void_p, C.c_uint32]
@@ -100,6 +105,9 @@ def lib():
         L.co3_ps_aggregate.argtypes = [C.c_void_p, C.POINTER(AggregateArgs), C.c_void_p]
         L.co3_profile_end.argtypes = [C.POINTER(KernelTime), C.c_uint32, C.POINTER(C.c_uint32)]
         L.co3_gennorm_weights.argtypes = [Format, C.c_int32, C.c_double, C.c_double, C.c_double, C.c_void_p]
+        L.co3_gennorm_fit.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_float, C.c_void_p, C.c_void_p,
+                                      C.c_size_t, C.c_void_p]
+        L.co3_model_weights_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.co3_status_string.argtypes = [C.c_int]
         L.co3_status_string.restype = C.c_char_p
         _lib = L
@@ -234,6 +242,33 @@ def co3_build_codebook_device(books, weights, status, stream=None):
     """Rebuild the set from device weights (uint64 viewed as an int64 tensor [nbooks][A])."""
     _check("co3_build_codebook_device",
            lib().co3_build_codebook_device(books.handle, _ptr(weights), _ptr(status), _stream(stream)))
+
+
+def co3_gennorm_fit(plan, g, m, gamma, params=None, workspace=None, stream=None):
+    """GenNorm(mu, alpha, beta) of v = g + gamma m per user and layer by matching mean, variance and
+    kurtosis (Sec. III eq. (kurtosis)).  Returns a float64 device tensor [U][nseg][4] = (mu, alpha, beta,
+    kurtosis); g, m are float32 device tensors [U][row_stride]."""
+    import torch
+    assert g.dim() == 2 and g.shape == m.shape and g.stride(1) == 1 and g.stride(0) == m.stride(0)
+    if params is None:
+        params = torch.zeros((plan.U, plan.nseg, 4), dtype=torch.float64, device=g.device)
+    if workspace is None:
+        workspace = torch.empty(int(lib().co3_plan_fit_workspace_bytes(plan.handle)), dtype=torch.uint8, device=g.device)
+    _check("co3_gennorm_fit", lib().co3_gennorm_fit(plan.handle, g.data_ptr(), m.data_ptr(), g.stride(0),
+                                                      float(np.float32(gamma)), params.data_ptr(), workspace.data_ptr(),
+                                                      workspace.numel(), _stream(stream)))
+    return params
+
+
+def co3_model_weights_device(plan, params, weights=None, stream=None):
+    """Integer weights [num_books][A] (uint64 viewed as an int64 device tensor) of the model code for fitted
+    parameters; feed them to co3_build_codebook_device."""
+    import torch
+    if weights is None:
+        weights = torch.zeros((plan.num_books, plan.A), dtype=torch.int64, device=params.device)
+    _check("co3_model_weights_device",
+           lib().co3_model_weights_device(plan.handle, params.data_ptr(), weights.data_ptr(), _stream(stream)))
+    return weights
 
 
 class RoundBuffers:

@@ -271,6 +271,32 @@ int co3_encode(const co3_plan *plan, const co3_encode_args *a, void *stream)
     return CO3_OK;
 }
 
+size_t co3_plan_fit_workspace_bytes(const co3_plan *plan) { return plan ? fit_workspace_bytes(plan->lay) : 0; }
+
+int co3_gennorm_fit(const co3_plan *plan, const float *g, const float *m, uint64_t row_stride, float gamma,
+                    co3_gennorm_params *params, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!plan || !g || !m || !params || !workspace) return CO3_ERR_ARG;
+    const Layout &lay = plan->lay;
+    if (!aligned16(g) || !aligned16(m) || (row_stride & 3u) || row_stride < lay.d) return CO3_ERR_ARG;
+    if (!(gamma == gamma)) return CO3_ERR_ARG;
+    if (workspace_bytes < fit_workspace_bytes(lay)) return CO3_ERR_CAPACITY;
+    DeviceGuard guard(plan->device);
+    double *partial = reinterpret_cast<double *>((reinterpret_cast<uintptr_t>(workspace) + 255u) & ~(uintptr_t)255u);
+    return launch_fit(lay, g, m, row_stride, gamma, params, partial, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? CO3_OK
+               : CO3_ERR_HIP;
+}
+
+int co3_model_weights_device(const co3_plan *plan, const co3_gennorm_params *params, uint64_t *weights, void *stream)
+{
+    if (!plan || !params || !weights) return CO3_ERR_ARG;
+    DeviceGuard guard(plan->device);
+    return launch_model_weights(plan->lay, params, weights, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? CO3_OK
+               : CO3_ERR_HIP;
+}
+
 int co3_decode(const co3_plan *plan, const co3_decode_args *a, void *stream)
 {
     if (!plan || !a) return CO3_ERR_ARG;

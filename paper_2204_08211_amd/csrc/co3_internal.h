@@ -87,7 +87,7 @@ namespace co3 {
 
 // Per-kernel event timing (profile.cpp).  A ProfScope around a launch records two events on
 // the stream when profiling is on, and does nothing otherwise.
-enum KernelId { K_ZERO = 0, K_QUANTIZE, K_REDUCE_HIST, K_BUILD_BOOKS, K_CHUNK_BITS, K_SCAN, K_PACK, K_DECODE, K_AGGREGATE, K_FUSED, K_COUNT };
+enum KernelId { K_ZERO = 0, K_QUANTIZE, K_REDUCE_HIST, K_BUILD_BOOKS, K_CHUNK_BITS, K_SCAN, K_PACK, K_DECODE, K_AGGREGATE, K_FUSED, K_MOMENTS, K_FIT, K_MODEL_WEIGHTS, K_COUNT };
 bool profile_enabled();
 class ProfScope {
 public:
@@ -117,6 +117,12 @@ hipError_t launch_pack(const Layout &lay, const co3_encode_args &a, const BookDe
 // single-sweep encoder for a fixed code (k_fused.hip); its workspace need in bytes
 hipError_t launch_encode_fused(const Layout &lay, const co3_encode_args &a, const BookDev *books, hipStream_t s);
 size_t fused_workspace_bytes(const Layout &lay);
+// GenNorm fit and model weights (k_fit.hip); partial: fit_workspace_bytes() of device memory
+size_t fit_workspace_bytes(const Layout &lay);
+hipError_t launch_fit(const Layout &lay, const float *g, const float *m, uint64_t row_stride, float gamma,
+                      co3_gennorm_params *params, double *partial, hipStream_t s);
+hipError_t launch_model_weights(const Layout &lay, const co3_gennorm_params *params, uint64_t *weights,
+                                hipStream_t s);
 hipError_t launch_decode(const Layout &lay, const co3_decode_args &a, const BookDev *books, hipStream_t s);
 hipError_t launch_aggregate(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
                             hipStream_t s);

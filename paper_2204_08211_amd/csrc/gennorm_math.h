@@ -1,0 +1,131 @@
+// GenNorm model arithmetic shared by the host helper and the device kernels of the library
+// (Sec. III of the paper: eq. (gennorm) for the density, eq. (kurtosis) for variance and
+// kurtosis; Sec. IV-A (ii): the Huffman code is designed under the GenNorm assumption).
+//
+//   f(x) = beta / (2 alpha Gamma(1/beta)) exp(-(|x - mu| / alpha)^beta)
+//   F(x) = 1/2 + 1/2 sgn(x - mu) P(1/beta, (|x - mu| / alpha)^beta),  P the regularised lower
+//          incomplete gamma function
+//   Var  = alpha^2 Gamma(3/beta) / Gamma(1/beta),  Kurt = Gamma(5/beta) Gamma(1/beta) / Gamma(3/beta)^2
+//
+// The cell of a representative of Q_fp is the set of inputs mapped to it: bounded by the
+// midpoints to its neighbours, the outermost cells reaching to infinity.
+#pragma once
+
+#include <math.h>
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define CO3_HD __host__ __device__
+#else
+#define CO3_HD
+#endif
+
+namespace co3 {
+
+constexpr double kBetaMin = 0.1;    // range the moment fit searches; the kurtosis falls from
+constexpr double kBetaMax = 64.0;   // about 3.3e4 to 1.8 (the uniform limit) over it
+
+// Regularised incomplete gamma functions P(a, x) and Q(a, x) = 1 - P(a, x): power series for
+// x < a + 1, continued fraction (modified Lentz) otherwise.
+CO3_HD inline void inc_gamma(double a, double x, double *P, double *Q)
+{
+    if (x <= 0.0) { *P = 0.0; *Q = 1.0; return; }
+    if (isinf(x)) { *P = 1.0; *Q = 0.0; return; }
+    const double lead = exp(a * log(x) - x - lgamma(a));
+    if (x < a + 1.0) {
+        double term = 1.0 / a, sum = term, ap = a;
+        for (int n = 0; n < 2000; ++n) {
+            ap += 1.0;
+            term *= x / ap;
+            sum += term;
+            if (fabs(term) < fabs(sum) * 1e-17) break;
+        }
+        *P = sum * lead;
+        *Q = 1.0 - *P;
+    } else {
+        const double tiny = 1e-300;
+        double b = x + 1.0 - a, c = 1.0 / tiny, d = 1.0 / b, h = d;
+        for (int i = 1; i < 2000; ++i) {
+            const double an = -(double)i * ((double)i - a);
+            b += 2.0;
+            d = an * d + b;
+            if (fabs(d) < tiny) d = tiny;
+            c = b + an / c;
+            if (fabs(c) < tiny) c = tiny;
+            d = 1.0 / d;
+            const double del = d * c;
+            h *= del;
+            if (fabs(del - 1.0) < 1e-16) break;
+        }
+        *Q = lead * h;
+        *P = 1.0 - *Q;
+    }
+}
+
+// F(x) and 1 - F(x), each without cancellation; x may be +-infinity
+CO3_HD inline void gennorm_cdf(double x, double mu, double alpha, double beta, double *F, double *S)
+{
+    double P, Q;
+    inc_gamma(1.0 / beta, pow(fabs(x - mu) / alpha, beta), &P, &Q);
+    if (x >= mu) { *F = 0.5 + 0.5 * P; *S = 0.5 * Q; }
+    else { *F = 0.5 * Q; *S = 0.5 + 0.5 * P; }
+}
+
+// Probability of (lo, hi], taken on the tail that keeps precision.
+CO3_HD inline double gennorm_mass(double lo, double hi, double mu, double alpha, double beta)
+{
+    double Flo, Slo, Fhi, Shi;
+    gennorm_cdf(lo, mu, alpha, beta, &Flo, &Slo);
+    gennorm_cdf(hi, mu, alpha, beta, &Fhi, &Shi);
+    double p;
+    if (Fhi <= 0.5) p = Fhi - Flo;
+    else if (Slo <= 0.5) p = Slo - Shi;
+    else p = Fhi - Flo;
+    return p < 0.0 ? 0.0 : p;
+}
+
+// Magnitude of magnitude code k (exponent field k >> M, mantissa field below) for one bias.
+CO3_HD inline double magnitude_of_code(int k, int M, int bias)
+{
+    const int f = k >> M, a = k & ((1 << M) - 1);
+    return f == 0 ? ldexp((double)a, 1 - bias - M) : ldexp((double)((1 << M) + a), f - bias - M);
+}
+
+// Whether Q_fp can produce symbol s (the top exponent field and negative zero never occur), and
+// the cell (lo, hi] of inputs it stands for.
+CO3_HD inline bool symbol_cell(uint32_t s, int E, int M, int bias, double *lo, double *hi)
+{
+    const int nmag = ((1 << E) - 1) << M;
+    const int k = (int)(s & ((1u << (E + M)) - 1u));
+    const bool neg = ((s >> (E + M)) & 1u) != 0u;
+    if (k >= nmag || (neg && k == 0) || (s >> (1 + E + M)) != 0u) return false;
+    const double v = magnitude_of_code(k, M, bias);
+    const double up = k == nmag - 1 ? INFINITY : 0.5 * (v + magnitude_of_code(k + 1, M, bias));
+    if (k == 0) { *lo = -up; *hi = up; return true; }
+    const double down = 0.5 * (v + magnitude_of_code(k - 1, M, bias));
+    if (neg) { *lo = -up; *hi = -down; }
+    else { *lo = down; *hi = up; }
+    return true;
+}
+
+// ln Kurt(beta) and Var / alpha^2 of eq. (kurtosis)
+CO3_HD inline double log_kurtosis_of_beta(double b) { return lgamma(5.0 / b) + lgamma(1.0 / b) - 2.0 * lgamma(3.0 / b); }
+CO3_HD inline double variance_factor(double b) { return exp(lgamma(3.0 / b) - lgamma(1.0 / b)); }
+
+// The beta in [kBetaMin, kBetaMax] whose kurtosis is kappa (clamped to that range): bisection on
+// ln beta; the kurtosis falls strictly with beta.
+CO3_HD inline double beta_of_kurtosis(double kappa)
+{
+    if (!(kappa == kappa) || isinf(kappa)) return kBetaMin;
+    const double lk = log(kappa);
+    if (lk >= log_kurtosis_of_beta(kBetaMin)) return kBetaMin;
+    if (lk <= log_kurtosis_of_beta(kBetaMax)) return kBetaMax;
+    double lo = log(kBetaMin), hi = log(kBetaMax);
+    for (int i = 0; i < 80; ++i) {
+        const double mid = 0.5 * (lo + hi);
+        if (log_kurtosis_of_beta(exp(mid)) > lk) lo = mid; else hi = mid;
+    }
+    return exp(0.5 * (lo + hi));
+}
+
+}  // namespace co3

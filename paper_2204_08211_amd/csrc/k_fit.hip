@@ -1,0 +1,197 @@
+// GenNorm parameters of the corrected gradient from the data, and the model code's weights from
+// those parameters, without a host round trip (Sec. III eq. (kurtosis): mean, variance and
+// kurtosis of GenNorm(mu, alpha, beta); Sec. IV-A (ii): the Huffman code is designed under the
+// GenNorm assumption; Sec. VI: the fitted parameters are then held for several epochs).
+//
+//   k_moments        one read sweep over g and m: per chunk the sums of v, v^2, v^3, v^4 in fp64,
+//                    v = fl32(g + fl32(gamma m)) (eq. (f_error_fb)); a wavefront owns a chunk, a
+//                    lane adds its elements in index order, the wavefront folds the lanes in a
+//                    fixed order: the sums do not depend on scheduling
+//   k_fit_params     per (user, layer): folds the chunk sums in a fixed order, central moments,
+//                    beta from the kurtosis by bisection, alpha from the variance
+//   k_model_weights  per code table: the element-count-weighted mixture of the quantized models
+//                    of the (user, layer) pairs the table serves -> integer Huffman weights
+//
+// The raw-moment route loses about (mu / sigma)^4 ulps of the fourth central moment to
+// cancellation; gradient layers have |mu| << sigma.
+// HBM traffic of k_moments per element: read g (4) + read m (4).
+#include "co3_internal.h"
+#include "gennorm_math.h"
+
+namespace co3 {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMoWaves = 4;                 // wavefronts (chunks) per workgroup
+constexpr int kMoThreads = 64 * kMoWaves;
+constexpr int kFitThreads = 256;
+
+__device__ inline uint32_t fit_find_chunk_segment(const SegDev *segs, uint32_t nseg, uint64_t chunk)
+{
+    uint32_t lo = 0, hi = nseg;  // segs[nseg].chunk_start = nchunks > chunk
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (segs[mid].chunk_start <= chunk) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+struct Sums4 {
+    double s1, s2, s3, s4;
+    __device__ inline void add(float vf)
+    {
+        const double v = (double)vf, v2 = v * v;  // v2 is exact
+        s1 += v;
+        s2 += v2;
+        s3 += v2 * v;
+        s4 += v2 * v2;
+    }
+};
+
+__global__ __launch_bounds__(kMoThreads) void k_moments(Layout lay, const float *__restrict__ g,
+                                                        const float *__restrict__ m, uint64_t row_stride,
+                                                        float gamma, double *__restrict__ partial)
+{
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t c = (uint64_t)blockIdx.x * kMoWaves + wave;
+    const uint32_t u = blockIdx.y;
+    if (c >= lay.nchunks) return;  // whole wavefront; no workgroup barriers below
+    const uint32_t seg = fit_find_chunk_segment(lay.segs, lay.nseg, c);
+    const SegDev sd = lay.segs[seg];
+    const uint64_t e0 = sd.offset + (c - sd.chunk_start) * kChunk;
+    const uint64_t left = sd.offset + sd.length - e0;
+    const uint32_t n = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
+    const float *gu = g + (uint64_t)u * row_stride + e0;
+    const float *mu = m + (uint64_t)u * row_stride + e0;
+
+    // every lane adds its elements in a fixed order: four consecutive ones at a time on the vector
+    // path, every 64th element of the chunk otherwise
+    Sums4 acc = {0.0, 0.0, 0.0, 0.0};
+    if (n == (uint32_t)kChunk && (e0 & 3u) == 0) {
+#pragma unroll 4
+        for (int r = 0; r < kChunk / 4 / 64; ++r) {
+            const uint32_t i = 4u * (lane + 64u * r);
+            const f4 gv = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(gu + i));
+            const f4 mv = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(mu + i));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc.add(__fadd_rn(gv[j], __fmul_rn(gamma, mv[j])));
+        }
+    } else {
+        for (uint32_t i = lane; i < n; i += 64) acc.add(__fadd_rn(gu[i], __fmul_rn(gamma, mu[i])));
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        acc.s1 += __shfl_xor(acc.s1, o, 64);
+        acc.s2 += __shfl_xor(acc.s2, o, 64);
+        acc.s3 += __shfl_xor(acc.s3, o, 64);
+        acc.s4 += __shfl_xor(acc.s4, o, 64);
+    }
+    if (lane == 0) {
+        double *p = partial + ((uint64_t)u * lay.nchunks + c) * 4;
+        p[0] = acc.s1; p[1] = acc.s2; p[2] = acc.s3; p[3] = acc.s4;
+    }
+}
+
+__global__ __launch_bounds__(kFitThreads) void k_fit_params(Layout lay, const double *__restrict__ partial,
+                                                            co3_gennorm_params *__restrict__ params)
+{
+    __shared__ double s_red[4][kFitThreads];
+    const uint32_t seg = blockIdx.x, u = blockIdx.y, t = threadIdx.x;
+    const uint64_t cs = lay.segs[seg].chunk_start, ce = lay.segs[seg + 1].chunk_start;
+    double a[4] = {0.0, 0.0, 0.0, 0.0};
+    for (uint64_t c = cs + t; c < ce; c += kFitThreads) {
+        const double *p = partial + ((uint64_t)u * lay.nchunks + c) * 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] += p[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) s_red[j][t] = a[j];
+    __syncthreads();
+    for (int o = kFitThreads / 2; o > 0; o >>= 1) {
+        if (t < (uint32_t)o) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s_red[j][t] += s_red[j][t + o];
+        }
+        __syncthreads();
+    }
+    if (t != 0) return;
+    co3_gennorm_params out = {0.0, 0.0, 0.0, 0.0};
+    const uint64_t n = lay.segs[seg].length;
+    if (n > 0) {
+        const double dn = (double)n;
+        const double S1 = s_red[0][0], S2 = s_red[1][0], S3 = s_red[2][0], S4 = s_red[3][0];
+        const double mean = S1 / dn, ms = S2 / dn;
+        const double m2 = ms - mean * mean;
+        const double m4 = (S4 - 4.0 * mean * S3 + 6.0 * mean * mean * S2) / dn - 3.0 * mean * mean * mean * mean;
+        out.mu = mean;
+        // a variance below 2^-40 of the mean square is rounding noise of the raw sums: constant layer
+        if (m2 > ms * 9.094947017729282e-13) {
+            out.kurtosis = m4 / (m2 * m2);
+            out.beta = beta_of_kurtosis(out.kurtosis);
+            out.alpha = sqrt(m2 / variance_factor(out.beta));
+        }
+    }
+    params[(uint64_t)u * lay.nseg + seg] = out;
+}
+
+__global__ __launch_bounds__(kMaxA) void k_model_weights(Layout lay, const co3_gennorm_params *__restrict__ params,
+                                                         uint64_t *__restrict__ weights)
+{
+    const uint32_t b = blockIdx.x, s = threadIdx.x;
+    if (s >= lay.A) return;
+    const uint32_t u_first = lay.per_user_books ? b / lay.books_per_user : 0u;
+    const uint32_t u_last = lay.per_user_books ? u_first : lay.U - 1u;
+    const int32_t book = (int32_t)(lay.per_user_books ? b % lay.books_per_user : b);
+    double lo, hi;
+    const bool producible = symbol_cell(s, lay.E, lay.M, lay.bias[0], &lo, &hi);  // the same for every bias
+    double mass = 0.0, count = 0.0;
+    if (producible) {
+        for (uint32_t u = u_first; u <= u_last; ++u) {
+            for (uint32_t k = 0; k < lay.nseg; ++k) {
+                const SegDev sd = lay.segs[k];
+                if (sd.book != book || sd.length == 0) continue;
+                const co3_gennorm_params p = params[(uint64_t)u * lay.nseg + k];
+                if (!(p.alpha > 0.0) || !(p.beta > 0.0)) continue;
+                symbol_cell(s, lay.E, lay.M, lay.bias[(uint64_t)u * lay.nseg + k], &lo, &hi);
+                mass += (double)sd.length * gennorm_mass(lo, hi, p.mu, p.alpha, p.beta);
+                count += (double)sd.length;
+            }
+        }
+    }
+    uint64_t w = 0;
+    if (producible) {
+        w = 1;
+        if (count > 0.0) {
+            const double x = floor(mass / count * 1099511627776.0);  // 2^40
+            if (x >= 1.0) w = (uint64_t)x;
+        }
+    }
+    weights[(uint64_t)b * lay.A + s] = w;
+}
+
+size_t fit_workspace_bytes(const Layout &lay) { return (size_t)lay.U * lay.nchunks * 4 * sizeof(double) + 256; }
+
+hipError_t launch_fit(const Layout &lay, const float *g, const float *m, uint64_t row_stride, float gamma,
+                      co3_gennorm_params *params, double *partial, hipStream_t s)
+{
+    if (lay.U == 0) return hipSuccess;
+    if (lay.nchunks) {
+        ProfScope prof(K_MOMENTS, s);
+        const uint32_t gx = (uint32_t)((lay.nchunks + kMoWaves - 1) / kMoWaves);
+        hipLaunchKernelGGL(k_moments, dim3(gx, lay.U), dim3(kMoThreads), 0, s, lay, g, m, row_stride, gamma, partial);
+    }
+    ProfScope prof(K_FIT, s);
+    hipLaunchKernelGGL(k_fit_params, dim3(lay.nseg, lay.U), dim3(kFitThreads), 0, s, lay, partial, params);
+    return hipGetLastError();
+}
+
+hipError_t launch_model_weights(const Layout &lay, const co3_gennorm_params *params, uint64_t *weights,
+                                hipStream_t s)
+{
+    if (lay.nbooks == 0) return hipSuccess;
+    ProfScope prof(K_MODEL_WEIGHTS, s);
+    hipLaunchKernelGGL(k_model_weights, dim3(lay.nbooks), dim3(kMaxA), 0, s, lay, params, weights);
+    return hipGetLastError();
+}
+
+}  // namespace co3

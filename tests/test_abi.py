@@ -34,7 +34,7 @@ def test_struct_layouts_match_the_header(tmp_path):
     # compile a C program against include/co3.h that prints sizeof / offsetof, compare with ctypes
     structs = {"co3_segment": binding.Segment, "co3_encode_args": binding.EncodeArgs,
                "co3_decode_args": binding.DecodeArgs, "co3_aggregate_args": binding.AggregateArgs,
-               "co3_format": binding.Format}
+               "co3_format": binding.Format, "co3_gennorm_params": binding.GennormParams}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "co3.h"', 'int main(void){']
     for cname, st in structs.items():
         lines.append(f'printf("{cname} %zu\\n", sizeof({cname}));')

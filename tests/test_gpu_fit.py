@@ -1,0 +1,158 @@
+"""GPU-vs-oracle parity of the GenNorm moment fit and the model code's weights (pytest -m gpu).
+
+Floating point: the GPU sums raw moments in one sweep in a fixed order, the oracle takes central
+moments in two passes with NumPy's pairwise sums, and the two use different log-gamma routines.
+Tolerances, from the arithmetic: mean within 1e-12 of the sample's standard deviation; kurtosis,
+alpha and beta within 1e-9 relative for samples with |mean| <= sigma (the raw-moment route loses
+about (mean/sigma)^4 ulps); weights within 1 + 1e-9 w of the oracle's SciPy-based ones (the floor
+of p 2^40 may fall on either side).  The fitted model's code is then used by the single-sweep
+encoder, whose streams are compared bit for bit with the oracle's encoding under the same tables.
+"""
+import numpy as np
+import pytest
+
+import co3_synth as syn
+from oracle import co3_gennorm_fit as fitm
+from oracle import co3_oracle as orc
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_fit(kw, g, m, gamma):
+    import torch
+    from paper_2204_08211_amd import binding as B
+    dev = torch.device("cuda:0")
+    plan = B.Plan(**kw)
+    U, d = plan.U, plan.d
+    stride = (d + 3) // 4 * 4
+    gt = torch.zeros((U, stride), dtype=torch.float32, device=dev)
+    mt = torch.zeros((U, stride), dtype=torch.float32, device=dev)
+    gt[:, :d] = torch.from_numpy(np.ascontiguousarray(g)).to(dev)
+    mt[:, :d] = torch.from_numpy(np.ascontiguousarray(m)).to(dev)
+    params = B.co3_gennorm_fit(plan, gt, mt, gamma)
+    weights = B.co3_model_weights_device(plan, params)
+    torch.cuda.synchronize()
+    return plan, params.cpu().numpy(), weights.cpu().numpy().view(np.uint64), (gt, mt, params, weights)
+
+
+def check_params(got, ref, sigma_floor=0.0):
+    assert got.shape == ref.shape
+    for idx in np.ndindex(ref.shape[:2]):
+        mu_r, a_r, b_r, k_r = ref[idx]
+        mu_g, a_g, b_g, k_g = got[idx]
+        if a_r == 0.0:
+            assert a_g == 0.0 and b_g == 0.0 and k_g == 0.0, idx
+            assert abs(mu_g - mu_r) <= 1e-12 * max(abs(mu_r), 1e-30), idx
+            continue
+        sigma = a_r * np.sqrt(float(fitm.variance_factor(b_r)))
+        assert abs(mu_g - mu_r) <= 1e-12 * sigma, (idx, mu_g, mu_r)
+        assert abs(k_g / k_r - 1.0) <= 1e-9, (idx, k_g, k_r)
+        assert abs(b_g / b_r - 1.0) <= 1e-9, (idx, b_g, b_r)
+        assert abs(a_g / a_r - 1.0) <= 1e-9, (idx, a_g, a_r)
+
+
+def check_weights(got, ref):
+    assert got.shape == ref.shape
+    assert np.array_equal(got > 0, ref > 0)
+    g = got.astype(np.float64); r = ref.astype(np.float64)
+    assert np.all(np.abs(g - r) <= 1.0 + 1e-9 * r), np.abs(g - r).max()
+
+
+@pytest.mark.parametrize("beta,alpha,d", [(0.7, 1e-3, 4096 * 5 + 123), (1.0, 2e-3, 4095), (1.5, 1e-4, 4096 * 33),
+                                          (2.0, 1e-2, 100_000)])
+def test_fit_single_layer(beta, alpha, d):
+    E, M, U = 4, 3, 2
+    rng = np.random.default_rng(int(beta * 100) + d)
+    g = np.stack([syn.gennorm_numpy(rng, d, beta, alpha) for _ in range(U)])
+    m = np.stack([syn.gennorm_numpy(rng, d, beta, alpha * 0.4) for _ in range(U)])
+    bias = syn.bias_for_max(np.abs(g + np.float32(0.9) * m).max(), E)
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[bias]] * U)
+    _, par, w, _ = gpu_fit(kw, g, m, 0.9)
+    ref = fitm.fit_round(g, m, 0.9, [d])
+    check_params(par, ref)
+    check_weights(w, fitm.pooled_model_weights(E, M, [[bias]] * U, ref, [d], [0], False))
+
+
+@pytest.mark.parametrize("per_user", [False, True])
+def test_fit_layers_empty_constant_and_shared_tables(per_user):
+    E, M, U = 3, 2, 3
+    seg_len = [1, 63, 4097, 0, 2048 * 3 + 5, 64, 9001, 4096, 4096 * 5, 7]
+    seg_book = [0, 1, 2, 0, 1, 3, 2, 0, 1, 3]
+    d = sum(seg_len)
+    rng = np.random.default_rng(91 + per_user)
+    bias = rng.integers(8, 20, (U, len(seg_len))).astype(np.int32)
+    g = np.empty((U, d), np.float32); m = np.empty((U, d), np.float32)
+    off = 0
+    for k, n in enumerate(seg_len):
+        for u in range(U):
+            top = orc.grid(E, M, int(bias[u, k]))[-1]
+            g[u, off:off + n] = syn.gennorm_numpy(rng, n, 0.8 + 0.3 * u, top / 8)
+            m[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, top / 30)
+        off += n
+    g[1, 64:64 + 4097] = 0.25; m[1, 64:64 + 4097] = 0.0          # a constant layer: variance 0
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias, seg_len=seg_len, seg_book=seg_book, per_user_books=per_user)
+    _, par, w, _ = gpu_fit(kw, g, m, 0.9)
+    ref = fitm.fit_round(g, m, 0.9, seg_len)
+    assert ref[0, 3, 1] == 0.0 and ref[1, 2, 1] == 0.0 and ref[0, 0, 1] == 0.0  # empty, constant, one element
+    check_params(par, ref)
+    check_weights(w, fitm.pooled_model_weights(E, M, bias, ref, seg_len, seg_book, per_user))
+
+
+def test_fit_closed_form_samples():
+    # {-1 (p), 0, +1 (p)} scaled: kurtosis 1/(2p) exactly; p = 1/12 is Laplace's 6, p = 1/6 the Normal's 3
+    E, M = 4, 3
+    d = 4096 * 3
+    x = np.zeros((2, d), np.float32)
+    x[0, : d // 12] = 0.5; x[0, d // 12: d // 6] = -0.5
+    x[1, : d // 6] = 0.5; x[1, d // 6: d // 3] = -0.5
+    kw = dict(E=E, M=M, U=2, d=d, bias=[[14]] * 2)
+    _, par, _, _ = gpu_fit(kw, x, np.zeros_like(x), 0.9)
+    assert abs(par[0, 0, 3] - 6.0) < 1e-12 and abs(par[0, 0, 2] - 1.0) < 1e-9
+    assert abs(par[0, 0, 1] - 0.5 * np.sqrt(1.0 / 12.0)) < 1e-10 and par[0, 0, 0] == 0.0
+    assert abs(par[1, 0, 3] - 3.0) < 1e-12 and abs(par[1, 0, 2] - 2.0) < 1e-9
+    assert abs(par[1, 0, 1] - 0.5 * np.sqrt(2.0 / 3.0)) < 1e-10
+
+
+def test_fit_is_deterministic_and_gamma_zero_ignores_memory():
+    E, M, U, d = 4, 3, 3, 4096 * 7 + 11
+    rng = np.random.default_rng(3)
+    g = np.stack([syn.gennorm_numpy(rng, d, 0.9, 1e-3) for _ in range(U)])
+    m = np.stack([syn.gennorm_numpy(rng, d, 1.2, 1e-2) for _ in range(U)])
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[14]] * U)
+    _, a, wa, _ = gpu_fit(kw, g, m, 0.0)
+    _, b, wb, _ = gpu_fit(kw, g, np.zeros_like(m), 0.0)
+    assert np.array_equal(a.view(np.uint64), b.view(np.uint64)) and np.array_equal(wa, wb)
+    _, c, _, _ = gpu_fit(kw, g, m, 0.0)
+    assert np.array_equal(a.view(np.uint64), c.view(np.uint64))
+
+
+def test_fitted_model_code_drives_the_single_sweep_encoder():
+    # fit on the device -> weights on the device -> code tables on the device -> single-sweep encode;
+    # the oracle encodes with the tables the device built (exported), so every stream bit is compared
+    import torch
+    from paper_2204_08211_amd import binding as B
+    w = syn.WORKLOADS["cfg3"].scaled(d=4096 * 9 + 77, U=4)
+    g = np.stack([syn.user_gradient_numpy(w, 0, u) for u in range(w.U)])
+    m = np.stack([syn.user_gradient_numpy(w, 1, u) for u in range(w.U)]) * np.float32(0.3)
+    v = g + np.float32(w.gamma) * m
+    bias = np.array([[syn.bias_for_max(np.abs(v[u]).max(), w.E)] for u in range(w.U)], np.int32)
+    kw = dict(E=w.E, M=w.M, U=w.U, d=w.d, bias=bias)
+    plan, par, wts, (gt, mt, params_t, weights_t) = gpu_fit(kw, g, m, w.gamma)
+    ref_par = fitm.fit_round(g, m, w.gamma, [w.d])
+    check_params(par, ref_par)
+    ref_w = fitm.pooled_model_weights(w.E, w.M, bias, ref_par, [w.d], [0], False)
+    check_weights(wts, ref_w)
+    books = B.co3_build_codebook(w.E, w.M, plan.num_books, None)
+    buf = B.RoundBuffers(plan, gt.device, max_code_len=64)
+    B.co3_build_codebook_device(books, weights_t, buf.status)
+    torch.cuda.synchronize()
+    lens_dev, codes_dev = books.export(0)
+    lens_o, codes_o = orc.codebook(wts[0])                 # the oracle's Huffman code of the device's weights
+    assert np.array_equal(lens_dev, lens_o) and np.array_equal(codes_dev, codes_o)
+    gpu, _ = gu.gpu_round(kw, g, m, w.gamma, 0, books=books, buf=buf, single_sweep=True)
+    ref = gu.oracle_round(kw, g, m, w.gamma, weights=wts)
+    gu.compare_round(gpu, ref, w.d, single_sweep=True)
+    # the model code costs little more than the code of the round's own histogram
+    emp = gu.oracle_round(kw, g, m, w.gamma)
+    assert ref["payload_bits"].sum() <= 1.01 * emp["payload_bits"].sum()
