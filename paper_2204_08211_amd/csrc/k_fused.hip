@@ -5,10 +5,10 @@
 // HBM traffic per element: read g (4) + read m (4) + write m' (4) + write b (r/d bits).
 //
 // A workgroup of four wavefronts takes four consecutive chunks of one user:
-//   1. all threads quantize the chunks one after the other (the next chunk's g and m are requested
-//      before the current one is computed) and leave the symbols in LDS, in the rows of 16 + 1
-//      words the pack step reads without bank conflicts;
-//   2. wavefront w sums the code lengths of chunk w: lane j owns sub-chunk j;
+//   1. wavefront w quantizes chunk w (16 KB of g and of m, requested a quarter at a time with the
+//      next quarter in flight while the current one is computed) and leaves the symbols in LDS,
+//      in the rows of 16 + 1 words the pack step reads without bank conflicts;
+//   2. it sums the code lengths: lane j owns sub-chunk j (steps 1 and 2 need no workgroup barrier);
 //   3. the workgroup's 32-bit-rounded size is published and the sizes of all earlier workgroups of
 //      the user are collected by a decoupled look-back: every workgroup first publishes its own
 //      size, then reads its predecessors' until it meets one that already knows its running total.
@@ -34,7 +34,8 @@ constexpr int kFuThreads = 64 * kFuCpb;
 constexpr int kFuRow = 17;                           // 16 words of symbols + 1 pad
 constexpr int kFuStage = kSubsPerChunk * kFuRow;     // 1088 words hold a chunk's symbols
 constexpr int kFuWin = 1088;                         // LDS window of the output: 8.5 bit/element per pass
-constexpr int kFuVec = kChunk / 4 / kFuThreads;      // 16-byte vectors of g (and of m) per thread and chunk
+constexpr int kFuBatch = 4;                          // 16-byte vectors of g (and of m) a lane requests at a time
+constexpr int kFuBatches = kChunk / 4 / 64 / kFuBatch; // batches per chunk
 constexpr uint32_t kFuSpinLimit = 1u << 20;          // polls of one predecessor entry before giving up
 
 // look-back entry: flag in the top two bits, size in bits below
@@ -43,7 +44,7 @@ constexpr uint64_t kLbPrefix = 2ull << 62;   // size of this workgroup and all b
 constexpr uint64_t kLbStalled = 3ull << 62;
 constexpr uint64_t kLbValue = (1ull << 62) - 1;
 
-static_assert(kChunk % (4 * kFuThreads) == 0, "whole vectors per thread and chunk");
+static_assert(kChunk % (4 * 64 * kFuBatch) == 0, "whole batches per chunk");
 
 __device__ inline uint32_t fu_find_chunk_segment(const SegDev *segs, uint32_t nseg, uint64_t chunk)
 {
@@ -115,100 +116,86 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
     }
     fu_lds_barrier();
 
-    // ---- 1. quantize the chunks, symbols to LDS ------------------------------------------------
-    const float *gu = g + (uint64_t)u * row_stride;
-    const float *mu = m + (uint64_t)u * row_stride;
-    float *mo = m_out + (uint64_t)u * row_stride;
+    // ---- 1. wavefront w quantizes chunk w, symbols to LDS ---------------------------------------
+    const bool active = wave < nck;
     const uint32_t sign_shift = lay.E + lay.M;
-    uint32_t n_nonfinite = 0, n_clamped = 0;
-
-    // a whole chunk at a 16-byte aligned position takes the vector path
-    auto vec_ok = [&](uint32_t k) { return k < nck && s_n[k] == (uint32_t)kChunk && (s_e0[k] & 3u) == 0; };
-    f4 gn[kFuVec], mn[kFuVec];
-    if (vec_ok(0)) {
-        const uint64_t e0 = s_e0[0];
+    if (active) {
+        const uint64_t e0 = s_e0[wave];
+        const uint32_t nk = s_n[wave];
+        const QConst qc = make_qconst(lay.E, lay.M, s_bias[wave]);
+        const float *gu = g + (uint64_t)u * row_stride + e0;
+        const float *mu = m + (uint64_t)u * row_stride + e0;
+        float *mo = m_out + (uint64_t)u * row_stride + e0;
+        uint32_t n_nonfinite = 0, n_clamped = 0;
+        // a whole chunk at a 16-byte aligned position takes the vector path: kFuBatch vectors of g and
+        // of m per lane at a time, the next batch requested before the current one is computed
+        if (nk == (uint32_t)kChunk && (e0 & 3u) == 0) {
+            f4 gn[kFuBatch], mn[kFuBatch];
 #pragma unroll
-        for (int r = 0; r < kFuVec; ++r) {
-            const uint64_t i = e0 + 4u * (t + (uint32_t)kFuThreads * r);
-            gn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(gu + i));
-            mn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(mu + i));
-        }
-    }
-    // the code-table entries of the chunks, one table per wavefront's chunk
-    for (uint32_t i = t; i < nck * (uint32_t)kMaxA; i += kFuThreads)
-        s_fast[i / kMaxA][i % kMaxA] = books[s_book[i / kMaxA]].fast[i % kMaxA];
-
-#pragma unroll 1
-    for (uint32_t k = 0; k < nck; ++k) {
-        const bool vk = vec_ok(k);
-        const uint64_t e0 = s_e0[k];
-        const QConst qc = make_qconst(lay.E, lay.M, s_bias[k]);
-        if (vk) {
-            f4 gc[kFuVec], mc[kFuVec];
-#pragma unroll
-            for (int r = 0; r < kFuVec; ++r) { gc[r] = gn[r]; mc[r] = mn[r]; }
-            if (vec_ok(k + 1)) {
-                const uint64_t e1 = s_e0[k + 1];
-#pragma unroll
-                for (int r = 0; r < kFuVec; ++r) {
-                    const uint64_t i = e1 + 4u * (t + (uint32_t)kFuThreads * r);
-                    gn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(gu + i));
-                    mn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(mu + i));
-                }
+            for (int r = 0; r < kFuBatch; ++r) {
+                const uint32_t i = 4u * (lane + 64u * r);
+                gn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(gu + i));
+                mn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(mu + i));
             }
+#pragma unroll 1
+            for (int bt = 0; bt < kFuBatches; ++bt) {
+                f4 gc[kFuBatch], mc[kFuBatch];
 #pragma unroll
-            for (int r = 0; r < kFuVec; ++r) {
-                const uint32_t dw = t + (uint32_t)kFuThreads * r;  // word of the chunk's symbols
-                f4 eo;
-                uint32_t packed = 0;
+                for (int r = 0; r < kFuBatch; ++r) { gc[r] = gn[r]; mc[r] = mn[r]; }
+                if (bt + 1 < kFuBatches) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float v = __fadd_rn(gc[r][j], __fmul_rn(gamma, mc[r][j]));
-                    uint32_t s, flags;
-                    float q;
-                    quantize(v, qc, sign_shift, s, q, flags);
-                    eo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
-                    n_nonfinite += flags & 1u;
-                    n_clamped += (flags >> 1) & 1u;
-                    packed |= s << (8 * j);
+                    for (int r = 0; r < kFuBatch; ++r) {
+                        const uint32_t i = 4u * (lane + 64u * (uint32_t)((bt + 1) * kFuBatch + r));
+                        gn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(gu + i));
+                        mn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(mu + i));
+                    }
                 }
-                __builtin_nontemporal_store(eo, reinterpret_cast<f4 *>(mo + e0 + 4u * dw));
-                s_stage[k][dw + (dw >> 4)] = packed;
+#pragma unroll
+                for (int r = 0; r < kFuBatch; ++r) {
+                    const uint32_t dw = lane + 64u * (uint32_t)(bt * kFuBatch + r);  // word of the chunk's symbols
+                    f4 eo;
+                    uint32_t packed = 0;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float v = __fadd_rn(gc[r][j], __fmul_rn(gamma, mc[r][j]));
+                        uint32_t s, flags;
+                        float q;
+                        quantize(v, qc, sign_shift, s, q, flags);
+                        eo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
+                        n_nonfinite += flags & 1u;
+                        n_clamped += (flags >> 1) & 1u;
+                        packed |= s << (8 * j);
+                    }
+                    __builtin_nontemporal_store(eo, reinterpret_cast<f4 *>(mo + 4u * dw));
+                    s_stage[wave][dw + (dw >> 4)] = packed;
+                }
             }
         } else {
-            // ragged or unaligned chunk: element path; the next chunk is requested afterwards
-            const uint32_t n = s_n[k];
-            uint8_t *stage_bytes = reinterpret_cast<uint8_t *>(s_stage[k]);
-            for (uint32_t j = t; j < n; j += kFuThreads) {
-                const float v = __fadd_rn(gu[e0 + j], __fmul_rn(gamma, mu[e0 + j]));
+            // ragged or unaligned chunk: element path
+            uint8_t *stage_bytes = reinterpret_cast<uint8_t *>(s_stage[wave]);
+            for (uint32_t j = lane; j < nk; j += 64) {
+                const float v = __fadd_rn(gu[j], __fmul_rn(gamma, mu[j]));
                 uint32_t s, flags;
                 float q;
                 quantize(v, qc, sign_shift, s, q, flags);
-                mo[e0 + j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
+                mo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
                 n_nonfinite += flags & 1u;
                 n_clamped += (flags >> 1) & 1u;
                 const uint32_t dw = j >> 2;
                 stage_bytes[4u * (dw + (dw >> 4)) + (j & 3u)] = (uint8_t)s;
             }
-            if (vec_ok(k + 1)) {
-                const uint64_t e1 = s_e0[k + 1];
-#pragma unroll
-                for (int r = 0; r < kFuVec; ++r) {
-                    const uint64_t i = e1 + 4u * (t + (uint32_t)kFuThreads * r);
-                    gn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(gu + i));
-                    mn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(mu + i));
-                }
-            }
         }
+        // the code-table entries of this wavefront's chunk
+        for (uint32_t i = lane; i < (uint32_t)kMaxA; i += 64) s_fast[wave][i] = books[s_book[wave]].fast[i];
+        if (n_nonfinite)
+            atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NONFINITE),
+                      (unsigned long long)n_nonfinite);
+        if (n_clamped)
+            atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CLAMPED), (unsigned long long)n_clamped);
     }
-    if (n_nonfinite)
-        atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NONFINITE), (unsigned long long)n_nonfinite);
-    if (n_clamped)
-        atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CLAMPED), (unsigned long long)n_clamped);
-    fu_lds_barrier();
+    fu_wave_sync_lds();  // stage and table of a wavefront are its own: no workgroup barrier
 
     // ---- 2. code lengths: wavefront = chunk, lane = sub-chunk ----------------------------------
-    const bool active = wave < nck;
     const uint64_t c = c0 + wave;
     const uint32_t n = active ? s_n[wave] : 0u;
     const int first = (int)lane * kSub;
