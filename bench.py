@@ -205,6 +205,9 @@ def main():
                 B.profile_begin()
             t0 = time.perf_counter()
             B.co3_gennorm_fit(plan, pool[0], m, w.gamma, params=params, workspace=ws)
+            # the model's own exponent bias (eq. (exp bias)) is computed and timed but not installed: the
+            # workload prescribes the bias rule "top binade covers max|v|"
+            model_bias, _ = B.co3_model_bias_device(plan, params, install=False)
             B.co3_model_weights_device(plan, params, weights=weights)
             B.co3_build_codebook_device(books, weights, buf.status)
             torch.cuda.synchronize()
@@ -214,7 +217,9 @@ def main():
                                kernel_ms={k: round(v[0] / v[1], 4) for k, v in kt.items()},
                                moments_sweep_hbm_frac=round(8.0 * elems / (kt["k_moments"][0] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
         p = params.cpu().numpy()
-        refresh.update(beta_fit_range=[round(float(p[:, :, 2].min()), 4), round(float(p[:, :, 2].max()), 4)])
+        refresh.update(beta_fit_range=[round(float(p[:, :, 2].min()), 4), round(float(p[:, :, 2].max()), 4)],
+                       model_bias_minus_workload_bias=[int(x) for x in
+                                                       (model_bias.cpu().numpy() - bias).ravel()[:16]])
         return books
 
     runs = {}

@@ -156,6 +156,21 @@ int co3_gennorm_fit(const co3_plan *plan, const float *g, const float *m, uint64
                     size_t workspace_bytes, void *stream);
 int co3_model_weights_device(const co3_plan *plan, const co3_gennorm_params *params,
                              uint64_t *weights, void *stream);
+/* Exponent bias from the model: eq. (exp bias) of Sec. IV-A (i), b_t = argmin_b E|Q_fp(G) - G|^2,
+ * with b restricted to the integers (power-of-two scale) and G ~ GenNorm(params): the expectation
+ * in closed form (partial moments of GenNorm through incomplete gamma functions) for every bias
+ * the library supports; errors within 1e-9 (relative) of the minimum count as equal and the
+ * smallest such bias is taken; a layer without a model (alpha = 0) gets 2^(exp_bits-1) - 1.
+ * bias: device [U][nseg] (out); error: device [U][nseg] expected squared errors, or NULL.
+ * co3_plan_set_bias_device installs a device bias table in the plan (device-to-device copy on
+ * `stream`, no synchronisation); its values must be in the supported range, as the ones written
+ * by co3_model_bias_device are.  co3_bias_from_model is the same argmin for one parameter triple
+ * on the host.                                                                               */
+int co3_model_bias_device(const co3_plan *plan, const co3_gennorm_params *params, int32_t *bias,
+                          double *error, void *stream);
+int co3_plan_set_bias_device(co3_plan *plan, const int32_t *bias, void *stream);
+int co3_bias_from_model(co3_format format, double mu, double alpha, double beta, int32_t *bias,
+                        double *error);
 
 /* ---- user side: Algorithm 1 lines 8-10 for all U users -----------------------------------
  * v = g + gamma m (eq. (f_error_fb)), ghat = Q_fp(v), m' = v - ghat, b = h_Hf(ghat).

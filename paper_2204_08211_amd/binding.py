@@ -26,7 +26,7 @@ EXPORTS = [
     "co3_build_codebook", "co3_build_codebook_device", "co3_codebook_export", "co3_codebook_num_books",
     "co3_codebook_destroy", "co3_encode", "co3_decode", "co3_ps_aggregate", "co3_status_string",
     "co3_profile_begin", "co3_profile_end", "co3_gennorm_weights", "co3_plan_fit_workspace_bytes", "co3_gennorm_fit",
-    "co3_model_weights_device",
+    "co3_model_weights_device", "co3_model_bias_device", "co3_plan_set_bias_device", "co3_bias_from_model",
 ]
 
 
@@ -108,6 +108,10 @@ def lib():
         L.co3_gennorm_fit.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_float, C.c_void_p, C.c_void_p,
                                       C.c_size_t, C.c_void_p]
         L.co3_model_weights_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.co3_model_bias_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.co3_plan_set_bias_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.co3_bias_from_model.argtypes = [Format, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_int32),
+                                          C.POINTER(C.c_double)]
         L.co3_status_string.argtypes = [C.c_int]
         L.co3_status_string.restype = C.c_char_p
         _lib = L
@@ -269,6 +273,29 @@ def co3_model_weights_device(plan, params, weights=None, stream=None):
     _check("co3_model_weights_device",
            lib().co3_model_weights_device(plan.handle, params.data_ptr(), weights.data_ptr(), _stream(stream)))
     return weights
+
+
+def co3_model_bias_device(plan, params, install=True, stream=None):
+    """Exponent bias per user and layer from fitted parameters (eq. (exp bias) with integer b): returns
+    (int32 device tensor [U][nseg], float64 device tensor [U][nseg] of expected squared errors) and, with
+    install, makes it the plan's bias table."""
+    import torch
+    bias = torch.zeros((plan.U, plan.nseg), dtype=torch.int32, device=params.device)
+    err = torch.zeros((plan.U, plan.nseg), dtype=torch.float64, device=params.device)
+    _check("co3_model_bias_device",
+           lib().co3_model_bias_device(plan.handle, params.data_ptr(), bias.data_ptr(), err.data_ptr(), _stream(stream)))
+    if install:
+        _check("co3_plan_set_bias_device", lib().co3_plan_set_bias_device(plan.handle, bias.data_ptr(), _stream(stream)))
+    return bias, err
+
+
+def co3_bias_from_model(E, M, mu, alpha, beta):
+    """(bias, expected squared error) of eq. (exp bias) with integer b for GenNorm(mu, alpha, beta); host."""
+    b = C.c_int32(0)
+    e = C.c_double(0.0)
+    _check("co3_bias_from_model", lib().co3_bias_from_model(Format(E, M), float(mu), float(alpha), float(beta),
+                                                          C.byref(b), C.byref(e)))
+    return int(b.value), float(e.value)
 
 
 class RoundBuffers:

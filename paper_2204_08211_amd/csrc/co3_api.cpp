@@ -297,6 +297,27 @@ int co3_model_weights_device(const co3_plan *plan, const co3_gennorm_params *par
                : CO3_ERR_HIP;
 }
 
+int co3_model_bias_device(const co3_plan *plan, const co3_gennorm_params *params, int32_t *bias, double *error,
+                          void *stream)
+{
+    if (!plan || !params || !bias) return CO3_ERR_ARG;
+    DeviceGuard guard(plan->device);
+    return launch_model_bias(plan->lay, params, bias, error, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? CO3_OK
+               : CO3_ERR_HIP;
+}
+
+int co3_plan_set_bias_device(co3_plan *plan, const int32_t *bias, void *stream)
+{
+    if (!plan || !bias) return CO3_ERR_ARG;
+    DeviceGuard guard(plan->device);
+    const size_t n = (size_t)plan->lay.U * plan->lay.nseg;
+    return hipMemcpyAsync(plan->d_bias, bias, sizeof(int32_t) * n, hipMemcpyDeviceToDevice,
+                          static_cast<hipStream_t>(stream)) == hipSuccess
+               ? CO3_OK
+               : CO3_ERR_HIP;
+}
+
 int co3_decode(const co3_plan *plan, const co3_decode_args *a, void *stream)
 {
     if (!plan || !a) return CO3_ERR_ARG;

@@ -87,7 +87,7 @@ namespace co3 {
 
 // Per-kernel event timing (profile.cpp).  A ProfScope around a launch records two events on
 // the stream when profiling is on, and does nothing otherwise.
-enum KernelId { K_ZERO = 0, K_QUANTIZE, K_REDUCE_HIST, K_BUILD_BOOKS, K_CHUNK_BITS, K_SCAN, K_PACK, K_DECODE, K_AGGREGATE, K_FUSED, K_MOMENTS, K_FIT, K_MODEL_WEIGHTS, K_COUNT };
+enum KernelId { K_ZERO = 0, K_QUANTIZE, K_REDUCE_HIST, K_BUILD_BOOKS, K_CHUNK_BITS, K_SCAN, K_PACK, K_DECODE, K_AGGREGATE, K_FUSED, K_MOMENTS, K_FIT, K_MODEL_WEIGHTS, K_MODEL_BIAS, K_COUNT };
 bool profile_enabled();
 class ProfScope {
 public:
@@ -123,6 +123,8 @@ hipError_t launch_fit(const Layout &lay, const float *g, const float *m, uint64_
                       co3_gennorm_params *params, double *partial, hipStream_t s);
 hipError_t launch_model_weights(const Layout &lay, const co3_gennorm_params *params, uint64_t *weights,
                                 hipStream_t s);
+hipError_t launch_model_bias(const Layout &lay, const co3_gennorm_params *params, int32_t *bias, double *error,
+                             hipStream_t s);
 hipError_t launch_decode(const Layout &lay, const co3_decode_args &a, const BookDev *books, hipStream_t s);
 hipError_t launch_aggregate(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
                             hipStream_t s);

@@ -108,6 +108,53 @@ CO3_HD inline bool symbol_cell(uint32_t s, int E, int M, int bias, double *lo, d
     return true;
 }
 
+// int_a^b y^k f_Y(y) dy for the zero-location density f_Y and 0 <= a <= b <= infinity:
+//   alpha^k Gamma((k+1)/beta) / (2 Gamma(1/beta)) [P((k+1)/beta, (b/alpha)^beta) - P(.., (a/alpha)^beta)],
+// the difference taken on the tail that keeps precision.
+CO3_HD inline double interval_moment_pos(int k, double a, double b, double alpha, double beta)
+{
+    if (!(b > a)) return 0.0;
+    const double shape = ((double)k + 1.0) / beta;
+    const double ck = 0.5 * exp((double)k * log(alpha) + lgamma(shape) - lgamma(1.0 / beta));
+    double Pa, Qa, Pb, Qb;
+    inc_gamma(shape, pow(a / alpha, beta), &Pa, &Qa);
+    inc_gamma(shape, pow(b / alpha, beta), &Pb, &Qb);
+    return ck * (Pa > 0.5 ? Qa - Qb : Pb - Pa);
+}
+
+// The same for any a <= b: the part on the negative axis is the mirrored integral with sign (-1)^k.
+CO3_HD inline double interval_moment(int k, double a, double b, double alpha, double beta)
+{
+    const double pos = interval_moment_pos(k, a > 0.0 ? a : 0.0, b > 0.0 ? b : 0.0, alpha, beta);
+    const double neg = interval_moment_pos(k, -b > 0.0 ? -b : 0.0, -a > 0.0 ? -a : 0.0, alpha, beta);
+    return (k & 1) ? pos - neg : pos + neg;
+}
+
+// E (Q_fp(X) - X)^2 for X ~ GenNorm(mu, alpha, beta) and one exponent bias: the objective of
+// eq. (exp bias), Sec. IV-A (i), summed over the cells of the representatives.
+CO3_HD inline double expected_sq_error(int E, int M, int bias, double mu, double alpha, double beta)
+{
+    const uint32_t A = 1u << (1 + E + M);
+    double total = 0.0;
+    for (uint32_t s = 0; s < A; ++s) {
+        double lo, hi;
+        if (!symbol_cell(s, E, M, bias, &lo, &hi)) continue;
+        const int k = (int)(s & ((1u << (E + M)) - 1u));
+        const double r = ((s >> (E + M)) & 1u) ? -magnitude_of_code(k, M, bias) : magnitude_of_code(k, M, bias);
+        const double c = r - mu, a = lo - mu, b = hi - mu;
+        const double j0 = interval_moment(0, a, b, alpha, beta);
+        const double j1 = interval_moment(1, a, b, alpha, beta);
+        const double j2 = interval_moment(2, a, b, alpha, beta);
+        total += j2 - 2.0 * c * j1 + c * c * j0;
+    }
+    return total;
+}
+
+// Candidate biases of the argmin: every bias the library supports for the format.
+constexpr int kBiasMax = 127;
+CO3_HD inline int bias_min_supported(int E) { return ((1 << E) - 2) - 100; }
+constexpr double kBiasTie = 1e-9;  // errors within this relative distance of the minimum count as equal
+
 // ln Kurt(beta) and Var / alpha^2 of eq. (kurtosis)
 CO3_HD inline double log_kurtosis_of_beta(double b) { return lgamma(5.0 / b) + lgamma(1.0 / b) - 2.0 * lgamma(3.0 / b); }
 CO3_HD inline double variance_factor(double b) { return exp(lgamma(3.0 / b) - lgamma(1.0 / b)); }

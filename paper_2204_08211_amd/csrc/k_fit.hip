@@ -169,6 +169,49 @@ __global__ __launch_bounds__(kMaxA) void k_model_weights(Layout lay, const co3_g
     weights[(uint64_t)b * lay.A + s] = w;
 }
 
+// Exponent bias from the model, eq. (exp bias) with integer b: workgroup per (user, layer), thread
+// per candidate bias; the smallest bias whose error is within kBiasTie of the minimum wins (a format
+// with many binades has a plateau of equally good biases; the smallest has the most headroom).
+// A layer without a model (alpha = 0) gets the IEEE bias 2^(exp-1) - 1.
+constexpr int kBiasThreads = 256;
+__global__ __launch_bounds__(kBiasThreads) void k_model_bias(Layout lay, const co3_gennorm_params *__restrict__ params,
+                                                             int32_t *__restrict__ bias_out,
+                                                             double *__restrict__ error_out)
+{
+    __shared__ double s_err[kBiasThreads];
+    const uint32_t seg = blockIdx.x, u = blockIdx.y, t = threadIdx.x;
+    const co3_gennorm_params p = params[(uint64_t)u * lay.nseg + seg];
+    const int b0 = bias_min_supported(lay.E);
+    const int ncand = kBiasMax - b0 + 1;  // at most 226
+    const bool model = p.alpha > 0.0 && p.beta > 0.0;
+    double e = INFINITY;
+    if (model && (int)t < ncand) e = expected_sq_error(lay.E, lay.M, b0 + (int)t, p.mu, p.alpha, p.beta);
+    s_err[t] = e;
+    __syncthreads();
+    if (t != 0) return;
+    int best = (1 << (lay.E - 1)) - 1;
+    double best_err = 0.0;
+    if (model) {
+        double lowest = INFINITY;
+        for (int i = 0; i < ncand; ++i) lowest = s_err[i] < lowest ? s_err[i] : lowest;
+        const double limit = lowest * (1.0 + kBiasTie);
+        for (int i = 0; i < ncand; ++i) {
+            if (s_err[i] <= limit) { best = b0 + i; best_err = s_err[i]; break; }
+        }
+    }
+    bias_out[(uint64_t)u * lay.nseg + seg] = best;
+    if (error_out) error_out[(uint64_t)u * lay.nseg + seg] = best_err;
+}
+
+hipError_t launch_model_bias(const Layout &lay, const co3_gennorm_params *params, int32_t *bias, double *error,
+                             hipStream_t s)
+{
+    if (lay.U == 0) return hipSuccess;
+    ProfScope prof(K_MODEL_BIAS, s);
+    hipLaunchKernelGGL(k_model_bias, dim3(lay.nseg, lay.U), dim3(kBiasThreads), 0, s, lay, params, bias, error);
+    return hipGetLastError();
+}
+
 size_t fit_workspace_bytes(const Layout &lay) { return (size_t)lay.U * lay.nchunks * 4 * sizeof(double) + 256; }
 
 hipError_t launch_fit(const Layout &lay, const float *g, const float *m, uint64_t row_stride, float gamma,

@@ -9,7 +9,7 @@ namespace co3 {
 
 static const char *kKernelNames[K_COUNT] = {"k_zero_u64", "k_quantize", "k_reduce_hist", "k_build_books", "k_chunk_bits",
                                             "k_scan_chunks", "k_pack", "k_decode", "k_aggregate", "k_encode_fused", "k_moments", "k_fit_params",
-                                            "k_model_weights"};
+                                            "k_model_weights", "k_model_bias"};
 
 struct ProfRecord { int kid; hipEvent_t a, b; };
 static std::mutex g_mu;

@@ -156,3 +156,65 @@ def test_fitted_model_code_drives_the_single_sweep_encoder():
     # the model code costs little more than the code of the round's own histogram
     emp = gu.oracle_round(kw, g, m, w.gamma)
     assert ref["payload_bits"].sum() <= 1.01 * emp["payload_bits"].sum()
+
+
+def test_model_bias_on_the_device_and_a_round_with_it():
+    # fit -> bias from the model (eq. (exp bias) with integer b) -> installed in the plan -> weights ->
+    # code -> single-sweep encode -> PS average, all without the host; the oracle repeats every step
+    import torch
+    from oracle import co3_bias_model as bm
+    from paper_2204_08211_amd import binding as B
+    E, M, U = 4, 3, 3
+    seg_len = [4096 * 2 + 100, 0, 4096 * 3, 777]
+    seg_book = [0, 1, 1, 0]
+    d = sum(seg_len)
+    rng = np.random.default_rng(123)
+    g = np.empty((U, d), np.float32); m = np.empty((U, d), np.float32)
+    off = 0
+    for k, n in enumerate(seg_len):
+        for u in range(U):
+            g[u, off:off + n] = syn.gennorm_numpy(rng, n, 0.7 + 0.4 * u, 10.0 ** (-4 + k))
+            m[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, 10.0 ** (-5 + k))
+        off += n
+    gamma = 0.9
+    start_bias = np.full((U, len(seg_len)), 14, np.int32)
+    kw = dict(E=E, M=M, U=U, d=d, bias=start_bias, seg_len=seg_len, seg_book=seg_book, per_user_books=False)
+    plan, par, _, (gt, mt, params_t, _) = gpu_fit(kw, g, m, gamma)
+    ref_par = fitm.fit_round(g, m, gamma, seg_len)
+    check_params(par, ref_par)
+    bias_t, err_t = B.co3_model_bias_device(plan, params_t, install=True)
+    torch.cuda.synchronize()
+    bias_gpu = bias_t.cpu().numpy(); err_gpu = err_t.cpu().numpy()
+    bias_ref, err_ref = bm.bias_table(E, M, ref_par)
+    assert np.array_equal(bias_gpu, bias_ref), (bias_gpu, bias_ref)
+    live = err_ref > 0
+    assert np.all(np.abs(err_gpu[live] / err_ref[live] - 1.0) < 1e-8) and np.all(err_gpu[~live] == 0.0)
+    assert bias_ref[0, 1] == 7                              # the empty layer: no model, IEEE bias
+    # the library's host routine agrees with its device kernel
+    for u in range(U):
+        for k in range(len(seg_len)):
+            assert B.co3_bias_from_model(E, M, *par[u, k, :3])[0] == bias_gpu[u, k]
+    # weights and code for the new biases, then a whole round under them
+    weights_t = B.co3_model_weights_device(plan, params_t)
+    torch.cuda.synchronize()
+    wts = weights_t.cpu().numpy().view(np.uint64)
+    check_weights(wts, fitm.pooled_model_weights(E, M, bias_ref, ref_par, seg_len, seg_book, False))
+    books = B.co3_build_codebook(E, M, plan.num_books, None)
+    buf = B.RoundBuffers(plan, gt.device, max_code_len=64)
+    B.co3_build_codebook_device(books, weights_t, buf.status)
+    out = torch.zeros(d, dtype=torch.float32, device=gt.device)
+    m_new = mt.clone()
+    B.co3_encode(plan, books, gt, m_new, m_new, gamma, buf, mode=B.BOOK_FIXED, single_sweep=True)
+    B.co3_ps_aggregate(plan, books, buf, out)
+    torch.cuda.synchronize()
+    kw_ref = dict(kw, bias=bias_ref)
+    ref = gu.oracle_round(kw_ref, g, m, gamma, weights=wts)
+    gu.assert_bits_equal(m_new[:, :d].cpu().numpy(), ref["m_new"], "memory m'")
+    gu.assert_bits_equal(buf.chunk_offset.cpu().numpy().view(np.uint64), ref["chunk_offset"], "chunk offsets")
+    for u, wds in enumerate(ref["words"]):
+        gu.assert_bits_equal(buf.words[u, :wds.size].cpu().numpy().view(np.uint32), wds, f"bitstream of user {u}")
+    gu.assert_bits_equal(out.cpu().numpy(), ref["avg"], "PS average")
+    st = buf.status.cpu().numpy()
+    assert st[B.STAT_NOCODE] == 0 and st[B.STAT_CORRUPT] == 0 and st[B.STAT_STALLED] == 0
+    # the model's bias clips far less than one element in a thousand
+    assert st[B.STAT_CLAMPED] < 1e-3 * U * d

@@ -30,3 +30,18 @@ def test_gennorm_weights_argument_checks():
     assert L.co3_gennorm_weights(B.Format(4, 3), 18, 0.0, 1e-3, 0.0, buf) == B.ERR_ARG
     assert L.co3_gennorm_weights(B.Format(4, 3), 300, 0.0, 1e-3, 1.0, buf) == B.ERR_FORMAT
     assert L.co3_gennorm_weights(B.Format(4, 3), 18, 0.0, 1e-3, 1.0, None) == B.ERR_ARG
+
+
+@pytest.mark.parametrize("E,M,mu,alpha,beta", [(2, 1, 0.0, 1.0, 1.0), (3, 2, 0.0, 2e-3, 0.7), (4, 3, 1e-4, 1e-3, 1.0),
+                                              (4, 1, -2e-3, 5e-2, 1.6), (5, 2, 0.0, 1e-4, 2.0), (3, 0, 0.0, 3.0, 0.5)])
+def test_library_bias_from_model_equals_the_oracle(E, M, mu, alpha, beta):
+    # eq. (exp bias) with integer b: the library's own incomplete gamma against the oracle's SciPy-based one
+    from oracle import co3_bias_model as bm
+    b_lib, e_lib = B.co3_bias_from_model(E, M, mu, alpha, beta)
+    b_ref, e_ref = bm.best_bias(E, M, mu, alpha, beta)
+    assert b_lib == b_ref
+    assert abs(e_lib / e_ref - 1.0) < 1e-9
+
+
+def test_library_bias_from_model_without_a_model():
+    assert B.co3_bias_from_model(4, 3, 0.0, 0.0, 0.0) == (7, 0.0)
