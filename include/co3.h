@@ -161,13 +161,15 @@ int co3_model_weights_device(const co3_plan *plan, const co3_gennorm_params *par
  * in closed form (partial moments of GenNorm through incomplete gamma functions) for every bias
  * the library supports; errors within 1e-9 (relative) of the minimum count as equal and the
  * smallest such bias is taken; a layer without a model (alpha = 0) gets 2^(exp_bits-1) - 1.
- * bias: device [U][nseg] (out); error: device [U][nseg] expected squared errors, or NULL.
+ * bias: device [U][nseg] (out); error: device [U][nseg] expected squared errors, or NULL;
+ * workspace: device, co3_plan_bias_workspace_bytes().
  * co3_plan_set_bias_device installs a device bias table in the plan (device-to-device copy on
  * `stream`, no synchronisation); its values must be in the supported range, as the ones written
  * by co3_model_bias_device are.  co3_bias_from_model is the same argmin for one parameter triple
  * on the host.                                                                               */
+size_t co3_plan_bias_workspace_bytes(const co3_plan *plan);
 int co3_model_bias_device(const co3_plan *plan, const co3_gennorm_params *params, int32_t *bias,
-                          double *error, void *stream);
+                          double *error, void *workspace, size_t workspace_bytes, void *stream);
 int co3_plan_set_bias_device(co3_plan *plan, const int32_t *bias, void *stream);
 int co3_bias_from_model(co3_format format, double mu, double alpha, double beta, int32_t *bias,
                         double *error);

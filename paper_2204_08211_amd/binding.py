@@ -27,6 +27,7 @@ EXPORTS = [
     "co3_codebook_destroy", "co3_encode", "co3_decode", "co3_ps_aggregate", "co3_status_string",
     "co3_profile_begin", "co3_profile_end", "co3_gennorm_weights", "co3_plan_fit_workspace_bytes", "co3_gennorm_fit",
     "co3_model_weights_device", "co3_model_bias_device", "co3_plan_set_bias_device", "co3_bias_from_model",
+    "co3_plan_bias_workspace_bytes",
 ]
 
 
@@ -88,7 +89,8 @@ def lib():
         L.co3_plan_destroy.restype = None
         for name, rt in [("co3_plan_num_chunks", C.c_uint64), ("co3_plan_num_books", C.c_uint32),
                          ("co3_plan_alphabet", C.c_uint32), ("co3_plan_symbols_bytes", C.c_size_t),
-                         ("co3_plan_workspace_bytes", C.c_size_t), ("co3_plan_fit_workspace_bytes", C.c_size_t)]:
+                         ("co3_plan_workspace_bytes", C.c_size_t), ("co3_plan_fit_workspace_bytes", C.c_size_t),
+                         ("co3_plan_bias_workspace_bytes", C.c_size_t)]:
             getattr(L, name).argtypes = [C.c_void_p]
             getattr(L, name).restype = rt
         L.co3_plan_stream_words.argtypes = [C.c_void_p, C.c_uint32]
@@ -108,7 +110,8 @@ def lib():
         L.co3_gennorm_fit.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_float, C.c_void_p, C.c_void_p,
                                       C.c_size_t, C.c_void_p]
         L.co3_model_weights_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
-        L.co3_model_bias_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.co3_model_bias_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                            C.c_void_p]
         L.co3_plan_set_bias_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.co3_bias_from_model.argtypes = [Format, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_int32),
                                           C.POINTER(C.c_double)]
@@ -282,8 +285,10 @@ def co3_model_bias_device(plan, params, install=True, stream=None):
     import torch
     bias = torch.zeros((plan.U, plan.nseg), dtype=torch.int32, device=params.device)
     err = torch.zeros((plan.U, plan.nseg), dtype=torch.float64, device=params.device)
+    ws = torch.empty(int(lib().co3_plan_bias_workspace_bytes(plan.handle)), dtype=torch.uint8, device=params.device)
     _check("co3_model_bias_device",
-           lib().co3_model_bias_device(plan.handle, params.data_ptr(), bias.data_ptr(), err.data_ptr(), _stream(stream)))
+           lib().co3_model_bias_device(plan.handle, params.data_ptr(), bias.data_ptr(), err.data_ptr(), ws.data_ptr(),
+                                       ws.numel(), _stream(stream)))
     if install:
         _check("co3_plan_set_bias_device", lib().co3_plan_set_bias_device(plan.handle, bias.data_ptr(), _stream(stream)))
     return bias, err

@@ -297,12 +297,17 @@ int co3_model_weights_device(const co3_plan *plan, const co3_gennorm_params *par
                : CO3_ERR_HIP;
 }
 
+size_t co3_plan_bias_workspace_bytes(const co3_plan *plan) { return plan ? bias_workspace_bytes(plan->lay) : 0; }
+
 int co3_model_bias_device(const co3_plan *plan, const co3_gennorm_params *params, int32_t *bias, double *error,
-                          void *stream)
+                          void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!plan || !params || !bias) return CO3_ERR_ARG;
+    if (!plan || !params || !bias || !workspace) return CO3_ERR_ARG;
+    if (workspace_bytes < bias_workspace_bytes(plan->lay)) return CO3_ERR_CAPACITY;
+    if (plan->lay.nseg > 65535u || plan->lay.U > 65535u) return CO3_ERR_ARG;  // grid.y, grid.z
     DeviceGuard guard(plan->device);
-    return launch_model_bias(plan->lay, params, bias, error, static_cast<hipStream_t>(stream)) == hipSuccess
+    double *ws = reinterpret_cast<double *>((reinterpret_cast<uintptr_t>(workspace) + 255u) & ~(uintptr_t)255u);
+    return launch_model_bias(plan->lay, params, bias, error, ws, static_cast<hipStream_t>(stream)) == hipSuccess
                ? CO3_OK
                : CO3_ERR_HIP;
 }

@@ -123,8 +123,9 @@ hipError_t launch_fit(const Layout &lay, const float *g, const float *m, uint64_
                       co3_gennorm_params *params, double *partial, hipStream_t s);
 hipError_t launch_model_weights(const Layout &lay, const co3_gennorm_params *params, uint64_t *weights,
                                 hipStream_t s);
+size_t bias_workspace_bytes(const Layout &lay);
 hipError_t launch_model_bias(const Layout &lay, const co3_gennorm_params *params, int32_t *bias, double *error,
-                             hipStream_t s);
+                             double *errors_ws, hipStream_t s);
 hipError_t launch_decode(const Layout &lay, const co3_decode_args &a, const BookDev *books, hipStream_t s);
 hipError_t launch_aggregate(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
                             hipStream_t s);

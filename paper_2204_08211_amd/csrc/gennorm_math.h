@@ -130,23 +130,27 @@ CO3_HD inline double interval_moment(int k, double a, double b, double alpha, do
     return (k & 1) ? pos - neg : pos + neg;
 }
 
-// E (Q_fp(X) - X)^2 for X ~ GenNorm(mu, alpha, beta) and one exponent bias: the objective of
-// eq. (exp bias), Sec. IV-A (i), summed over the cells of the representatives.
+// Share of symbol s in E (Q_fp(X) - X)^2 for X ~ GenNorm(mu, alpha, beta) and one exponent bias:
+// the integral of (x - r)^2 f(x) over the cell of its representative r (0 if Q_fp cannot produce s).
+CO3_HD inline double sq_error_of_symbol(uint32_t s, int E, int M, int bias, double mu, double alpha, double beta)
+{
+    double lo, hi;
+    if (!symbol_cell(s, E, M, bias, &lo, &hi)) return 0.0;
+    const int k = (int)(s & ((1u << (E + M)) - 1u));
+    const double r = ((s >> (E + M)) & 1u) ? -magnitude_of_code(k, M, bias) : magnitude_of_code(k, M, bias);
+    const double c = r - mu, a = lo - mu, b = hi - mu;
+    const double j0 = interval_moment(0, a, b, alpha, beta);
+    const double j1 = interval_moment(1, a, b, alpha, beta);
+    const double j2 = interval_moment(2, a, b, alpha, beta);
+    return j2 - 2.0 * c * j1 + c * c * j0;
+}
+
+// E (Q_fp(X) - X)^2: the objective of eq. (exp bias), Sec. IV-A (i), summed over the symbols.
 CO3_HD inline double expected_sq_error(int E, int M, int bias, double mu, double alpha, double beta)
 {
     const uint32_t A = 1u << (1 + E + M);
     double total = 0.0;
-    for (uint32_t s = 0; s < A; ++s) {
-        double lo, hi;
-        if (!symbol_cell(s, E, M, bias, &lo, &hi)) continue;
-        const int k = (int)(s & ((1u << (E + M)) - 1u));
-        const double r = ((s >> (E + M)) & 1u) ? -magnitude_of_code(k, M, bias) : magnitude_of_code(k, M, bias);
-        const double c = r - mu, a = lo - mu, b = hi - mu;
-        const double j0 = interval_moment(0, a, b, alpha, beta);
-        const double j1 = interval_moment(1, a, b, alpha, beta);
-        const double j2 = interval_moment(2, a, b, alpha, beta);
-        total += j2 - 2.0 * c * j1 + c * c * j0;
-    }
+    for (uint32_t s = 0; s < A; ++s) total += sq_error_of_symbol(s, E, M, bias, mu, alpha, beta);
     return total;
 }
 

@@ -169,46 +169,67 @@ __global__ __launch_bounds__(kMaxA) void k_model_weights(Layout lay, const co3_g
     weights[(uint64_t)b * lay.A + s] = w;
 }
 
-// Exponent bias from the model, eq. (exp bias) with integer b: workgroup per (user, layer), thread
-// per candidate bias; the smallest bias whose error is within kBiasTie of the minimum wins (a format
-// with many binades has a plateau of equally good biases; the smallest has the most headroom).
-// A layer without a model (alpha = 0) gets the IEEE bias 2^(exp-1) - 1.
-constexpr int kBiasThreads = 256;
-__global__ __launch_bounds__(kBiasThreads) void k_model_bias(Layout lay, const co3_gennorm_params *__restrict__ params,
-                                                             int32_t *__restrict__ bias_out,
-                                                             double *__restrict__ error_out)
+// Exponent bias from the model, eq. (exp bias) with integer b.
+//   k_model_bias_errors  workgroup per (candidate bias, layer, user), thread per symbol: every thread
+//                        integrates (x - r)^2 f(x) over its symbol's cell, the workgroup folds the
+//                        shares in a fixed order -> expected squared error of the candidate
+//   k_model_bias_pick    per (user, layer): the smallest bias whose error is within kBiasTie of the
+//                        minimum (a format with many binades has a plateau of equally good biases;
+//                        the smallest has the most headroom).  No model (alpha = 0): the IEEE bias.
+constexpr int kBiasSlots = 256;  // error slots per (user, layer); candidates: at most 226
+__global__ __launch_bounds__(kMaxA) void k_model_bias_errors(Layout lay, const co3_gennorm_params *__restrict__ params,
+                                                             double *__restrict__ errors)
 {
-    __shared__ double s_err[kBiasThreads];
-    const uint32_t seg = blockIdx.x, u = blockIdx.y, t = threadIdx.x;
+    __shared__ double s_red[kMaxA];
+    const uint32_t cand = blockIdx.x, seg = blockIdx.y, u = blockIdx.z, t = threadIdx.x;
     const co3_gennorm_params p = params[(uint64_t)u * lay.nseg + seg];
-    const int b0 = bias_min_supported(lay.E);
-    const int ncand = kBiasMax - b0 + 1;  // at most 226
     const bool model = p.alpha > 0.0 && p.beta > 0.0;
-    double e = INFINITY;
-    if (model && (int)t < ncand) e = expected_sq_error(lay.E, lay.M, b0 + (int)t, p.mu, p.alpha, p.beta);
-    s_err[t] = e;
+    double e = 0.0;
+    if (model && t < lay.A)
+        e = sq_error_of_symbol(t, lay.E, lay.M, bias_min_supported(lay.E) + (int)cand, p.mu, p.alpha, p.beta);
+    s_red[t] = e;
     __syncthreads();
-    if (t != 0) return;
-    int best = (1 << (lay.E - 1)) - 1;
-    double best_err = 0.0;
-    if (model) {
-        double lowest = INFINITY;
-        for (int i = 0; i < ncand; ++i) lowest = s_err[i] < lowest ? s_err[i] : lowest;
-        const double limit = lowest * (1.0 + kBiasTie);
-        for (int i = 0; i < ncand; ++i) {
-            if (s_err[i] <= limit) { best = b0 + i; best_err = s_err[i]; break; }
-        }
+    for (int o = kMaxA / 2; o > 0; o >>= 1) {
+        if (t < (uint32_t)o) s_red[t] += s_red[t + o];
+        __syncthreads();
     }
-    bias_out[(uint64_t)u * lay.nseg + seg] = best;
-    if (error_out) error_out[(uint64_t)u * lay.nseg + seg] = best_err;
+    if (t == 0) errors[((uint64_t)u * lay.nseg + seg) * kBiasSlots + cand] = model ? s_red[0] : INFINITY;
 }
 
+__global__ __launch_bounds__(64) void k_model_bias_pick(Layout lay, const double *__restrict__ errors,
+                                                        int32_t *__restrict__ bias_out, double *__restrict__ error_out)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;  // (user, layer) pair
+    if (i >= (uint64_t)lay.U * lay.nseg) return;
+    const double *err = errors + i * kBiasSlots;
+    const int b0 = bias_min_supported(lay.E);
+    const int ncand = kBiasMax - b0 + 1;
+    int best = (1 << (lay.E - 1)) - 1;
+    double best_err = 0.0, lowest = INFINITY;
+    for (int c = 0; c < ncand; ++c) lowest = err[c] < lowest ? err[c] : lowest;
+    if (lowest < INFINITY) {
+        const double limit = lowest * (1.0 + kBiasTie);
+        for (int c = 0; c < ncand; ++c) {
+            if (err[c] <= limit) { best = b0 + c; best_err = err[c]; break; }
+        }
+    }
+    bias_out[i] = best;
+    if (error_out) error_out[i] = best_err;
+}
+
+size_t bias_workspace_bytes(const Layout &lay) { return (size_t)lay.U * lay.nseg * kBiasSlots * sizeof(double) + 256; }
+
 hipError_t launch_model_bias(const Layout &lay, const co3_gennorm_params *params, int32_t *bias, double *error,
-                             hipStream_t s)
+                             double *errors_ws, hipStream_t s)
 {
     if (lay.U == 0) return hipSuccess;
+    const int ncand = kBiasMax - bias_min_supported(lay.E) + 1;
     ProfScope prof(K_MODEL_BIAS, s);
-    hipLaunchKernelGGL(k_model_bias, dim3(lay.nseg, lay.U), dim3(kBiasThreads), 0, s, lay, params, bias, error);
+    hipLaunchKernelGGL(k_model_bias_errors, dim3((uint32_t)ncand, lay.nseg, lay.U), dim3(kMaxA), 0, s, lay, params,
+                       errors_ws);
+    const uint64_t pairs = (uint64_t)lay.U * lay.nseg;
+    hipLaunchKernelGGL(k_model_bias_pick, dim3((uint32_t)((pairs + 63) / 64)), dim3(64), 0, s, lay, errors_ws, bias,
+                       error);
     return hipGetLastError();
 }
 
