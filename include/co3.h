@@ -233,12 +233,18 @@ typedef struct {
     const uint64_t *chunk_offset;
     const uint16_t *sub_bits;
     const co3_codebook *books;
-    float *out;                   /* device [d]: (1/U) sum_u ghat^(u)                         */
+    float *out;                   /* device [d]: (1/U) sum_u ghat^(u); may be NULL if model is set */
     uint64_t *status;
+    float *model;                 /* device [d] or NULL: w, updated in place (see below)          */
+    float eta;                    /* learning rate of the update                                  */
+    int32_t reserved;
 } co3_aggregate_args;
 
 /* Decode all U streams and average them (eq. (aggregate hat) without the learning rate):
- * out[i] = fl32((sum over u = 0..U-1, in fp64, of ghat_i^(u)) * (1.0 / U)).                 */
+ * out[i] = fl32((sum over u = 0..U-1, in fp64, of ghat_i^(u)) * (1.0 / U)).
+ * With `model`, also the PS model update of eq. (aggregate hat) / Algorithm 1 line 14 in the same
+ * pass: model[i] = fl32(model[i] - eta * ((sum over u) * (1.0 / U))), products and difference in
+ * fp64, one rounding.                                                                        */
 int co3_ps_aggregate(const co3_plan *plan, const co3_aggregate_args *args, void *stream);
 
 /* ---- measurement aid ---------------------------------------------------------------------

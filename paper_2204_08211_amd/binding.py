@@ -59,7 +59,8 @@ class DecodeArgs(C.Structure):
 
 class AggregateArgs(C.Structure):
     _fields_ = [("words", C.c_void_p), ("words_stride", C.c_uint64), ("chunk_offset", C.c_void_p),
-                ("sub_bits", C.c_void_p), ("books", C.c_void_p), ("out", C.c_void_p), ("status", C.c_void_p)]
+                ("sub_bits", C.c_void_p), ("books", C.c_void_p), ("out", C.c_void_p), ("status", C.c_void_p),
+                ("model", C.c_void_p), ("eta", C.c_float), ("reserved", C.c_int32)]
 
 
 class KernelTime(C.Structure):
@@ -350,9 +351,14 @@ def co3_decode(plan, books, buf, symbols=None, q=None, stream=None):
     _check("co3_decode", lib().co3_decode(plan.handle, C.byref(a), _stream(stream)))
 
 
-def co3_ps_aggregate(plan, books, buf, out, stream=None):
-    """PS side: out[d] = (1/U) sum_u ghat^(u) decoded from the streams in `buf`."""
-    assert out.numel() >= plan.d
+def co3_ps_aggregate(plan, books, buf, out, stream=None, model=None, eta=0.0):
+    """PS side: out[d] = (1/U) sum_u ghat^(u) decoded from the streams in `buf`; with `model` (float32
+    device tensor [d]) also model -= eta * that average (Algorithm 1 line 14), in the same pass.  `out`
+    may be None when `model` is given."""
+    assert out is not None or model is not None
+    assert out is None or out.numel() >= plan.d
+    assert model is None or (model.numel() >= plan.d and model.is_contiguous())
     a = AggregateArgs(buf.words.data_ptr(), buf.words_stride, buf.chunk_offset.data_ptr(), buf.sub_bits.data_ptr(),
-                      books.handle, out.data_ptr(), buf.status.data_ptr())
+                      books.handle, None if out is None else out.data_ptr(), buf.status.data_ptr(),
+                      None if model is None else model.data_ptr(), float(np.float32(eta)), 0)
     _check("co3_ps_aggregate", lib().co3_ps_aggregate(plan.handle, C.byref(a), _stream(stream)))

@@ -340,7 +340,8 @@ int co3_ps_aggregate(const co3_plan *plan, const co3_aggregate_args *a, void *st
 {
     if (!plan || !a) return CO3_ERR_ARG;
     const Layout &lay = plan->lay;
-    if (!a->words || !a->chunk_offset || !a->sub_bits || !a->status || !a->out) return CO3_ERR_ARG;
+    if (!a->words || !a->chunk_offset || !a->sub_bits || !a->status || (!a->out && !a->model)) return CO3_ERR_ARG;
+    if (a->model && !(a->eta == a->eta)) return CO3_ERR_ARG;
     int rc = check_books(plan, a->books);
     if (rc != CO3_OK) return rc;
     DeviceGuard guard(plan->device);

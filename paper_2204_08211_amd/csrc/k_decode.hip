@@ -338,6 +338,7 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
                                                       const uint64_t *__restrict__ chunk_offset,
                                                       const uint16_t *__restrict__ sub_bits,
                                                       const BookDev *__restrict__ books, float *__restrict__ out,
+                                                      float *__restrict__ model, float eta,
                                                       uint64_t *__restrict__ status)
 {
     extern __shared__ uint64_t smem64[];
@@ -399,21 +400,38 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
         }
         __syncthreads();
     }
+    // average, and with `model` the PS update w - eta * average (eq. (aggregate hat), Algorithm 1
+    // line 14): products and difference in fp64, one rounding
     const double inv_u = 1.0 / (double)lay.U;
-    float *dst = out + g.e0;
-    const bool vec_ok = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
+    const double eta64 = (double)eta;
+    const uintptr_t out_addr = out ? reinterpret_cast<uintptr_t>(out + g.e0) : 0u;
+    const uintptr_t model_addr = model ? reinterpret_cast<uintptr_t>(model + g.e0) : 0u;
+    const bool vec_ok = ((out_addr | model_addr) & 15u) == 0;
 #pragma unroll
     for (int i = 0; i < G; ++i) {
         const uint32_t e = 4u * (t + (uint32_t)i * T);
-        float r[4];
+        double avg[4];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) r[b] = (float)(acc[i][b] * inv_u);
+        for (int b = 0; b < 4; ++b) avg[b] = acc[i][b] * inv_u;
         if (vec_ok && e + 3 < g.n) {
-            *reinterpret_cast<float4 *>(dst + e) = make_float4(r[0], r[1], r[2], r[3]);
+            if (out)
+                *reinterpret_cast<float4 *>(out + g.e0 + e) =
+                    make_float4((float)avg[0], (float)avg[1], (float)avg[2], (float)avg[3]);
+            if (model) {
+                float4 w = *reinterpret_cast<const float4 *>(model + g.e0 + e);
+                w.x = (float)((double)w.x - eta64 * avg[0]);
+                w.y = (float)((double)w.y - eta64 * avg[1]);
+                w.z = (float)((double)w.z - eta64 * avg[2]);
+                w.w = (float)((double)w.w - eta64 * avg[3]);
+                *reinterpret_cast<float4 *>(model + g.e0 + e) = w;
+            }
         } else {
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
-                if (e + b < g.n) dst[e + b] = r[b];
+            for (int b = 0; b < 4; ++b) {
+                if (e + b >= g.n) continue;
+                if (out) out[g.e0 + e + b] = (float)avg[b];
+                if (model) model[g.e0 + e + b] = (float)((double)model[g.e0 + e + b] - eta64 * avg[b]);
+            }
         }
     }
 }
@@ -439,7 +457,7 @@ static hipError_t launch_aggregate_w(const Layout &lay, const co3_aggregate_args
     if (e != hipSuccess) return e;
     ProfScope prof(K_AGGREGATE, s);
     hipLaunchKernelGGL(k_aggregate<W>, dim3((uint32_t)lay.nchunks), dim3(64 * W), lds, s, lay, a.words,
-                       a.words_stride, a.chunk_offset, a.sub_bits, books, a.out, a.status);
+                       a.words_stride, a.chunk_offset, a.sub_bits, books, a.out, a.model, a.eta, a.status);
     return hipGetLastError();
 }
 

@@ -287,3 +287,42 @@ def test_single_sweep_capacity_and_nocode():
     w[0, third] = 0
     gpu, _ = gu.gpu_round(kw, g, m, 0.5, BOOK_FIXED, weights=w, want_decode=False, single_sweep=True)
     assert int(gpu["status_encode"][2]) == int(ref["hist"][0][third])
+
+
+# ---- PS model update fused into the average (Algorithm 1 line 14) -------------------------------
+
+@pytest.mark.parametrize("U,eta,with_out", [(1, 1.0, True), (3, 0.1, True), (10, 0.05, False), (16, 0.3, True)])
+def test_ps_model_update(U, eta, with_out):
+    import torch
+    from paper_2204_08211_amd import binding as B
+    E, M = 4, 3
+    seg_len = [4096 * 2 + 5, 0, 3000, 4096]
+    seg_book = [0, 1, 1, 0]
+    d = sum(seg_len)
+    rng = np.random.default_rng(50 + U)
+    bias = rng.integers(12, 18, (U, len(seg_len))).astype(np.int32)
+    g = np.empty((U, d), np.float32)
+    off = 0
+    for k, n in enumerate(seg_len):
+        for u in range(U):
+            g[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, orc.grid(E, M, int(bias[u, k]))[-1] / 10)
+        off += n
+    m = np.zeros_like(g)
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias, seg_len=seg_len, seg_book=seg_book)
+    gpu, (plan, books, buf, gt, mt) = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL)
+    ref = gu.oracle_round(kw, g, m, 0.9)
+    gu.compare_round(gpu, ref, d)
+    w0 = rng.normal(0, 1e-2, d).astype(np.float32)
+    w_ref = orc.model_update(ref["dec_sym"], seg_len, bias, E, M, eta, w0)
+    w_t = torch.from_numpy(w0.copy()).to(gt.device)
+    out = torch.full((d,), float("nan"), dtype=torch.float32, device=gt.device) if with_out else None
+    B.co3_ps_aggregate(plan, books, buf, out, model=w_t, eta=eta)
+    torch.cuda.synchronize()
+    gu.assert_bits_equal(w_t.cpu().numpy(), w_ref, "updated model")
+    if with_out:
+        gu.assert_bits_equal(out.cpu().numpy(), ref["avg"], "PS average")
+    # two steps in a row equal two oracle steps
+    B.co3_ps_aggregate(plan, books, buf, out, model=w_t, eta=eta)
+    torch.cuda.synchronize()
+    gu.assert_bits_equal(w_t.cpu().numpy(), orc.model_update(ref["dec_sym"], seg_len, bias, E, M, eta, w_ref),
+                         "model after two updates")
