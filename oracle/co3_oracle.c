@@ -220,6 +220,92 @@ int co3o_ef_step(const float *g, const float *m, uint64_t n, float gamma,
     return CO3O_OK;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Stochastic fp conversion (Sec. II-B (ii): "the mapping Q is meant as a     */
+/* stochastic mapping, so that non-subtractive dither quantization can be     */
+/* implemented"), reading R15: v goes to one of its two neighbours in X, the  */
+/* upper one with probability (|v| - lo) / (hi - lo), decided by adding a     */
+/* uniform integer dither to the position of |v| between them and truncating. */
+/* The dither has as many bits as fp32 resolves between the neighbours        */
+/* (23 - mant in the normal range) and 24 bits in the zero/subnormal row,     */
+/* where the position is first truncated to 24 fractional bits.  Random bits: */
+/* Philox4x32-10 (Salmon et al., SC'11), counter (i/4 low, i/4 high, user, 0) */
+/* with i the element index within the user, key = the 64-bit seed; element i */
+/* takes output word i mod 4.                                                 */
+/* ------------------------------------------------------------------------- */
+void co3o_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1, n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+static float quantize_one_sr(const double *mag, int nmag, int mant_bits, int sign_shift, float v,
+                             uint32_t rnd, uint32_t *code, int *flags)
+{
+    *flags = 0;
+    if (isnan(v)) { *code = 0; *flags = 1; return 0.0f; }
+    double a = fabs((double)v);
+    int k;
+    if (a >= mag[nmag - 1]) {
+        k = nmag - 1;
+        if (isinf(v)) *flags = 1;
+        else if (a > mag[nmag - 1]) *flags = 2;
+    } else {
+        int lo = 0, hi = nmag - 1;            /* mag[lo] <= a < mag[hi]      */
+        while (hi - lo > 1) {
+            int mid = (lo + hi) / 2;
+            if (mag[mid] <= a) lo = mid; else hi = mid;
+        }
+        double pos = (a - mag[lo]) / (mag[hi] - mag[lo]);   /* in [0, 1), exact */
+        int bits = (lo < (1 << mant_bits)) ? 24 : 23 - mant_bits;   /* zero/subnormal row : normal range */
+        double scale = ldexp(1.0, bits);
+        double units = floor(pos * scale);    /* exact already in the normal range */
+        double dither = (double)(rnd >> (32 - bits));
+        k = (units + dither >= scale) ? hi : lo;
+    }
+    uint32_t s = (signbit(v) && k != 0) ? 1u : 0u;
+    *code = (s << sign_shift) | (uint32_t)k;
+    double q = s ? -mag[k] : mag[k];
+    return (float)q;
+}
+
+/* Algorithm 1 lines 8 and 10 with the stochastic conversion.  `user` and     */
+/* `elem0` (index of g[0] within the user's vector) select the random words.  */
+int co3o_ef_step_sr(const float *g, const float *m, uint64_t n, float gamma,
+                    int exp_bits, int mant_bits, int bias, uint32_t user, uint64_t elem0, uint64_t seed,
+                    float *m_out, uint8_t *sym, float *q_out, uint64_t *counters)
+{
+    if (1 + exp_bits + mant_bits > 8) return CO3O_ERR_FORMAT;
+    int nmag = co3o_num_magnitudes(exp_bits, mant_bits);
+    double mag[256];
+    int rc = co3o_grid(exp_bits, mant_bits, bias, mag);
+    if (rc < 0) return rc;
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    for (uint64_t i = 0; i < n; ++i) {
+        uint64_t e = elem0 + i;
+        uint32_t ctr[4] = {(uint32_t)(e >> 2), (uint32_t)((e >> 2) >> 32), user, 0u}, r[4];
+        co3o_philox4x32_10(ctr, key, r);
+        volatile float t = gamma * m[i];
+        volatile float v = g[i] + t;
+        int fl; uint32_t c;
+        float q = quantize_one_sr(mag, nmag, mant_bits, exp_bits + mant_bits, v, r[e & 3u], &c, &fl);
+        volatile float err = v - q;
+        if (fl & 1) err = 0.0f;
+        if (counters) { counters[0] += (fl & 1); counters[1] += (fl >> 1) & 1; }
+        sym[i] = (uint8_t)c;
+        m_out[i] = err;
+        if (q_out) q_out[i] = q;
+    }
+    return CO3O_OK;
+}
+
 /* Symbol counts (the "distribution of the data source" that Huffman coding
  * requires, Sec. IV-A (ii)); adds into hist[0..A).                          */
 void co3o_histogram(const uint8_t *sym, uint64_t n, uint64_t *hist)

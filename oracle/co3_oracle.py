@@ -92,6 +92,34 @@ def ef_step(g, m, gamma, E, M, bias, want_q=True):
     return m_out, sym, q, counters
 
 
+def philox4x32_10(counter, key):
+    """Philox4x32-10 of Salmon et al. (SC'11): four 32-bit counter words, two key words -> four words."""
+    c = (C.c_uint32 * 4)(*[int(x) & 0xffffffff for x in counter])
+    k = (C.c_uint32 * 2)(*[int(x) & 0xffffffff for x in key])
+    o = (C.c_uint32 * 4)()
+    lib().co3o_philox4x32_10(c, k, o)
+    return [int(x) for x in o]
+
+
+def ef_step_sr(g, m, gamma, E, M, bias, user, elem0, seed, want_q=True):
+    """Algorithm 1 lines 8 and 10 with the stochastic fp conversion (Sec. II-B (ii)); see the C file for the
+    reading.  Returns (m_new, sym, q, counters[2])."""
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    m = np.ascontiguousarray(m, dtype=np.float32)
+    n = g.size
+    m_out = np.empty(n, dtype=np.float32)
+    sym = np.empty(n, dtype=np.uint8)
+    q = np.empty(n, dtype=np.float32) if want_q else None
+    cnt = np.zeros(2, dtype=np.uint64)
+    rc = lib().co3o_ef_step_sr(_p(g, C.c_float), _p(m, C.c_float), C.c_uint64(n), C.c_float(float(np.float32(gamma))),
+                               C.c_int(E), C.c_int(M), C.c_int(int(bias)), C.c_uint32(int(user)), C.c_uint64(int(elem0)),
+                               C.c_uint64(int(seed)), _p(m_out, C.c_float), _p(sym, C.c_uint8),
+                               _p(q, C.c_float) if want_q else None, _p(cnt, C.c_uint64))
+    if rc != 0:
+        raise ValueError(f"co3o_ef_step_sr: {rc}")
+    return m_out, sym, q, cnt
+
+
 def histogram(sym, A, hist=None):
     sym = np.ascontiguousarray(sym, dtype=np.uint8)
     if hist is None:

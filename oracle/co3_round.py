@@ -7,9 +7,11 @@ import numpy as np
 from . import co3_oracle as orc
 
 
-def encode_round(g, m, gamma, E, M, seg_len, seg_book, bias, per_user_books=False, weights=None, timings=None):
+def encode_round(g, m, gamma, E, M, seg_len, seg_book, bias, per_user_books=False, weights=None, timings=None,
+                 stochastic_seed=None):
     """g, m: float32 [U, d]; bias: int [U, nseg]; weights: None = build the code from this round's
-    histogram (pooled over users per table id, or per user), else uint64 [nbooks, A] fixed weights.
+    histogram (pooled over users per table id, or per user), else uint64 [nbooks, A] fixed weights;
+    stochastic_seed: None = closest representative, else the stochastic conversion with that seed.
 
     Returns a dict with m_new, sym, hist, lens, codes, words (list per user), chunk_offset,
     sub_bits, payload_bits, counters."""
@@ -32,8 +34,12 @@ def encode_round(g, m, gamma, E, M, seg_len, seg_book, bias, per_user_books=Fals
         off = 0
         for k, n in enumerate(seg_len):
             t0 = time.perf_counter()
-            mo, s, _, cnt = orc.ef_step(g[u, off:off + n], m[u, off:off + n], gamma, E, M, int(bias[u, k]),
-                                        want_q=False)
+            if stochastic_seed is None:
+                mo, s, _, cnt = orc.ef_step(g[u, off:off + n], m[u, off:off + n], gamma, E, M, int(bias[u, k]),
+                                            want_q=False)
+            else:
+                mo, s, _, cnt = orc.ef_step_sr(g[u, off:off + n], m[u, off:off + n], gamma, E, M, int(bias[u, k]),
+                                               u, off, stochastic_seed, want_q=False)
             tick("ef_quantize", t0)
             m_new[u, off:off + n] = mo; sym[u, off:off + n] = s; counters += cnt
             t0 = time.perf_counter()
