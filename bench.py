@@ -45,6 +45,8 @@ def parse():
     p.add_argument("--book", default="model", choices=["empirical", "model"])
     p.add_argument("--model-encoder", default="sweep", choices=["sweep", "three"],
                    help="encoder for --book model: the single-sweep kernel (symbols never stored) or the three-step one")
+    p.add_argument("--stochastic", action="store_true",
+                   help="stochastic fp conversion (dithered Q) instead of the closest representative; a new seed per step")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-other-book", action="store_true", help="measure only the headline code-table mode")
     p.add_argument("--ignore-status", action="store_true", help="tuning runs only: do not stop on codec error counters")
@@ -139,7 +141,7 @@ def main():
     def measure(books, mode, label, single_sweep=False):
         def step():
             B.co3_encode(plan, books, pool[counter[0] % a.pool], m, m, w.gamma, buf, mode=mode,
-                         single_sweep=single_sweep)
+                         single_sweep=single_sweep, stochastic_seed=(1000 + counter[0]) if a.stochastic else None)
             B.co3_ps_aggregate(plan, books, buf, out)
             counter[0] += 1
         for _ in range(a.warmup):

@@ -183,6 +183,13 @@ int co3_bias_from_model(co3_format format, double mu, double alpha, double beta,
  * the library runs the single-sweep encoder, in which the symbols never reach device memory
  * (12 bytes of traffic per element plus the stream).                                        */
 enum { CO3_BOOK_FIXED = 0, CO3_BOOK_EMPIRICAL = 1 };
+/* Q_fp picks the closest representative (Sec. IV-A (i)), or, as the stochastic mapping Sec. II-B
+ * (ii) allows (non-subtractive dither), the upper of the two neighbours with probability
+ * (|v| - lo) / (hi - lo): a uniform integer dither is added to the position of |v| between them
+ * (its low 23 - mant_bits fp32 pattern bits in the normal range; 24 fractional bits of
+ * |v| / 2^(1 - bias - mant_bits) in the zero/subnormal row) and the result truncated.  Element i
+ * of user u uses word i mod 4 of Philox4x32-10(counter = (i/4 low, i/4 high, u, 0), key = seed). */
+enum { CO3_ROUND_NEAREST = 0, CO3_ROUND_STOCHASTIC = 1 };
 
 typedef struct {
     const float *g;          /* device [U][row_stride] gradients; 16-byte aligned            */
@@ -203,6 +210,9 @@ typedef struct {
     uint64_t *status;        /* device [CO3_STATUS_WORDS] counters (added to)                */
     void *workspace;         /* device, co3_plan_workspace_bytes()                           */
     size_t workspace_bytes;
+    int32_t rounding;        /* CO3_ROUND_NEAREST or CO3_ROUND_STOCHASTIC                    */
+    int32_t reserved;
+    uint64_t seed;           /* key of the dither generator (vary it from round to round)    */
 } co3_encode_args;
 
 /* Enqueues the whole user side on `stream`.  Stream words beyond a user's last chunk are not

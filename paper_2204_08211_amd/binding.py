@@ -48,7 +48,8 @@ class EncodeArgs(C.Structure):
                 ("gamma", C.c_float), ("mode", C.c_int32), ("books", C.c_void_p), ("symbols", C.c_void_p),
                 ("hist", C.c_void_p), ("words", C.c_void_p), ("words_stride", C.c_uint64),
                 ("chunk_offset", C.c_void_p), ("sub_bits", C.c_void_p), ("payload_bits", C.c_void_p),
-                ("status", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+                ("status", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("rounding", C.c_int32), ("reserved", C.c_int32), ("seed", C.c_uint64)]
 
 
 class DecodeArgs(C.Structure):
@@ -327,10 +328,15 @@ class RoundBuffers:
         return self.symbols[:p.U * p.sym_stride].view(p.U, p.sym_stride)[:, :p.d]
 
 
-def co3_encode(plan, books, g, m, m_out, gamma, buf, mode=BOOK_EMPIRICAL, stream=None, single_sweep=False):
+ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
+
+
+def co3_encode(plan, books, g, m, m_out, gamma, buf, mode=BOOK_EMPIRICAL, stream=None, single_sweep=False,
+               stochastic_seed=None):
     """User side of one round for all U users (Algorithm 1 lines 8-10).  g, m, m_out are float32
     device tensors [U][row_stride]; outputs land in `buf` (RoundBuffers).  single_sweep (fixed code
-    only) passes no symbols and no hist buffer, which selects the library's single-sweep encoder."""
+    only) passes no symbols and no hist buffer, which selects the library's single-sweep encoder.
+    stochastic_seed: None = closest representative, else the stochastic conversion keyed by that seed."""
     assert not single_sweep or mode == BOOK_FIXED
     assert g.dim() == 2 and g.shape == m.shape == m_out.shape and g.stride(1) == 1
     assert g.stride(0) == m.stride(0) == m_out.stride(0)
@@ -339,7 +345,8 @@ def co3_encode(plan, books, g, m, m_out, gamma, buf, mode=BOOK_EMPIRICAL, stream
                    None if single_sweep else buf.hist.data_ptr(), buf.words.data_ptr(),
                    buf.words_stride, buf.chunk_offset.data_ptr(), buf.sub_bits.data_ptr(),
                    buf.payload_bits.data_ptr(), buf.status.data_ptr(), buf.workspace.data_ptr(),
-                   buf.workspace.numel())
+                   buf.workspace.numel(), ROUND_NEAREST if stochastic_seed is None else ROUND_STOCHASTIC, 0,
+                   0 if stochastic_seed is None else int(stochastic_seed) & 0xffffffffffffffff)
     _check("co3_encode", lib().co3_encode(plan.handle, C.byref(a), _stream(stream)))
 
 

@@ -241,6 +241,7 @@ int co3_encode(const co3_plan *plan, const co3_encode_args *a, void *stream)
         !a->status || !a->workspace)
         return CO3_ERR_ARG;
     if (a->mode != CO3_BOOK_FIXED && a->mode != CO3_BOOK_EMPIRICAL) return CO3_ERR_ARG;
+    if (a->rounding != CO3_ROUND_NEAREST && a->rounding != CO3_ROUND_STOCHASTIC) return CO3_ERR_ARG;
     // symbols and hist come as a pair; without them a fixed code is encoded in a single sweep
     const bool single_sweep = a->mode == CO3_BOOK_FIXED && !a->symbols && !a->hist;
     if (!single_sweep && (!a->symbols || !a->hist)) return CO3_ERR_ARG;

@@ -73,9 +73,12 @@ __device__ inline void fu_lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// kSR: the stochastic conversion (dither from Philox words of (element, user, seed)) instead of
+// the closest representative.
+template <bool kSR>
 __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
     Layout lay, const float *__restrict__ g, const float *m, float *m_out, uint64_t row_stride, float gamma,
-    const BookDev *__restrict__ books, uint32_t *__restrict__ tickets, uint64_t *lb_state, uint32_t nblk,
+    uint64_t seed, const BookDev *__restrict__ books, uint32_t *__restrict__ tickets, uint64_t *lb_state, uint32_t nblk,
     uint32_t spin_limit, uint64_t *__restrict__ chunk_offset, uint16_t *__restrict__ sub_bits,
     uint64_t *__restrict__ payload_bits, uint32_t *__restrict__ words, uint64_t words_stride,
     uint64_t *__restrict__ status)
@@ -122,7 +125,8 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
     if (active) {
         const uint64_t e0 = s_e0[wave];
         const uint32_t nk = s_n[wave];
-        const QConst qc = make_qconst(lay.E, lay.M, s_bias[wave]);
+        const int bias = s_bias[wave];
+        const QConst qc = make_qconst(lay.E, lay.M, bias);
         const float *gu = g + (uint64_t)u * row_stride + e0;
         const float *mu = m + (uint64_t)u * row_stride + e0;
         float *mo = m_out + (uint64_t)u * row_stride + e0;
@@ -155,12 +159,15 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
                     const uint32_t dw = lane + 64u * (uint32_t)(bt * kFuBatch + r);  // word of the chunk's symbols
                     f4 eo;
                     uint32_t packed = 0;
+                    Philox4 rw;
+                    if constexpr (kSR) rw = element_random_words(e0 + 4u * dw, u, seed);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const float v = __fadd_rn(gc[r][j], __fmul_rn(gamma, mc[r][j]));
                         uint32_t s, flags;
                         float q;
-                        quantize(v, qc, sign_shift, s, q, flags);
+                        if constexpr (kSR) quantize_stochastic(v, qc, lay.E, lay.M, bias, sign_shift, rw.w[j], s, q, flags);
+                        else quantize(v, qc, sign_shift, s, q, flags);
                         eo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
                         n_nonfinite += flags & 1u;
                         n_clamped += (flags >> 1) & 1u;
@@ -177,7 +184,10 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
                 const float v = __fadd_rn(gu[j], __fmul_rn(gamma, mu[j]));
                 uint32_t s, flags;
                 float q;
-                quantize(v, qc, sign_shift, s, q, flags);
+                if constexpr (kSR)
+                    quantize_stochastic(v, qc, lay.E, lay.M, bias, sign_shift,
+                                        element_random_words(e0 + j, u, seed).w[(e0 + j) & 3u], s, q, flags);
+                else quantize(v, qc, sign_shift, s, q, flags);
                 mo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
                 n_nonfinite += flags & 1u;
                 n_clamped += (flags >> 1) & 1u;
@@ -403,10 +413,15 @@ hipError_t launch_encode_fused(const Layout &lay, const co3_encode_args &a, cons
         return hipGetLastError();
     }
     ProfScope prof(K_FUSED, s);
-    hipLaunchKernelGGL(k_encode_fused, dim3((uint32_t)nblk, lay.U), dim3(kFuThreads), 0, s, lay, a.g, a.m, a.m_out,
-                       a.row_stride, a.gamma, books, reinterpret_cast<uint32_t *>(ticket_slots), lb_state,
-                       (uint32_t)nblk, kFuSpinLimit, a.chunk_offset, a.sub_bits, a.payload_bits, a.words,
-                       a.words_stride, a.status);
+    const dim3 grid((uint32_t)nblk, lay.U), block(kFuThreads);
+    if (a.rounding == CO3_ROUND_STOCHASTIC)
+        hipLaunchKernelGGL(k_encode_fused<true>, grid, block, 0, s, lay, a.g, a.m, a.m_out, a.row_stride, a.gamma,
+                           a.seed, books, reinterpret_cast<uint32_t *>(ticket_slots), lb_state, (uint32_t)nblk,
+                           kFuSpinLimit, a.chunk_offset, a.sub_bits, a.payload_bits, a.words, a.words_stride, a.status);
+    else
+        hipLaunchKernelGGL(k_encode_fused<false>, grid, block, 0, s, lay, a.g, a.m, a.m_out, a.row_stride, a.gamma,
+                           a.seed, books, reinterpret_cast<uint32_t *>(ticket_slots), lb_state, (uint32_t)nblk,
+                           kFuSpinLimit, a.chunk_offset, a.sub_bits, a.payload_bits, a.words, a.words_stride, a.status);
     return hipGetLastError();
 }
 

@@ -33,9 +33,12 @@ __device__ inline uint32_t find_segment(const SegDev *segs, uint32_t nseg, uint6
     return lo;
 }
 
+// kSR: the stochastic conversion (dither from Philox words of (element, user, seed)) instead of
+// the closest representative.
+template <bool kSR>
 __global__ __launch_bounds__(kQThreads) void k_quantize(
     Layout lay, const float *__restrict__ g, const float *m, float *m_out,
-    uint8_t *__restrict__ sym, uint64_t sym_stride, uint64_t row_stride, float gamma,
+    uint8_t *__restrict__ sym, uint64_t sym_stride, uint64_t row_stride, float gamma, uint64_t seed,
     uint64_t *__restrict__ hist_rep, uint64_t *__restrict__ status)
 {
     extern __shared__ uint32_t h_lds[];  // [A][kHistRep]
@@ -71,18 +74,22 @@ __global__ __launch_bounds__(kQThreads) void k_quantize(
 
     if (full && base + kQTile <= seg_end) {
         // whole tile inside one layer: one bias, LDS histogram
-        const QConst qc = make_qconst(lay.E, lay.M, lay.bias[(uint64_t)u * lay.nseg + seg]);
+        const int bias = lay.bias[(uint64_t)u * lay.nseg + seg];
+        const QConst qc = make_qconst(lay.E, lay.M, bias);
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
             const uint64_t i = base + (uint64_t)k * (kQThreads * 4) + threadIdx.x * 4;
             f4 eo;
             uint32_t packed = 0;
+            Philox4 rw;
+            if constexpr (kSR) rw = element_random_words(i, u, seed);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float v = __fadd_rn(gv[k][j], __fmul_rn(gamma, mv[k][j]));
                 uint32_t s, flags;
                 float q;
-                quantize(v, qc, sign_shift, s, q, flags);
+                if constexpr (kSR) quantize_stochastic(v, qc, lay.E, lay.M, bias, sign_shift, rw.w[j], s, q, flags);
+                else quantize(v, qc, sign_shift, s, q, flags);
                 eo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
                 n_nonfinite += flags & 1u;
                 n_clamped += (flags >> 1) & 1u;
@@ -107,11 +114,15 @@ __global__ __launch_bounds__(kQThreads) void k_quantize(
             if (i >= d) break;
             uint32_t s_i = seg;
             while (i >= lay.segs[s_i + 1].offset) ++s_i;
-            const QConst qe = make_qconst(lay.E, lay.M, lay.bias[(uint64_t)u * lay.nseg + s_i]);
+            const int bias = lay.bias[(uint64_t)u * lay.nseg + s_i];
+            const QConst qe = make_qconst(lay.E, lay.M, bias);
             const float v = __fadd_rn(gu[i], __fmul_rn(gamma, mu[i]));
             uint32_t s, flags;
             float q;
-            quantize(v, qe, sign_shift, s, q, flags);
+            if constexpr (kSR)
+                quantize_stochastic(v, qe, lay.E, lay.M, bias, sign_shift, element_random_words(i, u, seed).w[i & 3u], s,
+                                    q, flags);
+            else quantize(v, qe, sign_shift, s, q, flags);
             mo[i] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
             n_nonfinite += flags & 1u;
             n_clamped += (flags >> 1) & 1u;
@@ -161,8 +172,12 @@ hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, const En
     const size_t lds = (size_t)lay.A * kHistRep * sizeof(uint32_t);
     {
         ProfScope prof(K_QUANTIZE, s);
-        hipLaunchKernelGGL(k_quantize, dim3((uint32_t)ntiles, lay.U), dim3(kQThreads), lds, s, lay, a.g, a.m,
-                           a.m_out, a.symbols, sym_stride, a.row_stride, a.gamma, ws.hist_rep, a.status);
+        if (a.rounding == CO3_ROUND_STOCHASTIC)
+            hipLaunchKernelGGL(k_quantize<true>, dim3((uint32_t)ntiles, lay.U), dim3(kQThreads), lds, s, lay, a.g, a.m,
+                               a.m_out, a.symbols, sym_stride, a.row_stride, a.gamma, a.seed, ws.hist_rep, a.status);
+        else
+            hipLaunchKernelGGL(k_quantize<false>, dim3((uint32_t)ntiles, lay.U), dim3(kQThreads), lds, s, lay, a.g, a.m,
+                               a.m_out, a.symbols, sym_stride, a.row_stride, a.gamma, a.seed, ws.hist_rep, a.status);
     }
     const uint64_t n = (uint64_t)lay.nbooks * lay.A;
     ProfScope prof(K_REDUCE_HIST, s);

@@ -66,6 +66,31 @@ __device__ inline void quantize(float v, const QConst &c, uint32_t sign_shift, u
     q = __uint_as_float(__float_as_uint(qa) | (sgn << 31));
 }
 
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): counter-based generator, ten rounds.
+struct Philox4 { uint32_t w[4]; };
+__device__ __host__ inline Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                                 uint32_t k1)
+{
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1, n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    Philox4 r;
+    r.w[0] = c0; r.w[1] = c1; r.w[2] = c2; r.w[3] = c3;
+    return r;
+}
+
+// The four random words of elements 4j .. 4j+3 of user u (element i takes word i mod 4).
+__device__ inline Philox4 element_random_words(uint64_t elem, uint32_t user, uint64_t seed)
+{
+    const uint64_t j = elem >> 2;
+    return philox4x32_10((uint32_t)j, (uint32_t)(j >> 32), user, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
+}
+
 // fp32 pattern of the value of a symbol (exact: every representative is an fp32).
 __device__ inline uint32_t symbol_value_bits(uint32_t sym, int E, int M, int bias)
 {
@@ -87,6 +112,41 @@ __device__ inline uint32_t symbol_value_bits(uint32_t sym, int E, int M, int bia
         else bits = am << (1 - bias - M + 149);
     }
     return bits | (s << 31);
+}
+
+// Stochastic fp conversion (Sec. II-B (ii): Q as a stochastic mapping, non-subtractive dither): v
+// goes to the upper of its two neighbours with probability (|v| - lo) / (hi - lo).  A uniform
+// integer dither is added to the position of |v| between them and the result truncated: in the
+// normal range the position is the low 23 - mant bits of the fp32 pattern (the carry moves on to
+// the next representative, across binades too); in the zero/subnormal row it is |v| in units of
+// 2^(1 - bias - mant), truncated to 24 fractional bits.  rnd: this element's 32 random bits.
+// Non-finite and clamped inputs as in quantize().
+__device__ inline void quantize_stochastic(float v, const QConst &c, int E, int M, int bias, uint32_t sign_shift,
+                                           uint32_t rnd, uint32_t &sym, float &q, uint32_t &flags)
+{
+    const uint32_t bits = __float_as_uint(v);
+    const uint32_t a = bits & 0x7fffffffu;
+    const uint32_t ac = a < c.max_bits ? a : c.max_bits;
+    const bool nonfinite = a >= 0x7f800000u;
+    flags = (nonfinite ? 1u : 0u) | ((a > c.max_bits && !nonfinite) ? 2u : 0u);
+    uint32_t code, qbits;
+    if (ac >= (c.min_fexp << 23)) {
+        const uint32_t shift = c.c_add;                               // 23 - mant
+        const uint32_t mask = (1u << shift) - 1u;
+        qbits = (ac + (rnd >> (32u - shift))) & ~mask;                // never above max_bits
+        code = (((qbits >> 23) - c.min_fexp + 1u) << c.mant) | ((qbits >> shift) & ((1u << c.mant) - 1u));
+    } else {
+        const uint32_t field = ac >> 23;
+        const uint32_t mant24 = field ? ((ac & 0x7fffffu) | 0x800000u) : (ac & 0x7fffffu);
+        const int sh = (field ? (int)field - 127 : -126) + M + bias;  // |v| = mant24 2^(e - 23); units of 2^(1-bias-M-24)
+        const uint32_t xi = sh >= 0 ? mant24 << sh : (sh > -32 ? mant24 >> (-sh) : 0u);
+        code = (xi + (rnd >> 8)) >> 24;                               // 0 .. 2^mant (the smallest normal)
+        qbits = symbol_value_bits(code, E, M, bias);
+    }
+    code = (a > 0x7f800000u) ? 0u : code;                             // NaN
+    const uint32_t sgn = (code != 0u) ? (bits >> 31) : 0u;
+    sym = (sgn << sign_shift) | code;
+    q = __uint_as_float((code != 0u ? qbits : 0u) | (sgn << 31));
 }
 
 }  // namespace co3

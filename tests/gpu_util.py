@@ -22,7 +22,7 @@ def special_values(E, M, bias, rng, n):
 
 
 def gpu_round(plan_kwargs, g, m, gamma, mode, weights=None, words_stride=None, max_code_len=32, want_decode=True,
-              books=None, buf=None, single_sweep=False):
+              books=None, buf=None, single_sweep=False, stochastic_seed=None):
     """One encode (+ decode + aggregate) through the binding.  Returns (dict of numpy arrays, objects).
     single_sweep: fixed code, no symbols and no histogram requested (they stay as they were)."""
     import torch
@@ -42,7 +42,8 @@ def gpu_round(plan_kwargs, g, m, gamma, mode, weights=None, words_stride=None, m
     buf.status.zero_()
     if single_sweep:  # outputs the call must overwrite
         buf.payload_bits.fill_(-1); buf.chunk_offset.fill_(-1); buf.sub_bits.fill_(-1)
-    B.co3_encode(plan, books, gt, mt, mt, gamma, buf, mode=mode, single_sweep=single_sweep)
+    B.co3_encode(plan, books, gt, mt, mt, gamma, buf, mode=mode, single_sweep=single_sweep,
+                 stochastic_seed=stochastic_seed)
     torch.cuda.synchronize()
     out = dict(
         m_new=mt[:, :d].cpu().numpy(), sym=buf.symbols_2d().cpu().numpy(),
@@ -66,14 +67,14 @@ def gpu_round(plan_kwargs, g, m, gamma, mode, weights=None, words_stride=None, m
     return out, (plan, books, buf, gt, mt)
 
 
-def oracle_round(plan_kwargs, g, m, gamma, weights=None):
+def oracle_round(plan_kwargs, g, m, gamma, weights=None, stochastic_seed=None):
     E, M = plan_kwargs["E"], plan_kwargs["M"]
     U, d = g.shape
     seg_len = plan_kwargs.get("seg_len") or [d]
     seg_book = plan_kwargs.get("seg_book") or [0] * len(seg_len)
     bias = np.broadcast_to(np.asarray(plan_kwargs["bias"], np.int32), (U, len(seg_len)))
     pub = bool(plan_kwargs.get("per_user_books", False))
-    enc = oround.encode_round(g, m, gamma, E, M, seg_len, seg_book, bias, pub, weights)
+    enc = oround.encode_round(g, m, gamma, E, M, seg_len, seg_book, bias, pub, weights, stochastic_seed=stochastic_seed)
     sym, avg = oround.ps_round(enc, E, M, seg_len, seg_book, bias, pub)
     enc["dec_sym"] = sym
     enc["avg"] = avg

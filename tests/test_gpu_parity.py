@@ -326,3 +326,54 @@ def test_ps_model_update(U, eta, with_out):
     torch.cuda.synchronize()
     gu.assert_bits_equal(w_t.cpu().numpy(), orc.model_update(ref["dec_sym"], seg_len, bias, E, M, eta, w_ref),
                          "model after two updates")
+
+
+# ---- stochastic fp conversion (dithered Q, Sec. II-B (ii)) --------------------------------------
+
+@pytest.mark.parametrize("E,M,d,seed", [(3, 0, 5 * 2048 + 123, 1), (4, 3, 40000, 0xDEADBEEF12345678), (2, 1, 4095, 7),
+                                        (5, 2, 4096 * 4 + 1, 2 ** 63 + 5)])
+def test_stochastic_single_user_both_encoders(E, M, d, seed):
+    rng = np.random.default_rng(300 + d)
+    bias = {2: 2, 3: 6, 4: 14, 5: 22}[E]
+    g, m = make_inputs(rng, 1, d, E, M, bias, alpha=orc.grid(E, M, bias)[-1] / 6)
+    # the zero/subnormal row and tiny inputs
+    tiny = orc.grid(E, M, bias)[1]
+    g[0, :500] = rng.uniform(-2 * tiny, 2 * tiny, 500).astype(np.float32)
+    g[0, 500:520] = np.array([1e-45, -1e-45, 3e-39, -3e-39, 0.0] * 4, np.float32)
+    m[0, :520] = 0
+    kw = dict(E=E, M=M, U=1, d=d, bias=[[bias]])
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL, stochastic_seed=seed)
+    ref = gu.oracle_round(kw, g, m, 0.9, stochastic_seed=seed)
+    gu.compare_round(gpu, ref, d)
+    # the same dithers in the single-sweep encoder
+    gpu1, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=ref["hist"], single_sweep=True, stochastic_seed=seed)
+    ref1 = gu.oracle_round(kw, g, m, 0.9, weights=ref["hist"], stochastic_seed=seed)
+    gu.compare_round(gpu1, ref1, d, single_sweep=True)
+    # another seed gives another stream; the closest-representative mode is untouched by the seed
+    other = gu.oracle_round(kw, g, m, 0.9, stochastic_seed=seed + 1)
+    assert not np.array_equal(other["sym"], ref["sym"])
+
+
+def test_stochastic_multi_user_multi_segment():
+    E, M, U = 3, 2, 3
+    seg_len = [1, 63, 4097, 0, 2048 * 3 + 5, 64, 9001, 4096, 4096 * 5, 7]
+    seg_book = [0, 1, 2, 0, 1, 3, 2, 0, 1, 3]
+    d = sum(seg_len)
+    rng = np.random.default_rng(401)
+    bias = rng.integers(8, 20, (U, len(seg_len))).astype(np.int32)
+    g = np.empty((U, d), np.float32); m = np.empty((U, d), np.float32)
+    off = 0
+    for k, n in enumerate(seg_len):
+        for u in range(U):
+            top = orc.grid(E, M, int(bias[u, k]))[-1]
+            g[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, top / 8)
+            m[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, top / 30)
+        off += n
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias, seg_len=seg_len, seg_book=seg_book, per_user_books=False)
+    seed = 20240229
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL, stochastic_seed=seed)
+    ref = gu.oracle_round(kw, g, m, 0.9, stochastic_seed=seed)
+    gu.compare_round(gpu, ref, d)
+    gpu1, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=ref["hist"], single_sweep=True, stochastic_seed=seed)
+    ref1 = gu.oracle_round(kw, g, m, 0.9, weights=ref["hist"], stochastic_seed=seed)
+    gu.compare_round(gpu1, ref1, d, single_sweep=True)
