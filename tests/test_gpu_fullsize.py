@@ -273,6 +273,28 @@ def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000,
         assert torch.equal(buf2.words[u, :nw], buf.words[u, :nw]), f"stream of user {u}"
     print(f"[{name}] single-sweep round identical to the three-step round at {time.time() - t_start:.1f}s", flush=True)
 
+    # The model refresh at full size: moment fit of v = g + gamma m_in for every user and layer; the
+    # oracle (two-pass fp64 moments) checks the users it can afford.
+    from oracle import co3_gennorm_fit as fitm
+    params = B.co3_gennorm_fit(plan, g, m_in, w.gamma)
+    torch.cuda.synchronize()
+    par = params.cpu().numpy()
+    fit_users = list(full_users) if full_users else [0]
+    for u in fit_users[:2]:
+        gh = g[u, :d].cpu().numpy(); mh = m_in[u, :d].cpu().numpy()
+        ref = fitm.fit_round(gh[None, :], mh[None, :], w.gamma, seg_len)[0]
+        for k in range(nseg):
+            if ref[k, 1] == 0.0:
+                assert par[u, k, 1] == 0.0 and par[u, k, 2] == 0.0
+                continue
+            sigma = ref[k, 1] * float(np.sqrt(fitm.variance_factor(ref[k, 2])))
+            assert abs(par[u, k, 0] - ref[k, 0]) <= 1e-11 * sigma, (u, k)
+            assert abs(par[u, k, 3] / ref[k, 3] - 1.0) <= 1e-9, (u, k, par[u, k, 3], ref[k, 3])
+            assert abs(par[u, k, 2] / ref[k, 2] - 1.0) <= 1e-9 and abs(par[u, k, 1] / ref[k, 1] - 1.0) <= 1e-9, (u, k)
+        del gh, mh
+    print(f"[{name}] moment fit of users {fit_users[:2]} equals the oracle's at {time.time() - t_start:.1f}s; "
+          f"beta in [{par[:, :, 2].min():.3f}, {par[:, :, 2].max():.3f}]", flush=True)
+
 
 def test_cfg1_full():
     run_workload("cfg1", full_users=[0], n_random_chunks=24)
