@@ -242,7 +242,7 @@ def main():
 
     head = runs[a.book]
     kt, per_launch, bpe = head["kt"], head["per_launch"], head["bpe"]
-    alg_bytes = {  # algorithmic bytes per element of each kernel ("Kernels")
+    alg_bytes = {  # algorithmic bytes per element of each kernel
         "k_quantize": 13.0,               # read g, read m, write m', write symbol
         "k_chunk_bits": 1.0,              # read symbol
         "k_pack": 1.0 + bpe / 8.0,        # read symbol, write codewords
@@ -265,7 +265,7 @@ def main():
         "value": head["summary"]["gelem_s"], "unit": "GElem/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": head["summary"]["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32+u8",
-        "data": "synthetic GenNorm gradients (torch device generator), see DESIGN.md",
+        "data": "synthetic GenNorm gradients (seeded torch device generator; recipe in co3_synth.py)",
         "config": {"workload": f"{w.name}: U={U} d={d} [1,{w.E},{w.M}] gamma={w.gamma} nseg={nseg} book={a.book} "
                                f"({'per-user' if w.per_user_books else 'pooled over users'})",
                    "elements_per_step": elems},

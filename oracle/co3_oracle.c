@@ -41,6 +41,11 @@
  *       on a 32-bit boundary and consists of sub-chunks of 64 elements whose bit
  *       counts are stored beside the chunk's 64-bit bit offset.
  *   R8  average: sum over u = 0..U-1 in double, times 1.0/U, rounded to fp32.
+ *       Model update w - (eta/U) sum: the same sum, times 1.0/U, times eta, subtracted
+ *       from w in double, one rounding to fp32.
+ *   R9  optional stochastic conversion (Sec. II-B (ii) allows Q to be a stochastic
+ *       mapping): the upper neighbour with probability (|v| - lo) / (hi - lo), by an
+ *       integer dither from Philox4x32-10; details at co3o_ef_step_sr.
  *
  * Parity pins (tests/, marker "not gpu"): grid against the sets M and E printed
  * in Sec. V-B; nearest-value brute force with exact rationals; IEEE half,
@@ -48,7 +53,9 @@
  * bound Delta/2 and boundary B of Sec. V-B; Laplace tail closed form; Huffman
  * optimality by brute force, Kraft equality, dyadic / uniform / Fibonacci closed
  * forms, hand-worked tie-break cases; pack/unpack round trip and a hand-written
- * bitstream; error-feedback identity and telescoping sum.
+ * bitstream; error-feedback identity and telescoping sum; model update against
+ * exact rationals; Philox known-answer vectors, neighbour / probability /
+ * unbiasedness properties of the stochastic conversion.
  * Unpinned: the paper's own bits-per-element totals (Sec. VI) -- they are below
  * 1 bit/element, which an element-wise code cannot reach; "parity unpinned".
  *
@@ -223,7 +230,7 @@ int co3o_ef_step(const float *g, const float *m, uint64_t n, float gamma,
 /* ------------------------------------------------------------------------- */
 /* Stochastic fp conversion (Sec. II-B (ii): "the mapping Q is meant as a     */
 /* stochastic mapping, so that non-subtractive dither quantization can be     */
-/* implemented"), reading R15: v goes to one of its two neighbours in X, the  */
+/* implemented"), reading R9: v goes to one of its two neighbours in X, the   */
 /* upper one with probability (|v| - lo) / (hi - lo), decided by adding a     */
 /* uniform integer dither to the position of |v| between them and truncating. */
 /* The dither has as many bits as fp32 resolves between the neighbours        */
