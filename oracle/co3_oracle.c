@@ -18,8 +18,8 @@
  *   - PS reconstruction and average:  Sec. II-B (iv), eq. (aggregate hat);
  *     Algorithm 1 lines 13-14.
  *
- * Where the paper is silent the readings below are taken (they are listed, with
- * reasons, in the design document of this repository):
+ * Where the paper is silent, ambiguous or at odds with itself the readings below
+ * are taken:
  *   R1  exponent field f in [1, 2^exp - 2] <-> c_exp = f - (2^(exp-1) - 1); the
  *       integer parameter "bias" gives the value exponent f - bias, i.e. the
  *       paper's b is (2^(exp-1) - 1) - bias.
