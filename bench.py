@@ -47,6 +47,8 @@ def parse():
                    help="encoder for --book model: the single-sweep kernel (symbols never stored) or the three-step one")
     p.add_argument("--stochastic", action="store_true",
                    help="stochastic fp conversion (dithered Q) instead of the closest representative; a new seed per step")
+    p.add_argument("--graph", action="store_true",
+                   help="replay the step from HIP graphs (one per gradient set of the pool) instead of launching eagerly")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-other-book", action="store_true", help="measure only the headline code-table mode")
     p.add_argument("--ignore-status", action="store_true", help="tuning runs only: do not stop on codec error counters")
@@ -139,10 +141,31 @@ def main():
     counter = [0]
 
     def measure(books, mode, label, single_sweep=False):
-        def step():
-            B.co3_encode(plan, books, pool[counter[0] % a.pool], m, m, w.gamma, buf, mode=mode,
-                         single_sweep=single_sweep, stochastic_seed=(1000 + counter[0]) if a.stochastic else None)
+        def eager_step(idx):
+            B.co3_encode(plan, books, pool[idx], m, m, w.gamma, buf, mode=mode, single_sweep=single_sweep,
+                         stochastic_seed=(1000 + counter[0]) if a.stochastic else None)
             B.co3_ps_aggregate(plan, books, buf, out)
+
+        graphs = []
+        if a.graph:   # one captured step per gradient set; the seed of a stochastic run is then fixed per set
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                for idx in range(a.pool):
+                    eager_step(idx)
+                    side.synchronize()
+                    gr = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(gr, stream=side):
+                        eager_step(idx)
+                    graphs.append(gr)
+            torch.cuda.synchronize()
+
+        def step():
+            idx = counter[0] % a.pool
+            if graphs:
+                graphs[idx].replay()
+            else:
+                eager_step(idx)
             counter[0] += 1
         for _ in range(a.warmup):
             step()
@@ -162,6 +185,13 @@ def main():
         wall_ms = (time.perf_counter() - t0) * 1e3
         dev_ms = ev0.elapsed_time(ev1)
         kt = B.profile_end()
+        ksteps = a.steps
+        if graphs:   # replays launch nothing through the library: per-kernel times from a few eager steps
+            ksteps = 5
+            B.profile_begin()
+            for i in range(ksteps):
+                eager_step(i % a.pool)
+            kt = B.profile_end()
         status = buf.status.cpu().numpy().tolist()
         if (status[B.STAT_CAPACITY] or status[B.STAT_NOCODE] or status[B.STAT_CORRUPT] or status[B.STAT_CODELEN]
                 or status[B.STAT_STALLED]) \
@@ -174,8 +204,8 @@ def main():
             + 64.0 * U * (plan.num_chunks + 1) + 16.0 * U * plan.num_chunks * 64
         bpe = float(payload.sum()) / elems
         per_launch = {k: v[0] / v[1] for k, v in kt.items()}
-        enc_ms = sum(kt[k][0] for k in ENC_KERNELS if k in kt) / a.steps
-        dec_ms = kt["k_aggregate"][0] / a.steps
+        enc_ms = sum(kt[k][0] for k in ENC_KERNELS if k in kt) / ksteps
+        dec_ms = kt["k_aggregate"][0] / ksteps
         enc_alg = (12.0 + bpe / 8.0) * elems
         return dict(ms_per_step=ms_per_step, kt=kt, per_launch=per_launch, bpe=bpe, status=status,
                     summary={
