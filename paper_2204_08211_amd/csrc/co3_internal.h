@@ -16,6 +16,8 @@ constexpr int kMaxA = 256;          // symbols are bytes
 constexpr int kDecBits = 11;        // prefix width of the direct decode table
 constexpr int kDecEntries = 1 << kDecBits;
 constexpr int kLongSlots = 64 - kDecBits;  // lengths kDecBits+1 .. 64
+constexpr int kDec2Bits = 3;        // second-level tables resolve codes of up to kDecBits + kDec2Bits bits
+constexpr int kDec2Tables = 40;     // for the first prefixes that hold only longer codes (they are the largest ones)
 constexpr int kHistGlobalRep = 64;   // copies of the global symbol-count table the workgroups spread over
 constexpr int kFastLen = 24;        // longest code held in the 32-bit encode entry
 constexpr uint32_t kFastSlow = 0xFFu;  // length field marking "use the 64-bit table"
@@ -27,7 +29,8 @@ struct BookDev {
     uint32_t fast[kMaxA];        // (len << 24) | code for len <= 24; len field 0xFF: long code; 0: no code
     uint32_t count[65];          // count[L]: symbols with length L
     uint32_t offset[65];         // offset[L]: index of the first length-L symbol in sorted[]
-    uint16_t dec[kDecEntries];   // prefix -> (len << 8) | symbol for len <= 11, else 0
+    uint16_t dec[kDecEntries];   // prefix -> (len << 8) | symbol for len <= 11; else 1 + its second-level table, or 0
+    uint16_t dec2[kDec2Tables << kDec2Bits];  // [table][next kDec2Bits bits] -> (len << 8) | symbol, 0: longer code
     uint8_t len[kMaxA];          // codeword length, 0 = no code
     uint8_t sorted[kMaxA];       // symbols ordered by (length, symbol)
     uint32_t maxlen;

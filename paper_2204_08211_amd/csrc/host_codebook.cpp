@@ -23,6 +23,7 @@ static void finish_tables(BookDev *b, uint32_t A)
     std::memset(b->code, 0, sizeof(b->code));
     std::memset(b->fast, 0, sizeof(b->fast));
     std::memset(b->dec, 0, sizeof(b->dec));
+    std::memset(b->dec2, 0, sizeof(b->dec2));
     std::memset(b->sorted, 0, sizeof(b->sorted));
     b->maxlen = 0;
     b->nactive = 0;
@@ -56,6 +57,17 @@ static void finish_tables(BookDev *b, uint32_t A)
         b->long_base[k] = b->offset[L] - (uint32_t)b->first[L];
         b->long_len[k] = (uint32_t)L;
     }
+    // Prefixes of kDecBits bits under which only longer codes live are the largest ones (canonical
+    // codes grow with their length); the first kDec2Tables of them get a second-level table over
+    // the next kDec2Bits bits.
+    uint32_t long_prefix0 = kDecEntries;
+    for (int L = kDecBits + 1; L <= 64; ++L) {
+        if (!b->count[L]) continue;
+        long_prefix0 = (uint32_t)(b->first[L] >> (L - kDecBits));
+        break;
+    }
+    for (uint32_t p = long_prefix0; p < (uint32_t)kDecEntries && p - long_prefix0 < (uint32_t)kDec2Tables; ++p)
+        b->dec[p] = (uint16_t)(p - long_prefix0 + 1);  // entries of the second-level tables follow with the symbols
     uint32_t next[65];
     std::memset(next, 0, sizeof(next));
     for (uint32_t s = 0; s < A; ++s) {  // ascending symbol within each length
@@ -70,6 +82,13 @@ static void finish_tables(BookDev *b, uint32_t A)
             const uint32_t lo = (uint32_t)b->code[s] << (kDecBits - L);
             const uint32_t n = 1u << (kDecBits - L);
             for (uint32_t i = 0; i < n; ++i) b->dec[lo + i] = (uint16_t)((L << 8) | s);
+        } else if (L <= kDecBits + kDec2Bits) {
+            const uint32_t lo = (uint32_t)b->code[s] << (kDecBits + kDec2Bits - L);
+            const uint32_t n = 1u << (kDecBits + kDec2Bits - L);
+            for (uint32_t i = 0; i < n; ++i) {
+                const uint32_t j = ((lo + i) >> kDec2Bits) - long_prefix0;
+                if (j < (uint32_t)kDec2Tables) b->dec2[(j << kDec2Bits) | ((lo + i) & ((1u << kDec2Bits) - 1u))] = (uint16_t)((L << 8) | s);
+            }
         }
     }
 }

@@ -149,7 +149,13 @@ __global__ __launch_bounds__(kCbThreads) void k_build_books(BookDev *__restrict_
     __syncthreads();
     B.sorted[t] = (t < n && !bad) ? (uint8_t)sorted[t] : 0;
 
-    // direct decode table: every kDecBits-bit prefix whose code is at most kDecBits long
+    // direct decode table: every kDecBits-bit prefix whose code is at most kDecBits long; the first
+    // kDec2Tables prefixes that hold only longer codes (the largest prefixes: canonical codes grow
+    // with their length) point to a second-level table over the next kDec2Bits bits
+    uint32_t long_prefix0 = kDecEntries;
+    for (int l = kDecBits + 1; l <= 64; ++l) {
+        if (cnt[l]) { long_prefix0 = (uint32_t)(first[l] >> (l - kDecBits)); break; }
+    }
     for (int idx = t; idx < kDecEntries; idx += kCbThreads) {
         uint16_t e = 0;
         for (int l = 1; l <= kDecBits; ++l) {
@@ -160,7 +166,24 @@ __global__ __launch_bounds__(kCbThreads) void k_build_books(BookDev *__restrict_
                 break;
             }
         }
+        if (e == 0 && (uint32_t)idx >= long_prefix0 && (uint32_t)idx - long_prefix0 < (uint32_t)kDec2Tables)
+            e = (uint16_t)((uint32_t)idx - long_prefix0 + 1);
         B.dec[idx] = e;
+    }
+    for (int idx = t; idx < (kDec2Tables << kDec2Bits); idx += kCbThreads) {
+        const uint32_t wide = ((long_prefix0 + ((uint32_t)idx >> kDec2Bits)) << kDec2Bits) |
+                              ((uint32_t)idx & ((1u << kDec2Bits) - 1u));  // kDecBits + kDec2Bits bits
+        uint16_t e = 0;
+        if ((wide >> kDec2Bits) < (uint32_t)kDecEntries) {
+            for (int l = kDecBits + 1; l <= kDecBits + kDec2Bits; ++l) {
+                const uint64_t c = wide >> (kDecBits + kDec2Bits - l);
+                if (cnt[l] && c >= first[l] && c - first[l] < cnt[l]) {
+                    e = (uint16_t)((l << 8) | sorted[off[l] + (uint32_t)(c - first[l])]);
+                    break;
+                }
+            }
+        }
+        B.dec2[idx] = e;
     }
 }
 

@@ -29,6 +29,7 @@ constexpr int kPayloadAlloc = kPayloadWords + 2 + kSub + 6;
 // Decode tables of one code in LDS.
 struct DecLds {
     uint16_t dec[kDecEntries];
+    uint16_t dec2[kDec2Tables << kDec2Bits];
     uint64_t long_last[kLongSlots];
     uint32_t long_base[kLongSlots];
     uint32_t long_len[kLongSlots];
@@ -41,6 +42,8 @@ __device__ inline void load_dec_tables(DecLds *T, const BookDev &book, uint32_t 
 {
     for (uint32_t i = t; i < kDecEntries / 2; i += nthreads)
         reinterpret_cast<uint32_t *>(T->dec)[i] = reinterpret_cast<const uint32_t *>(book.dec)[i];
+    for (uint32_t i = t; i < (uint32_t)((kDec2Tables << kDec2Bits) / 2); i += nthreads)
+        reinterpret_cast<uint32_t *>(T->dec2)[i] = reinterpret_cast<const uint32_t *>(book.dec2)[i];
     for (uint32_t i = t; i < (uint32_t)kLongSlots; i += nthreads) {
         T->long_last[i] = book.long_last[i];
         T->long_base[i] = book.long_base[i];
@@ -148,12 +151,20 @@ __device__ inline uint32_t decode_symbol(Reader<Src> &r, const DecLds *T, bool &
     asm volatile("" : "+v"(nextw), "+v"(e));
     uint32_t L = e >> 8, s = e & 0xffu;
     if (__builtin_expect(L == 0u, 0)) {
-        const uint32_t n = T->nlong;
-        uint32_t k = 0;
-        while (k < n && win > T->long_last[k]) ++k;
-        if (k < n) {
-            L = T->long_len[k];
-            if (L <= 32u) s = T->sorted[((uint32_t)(win >> (64u - L)) + T->long_base[k]) & (kMaxA - 1)];
+        // codes a little longer than the direct table: one more look-up in the prefix's second-level table
+        uint32_t e2 = 0;
+        if (s) e2 = T->dec2[((s - 1u) << kDec2Bits) | ((uint32_t)(win >> (64 - kDecBits - kDec2Bits)) & ((1u << kDec2Bits) - 1u))];
+        if (e2) {
+            L = e2 >> 8;
+            s = e2 & 0xffu;
+        } else {
+            const uint32_t n = T->nlong;
+            uint32_t k = 0;
+            while (k < n && win > T->long_last[k]) ++k;
+            if (k < n) {
+                L = T->long_len[k];
+                if (L <= 32u) s = T->sorted[((uint32_t)(win >> (64u - L)) + T->long_base[k]) & (kMaxA - 1)];
+            }
         }
         if (__builtin_expect(L == 0u || L > 32u, 0)) {
             const uint32_t pos = r.pos();
