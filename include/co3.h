@@ -205,7 +205,8 @@ typedef struct {
     uint32_t *words;         /* device [U][words_stride] streams (out)                       */
     uint64_t words_stride;   /* capacity of one user's stream in 32-bit words                */
     uint64_t *chunk_offset;  /* device [U][num_chunks+1] bit offsets of the chunks (out)     */
-    uint16_t *sub_bits;      /* device [U][num_chunks*64] bits per sub-chunk (out)           */
+    uint16_t *sub_bits;      /* device [U][num_chunks*64] bits per sub-chunk (out); may be   */
+                             /* NULL when d = 0                                              */
     uint64_t *payload_bits;  /* device [U]: r = sum of codeword lengths (out)                */
     uint64_t *status;        /* device [CO3_STATUS_WORDS] counters (added to)                */
     void *workspace;         /* device, co3_plan_workspace_bytes()                           */

@@ -237,7 +237,8 @@ int co3_encode(const co3_plan *plan, const co3_encode_args *a, void *stream)
 {
     if (!plan || !a) return CO3_ERR_ARG;
     const Layout &lay = plan->lay;
-    if (!a->g || !a->m || !a->m_out || !a->words || !a->chunk_offset || !a->sub_bits || !a->payload_bits ||
+    // a vector without elements has no sub-chunks: its (empty) sub_bits array may be NULL
+    if (!a->g || !a->m || !a->m_out || !a->words || !a->chunk_offset || (!a->sub_bits && lay.nchunks) || !a->payload_bits ||
         !a->status || !a->workspace)
         return CO3_ERR_ARG;
     if (a->mode != CO3_BOOK_FIXED && a->mode != CO3_BOOK_EMPIRICAL) return CO3_ERR_ARG;
@@ -328,7 +329,8 @@ int co3_decode(const co3_plan *plan, const co3_decode_args *a, void *stream)
 {
     if (!plan || !a) return CO3_ERR_ARG;
     const Layout &lay = plan->lay;
-    if (!a->words || !a->chunk_offset || !a->sub_bits || !a->status || (!a->symbols && !a->q)) return CO3_ERR_ARG;
+    if (!a->words || !a->chunk_offset || (!a->sub_bits && lay.nchunks) || !a->status || (!a->symbols && !a->q))
+        return CO3_ERR_ARG;
     if (a->q && a->q_stride < lay.d) return CO3_ERR_ARG;
     int rc = check_books(plan, a->books);
     if (rc != CO3_OK) return rc;
@@ -341,7 +343,8 @@ int co3_ps_aggregate(const co3_plan *plan, const co3_aggregate_args *a, void *st
 {
     if (!plan || !a) return CO3_ERR_ARG;
     const Layout &lay = plan->lay;
-    if (!a->words || !a->chunk_offset || !a->sub_bits || !a->status || (!a->out && !a->model)) return CO3_ERR_ARG;
+    if (!a->words || !a->chunk_offset || (!a->sub_bits && lay.nchunks) || !a->status || (!a->out && !a->model))
+        return CO3_ERR_ARG;
     if (a->model && !(a->eta == a->eta)) return CO3_ERR_ARG;
     int rc = check_books(plan, a->books);
     if (rc != CO3_OK) return rc;

@@ -377,3 +377,38 @@ def test_stochastic_multi_user_multi_segment():
     gpu1, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=ref["hist"], single_sweep=True, stochastic_seed=seed)
     ref1 = gu.oracle_round(kw, g, m, 0.9, weights=ref["hist"], stochastic_seed=seed)
     gu.compare_round(gpu1, ref1, d, single_sweep=True)
+
+
+# ---- degenerate sizes ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("d", [0, 1, 2, 3, 5, 63, 64, 65])
+def test_tiny_vectors_both_encoders(d):
+    import torch
+    from paper_2204_08211_amd import binding as B
+    E, M, U, bias = 3, 2, 3, 6
+    rng = np.random.default_rng(600 + d)
+    g = rng.laplace(0, 0.3, (U, d)).astype(np.float32)
+    m = rng.laplace(0, 0.1, (U, d)).astype(np.float32)
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[bias]] * U)
+    if d == 0:
+        # nothing to encode: empty streams, zero payload, offsets [0]; the calls must still succeed
+        plan = B.Plan(**kw)
+        books = B.co3_build_codebook(E, M, plan.num_books, None)
+        buf = B.RoundBuffers(plan, "cuda:0")
+        z = torch.zeros((U, 4), dtype=torch.float32, device="cuda:0")
+        out = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+        for single in (False, True):
+            buf.chunk_offset.fill_(-1); buf.payload_bits.fill_(-1)
+            B.co3_encode(plan, books, z, z, z, 0.9, buf, mode=B.BOOK_FIXED if single else B.BOOK_EMPIRICAL,
+                         single_sweep=single)
+            B.co3_ps_aggregate(plan, books, buf, out)
+            torch.cuda.synchronize()
+            assert buf.chunk_offset.cpu().numpy().tolist() == [[0]] * U
+            assert buf.payload_bits.cpu().numpy().tolist() == [0] * U
+        return
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL)
+    ref = gu.oracle_round(kw, g, m, 0.9)
+    gu.compare_round(gpu, ref, d)
+    gpu1, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=ref["hist"], single_sweep=True)
+    ref1 = gu.oracle_round(kw, g, m, 0.9, weights=ref["hist"])
+    gu.compare_round(gpu1, ref1, d, single_sweep=True)
