@@ -36,6 +36,7 @@ constexpr int kFuStage = kSubsPerChunk * kFuRow;     // 1088 words hold a chunk'
 constexpr int kFuWin = 1088;                         // LDS window of the output: 8.5 bit/element per pass
 constexpr int kFuBatch = 4;                          // 16-byte vectors of g (and of m) a lane requests at a time
 constexpr int kFuBatches = kChunk / 4 / 64 / kFuBatch; // batches per chunk
+constexpr int kFuScalar = 8;                         // element rounds a lane requests together on the element path
 constexpr uint32_t kFuSpinLimit = 1u << 20;          // polls of one predecessor entry before giving up
 
 // look-back entry: flag in the top two bits, size in bits below
@@ -45,6 +46,7 @@ constexpr uint64_t kLbStalled = 3ull << 62;
 constexpr uint64_t kLbValue = (1ull << 62) - 1;
 
 static_assert(kChunk % (4 * 64 * kFuBatch) == 0, "whole batches per chunk");
+static_assert(kChunk % (64 * kFuScalar) == 0, "whole element rounds per chunk");
 
 __device__ inline uint32_t fu_find_chunk_segment(const SegDev *segs, uint32_t nseg, uint64_t chunk)
 {
@@ -178,21 +180,39 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
                 }
             }
         } else {
-            // ragged or unaligned chunk: element path
-            uint8_t *stage_bytes = reinterpret_cast<uint8_t *>(s_stage[wave]);
-            for (uint32_t j = lane; j < nk; j += 64) {
-                const float v = __fadd_rn(gu[j], __fmul_rn(gamma, mu[j]));
-                uint32_t s, flags;
-                float q;
-                if constexpr (kSR)
-                    quantize_stochastic(v, qc, lay.E, lay.M, bias, sign_shift,
-                                        element_random_words(e0 + j, u, seed).w[(e0 + j) & 3u], s, q, flags);
-                else quantize(v, qc, sign_shift, s, q, flags);
-                mo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
-                n_nonfinite += flags & 1u;
-                n_clamped += (flags >> 1) & 1u;
-                const uint32_t dw = j >> 2;
-                stage_bytes[4u * (dw + (dw >> 4)) + (j & 3u)] = (uint8_t)s;
+            // ragged or unaligned chunk (a layer may start at any element): a lane takes one element
+            // of every 64, kFuScalar rounds requested together; four neighbouring lanes then gather
+            // their symbols into one word of the stage
+            for (uint32_t base = 0; base < nk; base += 64u * kFuScalar) {
+                float gs[kFuScalar], ms[kFuScalar];
+#pragma unroll
+                for (int r = 0; r < kFuScalar; ++r) {
+                    const uint32_t j = base + lane + 64u * r;
+                    gs[r] = j < nk ? gu[j] : 0.0f;
+                    ms[r] = j < nk ? mu[j] : 0.0f;
+                }
+#pragma unroll
+                for (int r = 0; r < kFuScalar; ++r) {
+                    const uint32_t j = base + lane + 64u * r;  // < kChunk: base is a multiple of 64 kFuScalar
+                    const bool in = j < nk;
+                    const float v = __fadd_rn(gs[r], __fmul_rn(gamma, ms[r]));
+                    uint32_t s, flags;
+                    float q;
+                    if constexpr (kSR)
+                        quantize_stochastic(v, qc, lay.E, lay.M, bias, sign_shift,
+                                            element_random_words(e0 + j, u, seed).w[(e0 + j) & 3u], s, q, flags);
+                    else quantize(v, qc, sign_shift, s, q, flags);
+                    if (in) {
+                        mo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
+                        n_nonfinite += flags & 1u;
+                        n_clamped += (flags >> 1) & 1u;
+                    }
+                    s = in ? s : 0u;
+                    const uint32_t s4 = s | (__shfl_down(s, 1, 64) << 8) | (__shfl_down(s, 2, 64) << 16) |
+                                        (__shfl_down(s, 3, 64) << 24);
+                    const uint32_t dw = j >> 2;
+                    if ((lane & 3u) == 0 && in) s_stage[wave][dw + (dw >> 4)] = s4;
+                }
             }
         }
         // the code-table entries of this wavefront's chunk
