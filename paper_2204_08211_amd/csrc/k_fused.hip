@@ -133,9 +133,30 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
         const float *mu = m + (uint64_t)u * row_stride + e0;
         float *mo = m_out + (uint64_t)u * row_stride + e0;
         uint32_t n_nonfinite = 0, n_clamped = 0;
-        // a whole chunk at a 16-byte aligned position takes the vector path: kFuBatch vectors of g and
-        // of m per lane at a time, the next batch requested before the current one is computed
-        if (nk == (uint32_t)kChunk && (e0 & 3u) == 0) {
+        // Four elements of a 16-byte vector: symbols packed into a word, new memory, counters for the
+        // elements `valid` marks (bit j: element j belongs to this chunk).
+        auto quant4 = [&](const f4 &gv, const f4 &mv, uint64_t elem, uint32_t valid, f4 &eo, uint32_t &packed) {
+            packed = 0;
+            Philox4 rw;
+            if constexpr (kSR) rw = element_random_words(elem, u, seed);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float v = __fadd_rn(gv[j], __fmul_rn(gamma, mv[j]));
+                uint32_t s, flags;
+                float q;
+                if constexpr (kSR) quantize_stochastic(v, qc, lay.E, lay.M, bias, sign_shift, rw.w[j], s, q, flags);
+                else quantize(v, qc, sign_shift, s, q, flags);
+                eo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
+                const uint32_t ok = (valid >> j) & 1u;
+                n_nonfinite += flags & ok;
+                n_clamped += (flags >> 1) & ok;
+                packed |= s << (8 * j);
+            }
+        };
+        // A whole chunk takes a vector path: kFuBatch 16-byte vectors of g and of m per lane at a time,
+        // the next batch requested before the current one is computed.
+        const uint32_t shift = (uint32_t)(e0 & 3u);
+        if (nk == (uint32_t)kChunk && shift == 0) {
             f4 gn[kFuBatch], mn[kFuBatch];
 #pragma unroll
             for (int r = 0; r < kFuBatch; ++r) {
@@ -160,28 +181,71 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
                 for (int r = 0; r < kFuBatch; ++r) {
                     const uint32_t dw = lane + 64u * (uint32_t)(bt * kFuBatch + r);  // word of the chunk's symbols
                     f4 eo;
-                    uint32_t packed = 0;
-                    Philox4 rw;
-                    if constexpr (kSR) rw = element_random_words(e0 + 4u * dw, u, seed);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float v = __fadd_rn(gc[r][j], __fmul_rn(gamma, mc[r][j]));
-                        uint32_t s, flags;
-                        float q;
-                        if constexpr (kSR) quantize_stochastic(v, qc, lay.E, lay.M, bias, sign_shift, rw.w[j], s, q, flags);
-                        else quantize(v, qc, sign_shift, s, q, flags);
-                        eo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
-                        n_nonfinite += flags & 1u;
-                        n_clamped += (flags >> 1) & 1u;
-                        packed |= s << (8 * j);
-                    }
+                    uint32_t packed;
+                    quant4(gc[r], mc[r], e0 + 4u * dw, 0xfu, eo, packed);
                     __builtin_nontemporal_store(eo, reinterpret_cast<f4 *>(mo + 4u * dw));
                     s_stage[wave][dw + (dw >> 4)] = packed;
                 }
             }
+        } else if (nk == (uint32_t)kChunk) {
+            // A layer may start at any element.  The same vectors, taken from the 16-byte boundary
+            // below the chunk: vector k holds the chunk's elements 4k - shift .. 4k - shift + 3, so
+            // its symbols fall into words k - 1 and k of the stage (OR-ed in; the stage is cleared
+            // first) and the vectors at both ends are partial.
+            const float *ga = gu - shift, *ma = mu - shift;
+            float *moa = mo - shift;
+            for (uint32_t i = lane; i < (uint32_t)(kFuStage + 1); i += 64) s_stage[wave][i] = 0;
+            fu_wave_sync_lds();
+            f4 gn[kFuBatch], mn[kFuBatch];
+#pragma unroll
+            for (int r = 0; r < kFuBatch; ++r) {
+                const uint32_t i = 4u * (lane + 64u * r);
+                gn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(ga + i));
+                mn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(ma + i));
+            }
+#pragma unroll 1
+            for (int bt = 0; bt < kFuBatches; ++bt) {
+                f4 gc[kFuBatch], mc[kFuBatch];
+#pragma unroll
+                for (int r = 0; r < kFuBatch; ++r) { gc[r] = gn[r]; mc[r] = mn[r]; }
+                if (bt + 1 < kFuBatches) {
+#pragma unroll
+                    for (int r = 0; r < kFuBatch; ++r) {
+                        const uint32_t i = 4u * (lane + 64u * (uint32_t)((bt + 1) * kFuBatch + r));
+                        gn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(ga + i));
+                        mn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(ma + i));
+                    }
+                }
+#pragma unroll
+                for (int r = 0; r < kFuBatch; ++r) {
+                    const uint32_t k = lane + 64u * (uint32_t)(bt * kFuBatch + r);  // vector, 0 .. 1023
+                    const uint32_t valid = k ? 0xfu : (0xfu << shift) & 0xfu;      // vector 0 starts before the chunk
+                    f4 eo;
+                    uint32_t packed;
+                    quant4(gc[r], mc[r], e0 - shift + 4u * k, valid, eo, packed);
+                    if (k) {
+                        __builtin_nontemporal_store(eo, reinterpret_cast<f4 *>(moa + 4u * k));
+                        atomicOr(&s_stage[wave][(k - 1u) + ((k - 1u) >> 4)], packed << (8u * (4u - shift)));
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if ((valid >> j) & 1u) moa[j] = eo[j];
+                    }
+                    atomicOr(&s_stage[wave][k + (k >> 4)], packed >> (8u * shift));
+                }
+            }
+            if (lane == 0) {
+                // vector 1024: the chunk's last `shift` elements
+                f4 gv = {0.0f, 0.0f, 0.0f, 0.0f}, mv = {0.0f, 0.0f, 0.0f, 0.0f}, eo;
+                for (uint32_t j = 0; j < shift; ++j) { gv[j] = ga[kChunk + j]; mv[j] = ma[kChunk + j]; }
+                uint32_t packed;
+                quant4(gv, mv, e0 - shift + kChunk, (1u << shift) - 1u, eo, packed);
+                for (uint32_t j = 0; j < shift; ++j) moa[kChunk + j] = eo[j];
+                const uint32_t last = kChunk / 4 - 1;
+                atomicOr(&s_stage[wave][last + (last >> 4)], (packed & ((1u << (8u * shift)) - 1u)) << (8u * (4u - shift)));
+            }
         } else {
-            // ragged or unaligned chunk (a layer may start at any element): a lane takes one element
-            // of every 64, kFuScalar rounds requested together; four neighbouring lanes then gather
+            // ragged chunk (the end of a layer): a lane takes one element of every 64, kFuScalar rounds requested together; four neighbouring lanes then gather
             // their symbols into one word of the stage
             for (uint32_t base = 0; base < nk; base += 64u * kFuScalar) {
                 float gs[kFuScalar], ms[kFuScalar];
