@@ -255,6 +255,7 @@ def main():
         return books
 
     runs = {}
+    model_code = None
     order = ["empirical", "model"] if a.book == "empirical" else ["model", "empirical"]
     if a.no_other_book:
         order = order[:1]
@@ -268,7 +269,8 @@ def main():
         if label == "empirical":
             runs[label] = measure(emp_books, B.BOOK_EMPIRICAL, "empirical")
         else:
-            runs[label] = measure(model_books(), B.BOOK_FIXED, "model", single_sweep=a.model_encoder == "sweep")
+            model_code = model_books()
+            runs[label] = measure(model_code, B.BOOK_FIXED, "model", single_sweep=a.model_encoder == "sweep")
 
     head = runs[a.book]
     kt, per_launch, bpe = head["kt"], head["per_launch"], head["bpe"]
@@ -308,6 +310,18 @@ def main():
     }
     if refresh:
         res["model_refresh"] = refresh
+    # co3_decode on its own (symbols of every user back to HBM), streams of the last measured round
+    last_books = model_code if order[-1] == "model" else emp_books
+    sym_out = torch.empty(plan.symbols_bytes, dtype=torch.uint8, device=dev)
+    B.co3_decode(plan, last_books, buf, symbols=sym_out)
+    torch.cuda.synchronize()
+    B.profile_begin()
+    for _ in range(3):
+        B.co3_decode(plan, last_books, buf, symbols=sym_out)
+    kd = B.profile_end()
+    res["decode_symbols"] = {"ms": round(kd["k_decode"][0] / kd["k_decode"][1], 4),
+                             "gelem_s": round(elems / (kd["k_decode"][0] / kd["k_decode"][1]) / 1e6, 2)}
+    del sym_out
     others = [runs[k]["summary"] for k in runs if k != a.book]
     if others:
         res["other_book"] = others[0]
