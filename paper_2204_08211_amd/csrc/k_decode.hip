@@ -293,26 +293,45 @@ __device__ inline void decode_user_chunk(const ChunkGeom &g, const ChunkIndex &i
         atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CORRUPT), 1ull);
 }
 
-__global__ __launch_bounds__(64) void k_decode(Layout lay, const uint32_t *__restrict__ words, uint64_t words_stride,
-                                               const uint64_t *__restrict__ chunk_offset,
-                                               const uint16_t *__restrict__ sub_bits,
-                                               const BookDev *__restrict__ books, uint8_t *__restrict__ sym,
-                                               uint64_t sym_stride, float *__restrict__ q, uint64_t q_stride,
-                                               uint64_t *__restrict__ status)
+// co3_decode: a workgroup takes one chunk of kDecWaves consecutive users, a wavefront per user, so
+// that the users share one copy of the code's tables in LDS (with per-user tables every wavefront
+// loads its own).  After decoding, every wavefront writes its own chunk out: no workgroup barrier
+// follows the one that publishes the tables.
+constexpr int kDecWaves = 8;
+__global__ __launch_bounds__(64 * kDecWaves) void k_decode(Layout lay, const uint32_t *__restrict__ words,
+                                                           uint64_t words_stride,
+                                                           const uint64_t *__restrict__ chunk_offset,
+                                                           const uint16_t *__restrict__ sub_bits,
+                                                           const BookDev *__restrict__ books, uint8_t *__restrict__ sym,
+                                                           uint64_t sym_stride, float *__restrict__ q, uint64_t q_stride,
+                                                           uint64_t *__restrict__ status)
 {
-    __shared__ DecLds s_tab;
-    __shared__ uint32_t s_stage[kStageWords];
-    __shared__ uint32_t s_pay[kPayloadAlloc];
-    const uint32_t lane = threadIdx.x;
+    extern __shared__ uint64_t smem64[];
+    DecLds *s_tab = reinterpret_cast<DecLds *>(smem64);   // [per-user books ? kDecWaves : 1]
+    const uint32_t ntab = lay.per_user_books ? kDecWaves : 1;
+    uint32_t *s_stage_all = reinterpret_cast<uint32_t *>(s_tab + ntab);    // [kDecWaves][kStageWords]
+    uint32_t *s_pay_all = s_stage_all + kDecWaves * kStageWords;           // [kDecWaves][kPayloadAlloc]
+    const uint32_t t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const uint64_t c = blockIdx.x;
-    const uint32_t u = blockIdx.y;
+    const uint32_t u = blockIdx.y * kDecWaves + wave;
+    const bool active = u < lay.U;
     const ChunkGeom g = chunk_geom(lay, c);
-    const BookDev &book = books[(lay.per_user_books ? u * lay.books_per_user : 0u) + (uint32_t)g.book];
-    const ChunkIndex ix = read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits);
-    load_dec_tables(&s_tab, book, lane, 64);
+    ChunkIndex ix;
+    if (active) ix = read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits);
+    const DecLds *my_tab = s_tab;
+    if (lay.per_user_books) {
+        my_tab = s_tab + wave;
+        if (active) load_dec_tables(s_tab + wave, books[u * lay.books_per_user + (uint32_t)g.book], lane, 64);
+    } else {
+        load_dec_tables(s_tab, books[(uint32_t)g.book], t, 64 * kDecWaves);
+    }
     __syncthreads();
-    decode_user_chunk(g, ix, &s_tab, s_pay, s_stage, status);
-    __syncthreads();
+    if (!active) return;  // whole wavefront; wavefront-level synchronisation only from here on
+    uint32_t *s_stage = s_stage_all + wave * kStageWords;
+    decode_user_chunk(g, ix, my_tab, s_pay_all + wave * kPayloadAlloc, s_stage, status);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const uint8_t *stage_b = reinterpret_cast<const uint8_t *>(s_stage);
     if (sym) {
         uint8_t *dst = sym + (uint64_t)u * sym_stride + g.e0;
@@ -451,9 +470,15 @@ hipError_t launch_decode(const Layout &lay, const co3_decode_args &a, const Book
 {
     if (lay.U == 0 || lay.nchunks == 0) return hipSuccess;
     const uint64_t sym_stride = (lay.d + 15) & ~(uint64_t)15;
+    const size_t lds = (size_t)(lay.per_user_books ? kDecWaves : 1) * sizeof(DecLds) +
+                       (size_t)kDecWaves * (kStageWords + kPayloadAlloc) * 4;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_decode),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
     ProfScope prof(K_DECODE, s);
-    hipLaunchKernelGGL(k_decode, dim3((uint32_t)lay.nchunks, lay.U), dim3(64), 0, s, lay, a.words, a.words_stride,
-                       a.chunk_offset, a.sub_bits, books, a.symbols, sym_stride, a.q, a.q_stride, a.status);
+    hipLaunchKernelGGL(k_decode, dim3((uint32_t)lay.nchunks, (lay.U + kDecWaves - 1) / kDecWaves), dim3(64 * kDecWaves),
+                       lds, s, lay, a.words, a.words_stride, a.chunk_offset, a.sub_bits, books, a.symbols, sym_stride,
+                       a.q, a.q_stride, a.status);
     return hipGetLastError();
 }
 
