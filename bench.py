@@ -326,7 +326,7 @@ def main():
     if others:
         res["other_book"] = others[0]
     if not a.no_cpu_baseline:
-        ns = min(U, max(1, int(100e6 // d)))
+        ns = min(U, max(1, int(200e6 // d)))   # about 10-15 s of single-thread oracle work
         host = pool[0][:ns, :d].cpu().numpy()
         res["cpu_baseline"] = cpu_baseline(w, host, bias)
     print(json.dumps(res))
