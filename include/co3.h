@@ -140,7 +140,8 @@ int co3_gennorm_weights(co3_format format, int32_t bias, double mu, double alpha
  * and kurtosis (eq. (kurtosis)) equal those of the sample v = g + gamma m: one read sweep over g
  * and m (fp64 sums of v, v^2, v^3, v^4 in a fixed order), then beta from the kurtosis by bisection
  * on [0.1, 64] (clamped) and alpha from the variance.  params is device memory [U][nseg]; an empty
- * or constant layer (variance below 2^-40 of the mean square) gets alpha = beta = 0.  workspace: device, co3_plan_fit_workspace_bytes().
+ * or constant layer (variance below 2^-40 of the mean square) gets alpha = beta = 0.
+ * workspace: device, co3_plan_fit_workspace_bytes().
  * The paper fits once and holds the parameters for several epochs; so does a caller of this.
  * co3_model_weights_device: integer Huffman weights (device, [num_books][A]) of the model code
  * for those parameters: a table's source is the mixture of the quantized models of the (user,
