@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the same counters
 # on a plain copy (profiles/cfg3_hbm_traffic.md); only valid for the workload they were taken on.
-MEASURED_TRAFFIC_BYTES = {("cfg3", "k_encode_fused"): 5408.8e6, ("cfg3", "k_quantize"): 5585.7e6,
+MEASURED_TRAFFIC_BYTES = {("cfg3", "k_encode_fused"): 5412.8e6, ("cfg3", "k_quantize"): 5585.7e6,
                           ("cfg3", "k_pack"): 847.6e6, ("cfg3", "k_chunk_bits"): 425.5e6,
                           ("cfg3", "k_aggregate"): 486.1e6, ("cfg3", "k_moments"): 3343.7e6}
 
