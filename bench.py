@@ -18,6 +18,7 @@ the device from that round's pooled symbol histogram (quantize sweep, code build
 Whichever is not the headline is measured too and reported under "other_book".
 """
 import argparse
+import dataclasses
 import json
 import math
 import os
@@ -47,6 +48,7 @@ def parse():
                    help="encoder for --book model: the single-sweep kernel (symbols never stored) or the three-step one")
     p.add_argument("--stochastic", action="store_true",
                    help="stochastic fp conversion (dithered Q) instead of the closest representative; a new seed per step")
+    p.add_argument("--per-user-books", action="store_true", help="every user its own code tables instead of pooled ones")
     p.add_argument("--graph", action="store_true",
                    help="replay the step from HIP graphs (one per gradient set of the pool) instead of launching eagerly")
     p.add_argument("--no-cpu-baseline", action="store_true")
@@ -110,6 +112,8 @@ def main():
     from paper_2204_08211_amd import binding as B
 
     w = syn.WORKLOADS[a.workload]
+    if a.per_user_books:
+        w = dataclasses.replace(w, per_user_books=True)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     U, d = w.U, w.d
