@@ -7,7 +7,9 @@
 // A workgroup of four wavefronts takes four consecutive chunks of one user:
 //   1. wavefront w quantizes chunk w (16 KB of g and of m, requested a quarter at a time with the
 //      next quarter in flight while the current one is computed) and leaves the symbols in LDS,
-//      in the rows of 16 + 1 words the pack step reads without bank conflicts;
+//      in the rows of 16 + 1 words the pack step reads without bank conflicts.  A chunk that starts
+//      at an element off the 16-byte grid (layers begin anywhere) takes the same vectors from the
+//      boundary below it; only the ragged last chunk of a layer goes element by element;
 //   2. it sums the code lengths: lane j owns sub-chunk j (steps 1 and 2 need no workgroup barrier);
 //   3. the workgroup's 32-bit-rounded size is published and the sizes of all earlier workgroups of
 //      the user are collected by a decoupled look-back: every workgroup first publishes its own
