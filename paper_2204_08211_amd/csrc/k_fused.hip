@@ -31,8 +31,9 @@ namespace co3 {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 
-constexpr int kFuCpb = 4;                            // chunks (= wavefronts) per workgroup
-constexpr int kFuThreads = 64 * kFuCpb;
+constexpr int kFuCpb = 4;                            // chunks (= wavefronts) per workgroup ...
+constexpr int kFuCpbSmall = 1;                       // ... and for inputs too small to fill the device that way
+constexpr uint64_t kFuSmallGrid = 2048;              // workgroups of kFuCpb chunks below which the small form is used
 constexpr int kFuRow = 17;                           // 16 words of symbols + 1 pad
 constexpr int kFuStage = kSubsPerChunk * kFuRow;     // 1088 words hold a chunk's symbols
 constexpr int kFuWin = 1088;                         // LDS window of the output: 8.5 bit/element per pass
@@ -79,20 +80,20 @@ __device__ inline void fu_lds_barrier()
 
 // kSR: the stochastic conversion (dither from Philox words of (element, user, seed)) instead of
 // the closest representative.
-template <bool kSR>
-__global__ __launch_bounds__(kFuThreads) void k_encode_fused(
+template <bool kSR, int kCpb>
+__global__ __launch_bounds__(64 * kCpb) void k_encode_fused(
     Layout lay, const float *__restrict__ g, const float *m, float *m_out, uint64_t row_stride, float gamma,
     uint64_t seed, const BookDev *__restrict__ books, uint32_t *__restrict__ tickets, uint64_t *lb_state, uint32_t nblk,
     uint32_t spin_limit, uint64_t *__restrict__ chunk_offset, uint16_t *__restrict__ sub_bits,
     uint64_t *__restrict__ payload_bits, uint32_t *__restrict__ words, uint64_t words_stride,
     uint64_t *__restrict__ status)
 {
-    __shared__ uint32_t s_stage[kFuCpb][kFuStage + 1];
-    __shared__ uint32_t s_win[kFuCpb][kFuWin + 1];
-    __shared__ uint32_t s_fast[kFuCpb][kMaxA];
-    __shared__ uint64_t s_e0[kFuCpb];
-    __shared__ uint32_t s_n[kFuCpb], s_book[kFuCpb], s_cbits[kFuCpb];
-    __shared__ int32_t s_bias[kFuCpb];
+    __shared__ uint32_t s_stage[kCpb][kFuStage + 1];
+    __shared__ uint32_t s_win[kCpb][kFuWin + 1];
+    __shared__ uint32_t s_fast[kCpb][kMaxA];
+    __shared__ uint64_t s_e0[kCpb];
+    __shared__ uint32_t s_n[kCpb], s_book[kCpb], s_cbits[kCpb];
+    __shared__ int32_t s_bias[kCpb];
     __shared__ uint64_t s_prefix;
     __shared__ uint32_t s_ticket, s_stalled;
 
@@ -102,10 +103,10 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
     if (t == 0) s_ticket = atomicAdd(&tickets[u], 1u);
     fu_lds_barrier();
     const uint32_t b = s_ticket;  // position among the user's workgroups, < nblk = gridDim.x
-    const uint64_t c0 = (uint64_t)b * kFuCpb;
-    const uint32_t nck = lay.nchunks - c0 < (uint64_t)kFuCpb ? (uint32_t)(lay.nchunks - c0) : (uint32_t)kFuCpb;
+    const uint64_t c0 = (uint64_t)b * kCpb;
+    const uint32_t nck = lay.nchunks - c0 < (uint64_t)kCpb ? (uint32_t)(lay.nchunks - c0) : (uint32_t)kCpb;
 
-    if (t < (uint32_t)kFuCpb) {
+    if (t < (uint32_t)kCpb) {
         uint64_t e0 = 0;
         uint32_t n = 0, bk = 0;
         int32_t bias = 0;
@@ -334,7 +335,7 @@ __global__ __launch_bounds__(kFuThreads) void k_encode_fused(
     uint32_t before = 0;  // 32-bit-rounded sizes of the workgroup's chunks ahead of this wavefront's
     uint32_t own = 0, pay = 0;
 #pragma unroll
-    for (int k = 0; k < kFuCpb; ++k) {
+    for (int k = 0; k < kCpb; ++k) {
         const uint32_t a = (s_cbits[k] + 31u) & ~31u;
         if ((uint32_t)k < wave) before += a;
         own += a;
@@ -470,17 +471,35 @@ __global__ void k_zero_fused(uint64_t *p, uint64_t n, uint64_t *q, uint64_t nq)
     if (i < nq) q[i] = 0;
 }
 
+// Chunks per workgroup for this layout: fewer when there would be too few workgroups to fill the device.
+static int fused_chunks_per_workgroup(const Layout &lay)
+{
+    const uint64_t groups = (uint64_t)lay.U * ((lay.nchunks + kFuCpb - 1) / kFuCpb);
+    return groups < kFuSmallGrid ? kFuCpbSmall : kFuCpb;
+}
+
 size_t fused_workspace_bytes(const Layout &lay)
 {
-    const uint64_t nblk = (lay.nchunks + kFuCpb - 1) / kFuCpb;
+    const uint64_t cpb = (uint64_t)fused_chunks_per_workgroup(lay);
+    const uint64_t nblk = (lay.nchunks + cpb - 1) / cpb;
     // tickets (one 64-bit slot per user) and the look-back entries, plus alignment slack
     return (size_t)(((uint64_t)lay.U + (uint64_t)lay.U * nblk) * sizeof(uint64_t) + 512);
+}
+
+template <bool kSR, int kCpb>
+static void launch_fused_variant(const Layout &lay, const co3_encode_args &a, const BookDev *books, uint32_t *tickets,
+                                 uint64_t *lb_state, uint32_t nblk, hipStream_t s)
+{
+    hipLaunchKernelGGL((k_encode_fused<kSR, kCpb>), dim3(nblk, lay.U), dim3(64 * kCpb), 0, s, lay, a.g, a.m, a.m_out,
+                       a.row_stride, a.gamma, a.seed, books, tickets, lb_state, nblk, kFuSpinLimit, a.chunk_offset,
+                       a.sub_bits, a.payload_bits, a.words, a.words_stride, a.status);
 }
 
 hipError_t launch_encode_fused(const Layout &lay, const co3_encode_args &a, const BookDev *books, hipStream_t s)
 {
     if (lay.U == 0) return hipSuccess;
-    const uint64_t nblk = (lay.nchunks + kFuCpb - 1) / kFuCpb;
+    const int cpb = fused_chunks_per_workgroup(lay);
+    const uint64_t nblk = (lay.nchunks + (uint64_t)cpb - 1) / (uint64_t)cpb;
     uint64_t *base = reinterpret_cast<uint64_t *>((reinterpret_cast<uintptr_t>(a.workspace) + 255u) & ~(uintptr_t)255u);
     uint64_t *ticket_slots = base;               // [U], the low 32 bits of each are the counter
     uint64_t *lb_state = base + lay.U;           // [U][nblk]
@@ -499,15 +518,15 @@ hipError_t launch_encode_fused(const Layout &lay, const co3_encode_args &a, cons
         return hipGetLastError();
     }
     ProfScope prof(K_FUSED, s);
-    const dim3 grid((uint32_t)nblk, lay.U), block(kFuThreads);
-    if (a.rounding == CO3_ROUND_STOCHASTIC)
-        hipLaunchKernelGGL(k_encode_fused<true>, grid, block, 0, s, lay, a.g, a.m, a.m_out, a.row_stride, a.gamma,
-                           a.seed, books, reinterpret_cast<uint32_t *>(ticket_slots), lb_state, (uint32_t)nblk,
-                           kFuSpinLimit, a.chunk_offset, a.sub_bits, a.payload_bits, a.words, a.words_stride, a.status);
-    else
-        hipLaunchKernelGGL(k_encode_fused<false>, grid, block, 0, s, lay, a.g, a.m, a.m_out, a.row_stride, a.gamma,
-                           a.seed, books, reinterpret_cast<uint32_t *>(ticket_slots), lb_state, (uint32_t)nblk,
-                           kFuSpinLimit, a.chunk_offset, a.sub_bits, a.payload_bits, a.words, a.words_stride, a.status);
+    uint32_t *tickets = reinterpret_cast<uint32_t *>(ticket_slots);
+    const bool sr = a.rounding == CO3_ROUND_STOCHASTIC;
+    if (cpb == kFuCpb) {
+        if (sr) launch_fused_variant<true, kFuCpb>(lay, a, books, tickets, lb_state, (uint32_t)nblk, s);
+        else launch_fused_variant<false, kFuCpb>(lay, a, books, tickets, lb_state, (uint32_t)nblk, s);
+    } else {
+        if (sr) launch_fused_variant<true, kFuCpbSmall>(lay, a, books, tickets, lb_state, (uint32_t)nblk, s);
+        else launch_fused_variant<false, kFuCpbSmall>(lay, a, books, tickets, lb_state, (uint32_t)nblk, s);
+    }
     return hipGetLastError();
 }
 

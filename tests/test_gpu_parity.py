@@ -232,10 +232,23 @@ def test_single_sweep_multi_user_multi_segment(per_user):
 
 
 def test_single_sweep_many_workgroups():
-    # more than 64 workgroups per user, so the look-back walks several windows of entries
-    E, M, U = 4, 3, 2
-    d = 4096 * 4 * 150 + 4096 + 17
+    # enough chunks that the encoder takes four chunks per workgroup (smaller inputs get one), and more
+    # than 64 workgroups per user, so that the look-back walks several windows of entries
+    E, M, U = 4, 3, 8
+    d = 4096 * 4 * 261 + 4096 + 17
     rng = np.random.default_rng(31)
+    g = np.stack([syn.gennorm_numpy(rng, d, 1.0, 1e-3) for _ in range(U)])
+    m = np.stack([syn.gennorm_numpy(rng, d, 1.0, 3e-4) for _ in range(U)])
+    bias = syn.bias_for_max(np.abs(g + np.float32(0.9) * m).max(), E)
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[bias]] * U)
+    _single_sweep_case(kw, g, m, 0.9)
+
+
+def test_single_sweep_one_chunk_per_workgroup_many_entries():
+    # the small form (one chunk per workgroup) with more than 64 look-back entries per user
+    E, M, U = 4, 3, 2
+    d = 4096 * 150 + 17
+    rng = np.random.default_rng(32)
     g = np.stack([syn.gennorm_numpy(rng, d, 1.0, 1e-3) for _ in range(U)])
     m = np.stack([syn.gennorm_numpy(rng, d, 1.0, 3e-4) for _ in range(U)])
     bias = syn.bias_for_max(np.abs(g + np.float32(0.9) * m).max(), E)
