@@ -1,5 +1,6 @@
 // Optional per-kernel timing with HIP events recorded on the caller's stream around every
 // kernel the library launches (co3_profile_begin / co3_profile_end in include/co3.h).
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -13,7 +14,7 @@ static const char *kKernelNames[K_COUNT] = {"k_zero_u64", "k_quantize", "k_reduc
 
 struct ProfRecord { int kid; hipEvent_t a, b; };
 static std::mutex g_mu;
-static bool g_on = false;
+static std::atomic<bool> g_on{false};
 static std::vector<ProfRecord> g_recs;
 
 bool profile_enabled() { return g_on; }
