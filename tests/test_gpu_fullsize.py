@@ -117,16 +117,22 @@ def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000,
     assert status[B.STAT_NOCODE] == 0 and status[B.STAT_CAPACITY] == 0 and status[B.STAT_CORRUPT] == 0
     assert status[B.STAT_NONFINITE] == 0
 
-    def verify(m_res, bf, out_res, first):
+    def verify(m_res, bf, out_res, first, seed=None, bk=None):
         """Check one round's outputs (memory m_res, buffers bf, average out_res) against the oracle.
         first: the three-step encoder's round, which also has symbols, a histogram and fresh code tables;
-        otherwise the single-sweep encoder's round with those tables held."""
-        label = name if first else name + " single-sweep"
+        otherwise the single-sweep encoder's round with those tables held; seed: that round used the
+        stochastic conversion with this seed."""
+        label = name if first else name + (" single-sweep" if seed is None else " single-sweep stochastic")
+
+        def ef(gs, ms, b, u, e_first):
+            if seed is None:
+                return orc.ef_step(gs, ms, w.gamma, E, M, b, want_q=False)
+            return orc.ef_step_sr(gs, ms, w.gamma, E, M, b, u, e_first, seed, want_q=False)
         nch = plan.num_chunks
         ctab = chunk_table(seg_len)
         assert len(ctab) == nch
         hist = buf.hist.cpu().numpy().view(np.uint64)
-        lc = [books.export(b) for b in range(plan.num_books)]
+        lc = [(bk or books).export(b) for b in range(plan.num_books)]
         lens = np.stack([x[0] for x in lc]); codes = np.stack([x[1] for x in lc])
         sub_bits = bf.sub_bits.cpu().numpy().view(np.uint16).reshape(U, nch, 64)
         chunk_offset = bf.chunk_offset.cpu().numpy().view(np.uint64)
@@ -168,7 +174,7 @@ def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000,
             m_gpu = m_res[u, :d].cpu().numpy() if detailed else None
             for k in range(nseg):
                 sl = slice(int(seg_off[k]), int(seg_off[k + 1]))
-                mo, so, _, cnt = orc.ef_step(gh[sl], mh[sl], w.gamma, E, M, int(bias[u, k]), want_q=False)
+                mo, so, _, cnt = ef(gh[sl], mh[sl], int(bias[u, k]), u, int(seg_off[k]))
                 sym_o[sl] = so
                 clamped += int(cnt[1])
                 orc.histogram(so, A, oracle_hist[book_of(u, k)])
@@ -226,7 +232,7 @@ def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000,
             syms = np.empty((U, n), np.uint8)
             for u in range(U):
                 gh = g[u, e0:e0 + n].cpu().numpy(); mh = m_in[u, e0:e0 + n].cpu().numpy()
-                mo, so, _, _ = orc.ef_step(gh, mh, w.gamma, E, M, int(bias[u, k]), want_q=False)
+                mo, so, _, _ = ef(gh, mh, int(bias[u, k]), u, e0)
                 assert np.array_equal(mo.view(np.uint32), m_res[u, e0:e0 + n].cpu().numpy().view(np.uint32)), (c, u)
                 if first:
                     assert np.array_equal(so, sym_gpu[u, e0:e0 + n].cpu().numpy()), (c, u)
@@ -272,6 +278,25 @@ def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000,
         nw = int(buf.chunk_offset[u, -1].item()) // 32
         assert torch.equal(buf2.words[u, :nw], buf.words[u, :nw]), f"stream of user {u}"
     print(f"[{name}] single-sweep round identical to the three-step round at {time.time() - t_start:.1f}s", flush=True)
+
+    # Once more with the stochastic conversion (single-sweep encoder, tables held): every element draws its
+    # dither from its index, user and the seed, so the oracle can check any chunk on its own.
+    # The dither reaches symbols the closest-representative round never produced, so the held code is
+    # rebuilt with a weight of at least one for every producible symbol.
+    seed = 0xC03 + w.cfg
+    hist_all = buf.hist.cpu().numpy().view(np.uint64).copy()
+    producible = np.array([not np.isnan(orc.value(s, E, M, 10)) for s in range(A)])
+    hist_all[:, producible] += np.uint64(1)
+    books_sr = B.co3_build_codebook(E, M, plan.num_books, hist_all)
+    m3 = m_in.clone()
+    B.co3_encode(plan, books_sr, g, m3, m3, w.gamma, buf2, mode=B.BOOK_FIXED, single_sweep=True, stochastic_seed=seed)
+    B.co3_ps_aggregate(plan, books_sr, buf2, out2)
+    torch.cuda.synchronize()
+    status3 = buf2.status.cpu().numpy()
+    assert status3[B.STAT_NOCODE] == 0 and status3[B.STAT_CAPACITY] == 0 and status3[B.STAT_CORRUPT] == 0
+    assert status3[B.STAT_STALLED] == 0
+    assert not torch.equal(m3, m2)
+    verify(m3, buf2, out2, False, seed=seed, bk=books_sr)
 
     # The model refresh at full size: moment fit of v = g + gamma m_in for every user and layer; the
     # oracle (two-pass fp64 moments) checks the users it can afford.
