@@ -29,6 +29,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # vector lane-operations per second (non-packed), in 10^12
+VALU_OPS_PER_SYMBOL = {"cfg3": 31.6}          # k_aggregate, measured: SQ_INSTS_VALU x 64 / symbols
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the same counters
 # on a plain copy (profiles/cfg3_hbm_traffic.md); only valid for the workload they were taken on.
@@ -296,6 +298,14 @@ def main():
     roof["kernels"] = {k: {"achieved_GBs": round(alg_bytes[k] * elems / (per_launch[k] * 1e-3) / 1e9, 1),
                            "frac": round(alg_bytes[k] * elems / (per_launch[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
                        for k in alg_bytes if k in per_launch}
+    if "k_aggregate" in roof["kernels"] and w.name in VALU_OPS_PER_SYMBOL:
+        # the decoder moves few bytes: its bound is the vector ALU (and the LDS pipe).  Peak: 256 CUs x 4 SIMDs x
+        # 16 lanes x 2.4 GHz integer lane-operations per second; operations per symbol from SQ_INSTS_VALU
+        # (profiles/cfg3_sq_counters.md)
+        ops = VALU_OPS_PER_SYMBOL[w.name] * elems / (per_launch["k_aggregate"] * 1e-3) / 1e12
+        roof["kernels"]["k_aggregate"].update(bound="alu", valu_ops_per_symbol=VALU_OPS_PER_SYMBOL[w.name],
+                                              achieved_Tops=round(ops, 2), peak_Tops=ALU_PEAK_TOPS,
+                                              alu_frac=round(ops / ALU_PEAK_TOPS, 4))
     res = {
         "metric": "CO3 encode+decode GElem/s and % HBM roofline on 1 MI355X; bits/element",
         "value": head["summary"]["gelem_s"], "unit": "GElem/s",
