@@ -87,8 +87,8 @@ typedef struct co3_codebook co3_codebook;   /* a set of Huffman code tables: lib
  * segments == NULL means one segment covering [0, d) with codebook 0.  per_user_books != 0
  * gives every user its own tables (table index u * books_per_user + segment.codebook)
  * instead of one table per layer shared by all users.
- * Allocates small device tables; synchronises the device.  Not on the per-iteration path:
- * the paper holds the bias for several epochs (Sec. VI).                                   */
+ * 1 <= U <= 65535.  Allocates small device tables; synchronises the device.  Not on the
+ * per-iteration path: the paper holds the bias for several epochs (Sec. VI).               */
 int co3_plan_create(co3_format format, uint32_t U, uint64_t d, uint32_t nseg,
                     const co3_segment *segments, const int32_t *bias, int32_t per_user_books,
                     co3_plan **out);

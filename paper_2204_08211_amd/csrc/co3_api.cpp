@@ -56,7 +56,7 @@ const char *co3_status_string(int status)
 int co3_plan_create(co3_format format, uint32_t U, uint64_t d, uint32_t nseg, const co3_segment *segments,
                     const int32_t *bias, int32_t per_user_books, co3_plan **out)
 {
-    if (!out || !bias || U == 0) return CO3_ERR_ARG;
+    if (!out || !bias || U == 0 || U > 65535u) return CO3_ERR_ARG;  // users are the second grid dimension
     *out = nullptr;
     if (format.exp_bits < 2 || format.mant_bits < 0 || 1 + format.exp_bits + format.mant_bits > 8)
         return CO3_ERR_FORMAT;
