@@ -66,3 +66,16 @@ def test_host_side_argument_checks_need_no_gpu():
                              (ctypes.c_int32 * 2)(3, 3), 0, ctypes.byref(out)) == binding.ERR_ARG
     assert L.co3_encode(None, None, None) == binding.ERR_ARG
     assert L.co3_plan_num_chunks(None) == 0
+    # no users, too many users (they are a grid dimension)
+    assert L.co3_plan_create(binding.Format(4, 3), 0, 10, 0, None, (ctypes.c_int32 * 1)(14), 0, ctypes.byref(out)) == binding.ERR_ARG
+    assert L.co3_plan_create(binding.Format(4, 3), 70000, 10, 0, None, (ctypes.c_int32 * 1)(14), 0, ctypes.byref(out)) == binding.ERR_ARG
+    # null arguments of the model routines; host model routines with impossible parameters
+    assert L.co3_gennorm_fit(None, None, None, 0, 0.9, None, None, 0, None) == binding.ERR_ARG
+    assert L.co3_model_weights_device(None, None, None, None) == binding.ERR_ARG
+    assert L.co3_model_bias_device(None, None, None, None, None, 0, None) == binding.ERR_ARG
+    assert L.co3_plan_set_bias_device(None, None, None) == binding.ERR_ARG
+    b = ctypes.c_int32(0)
+    e = ctypes.c_double(0.0)
+    assert L.co3_bias_from_model(binding.Format(4, 3), 0.0, -1.0, 1.0, ctypes.byref(b), ctypes.byref(e)) == binding.ERR_ARG
+    assert L.co3_bias_from_model(binding.Format(1, 3), 0.0, 1.0, 1.0, ctypes.byref(b), ctypes.byref(e)) == binding.ERR_FORMAT
+    assert L.co3_plan_fit_workspace_bytes(None) == 0 and L.co3_plan_bias_workspace_bytes(None) == 0
