@@ -30,13 +30,21 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # vector lane-operations per second (non-packed), in 10^12
-VALU_OPS_PER_SYMBOL = {"cfg3": 31.6}          # k_aggregate, measured: SQ_INSTS_VALU x 64 / symbols
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the same counters
-# on a plain copy (profiles/cfg3_hbm_traffic.md); only valid for the workload they were taken on.
-MEASURED_TRAFFIC_BYTES = {("cfg3", "k_encode_fused"): 5412.8e6, ("cfg3", "k_quantize"): 5585.7e6,
-                          ("cfg3", "k_pack"): 847.6e6, ("cfg3", "k_chunk_bits"): 425.5e6,
-                          ("cfg3", "k_aggregate"): 486.1e6, ("cfg3", "k_moments"): 3343.7e6}
+
+def counter_figures(workload):
+    """Per-kernel figures from rocprofv3 --pmc runs (HBM bytes per launch, vector instructions per element, LDS
+    bank-conflict share), read from profiles/<workload>_counters.json.  That file records the digest of the library
+    sources it was measured on; for any other build the figures are not quoted (None)."""
+    from paper_2204_08211_amd import build as hip_build
+    path = os.path.join(ROOT, "profiles", f"{workload}_counters.json")
+    if not os.path.exists(path):
+        return None, "no counter file for this workload"
+    with open(path) as fh:
+        c = json.load(fh)
+    if c.get("source_digest") != hip_build.source_digest():
+        return None, "counter file was measured on other sources"
+    return c, None
 
 
 def parse():
@@ -46,6 +54,9 @@ def parse():
     p.add_argument("--warmup", type=int, default=3)
     p.add_argument("--workload", default="cfg3", help="cfg1..cfg5 of BASELINE.json (default: the one the target is quoted on)")
     p.add_argument("--book", default="model", choices=["empirical", "model"])
+    p.add_argument("--gamma", type=float, default=None,
+                   help="memory-decay coefficient (default: the workload's; the others it names are reported under gamma_sweep)")
+    p.add_argument("--no-gamma-sweep", action="store_true", help="skip the workload's other memory-decay coefficients")
     p.add_argument("--model-encoder", default="sweep", choices=["sweep", "three"],
                    help="encoder for --book model: the single-sweep kernel (symbols never stored) or the three-step one")
     p.add_argument("--stochastic", action="store_true",
@@ -116,6 +127,9 @@ def main():
     w = syn.WORKLOADS[a.workload]
     if a.per_user_books:
         w = dataclasses.replace(w, per_user_books=True)
+    sweep_gammas = [] if (a.gamma is not None or a.no_gamma_sweep) else [x for x in w.gammas if x != w.gamma]
+    if a.gamma is not None:
+        w = dataclasses.replace(w, gamma=a.gamma)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     U, d = w.U, w.d
@@ -146,9 +160,11 @@ def main():
     out = torch.zeros(d, dtype=torch.float32, device=dev)
     counter = [0]
 
-    def measure(books, mode, label, single_sweep=False):
+    def measure(books, mode, label, single_sweep=False, gamma=None):
+        gamma = w.gamma if gamma is None else gamma
+
         def eager_step(idx):
-            B.co3_encode(plan, books, pool[idx], m, m, w.gamma, buf, mode=mode, single_sweep=single_sweep,
+            B.co3_encode(plan, books, pool[idx], m, m, gamma, buf, mode=mode, single_sweep=single_sweep,
                          stochastic_seed=(1000 + counter[0]) if a.stochastic else None)
             B.co3_ps_aggregate(plan, books, buf, out)
 
@@ -229,10 +245,11 @@ def main():
 
     refresh = {}
 
-    def model_books():
+    def model_books(gamma=None, refresh=refresh):
         """Code tables of the GenNorm model of v = g + gamma m, all on the device and off the timed path (the
         paper holds the fitted parameters for several epochs): moment fit per user and layer, mixture weights
         per table, Huffman build.  Its cost is reported as "model_refresh"."""
+        gamma = w.gamma if gamma is None else gamma
         books = B.co3_build_codebook(w.E, w.M, plan.num_books, None)
         ws = torch.empty(int(B.lib().co3_plan_fit_workspace_bytes(plan.handle)), dtype=torch.uint8, device=dev)
         params = torch.zeros((U, nseg, 4), dtype=torch.float64, device=dev)
@@ -242,7 +259,7 @@ def main():
             if rep == 2:
                 B.profile_begin()
             t0 = time.perf_counter()
-            B.co3_gennorm_fit(plan, pool[0], m, w.gamma, params=params, workspace=ws)
+            B.co3_gennorm_fit(plan, pool[0], m, gamma, params=params, workspace=ws)
             # the model's own exponent bias (eq. (exp bias)) is computed and timed but not installed: the
             # workload prescribes the bias rule "top binade covers max|v|"
             model_bias, _ = B.co3_model_bias_device(plan, params, install=False)
@@ -260,17 +277,24 @@ def main():
                                                        (model_bias.cpu().numpy() - bias).ravel()[:16]])
         return books
 
+    def settle(gamma):
+        """m_0 = 0, then enough rounds for the memory to reach its steady state under this decay coefficient
+        (a clamped element's remainder drains by a factor gamma per round) before a model of v is fitted."""
+        m.zero_()
+        n = int(min(400, math.ceil(4.0 / max(1.0 - gamma, 1e-2))))
+        for _ in range(n):
+            B.co3_encode(plan, emp_books, pool[counter[0] % a.pool], m, m, gamma, buf, mode=B.BOOK_EMPIRICAL)
+            counter[0] += 1
+        torch.cuda.synchronize()
+        return n
+
     runs = {}
     model_code = None
     order = ["empirical", "model"] if a.book == "empirical" else ["model", "empirical"]
     if a.no_other_book:
         order = order[:1]
-    # the memory m needs a few rounds to reach its steady state before a model of v can be fitted
     emp_books = B.co3_build_codebook(w.E, w.M, plan.num_books, None)
-    for _ in range(2):
-        B.co3_encode(plan, emp_books, pool[counter[0] % a.pool], m, m, w.gamma, buf, mode=B.BOOK_EMPIRICAL)
-        counter[0] += 1
-    torch.cuda.synchronize()
+    settle_rounds = settle(w.gamma)
     for label in order:
         if label == "empirical":
             runs[label] = measure(emp_books, B.BOOK_EMPIRICAL, "empirical")
@@ -289,23 +313,28 @@ def main():
     }
     dom = max(per_launch, key=lambda k: kt[k][0])
     ach = alg_bytes.get(dom, 0.0) * elems / (per_launch[dom] * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, dom))
+    counters, counters_note = counter_figures(w.name)
+    ck = (counters or {}).get("kernels", {})
     roof = dict(bound="hbm", kernel=dom, achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                frac=round(ach / HBM_PEAK_GBS, 4), traffic=traffic,
+                frac=round(ach / HBM_PEAK_GBS, 4), traffic=ck.get(dom, {}).get("traffic_bytes"),
                 bytes_per_element=alg_bytes.get(dom), avg_launch_ms=round(per_launch[dom], 4))
+    if counters_note:
+        roof["traffic_note"] = counters_note
     if dom == "k_aggregate":
         roof["note"] = "the decoder is bound by its serial table-lookup chain (integer ALU / LDS latency), not by HBM"
     roof["kernels"] = {k: {"achieved_GBs": round(alg_bytes[k] * elems / (per_launch[k] * 1e-3) / 1e9, 1),
                            "frac": round(alg_bytes[k] * elems / (per_launch[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
                        for k in alg_bytes if k in per_launch}
-    if "k_aggregate" in roof["kernels"] and w.name in VALU_OPS_PER_SYMBOL:
-        # the decoder moves few bytes: its bound is the vector ALU (and the LDS pipe).  Peak: 256 CUs x 4 SIMDs x
-        # 16 lanes x 2.4 GHz integer lane-operations per second; operations per symbol from SQ_INSTS_VALU
-        # (profiles/cfg3_sq_counters.md)
-        ops = VALU_OPS_PER_SYMBOL[w.name] * elems / (per_launch["k_aggregate"] * 1e-3) / 1e12
-        roof["kernels"]["k_aggregate"].update(bound="alu", valu_ops_per_symbol=VALU_OPS_PER_SYMBOL[w.name],
-                                              achieved_Tops=round(ops, 2), peak_Tops=ALU_PEAK_TOPS,
-                                              alu_frac=round(ops / ALU_PEAK_TOPS, 4))
+    for k, entry in roof["kernels"].items():
+        # what the counters say about the binding unit: vector instructions per element (SQ_INSTS_VALU x 64 /
+        # elements) and the share of the launch the vector ALUs would need for them at the nominal issue rate
+        # (256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz); this is an occupancy of the unit, not a roofline fraction
+        if k in ck and ck[k].get("valu_per_element") is not None:
+            vpe = ck[k]["valu_per_element"]
+            entry.update(valu_per_element=vpe, lds_bank_conflict_share=ck[k].get("lds_conflict_share"),
+                         valu_busy=round(vpe * elems / (per_launch[k] * 1e-3) / 1e12 / ALU_PEAK_TOPS, 4))
+    if "k_aggregate" in roof["kernels"]:
+        roof["kernels"]["k_aggregate"]["gsymbols_s"] = round(elems / (per_launch["k_aggregate"] * 1e-3) / 1e9, 2)
     res = {
         "metric": "CO3 encode+decode GElem/s and % HBM roofline on 1 MI355X; bits/element",
         "value": head["summary"]["gelem_s"], "unit": "GElem/s",
@@ -339,6 +368,27 @@ def main():
     others = [runs[k]["summary"] for k in runs if k != a.book]
     if others:
         res["other_book"] = others[0]
+    res["settle_rounds"] = settle_rounds
+    res["source_digest"] = __import__("paper_2204_08211_amd.build", fromlist=["x"]).source_digest()
+    # the workload's other memory-decay coefficients: the same two measurements from a memory settled under each
+    if sweep_gammas:
+        sweep = {}
+        for gm in sweep_gammas:
+            n = settle(gm)
+            mb = model_books(gm, refresh={})
+            r_model = measure(mb, B.BOOK_FIXED, "model", single_sweep=a.model_encoder == "sweep", gamma=gm)
+            r_emp = measure(emp_books, B.BOOK_EMPIRICAL, "empirical", gamma=gm)
+            sweep[str(gm)] = {
+                "settle_rounds": n,
+                "model": {k: r_model["summary"][k] for k in ("ms_per_step", "gelem_s", "encode", "decode_average", "bits_per_element")},
+                "empirical": {k: r_emp["summary"][k] for k in ("ms_per_step", "gelem_s", "encode", "decode_average", "bits_per_element")},
+                "clamped_per_step": round(r_model["status"][B.STAT_CLAMPED] / a.steps, 1),
+                "encode_fused_hbm_frac": round((12.0 + r_model["bpe"] / 8.0) * elems / (r_model["per_launch"]["k_encode_fused"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+                if "k_encode_fused" in r_model["per_launch"] else None,
+            }
+            del mb
+        res["gamma_sweep"] = sweep
+    res["clamped_per_step"] = round(head["status"][B.STAT_CLAMPED] / a.steps, 1)
     if not a.no_cpu_baseline:
         ns = min(U, max(1, int(200e6 // d)))   # about 10-15 s of single-thread oracle work
         host = pool[0][:ns, :d].cpu().numpy()

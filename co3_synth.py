@@ -30,6 +30,7 @@ class Workload:
     M: int
     gamma: float                       # memory-decay coefficient (lambda of the workload list)
     iters: int
+    gammas: tuple = ()                 # every coefficient the workload names (default: just gamma)
     beta: Optional[float] = None       # None: per-user, uniform in beta_range
     beta_range: tuple = (0.6, 1.4)
     alpha: Optional[float] = None      # None: per-user log-uniform in alpha_range
@@ -42,6 +43,8 @@ class Workload:
     seg_len: List[int] = field(default_factory=list)
 
     def __post_init__(self):
+        if not self.gammas:
+            self.gammas = (self.gamma,)
         if not self.seg_len:
             self.seg_len = powerlaw_segments(self.d, self.nseg) if self.nseg > 1 else [self.d]
 
@@ -83,7 +86,7 @@ def powerlaw_segments(d: int, nseg: int, exponent: float = 1.2) -> List[int]:
 WORKLOADS = {
     "cfg1": Workload("cfg1", 1, U=1, d=1 << 20, E=3, M=0, gamma=0.9, iters=3, beta=1.0, alpha=1e-3),
     "cfg2": Workload("cfg2", 2, U=10, d=11_689_512, E=4, M=1, gamma=0.9, iters=5, beta=0.8, alpha=1e-3),
-    "cfg3": Workload("cfg3", 3, U=16, d=25_557_032, E=4, M=3, gamma=0.9, iters=3,
+    "cfg3": Workload("cfg3", 3, U=16, d=25_557_032, E=4, M=3, gamma=0.9, iters=3, gammas=(0.5, 0.9, 0.99),
                      per_user_books=False),
     "cfg4": Workload("cfg4", 4, U=8, d=138_357_544, E=3, M=2, gamma=0.9, iters=3, beta=1.0, alpha=1e-3,
                      nseg=16, seg_alpha_range=(1e-5, 1e-2)),

@@ -127,8 +127,8 @@ uint32_t co3_codebook_num_books(const co3_codebook *books);
 void co3_codebook_destroy(co3_codebook *books);
 
 /* Integer weights for co3_build_codebook when the corrected gradient g + gamma m of a layer is
- * modelled as GenNorm(mu, alpha, beta) (Sec. III eq. (gennorm); Sec. IV-A (ii): Huffman coding
- * "using the GenNorm assumption").  weights is host memory, A entries: every symbol Q_fp can
+ * modelled as GenNorm(mu, alpha, beta) (Sec. III eq. (gennorm); Sec. IV-A (ii): the Huffman code
+ * is designed from that model).  weights is host memory, A entries: every symbol Q_fp can
  * produce gets max(1, floor(p * 2^40)), p the model probability that Q_fp yields it; the other
  * bit patterns (top exponent field, negative zero) get 0.  Host arithmetic, no GPU involved.
  * Errors: CO3_ERR_ARG for alpha <= 0, beta <= 0 or a non-finite mu; CO3_ERR_FORMAT.          */
@@ -271,6 +271,16 @@ typedef struct {
 } co3_kernel_time;
 int co3_profile_begin(void);
 int co3_profile_end(co3_kernel_time *out, uint32_t capacity, uint32_t *count);
+
+/* The single-sweep encoder waits for the sizes of the chunks ahead of a workgroup by polling; the
+ * wait is bounded by `polls` re-reads per predecessor entry (default CO3_LOOKBACK_POLLS_DEFAULT,
+ * far more than any wait that ends).  A workgroup whose bound runs out writes no stream words,
+ * leaves its chunk_offset entries untouched and is counted in status[CO3_STAT_STALLED]; so are all
+ * later workgroups of that user.  m_out, sub_bits and payload_bits are complete all the same.
+ * polls = 0 gives up at the first entry that is not there yet (a way to exercise that path from
+ * the host).  Process-wide; applies to calls of co3_encode made afterwards.                    */
+#define CO3_LOOKBACK_POLLS_DEFAULT (1u << 20)
+void co3_set_lookback_polls(uint32_t polls);
 
 /* Human-readable name of a status code.                                                     */
 const char *co3_status_string(int status);

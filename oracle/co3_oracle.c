@@ -228,9 +228,9 @@ int co3o_ef_step(const float *g, const float *m, uint64_t n, float gamma,
 }
 
 /* ------------------------------------------------------------------------- */
-/* Stochastic fp conversion (Sec. II-B (ii): "the mapping Q is meant as a     */
-/* stochastic mapping, so that non-subtractive dither quantization can be     */
-/* implemented"), reading R9: v goes to one of its two neighbours in X, the   */
+/* Stochastic fp conversion (Sec. II-B (ii) allows Q to be a random mapping,   */
+/* which is what non-subtractive dithering needs; the paper gives no          */
+/* construction).  Reading: v goes to one of its two neighbours in X, the     */
 /* upper one with probability (|v| - lo) / (hi - lo), decided by adding a     */
 /* uniform integer dither to the position of |v| between them and truncating. */
 /* The dither has as many bits as fp32 resolves between the neighbours        */

@@ -27,7 +27,7 @@ EXPORTS = [
     "co3_codebook_destroy", "co3_encode", "co3_decode", "co3_ps_aggregate", "co3_status_string",
     "co3_profile_begin", "co3_profile_end", "co3_gennorm_weights", "co3_plan_fit_workspace_bytes", "co3_gennorm_fit",
     "co3_model_weights_device", "co3_model_bias_device", "co3_plan_set_bias_device", "co3_bias_from_model",
-    "co3_plan_bias_workspace_bytes",
+    "co3_plan_bias_workspace_bytes", "co3_set_lookback_polls",
 ]
 
 
@@ -117,6 +117,8 @@ def lib():
         L.co3_plan_set_bias_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.co3_bias_from_model.argtypes = [Format, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_int32),
                                           C.POINTER(C.c_double)]
+        L.co3_set_lookback_polls.argtypes = [C.c_uint32]
+        L.co3_set_lookback_polls.restype = None
         L.co3_status_string.argtypes = [C.c_int]
         L.co3_status_string.restype = C.c_char_p
         _lib = L
@@ -133,6 +135,14 @@ def profile_end():
     n = C.c_uint32(0)
     _check("co3_profile_end", lib().co3_profile_end(arr, 16, C.byref(n)))
     return {arr[i].name.decode(): (arr[i].total_ms, int(arr[i].launches)) for i in range(n.value)}
+
+
+LOOKBACK_POLLS_DEFAULT = 1 << 20
+
+
+def set_lookback_polls(polls):
+    """Bound of the single-sweep encoder's wait for the chunks ahead (re-reads per entry); 0 gives up at once."""
+    lib().co3_set_lookback_polls(int(polls))
 
 
 def status_string(code):

@@ -22,6 +22,21 @@ FLAGS = [
 ]
 
 
+def source_digest() -> str:
+    """SHA-256 over the library's sources (csrc/ and include/co3.h), names and contents in sorted order.
+    Counter figures measured on one build are only quoted for a build with the same digest."""
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".cpp", ".h")))
+    files.append(os.path.join(ROOT, "include", "co3.h"))
+    for f in files:
+        h.update(os.path.basename(f).encode() + b"\0")
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+        h.update(b"\0")
+    return h.hexdigest()
+
+
 def build(verbose: bool = False) -> str:
     objs = []
     procs = []

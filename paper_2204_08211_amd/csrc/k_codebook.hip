@@ -34,6 +34,10 @@ __global__ __launch_bounds__(kCbThreads) void k_build_books(BookDev *__restrict_
     parent[t + kMaxA] = -1;
     if (t < 65) { cnt[t] = 0; off[t] = 0; first[t] = 0; }
     if (t == 0) err = 0;
+    __syncthreads();
+    // 2^64 - 1 marks an exhausted queue in the merge below; as a weight it is refused, like the
+    // host builder refuses it (the table's weights would sum to 2^64 - 1 or more)
+    if (myw == ~0ull) err = 1;
     const int n = __syncthreads_count(myw > 0);
 
     // rank of this leaf in (weight, symbol) order among the active symbols
@@ -49,7 +53,7 @@ __global__ __launch_bounds__(kCbThreads) void k_build_books(BookDev *__restrict_
     }
     __syncthreads();
 
-    if (t == 0 && n >= 2) {
+    if (t == 0 && n >= 2 && !err) {
         // the two front entries of each queue live in registers, so that the load refilling a queue
         // is not needed before the pick after next; an exhausted slot shows the sentinel
         const uint64_t kNone = ~0ull;

@@ -24,6 +24,8 @@
 //   4. wavefront w appends the codewords of chunk w inside an LDS window at the bit offsets given
 //      by the wave prefix sum of the sub-chunk sizes (this needs no stream offset and runs while
 //      the look-back's answers travel) and copies the window out coalesced.
+#include <atomic>
+
 #include "co3_internal.h"
 #include "quantize_math.h"
 
@@ -40,7 +42,7 @@ constexpr int kFuWin = 1088;                         // LDS window of the output
 constexpr int kFuBatch = 4;                          // 16-byte vectors of g (and of m) a lane requests at a time
 constexpr int kFuBatches = kChunk / 4 / 64 / kFuBatch; // batches per chunk
 constexpr int kFuScalar = 8;                         // element rounds a lane requests together on the element path
-constexpr uint32_t kFuSpinLimit = 1u << 20;          // polls of one predecessor entry before giving up
+static std::atomic<uint32_t> g_spin_limit{CO3_LOOKBACK_POLLS_DEFAULT};  // polls of one predecessor entry before giving up
 
 // look-back entry: flag in the top two bits, size in bits below
 constexpr uint64_t kLbAgg = 1ull << 62;      // size of this workgroup alone
@@ -491,7 +493,7 @@ static void launch_fused_variant(const Layout &lay, const co3_encode_args &a, co
                                  uint64_t *lb_state, uint32_t nblk, hipStream_t s)
 {
     hipLaunchKernelGGL((k_encode_fused<kSR, kCpb>), dim3(nblk, lay.U), dim3(64 * kCpb), 0, s, lay, a.g, a.m, a.m_out,
-                       a.row_stride, a.gamma, a.seed, books, tickets, lb_state, nblk, kFuSpinLimit, a.chunk_offset,
+                       a.row_stride, a.gamma, a.seed, books, tickets, lb_state, nblk, g_spin_limit.load(), a.chunk_offset,
                        a.sub_bits, a.payload_bits, a.words, a.words_stride, a.status);
 }
 
@@ -531,3 +533,5 @@ hipError_t launch_encode_fused(const Layout &lay, const co3_encode_args &a, cons
 }
 
 }  // namespace co3
+
+extern "C" void co3_set_lookback_polls(uint32_t polls) { co3::g_spin_limit.store(polls); }

@@ -166,11 +166,11 @@ hipError_t launch_zero_u64(uint64_t *p, uint64_t n, hipStream_t s)
 
 hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, const EncodeWs &ws, hipStream_t s)
 {
-    if (lay.d == 0 || lay.U == 0) return hipSuccess;
+    if (lay.U == 0) return hipSuccess;
     const uint64_t ntiles = (lay.d + kQTile - 1) / kQTile;
     const uint64_t sym_stride = (lay.d + 15) & ~(uint64_t)15;
     const size_t lds = (size_t)lay.A * kHistRep * sizeof(uint32_t);
-    {
+    if (lay.d) {  // a vector without elements still gets its (all-zero) symbol counts from the fold below
         ProfScope prof(K_QUANTIZE, s);
         if (a.rounding == CO3_ROUND_STOCHASTIC)
             hipLaunchKernelGGL(k_quantize<true>, dim3((uint32_t)ntiles, lay.U), dim3(kQThreads), lds, s, lay, a.g, a.m,

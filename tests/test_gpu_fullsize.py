@@ -14,8 +14,19 @@ The oracle cannot run a whole round of the large workloads in test time, so:
 Where the oracle has every user's symbols (workloads 1-3) the histogram and the code tables are
 compared exactly instead.  The round is then repeated through the single-sweep encoder (the
 configuration bench.py's headline times) with the code tables held, checked against the oracle
-in the same way, and compared with the first round everywhere.  Inputs are drawn on the device with the seeded generator and copied to
-the host for the oracle; nothing the oracle computes takes a GPU result as input.
+in the same way, and compared with the first round everywhere; once more with the stochastic
+conversion; and, for the workloads whose users the oracle can fit, once more exactly as bench.py's
+headline runs it: moment fit, model weights and Huffman build on the device, single-sweep encode
+under that model code, PS average.
+
+Inputs are drawn on the device with the seeded generator and copied to the host for the oracle.
+The memory the checked round starts from is the result of a first round from m_0 = 0: the GPU
+carries it, and the oracle recomputes it from that round's gradients wherever it checks something,
+so nothing the oracle computes takes a GPU result as input.  The exponent bias follows the
+workload's rule on the first round (v = g, since m_0 = 0) and is held, as in bench.py.  The one
+exception is stated where it occurs: the model code's integer weights cannot be reproduced bit for
+bit by a second incomplete-gamma routine, so they are compared with the oracle's to a tolerance and
+the device's weights then define the code both sides encode with.
 """
 import heapq
 import time
@@ -66,11 +77,21 @@ def check_code_is_optimal(hist, lens, codes):
     assert np.array_equal(ref, codes)
 
 
-def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000, exact_hist=True):
+def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000, exact_hist=True, gamma=None,
+                 full_users_later=None, model_round=False):
+    """full_users: users checked completely in the first (three-step) round; full_users_later: in the
+    later rounds (default: the same); gamma: another memory-decay coefficient than the workload's
+    default; model_round: also the device-fitted model code, as bench.py's headline runs it."""
+    import dataclasses
     import torch
     from paper_2204_08211_amd import binding as B
     t_start = time.time()
     w = syn.WORKLOADS[name]
+    if gamma is not None:
+        w = dataclasses.replace(w, gamma=gamma)
+        name = f"{name} gamma={gamma}"
+    if full_users_later is None:
+        full_users_later = full_users
     dev = torch.device("cuda:0")
     U, d, E, M = w.U, w.d, w.E, w.M
     A = 1 << (1 + E + M)
@@ -81,32 +102,25 @@ def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000,
     seg_off = np.concatenate([[0], np.cumsum(seg_len)]).astype(np.int64)
     print(f"[{name}] U={U} d={d} [1,{E},{M}] nseg={nseg}", flush=True)
 
-    def bias_for(g, m):
-        mx = np.zeros((U, nseg))
-        for k in range(nseg):
-            sl = slice(int(seg_off[k]), int(seg_off[k + 1]))
-            v = g[:, sl] + np.float32(w.gamma) * m[:, sl]
-            mx[:, k] = v.abs().amax(dim=1).cpu().numpy()
-            del v
-        return syn.bias_table(mx, E)
-
+    g0 = torch.zeros((U, stride), dtype=torch.float32, device=dev)
     g = torch.zeros((U, stride), dtype=torch.float32, device=dev)
     m = torch.zeros((U, stride), dtype=torch.float32, device=dev)
     out = torch.zeros(d, dtype=torch.float32, device=dev)
 
-    # iteration 0 (m_0 = 0) only produces a realistic memory; iteration 1 is the one checked
+    # round 0 (m_0 = 0) only produces a realistic memory; round 1 is the one checked.  The bias is the
+    # workload's rule on round 0 (v = g there), held for round 1, where some elements then clamp.
     for u in range(U):
-        syn.user_gradient_torch(w, 0, u, dev, out=g[u, :d])
-    bias = bias_for(g, m)
+        syn.user_gradient_torch(w, 0, u, dev, out=g0[u, :d])
+        syn.user_gradient_torch(w, 1, u, dev, out=g[u, :d])
+    mx = np.zeros((U, nseg))
+    for k in range(nseg):
+        mx[:, k] = g0[:, int(seg_off[k]):int(seg_off[k + 1])].abs().amax(dim=1).cpu().numpy()
+    bias = syn.bias_table(mx, E)
     plan = B.Plan(E, M, U, d, bias, seg_len=seg_len, seg_book=seg_book, per_user_books=w.per_user_books)
     books = B.co3_build_codebook(E, M, plan.num_books, None)
     buf = B.RoundBuffers(plan, dev, max_code_len=16)
-    B.co3_encode(plan, books, g, m, m, w.gamma, buf, mode=B.BOOK_EMPIRICAL)
+    B.co3_encode(plan, books, g0, m, m, w.gamma, buf, mode=B.BOOK_EMPIRICAL)
     torch.cuda.synchronize()
-    for u in range(U):
-        syn.user_gradient_torch(w, 1, u, dev, out=g[u, :d])
-    bias = bias_for(g, m)
-    plan.set_bias(bias)
     m_in = m.clone()
     buf.status.zero_()
     B.co3_encode(plan, books, g, m, m, w.gamma, buf, mode=B.BOOK_EMPIRICAL)
@@ -117,12 +131,21 @@ def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000,
     assert status[B.STAT_NOCODE] == 0 and status[B.STAT_CAPACITY] == 0 and status[B.STAT_CORRUPT] == 0
     assert status[B.STAT_NONFINITE] == 0
 
-    def verify(m_res, bf, out_res, first, seed=None, bk=None):
+    def oracle_m_in(u, lo, hi, k):
+        """The memory after round 0 (from m_0 = 0), elements lo..hi of user u in layer k: the oracle's own."""
+        g0h = g0[u, lo:hi].cpu().numpy()
+        mo = orc.ef_step(g0h, np.zeros_like(g0h), w.gamma, E, M, int(bias[u, k]), want_q=False)[0]
+        assert np.array_equal(mo.view(np.uint32), m_in[u, lo:hi].cpu().numpy().view(np.uint32)), \
+            f"memory after round 0, user {u} layer {k}"
+        return mo
+
+    def verify(m_res, bf, out_res, first, seed=None, bk=None, tag=None):
         """Check one round's outputs (memory m_res, buffers bf, average out_res) against the oracle.
         first: the three-step encoder's round, which also has symbols, a histogram and fresh code tables;
-        otherwise the single-sweep encoder's round with those tables held; seed: that round used the
-        stochastic conversion with this seed."""
-        label = name if first else name + (" single-sweep" if seed is None else " single-sweep stochastic")
+        otherwise the single-sweep encoder's round with the tables `bk` (default: those of the first
+        round) held; seed: that round used the stochastic conversion with this seed."""
+        label = name if first else name + " " + (tag or ("single-sweep" if seed is None else "single-sweep stochastic"))
+        detailed_users = full_users if first else full_users_later
 
         def ef(gs, ms, b, u, e_first):
             if seed is None:
@@ -166,11 +189,14 @@ def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000,
         # ---- users checked completely ----------------------------------------------------------
         oracle_hist = np.zeros_like(hist)
         clamped = 0
-        full_list = list(range(U)) if exact_hist and first else list(full_users)
+        full_list = list(range(U)) if exact_hist and first else list(detailed_users)
         for u in full_list:
-            gh = g[u, :d].cpu().numpy(); mh = m_in[u, :d].cpu().numpy()
+            gh = g[u, :d].cpu().numpy()
+            mh = np.empty(d, np.float32)
+            for k in range(nseg):
+                mh[int(seg_off[k]):int(seg_off[k + 1])] = oracle_m_in(u, int(seg_off[k]), int(seg_off[k + 1]), k)
             sym_o = np.empty(d, np.uint8)
-            detailed = u in full_users
+            detailed = u in detailed_users
             m_gpu = m_res[u, :d].cpu().numpy() if detailed else None
             for k in range(nseg):
                 sl = slice(int(seg_off[k]), int(seg_off[k + 1]))
@@ -197,7 +223,7 @@ def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000,
                 if d <= full_words_limit and exact_hist:
                     pass  # the whole bitstream is compared below, once the oracle's own code is known
             print(f"[{label}] user {u} {'checked' if detailed else 'counted'} at {time.time() - t_start:.1f}s", flush=True)
-            if detailed and d <= full_words_limit:
+            if detailed and (d <= full_words_limit or (first and full_words_limit < 0)):
                 # whole bitstream of this user with the exported tables (they are checked against the
                 # oracle's own tables below when the oracle has the full histogram)
                 r = orc.pack(sym_o, seg_len, [book_of(u, k) for k in range(nseg)], lens, codes)
@@ -231,7 +257,7 @@ def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000,
             e0, n, k = ctab[c]
             syms = np.empty((U, n), np.uint8)
             for u in range(U):
-                gh = g[u, e0:e0 + n].cpu().numpy(); mh = m_in[u, e0:e0 + n].cpu().numpy()
+                gh = g[u, e0:e0 + n].cpu().numpy(); mh = oracle_m_in(u, e0, e0 + n, k)
                 mo, so, _, _ = ef(gh, mh, int(bias[u, k]), u, e0)
                 assert np.array_equal(mo.view(np.uint32), m_res[u, e0:e0 + n].cpu().numpy().view(np.uint32)), (c, u)
                 if first:
@@ -298,16 +324,21 @@ def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000,
     assert not torch.equal(m3, m2)
     verify(m3, buf2, out2, False, seed=seed, bk=books_sr)
 
-    # The model refresh at full size: moment fit of v = g + gamma m_in for every user and layer; the
-    # oracle (two-pass fp64 moments) checks the users it can afford.
+    # The model refresh at full size: moment fit of v = g + gamma m_in for every user and layer.  The oracle
+    # (two-pass fp64 moments of its own v) checks every user when it can afford to, else the first full ones.
     from oracle import co3_gennorm_fit as fitm
     params = B.co3_gennorm_fit(plan, g, m_in, w.gamma)
     torch.cuda.synchronize()
     par = params.cpu().numpy()
-    fit_users = list(full_users) if full_users else [0]
-    for u in fit_users[:2]:
-        gh = g[u, :d].cpu().numpy(); mh = m_in[u, :d].cpu().numpy()
+    fit_users = list(range(U)) if model_round else (list(full_users) if full_users else [0])[:2]
+    ref_par = np.zeros((U, nseg, 4))
+    for u in fit_users:
+        gh = g[u, :d].cpu().numpy()
+        mh = np.empty(d, np.float32)
+        for k in range(nseg):
+            mh[int(seg_off[k]):int(seg_off[k + 1])] = oracle_m_in(u, int(seg_off[k]), int(seg_off[k + 1]), k)
         ref = fitm.fit_round(gh[None, :], mh[None, :], w.gamma, seg_len)[0]
+        ref_par[u] = ref
         for k in range(nseg):
             if ref[k, 1] == 0.0:
                 assert par[u, k, 1] == 0.0 and par[u, k, 2] == 0.0
@@ -317,21 +348,61 @@ def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000,
             assert abs(par[u, k, 3] / ref[k, 3] - 1.0) <= 1e-9, (u, k, par[u, k, 3], ref[k, 3])
             assert abs(par[u, k, 2] / ref[k, 2] - 1.0) <= 1e-9 and abs(par[u, k, 1] / ref[k, 1] - 1.0) <= 1e-9, (u, k)
         del gh, mh
-    print(f"[{name}] moment fit of users {fit_users[:2]} equals the oracle's at {time.time() - t_start:.1f}s; "
+    print(f"[{name}] moment fit of users {fit_users} equals the oracle's at {time.time() - t_start:.1f}s; "
           f"beta in [{par[:, :, 2].min():.3f}, {par[:, :, 2].max():.3f}]", flush=True)
+    if not model_round:
+        return
+
+    # The round as bench.py's headline runs it: the model code designed on the device (fit above ->
+    # mixture weights -> Huffman build, no host step), held, and the single-sweep encoder under it.  Every
+    # producible symbol has a weight of at least one, so this code has far longer codewords than the
+    # histogram's.  The device's integer weights are held to |dw| <= 1 + 1e-9 w against the oracle's own
+    # (from its own fit); the oracle's Huffman construction on the device's weights must then give the
+    # device's tables, and the streams are checked against the oracle under those tables.
+    weights_t = B.co3_model_weights_device(plan, params)
+    books_m = B.co3_build_codebook(E, M, plan.num_books, None)
+    B.co3_build_codebook_device(books_m, weights_t, buf2.status)
+    torch.cuda.synchronize()
+    wts = weights_t.cpu().numpy().view(np.uint64)
+    ref_w = fitm.pooled_model_weights(E, M, bias, ref_par, seg_len, seg_book, w.per_user_books)
+    assert np.array_equal(wts > 0, ref_w > 0)
+    dw = np.abs(wts.astype(np.float64) - ref_w.astype(np.float64))
+    assert np.all(dw <= 1.0 + 1e-9 * ref_w.astype(np.float64)), dw.max()
+    for b in range(plan.num_books):
+        lo, co = orc.codebook(wts[b])
+        ld, cd = books_m.export(b)
+        assert np.array_equal(lo, ld) and np.array_equal(co, cd), f"model code table {b}"
+    m4 = m_in.clone()
+    buf2.status.zero_()
+    buf2.chunk_offset.fill_(-1); buf2.sub_bits.fill_(-1); buf2.payload_bits.fill_(-1)
+    B.co3_encode(plan, books_m, g, m4, m4, w.gamma, buf2, mode=B.BOOK_FIXED, single_sweep=True)
+    B.co3_ps_aggregate(plan, books_m, buf2, out2)
+    torch.cuda.synchronize()
+    status4 = buf2.status.cpu().numpy()
+    assert status4[B.STAT_NOCODE] == 0 and status4[B.STAT_CAPACITY] == 0 and status4[B.STAT_CORRUPT] == 0
+    assert status4[B.STAT_STALLED] == 0 and status4[B.STAT_CODELEN] == 0
+    assert status4[B.STAT_CLAMPED] == status[B.STAT_CLAMPED]
+    assert torch.equal(m4, m) and torch.equal(out2, out)       # memory and average do not depend on the code
+    verify(m4, buf2, out2, False, bk=books_m, tag="single-sweep, device-fitted model code")
+    bits_model = float(buf2.payload_bits.cpu().numpy().astype(np.float64).sum()) / (U * d)
+    bits_emp = float(buf.payload_bits.cpu().numpy().astype(np.float64).sum()) / (U * d)
+    print(f"[{name}] model code {bits_model:.4f} bit/element, histogram code {bits_emp:.4f}; clamped "
+          f"{int(status[B.STAT_CLAMPED])} of {U * d}", flush=True)
+    assert bits_model <= 1.02 * bits_emp
 
 
 def test_cfg1_full():
-    run_workload("cfg1", full_users=[0], n_random_chunks=24)
+    run_workload("cfg1", full_users=[0], n_random_chunks=24, model_round=True)
 
 
 def test_cfg2_full():
-    run_workload("cfg2", full_users=[0, 9], n_random_chunks=24)
+    run_workload("cfg2", full_users=[0, 9], n_random_chunks=24, model_round=True)
 
 
-def test_cfg3_full():
-    # the workload bench.py times
-    run_workload("cfg3", full_users=[0, 15], n_random_chunks=24)
+@pytest.mark.parametrize("gamma", syn.WORKLOADS["cfg3"].gammas)
+def test_cfg3_full(gamma):
+    # the workload bench.py times, at each memory-decay coefficient the workload names
+    run_workload("cfg3", full_users=[0, 15], n_random_chunks=24, gamma=gamma, model_round=True)
 
 
 def test_cfg4_full():
@@ -340,5 +411,7 @@ def test_cfg4_full():
 
 
 def test_cfg5_full():
-    # more than 2^32 stream bits per user and more than 2^32 elements in the batch
-    run_workload("cfg5", full_users=[], n_random_chunks=24, exact_hist=False, full_words_limit=0)
+    # more than 2^32 stream bits per user and more than 2^32 elements in the batch; user 0 is checked
+    # completely (memory, symbols, sub-chunk bits, every stream word) in the three-step round
+    run_workload("cfg5", full_users=[0], full_users_later=[], n_random_chunks=24, exact_hist=False,
+                 full_words_limit=-1)

@@ -302,6 +302,83 @@ def test_single_sweep_capacity_and_nocode():
     assert int(gpu["status_encode"][2]) == int(ref["hist"][0][third])
 
 
+def test_single_sweep_bounded_wait_gives_up():
+    # The look-back's wait is bounded.  With the bound set to zero from the host a workgroup gives up at the
+    # first predecessor entry that is not there yet: it writes no stream words, leaves its chunk offsets
+    # untouched and is counted, and so are the workgroups behind it that meet its entry.  Every kernel
+    # still ends normally; memory, sub-chunk bits and payload are complete; and whatever was written to
+    # the streams is what the oracle writes there.
+    import torch
+    from paper_2204_08211_amd import binding as B
+    E, M, U = 4, 3, 4
+    d = 4096 * 4 * 300 + 4096 + 17
+    rng = np.random.default_rng(77)
+    g = np.stack([syn.gennorm_numpy(rng, d, 1.0, 1e-3) for _ in range(U)])
+    m = np.stack([syn.gennorm_numpy(rng, d, 1.0, 3e-4) for _ in range(U)])
+    bias = syn.bias_for_max(np.abs(g + np.float32(0.9) * m).max(), E)
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[bias]] * U)
+    weights = gu.oracle_round(kw, g, m, 0.9)["hist"]
+    ref = gu.oracle_round(kw, g, m, 0.9, weights=weights)
+    B.set_lookback_polls(0)
+    try:
+        gpu, (plan, books, buf, gt, mt) = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=weights, single_sweep=True,
+                                                       want_decode=False)
+    finally:
+        B.set_lookback_polls(B.LOOKBACK_POLLS_DEFAULT)
+    stalled = int(gpu["status_encode"][B.STAT_STALLED])
+    nch = plan.num_chunks
+    print(f"{stalled} of {U * ((nch + 3) // 4)} workgroups gave up", flush=True)
+    assert stalled > 0
+    gu.assert_bits_equal(gpu["m_new"], ref["m_new"], "memory m'")
+    gu.assert_bits_equal(gpu["sub_bits"], ref["sub_bits"], "sub-chunk bits")
+    gu.assert_bits_equal(gpu["payload_bits"], ref["payload_bits"], "payload bits")
+    untouched = np.uint64(0xFFFFFFFFFFFFFFFF)
+    skipped = 0
+    for u in range(U):
+        co = gpu["chunk_offset"][u]
+        expect = np.zeros(buf.words_stride, np.uint32)       # the buffer starts out as zeros
+        for c in range(nch):
+            if co[c] == untouched:
+                skipped += 1
+                continue
+            assert co[c] == ref["chunk_offset"][u][c], (u, c)
+            w0, w1 = int(ref["chunk_offset"][u][c]) // 32, int(ref["chunk_offset"][u][c + 1]) // 32
+            expect[w0:w1] = ref["words"][u][w0:w1]
+        assert co[nch] in (untouched, ref["chunk_offset"][u][nch])
+        gu.assert_bits_equal(gpu["words"][u], expect, f"stream of user {u}: written chunks as the oracle's, the rest untouched")
+    # chunks are skipped by whole workgroups of four
+    assert skipped >= stalled and skipped <= 4 * stalled
+    # and with the default bound the same call completes
+    gpu2, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=weights, single_sweep=True, want_decode=False)
+    gu.compare_round(gpu2, ref, d, decode=False, single_sweep=True)
+
+
+def test_device_builder_refuses_the_sentinel_weight():
+    # 2^64 - 1 is the device merge's "queue exhausted" mark; as a weight it is refused before the merge
+    # (the host builder refuses it too: the weights sum to 2^64 - 1 or more): counted, table left empty
+    import torch
+    from paper_2204_08211_amd import binding as B
+    E, M = 3, 2
+    A = 1 << (1 + E + M)
+    w = np.zeros((2, A), np.uint64)
+    w[0, 1] = 1; w[0, 2] = np.uint64(0xFFFFFFFFFFFFFFFF)
+    w[1, :8] = np.arange(1, 9, dtype=np.uint64)              # a sound table next to it
+    with pytest.raises(B.Co3Error) as ei:
+        B.co3_build_codebook(E, M, 2, w)
+    assert ei.value.code == B.ERR_ARG
+    books = B.co3_build_codebook(E, M, 2, None)
+    status = torch.zeros(B.STATUS_WORDS, dtype=torch.int64, device="cuda:0")
+    wt = torch.from_numpy(w.view(np.int64)).to("cuda:0")
+    B.co3_build_codebook_device(books, wt, status)
+    torch.cuda.synchronize()
+    assert int(status[B.STAT_CODELEN].item()) == 1
+    lens0, codes0 = books.export(0)
+    assert not lens0.any() and not codes0.any()
+    lens1, codes1 = books.export(1)
+    lo, co = orc.codebook(w[1])
+    assert np.array_equal(lens1, lo) and np.array_equal(codes1, co)
+
+
 # ---- PS model update fused into the average (Algorithm 1 line 14) -------------------------------
 
 @pytest.mark.parametrize("U,eta,with_out", [(1, 1.0, True), (3, 0.1, True), (10, 0.05, False), (16, 0.3, True)])
@@ -411,13 +488,15 @@ def test_tiny_vectors_both_encoders(d):
         z = torch.zeros((U, 4), dtype=torch.float32, device="cuda:0")
         out = torch.zeros(4, dtype=torch.float32, device="cuda:0")
         for single in (False, True):
-            buf.chunk_offset.fill_(-1); buf.payload_bits.fill_(-1)
+            buf.chunk_offset.fill_(-1); buf.payload_bits.fill_(-1); buf.hist.fill_(12345)
             B.co3_encode(plan, books, z, z, z, 0.9, buf, mode=B.BOOK_FIXED if single else B.BOOK_EMPIRICAL,
                          single_sweep=single)
             B.co3_ps_aggregate(plan, books, buf, out)
             torch.cuda.synchronize()
             assert buf.chunk_offset.cpu().numpy().tolist() == [[0]] * U
             assert buf.payload_bits.cpu().numpy().tolist() == [0] * U
+            if not single:   # the histogram is an output of the three-step encoder: cleared even when nothing is counted
+                assert not buf.hist.cpu().numpy().any()
         return
     gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL)
     ref = gu.oracle_round(kw, g, m, 0.9)
