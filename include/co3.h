@@ -221,6 +221,20 @@ typedef struct {
  * written.  A chunk that does not fit words_stride is skipped and counted.                  */
 int co3_encode(const co3_plan *plan, const co3_encode_args *args, void *stream);
 
+/* co3_encode for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and same results as co3_encode, but `workspace` / `workspace_bytes` are ignored: the
+ * partial histograms, per-chunk sizes, ticket counters and look-back entries live in a static
+ * device array of CO3_STATIC_SCRATCH_BYTES that is part of the library (every GPU the library runs
+ * on holds one copy until the process ends; its address on a device is resolved when a plan is
+ * created there).  The call allocates nothing.  A plan with co3_plan_workspace_bytes() above
+ * CO3_STATIC_SCRATCH_BYTES is refused with CO3_ERR_CAPACITY before anything is launched; between
+ * co3_profile_begin() and co3_profile_end() (event timing creates events) it returns CO3_ERR_ARG.
+ * All calls on one GPU share that array: what must start at zero is cleared by the call itself,
+ * but two calls that overlap on one GPU (different streams, or threads) race -- serialise them.   */
+#define CO3_STATIC_SCRATCH_BYTES (8u << 20)
+int co3_encode_static(const co3_plan *plan, const co3_encode_args *args, void *stream);
+
 /* ---- PS side: Algorithm 1 lines 13-14 ----------------------------------------------------*/
 typedef struct {
     const uint32_t *words;        /* device [U][words_stride]                                */

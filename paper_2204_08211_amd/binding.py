@@ -27,7 +27,7 @@ EXPORTS = [
     "co3_codebook_destroy", "co3_encode", "co3_decode", "co3_ps_aggregate", "co3_status_string",
     "co3_profile_begin", "co3_profile_end", "co3_gennorm_weights", "co3_plan_fit_workspace_bytes", "co3_gennorm_fit",
     "co3_model_weights_device", "co3_model_bias_device", "co3_plan_set_bias_device", "co3_bias_from_model",
-    "co3_plan_bias_workspace_bytes", "co3_set_lookback_polls",
+    "co3_plan_bias_workspace_bytes", "co3_set_lookback_polls", "co3_encode_static",
 ]
 
 
@@ -105,6 +105,7 @@ def lib():
         L.co3_codebook_destroy.argtypes = [C.c_void_p]
         L.co3_codebook_destroy.restype = None
         L.co3_encode.argtypes = [C.c_void_p, C.POINTER(EncodeArgs), C.c_void_p]
+        L.co3_encode_static.argtypes = [C.c_void_p, C.POINTER(EncodeArgs), C.c_void_p]
         L.co3_decode.argtypes = [C.c_void_p, C.POINTER(DecodeArgs), C.c_void_p]
         L.co3_ps_aggregate.argtypes = [C.c_void_p, C.POINTER(AggregateArgs), C.c_void_p]
         L.co3_profile_end.argtypes = [C.POINTER(KernelTime), C.c_uint32, C.POINTER(C.c_uint32)]
@@ -341,12 +342,16 @@ class RoundBuffers:
 ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
 
 
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
 def co3_encode(plan, books, g, m, m_out, gamma, buf, mode=BOOK_EMPIRICAL, stream=None, single_sweep=False,
-               stochastic_seed=None):
+               stochastic_seed=None, static=False):
     """User side of one round for all U users (Algorithm 1 lines 8-10).  g, m, m_out are float32
     device tensors [U][row_stride]; outputs land in `buf` (RoundBuffers).  single_sweep (fixed code
     only) passes no symbols and no hist buffer, which selects the library's single-sweep encoder.
-    stochastic_seed: None = closest representative, else the stochastic conversion keyed by that seed."""
+    stochastic_seed: None = closest representative, else the stochastic conversion keyed by that seed.
+    static: call co3_encode_static (the library's own static workspace, no allocation; buf.workspace is not passed)."""
     assert not single_sweep or mode == BOOK_FIXED
     assert g.dim() == 2 and g.shape == m.shape == m_out.shape and g.stride(1) == 1
     assert g.stride(0) == m.stride(0) == m_out.stride(0)
@@ -354,10 +359,13 @@ def co3_encode(plan, books, g, m, m_out, gamma, buf, mode=BOOK_EMPIRICAL, stream
                    books.handle, None if single_sweep else buf.symbols.data_ptr(),
                    None if single_sweep else buf.hist.data_ptr(), buf.words.data_ptr(),
                    buf.words_stride, buf.chunk_offset.data_ptr(), buf.sub_bits.data_ptr(),
-                   buf.payload_bits.data_ptr(), buf.status.data_ptr(), buf.workspace.data_ptr(),
-                   buf.workspace.numel(), ROUND_NEAREST if stochastic_seed is None else ROUND_STOCHASTIC, 0,
+                   buf.payload_bits.data_ptr(), buf.status.data_ptr(), None if static else buf.workspace.data_ptr(),
+                   0 if static else buf.workspace.numel(), ROUND_NEAREST if stochastic_seed is None else ROUND_STOCHASTIC, 0,
                    0 if stochastic_seed is None else int(stochastic_seed) & 0xffffffffffffffff)
-    _check("co3_encode", lib().co3_encode(plan.handle, C.byref(a), _stream(stream)))
+    if static:
+        _check("co3_encode_static", lib().co3_encode_static(plan.handle, C.byref(a), _stream(stream)))
+    else:
+        _check("co3_encode", lib().co3_encode(plan.handle, C.byref(a), _stream(stream)))
 
 
 def co3_decode(plan, books, buf, symbols=None, q=None, stream=None):

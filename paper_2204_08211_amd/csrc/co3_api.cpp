@@ -3,6 +3,7 @@
 // co3_build_codebook exposes.
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -10,6 +11,11 @@
 #include "quantize_math.h"
 
 using namespace co3;
+
+// Workspace of co3_encode_static: one array per GPU, part of the library's code object, so that the
+// call needs no allocation.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the device address it yields (one per device) is what kernels and copies get.
+static __device__ __align__(256) unsigned char scratch[CO3_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -27,6 +33,24 @@ struct DeviceGuard {
 };
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, which must be `dev`; resolved once per device.
+int scratch_address(int dev, void **out)
+{
+    if (dev < 0 || dev >= kMaxDevices) return CO3_ERR_ARG;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CO3_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return CO3_OK;
+}
 
 int check_bias_table(const co3_format &f, const int32_t *bias, size_t n)
 {
@@ -84,6 +108,13 @@ int co3_plan_create(co3_format format, uint32_t U, uint64_t d, uint32_t nseg, co
     co3_plan *p = new (std::nothrow) co3_plan;
     if (!p) return CO3_ERR_ARG;
     if (hipGetDevice(&p->device) != hipSuccess) { delete p; return CO3_ERR_HIP; }
+    {
+        // set-up is the place to resolve the static workspace's address on this device, so that
+        // co3_encode_static itself only looks it up
+        // (a failure here is reported by co3_encode_static, the only call that needs the address)
+        void *unused = nullptr;
+        (void)scratch_address(p->device, &unused);
+    }
     if (hipMalloc(&p->d_segs, sizeof(SegDev) * (nseg + 1)) != hipSuccess ||
         hipMalloc(&p->d_bias, sizeof(int32_t) * (size_t)U * nseg) != hipSuccess ||
         hipMemcpy(p->d_segs, segs.data(), sizeof(SegDev) * (nseg + 1), hipMemcpyHostToDevice) != hipSuccess ||
@@ -233,13 +264,14 @@ static int check_books(const co3_plan *plan, const co3_codebook *books)
     return CO3_OK;
 }
 
-int co3_encode(const co3_plan *plan, const co3_encode_args *a, void *stream)
+// The user side with its workspace given explicitly (the caller's, or the static array).
+static int encode_with_workspace(const co3_plan *plan, const co3_encode_args *a, void *workspace, size_t workspace_bytes,
+                                 void *stream)
 {
-    if (!plan || !a) return CO3_ERR_ARG;
     const Layout &lay = plan->lay;
     // a vector without elements has no sub-chunks: its (empty) sub_bits array may be NULL
     if (!a->g || !a->m || !a->m_out || !a->words || !a->chunk_offset || (!a->sub_bits && lay.nchunks) || !a->payload_bits ||
-        !a->status || !a->workspace)
+        !a->status || !workspace)
         return CO3_ERR_ARG;
     if (a->mode != CO3_BOOK_FIXED && a->mode != CO3_BOOK_EMPIRICAL) return CO3_ERR_ARG;
     if (a->rounding != CO3_ROUND_NEAREST && a->rounding != CO3_ROUND_STOCHASTIC) return CO3_ERR_ARG;
@@ -251,26 +283,47 @@ int co3_encode(const co3_plan *plan, const co3_encode_args *a, void *stream)
         return CO3_ERR_ARG;
     int rc = check_books(plan, a->books);
     if (rc != CO3_OK) return rc;
-    if (a->workspace_bytes < co3_plan_workspace_bytes(plan)) return CO3_ERR_CAPACITY;
+    if (workspace_bytes < co3_plan_workspace_bytes(plan)) return CO3_ERR_CAPACITY;
     if (!(a->gamma == a->gamma)) return CO3_ERR_ARG;
 
-    DeviceGuard guard(plan->device);
+    co3_encode_args args = *a;
+    args.workspace = workspace;
+    args.workspace_bytes = workspace_bytes;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (single_sweep)
-        return launch_encode_fused(lay, *a, a->books->d_books, s) == hipSuccess ? CO3_OK : CO3_ERR_HIP;
+        return launch_encode_fused(lay, args, a->books->d_books, s) == hipSuccess ? CO3_OK : CO3_ERR_HIP;
     EncodeWs ws;
     const uint64_t hist_rep_n = (uint64_t)kHistGlobalRep * lay.nbooks * lay.A;
-    ws.hist_rep = reinterpret_cast<uint64_t *>((reinterpret_cast<uintptr_t>(a->workspace) + 255u) & ~(uintptr_t)255u);
+    ws.hist_rep = reinterpret_cast<uint64_t *>((reinterpret_cast<uintptr_t>(workspace) + 255u) & ~(uintptr_t)255u);
     ws.chunk_bits = reinterpret_cast<uint32_t *>(
         (reinterpret_cast<uintptr_t>(ws.hist_rep + hist_rep_n) + 255u) & ~(uintptr_t)255u);
 
     if (launch_zero_u64(ws.hist_rep, hist_rep_n, s) != hipSuccess) return CO3_ERR_HIP;
-    if (launch_quantize(lay, *a, ws, s) != hipSuccess) return CO3_ERR_HIP;
+    if (launch_quantize(lay, args, ws, s) != hipSuccess) return CO3_ERR_HIP;
     if (a->mode == CO3_BOOK_EMPIRICAL &&
         launch_build_books(a->books->d_books, lay.nbooks, lay.A, a->hist, a->status, s) != hipSuccess)
         return CO3_ERR_HIP;
-    if (launch_pack(lay, *a, a->books->d_books, ws, s) != hipSuccess) return CO3_ERR_HIP;
+    if (launch_pack(lay, args, a->books->d_books, ws, s) != hipSuccess) return CO3_ERR_HIP;
     return CO3_OK;
+}
+
+int co3_encode(const co3_plan *plan, const co3_encode_args *a, void *stream)
+{
+    if (!plan || !a) return CO3_ERR_ARG;
+    DeviceGuard guard(plan->device);
+    return encode_with_workspace(plan, a, a->workspace, a->workspace_bytes, stream);
+}
+
+int co3_encode_static(const co3_plan *plan, const co3_encode_args *a, void *stream)
+{
+    if (!plan || !a) return CO3_ERR_ARG;
+    if (co3_plan_workspace_bytes(plan) > (size_t)CO3_STATIC_SCRATCH_BYTES) return CO3_ERR_CAPACITY;
+    if (profile_enabled()) return CO3_ERR_ARG;   // event timing creates events: not for this entry point
+    DeviceGuard guard(plan->device);
+    void *ws = nullptr;
+    int rc = scratch_address(plan->device, &ws);  // resolved by co3_plan_create; a table look-up here
+    if (rc != CO3_OK) return rc;
+    return encode_with_workspace(plan, a, ws, (size_t)CO3_STATIC_SCRATCH_BYTES, stream);
 }
 
 size_t co3_plan_fit_workspace_bytes(const co3_plan *plan) { return plan ? fit_workspace_bytes(plan->lay) : 0; }

@@ -1,0 +1,82 @@
+"""co3_encode_static, the entry point for callers that cannot allocate (pytest -m gpu): it must give
+exactly what co3_encode gives, on two calls in a row that share the library's static workspace, the
+second with a smaller input, for both encoders; and it must refuse a plan whose workspace does not fit
+the static array before launching anything."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+import co3_synth as syn
+
+pytestmark = pytest.mark.gpu
+
+KEYS = ("m", "symbols", "hist", "words", "chunk_offset", "sub_bits", "payload_bits", "status")
+
+
+def one_call(U, d, seed, single_sweep, static):
+    """One encode through co3_encode or co3_encode_static on fresh buffers; every output as numpy."""
+    import torch
+    from paper_2204_08211_amd import binding as B
+    dev = torch.device("cuda:0")
+    E, M = 4, 3
+    rng = np.random.default_rng(seed)
+    g = np.stack([syn.gennorm_numpy(rng, d, 0.9, 1e-3) for _ in range(U)])
+    m = np.stack([syn.gennorm_numpy(rng, d, 1.1, 3e-4) for _ in range(U)])
+    bias = syn.bias_for_max(np.abs(g + np.float32(0.9) * m).max(), E)
+    plan = B.Plan(E, M, U, d, [[bias]] * U)
+    stride = (d + 3) // 4 * 4
+    gt = torch.zeros((U, stride), dtype=torch.float32, device=dev); gt[:, :d] = torch.from_numpy(g).to(dev)
+    mt = torch.zeros((U, stride), dtype=torch.float32, device=dev); mt[:, :d] = torch.from_numpy(m).to(dev)
+    buf = B.RoundBuffers(plan, dev, max_code_len=32)
+    books = B.co3_build_codebook(E, M, plan.num_books, None)
+    # the code: built by the three-step encoder from this round's histogram (through the entry point under
+    # test); the single-sweep encoder then runs with that code held
+    mt0 = mt.clone()
+    B.co3_encode(plan, books, gt, mt0, mt0, 0.9, buf, mode=B.BOOK_EMPIRICAL, static=static)
+    if single_sweep:
+        buf.status.zero_()
+        buf.chunk_offset.fill_(-1); buf.sub_bits.fill_(-1); buf.payload_bits.fill_(-1); buf.words.zero_()
+        B.co3_encode(plan, books, gt, mt, mt, 0.9, buf, mode=B.BOOK_FIXED, single_sweep=True, static=static)
+    else:
+        mt = mt0
+    torch.cuda.synchronize()
+    out = dict(m=mt[:, :d].cpu().numpy().view(np.uint32), symbols=buf.symbols.cpu().numpy(), hist=buf.hist.cpu().numpy(),
+               words=buf.words.cpu().numpy(), chunk_offset=buf.chunk_offset.cpu().numpy(),
+               sub_bits=buf.sub_bits.cpu().numpy(), payload_bits=buf.payload_bits.cpu().numpy(),
+               status=buf.status.cpu().numpy())
+    out["codes"] = np.stack([np.concatenate(books.export(b)) for b in range(plan.num_books)])
+    return out
+
+
+@pytest.mark.parametrize("single_sweep", [False, True])
+def test_static_workspace_entry_point_equals_co3_encode(single_sweep):
+    # two calls in a row on the shared static workspace, the second smaller: whatever the first left there
+    # (partial histograms, chunk sizes, tickets, look-back entries) must not leak into the second
+    shapes = [(3, 4096 * 4 * 70 + 4096 + 77, 11), (2, 4096 + 905, 12)]
+    static = [one_call(U, d, seed, single_sweep, True) for U, d, seed in shapes]
+    plain = [one_call(U, d, seed, single_sweep, False) for U, d, seed in shapes]
+    for (U, d, _), a, b in zip(shapes, static, plain):
+        for k in KEYS + ("codes",):
+            assert a[k].shape == b[k].shape and np.array_equal(a[k], b[k]), (U, d, k)
+        assert int(a["status"][2:].sum()) == 0
+        assert int(a["payload_bits"].sum()) > 0
+
+
+def test_static_workspace_entry_point_refuses_what_does_not_fit():
+    import torch
+    from paper_2204_08211_amd import binding as B
+    # U x chunks x 4 bytes of per-chunk sizes alone exceed the static array: refused on the host, nothing is
+    # launched (the buffers handed over are far too small for this plan and are never touched)
+    U, d = 64, 4096 * 40000
+    plan = B.Plan(4, 3, U, d, [[14]] * U)
+    assert plan.workspace_bytes > B.STATIC_SCRATCH_BYTES
+    books = B.co3_build_codebook(4, 3, plan.num_books, None)
+    t = torch.zeros(64, dtype=torch.int64, device="cuda:0")
+    a = B.EncodeArgs(t.data_ptr(), t.data_ptr(), t.data_ptr(), (d + 3) // 4 * 4, 0.9, B.BOOK_EMPIRICAL, books.handle,
+                     t.data_ptr(), t.data_ptr(), t.data_ptr(), 16, t.data_ptr(), t.data_ptr(), t.data_ptr(),
+                     t.data_ptr(), None, 0, 0, 0, 0)
+    rc = B.lib().co3_encode_static(plan.handle, C.byref(a), C.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert rc == B.ERR_CAPACITY
+    torch.cuda.synchronize()
+    assert not t.cpu().numpy().any()
