@@ -227,8 +227,11 @@ int co3_encode(const co3_plan *plan, const co3_encode_args *args, void *stream);
  * partial histograms, per-chunk sizes, ticket counters and look-back entries live in a static
  * device array of CO3_STATIC_SCRATCH_BYTES that is part of the library (every GPU the library runs
  * on holds one copy until the process ends; its address on a device is resolved when a plan is
- * created there).  The call allocates nothing.  A plan with co3_plan_workspace_bytes() above
- * CO3_STATIC_SCRATCH_BYTES is refused with CO3_ERR_CAPACITY before anything is launched; between
+ * created there).  The call allocates nothing.  The static array has room for the encoders' smallest
+ * workspace only (about 4 bytes per user and chunk plus the partial histograms, not the per-chunk
+ * symbol counts co3_plan_workspace_bytes() also provides for, which spare the three-step encoder a
+ * sweep): a plan whose smallest workspace exceeds CO3_STATIC_SCRATCH_BYTES is refused with
+ * CO3_ERR_CAPACITY before anything is launched; between
  * co3_profile_begin() and co3_profile_end() (event timing creates events) it returns CO3_ERR_ARG.
  * All calls on one GPU share that array: what must start at zero is cleared by the call itself,
  * but two calls that overlap on one GPU (different streams, or threads) race -- serialise them.   */

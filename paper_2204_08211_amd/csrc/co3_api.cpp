@@ -61,6 +61,37 @@ int check_bias_table(const co3_format &f, const int32_t *bias, size_t n)
 
 }  // namespace
 
+namespace co3 {
+
+static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+size_t three_step_workspace_min(const Layout &l)
+{
+    return up256((size_t)kHistGlobalRep * l.nbooks * l.A * sizeof(uint64_t)) +
+           up256((size_t)l.U * l.nchunks * sizeof(uint32_t)) + 512;
+}
+
+size_t three_step_workspace_full(const Layout &l)
+{
+    size_t n = three_step_workspace_min(l);
+    if (l.nseg == 1) n += up256((size_t)l.U * l.nchunks * l.A * sizeof(uint16_t));
+    return n;
+}
+
+EncodeWs three_step_workspace(const Layout &l, void *workspace, size_t bytes)
+{
+    EncodeWs ws;
+    uintptr_t p = (reinterpret_cast<uintptr_t>(workspace) + 255u) & ~(uintptr_t)255u;
+    ws.hist_rep = reinterpret_cast<uint64_t *>(p);
+    p += up256((size_t)kHistGlobalRep * l.nbooks * l.A * sizeof(uint64_t));
+    ws.chunk_bits = reinterpret_cast<uint32_t *>(p);
+    p += up256((size_t)l.U * l.nchunks * sizeof(uint32_t));
+    ws.chunk_hist = (l.nseg == 1 && bytes >= three_step_workspace_full(l)) ? reinterpret_cast<uint16_t *>(p) : nullptr;
+    return ws;
+}
+
+}  // namespace co3
+
 extern "C" {
 
 const char *co3_status_string(int status)
@@ -174,8 +205,15 @@ size_t co3_plan_workspace_bytes(const co3_plan *plan)
 {
     if (!plan) return 0;
     const Layout &l = plan->lay;
-    const size_t hist_rep = ((size_t)kHistGlobalRep * l.nbooks * l.A * sizeof(uint64_t) + 255) & ~(size_t)255;
-    const size_t three_step = hist_rep + (size_t)l.U * l.nchunks * sizeof(uint32_t) + 512;
+    const size_t three_step = three_step_workspace_full(l);
+    const size_t single_sweep = fused_workspace_bytes(l);
+    return three_step > single_sweep ? three_step : single_sweep;
+}
+
+// What co3_encode_static needs of its static array: the encoders' smallest workspace.
+static size_t workspace_bytes_min(const Layout &l)
+{
+    const size_t three_step = three_step_workspace_min(l);
     const size_t single_sweep = fused_workspace_bytes(l);
     return three_step > single_sweep ? three_step : single_sweep;
 }
@@ -197,6 +235,8 @@ int co3_build_codebook(co3_format format, uint32_t nbooks, const uint64_t *weigh
     const uint32_t A = 1u << (1 + format.exp_bits + format.mant_bits);
     std::vector<BookDev> host(nbooks);
     std::memset(host.data(), 0, sizeof(BookDev) * nbooks);
+    for (auto &b : host)   // a table not built yet has no codes at all
+        for (uint32_t s = 0; s < (uint32_t)kMaxA; ++s) b.fast[s] = kFastSlow << 24;
     if (weights) {
         for (uint32_t b = 0; b < nbooks; ++b) {
             int rc = build_book_host(weights + (size_t)b * A, A, &host[b]);
@@ -283,7 +323,7 @@ static int encode_with_workspace(const co3_plan *plan, const co3_encode_args *a,
         return CO3_ERR_ARG;
     int rc = check_books(plan, a->books);
     if (rc != CO3_OK) return rc;
-    if (workspace_bytes < co3_plan_workspace_bytes(plan)) return CO3_ERR_CAPACITY;
+    if (workspace_bytes < workspace_bytes_min(lay)) return CO3_ERR_CAPACITY;
     if (!(a->gamma == a->gamma)) return CO3_ERR_ARG;
 
     co3_encode_args args = *a;
@@ -292,11 +332,8 @@ static int encode_with_workspace(const co3_plan *plan, const co3_encode_args *a,
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (single_sweep)
         return launch_encode_fused(lay, args, a->books->d_books, s) == hipSuccess ? CO3_OK : CO3_ERR_HIP;
-    EncodeWs ws;
+    const EncodeWs ws = three_step_workspace(lay, workspace, workspace_bytes);
     const uint64_t hist_rep_n = (uint64_t)kHistGlobalRep * lay.nbooks * lay.A;
-    ws.hist_rep = reinterpret_cast<uint64_t *>((reinterpret_cast<uintptr_t>(workspace) + 255u) & ~(uintptr_t)255u);
-    ws.chunk_bits = reinterpret_cast<uint32_t *>(
-        (reinterpret_cast<uintptr_t>(ws.hist_rep + hist_rep_n) + 255u) & ~(uintptr_t)255u);
 
     if (launch_zero_u64(ws.hist_rep, hist_rep_n, s) != hipSuccess) return CO3_ERR_HIP;
     if (launch_quantize(lay, args, ws, s) != hipSuccess) return CO3_ERR_HIP;
@@ -317,7 +354,7 @@ int co3_encode(const co3_plan *plan, const co3_encode_args *a, void *stream)
 int co3_encode_static(const co3_plan *plan, const co3_encode_args *a, void *stream)
 {
     if (!plan || !a) return CO3_ERR_ARG;
-    if (co3_plan_workspace_bytes(plan) > (size_t)CO3_STATIC_SCRATCH_BYTES) return CO3_ERR_CAPACITY;
+    if (workspace_bytes_min(plan->lay) > (size_t)CO3_STATIC_SCRATCH_BYTES) return CO3_ERR_CAPACITY;
     if (profile_enabled()) return CO3_ERR_ARG;   // event timing creates events: not for this entry point
     DeviceGuard guard(plan->device);
     void *ws = nullptr;

@@ -26,7 +26,7 @@ constexpr uint32_t kFastSlow = 0xFFu;  // length field marking "use the 64-bit t
 struct BookDev {
     uint64_t code[kMaxA];        // right-aligned codeword of each symbol
     uint64_t first[65];          // first[L]: first canonical code of length L (L = 1..64)
-    uint32_t fast[kMaxA];        // (len << 24) | code for len <= 24; len field 0xFF: long code; 0: no code
+    uint32_t fast[kMaxA];        // (len << 24) | code for len <= 24; len field 0xFF: a longer code, or none
     uint32_t count[65];          // count[L]: symbols with length L
     uint32_t offset[65];         // offset[L]: index of the first length-L symbol in sorted[]
     uint16_t dec[kDecEntries];   // prefix -> (len << 8) | symbol for len <= 11; else 1 + its second-level table, or 0
@@ -109,7 +109,13 @@ int build_book_host(const uint64_t *weights, uint32_t A, BookDev *out);
 struct EncodeWs {
     uint64_t *hist_rep;     // [kHistGlobalRep][nbooks][A] partial symbol counts
     uint32_t *chunk_bits;   // [U][nchunks] payload bits of every chunk
+    uint16_t *chunk_hist;   // [U][nchunks][A] symbol counts of every chunk, or nullptr (single-layer vectors only)
 };
+// bytes of the three-step encoder's workspace: what it cannot do without, and what it takes when it gets it (the
+// per-chunk symbol counts spare it a sweep over the symbols)
+size_t three_step_workspace_min(const Layout &lay);
+size_t three_step_workspace_full(const Layout &lay);
+EncodeWs three_step_workspace(const Layout &lay, void *workspace, size_t bytes);
 
 hipError_t launch_zero_u64(uint64_t *p, uint64_t n, hipStream_t s);
 hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, const EncodeWs &ws, hipStream_t s);

@@ -21,7 +21,7 @@ static void finish_tables(BookDev *b, uint32_t A)
     std::memset(b->first, 0, sizeof(b->first));
     std::memset(b->offset, 0, sizeof(b->offset));
     std::memset(b->code, 0, sizeof(b->code));
-    std::memset(b->fast, 0, sizeof(b->fast));
+    for (uint32_t s = 0; s < (uint32_t)kMaxA; ++s) b->fast[s] = kFastSlow << 24;  // no code: the coders' general path counts it
     std::memset(b->dec, 0, sizeof(b->dec));
     std::memset(b->dec2, 0, sizeof(b->dec2));
     std::memset(b->sorted, 0, sizeof(b->sorted));

@@ -137,14 +137,14 @@ __global__ __launch_bounds__(kCbThreads) void k_build_books(BookDev *__restrict_
     __syncthreads();
 
     uint64_t code = 0;
-    uint32_t fast = 0;
+    uint32_t fast = kFastSlow << 24;  // a longer code, or none: the coders' general path
     if (L) {
         uint32_t rank = 0;
 #pragma unroll 8
         for (int j = 0; j < (int)A; ++j) rank += (uint32_t)((j < t) & (slen[j] == L));
         code = first[L] + rank;
         sorted[off[L] + rank] = (uint32_t)t;
-        fast = (L <= (uint32_t)kFastLen) ? ((L << 24) | (uint32_t)code) : (kFastSlow << 24);
+        if (L <= (uint32_t)kFastLen) fast = (L << 24) | (uint32_t)code;
     }
     B.code[t] = code;
     B.fast[t] = fast;

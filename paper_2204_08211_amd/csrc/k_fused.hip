@@ -10,7 +10,9 @@
 //      in the rows of 16 + 1 words the pack step reads without bank conflicts.  A chunk that starts
 //      at an element off the 16-byte grid (layers begin anywhere) takes the same vectors from the
 //      boundary below it; only the ragged last chunk of a layer goes element by element;
-//   2. it sums the code lengths: lane j owns sub-chunk j (steps 1 and 2 need no workgroup barrier);
+//   2. lane j of the wavefront owns sub-chunk j: the wavefront-level coder of pack_core.h concatenates every
+//      lane's codewords in a private LDS row, which also yields the sub-chunk sizes (steps 1 and 2 need
+//      no workgroup barrier);
 //   3. the workgroup's 32-bit-rounded size is published and the sizes of all earlier workgroups of
 //      the user are collected by a decoupled look-back: every workgroup first publishes its own
 //      size, then reads its predecessors' until it meets one that already knows its running total.
@@ -20,13 +22,14 @@
 //      inherit instead of waiting, writes no stream words and is counted in the status block.
 //      An entry is one 64-bit word (flag and size together) and carries everything a successor
 //      needs, so it is written and read with relaxed device-scope atomics: ordering fences would
-//      make every workgroup write back and invalidate its L2;
-//   4. wavefront w appends the codewords of chunk w inside an LDS window at the bit offsets given
-//      by the wave prefix sum of the sub-chunk sizes (this needs no stream offset and runs while
-//      the look-back's answers travel) and copies the window out coalesced.
+//      make every workgroup write back and invalidate its L2.  While the look-back's answers travel,
+//      every wavefront moves its rows to their bit offsets within the chunk (this needs no stream
+//      offset: chunks are word-aligned);
+//   4. the chunk's words are copied out coalesced.
 #include <atomic>
 
 #include "co3_internal.h"
+#include "pack_core.h"
 #include "quantize_math.h"
 
 namespace co3 {
@@ -36,9 +39,8 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 constexpr int kFuCpb = 4;                            // chunks (= wavefronts) per workgroup ...
 constexpr int kFuCpbSmall = 1;                       // ... and for inputs too small to fill the device that way
 constexpr uint64_t kFuSmallGrid = 2048;              // workgroups of kFuCpb chunks below which the small form is used
-constexpr int kFuRow = 17;                           // 16 words of symbols + 1 pad
-constexpr int kFuStage = kSubsPerChunk * kFuRow;     // 1088 words hold a chunk's symbols
-constexpr int kFuWin = 1088;                         // LDS window of the output: 8.5 bit/element per pass
+constexpr int kFuRow = kPcSymRow;                    // 16 words of symbols + 1 pad
+constexpr int kFuStage = kPcSymWords;                // 1088 words hold a chunk's symbols
 constexpr int kFuBatch = 4;                          // 16-byte vectors of g (and of m) a lane requests at a time
 constexpr int kFuBatches = kChunk / 4 / 64 / kFuBatch; // batches per chunk
 constexpr int kFuScalar = 8;                         // element rounds a lane requests together on the element path
@@ -83,16 +85,16 @@ __device__ inline void fu_lds_barrier()
 // kSR: the stochastic conversion (dither from Philox words of (element, user, seed)) instead of
 // the closest representative.
 template <bool kSR, int kCpb>
-__global__ __launch_bounds__(64 * kCpb) void k_encode_fused(
+__global__ __launch_bounds__(64 * kCpb, 5) void k_encode_fused(
     Layout lay, const float *__restrict__ g, const float *m, float *m_out, uint64_t row_stride, float gamma,
     uint64_t seed, const BookDev *__restrict__ books, uint32_t *__restrict__ tickets, uint64_t *lb_state, uint32_t nblk,
     uint32_t spin_limit, uint64_t *__restrict__ chunk_offset, uint16_t *__restrict__ sub_bits,
     uint64_t *__restrict__ payload_bits, uint32_t *__restrict__ words, uint64_t words_stride,
     uint64_t *__restrict__ status)
 {
-    __shared__ uint32_t s_stage[kCpb][kFuStage + 1];
-    __shared__ uint32_t s_win[kCpb][kFuWin + 1];
+    __shared__ uint32_t s_stage[kCpb][kPcRegion];     // a wavefront's symbols, then its lanes' rows, then its chunk's words
     __shared__ uint32_t s_fast[kCpb][kMaxA];
+    __shared__ uint8_t s_len[kCpb][kMaxA];            // code lengths (0: no code), for the chunk's size
     __shared__ uint64_t s_e0[kCpb];
     __shared__ uint32_t s_n[kCpb], s_book[kCpb], s_cbits[kCpb];
     __shared__ int32_t s_bias[kCpb];
@@ -129,6 +131,7 @@ __global__ __launch_bounds__(64 * kCpb) void k_encode_fused(
     // ---- 1. wavefront w quantizes chunk w, symbols to LDS ---------------------------------------
     const bool active = wave < nck;
     const uint32_t sign_shift = lay.E + lay.M;
+    uint32_t len_sum = 0;   // code lengths of the elements this lane quantizes
     if (active) {
         const uint64_t e0 = s_e0[wave];
         const uint32_t nk = s_n[wave];
@@ -138,8 +141,21 @@ __global__ __launch_bounds__(64 * kCpb) void k_encode_fused(
         const float *mu = m + (uint64_t)u * row_stride + e0;
         float *mo = m_out + (uint64_t)u * row_stride + e0;
         uint32_t n_nonfinite = 0, n_clamped = 0;
-        // Four elements of a 16-byte vector: symbols packed into a word, new memory, counters for the
-        // elements `valid` marks (bit j: element j belongs to this chunk).
+        // The code's tables are requested first and stored to LDS once the first vectors of g and m are under
+        // way: the chunk's size is summed while it is quantized, so that it can be published right after.
+        uint32_t tab_fast[kMaxA / 64];
+#pragma unroll
+        for (int r = 0; r < kMaxA / 64; ++r) tab_fast[r] = books[s_book[wave]].fast[lane + 64 * r];
+        const uint32_t tab_len = reinterpret_cast<const uint32_t *>(books[s_book[wave]].len)[lane];
+        auto tables_to_lds = [&]() {
+#pragma unroll
+            for (int r = 0; r < kMaxA / 64; ++r) s_fast[wave][lane + 64 * r] = tab_fast[r];
+            reinterpret_cast<uint32_t *>(s_len[wave])[lane] = tab_len;
+            fu_wave_sync_lds();
+        };
+        const uint8_t *len_tab = s_len[wave];
+        // Four elements of a 16-byte vector: symbols packed into a word, new memory, counters and code
+        // lengths for the elements `valid` marks (bit j: element j belongs to this chunk).
         auto quant4 = [&](const f4 &gv, const f4 &mv, uint64_t elem, uint32_t valid, f4 &eo, uint32_t &packed) {
             packed = 0;
             Philox4 rw;
@@ -155,6 +171,7 @@ __global__ __launch_bounds__(64 * kCpb) void k_encode_fused(
                 const uint32_t ok = (valid >> j) & 1u;
                 n_nonfinite += flags & ok;
                 n_clamped += (flags >> 1) & ok;
+                len_sum += ok ? (uint32_t)len_tab[s] : 0u;
                 packed |= s << (8 * j);
             }
         };
@@ -169,6 +186,7 @@ __global__ __launch_bounds__(64 * kCpb) void k_encode_fused(
                 gn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(gu + i));
                 mn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(mu + i));
             }
+            tables_to_lds();
 #pragma unroll 1
             for (int bt = 0; bt < kFuBatches; ++bt) {
                 f4 gc[kFuBatch], mc[kFuBatch];
@@ -200,7 +218,7 @@ __global__ __launch_bounds__(64 * kCpb) void k_encode_fused(
             const float *ga = gu - shift, *ma = mu - shift;
             float *moa = mo - shift;
             for (uint32_t i = lane; i < (uint32_t)(kFuStage + 1); i += 64) s_stage[wave][i] = 0;
-            fu_wave_sync_lds();
+            tables_to_lds();
             f4 gn[kFuBatch], mn[kFuBatch];
 #pragma unroll
             for (int r = 0; r < kFuBatch; ++r) {
@@ -252,6 +270,7 @@ __global__ __launch_bounds__(64 * kCpb) void k_encode_fused(
         } else {
             // ragged chunk (the end of a layer): a lane takes one element of every 64, kFuScalar rounds requested together; four neighbouring lanes then gather
             // their symbols into one word of the stage
+            tables_to_lds();
             for (uint32_t base = 0; base < nk; base += 64u * kFuScalar) {
                 float gs[kFuScalar], ms[kFuScalar];
 #pragma unroll
@@ -275,6 +294,7 @@ __global__ __launch_bounds__(64 * kCpb) void k_encode_fused(
                         mo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
                         n_nonfinite += flags & 1u;
                         n_clamped += (flags >> 1) & 1u;
+                        len_sum += (uint32_t)len_tab[s];
                     }
                     s = in ? s : 0u;
                     const uint32_t s4 = s | (__shfl_down(s, 1, 64) << 8) | (__shfl_down(s, 2, 64) << 16) |
@@ -284,56 +304,19 @@ __global__ __launch_bounds__(64 * kCpb) void k_encode_fused(
                 }
             }
         }
-        // the code-table entries of this wavefront's chunk
-        for (uint32_t i = lane; i < (uint32_t)kMaxA; i += 64) s_fast[wave][i] = books[s_book[wave]].fast[i];
         if (n_nonfinite)
             atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NONFINITE),
                       (unsigned long long)n_nonfinite);
         if (n_clamped)
             atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CLAMPED), (unsigned long long)n_clamped);
     }
-    fu_wave_sync_lds();  // stage and table of a wavefront are its own: no workgroup barrier
-
-    // ---- 2. code lengths: wavefront = chunk, lane = sub-chunk ----------------------------------
-    const uint64_t c = c0 + wave;
-    const uint32_t n = active ? s_n[wave] : 0u;
-    const int first = (int)lane * kSub;
-    const int cnt = (int)n - first < 0 ? 0 : ((int)n - first > kSub ? kSub : (int)n - first);
-    const uint32_t *row = s_stage[wave] + kFuRow * lane;
-    const uint32_t *fast = s_fast[wave];
-    const BookDev &book = books[s_book[wave]];
-    uint32_t my_bits = 0;
-    if (active) {
-        uint32_t nocode = 0;
-#pragma unroll 4
-        for (int jj = 0; jj < kSub / 4; ++jj) {
-            const uint32_t w4 = row[jj];
+    // the chunk's size: every lane summed the code lengths of the elements it quantized
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t s = (w4 >> (8 * q)) & 0xffu;
-                const bool in = 4 * jj + q < cnt;
-                uint32_t L = in ? (fast[s] >> 24) : 0u;
-                if (__builtin_expect(L == kFastSlow, 0)) L = book.len[s];
-                nocode += (in && L == 0u) ? 1u : 0u;
-                my_bits += L;
-            }
-        }
-        sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane] = (uint16_t)my_bits;
-        if (nocode)
-            atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NOCODE), (unsigned long long)nocode);
-    }
-    uint32_t incl = my_bits;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t y = __shfl_up(incl, o, 64);
-        if ((int)lane >= o) incl += y;
-    }
-    const uint32_t excl = incl - my_bits;
-    const uint32_t chunk_total = __shfl(incl, 63, 64);
-    if (lane == 0) s_cbits[wave] = chunk_total;  // 0 for a wavefront without a chunk
-    fu_lds_barrier();
+    for (int o = 32; o > 0; o >>= 1) len_sum += __shfl_xor(len_sum, o, 64);
+    if (lane == 0) s_cbits[wave] = len_sum;  // 0 for a wavefront without a chunk
+    fu_lds_barrier();                        // also: every wavefront's symbols are staged
 
-    // ---- 3. publish the workgroup's size; pack while the predecessors publish theirs ----------
+    // ---- 2. publish the workgroup's size; request the predecessors' ------------------------------
     uint32_t before = 0;  // 32-bit-rounded sizes of the workgroup's chunks ahead of this wavefront's
     uint32_t own = 0, pay = 0;
 #pragma unroll
@@ -347,53 +330,43 @@ __global__ __launch_bounds__(64 * kCpb) void k_encode_fused(
     if (t == 0)
         __hip_atomic_store(&state[b], (b == 0 ? kLbPrefix : kLbAgg) | own, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
+    // the nearest 64 predecessor entries, requested now and looked at after the coding below
+    uint64_t lb_first = kLbPrefix;  // before the first workgroup: running total 0
+    if (wave == 0 && (int64_t)b - 1 - (int64_t)lane >= 0)
+        lb_first = __hip_atomic_load(&state[b - 1 - lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
-    // Words [wbase, wbase + wn) of the chunk's codewords, built in the wavefront's LDS window.  A
-    // chunk starts on a word boundary, so the window's content does not depend on where the chunk
-    // lands in the stream.
-    const uint32_t nwords = (chunk_total + 31u) >> 5;
-    uint32_t *win = s_win[wave];
-    auto pack_window = [&](uint32_t wbase, uint32_t wn) {
-        for (uint32_t i = lane; i <= wn; i += 64) win[i] = 0;
-        fu_wave_sync_lds();
-        uint32_t wi = (excl >> 5) - wbase;  // window word receiving the next completed 32 bits
-        uint32_t np = excl & 31u;           // bits pending in acc (the leading np bits belong to earlier lanes)
-        uint64_t acc = 0;
-        auto append = [&](uint64_t code, uint32_t L) {  // L <= 32, np < 32
-            acc = (acc << L) | code;
-            np += L;
-            if (np >= 32u) {
-                np -= 32u;
-                if (wi < wn) atomicOr(&win[wi], (uint32_t)(acc >> np));  // unsigned: false below the window
-                ++wi;
-            }
-        };
-#pragma unroll 2
-        for (int jj = 0; jj < kSub / 4; ++jj) {
-            const uint32_t w4 = row[jj];
+    // ---- 3. wavefront = chunk, lane = sub-chunk: the chunk's words, built in LDS ---------------------
+    // A chunk starts on a word boundary, so its words do not depend on where it lands in the stream.
+    const uint64_t c = c0 + wave;
+    const uint32_t n = active ? s_n[wave] : 0u;
+    const int first = (int)lane * kSub;
+    const int cnt = (int)n - first < 0 ? 0 : ((int)n - first > kSub ? kSub : (int)n - first);
+    uint32_t *region = s_stage[wave];
+    const uint32_t *fast = s_fast[wave];
+    const BookDev &book = books[s_book[wave]];
+    uint32_t symw[kSub / 4];
+    uint32_t my_bits = 0;
+    bool fast_ok = true;
+    if (active) {
+        const uint32_t *row = region + kFuRow * lane;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t s = (w4 >> (8 * q)) & 0xffu;
-                const uint32_t e = (4 * jj + q < cnt) ? fast[s] : 0u;
-                uint32_t L = e >> 24;
-                uint64_t code = e & 0x00ffffffu;
-                if (__builtin_expect(L == kFastSlow, 0)) {
-                    L = book.len[s];
-                    code = book.code[s];
-                    if (L > 32u) {
-                        append(code >> 32, L - 32u);
-                        code &= 0xffffffffull;
-                        L = 32u;
-                    }
-                }
-                if (L) append(code, L);
-            }
+        for (int jj = 0; jj < kSub / 4; ++jj) symw[jj] = row[jj];
+        fu_wave_sync_lds();  // every lane has its symbols: the region is free
+        fast_ok = n == (uint32_t)kChunk ? pc_pack_rows<true>(symw, cnt, fast, region, lane, my_bits)
+                                        : pc_pack_rows<false>(symw, cnt, fast, region, lane, my_bits);
+        if (!fast_ok) {
+            uint32_t nocode = 0;
+            my_bits = pc_general_count(symw, cnt, fast, book, region, lane, nocode);
+            if (nocode)
+                atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NOCODE), (unsigned long long)nocode);
         }
-        if (np && wi < wn) atomicOr(&win[wi], (uint32_t)(acc << (32u - np)));
-        fu_wave_sync_lds();
-    };
-    const bool one_window = nwords <= (uint32_t)kFuWin;  // up to 8.5 bit/element
-    if (active && one_window) pack_window(0, nwords);
+        sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane] = (uint16_t)my_bits;
+    }
+    const uint32_t incl = pc_wave_inclusive_scan(my_bits, lane);
+    const uint32_t excl = incl - my_bits;
+    const uint32_t chunk_total = __shfl(incl, 63, 64);   // equals s_cbits[wave]: the same lengths, summed in another order
+    const uint32_t nwords = (chunk_total + 31u) >> 5;
+    if (active && fast_ok) pc_rows_to_window(region, lane, my_bits, excl, nwords);
 
     if (wave == 0) {
         uint64_t prefix = 0;
@@ -404,7 +377,8 @@ __global__ __launch_bounds__(64 * kCpb) void k_encode_fused(
             uint64_t v = kLbPrefix;  // before the first workgroup: running total 0
             if (idx >= 0) {
                 uint32_t spins = 0;
-                v = __hip_atomic_load(&state[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v = pos == (int64_t)b - 1 ? lb_first
+                                          : __hip_atomic_load(&state[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 while ((v >> 62) == 0 && spins < spin_limit) {
                     __builtin_amdgcn_s_sleep(1);
                     v = __hip_atomic_load(&state[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -452,12 +426,14 @@ __global__ __launch_bounds__(64 * kCpb) void k_encode_fused(
         return;
     }
     uint32_t *dst = words + (uint64_t)u * words_stride + off_words;
-    if (one_window) {
-        for (uint32_t i = lane; i < nwords; i += 64) __builtin_nontemporal_store(win[i], dst + i);
+    if (fast_ok) {
+        for (uint32_t i = lane; i < nwords; i += 64) __builtin_nontemporal_store(region[i], dst + i);
     } else {
-        for (uint32_t wbase = 0; wbase < nwords; wbase += kFuWin) {
-            const uint32_t wn = nwords - wbase < (uint32_t)kFuWin ? nwords - wbase : (uint32_t)kFuWin;
-            pack_window(wbase, wn);
+        // the general coder: the symbols are back in LDS, the words pass through a small window
+        const uint32_t *win = region + kPcSymWords;
+        for (uint32_t wbase = 0; wbase < nwords; wbase += kPcWin) {
+            const uint32_t wn = nwords - wbase < (uint32_t)kPcWin ? nwords - wbase : (uint32_t)kPcWin;
+            pc_general_window(cnt, fast, book, region, lane, excl, wbase, wn);
             for (uint32_t i = lane; i < wn; i += 64) __builtin_nontemporal_store(win[i], dst + wbase + i);
             fu_wave_sync_lds();
         }

@@ -6,27 +6,23 @@
 // restarting at each layer) starts on a 32-bit boundary, so wavefronts own disjoint words of the
 // output and no global atomics touch the stream.
 //
-// A wavefront owns a chunk and lane j owns sub-chunk j (64 elements), exactly as in the decoder;
-// nothing in these kernels needs a workgroup barrier.  Three steps:
-//   k_pack_wave<false>  code lengths -> bits per sub-chunk (the lane's sum) and per chunk
-//   k_scan_chunks       exclusive scan of the 32-bit-rounded chunk sizes (64-bit offsets)
-//   k_pack_wave<true>   every lane appends its 64 codewords at its bit offset inside an LDS
-//                       window (the offset is the wave prefix sum of the sub-chunk bits), then the
-//                       wavefront copies the window's words out coalesced
-// The symbols of a chunk are staged in LDS in rows of 16 + 1 words so that every lane reads its
-// own row without bank conflicts; once they sit in registers the same LDS words become the
-// output window.
+// Coder for symbols stored by the quantize sweep.  Three steps:
+//   k_chunk_bits   sum of the code lengths of every chunk: a wavefront per chunk, coalesced loads, a
+//                  byte table of lengths in LDS (k_chunk_bits_hist: the same sums from the per-chunk symbol
+//                  counts the quantize sweep writes for single-layer vectors, without touching the symbols)
+//   k_scan_chunks  exclusive scan of the 32-bit-rounded chunk sizes (64-bit offsets), payload r
+//   k_pack_chunk   a wavefront per chunk, lane j owns sub-chunk j (64 elements), exactly as in the
+//                  decoder: the wavefront-level coder of pack_core.h builds the chunk's words in LDS,
+//                  which are then copied out coalesced; the lanes' bit counts are the sub-chunk index
+// Nothing in these kernels needs a workgroup barrier.
 #include "co3_internal.h"
+#include "pack_core.h"
 
 namespace co3 {
 
 constexpr int kPkWaves = 4;                         // wavefronts (chunks) per workgroup
 constexpr int kPkThreads = 64 * kPkWaves;
-constexpr int kRowWords = 17;                       // 16 words of symbols + 1 pad
-constexpr int kStageWords = kSubsPerChunk * kRowWords;  // 1088 words hold a chunk's symbols
-constexpr int kWinWords = 1088;                     // LDS window of the output: 8.5 bit/element per pass
-constexpr int kSymLoads = (kChunk / 4 + 1 + 63) / 64;  // dword loads per lane to stage a chunk (17)
-constexpr uint32_t kPlainFlag = 1u << 31;              // in chunk_bits: full chunk, every code at most kFastLen bits
+constexpr int kSymLoads = (kChunk / 4 + 1 + 63) / 64;  // dword loads per lane to cover a chunk at any byte offset (17)
 
 __device__ inline uint32_t find_chunk_segment(const SegDev *segs, uint32_t nseg, uint64_t chunk)
 {
@@ -40,13 +36,7 @@ __device__ inline uint32_t find_chunk_segment(const SegDev *segs, uint32_t nseg,
 
 __device__ inline uint32_t wave_inclusive_scan(uint32_t x)
 {
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t y = __shfl_up(x, o, 64);
-        if (lane >= o) x += y;
-    }
-    return x;
+    return pc_wave_inclusive_scan(x, threadIdx.x & 63);
 }
 
 __device__ inline uint32_t wave_sum(uint32_t x)
@@ -56,204 +46,183 @@ __device__ inline uint32_t wave_sum(uint32_t x)
     return x;
 }
 
-__device__ inline void wave_sync_lds()
+// Where chunk c of user u lies: first symbol byte (within the symbol buffer), element count, code table.
+struct PkChunk {
+    uint64_t byte0;
+    uint32_t n;
+    uint32_t book;
+};
+
+__device__ inline PkChunk pk_chunk(const Layout &lay, uint64_t c, uint32_t u, uint64_t sym_stride)
 {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint32_t seg = find_chunk_segment(lay.segs, lay.nseg, c);
+    const SegDev sd = lay.segs[seg];
+    const uint64_t e0 = sd.offset + (c - sd.chunk_start) * kChunk;
+    const uint64_t left = sd.offset + sd.length - e0;
+    PkChunk k;
+    k.byte0 = (uint64_t)u * sym_stride + e0;
+    k.n = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
+    k.book = (lay.per_user_books ? u * lay.books_per_user : 0u) + (uint32_t)sd.book;
+    return k;
 }
 
-template <bool kPack>
-__global__ __launch_bounds__(kPkThreads) void k_pack_wave(
-    Layout lay, const uint8_t *__restrict__ sym, uint64_t sym_stride, const BookDev *__restrict__ books,
-    uint32_t *__restrict__ chunk_bits, const uint64_t *__restrict__ chunk_offset,
-    uint16_t *__restrict__ sub_bits, uint32_t *__restrict__ words, uint64_t words_stride,
-    uint64_t *__restrict__ status)
+// chunk_bits[u][c] = sum of the code lengths of the chunk's symbols (symbols without a code add nothing;
+// they are counted where they are coded).  Lane l takes dwords l, l + 64, ... of the chunk's bytes.
+__global__ __launch_bounds__(kPkThreads) void k_chunk_bits(Layout lay, const uint8_t *__restrict__ sym, uint64_t sym_stride,
+                                                          const BookDev *__restrict__ books,
+                                                          uint32_t *__restrict__ chunk_bits)
 {
-    __shared__ uint32_t s_stage_all[kPkWaves][kStageWords + 1];
-    __shared__ uint32_t s_win_all[kPkWaves][kPack ? kWinWords + 1 : 1];
+    __shared__ uint8_t s_len_all[kPkWaves][kMaxA];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t c = (uint64_t)blockIdx.x * kPkWaves + wave;
+    const uint32_t u = blockIdx.y;
+    if (c >= lay.nchunks) return;  // whole wavefront; no workgroup barriers below
+    const PkChunk k = pk_chunk(lay, c, u, sym_stride);
+    uint8_t *s_len = s_len_all[wave];
+    const uint32_t len4 = reinterpret_cast<const uint32_t *>(books[k.book].len)[lane];
+    const uint32_t shift = (uint32_t)(k.byte0 & 3u);
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(sym + (k.byte0 - shift));
+    const uint32_t ndw = (shift + k.n + 3u) >> 2;
+    uint32_t w[kSymLoads];
+#pragma unroll
+    for (int r = 0; r < kSymLoads; ++r) {
+        const uint32_t i = lane + 64u * r;
+        w[r] = i < ndw ? __builtin_nontemporal_load(src + i) : 0u;
+    }
+    reinterpret_cast<uint32_t *>(s_len)[lane] = len4;
+    pc_wave_sync_lds();
+    uint32_t total = 0;
+    if (shift == 0 && k.n == (uint32_t)kChunk) {
+#pragma unroll
+        for (int r = 0; r < kChunk / 4 / 64; ++r)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) total += s_len[(w[r] >> (8 * b)) & 0xffu];
+    } else {
+#pragma unroll
+        for (int r = 0; r < kSymLoads; ++r) {
+            const uint32_t i = lane + 64u * r;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t pos = 4u * i + b;                       // byte within the loaded dwords
+                const bool in = pos >= shift && pos < shift + k.n;
+                total += in ? s_len[(w[r] >> (8 * b)) & 0xffu] : 0u;
+            }
+        }
+    }
+    total = wave_sum(total);
+    if (lane == 0) chunk_bits[(uint64_t)u * lay.nchunks + c] = total;
+}
+
+// The same sizes from the symbol counts of every chunk that the quantize sweep left behind (single-layer
+// vectors): chunk_bits[u][c] = sum over symbols of count x code length.  A wavefront per chunk, four bins per lane.
+__global__ __launch_bounds__(kPkThreads) void k_chunk_bits_hist(Layout lay, const uint16_t *__restrict__ chunk_hist,
+                                                               const BookDev *__restrict__ books,
+                                                               uint32_t *__restrict__ chunk_bits)
+{
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t c = (uint64_t)blockIdx.x * kPkWaves + wave;
+    const uint32_t u = blockIdx.y;
+    if (c >= lay.nchunks) return;
+    const BookDev &book = books[(lay.per_user_books ? u * lay.books_per_user : 0u) + (uint32_t)lay.segs[0].book];
+    const uint16_t *h = chunk_hist + ((uint64_t)u * lay.nchunks + c) * lay.A;
+    uint32_t total = 0;
+    for (uint32_t b0 = 4u * lane; b0 < lay.A; b0 += 256u) {   // A is a power of two, at least 8
+        const uint2 cnt = *reinterpret_cast<const uint2 *>(h + b0);
+        const uint32_t len4 = *reinterpret_cast<const uint32_t *>(book.len + b0);
+        total += (cnt.x & 0xffffu) * (len4 & 0xffu) + (cnt.x >> 16) * ((len4 >> 8) & 0xffu) +
+                 (cnt.y & 0xffffu) * ((len4 >> 16) & 0xffu) + (cnt.y >> 16) * (len4 >> 24);
+    }
+    total = wave_sum(total);
+    if (lane == 0) chunk_bits[(uint64_t)u * lay.nchunks + c] = total;
+}
+
+// The coder proper.  chunk_offset comes from k_scan_chunks.
+__global__ __launch_bounds__(kPkThreads) void k_pack_chunk(
+    Layout lay, const uint8_t *__restrict__ sym, uint64_t sym_stride, const BookDev *__restrict__ books,
+    const uint64_t *__restrict__ chunk_offset, uint16_t *__restrict__ sub_bits, uint32_t *__restrict__ words,
+    uint64_t words_stride, uint64_t *__restrict__ status)
+{
+    __shared__ uint32_t s_region_all[kPkWaves][kPcRegion];
     __shared__ uint32_t s_fast_all[kPkWaves][kMaxA];
 
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint64_t c = (uint64_t)blockIdx.x * kPkWaves + wave;
     const uint32_t u = blockIdx.y;
     if (c >= lay.nchunks) return;  // whole wavefront; no workgroup barriers below
-    uint32_t *s_stage = s_stage_all[wave];
-    uint32_t *s_win = s_win_all[wave];
+    uint32_t *region = s_region_all[wave];
     uint32_t *s_fast = s_fast_all[wave];
+    const PkChunk k = pk_chunk(lay, c, u, sym_stride);
+    const BookDev &book = books[k.book];
 
-    const uint32_t seg = find_chunk_segment(lay.segs, lay.nseg, c);
-    const SegDev sd = lay.segs[seg];
-    const uint64_t e0 = sd.offset + (c - sd.chunk_start) * kChunk;
-    const uint64_t left = sd.offset + sd.length - e0;
-    const uint32_t n = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
-    const BookDev &book = books[(lay.per_user_books ? u * lay.books_per_user : 0u) + (uint32_t)sd.book];
-
-    // what the wavefront needs from memory, requested together: table, symbols, (pack) sub-chunk bits
+    // what the wavefront needs from memory, requested together: table, symbols, stream offset
     uint32_t tab[kMaxA / 64];
 #pragma unroll
-    for (int k = 0; k < kMaxA / 64; ++k) tab[k] = book.fast[lane + 64 * k];
-    const uint64_t byte0 = (uint64_t)u * sym_stride + e0;
-    const uint32_t shift = (uint32_t)(byte0 & 3u);
-    const uint32_t *src = reinterpret_cast<const uint32_t *>(sym + (byte0 - shift));
-    const uint32_t ndw = (shift + n + 3u) >> 2;
-    uint32_t tmp[kSymLoads];
+    for (int r = 0; r < kMaxA / 64; ++r) tab[r] = book.fast[lane + 64 * r];
+    const uint64_t off = chunk_offset[(uint64_t)u * (lay.nchunks + 1) + c];
+    uint32_t symw[kSub / 4];   // the lane's 64 symbols, four per word
+    {
+        // any byte offset, any length: coalesced dwords from the 4-byte boundary below the chunk, staged in LDS
+        // rows of 16 + 1 words, from which every lane funnels its 64 bytes
+        const uint32_t shift = (uint32_t)(k.byte0 & 3u);
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(sym + (k.byte0 - shift));
+        const uint32_t ndw = (shift + k.n + 3u) >> 2;
+        uint32_t tmp[kSymLoads];
 #pragma unroll
-    for (int k = 0; k < kSymLoads; ++k) {
-        const uint32_t i = lane + 64u * k;
-        tmp[k] = i < ndw ? src[i] : 0u;
-    }
-    uint32_t my_bits = 0;
-    uint64_t off = 0;
-    bool all_plain = false;
-    if (kPack) {
-        my_bits = sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane];
-        off = chunk_offset[(uint64_t)u * (lay.nchunks + 1) + c];
-        all_plain = (chunk_bits[(uint64_t)u * lay.nchunks + c] & kPlainFlag) != 0u;
-    }
+        for (int r = 0; r < kSymLoads; ++r) {
+            const uint32_t i = lane + 64u * r;
+            tmp[r] = i < ndw ? __builtin_nontemporal_load(src + i) : 0u;
+        }
 #pragma unroll
-    for (int k = 0; k < kMaxA / 64; ++k) s_fast[lane + 64 * k] = tab[k];
+        for (int r = 0; r < kMaxA / 64; ++r) s_fast[lane + 64 * r] = tab[r];
 #pragma unroll
-    for (int k = 0; k < kSymLoads; ++k) {
-        const uint32_t i = lane + 64u * k;
-        if (i < kChunk / 4 + 1) s_stage[i + (i >> 4)] = tmp[k];  // rows of 16 words, 17 apart
+        for (int r = 0; r < kSymLoads; ++r) {
+            const uint32_t i = lane + 64u * r;
+            if (i < kChunk / 4 + 1) region[i + (i >> 4)] = tmp[r];  // word 1024 lands at 1088
+        }
+        pc_wave_sync_lds();
+        const uint32_t *row = region + kPcSymRow * lane;   // dwords 16 lane .. 16 lane + 15; dword 16 lane + 16 is row[17]
+        uint32_t cur = row[0];
+#pragma unroll
+        for (int jj = 0; jj < kSub / 4; ++jj) {
+            const uint32_t nxt = row[jj + 1 + (jj == kSub / 4 - 1 ? 1 : 0)];
+            symw[jj] = __builtin_amdgcn_alignbit(nxt, cur, 8u * shift);
+            cur = nxt;
+        }
+        pc_wave_sync_lds();                                // the region is free again
     }
     const int first = (int)lane * kSub;
-    const int cnt = (int)n - first < 0 ? 0 : ((int)n - first > kSub ? kSub : (int)n - first);
-    const uint32_t *row = s_stage + kRowWords * lane;   // words 16*lane .. of the staged bytes; word 16 is row[17]
+    const int cnt = (int)k.n - first < 0 ? 0 : ((int)k.n - first > kSub ? kSub : (int)k.n - first);
 
-    if (!kPack) {
-        wave_sync_lds();
-        uint32_t total = 0;
-        // A full chunk whose symbols all have codes of at most kFastLen bits needs no per-symbol
-        // checks; bit 31 of chunk_bits tells the pack step so.
-        bool plain = false;
-        if (n == (uint32_t)kChunk) {
-            uint32_t lo = 0xffu, hi = 0u;
-            uint32_t cur = row[0];
-#pragma unroll 4
-            for (int jj = 0; jj < kSub / 4; ++jj) {
-                const uint32_t nxt = row[jj + 1 + (jj == kSub / 4 - 1 ? 1 : 0)];
-                const uint32_t w4 = (uint32_t)((((uint64_t)nxt << 32) | cur) >> (8 * shift));
-                cur = nxt;
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const uint32_t L = s_fast[(w4 >> (8 * b)) & 0xffu] >> 24;
-                    total += L;
-                    lo = lo < L ? lo : L;
-                    hi = hi > L ? hi : L;
-                }
-            }
-            plain = lo > 0u && hi < kFastSlow;
-        }
-        if (!plain) {
-            uint32_t nocode = 0;
-            total = 0;
-            uint32_t cur = row[0];
-#pragma unroll 4
-            for (int jj = 0; jj < kSub / 4; ++jj) {
-                const uint32_t nxt = row[jj + 1 + (jj == kSub / 4 - 1 ? 1 : 0)];
-                const uint32_t w4 = (uint32_t)((((uint64_t)nxt << 32) | cur) >> (8 * shift));
-                cur = nxt;
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const uint32_t s = (w4 >> (8 * b)) & 0xffu;
-                    const bool in = 4 * jj + b < cnt;
-                    uint32_t L = in ? (s_fast[s] >> 24) : 0u;
-                    if (__builtin_expect(L == kFastSlow, 0)) L = book.len[s];
-                    nocode += (in && L == 0u) ? 1u : 0u;
-                    total += L;
-                }
-            }
-            if (nocode)
-                atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NOCODE), (unsigned long long)nocode);
-        }
-        sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane] = (uint16_t)total;
-        const uint32_t chunk_total = wave_sum(total);
-        const bool all_plain = !__any(!plain);
-        if (lane == 0) chunk_bits[(uint64_t)u * lay.nchunks + c] = chunk_total | (all_plain ? kPlainFlag : 0u);
+    uint32_t bits = 0;
+    const bool fast_ok = k.n == (uint32_t)kChunk ? pc_pack_rows<true>(symw, cnt, s_fast, region, lane, bits)
+                                                 : pc_pack_rows<false>(symw, cnt, s_fast, region, lane, bits);
+    if (!fast_ok) {
+        uint32_t nocode = 0;
+        bits = pc_general_count(symw, cnt, s_fast, book, region, lane, nocode);
+        if (nocode)
+            atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NOCODE), (unsigned long long)nocode);
+    }
+    sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane] = (uint16_t)bits;
+    const uint32_t incl = wave_inclusive_scan(bits);
+    const uint32_t excl = incl - bits;
+    const uint32_t chunk_total = __shfl(incl, 63, 64);
+    const uint32_t nwords = (chunk_total + 31u) >> 5;
+    const uint64_t off_words = off >> 5;
+    if (off_words + nwords > words_stride) {
+        if (lane == 0) atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CAPACITY), 1ull);
         return;
+    }
+    uint32_t *dst = words + (uint64_t)u * words_stride + off_words;
+    if (fast_ok) {
+        pc_rows_to_window(region, lane, bits, excl, nwords);
+        for (uint32_t i = lane; i < nwords; i += 64) __builtin_nontemporal_store(region[i], dst + i);
     } else {
-        const uint32_t incl = wave_inclusive_scan(my_bits);
-        const uint32_t excl = incl - my_bits;
-        const uint32_t chunk_total = __shfl(incl, 63, 64);
-        const uint32_t nwords = (chunk_total + 31u) >> 5;
-        const uint64_t off_words = off >> 5;
-        if (off_words + nwords > words_stride) {
-            if (lane == 0) atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CAPACITY), 1ull);
-            return;
-        }
-        uint32_t *dst = words + (uint64_t)u * words_stride + off_words;
-
-        // the chunk's words pass through the LDS window, kWinWords at a time (one pass up to
-        // 8.5 bit/element); every lane ORs its words in, so neighbours may share a word
-        for (uint32_t wbase = 0; wbase < nwords; wbase += kWinWords) {
-            const uint32_t wn = nwords - wbase < (uint32_t)kWinWords ? nwords - wbase : (uint32_t)kWinWords;
-            for (uint32_t i = lane; i <= wn; i += 64) s_win[i] = 0;
-            wave_sync_lds();
-            uint32_t wi = (excl >> 5) - wbase;  // window word receiving the next completed 32 bits
-            uint32_t np = excl & 31u;           // bits pending in acc (the leading np bits belong to earlier lanes)
-            uint64_t acc = 0;
-            auto append = [&](uint64_t code, uint32_t L) {  // L <= 32, np < 32
-                acc = (acc << L) | code;
-                np += L;
-                if (np >= 32u) {
-                    np -= 32u;
-                    if (wi < wn) atomicOr(&s_win[wi], (uint32_t)(acc >> np));  // unsigned: false below the window
-                    ++wi;
-                }
-            };
-            uint32_t cur = row[0];
-            if (all_plain) {
-                // the table entries of the next four symbols are requested before the current four
-                // are appended: the appends' LDS atomics keep later look-ups behind them
-                uint32_t en[4];
-                auto lookup4 = [&](int jj) {
-                    const uint32_t nxt = row[jj + 1 + (jj == kSub / 4 - 1 ? 1 : 0)];
-                    const uint32_t w4 = (uint32_t)((((uint64_t)nxt << 32) | cur) >> (8 * shift));
-                    cur = nxt;
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) en[b] = s_fast[(w4 >> (8 * b)) & 0xffu];
-                };
-                lookup4(0);
-#pragma unroll 2
-                for (int jj = 0; jj < kSub / 4; ++jj) {
-                    uint32_t e[4];
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) e[b] = en[b];
-                    if (jj + 1 < kSub / 4) lookup4(jj + 1);
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) append(e[b] & 0x00ffffffu, e[b] >> 24);
-                }
-            } else {
-#pragma unroll 2
-                for (int jj = 0; jj < kSub / 4; ++jj) {
-                    const uint32_t nxt = row[jj + 1 + (jj == kSub / 4 - 1 ? 1 : 0)];
-                    const uint32_t w4 = (uint32_t)((((uint64_t)nxt << 32) | cur) >> (8 * shift));
-                    cur = nxt;
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const uint32_t s = (w4 >> (8 * b)) & 0xffu;
-                        const uint32_t e = (4 * jj + b < cnt) ? s_fast[s] : 0u;
-                        uint32_t L = e >> 24;
-                        uint64_t code = e & 0x00ffffffu;
-                        if (__builtin_expect(L == kFastSlow, 0)) {
-                            L = book.len[s];
-                            code = book.code[s];
-                            if (L > 32u) {
-                                append(code >> 32, L - 32u);
-                                code &= 0xffffffffull;
-                                L = 32u;
-                            }
-                        }
-                        if (L) append(code, L);
-                    }
-                }
-            }
-            if (np && wi < wn) atomicOr(&s_win[wi], (uint32_t)(acc << (32u - np)));
-            wave_sync_lds();
-            for (uint32_t i = lane; i < wn; i += 64) __builtin_nontemporal_store(s_win[i], dst + wbase + i);
-            wave_sync_lds();
+        const uint32_t *win = region + kPcSymWords;
+        for (uint32_t wbase = 0; wbase < nwords; wbase += kPcWin) {
+            const uint32_t wn = nwords - wbase < (uint32_t)kPcWin ? nwords - wbase : (uint32_t)kPcWin;
+            pc_general_window(cnt, s_fast, book, region, lane, excl, wbase, wn);
+            for (uint32_t i = lane; i < wn; i += 64) __builtin_nontemporal_store(win[i], dst + wbase + i);
+            pc_wave_sync_lds();
         }
     }
 }
@@ -272,7 +241,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_chunks(uint64_t nchunks, 
     uint64_t running = 0, payload = 0;
     for (uint64_t base = 0; base < nchunks; base += kScanThreads) {
         const uint64_t i = base + t;
-        const uint32_t b = (i < nchunks) ? (cb[i] & ~kPlainFlag) : 0u;
+        const uint32_t b = (i < nchunks) ? cb[i] : 0u;
         const uint32_t a = (b + 31u) & ~31u;
         const uint32_t incl_w = wave_inclusive_scan(a);
         const uint32_t pay = wave_sum(b);
@@ -300,8 +269,12 @@ hipError_t launch_pack(const Layout &lay, const co3_encode_args &a, const BookDe
     const uint32_t gx = (uint32_t)((lay.nchunks + kPkWaves - 1) / kPkWaves);
     if (lay.nchunks) {
         ProfScope prof(K_CHUNK_BITS, s);
-        hipLaunchKernelGGL(k_pack_wave<false>, dim3(gx, lay.U), dim3(kPkThreads), 0, s, lay, a.symbols, sym_stride,
-                           books, ws.chunk_bits, a.chunk_offset, a.sub_bits, a.words, a.words_stride, a.status);
+        if (ws.chunk_hist)
+            hipLaunchKernelGGL(k_chunk_bits_hist, dim3(gx, lay.U), dim3(kPkThreads), 0, s, lay, ws.chunk_hist, books,
+                               ws.chunk_bits);
+        else
+            hipLaunchKernelGGL(k_chunk_bits, dim3(gx, lay.U), dim3(kPkThreads), 0, s, lay, a.symbols, sym_stride, books,
+                               ws.chunk_bits);
     }
     {
         ProfScope prof(K_SCAN, s);
@@ -310,8 +283,8 @@ hipError_t launch_pack(const Layout &lay, const co3_encode_args &a, const BookDe
     }
     if (lay.nchunks) {
         ProfScope prof(K_PACK, s);
-        hipLaunchKernelGGL(k_pack_wave<true>, dim3(gx, lay.U), dim3(kPkThreads), 0, s, lay, a.symbols, sym_stride,
-                           books, ws.chunk_bits, a.chunk_offset, a.sub_bits, a.words, a.words_stride, a.status);
+        hipLaunchKernelGGL(k_pack_chunk, dim3(gx, lay.U), dim3(kPkThreads), 0, s, lay, a.symbols, sym_stride, books,
+                           a.chunk_offset, a.sub_bits, a.words, a.words_stride, a.status);
     }
     return hipGetLastError();
 }

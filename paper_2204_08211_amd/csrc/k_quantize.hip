@@ -39,7 +39,7 @@ template <bool kSR>
 __global__ __launch_bounds__(kQThreads) void k_quantize(
     Layout lay, const float *__restrict__ g, const float *m, float *m_out,
     uint8_t *__restrict__ sym, uint64_t sym_stride, uint64_t row_stride, float gamma, uint64_t seed,
-    uint64_t *__restrict__ hist_rep, uint64_t *__restrict__ status)
+    uint64_t *__restrict__ hist_rep, uint16_t *__restrict__ chunk_hist, uint64_t *__restrict__ status)
 {
     extern __shared__ uint32_t h_lds[];  // [A][kHistRep]
     const uint32_t u = blockIdx.y;
@@ -101,11 +101,15 @@ __global__ __launch_bounds__(kQThreads) void k_quantize(
         }
         __syncthreads();
         uint64_t *hist_book = hist + (uint64_t)(book_base + lay.segs[seg].book) * lay.A;
+        // chunk_hist (single-layer vectors only: a tile is then a chunk): this tile's own counts, from which the
+        // chunk's coded size follows once the code is known, without another sweep over the symbols
+        uint16_t *ch = chunk_hist ? chunk_hist + ((uint64_t)u * lay.nchunks + blockIdx.x) * lay.A : nullptr;
         for (uint32_t bin = threadIdx.x; bin < lay.A; bin += kQThreads) {
             uint32_t s = 0;
 #pragma unroll
             for (int r = 0; r < kHistRep; ++r) s += h_lds[bin * kHistRep + ((r + bin) & (kHistRep - 1))];
             if (s) atomicAdd(reinterpret_cast<unsigned long long *>(hist_book + bin), (unsigned long long)s);
+            if (ch) ch[bin] = (uint16_t)s;
         }
     } else {
         // ragged tail of the vector or a tile that crosses a layer boundary: element path
@@ -129,6 +133,12 @@ __global__ __launch_bounds__(kQThreads) void k_quantize(
             su[i] = (uint8_t)s;
             atomicAdd(reinterpret_cast<unsigned long long *>(
                           hist + (uint64_t)(book_base + lay.segs[s_i].book) * lay.A + s), 1ull);
+            if (chunk_hist) atomicAdd(&h_lds[s * kHistRep], 1u);
+        }
+        if (chunk_hist) {  // wavefront-uniform; single-layer vectors only: this is the vector's ragged last tile
+            __syncthreads();
+            uint16_t *ch = chunk_hist + ((uint64_t)u * lay.nchunks + blockIdx.x) * lay.A;
+            for (uint32_t bin = threadIdx.x; bin < lay.A; bin += kQThreads) ch[bin] = (uint16_t)h_lds[bin * kHistRep];
         }
     }
     if (n_nonfinite)
@@ -174,10 +184,10 @@ hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, const En
         ProfScope prof(K_QUANTIZE, s);
         if (a.rounding == CO3_ROUND_STOCHASTIC)
             hipLaunchKernelGGL(k_quantize<true>, dim3((uint32_t)ntiles, lay.U), dim3(kQThreads), lds, s, lay, a.g, a.m,
-                               a.m_out, a.symbols, sym_stride, a.row_stride, a.gamma, a.seed, ws.hist_rep, a.status);
+                               a.m_out, a.symbols, sym_stride, a.row_stride, a.gamma, a.seed, ws.hist_rep, ws.chunk_hist, a.status);
         else
             hipLaunchKernelGGL(k_quantize<false>, dim3((uint32_t)ntiles, lay.U), dim3(kQThreads), lds, s, lay, a.g, a.m,
-                               a.m_out, a.symbols, sym_stride, a.row_stride, a.gamma, a.seed, ws.hist_rep, a.status);
+                               a.m_out, a.symbols, sym_stride, a.row_stride, a.gamma, a.seed, ws.hist_rep, ws.chunk_hist, a.status);
     }
     const uint64_t n = (uint64_t)lay.nbooks * lay.A;
     ProfScope prof(K_REDUCE_HIST, s);

@@ -327,7 +327,7 @@ def test_single_sweep_bounded_wait_gives_up():
         B.set_lookback_polls(B.LOOKBACK_POLLS_DEFAULT)
     stalled = int(gpu["status_encode"][B.STAT_STALLED])
     nch = plan.num_chunks
-    print(f"{stalled} of {U * ((nch + 3) // 4)} workgroups gave up", flush=True)
+    print(f"{stalled} workgroups gave up", flush=True)
     assert stalled > 0
     gu.assert_bits_equal(gpu["m_new"], ref["m_new"], "memory m'")
     gu.assert_bits_equal(gpu["sub_bits"], ref["sub_bits"], "sub-chunk bits")
