@@ -138,10 +138,42 @@ struct Reader {
     __device__ inline uint64_t window() const { return (((uint64_t)w0 << 32) | w1) << sh; }
 };
 
-// One symbol; `bad` is set if nothing matched.  A code longer than the direct table is found by
-// comparing the window with the left-aligned last code of every longer length that occurs (they
-// grow with the length).  The window's valid bits decide lengths up to 32; longer ones take the
-// exact path, which repositions the reader itself.
+// The rare part of decode_symbol, for the lanes whose prefix the direct table does not resolve (L == 0 on
+// entry; s is then 0 or 1 + the prefix's second-level table): codes a little longer than the direct table take
+// one more look-up; the rest compare the window with the left-aligned last code of every longer length that
+// occurs (they grow with the length).  The window's valid bits decide lengths up to 32; longer ones take the
+// exact path, which repositions the reader itself and leaves L = 0.
+template <class Src>
+__device__ inline void decode_symbol_long(Reader<Src> &r, const DecLds *T, uint64_t win, uint32_t &L, uint32_t &s, bool &bad)
+{
+    if (L != 0u) return;
+    uint32_t e2 = 0;
+    if (s) e2 = T->dec2[((s - 1u) << kDec2Bits) | ((uint32_t)(win >> (64 - kDecBits - kDec2Bits)) & ((1u << kDec2Bits) - 1u))];
+    if (e2) {
+        L = e2 >> 8;
+        s = e2 & 0xffu;
+        return;
+    }
+    const uint32_t n = T->nlong;
+    uint32_t k = 0;
+    while (k < n && win > T->long_last[k]) ++k;
+    if (k < n) {
+        L = T->long_len[k];
+        if (L <= 32u) s = T->sorted[((uint32_t)(win >> (64u - L)) + T->long_base[k]) & (kMaxA - 1)];
+    }
+    if (L == 0u || L > 32u) {
+        const uint32_t pos = r.pos();
+        const uint32_t code = long_code(r.src, T, pos);  // exact 64-bit window
+        uint32_t len = code >> 8;
+        s = code & 0xffu;
+        if (len == 0u) { bad = true; len = 1u; }
+        r.seek(pos + len);
+        L = 0u;                                          // the reader stands behind the code already
+    }
+}
+
+// One symbol; `bad` is set if nothing matched.  The common case is one look-up in the direct table and a
+// branch-free advance; the branch to the rare part is taken by the whole wavefront or not at all.
 template <class Src>
 __device__ inline uint32_t decode_symbol(Reader<Src> &r, const DecLds *T, bool &bad)
 {
@@ -150,32 +182,7 @@ __device__ inline uint32_t decode_symbol(Reader<Src> &r, const DecLds *T, bool &
     uint32_t e = T->dec[win >> (64 - kDecBits)];             // before either result is needed
     asm volatile("" : "+v"(nextw), "+v"(e));
     uint32_t L = e >> 8, s = e & 0xffu;
-    if (__builtin_expect(L == 0u, 0)) {
-        // codes a little longer than the direct table: one more look-up in the prefix's second-level table
-        uint32_t e2 = 0;
-        if (s) e2 = T->dec2[((s - 1u) << kDec2Bits) | ((uint32_t)(win >> (64 - kDecBits - kDec2Bits)) & ((1u << kDec2Bits) - 1u))];
-        if (e2) {
-            L = e2 >> 8;
-            s = e2 & 0xffu;
-        } else {
-            const uint32_t n = T->nlong;
-            uint32_t k = 0;
-            while (k < n && win > T->long_last[k]) ++k;
-            if (k < n) {
-                L = T->long_len[k];
-                if (L <= 32u) s = T->sorted[((uint32_t)(win >> (64u - L)) + T->long_base[k]) & (kMaxA - 1)];
-            }
-        }
-        if (__builtin_expect(L == 0u || L > 32u, 0)) {
-            const uint32_t pos = r.pos();
-            const uint32_t code = long_code(r.src, T, pos);  // exact 64-bit window
-            uint32_t len = code >> 8;
-            s = code & 0xffu;
-            if (len == 0u) { bad = true; len = 1u; }
-            r.seek(pos + len);
-            L = 0u;                                          // the reader stands behind the code already
-        }
-    }
+    if (__builtin_expect(__any(L == 0u), 0)) decode_symbol_long(r, T, win, L, s, bad);
     const uint32_t t = r.sh + L;
     const bool take = t >= 32u;
     r.sh = t & 31u;
@@ -185,11 +192,36 @@ __device__ inline uint32_t decode_symbol(Reader<Src> &r, const DecLds *T, bool &
     return s;
 }
 
-// Decode `cnt` (<= 64) symbols of one sub-chunk starting `p0` bits into the chunk; symbols go to
-// stage_row[0..16] (4 per word).  Returns the number of bits consumed, or ~0u if a prefix matched
-// no codeword.
-template <class Src>
-__device__ inline uint32_t decode_subchunk(Src src, uint32_t p0, int cnt, const DecLds *T, uint32_t *stage_row)
+// Where a lane's decoded symbols go.
+// StageSink: four per word into an LDS row (co3_decode: coalesced stores of symbols and values follow).
+struct StageSink {
+    uint32_t *row;
+    uint32_t packed;
+    __device__ inline void sym(int j, uint32_t s)
+    {
+        packed |= s << (8 * (j & 3));
+        if ((j & 3) == 3) { row[j >> 2] = packed; packed = 0; }
+    }
+    __device__ inline void finish(int cnt) { if (cnt & 3) row[cnt >> 2] = packed; }
+};
+// AccSink: the symbol's value is added to the element's fp64 accumulator in LDS (co3_ps_aggregate).  The value
+// is the magnitude's entry in the user's table of fp32 patterns with the symbol's sign bit moved to bit 31.
+struct AccSink {
+    double *row;            // the lane's 64 accumulators
+    const uint32_t *mag;
+    uint32_t mag_mask, sign_up;
+    __device__ inline void sym(int j, uint32_t s)
+    {
+        const uint32_t bits = mag[s & mag_mask] | ((s << sign_up) & 0x80000000u);
+        __hip_atomic_fetch_add(&row[j], (double)__uint_as_float(bits), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    __device__ inline void finish(int) {}
+};
+
+// Decode `cnt` (<= 64) symbols of one sub-chunk starting `p0` bits into the chunk and hand them to the sink.
+// Returns the number of bits consumed, or ~0u if a prefix matched no codeword.
+template <class Src, class Sink>
+__device__ inline uint32_t decode_subchunk(Src src, uint32_t p0, int cnt, const DecLds *T, Sink sink)
 {
     Reader<Src> r;
     r.src = src;
@@ -197,18 +229,12 @@ __device__ inline uint32_t decode_subchunk(Src src, uint32_t p0, int cnt, const 
     bool bad = false;
     if (cnt == kSub) {
         for (int jj = 0; jj < kSub / 4; ++jj) {
-            uint32_t packed = 0;
 #pragma unroll
-            for (int b = 0; b < 4; ++b) packed |= decode_symbol(r, T, bad) << (8 * b);
-            stage_row[jj] = packed;
+            for (int b = 0; b < 4; ++b) sink.sym(4 * jj + b, decode_symbol(r, T, bad));
         }
     } else {
-        uint32_t packed = 0;
-        for (int j = 0; j < cnt; ++j) {
-            packed |= decode_symbol(r, T, bad) << (8 * (j & 3));
-            if ((j & 3) == 3) { stage_row[j >> 2] = packed; packed = 0; }
-        }
-        if (cnt & 3) stage_row[cnt >> 2] = packed;
+        for (int j = 0; j < cnt; ++j) sink.sym(j, decode_symbol(r, T, bad));
+        sink.finish(cnt);
     }
     return bad ? ~0u : r.pos() - p0;
 }
@@ -258,11 +284,12 @@ __device__ inline ChunkIndex read_index(const Layout &lay, uint64_t c, uint32_t 
     return ix;
 }
 
-// One wavefront: bring the chunk into s_pay (if it fits), decode it into s_stage.  Every read of
+// One wavefront: bring the chunk into s_pay (if it fits), decode it into the lanes' sinks.  Every read of
 // the stream stays inside the chunk's words.  Inconsistent sub-chunks are counted in
 // status[CO3_STAT_CORRUPT].  Contains wave-level synchronisation only.
+template <class Sink>
 __device__ inline void decode_user_chunk(const ChunkGeom &g, const ChunkIndex &ix, const DecLds *T,
-                                         uint32_t *s_pay, uint32_t *s_stage, uint64_t *status)
+                                         uint32_t *s_pay, Sink sink, uint64_t *status)
 {
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t p0 = wave_exclusive_scan_u32(ix.sb);
@@ -285,9 +312,9 @@ __device__ inline void decode_user_chunk(const ChunkGeom &g, const ChunkIndex &i
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        if (cnt > 0) used = decode_subchunk(LdsWords{s_pay}, p0, cnt, T, s_stage + lane * kStageStride);
+        if (cnt > 0) used = decode_subchunk(LdsWords{s_pay}, p0, cnt, T, sink);
     } else if (cnt > 0) {
-        used = decode_subchunk(GlobalWords{ix.w, ix.nw}, p0, cnt, T, s_stage + lane * kStageStride);
+        used = decode_subchunk(GlobalWords{ix.w, ix.nw}, p0, cnt, T, sink);
     }
     if (used != ix.sb || !ix.ok)
         atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CORRUPT), 1ull);
@@ -328,7 +355,7 @@ __global__ __launch_bounds__(64 * kDecWaves) void k_decode(Layout lay, const uin
     __syncthreads();
     if (!active) return;  // whole wavefront; wavefront-level synchronisation only from here on
     uint32_t *s_stage = s_stage_all + wave * kStageWords;
-    decode_user_chunk(g, ix, my_tab, s_pay_all + wave * kPayloadAlloc, s_stage, status);
+    decode_user_chunk(g, ix, my_tab, s_pay_all + wave * kPayloadAlloc, StageSink{s_stage + lane * kStageStride, 0u}, status);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -357,11 +384,15 @@ __global__ __launch_bounds__(64 * kDecWaves) void k_decode(Layout lay, const uin
 }
 
 constexpr int kMagEntries = kMaxA / 2;  // magnitude codes of a symbol alphabet (the sign bit is on top)
+constexpr int kAccStride = kSub + 1;    // a lane's 64 accumulators + 1 pad: lanes hit different banks
+constexpr int kAccWords = kSubsPerChunk * kAccStride;
 
-// One workgroup per chunk; W wavefronts decode W users at a time into LDS, then every thread
-// sums its elements over those users in ascending user order, in fp64.  The value of a symbol is
-// its magnitude's entry in a per-user LDS table (every representative is an fp32) with the
-// symbol's sign bit moved to bit 31.
+// One workgroup per chunk.  The chunk's 4096 sums live in LDS as fp64; W wavefronts decode W users at a time,
+// lane j of each taking sub-chunk j, and every decoded symbol's value is added to its element's sum with an
+// LDS atomic (the users' values are fp32 numbers whose exponents lie within a few dozen binades, so the fp64
+// sums are exact and their order does not matter; with exponent biases more than about 45 binades apart the
+// last bit may depend on it).  The wavefronts meet only twice: after the sums are cleared and before they
+// are written out.
 template <int W>
 __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t *__restrict__ words,
                                                       uint64_t words_stride,
@@ -372,64 +403,42 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
                                                       uint64_t *__restrict__ status)
 {
     extern __shared__ uint64_t smem64[];
-    DecLds *s_tab = reinterpret_cast<DecLds *>(smem64);   // [per-user books ? W : 1]
+    double *s_acc = reinterpret_cast<double *>(smem64);                    // [64][kAccStride]
+    DecLds *s_tab = reinterpret_cast<DecLds *>(s_acc + kAccWords);         // [per-user books ? W : 1]
     const uint32_t ntab = lay.per_user_books ? W : 1;
     uint32_t *s_mag = reinterpret_cast<uint32_t *>(s_tab + ntab);          // [W][kMagEntries] fp32 patterns
-    uint32_t *s_stage = s_mag + W * kMagEntries;                           // [W][kStageWords]
-    uint32_t *s_pay = s_stage + W * kStageWords;                           // [W][kPayloadAlloc]
+    uint32_t *s_pay = s_mag + W * kMagEntries;                             // [W][kPayloadAlloc]
     constexpr int T = 64 * W;
-    constexpr int G = (kChunk / 4) / T;  // 4-element groups per thread
-    const uint32_t t = threadIdx.x, wave = t >> 6;
+    const uint32_t t = threadIdx.x, wave = t >> 6, lane = t & 63u;
     const uint64_t c = blockIdx.x;
     const ChunkGeom g = chunk_geom(lay, c);
     const uint32_t sign_shift = (uint32_t)(lay.E + lay.M);
     const uint32_t mag_mask = (1u << sign_shift) - 1u;
     const uint32_t sign_up = 31u - sign_shift;
 
-    double acc[G][4];
-#pragma unroll
-    for (int i = 0; i < G; ++i)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) acc[i][b] = 0.0;
+    for (uint32_t i = t; i < (uint32_t)kAccWords; i += T) s_acc[i] = 0.0;
+    if (!lay.per_user_books) load_dec_tables(s_tab, books[(uint32_t)g.book], t, T);
+    __syncthreads();
 
-    for (uint32_t u0 = 0; u0 < lay.U; u0 += W) {
-        const uint32_t u = u0 + wave;
-        const bool active = u < lay.U;
-        ChunkIndex ix;
-        if (active) ix = read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits);
-        const DecLds *my_tab = s_tab;
-        if (lay.per_user_books) {
-            my_tab = s_tab + wave;
-            if (active) load_dec_tables(s_tab + wave, books[u * lay.books_per_user + (uint32_t)g.book], t & 63u, 64);
-        } else if (u0 == 0) {
-            load_dec_tables(s_tab, books[(uint32_t)g.book], t, T);
-        }
-        for (uint32_t i = t; i < (uint32_t)(W * kMagEntries); i += T) {
-            const uint32_t uu = i / kMagEntries, k = i % kMagEntries;
-            if (u0 + uu < lay.U && k <= mag_mask)
-                s_mag[i] = symbol_value_bits(k, lay.E, lay.M, lay.bias[(uint64_t)(u0 + uu) * lay.nseg + g.seg]);
-        }
-        __syncthreads();
-        if (active) decode_user_chunk(g, ix, my_tab, s_pay + wave * kPayloadAlloc, s_stage + wave * kStageWords, status);
-        __syncthreads();
-        const uint32_t nu = (lay.U - u0 < (uint32_t)W) ? lay.U - u0 : (uint32_t)W;
-        for (uint32_t uu = 0; uu < nu; ++uu) {
-            const uint32_t *mag = s_mag + uu * kMagEntries;
-            const uint32_t *st = s_stage + uu * kStageWords;
-#pragma unroll
-            for (int i = 0; i < G; ++i) {
-                const uint32_t e4 = t + (uint32_t)i * T;  // group of elements 4*e4 .. 4*e4+3
-                const uint32_t wv = st[(e4 >> 4) * kStageStride + (e4 & 15u)];
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const uint32_t s = (wv >> (8 * b)) & 0xffu;
-                    const uint32_t bits = mag[s & mag_mask] | ((s << sign_up) & 0x80000000u);
-                    acc[i][b] += (double)__uint_as_float(bits);
-                }
-            }
-        }
-        __syncthreads();
+    // wavefront `wave` takes users wave, wave + W, ...; everything it touches besides the sums is its own
+    uint32_t *my_mag = s_mag + wave * kMagEntries;
+    uint32_t *my_pay = s_pay + wave * kPayloadAlloc;
+    const DecLds *my_tab = lay.per_user_books ? s_tab + wave : s_tab;
+    for (uint32_t u = wave; u < lay.U; u += W) {
+        const ChunkIndex ix = read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits);
+        if (lay.per_user_books) load_dec_tables(s_tab + wave, books[u * lay.books_per_user + (uint32_t)g.book], lane, 64);
+        const int bias = lay.bias[(uint64_t)u * lay.nseg + g.seg];
+        for (uint32_t k = lane; k <= mag_mask; k += 64) my_mag[k] = symbol_value_bits(k, lay.E, lay.M, bias);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        decode_user_chunk(g, ix, my_tab, my_pay, AccSink{s_acc + lane * kAccStride, my_mag, mag_mask, sign_up}, status);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();   // the next user's tables and words overwrite these
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
+    __syncthreads();
+
     // average, and with `model` the PS update w - eta * average (eq. (aggregate hat), Algorithm 1
     // line 14): products and difference in fp64, one rounding
     const double inv_u = 1.0 / (double)lay.U;
@@ -437,12 +446,14 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
     const uintptr_t out_addr = out ? reinterpret_cast<uintptr_t>(out + g.e0) : 0u;
     const uintptr_t model_addr = model ? reinterpret_cast<uintptr_t>(model + g.e0) : 0u;
     const bool vec_ok = ((out_addr | model_addr) & 15u) == 0;
+    constexpr int G = (kChunk / 4) / T;  // 4-element groups per thread
 #pragma unroll
     for (int i = 0; i < G; ++i) {
-        const uint32_t e = 4u * (t + (uint32_t)i * T);
+        const uint32_t e = 4u * (t + (uint32_t)i * T);                     // elements e .. e + 3: one lane's row
+        const double *a = s_acc + (e >> 6) * kAccStride + (e & 63u);
         double avg[4];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) avg[b] = acc[i][b] * inv_u;
+        for (int b = 0; b < 4; ++b) avg[b] = a[b] * inv_u;
         if (vec_ok && e + 3 < g.n) {
             if (out)
                 *reinterpret_cast<float4 *>(out + g.e0 + e) =
@@ -486,8 +497,8 @@ template <int W>
 static hipError_t launch_aggregate_w(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
                                      hipStream_t s)
 {
-    const size_t lds = (size_t)(lay.per_user_books ? W : 1) * sizeof(DecLds) +
-                       (size_t)W * (kMagEntries + kStageWords + kPayloadAlloc) * 4;
+    const size_t lds = (size_t)kAccWords * sizeof(double) + (size_t)(lay.per_user_books ? W : 1) * sizeof(DecLds) +
+                       (size_t)W * (kMagEntries + kPayloadAlloc) * 4;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_aggregate<W>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
