@@ -94,6 +94,16 @@ int co3_plan_create(co3_format format, uint32_t U, uint64_t d, uint32_t nseg,
                     co3_plan **out);
 /* Replace the [U][nseg] bias table (host memory).  Synchronises `stream`.                  */
 int co3_plan_set_bias(co3_plan *plan, const int32_t *bias, void *stream);
+/* Real-valued scale (eq. (exp bias) of Sec. IV-A (i) lets b range over the reals, so c_scale = 2^b need not be
+ * a power of two).  The integer bias carries the power-of-two part; this call adds, per user and layer, a
+ * gain s applied to the input of the conversion and its reciprocal c applied to the representative, in fp32:
+ *   y = fl32(v s),  symbol = code of Q_fp(y),  ghat = fl32(value(symbol) c),  m' = fl32(v - ghat),
+ * so that the representative set becomes {c x : x in X}; m' is then no longer the exact difference.  The PS side
+ * (co3_decode's q, co3_ps_aggregate) forms ghat the same way.  gain, inv_gain: host [U][nseg], positive normal
+ * fp32 numbers, the caller supplying the pair (typically inv_gain = 2^(b - round(b)), gain = 1 / inv_gain); both
+ * NULL restores 1.  Non-finite and clamped inputs are judged on y.  Not combined with CO3_ROUND_STOCHASTIC
+ * (co3_encode then returns CO3_ERR_ARG).  Synchronises `stream`.                                              */
+int co3_plan_set_gain(co3_plan *plan, const float *gain, const float *inv_gain, void *stream);
 void co3_plan_destroy(co3_plan *plan);
 uint64_t co3_plan_num_chunks(const co3_plan *plan);     /* chunks per user                  */
 uint32_t co3_plan_num_books(const co3_plan *plan);      /* tables in a matching set         */

@@ -87,12 +87,13 @@ def fit_round(g, m, gamma, seg_len):
     return out
 
 
-def pooled_model_weights(E, M, bias, params, seg_len, seg_book, per_user_books, scale_bits=40):
+def pooled_model_weights(E, M, bias, params, seg_len, seg_book, per_user_books, scale_bits=40, gain=None):
     """Integer Huffman weights [nbooks][A] of the model code (Sec. IV-A (ii)) when table b serves the
     (user, layer) pairs mapped to it: the table's source is the mixture of the pairs' quantized
     GenNorm models weighted by their element counts; every symbol Q_fp can produce gets
     max(1, floor(p 2^scale_bits)).  Pairs with alpha == 0 or no elements contribute nothing; a table
-    without contributions gets weight 1 on every producible symbol."""
+    without contributions gets weight 1 on every producible symbol.  gain [U][nseg]: with a real-valued scale the
+    conversion sees v gain, a GenNorm with location and scale multiplied by the gain."""
     params = np.asarray(params, np.float64)
     U, nseg = params.shape[:2]
     bias = np.broadcast_to(np.asarray(bias, np.int32), (U, nseg))
@@ -106,6 +107,9 @@ def pooled_model_weights(E, M, bias, params, seg_len, seg_book, per_user_books, 
         for k in range(nseg):
             b = (u * bpu if per_user_books else 0) + seg_book[k]
             mu, alpha, beta = params[u, k, :3]
+            if gain is not None:
+                gn = float(np.asarray(gain, np.float32).reshape(U, nseg)[u, k])
+                mu, alpha = mu * gn, alpha * gn
             _, p, syms = orc.gennorm_weights(E, M, int(bias[u, k]), 0.0, 1.0, 1.0, scale_bits)
             emit[b, syms] = True
             if seg_len[k] == 0 or not (alpha > 0.0 and beta > 0.0):

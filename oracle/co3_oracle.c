@@ -228,6 +228,44 @@ int co3o_ef_step(const float *g, const float *m, uint64_t n, float gamma,
 }
 
 /* ------------------------------------------------------------------------- */
+/* Real-valued scale (eq. (exp bias) of Sec. IV-A (i) has b in R, i.e. a scale */
+/* c_scale = 2^b that need not be a power of two).  Reading R16: the integer   */
+/* bias carries the power-of-two part; on top of it the input is multiplied by */
+/* a gain s before the conversion and the representative by c (the caller's    */
+/* reciprocal of s) after it, all in fp32:                                     */
+/*   y = fl32(v s),  sym = code of Q_fp(y),  ghat = fl32(value(sym) c),        */
+/*   m' = fl32(v - ghat).                                                      */
+/* The representative set is {c x : x in X}.  s = c = 1 is the plain step.     */
+/* m' is no longer the exact difference (ghat is itself rounded).  Non-finite  */
+/* y and clamping as R4, decided on y.                                         */
+/* ------------------------------------------------------------------------- */
+int co3o_ef_step_gain(const float *g, const float *m, uint64_t n, float gamma,
+                      int exp_bits, int mant_bits, int bias, float gain, float inv_gain,
+                      float *m_out, uint8_t *sym, float *q_out, uint64_t *counters)
+{
+    if (1 + exp_bits + mant_bits > 8) return CO3O_ERR_FORMAT;
+    int nmag = co3o_num_magnitudes(exp_bits, mant_bits);
+    double mag[256];
+    int rc = co3o_grid(exp_bits, mant_bits, bias, mag);
+    if (rc < 0) return rc;
+    for (uint64_t i = 0; i < n; ++i) {
+        volatile float t = gamma * m[i];
+        volatile float v = g[i] + t;
+        volatile float y = v * gain;          /* fl32(v s)                   */
+        int fl; uint32_t c;
+        volatile float qy = quantize_one(mag, nmag, exp_bits + mant_bits, y, &c, &fl);
+        volatile float q = qy * inv_gain;     /* fl32(value c)               */
+        volatile float err = v - q;
+        if (fl & 1) err = 0.0f;
+        if (counters) { counters[0] += (fl & 1); counters[1] += (fl >> 1) & 1; }
+        sym[i] = (uint8_t)c;
+        m_out[i] = err;
+        if (q_out) q_out[i] = q;
+    }
+    return CO3O_OK;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Stochastic fp conversion (Sec. II-B (ii) allows Q to be a random mapping,   */
 /* which is what non-subtractive dithering needs; the paper gives no          */
 /* construction).  Reading: v goes to one of its two neighbours in X, the     */
@@ -537,6 +575,31 @@ int co3o_aggregate(const uint8_t *sym, uint32_t U, uint64_t d, int nseg,
             for (uint32_t u = 0; u < U; ++u)
                 acc += co3o_value(sym[(size_t)u * d + i], exp_bits, mant_bits,
                                   bias[(size_t)u * nseg + k]);
+            out[i] = (float)(acc * inv_u);
+        }
+        elem += seg_len[k];
+    }
+    return (elem == d) ? CO3O_OK : CO3O_ERR_ARG;
+}
+
+/* The same average when the users' representatives carry a real-valued scale */
+/* (reading R16): ghat = fl32(value(sym) c) with c = inv_gain[u][k], fp32.     */
+int co3o_aggregate_gain(const uint8_t *sym, uint32_t U, uint64_t d, int nseg,
+                        const uint64_t *seg_len, const int32_t *bias, const float *inv_gain,
+                        int exp_bits, int mant_bits, float *out)
+{
+    if (U == 0) return CO3O_ERR_ARG;
+    double inv_u = 1.0 / (double)U;
+    uint64_t elem = 0;
+    for (int k = 0; k < nseg; ++k) {
+        for (uint64_t i = elem; i < elem + seg_len[k]; ++i) {
+            double acc = 0.0;
+            for (uint32_t u = 0; u < U; ++u) {
+                volatile float val = (float)co3o_value(sym[(size_t)u * d + i], exp_bits, mant_bits,
+                                                       bias[(size_t)u * nseg + k]);
+                volatile float q = val * inv_gain[(size_t)u * nseg + k];
+                acc += (double)q;
+            }
             out[i] = (float)(acc * inv_u);
         }
         elem += seg_len[k];

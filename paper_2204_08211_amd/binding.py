@@ -27,7 +27,7 @@ EXPORTS = [
     "co3_codebook_destroy", "co3_encode", "co3_decode", "co3_ps_aggregate", "co3_status_string",
     "co3_profile_begin", "co3_profile_end", "co3_gennorm_weights", "co3_plan_fit_workspace_bytes", "co3_gennorm_fit",
     "co3_model_weights_device", "co3_model_bias_device", "co3_plan_set_bias_device", "co3_bias_from_model",
-    "co3_plan_bias_workspace_bytes", "co3_set_lookback_polls", "co3_encode_static",
+    "co3_plan_bias_workspace_bytes", "co3_set_lookback_polls", "co3_encode_static", "co3_plan_set_gain",
 ]
 
 
@@ -87,6 +87,7 @@ def lib():
         L.co3_plan_create.argtypes = [Format, C.c_uint32, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p,
                                       C.c_int32, C.POINTER(C.c_void_p)]
         L.co3_plan_set_bias.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.co3_plan_set_gain.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.co3_plan_destroy.argtypes = [C.c_void_p]
         L.co3_plan_destroy.restype = None
         for name, rt in [("co3_plan_num_chunks", C.c_uint64), ("co3_plan_num_books", C.c_uint32),
@@ -197,6 +198,16 @@ class Plan:
         bias = np.ascontiguousarray(np.broadcast_to(np.asarray(bias, dtype=np.int32), (self.U, self.nseg)))
         _check("co3_plan_set_bias", lib().co3_plan_set_bias(self.handle, bias.ctypes.data_as(C.c_void_p), _stream(stream)))
         self.bias = bias
+
+    def set_gain(self, gain, inv_gain, stream=None):
+        """Real-valued scale on top of the integer bias: float32 [U][nseg] pairs (None, None: back to 1)."""
+        if gain is None:
+            _check("co3_plan_set_gain", lib().co3_plan_set_gain(self.handle, None, None, _stream(stream)))
+            return
+        gain = np.ascontiguousarray(np.broadcast_to(np.asarray(gain, dtype=np.float32), (self.U, self.nseg)))
+        inv_gain = np.ascontiguousarray(np.broadcast_to(np.asarray(inv_gain, dtype=np.float32), (self.U, self.nseg)))
+        _check("co3_plan_set_gain", lib().co3_plan_set_gain(self.handle, gain.ctypes.data_as(C.c_void_p),
+                                                          inv_gain.ctypes.data_as(C.c_void_p), _stream(stream)))
 
     def stream_words(self, max_code_len=64):
         return int(lib().co3_plan_stream_words(self.handle, int(max_code_len)))

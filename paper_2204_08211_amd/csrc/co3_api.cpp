@@ -146,10 +146,13 @@ int co3_plan_create(co3_format format, uint32_t U, uint64_t d, uint32_t nseg, co
         void *unused = nullptr;
         (void)scratch_address(p->device, &unused);
     }
+    const std::vector<float> ones((size_t)U * nseg * 2, 1.0f);
     if (hipMalloc(&p->d_segs, sizeof(SegDev) * (nseg + 1)) != hipSuccess ||
         hipMalloc(&p->d_bias, sizeof(int32_t) * (size_t)U * nseg) != hipSuccess ||
+        hipMalloc(&p->d_gain, sizeof(float) * ones.size()) != hipSuccess ||
         hipMemcpy(p->d_segs, segs.data(), sizeof(SegDev) * (nseg + 1), hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(p->d_bias, bias, sizeof(int32_t) * (size_t)U * nseg, hipMemcpyHostToDevice) != hipSuccess) {
+        hipMemcpy(p->d_bias, bias, sizeof(int32_t) * (size_t)U * nseg, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(p->d_gain, ones.data(), sizeof(float) * ones.size(), hipMemcpyHostToDevice) != hipSuccess) {
         co3_plan_destroy(p);
         return CO3_ERR_HIP;
     }
@@ -162,6 +165,7 @@ int co3_plan_create(co3_format format, uint32_t U, uint64_t d, uint32_t nseg, co
     l.nbooks = l.books_per_user * (per_user_books ? U : 1u);
     l.segs = p->d_segs;
     l.bias = p->d_bias;
+    l.gain = p->d_gain;
     *out = p;
     return CO3_OK;
 }
@@ -181,12 +185,36 @@ int co3_plan_set_bias(co3_plan *plan, const int32_t *bias, void *stream)
     return CO3_OK;
 }
 
+int co3_plan_set_gain(co3_plan *plan, const float *gain, const float *inv_gain, void *stream)
+{
+    if (!plan || (gain == nullptr) != (inv_gain == nullptr)) return CO3_ERR_ARG;
+    const size_t n = (size_t)plan->lay.U * plan->lay.nseg;
+    std::vector<float> pairs(2 * n, 1.0f);
+    bool any = false;
+    for (size_t i = 0; gain && i < n; ++i) {
+        // positive normal fp32 numbers only
+        if (!(gain[i] >= 1.17549435e-38f && gain[i] <= 3.4e38f) || !(inv_gain[i] >= 1.17549435e-38f && inv_gain[i] <= 3.4e38f))
+            return CO3_ERR_ARG;
+        pairs[2 * i] = gain[i];
+        pairs[2 * i + 1] = inv_gain[i];
+        any = any || gain[i] != 1.0f || inv_gain[i] != 1.0f;
+    }
+    DeviceGuard guard(plan->device);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(plan->d_gain, pairs.data(), sizeof(float) * pairs.size(), hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        return CO3_ERR_HIP;
+    plan->has_gain = any;
+    return CO3_OK;
+}
+
 void co3_plan_destroy(co3_plan *plan)
 {
     if (!plan) return;
     DeviceGuard guard(plan->device);
     if (plan->d_segs) (void)hipFree(plan->d_segs);
     if (plan->d_bias) (void)hipFree(plan->d_bias);
+    if (plan->d_gain) (void)hipFree(plan->d_gain);
     delete plan;
 }
 
@@ -315,6 +343,7 @@ static int encode_with_workspace(const co3_plan *plan, const co3_encode_args *a,
         return CO3_ERR_ARG;
     if (a->mode != CO3_BOOK_FIXED && a->mode != CO3_BOOK_EMPIRICAL) return CO3_ERR_ARG;
     if (a->rounding != CO3_ROUND_NEAREST && a->rounding != CO3_ROUND_STOCHASTIC) return CO3_ERR_ARG;
+    if (a->rounding == CO3_ROUND_STOCHASTIC && plan->has_gain) return CO3_ERR_ARG;  // defined for the closest representative only
     // symbols and hist come as a pair; without them a fixed code is encoded in a single sweep
     const bool single_sweep = a->mode == CO3_BOOK_FIXED && !a->symbols && !a->hist;
     if (!single_sweep && (!a->symbols || !a->hist)) return CO3_ERR_ARG;

@@ -67,6 +67,7 @@ struct Layout {
     uint32_t nbooks;           // tables in a set
     const SegDev *segs;        // device [nseg + 1] (last entry: offset = d, chunk_start = nchunks)
     const int32_t *bias;       // device [U][nseg]
+    const float *gain;         // device [U][nseg][2]: (gain, inv_gain) of the real-valued scale; (1, 1) when unused
 };
 
 }  // namespace co3
@@ -75,6 +76,8 @@ struct co3_plan {
     co3::Layout lay;
     co3::SegDev *d_segs = nullptr;
     int32_t *d_bias = nullptr;
+    float *d_gain = nullptr;
+    bool has_gain = false;     // a gain other than (1, 1) was installed
     int device = 0;
 };
 

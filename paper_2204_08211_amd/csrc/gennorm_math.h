@@ -55,7 +55,7 @@ CO3_HD inline void inc_gamma(double a, double x, double *P, double *Q)
             d = 1.0 / d;
             const double del = d * c;
             h *= del;
-            if (fabs(del - 1.0) < 1e-16) break;
+            if (fabs(del - 1.0) < 4e-16) break;   // within an ulp of 1 (a tighter test can miss it for good)
         }
         *Q = lead * h;
         *P = 1.0 - *Q;

@@ -375,10 +375,11 @@ __global__ __launch_bounds__(64 * kDecWaves) void k_decode(Layout lay, const uin
     }
     if (q) {
         const int bias = lay.bias[(uint64_t)u * lay.nseg + g.seg];
+        const float inv_gain = lay.gain[2 * ((uint64_t)u * lay.nseg + g.seg) + 1];   // 1 unless the plan carries a scale
         float *dst = q + (uint64_t)u * q_stride + g.e0;
         for (uint32_t e = lane; e < g.n; e += 64) {
             const uint32_t s = stage_b[(e >> 6) * (kStageStride * 4) + (e & 63u)];
-            dst[e] = __uint_as_float(symbol_value_bits(s, lay.E, lay.M, bias));
+            dst[e] = __fmul_rn(__uint_as_float(symbol_value_bits(s, lay.E, lay.M, bias)), inv_gain);
         }
     }
 }
@@ -428,7 +429,9 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
         const ChunkIndex ix = read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits);
         if (lay.per_user_books) load_dec_tables(s_tab + wave, books[u * lay.books_per_user + (uint32_t)g.book], lane, 64);
         const int bias = lay.bias[(uint64_t)u * lay.nseg + g.seg];
-        for (uint32_t k = lane; k <= mag_mask; k += 64) my_mag[k] = symbol_value_bits(k, lay.E, lay.M, bias);
+        const float inv_gain = lay.gain[2 * ((uint64_t)u * lay.nseg + g.seg) + 1];   // 1 unless the plan carries a scale
+        for (uint32_t k = lane; k <= mag_mask; k += 64)
+            my_mag[k] = __float_as_uint(__fmul_rn(__uint_as_float(symbol_value_bits(k, lay.E, lay.M, bias)), inv_gain));
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");

@@ -153,7 +153,9 @@ __global__ __launch_bounds__(kMaxA) void k_model_weights(Layout lay, const co3_g
                 const co3_gennorm_params p = params[(uint64_t)u * lay.nseg + k];
                 if (!(p.alpha > 0.0) || !(p.beta > 0.0)) continue;
                 symbol_cell(s, lay.E, lay.M, lay.bias[(uint64_t)u * lay.nseg + k], &lo, &hi);
-                mass += (double)sd.length * gennorm_mass(lo, hi, p.mu, p.alpha, p.beta);
+                // with a real-valued scale the conversion sees y = v * gain: the model's location and scale times gain
+                const double gn = (double)lay.gain[2 * ((uint64_t)u * lay.nseg + k)];
+                mass += (double)sd.length * gennorm_mass(lo, hi, p.mu * gn, p.alpha * gn, p.beta);
                 count += (double)sd.length;
             }
         }
@@ -169,31 +171,96 @@ __global__ __launch_bounds__(kMaxA) void k_model_weights(Layout lay, const co3_g
     weights[(uint64_t)b * lay.A + s] = w;
 }
 
-// Exponent bias from the model, eq. (exp bias) with integer b.
+// Exponent bias from the model, eq. (exp bias) with integer b.  The expected squared error of a candidate
+// bias is a sum of non-negative shares, one per symbol's cell, so any few shares bound it from below:
+//   k_model_bias_bounds  per (user, layer), thread per candidate: the shares of the zero cell and of the two
+//                        outermost cells (too coarse a set loses in the first, too narrow a one in the others)
+//   k_model_bias_ref     per (user, layer): the candidate with the smallest bound, evaluated in full; no
+//                        candidate whose bound exceeds that error can be the minimum or tie with it
 //   k_model_bias_errors  workgroup per (candidate bias, layer, user), thread per symbol: every thread
 //                        integrates (x - r)^2 f(x) over its symbol's cell, the workgroup folds the
-//                        shares in a fixed order -> expected squared error of the candidate
+//                        shares in a fixed order -> expected squared error of the candidate; candidates
+//                        ruled out by their bound leave at once (a handful of the 226 remain)
 //   k_model_bias_pick    per (user, layer): the smallest bias whose error is within kBiasTie of the
 //                        minimum (a format with many binades has a plateau of equally good biases;
 //                        the smallest has the most headroom).  No model (alpha = 0): the IEEE bias.
 constexpr int kBiasSlots = 256;  // error slots per (user, layer); candidates: at most 226
-__global__ __launch_bounds__(kMaxA) void k_model_bias_errors(Layout lay, const co3_gennorm_params *__restrict__ params,
-                                                             double *__restrict__ errors)
+constexpr double kBiasPrune = 1e-6;  // margin of the bound test, far above the rounding of the sums and the tie width
+
+// the workgroup's sum of one value per thread, folded in a fixed order
+__device__ inline double bias_fold(double *s_red, uint32_t t, double e)
 {
-    __shared__ double s_red[kMaxA];
-    const uint32_t cand = blockIdx.x, seg = blockIdx.y, u = blockIdx.z, t = threadIdx.x;
-    const co3_gennorm_params p = params[(uint64_t)u * lay.nseg + seg];
-    const bool model = p.alpha > 0.0 && p.beta > 0.0;
-    double e = 0.0;
-    if (model && t < lay.A)
-        e = sq_error_of_symbol(t, lay.E, lay.M, bias_min_supported(lay.E) + (int)cand, p.mu, p.alpha, p.beta);
     s_red[t] = e;
     __syncthreads();
     for (int o = kMaxA / 2; o > 0; o >>= 1) {
         if (t < (uint32_t)o) s_red[t] += s_red[t + o];
         __syncthreads();
     }
-    if (t == 0) errors[((uint64_t)u * lay.nseg + seg) * kBiasSlots + cand] = model ? s_red[0] : INFINITY;
+    const double r = s_red[0];
+    __syncthreads();
+    return r;
+}
+
+__global__ __launch_bounds__(kMaxA) void k_model_bias_bounds(Layout lay, const co3_gennorm_params *__restrict__ params,
+                                                             double *__restrict__ bounds)
+{
+    const uint32_t seg = blockIdx.x, u = blockIdx.y, cand = threadIdx.x;
+    const co3_gennorm_params p = params[(uint64_t)u * lay.nseg + seg];
+    const int ncand = kBiasMax - bias_min_supported(lay.E) + 1;
+    if ((int)cand >= ncand) return;
+    double lb = INFINITY;
+    if (p.alpha > 0.0 && p.beta > 0.0) {
+        const int bias = bias_min_supported(lay.E) + (int)cand;
+        const uint32_t top = (((1u << lay.E) - 1u) << lay.M) - 1u;        // largest magnitude code
+        lb = sq_error_of_symbol(0u, lay.E, lay.M, bias, p.mu, p.alpha, p.beta) +
+             sq_error_of_symbol(top, lay.E, lay.M, bias, p.mu, p.alpha, p.beta) +
+             sq_error_of_symbol((1u << (lay.E + lay.M)) | top, lay.E, lay.M, bias, p.mu, p.alpha, p.beta);
+    }
+    bounds[((uint64_t)u * lay.nseg + seg) * kBiasSlots + cand] = lb;
+}
+
+__global__ __launch_bounds__(kMaxA) void k_model_bias_ref(Layout lay, const co3_gennorm_params *__restrict__ params,
+                                                          const double *__restrict__ bounds, double *__restrict__ ref)
+{
+    __shared__ double s_red[kMaxA];
+    __shared__ int s_c0;
+    const uint32_t seg = blockIdx.x, u = blockIdx.y, t = threadIdx.x;
+    const co3_gennorm_params p = params[(uint64_t)u * lay.nseg + seg];
+    const bool model = p.alpha > 0.0 && p.beta > 0.0;
+    const int ncand = kBiasMax - bias_min_supported(lay.E) + 1;
+    if (t == 0) {
+        const double *lb = bounds + ((uint64_t)u * lay.nseg + seg) * kBiasSlots;
+        int c0 = 0;
+        for (int c = 1; c < ncand; ++c) c0 = lb[c] < lb[c0] ? c : c0;
+        s_c0 = c0;
+    }
+    __syncthreads();
+    double e = 0.0;
+    if (model && t < lay.A)
+        e = sq_error_of_symbol(t, lay.E, lay.M, bias_min_supported(lay.E) + s_c0, p.mu, p.alpha, p.beta);
+    const double total = bias_fold(s_red, t, e);
+    if (t == 0) ref[(uint64_t)u * lay.nseg + seg] = model ? total : INFINITY;
+}
+
+__global__ __launch_bounds__(kMaxA) void k_model_bias_errors(Layout lay, const co3_gennorm_params *__restrict__ params,
+                                                             const double *__restrict__ bounds,
+                                                             const double *__restrict__ ref, double *__restrict__ errors)
+{
+    __shared__ double s_red[kMaxA];
+    const uint32_t cand = blockIdx.x, seg = blockIdx.y, u = blockIdx.z, t = threadIdx.x;
+    const uint64_t pair = (uint64_t)u * lay.nseg + seg;
+    const co3_gennorm_params p = params[pair];
+    const bool model = p.alpha > 0.0 && p.beta > 0.0;
+    // uniform over the workgroup: a candidate whose lower bound lies above the reference error cannot win or tie
+    if (!model || bounds[pair * kBiasSlots + cand] > ref[pair] * (1.0 + kBiasPrune)) {
+        if (t == 0) errors[pair * kBiasSlots + cand] = INFINITY;
+        return;
+    }
+    double e = 0.0;
+    if (t < lay.A)
+        e = sq_error_of_symbol(t, lay.E, lay.M, bias_min_supported(lay.E) + (int)cand, p.mu, p.alpha, p.beta);
+    const double total = bias_fold(s_red, t, e);
+    if (t == 0) errors[pair * kBiasSlots + cand] = total;
 }
 
 __global__ __launch_bounds__(64) void k_model_bias_pick(Layout lay, const double *__restrict__ errors,
@@ -217,7 +284,8 @@ __global__ __launch_bounds__(64) void k_model_bias_pick(Layout lay, const double
     if (error_out) error_out[i] = best_err;
 }
 
-size_t bias_workspace_bytes(const Layout &lay) { return (size_t)lay.U * lay.nseg * kBiasSlots * sizeof(double) + 256; }
+// errors and bounds per candidate, reference error per pair
+size_t bias_workspace_bytes(const Layout &lay) { return (size_t)lay.U * lay.nseg * (2 * kBiasSlots + 1) * sizeof(double) + 256; }
 
 hipError_t launch_model_bias(const Layout &lay, const co3_gennorm_params *params, int32_t *bias, double *error,
                              double *errors_ws, hipStream_t s)
@@ -225,9 +293,12 @@ hipError_t launch_model_bias(const Layout &lay, const co3_gennorm_params *params
     if (lay.U == 0) return hipSuccess;
     const int ncand = kBiasMax - bias_min_supported(lay.E) + 1;
     ProfScope prof(K_MODEL_BIAS, s);
-    hipLaunchKernelGGL(k_model_bias_errors, dim3((uint32_t)ncand, lay.nseg, lay.U), dim3(kMaxA), 0, s, lay, params,
-                       errors_ws);
     const uint64_t pairs = (uint64_t)lay.U * lay.nseg;
+    double *bounds = errors_ws + pairs * kBiasSlots, *ref = bounds + pairs * kBiasSlots;
+    hipLaunchKernelGGL(k_model_bias_bounds, dim3(lay.nseg, lay.U), dim3(kMaxA), 0, s, lay, params, bounds);
+    hipLaunchKernelGGL(k_model_bias_ref, dim3(lay.nseg, lay.U), dim3(kMaxA), 0, s, lay, params, bounds, ref);
+    hipLaunchKernelGGL(k_model_bias_errors, dim3((uint32_t)ncand, lay.nseg, lay.U), dim3(kMaxA), 0, s, lay, params,
+                       bounds, ref, errors_ws);
     hipLaunchKernelGGL(k_model_bias_pick, dim3((uint32_t)((pairs + 63) / 64)), dim3(64), 0, s, lay, errors_ws, bias,
                        error);
     return hipGetLastError();

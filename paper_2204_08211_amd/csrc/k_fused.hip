@@ -98,6 +98,7 @@ __global__ __launch_bounds__(64 * kCpb, 5) void k_encode_fused(
     __shared__ uint64_t s_e0[kCpb];
     __shared__ uint32_t s_n[kCpb], s_book[kCpb], s_cbits[kCpb];
     __shared__ int32_t s_bias[kCpb];
+    __shared__ float s_gain[kCpb][2];
     __shared__ uint64_t s_prefix;
     __shared__ uint32_t s_ticket, s_stalled;
 
@@ -114,6 +115,7 @@ __global__ __launch_bounds__(64 * kCpb, 5) void k_encode_fused(
         uint64_t e0 = 0;
         uint32_t n = 0, bk = 0;
         int32_t bias = 0;
+        float gn = 1.0f, gi = 1.0f;
         if (t < nck) {
             const uint64_t c = c0 + t;
             const uint32_t seg = fu_find_chunk_segment(lay.segs, lay.nseg, c);
@@ -123,8 +125,10 @@ __global__ __launch_bounds__(64 * kCpb, 5) void k_encode_fused(
             n = left < (uint64_t)kChunk ? (uint32_t)left : (uint32_t)kChunk;
             bk = (lay.per_user_books ? u * lay.books_per_user : 0u) + (uint32_t)sd.book;
             bias = lay.bias[(uint64_t)u * lay.nseg + seg];
+            gn = lay.gain[2 * ((uint64_t)u * lay.nseg + seg)];
+            gi = lay.gain[2 * ((uint64_t)u * lay.nseg + seg) + 1];
         }
-        s_e0[t] = e0; s_n[t] = n; s_book[t] = bk; s_bias[t] = bias;
+        s_e0[t] = e0; s_n[t] = n; s_book[t] = bk; s_bias[t] = bias; s_gain[t][0] = gn; s_gain[t][1] = gi;
     }
     fu_lds_barrier();
 
@@ -137,6 +141,7 @@ __global__ __launch_bounds__(64 * kCpb, 5) void k_encode_fused(
         const uint32_t nk = s_n[wave];
         const int bias = s_bias[wave];
         const QConst qc = make_qconst(lay.E, lay.M, bias);
+        const float gain = s_gain[wave][0], inv_gain = s_gain[wave][1];   // real-valued scale: (1, 1) unless the plan carries one
         const float *gu = g + (uint64_t)u * row_stride + e0;
         const float *mu = m + (uint64_t)u * row_stride + e0;
         float *mo = m_out + (uint64_t)u * row_stride + e0;
@@ -163,10 +168,12 @@ __global__ __launch_bounds__(64 * kCpb, 5) void k_encode_fused(
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float v = __fadd_rn(gv[j], __fmul_rn(gamma, mv[j]));
+                const float y = __fmul_rn(v, gain);
                 uint32_t s, flags;
                 float q;
-                if constexpr (kSR) quantize_stochastic(v, qc, lay.E, lay.M, bias, sign_shift, rw.w[j], s, q, flags);
-                else quantize(v, qc, sign_shift, s, q, flags);
+                if constexpr (kSR) quantize_stochastic(y, qc, lay.E, lay.M, bias, sign_shift, rw.w[j], s, q, flags);
+                else quantize(y, qc, sign_shift, s, q, flags);
+                q = __fmul_rn(q, inv_gain);
                 eo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
                 const uint32_t ok = (valid >> j) & 1u;
                 n_nonfinite += flags & ok;
@@ -284,12 +291,14 @@ __global__ __launch_bounds__(64 * kCpb, 5) void k_encode_fused(
                     const uint32_t j = base + lane + 64u * r;  // < kChunk: base is a multiple of 64 kFuScalar
                     const bool in = j < nk;
                     const float v = __fadd_rn(gs[r], __fmul_rn(gamma, ms[r]));
+                    const float y = __fmul_rn(v, gain);
                     uint32_t s, flags;
                     float q;
                     if constexpr (kSR)
-                        quantize_stochastic(v, qc, lay.E, lay.M, bias, sign_shift,
+                        quantize_stochastic(y, qc, lay.E, lay.M, bias, sign_shift,
                                             element_random_words(e0 + j, u, seed).w[(e0 + j) & 3u], s, q, flags);
-                    else quantize(v, qc, sign_shift, s, q, flags);
+                    else quantize(y, qc, sign_shift, s, q, flags);
+                    q = __fmul_rn(q, inv_gain);
                     if (in) {
                         mo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
                         n_nonfinite += flags & 1u;

@@ -76,6 +76,7 @@ __global__ __launch_bounds__(kQThreads) void k_quantize(
         // whole tile inside one layer: one bias, LDS histogram
         const int bias = lay.bias[(uint64_t)u * lay.nseg + seg];
         const QConst qc = make_qconst(lay.E, lay.M, bias);
+        const float gain = lay.gain[2 * ((uint64_t)u * lay.nseg + seg)], inv_gain = lay.gain[2 * ((uint64_t)u * lay.nseg + seg) + 1];
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
             const uint64_t i = base + (uint64_t)k * (kQThreads * 4) + threadIdx.x * 4;
@@ -86,10 +87,12 @@ __global__ __launch_bounds__(kQThreads) void k_quantize(
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float v = __fadd_rn(gv[k][j], __fmul_rn(gamma, mv[k][j]));
+                const float y = __fmul_rn(v, gain);   // real-valued scale: (1, 1) unless the plan carries one
                 uint32_t s, flags;
                 float q;
-                if constexpr (kSR) quantize_stochastic(v, qc, lay.E, lay.M, bias, sign_shift, rw.w[j], s, q, flags);
-                else quantize(v, qc, sign_shift, s, q, flags);
+                if constexpr (kSR) quantize_stochastic(y, qc, lay.E, lay.M, bias, sign_shift, rw.w[j], s, q, flags);
+                else quantize(y, qc, sign_shift, s, q, flags);
+                q = __fmul_rn(q, inv_gain);
                 eo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
                 n_nonfinite += flags & 1u;
                 n_clamped += (flags >> 1) & 1u;
@@ -121,12 +124,14 @@ __global__ __launch_bounds__(kQThreads) void k_quantize(
             const int bias = lay.bias[(uint64_t)u * lay.nseg + s_i];
             const QConst qe = make_qconst(lay.E, lay.M, bias);
             const float v = __fadd_rn(gu[i], __fmul_rn(gamma, mu[i]));
+            const float y = __fmul_rn(v, lay.gain[2 * ((uint64_t)u * lay.nseg + s_i)]);
             uint32_t s, flags;
             float q;
             if constexpr (kSR)
-                quantize_stochastic(v, qe, lay.E, lay.M, bias, sign_shift, element_random_words(i, u, seed).w[i & 3u], s,
+                quantize_stochastic(y, qe, lay.E, lay.M, bias, sign_shift, element_random_words(i, u, seed).w[i & 3u], s,
                                     q, flags);
-            else quantize(v, qe, sign_shift, s, q, flags);
+            else quantize(y, qe, sign_shift, s, q, flags);
+            q = __fmul_rn(q, lay.gain[2 * ((uint64_t)u * lay.nseg + s_i) + 1]);
             mo[i] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
             n_nonfinite += flags & 1u;
             n_clamped += (flags >> 1) & 1u;

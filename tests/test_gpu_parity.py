@@ -504,3 +504,100 @@ def test_tiny_vectors_both_encoders(d):
     gpu1, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=ref["hist"], single_sweep=True)
     ref1 = gu.oracle_round(kw, g, m, 0.9, weights=ref["hist"])
     gu.compare_round(gpu1, ref1, d, single_sweep=True)
+
+
+# ---- real-valued scale on top of the integer bias (eq. (exp bias) with b in R) --------------------
+
+def _gain_case(single_sweep):
+    import torch
+    from oracle import co3_bias_model as bm
+    from paper_2204_08211_amd import binding as B
+    E, M, U = 4, 3, 3
+    seg_len = [4096 * 2 + 77, 0, 4096 * 3, 1000]
+    seg_book = [0, 1, 1, 0]
+    nseg = len(seg_len)
+    d = sum(seg_len)
+    rng = np.random.default_rng(900 + single_sweep)
+    # per (user, layer): a GenNorm model, its real-valued optimum of eq. (exp bias), split into bias and gain
+    bias = np.zeros((U, nseg), np.int32); gain = np.ones((U, nseg), np.float32); inv_gain = np.ones((U, nseg), np.float32)
+    g = np.empty((U, d), np.float32); m = np.empty((U, d), np.float32)
+    off = 0
+    for k, n in enumerate(seg_len):
+        for u in range(U):
+            beta, alpha = 0.7 + 0.3 * u, 10.0 ** (-3 + 0.5 * k)
+            b, _ = bm.best_real_scale(bm.signed_set(E, M, 7), alpha, beta, lo=-30, hi=10, step=0.25)
+            bias[u, k], gain[u, k], inv_gain[u, k] = bm.split_real_scale(E, b)
+            g[u, off:off + n] = syn.gennorm_numpy(rng, n, beta, alpha)
+            m[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, alpha / 5)
+        off += n
+    assert np.any(gain != 1.0)
+    g[0, :6] = [np.nan, np.inf, -np.inf, 1e30, -1e30, 0.0]
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias, seg_len=seg_len, seg_book=seg_book)
+    gamma = 0.9
+    # the oracle: Algorithm 1 lines 8-10 with the scaled set, then the code of its own histogram
+    sym = np.empty((U, d), np.uint8); m_ref = np.empty_like(g); q_ref = np.empty_like(g)
+    counters = np.zeros(2, np.uint64)
+    hist = np.zeros((2, 256), np.uint64)
+    off = 0
+    for k, n in enumerate(seg_len):
+        for u in range(U):
+            mo, so, qo, cnt = orc.ef_step_gain(g[u, off:off + n], m[u, off:off + n], gamma, E, M, int(bias[u, k]),
+                                               gain[u, k], inv_gain[u, k])
+            sym[u, off:off + n] = so; m_ref[u, off:off + n] = mo; q_ref[u, off:off + n] = qo; counters += cnt
+            orc.histogram(so, 256, hist[seg_book[k]])
+        off += n
+    lens = np.stack([orc.huffman_lengths(hist[b]) for b in range(2)])
+    codes = np.stack([orc.canonical_codes(lens[b]) for b in range(2)])
+    avg_ref = orc.aggregate_gain(sym, seg_len, bias, inv_gain, E, M)
+    # the library
+    dev = torch.device("cuda:0")
+    plan = B.Plan(**kw)
+    plan.set_gain(gain, inv_gain)
+    stride = (d + 3) // 4 * 4
+    gt = torch.zeros((U, stride), dtype=torch.float32, device=dev); gt[:, :d] = torch.from_numpy(g).to(dev)
+    mt = torch.zeros((U, stride), dtype=torch.float32, device=dev); mt[:, :d] = torch.from_numpy(m).to(dev)
+    buf = B.RoundBuffers(plan, dev, max_code_len=32)
+    if single_sweep:
+        books = B.co3_build_codebook(E, M, plan.num_books, hist)
+        B.co3_encode(plan, books, gt, mt, mt, gamma, buf, mode=B.BOOK_FIXED, single_sweep=True)
+    else:
+        books = B.co3_build_codebook(E, M, plan.num_books, None)
+        B.co3_encode(plan, books, gt, mt, mt, gamma, buf, mode=B.BOOK_EMPIRICAL)
+    qd = torch.full((U, stride), float("nan"), dtype=torch.float32, device=dev)
+    symd = torch.full((plan.symbols_bytes,), 255, dtype=torch.uint8, device=dev)
+    avg = torch.full((d,), float("nan"), dtype=torch.float32, device=dev)
+    B.co3_decode(plan, books, buf, symbols=symd, q=qd)
+    B.co3_ps_aggregate(plan, books, buf, avg)
+    torch.cuda.synchronize()
+    gu.assert_bits_equal(mt[:, :d].cpu().numpy(), m_ref, "memory m'")
+    if not single_sweep:
+        gu.assert_bits_equal(buf.symbols_2d().cpu().numpy(), sym, "symbols")
+        gu.assert_bits_equal(buf.hist.cpu().numpy().view(np.uint64), hist, "histogram")
+    for b in range(2):
+        lb, cb = books.export(b)
+        assert np.array_equal(lb, lens[b]) and np.array_equal(cb, codes[b])
+    for u in range(U):
+        r = orc.pack(sym[u], seg_len, seg_book, lens, codes)
+        nw = int(r["chunk_offset"][-1]) // 32
+        gu.assert_bits_equal(buf.words[u, :nw].cpu().numpy().view(np.uint32), r["words"][:nw], f"bitstream of user {u}")
+    gu.assert_bits_equal(symd[:U * plan.sym_stride].view(U, plan.sym_stride)[:, :d].cpu().numpy(), sym, "decoded symbols")
+    gu.assert_bits_equal(qd[:, :d].cpu().numpy(), q_ref, "decoded values")
+    gu.assert_bits_equal(avg.cpu().numpy(), avg_ref, "PS average")
+    st = buf.status.cpu().numpy()
+    assert int(st[0]) == int(counters[0]) == 3 and int(st[1]) == int(counters[1])
+    # not defined together with the stochastic conversion; and switching the scale off restores the plain step
+    with pytest.raises(B.Co3Error):
+        B.co3_encode(plan, books, gt, mt, mt, gamma, buf, mode=B.BOOK_FIXED, single_sweep=True, stochastic_seed=1)
+    plan.set_gain(None, None)
+    mt[:, :d] = torch.from_numpy(m).to(dev)
+    B.co3_encode(plan, books, gt, mt, mt, gamma, buf, mode=B.BOOK_EMPIRICAL)
+    torch.cuda.synchronize()
+    n0 = seg_len[0]
+    mo, so, _, _ = orc.ef_step(g[1, :n0], m[1, :n0], gamma, E, M, int(bias[1, 0]), want_q=False)
+    gu.assert_bits_equal(mt[1, :n0].cpu().numpy(), mo, "memory m' with the scale switched off")
+    gu.assert_bits_equal(buf.symbols_2d()[1, :n0].cpu().numpy(), so, "symbols with the scale switched off")
+
+
+@pytest.mark.parametrize("single_sweep", [False, True])
+def test_real_valued_scale_both_encoders(single_sweep):
+    _gain_case(single_sweep)
