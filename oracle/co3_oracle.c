@@ -47,6 +47,9 @@
  *       mapping): the upper neighbour with probability (|v| - lo) / (hi - lo), by an
  *       integer dither from Philox4x32-10; details at co3o_ef_step_sr.
  *
+ *   R17 alphabets wider than one byte (1 + exp + mant up to 12 bits): the same steps with symbols
+ *       stored in 16-bit words (functions with the suffix _w); nothing else changes.
+ *
  * Parity pins (tests/, marker "not gpu"): grid against the sets M and E printed
  * in Sec. V-B; nearest-value brute force with exact rationals; IEEE half,
  * bfloat16 and float8-e5m2 casts of NumPy / PyTorch as special cases; error
@@ -66,6 +69,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#define CO3O_MAX_A 4096          /* symbols of the widest alphabet (1 + exp + mant = 12 bits) */
 #define CO3O_CHUNK 4096u
 #define CO3O_SUB 64u
 #define CO3O_SUBS_PER_CHUNK (CO3O_CHUNK / CO3O_SUB)
@@ -79,6 +83,16 @@ enum {
     CO3O_ERR_CORRUPT = -5,
     CO3O_ERR_NOCODE = -7
 };
+
+/* Symbols are stored in bytes, or (suffix _w) in 16-bit words.               */
+static inline uint32_t sym_get(const void *sym, int wide, uint64_t i)
+{
+    return wide ? ((const uint16_t *)sym)[i] : ((const uint8_t *)sym)[i];
+}
+static inline void sym_put(void *sym, int wide, uint64_t i, uint32_t s)
+{
+    if (wide) ((uint16_t *)sym)[i] = (uint16_t)s; else ((uint8_t *)sym)[i] = (uint8_t)s;
+}
 
 /* ------------------------------------------------------------------------- */
 /* Representative set X (Sec. V-B).                                           */
@@ -203,13 +217,13 @@ int co3o_quantize_wide(const float *v, uint64_t n, int exp_bits, int mant_bits,
 /* counters[0] += NaN/Inf inputs, counters[1] += finite clamped inputs.       */
 /* m_out may alias m.  q_out may be NULL.                                     */
 /* ------------------------------------------------------------------------- */
-int co3o_ef_step(const float *g, const float *m, uint64_t n, float gamma,
-                 int exp_bits, int mant_bits, int bias,
-                 float *m_out, uint8_t *sym, float *q_out, uint64_t *counters)
+static int ef_step_any(const float *g, const float *m, uint64_t n, float gamma,
+                       int exp_bits, int mant_bits, int bias,
+                       float *m_out, void *sym, int wide, float *q_out, uint64_t *counters)
 {
-    if (1 + exp_bits + mant_bits > 8) return CO3O_ERR_FORMAT;
+    if (1 + exp_bits + mant_bits > (wide ? 12 : 8)) return CO3O_ERR_FORMAT;
     int nmag = co3o_num_magnitudes(exp_bits, mant_bits);
-    double mag[256];
+    static double mag[CO3O_MAX_A];
     int rc = co3o_grid(exp_bits, mant_bits, bias, mag);
     if (rc < 0) return rc;
     for (uint64_t i = 0; i < n; ++i) {
@@ -220,11 +234,25 @@ int co3o_ef_step(const float *g, const float *m, uint64_t n, float gamma,
         volatile float err = v - q;           /* fl32(v - q)                 */
         if (fl & 1) err = 0.0f;               /* R4                          */
         if (counters) { counters[0] += (fl & 1); counters[1] += (fl >> 1) & 1; }
-        sym[i] = (uint8_t)c;
+        sym_put(sym, wide, i, c);
         m_out[i] = err;
         if (q_out) q_out[i] = q;
     }
     return CO3O_OK;
+}
+
+int co3o_ef_step(const float *g, const float *m, uint64_t n, float gamma,
+                 int exp_bits, int mant_bits, int bias,
+                 float *m_out, uint8_t *sym, float *q_out, uint64_t *counters)
+{
+    return ef_step_any(g, m, n, gamma, exp_bits, mant_bits, bias, m_out, sym, 0, q_out, counters);
+}
+
+int co3o_ef_step_w(const float *g, const float *m, uint64_t n, float gamma,
+                   int exp_bits, int mant_bits, int bias,
+                   float *m_out, uint16_t *sym, float *q_out, uint64_t *counters)
+{
+    return ef_step_any(g, m, n, gamma, exp_bits, mant_bits, bias, m_out, sym, 1, q_out, counters);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -357,15 +385,19 @@ void co3o_histogram(const uint8_t *sym, uint64_t n, uint64_t *hist)
 {
     for (uint64_t i = 0; i < n; ++i) hist[sym[i]] += 1;
 }
+void co3o_histogram_w(const uint16_t *sym, uint64_t n, uint64_t *hist)
+{
+    for (uint64_t i = 0; i < n; ++i) hist[sym[i]] += 1;
+}
 
 /* ------------------------------------------------------------------------- */
 /* Huffman code for integer weights (R6).                                     */
 /* ------------------------------------------------------------------------- */
 int co3o_huffman_lengths(const uint64_t *w, int A, uint8_t *len)
 {
-    if (A < 1 || A > 256) return CO3O_ERR_ARG;
+    if (A < 1 || A > CO3O_MAX_A) return CO3O_ERR_ARG;
     /* node store: leaves 0..A-1, internal nodes A.. in creation order       */
-    uint64_t weight[512]; int parent[512]; int alive[512];
+    static uint64_t weight[2 * CO3O_MAX_A]; static int parent[2 * CO3O_MAX_A]; static int alive[2 * CO3O_MAX_A];
     int n_active = 0, only = -1;
     uint64_t total = 0;
     for (int s = 0; s < A; ++s) {
@@ -410,7 +442,8 @@ int co3o_huffman_lengths(const uint64_t *w, int A, uint8_t *len)
 /* Canonical codes from lengths (R6): symbols with length 0 have no code.     */
 int co3o_canonical_codes(const uint8_t *len, int A, uint64_t *code)
 {
-    int order[256]; int n = 0;
+    static int order[CO3O_MAX_A]; int n = 0;
+    if (A < 1 || A > CO3O_MAX_A) return CO3O_ERR_ARG;
     for (int s = 0; s < A; ++s) { code[s] = 0; if (len[s]) order[n++] = s; }
     for (int i = 1; i < n; ++i) {             /* insertion sort by (len, sym) */
         int s = order[i], j = i - 1;
@@ -457,10 +490,10 @@ uint64_t co3o_num_chunks(int nseg, const uint64_t *seg_len)
  * words[cap_words] is cleared and written; chunk_offset[nchunks+1] (bits),
  * sub_bits[nchunks*64] and *payload_bits (= r, the sum of codeword lengths)
  * are outputs.                                                               */
-int co3o_pack(const uint8_t *sym, int nseg, const uint64_t *seg_len,
-              const int32_t *seg_book, const uint8_t *len, const uint64_t *code,
-              int A, uint32_t *words, uint64_t cap_words,
-              uint64_t *chunk_offset, uint16_t *sub_bits, uint64_t *payload_bits)
+static int pack_any(const void *sym, int wide, int nseg, const uint64_t *seg_len,
+                    const int32_t *seg_book, const uint8_t *len, const uint64_t *code,
+                    int A, uint32_t *words, uint64_t cap_words,
+                    uint64_t *chunk_offset, uint16_t *sub_bits, uint64_t *payload_bits)
 {
     memset(words, 0, cap_words * sizeof(uint32_t));
     uint64_t pos = 0, payload = 0, chunk = 0, elem = 0;
@@ -477,7 +510,8 @@ int co3o_pack(const uint8_t *sym, int nseg, const uint64_t *seg_len,
                 uint64_t start = pos;
                 uint64_t j0 = (uint64_t)sc * CO3O_SUB;
                 for (uint64_t j = j0; j < j0 + CO3O_SUB && j < n_in_chunk; ++j) {
-                    uint8_t s = sym[elem + c0 + j];
+                    uint32_t s = sym_get(sym, wide, elem + c0 + j);
+                    if ((int)s >= A) { rc = CO3O_ERR_NOCODE; continue; }
                     int l = L[s];
                     if (l == 0) { rc = CO3O_ERR_NOCODE; continue; }
                     if (pos + (uint64_t)l > cap_words * 32) return CO3O_ERR_CAPACITY;
@@ -496,18 +530,36 @@ int co3o_pack(const uint8_t *sym, int nseg, const uint64_t *seg_len,
     return rc;
 }
 
+int co3o_pack(const uint8_t *sym, int nseg, const uint64_t *seg_len,
+              const int32_t *seg_book, const uint8_t *len, const uint64_t *code,
+              int A, uint32_t *words, uint64_t cap_words,
+              uint64_t *chunk_offset, uint16_t *sub_bits, uint64_t *payload_bits)
+{
+    return pack_any(sym, 0, nseg, seg_len, seg_book, len, code, A, words, cap_words, chunk_offset, sub_bits,
+                    payload_bits);
+}
+int co3o_pack_w(const uint16_t *sym, int nseg, const uint64_t *seg_len,
+                const int32_t *seg_book, const uint8_t *len, const uint64_t *code,
+                int A, uint32_t *words, uint64_t cap_words,
+                uint64_t *chunk_offset, uint16_t *sub_bits, uint64_t *payload_bits)
+{
+    return pack_any(sym, 1, nseg, seg_len, seg_book, len, code, A, words, cap_words, chunk_offset, sub_bits,
+                    payload_bits);
+}
+
 /* Invert co3o_pack: walk the code tree bit by bit.  Reads nothing outside
  * words[0..n_words).                                                         */
-int co3o_unpack(const uint32_t *words, uint64_t n_words, int nseg,
-                const uint64_t *seg_len, const int32_t *seg_book,
-                const uint8_t *len, const uint64_t *code, int A,
-                const uint64_t *chunk_offset, const uint16_t *sub_bits,
-                uint8_t *sym)
+static int unpack_any(const uint32_t *words, uint64_t n_words, int nseg,
+                      const uint64_t *seg_len, const int32_t *seg_book,
+                      const uint8_t *len, const uint64_t *code, int A,
+                      const uint64_t *chunk_offset, const uint16_t *sub_bits,
+                      void *sym, int wide)
 {
     uint64_t chunk = 0, elem = 0;
     /* tree of the current book: child[node][bit]; >= 0 internal, -1 none,
      * leaves stored as -(2 + symbol)                                         */
-    static int child[2 * 64 * 256 + 2][2];
+    static int child[64 * CO3O_MAX_A + 2][2];
+    if (A > CO3O_MAX_A) return CO3O_ERR_ARG;
     for (int k = 0; k < nseg; ++k) {
         const uint8_t *L = len + (size_t)seg_book[k] * A;
         const uint64_t *C = code + (size_t)seg_book[k] * A;
@@ -522,6 +574,7 @@ int co3o_unpack(const uint32_t *words, uint64_t n_words, int nseg,
                     child[node][bit] = -(2 + s);
                 } else {
                     if (child[node][bit] == -1) {
+                        if (n_nodes >= 64 * CO3O_MAX_A + 2) return CO3O_ERR_ARG;
                         child[n_nodes][0] = child[n_nodes][1] = -1;
                         child[node][bit] = n_nodes++;
                     } else if (child[node][bit] < -1) return CO3O_ERR_ARG;
@@ -544,7 +597,7 @@ int co3o_unpack(const uint32_t *words, uint64_t n_words, int nseg,
                         if (pos >= end) return CO3O_ERR_CORRUPT;
                         int nx = child[node][get_bit(words, pos++)];
                         if (nx == -1) return CO3O_ERR_CORRUPT;
-                        if (nx < -1) { sym[elem + c0 + j] = (uint8_t)(-nx - 2); break; }
+                        if (nx < -1) { sym_put(sym, wide, elem + c0 + j, (uint32_t)(-nx - 2)); break; }
                         node = nx;
                     }
                 }
@@ -561,10 +614,27 @@ int co3o_unpack(const uint32_t *words, uint64_t n_words, int nseg,
 /* PS side, eq. (aggregate hat) without the learning rate: the average of the */
 /* users' reconstructed gradients (R8).  sym is [U][d] (row stride d), bias   */
 /* is [U][nseg].                                                              */
+int co3o_unpack(const uint32_t *words, uint64_t n_words, int nseg,
+                const uint64_t *seg_len, const int32_t *seg_book,
+                const uint8_t *len, const uint64_t *code, int A,
+                const uint64_t *chunk_offset, const uint16_t *sub_bits,
+                uint8_t *sym)
+{
+    return unpack_any(words, n_words, nseg, seg_len, seg_book, len, code, A, chunk_offset, sub_bits, sym, 0);
+}
+int co3o_unpack_w(const uint32_t *words, uint64_t n_words, int nseg,
+                  const uint64_t *seg_len, const int32_t *seg_book,
+                  const uint8_t *len, const uint64_t *code, int A,
+                  const uint64_t *chunk_offset, const uint16_t *sub_bits,
+                  uint16_t *sym)
+{
+    return unpack_any(words, n_words, nseg, seg_len, seg_book, len, code, A, chunk_offset, sub_bits, sym, 1);
+}
+
 /* ------------------------------------------------------------------------- */
-int co3o_aggregate(const uint8_t *sym, uint32_t U, uint64_t d, int nseg,
-                   const uint64_t *seg_len, const int32_t *bias,
-                   int exp_bits, int mant_bits, float *out)
+static int aggregate_any(const void *sym, int wide, uint32_t U, uint64_t d, int nseg,
+                         const uint64_t *seg_len, const int32_t *bias,
+                         int exp_bits, int mant_bits, float *out)
 {
     if (U == 0) return CO3O_ERR_ARG;
     double inv_u = 1.0 / (double)U;
@@ -573,13 +643,25 @@ int co3o_aggregate(const uint8_t *sym, uint32_t U, uint64_t d, int nseg,
         for (uint64_t i = elem; i < elem + seg_len[k]; ++i) {
             double acc = 0.0;
             for (uint32_t u = 0; u < U; ++u)
-                acc += co3o_value(sym[(size_t)u * d + i], exp_bits, mant_bits,
+                acc += co3o_value(sym_get(sym, wide, (size_t)u * d + i), exp_bits, mant_bits,
                                   bias[(size_t)u * nseg + k]);
             out[i] = (float)(acc * inv_u);
         }
         elem += seg_len[k];
     }
     return (elem == d) ? CO3O_OK : CO3O_ERR_ARG;
+}
+int co3o_aggregate(const uint8_t *sym, uint32_t U, uint64_t d, int nseg,
+                   const uint64_t *seg_len, const int32_t *bias,
+                   int exp_bits, int mant_bits, float *out)
+{
+    return aggregate_any(sym, 0, U, d, nseg, seg_len, bias, exp_bits, mant_bits, out);
+}
+int co3o_aggregate_w(const uint16_t *sym, uint32_t U, uint64_t d, int nseg,
+                     const uint64_t *seg_len, const int32_t *bias,
+                     int exp_bits, int mant_bits, float *out)
+{
+    return aggregate_any(sym, 1, U, d, nseg, seg_len, bias, exp_bits, mant_bits, out);
 }
 
 /* The same average when the users' representatives carry a real-valued scale */

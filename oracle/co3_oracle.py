@@ -39,6 +39,11 @@ def _p(a, t):
     return a.ctypes.data_as(C.POINTER(t))
 
 
+def is_wide(E, M):
+    """Alphabets of more than 8 bits keep their symbols in 16-bit words (up to 12 bits are provided for)."""
+    return 1 + E + M > 8
+
+
 def num_magnitudes(E, M):
     return int(lib().co3o_num_magnitudes(C.c_int(E), C.c_int(M)))
 
@@ -80,13 +85,15 @@ def ef_step(g, m, gamma, E, M, bias, want_q=True):
     m = np.ascontiguousarray(m, dtype=np.float32)
     assert g.shape == m.shape and g.ndim == 1
     m_out = np.empty_like(g)
-    sym = np.empty(g.shape, dtype=np.uint8)
+    wide = is_wide(E, M)                      # alphabets above 8 bits: symbols in 16-bit words
+    sym = np.empty(g.shape, dtype=np.uint16 if wide else np.uint8)
     q = np.empty_like(g) if want_q else None
     counters = np.zeros(2, dtype=np.uint64)
-    rc = lib().co3o_ef_step(_p(g, C.c_float), _p(m, C.c_float), C.c_uint64(g.size),
-                            C.c_float(np.float32(gamma)), C.c_int(E), C.c_int(M), C.c_int(bias),
-                            _p(m_out, C.c_float), _p(sym, C.c_uint8),
-                            _p(q, C.c_float) if want_q else None, _p(counters, C.c_uint64))
+    fn = lib().co3o_ef_step_w if wide else lib().co3o_ef_step
+    rc = fn(_p(g, C.c_float), _p(m, C.c_float), C.c_uint64(g.size),
+            C.c_float(np.float32(gamma)), C.c_int(E), C.c_int(M), C.c_int(bias),
+            _p(m_out, C.c_float), sym.ctypes.data_as(C.c_void_p),
+            _p(q, C.c_float) if want_q else None, _p(counters, C.c_uint64))
     if rc < 0:
         raise ValueError(f"co3o_ef_step: {rc}")
     return m_out, sym, q, counters
@@ -157,11 +164,15 @@ def ef_step_sr(g, m, gamma, E, M, bias, user, elem0, seed, want_q=True):
 
 
 def histogram(sym, A, hist=None):
-    sym = np.ascontiguousarray(sym, dtype=np.uint8)
+    wide = A > 256
+    sym = np.ascontiguousarray(sym, dtype=np.uint16 if wide else np.uint8)
     if hist is None:
         hist = np.zeros(A, dtype=np.uint64)
-    assert hist.size >= 256 or int(sym.max(initial=0)) < hist.size
-    lib().co3o_histogram(_p(sym, C.c_uint8), C.c_uint64(sym.size), _p(hist, C.c_uint64))
+    assert int(sym.max(initial=0)) < hist.size
+    if wide:
+        lib().co3o_histogram_w(_p(sym, C.c_uint16), C.c_uint64(sym.size), _p(hist, C.c_uint64))
+    else:
+        lib().co3o_histogram(_p(sym, C.c_uint8), C.c_uint64(sym.size), _p(hist, C.c_uint64))
     return hist
 
 
@@ -195,7 +206,8 @@ def num_chunks(seg_len):
 def pack(sym, seg_len, seg_book, lens, codes, cap_words=None):
     """h_Hf of Sec. IV-A (ii) for one user: returns dict(words, chunk_offset, sub_bits,
     payload_bits, rc)."""
-    sym = np.ascontiguousarray(sym, dtype=np.uint8)
+    wide = lens.shape[-1] > 256
+    sym = np.ascontiguousarray(sym, dtype=np.uint16 if wide else np.uint8)
     seg_len = np.ascontiguousarray(seg_len, dtype=np.uint64)
     seg_book = np.ascontiguousarray(seg_book, dtype=np.int32)
     lens = np.ascontiguousarray(lens, dtype=np.uint8).reshape(-1, lens.shape[-1])
@@ -209,7 +221,7 @@ def pack(sym, seg_len, seg_book, lens, codes, cap_words=None):
     chunk_offset = np.zeros(nch + 1, dtype=np.uint64)
     sub_bits = np.zeros(nch * SUBS_PER_CHUNK, dtype=np.uint16)
     payload = C.c_uint64(0)
-    rc = lib().co3o_pack(_p(sym, C.c_uint8), C.c_int(seg_len.size), _p(seg_len, C.c_uint64),
+    rc = (lib().co3o_pack_w if wide else lib().co3o_pack)(sym.ctypes.data_as(C.c_void_p), C.c_int(seg_len.size), _p(seg_len, C.c_uint64),
                          _p(seg_book, C.c_int32), _p(lens, C.c_uint8), _p(codes, C.c_uint64),
                          C.c_int(A), _p(words, C.c_uint32), C.c_uint64(cap_words),
                          _p(chunk_offset, C.c_uint64), _p(sub_bits, C.c_uint16), C.byref(payload))
@@ -226,24 +238,27 @@ def unpack(words, d, seg_len, seg_book, lens, codes, chunk_offset, sub_bits):
     codes = np.ascontiguousarray(codes, dtype=np.uint64).reshape(-1, codes.shape[-1])
     chunk_offset = np.ascontiguousarray(chunk_offset, dtype=np.uint64)
     sub_bits = np.ascontiguousarray(sub_bits, dtype=np.uint16)
-    sym = np.zeros(d, dtype=np.uint8)
-    rc = lib().co3o_unpack(_p(words, C.c_uint32), C.c_uint64(words.size), C.c_int(seg_len.size),
-                           _p(seg_len, C.c_uint64), _p(seg_book, C.c_int32), _p(lens, C.c_uint8),
-                           _p(codes, C.c_uint64), C.c_int(lens.shape[1]),
-                           _p(chunk_offset, C.c_uint64), _p(sub_bits, C.c_uint16), _p(sym, C.c_uint8))
+    wide = lens.shape[1] > 256
+    sym = np.zeros(d, dtype=np.uint16 if wide else np.uint8)
+    rc = (lib().co3o_unpack_w if wide else lib().co3o_unpack)(
+        _p(words, C.c_uint32), C.c_uint64(words.size), C.c_int(seg_len.size),
+        _p(seg_len, C.c_uint64), _p(seg_book, C.c_int32), _p(lens, C.c_uint8),
+        _p(codes, C.c_uint64), C.c_int(lens.shape[1]),
+        _p(chunk_offset, C.c_uint64), _p(sub_bits, C.c_uint16), sym.ctypes.data_as(C.c_void_p))
     return int(rc), sym
 
 
 def aggregate(sym, seg_len, bias, E, M):
     """(1/U) sum_u ghat^(u), eq. (aggregate hat); sym is [U, d], bias is [U, nseg]."""
-    sym = np.ascontiguousarray(sym, dtype=np.uint8)
+    wide = is_wide(E, M)
+    sym = np.ascontiguousarray(sym, dtype=np.uint16 if wide else np.uint8)
     U, d = sym.shape
     seg_len = np.ascontiguousarray(seg_len, dtype=np.uint64)
     bias = np.ascontiguousarray(bias, dtype=np.int32).reshape(U, seg_len.size)
     out = np.empty(d, dtype=np.float32)
-    rc = lib().co3o_aggregate(_p(sym, C.c_uint8), C.c_uint32(U), C.c_uint64(d), C.c_int(seg_len.size),
-                              _p(seg_len, C.c_uint64), _p(bias, C.c_int32), C.c_int(E), C.c_int(M),
-                              _p(out, C.c_float))
+    rc = (lib().co3o_aggregate_w if wide else lib().co3o_aggregate)(
+        sym.ctypes.data_as(C.c_void_p), C.c_uint32(U), C.c_uint64(d), C.c_int(seg_len.size),
+        _p(seg_len, C.c_uint64), _p(bias, C.c_int32), C.c_int(E), C.c_int(M), _p(out, C.c_float))
     if rc < 0:
         raise ValueError(f"co3o_aggregate: {rc}")
     return out

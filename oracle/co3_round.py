@@ -27,7 +27,7 @@ def encode_round(g, m, gamma, E, M, seg_len, seg_book, bias, per_user_books=Fals
     def tick(name, t0):
         tm[name] = tm.get(name, 0.0) + time.perf_counter() - t0
 
-    m_new = np.empty_like(g); sym = np.empty((U, d), np.uint8)
+    m_new = np.empty_like(g); sym = np.empty((U, d), np.uint16 if orc.is_wide(E, M) else np.uint8)
     counters = np.zeros(2, np.uint64)
     hist = np.zeros((nbooks, A), np.uint64)
     for u in range(U):                                     # Algorithm 1 lines 8 and 10
@@ -70,7 +70,7 @@ def ps_round(enc, E, M, seg_len, seg_book, bias, per_user_books=False, timings=N
     U = len(enc["words"])
     d = int(sum(seg_len))
     tm = timings if timings is not None else {}
-    sym = np.empty((U, d), np.uint8)
+    sym = np.empty((U, d), np.uint16 if orc.is_wide(E, M) else np.uint8)
     for u in range(U):
         books_u = [(u * enc["bpu"] if per_user_books else 0) + b for b in seg_book]
         t0 = time.perf_counter()
