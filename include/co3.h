@@ -60,7 +60,13 @@ enum {
 
 /* Float format of Q_fp: one sign bit, exp_bits exponent bits, mant_bits mantissa bits
  * (Sec. IV-A (i); the sets M and E of Sec. V-B).  Requires exp_bits >= 2 and
- * 1 + exp_bits + mant_bits <= 8 (a symbol is one byte).                                    */
+ * 1 + exp_bits + mant_bits <= 12.  Up to 8 bits a symbol is one byte.  With 9 to 12 bits ("wide"
+ * alphabets) a symbol is a 16-bit word: every `symbols` buffer below then holds uint16_t (its size is
+ * co3_plan_symbols_bytes() all the same), the code tables have up to 4096 entries and the library
+ * runs simpler, slower kernels that keep them in device memory.  Not provided for wide alphabets:
+ * CO3_ROUND_STOCHASTIC (CO3_ERR_ARG) and the model routines co3_model_weights_device and
+ * co3_model_bias_device (CO3_ERR_FORMAT); a fixed code without a symbol buffer is coded in the same
+ * three steps as with one, the symbols kept in the workspace.                                 */
 typedef struct {
     int32_t exp_bits;
     int32_t mant_bits;
@@ -108,7 +114,8 @@ void co3_plan_destroy(co3_plan *plan);
 uint64_t co3_plan_num_chunks(const co3_plan *plan);     /* chunks per user                  */
 uint32_t co3_plan_num_books(const co3_plan *plan);      /* tables in a matching set         */
 uint32_t co3_plan_alphabet(const co3_plan *plan);       /* A = 2^(1+exp_bits+mant_bits)     */
-/* bytes of the `symbols` buffer of co3_encode_args / co3_decode_args (U*d plus padding)    */
+/* bytes of the `symbols` buffer of co3_encode_args / co3_decode_args: U rows of d symbols, each row
+ * padded to a multiple of 16 symbols, plus 16 symbols; one byte per symbol (two for wide alphabets) */
 size_t co3_plan_symbols_bytes(const co3_plan *plan);
 /* bytes of the `workspace` buffer of co3_encode_args                                       */
 size_t co3_plan_workspace_bytes(const co3_plan *plan);
@@ -210,7 +217,8 @@ typedef struct {
     float gamma;             /* memory-decay coefficient                                     */
     int32_t mode;            /* CO3_BOOK_FIXED or CO3_BOOK_EMPIRICAL                         */
     co3_codebook *books;     /* set with co3_plan_num_books() tables                         */
-    uint8_t *symbols;        /* device, co3_plan_symbols_bytes(): [U][d] symbols (out)       */
+    uint8_t *symbols;        /* device, co3_plan_symbols_bytes(): [U][d] symbols (out);      */
+                             /* uint16_t words for wide alphabets                            */
     uint64_t *hist;          /* device [num_books][A] symbol counts (out; cleared here)      */
                              /* (symbols, hist: both NULL selects the single-sweep encoder)  */
     uint32_t *words;         /* device [U][words_stride] streams (out)                       */
@@ -255,7 +263,8 @@ typedef struct {
     const uint64_t *chunk_offset; /* device [U][num_chunks+1]                                */
     const uint16_t *sub_bits;     /* device [U][num_chunks*64]                               */
     const co3_codebook *books;
-    uint8_t *symbols;             /* device, co3_plan_symbols_bytes(), or NULL (out)         */
+    uint8_t *symbols;             /* device, co3_plan_symbols_bytes(), or NULL (out);        */
+                                  /* uint16_t words for wide alphabets                       */
     float *q;                     /* device [U][q_stride] reconstructed ghat, or NULL (out)  */
     uint64_t q_stride;
     uint64_t *status;

@@ -193,6 +193,7 @@ class Plan:
         self.symbols_bytes = int(lib().co3_plan_symbols_bytes(h))
         self.workspace_bytes = int(lib().co3_plan_workspace_bytes(h))
         self.sym_stride = (self.d + 15) // 16 * 16
+        self.wide = self.A > 256          # alphabets above 8 bits: 16-bit symbols
 
     def set_bias(self, bias, stream=None):
         bias = np.ascontiguousarray(np.broadcast_to(np.asarray(bias, dtype=np.int32), (self.U, self.nseg)))
@@ -346,8 +347,15 @@ class RoundBuffers:
         self.workspace = torch.zeros(plan.workspace_bytes, dtype=torch.uint8, device=dev)
 
     def symbols_2d(self):
-        p = self.plan
-        return self.symbols[:p.U * p.sym_stride].view(p.U, p.sym_stride)[:, :p.d]
+        return symbols_2d(self.plan, self.symbols)
+
+
+def symbols_2d(plan, buf):
+    """[U][d] view of a symbols buffer (uint8 tensor of plan.symbols_bytes): bytes, or 16-bit words for wide alphabets."""
+    import torch
+    if plan.wide:
+        return buf[:2 * plan.U * plan.sym_stride].view(torch.int16).view(plan.U, plan.sym_stride)[:, :plan.d]
+    return buf[:plan.U * plan.sym_stride].view(plan.U, plan.sym_stride)[:, :plan.d]
 
 
 ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libco3.so")
-SOURCES = ["co3_api.cpp", "host_codebook.cpp", "host_gennorm.cpp", "profile.cpp", "k_quantize.hip", "k_codebook.hip", "k_pack.hip", "k_fused.hip", "k_fit.hip", "k_decode.hip"]
+SOURCES = ["co3_api.cpp", "host_codebook.cpp", "host_gennorm.cpp", "profile.cpp", "k_quantize.hip", "k_codebook.hip", "k_pack.hip", "k_fused.hip", "k_fit.hip", "k_decode.hip", "k_wide.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -113,7 +113,7 @@ int co3_plan_create(co3_format format, uint32_t U, uint64_t d, uint32_t nseg, co
 {
     if (!out || !bias || U == 0 || U > 65535u) return CO3_ERR_ARG;  // users are the second grid dimension
     *out = nullptr;
-    if (format.exp_bits < 2 || format.mant_bits < 0 || 1 + format.exp_bits + format.mant_bits > 8)
+    if (format.exp_bits < 2 || format.mant_bits < 0 || 1 + format.exp_bits + format.mant_bits > 12)
         return CO3_ERR_FORMAT;
     co3_segment whole = {0, d, 0, 0};
     if (!segments) { segments = &whole; nseg = 1; }
@@ -160,6 +160,8 @@ int co3_plan_create(co3_format format, uint32_t U, uint64_t d, uint32_t nseg, co
     l.U = U; l.nseg = nseg; l.d = d; l.nchunks = chunks;
     l.E = format.exp_bits; l.M = format.mant_bits;
     l.A = 1u << (1 + format.exp_bits + format.mant_bits);
+    l.wide = l.A > (uint32_t)kMaxA ? 1u : 0u;
+    l.pad0 = 0;
     l.books_per_user = (uint32_t)max_book + 1;
     l.per_user_books = per_user_books ? 1u : 0u;
     l.nbooks = l.books_per_user * (per_user_books ? U : 1u);
@@ -226,13 +228,14 @@ size_t co3_plan_symbols_bytes(const co3_plan *plan)
 {
     if (!plan) return 0;
     const uint64_t stride = (plan->lay.d + 15) & ~(uint64_t)15;
-    return (size_t)(stride * plan->lay.U + 16);
+    return (size_t)(stride * plan->lay.U + 16) * (plan->lay.wide ? 2u : 1u);   // 16-bit symbols above 8 bits
 }
 
 size_t co3_plan_workspace_bytes(const co3_plan *plan)
 {
     if (!plan) return 0;
     const Layout &l = plan->lay;
+    if (l.wide) return wide_workspace_bytes(l);
     const size_t three_step = three_step_workspace_full(l);
     const size_t single_sweep = fused_workspace_bytes(l);
     return three_step > single_sweep ? three_step : single_sweep;
@@ -241,6 +244,7 @@ size_t co3_plan_workspace_bytes(const co3_plan *plan)
 // What co3_encode_static needs of its static array: the encoders' smallest workspace.
 static size_t workspace_bytes_min(const Layout &l)
 {
+    if (l.wide) return wide_workspace_bytes(l);
     const size_t three_step = three_step_workspace_min(l);
     const size_t single_sweep = fused_workspace_bytes(l);
     return three_step > single_sweep ? three_step : single_sweep;
@@ -258,15 +262,23 @@ int co3_build_codebook(co3_format format, uint32_t nbooks, const uint64_t *weigh
 {
     if (!out || nbooks == 0) return CO3_ERR_ARG;
     *out = nullptr;
-    if (format.exp_bits < 2 || format.mant_bits < 0 || 1 + format.exp_bits + format.mant_bits > 8)
+    if (format.exp_bits < 2 || format.mant_bits < 0 || 1 + format.exp_bits + format.mant_bits > 12)
         return CO3_ERR_FORMAT;
     const uint32_t A = 1u << (1 + format.exp_bits + format.mant_bits);
-    std::vector<BookDev> host(nbooks);
-    std::memset(host.data(), 0, sizeof(BookDev) * nbooks);
-    for (auto &b : host)   // a table not built yet has no codes at all
-        for (uint32_t s = 0; s < (uint32_t)kMaxA; ++s) b.fast[s] = kFastSlow << 24;
-    if (weights) {
-        for (uint32_t b = 0; b < nbooks; ++b) {
+    const bool wide = A > (uint32_t)kMaxA;
+    std::vector<BookDev> host(wide ? 0 : nbooks);
+    std::vector<BookWide> host_wide(wide ? nbooks : 0);
+    if (wide) {
+        std::memset(host_wide.data(), 0, sizeof(BookWide) * nbooks);
+        for (uint32_t b = 0; weights && b < nbooks; ++b) {
+            int rc = build_wide_host(weights + (size_t)b * A, A, &host_wide[b]);
+            if (rc != CO3_OK) return rc;
+        }
+    } else {
+        std::memset(host.data(), 0, sizeof(BookDev) * nbooks);
+        for (auto &b : host)   // a table not built yet has no codes at all
+            for (uint32_t s = 0; s < (uint32_t)kMaxA; ++s) b.fast[s] = kFastSlow << 24;
+        for (uint32_t b = 0; weights && b < nbooks; ++b) {
             int rc = build_book_host(weights + (size_t)b * A, A, &host[b]);
             if (rc != CO3_OK) return rc;
         }
@@ -276,9 +288,14 @@ int co3_build_codebook(co3_format format, uint32_t nbooks, const uint64_t *weigh
     cb->format = format;
     cb->nbooks = nbooks;
     cb->A = A;
-    if (hipGetDevice(&cb->device) != hipSuccess ||
-        hipMalloc(&cb->d_books, sizeof(BookDev) * nbooks) != hipSuccess ||
-        hipMemcpy(cb->d_books, host.data(), sizeof(BookDev) * nbooks, hipMemcpyHostToDevice) != hipSuccess) {
+    bool ok = hipGetDevice(&cb->device) == hipSuccess;
+    if (ok && wide)
+        ok = hipMalloc(&cb->d_wide, sizeof(BookWide) * nbooks) == hipSuccess &&
+             hipMemcpy(cb->d_wide, host_wide.data(), sizeof(BookWide) * nbooks, hipMemcpyHostToDevice) == hipSuccess;
+    else if (ok)
+        ok = hipMalloc(&cb->d_books, sizeof(BookDev) * nbooks) == hipSuccess &&
+             hipMemcpy(cb->d_books, host.data(), sizeof(BookDev) * nbooks, hipMemcpyHostToDevice) == hipSuccess;
+    if (!ok) {
         co3_codebook_destroy(cb);
         return CO3_ERR_HIP;
     }
@@ -290,8 +307,11 @@ int co3_build_codebook_device(co3_codebook *books, const uint64_t *weights, uint
 {
     if (!books || !weights || !status) return CO3_ERR_ARG;
     DeviceGuard guard(books->device);
-    hipError_t e = launch_build_books(books->d_books, books->nbooks, books->A, weights, status,
-                                      static_cast<hipStream_t>(stream));
+    hipError_t e = books->d_wide
+                       ? launch_build_books_wide(books->d_wide, books->nbooks, books->A, weights, status,
+                                                 static_cast<hipStream_t>(stream))
+                       : launch_build_books(books->d_books, books->nbooks, books->A, weights, status,
+                                            static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CO3_OK : CO3_ERR_HIP;
 }
 
@@ -300,9 +320,22 @@ int co3_codebook_export(const co3_codebook *books, uint32_t book, uint8_t *len, 
     if (!books || book >= books->nbooks || !len || !code) return CO3_ERR_ARG;
     DeviceGuard guard(books->device);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = CO3_OK;
+    if (books->d_wide) {
+        BookWide *h = new (std::nothrow) BookWide;
+        if (!h) return CO3_ERR_ARG;
+        if (hipMemcpyAsync(h, books->d_wide + book, sizeof(BookWide), hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess)
+            rc = CO3_ERR_HIP;
+        else {
+            std::memcpy(len, h->len, books->A);
+            std::memcpy(code, h->code, sizeof(uint64_t) * books->A);
+        }
+        delete h;
+        return rc;
+    }
     BookDev *h = new (std::nothrow) BookDev;
     if (!h) return CO3_ERR_ARG;
-    int rc = CO3_OK;
     if (hipMemcpyAsync(h, books->d_books + book, sizeof(BookDev), hipMemcpyDeviceToHost, s) != hipSuccess ||
         hipStreamSynchronize(s) != hipSuccess)
         rc = CO3_ERR_HIP;
@@ -321,6 +354,7 @@ void co3_codebook_destroy(co3_codebook *books)
     if (!books) return;
     DeviceGuard guard(books->device);
     if (books->d_books) (void)hipFree(books->d_books);
+    if (books->d_wide) (void)hipFree(books->d_wide);
     delete books;
 }
 
@@ -359,6 +393,11 @@ static int encode_with_workspace(const co3_plan *plan, const co3_encode_args *a,
     args.workspace = workspace;
     args.workspace_bytes = workspace_bytes;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (lay.wide) {   // alphabets above 8 bits: closest representative only; a fixed code without a symbol buffer
+                      // keeps its symbols in the workspace
+        if (a->rounding != CO3_ROUND_NEAREST) return CO3_ERR_ARG;
+        return launch_encode_wide(lay, args, a->books->d_wide, workspace, s) == hipSuccess ? CO3_OK : CO3_ERR_HIP;
+    }
     if (single_sweep)
         return launch_encode_fused(lay, args, a->books->d_books, s) == hipSuccess ? CO3_OK : CO3_ERR_HIP;
     const EncodeWs ws = three_step_workspace(lay, workspace, workspace_bytes);
@@ -412,6 +451,7 @@ int co3_gennorm_fit(const co3_plan *plan, const float *g, const float *m, uint64
 int co3_model_weights_device(const co3_plan *plan, const co3_gennorm_params *params, uint64_t *weights, void *stream)
 {
     if (!plan || !params || !weights) return CO3_ERR_ARG;
+    if (plan->lay.wide) return CO3_ERR_FORMAT;   // the model routines serve alphabets of up to 8 bits
     DeviceGuard guard(plan->device);
     return launch_model_weights(plan->lay, params, weights, static_cast<hipStream_t>(stream)) == hipSuccess
                ? CO3_OK
@@ -424,6 +464,7 @@ int co3_model_bias_device(const co3_plan *plan, const co3_gennorm_params *params
                           void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!plan || !params || !bias || !workspace) return CO3_ERR_ARG;
+    if (plan->lay.wide) return CO3_ERR_FORMAT;
     if (workspace_bytes < bias_workspace_bytes(plan->lay)) return CO3_ERR_CAPACITY;
     if (plan->lay.nseg > 65535u || plan->lay.U > 65535u) return CO3_ERR_ARG;  // grid.y, grid.z
     DeviceGuard guard(plan->device);
@@ -454,8 +495,9 @@ int co3_decode(const co3_plan *plan, const co3_decode_args *a, void *stream)
     int rc = check_books(plan, a->books);
     if (rc != CO3_OK) return rc;
     DeviceGuard guard(plan->device);
-    return launch_decode(lay, *a, a->books->d_books, static_cast<hipStream_t>(stream)) == hipSuccess ? CO3_OK
-                                                                                                  : CO3_ERR_HIP;
+    const hipError_t e = lay.wide ? launch_decode_wide(lay, *a, a->books->d_wide, static_cast<hipStream_t>(stream))
+                                  : launch_decode(lay, *a, a->books->d_books, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CO3_OK : CO3_ERR_HIP;
 }
 
 int co3_ps_aggregate(const co3_plan *plan, const co3_aggregate_args *a, void *stream)
@@ -468,9 +510,9 @@ int co3_ps_aggregate(const co3_plan *plan, const co3_aggregate_args *a, void *st
     int rc = check_books(plan, a->books);
     if (rc != CO3_OK) return rc;
     DeviceGuard guard(plan->device);
-    return launch_aggregate(lay, *a, a->books->d_books, static_cast<hipStream_t>(stream)) == hipSuccess
-               ? CO3_OK
-               : CO3_ERR_HIP;
+    const hipError_t e = lay.wide ? launch_aggregate_wide(lay, *a, a->books->d_wide, static_cast<hipStream_t>(stream))
+                                  : launch_aggregate(lay, *a, a->books->d_books, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CO3_OK : CO3_ERR_HIP;
 }
 
 }  // extern "C"

@@ -12,7 +12,9 @@ namespace co3 {
 constexpr int kChunk = CO3_CHUNK;
 constexpr int kSub = CO3_SUB;
 constexpr int kSubsPerChunk = CO3_SUBS_PER_CHUNK;
-constexpr int kMaxA = 256;          // symbols are bytes
+constexpr int kMaxA = 256;          // alphabets of up to 8 bits: symbols are bytes
+constexpr int kWideMaxA = 4096;     // alphabets of 9 to 12 bits: symbols are 16-bit words (k_wide.hip)
+constexpr int kWideDecBits = 11;    // prefix width of the wide path's direct decode table
 constexpr int kDecBits = 11;        // prefix width of the direct decode table
 constexpr int kDecEntries = 1 << kDecBits;
 constexpr int kLongSlots = 64 - kDecBits;  // lengths kDecBits+1 .. 64
@@ -45,6 +47,19 @@ struct BookDev {
     uint32_t long_len[kLongSlots];
 };
 
+// One Huffman code table of a wide alphabet (9 to 12 symbol bits) as the wide kernels read it.
+struct BookWide {
+    uint64_t code[kWideMaxA];             // right-aligned codeword of each symbol
+    uint64_t first[65];                   // first[L]: first canonical code of length L
+    uint32_t count[65];                   // symbols with length L
+    uint32_t offset[65];                  // index of the first length-L symbol in sorted[]
+    uint32_t dec[1 << kWideDecBits];      // prefix -> (len << 16) | symbol for len <= kWideDecBits, else 0
+    uint16_t sorted[kWideMaxA];           // symbols ordered by (length, symbol)
+    uint8_t len[kWideMaxA];               // codeword length, 0 = no code
+    uint32_t maxlen;
+    uint32_t nactive;
+};
+
 // One layer of the flat vector as the kernels read it.
 struct SegDev {
     uint64_t offset;       // first element
@@ -65,6 +80,8 @@ struct Layout {
     uint32_t books_per_user;   // 1 + max segment.codebook
     uint32_t per_user_books;
     uint32_t nbooks;           // tables in a set
+    uint32_t wide;             // alphabet above 8 bits: 16-bit symbols, the kernels of k_wide.hip
+    uint32_t pad0;
     const SegDev *segs;        // device [nseg + 1] (last entry: offset = d, chunk_start = nchunks)
     const int32_t *bias;       // device [U][nseg]
     const float *gain;         // device [U][nseg][2]: (gain, inv_gain) of the real-valued scale; (1, 1) when unused
@@ -85,7 +102,8 @@ struct co3_codebook {
     co3_format format;
     uint32_t nbooks = 0;
     uint32_t A = 0;
-    co3::BookDev *d_books = nullptr;
+    co3::BookDev *d_books = nullptr;    // byte alphabets
+    co3::BookWide *d_wide = nullptr;    // wide alphabets (exactly one of the two is set)
     int device = 0;
 };
 
@@ -107,6 +125,7 @@ private:
 
 // Host Huffman builder (host_codebook.cpp): fills one table; returns a co3_status.
 int build_book_host(const uint64_t *weights, uint32_t A, BookDev *out);
+int build_wide_host(const uint64_t *weights, uint32_t A, BookWide *out);
 
 // Kernel launchers (one per .hip file).  All return a hipError_t from hipGetLastError().
 struct EncodeWs {
@@ -126,6 +145,9 @@ hipError_t launch_build_books(BookDev *books, uint32_t nbooks, uint32_t A, const
                               uint64_t *status, hipStream_t s);
 hipError_t launch_pack(const Layout &lay, const co3_encode_args &a, const BookDev *books,
                        const EncodeWs &ws, hipStream_t s);
+// exclusive scan of the 32-bit-rounded chunk sizes of every user (k_pack.hip), shared with the wide path
+hipError_t launch_scan_chunks(const Layout &lay, const uint32_t *chunk_bits, uint64_t *chunk_offset,
+                              uint64_t *payload_bits, hipStream_t s);
 // single-sweep encoder for a fixed code (k_fused.hip); its workspace need in bytes
 hipError_t launch_encode_fused(const Layout &lay, const co3_encode_args &a, const BookDev *books, hipStream_t s);
 size_t fused_workspace_bytes(const Layout &lay);
@@ -141,5 +163,14 @@ hipError_t launch_model_bias(const Layout &lay, const co3_gennorm_params *params
 hipError_t launch_decode(const Layout &lay, const co3_decode_args &a, const BookDev *books, hipStream_t s);
 hipError_t launch_aggregate(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
                             hipStream_t s);
+// wide alphabets (k_wide.hip): the same steps with 16-bit symbols and tables in device memory
+size_t wide_workspace_bytes(const Layout &lay);
+hipError_t launch_encode_wide(const Layout &lay, const co3_encode_args &a, BookWide *books, void *workspace,
+                              hipStream_t s);
+hipError_t launch_build_books_wide(BookWide *books, uint32_t nbooks, uint32_t A, const uint64_t *weights,
+                                   uint64_t *status, hipStream_t s);
+hipError_t launch_decode_wide(const Layout &lay, const co3_decode_args &a, const BookWide *books, hipStream_t s);
+hipError_t launch_aggregate_wide(const Layout &lay, const co3_aggregate_args &a, const BookWide *books,
+                                 hipStream_t s);
 
 }  // namespace co3

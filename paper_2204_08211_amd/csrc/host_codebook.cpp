@@ -93,6 +93,84 @@ static void finish_tables(BookDev *b, uint32_t A)
     }
 }
 
+// Huffman code lengths by the two-queue merge (leaves sorted by (weight, symbol), internal nodes in creation
+// order, leaves first on equal weight); len must hold A zeros.
+static int huffman_lengths_host(const uint64_t *w, uint32_t A, uint8_t *len)
+{
+    struct Leaf { uint64_t w; uint32_t s; };
+    std::vector<Leaf> leaves;
+    uint64_t total = 0;
+    for (uint32_t s = 0; s < A; ++s) {
+        if (!w[s]) continue;
+        if (total + w[s] < total || total + w[s] == ~0ull) return CO3_ERR_ARG;
+        total += w[s];
+        leaves.push_back({w[s], s});
+    }
+    const int n = (int)leaves.size();
+    if (n == 0) return CO3_OK;
+    if (n == 1) { len[leaves[0].s] = 1; return CO3_OK; }
+    std::sort(leaves.begin(), leaves.end(),
+              [](const Leaf &x, const Leaf &y) { return x.w != y.w ? x.w < y.w : x.s < y.s; });
+    std::vector<uint64_t> nw(2 * n - 1);
+    std::vector<int> parent(2 * n - 1, -1);
+    for (int i = 0; i < n; ++i) nw[i] = leaves[i].w;
+    int li = 0, ii = n, made = n;
+    for (int step = 0; step < n - 1; ++step) {
+        int pick[2];
+        for (int r = 0; r < 2; ++r) {
+            const bool have_leaf = li < n, have_int = ii < made;
+            if (have_leaf && (!have_int || nw[li] <= nw[ii])) pick[r] = li++;
+            else pick[r] = ii++;
+        }
+        nw[made] = nw[pick[0]] + nw[pick[1]];
+        parent[pick[0]] = made;
+        parent[pick[1]] = made;
+        ++made;
+    }
+    for (int i = 0; i < n; ++i) {
+        int depth = 0;
+        for (int p = parent[i]; p >= 0; p = parent[p]) ++depth;
+        if (depth > CO3_MAX_CODE_LEN) return CO3_ERR_CODELEN;
+        len[leaves[i].s] = (uint8_t)depth;
+    }
+    return CO3_OK;
+}
+
+int build_wide_host(const uint64_t *w, uint32_t A, BookWide *b)
+{
+    std::memset(b, 0, sizeof(*b));
+    int rc = huffman_lengths_host(w, A, b->len);
+    if (rc != CO3_OK) { std::memset(b, 0, sizeof(*b)); return rc; }
+    for (uint32_t s = 0; s < A; ++s) {
+        if (!b->len[s]) continue;
+        b->count[b->len[s]]++;
+        b->nactive++;
+        if (b->len[s] > b->maxlen) b->maxlen = b->len[s];
+    }
+    uint64_t code = 0;
+    uint32_t off = 0;
+    for (int L = 1; L <= 64; ++L) {   // canonical codes: first[L] = (first[L-1] + count[L-1]) << 1
+        code = (code + b->count[L - 1]) << 1;
+        b->first[L] = code;
+        b->offset[L] = off;
+        off += b->count[L];
+    }
+    uint32_t next[65];
+    std::memset(next, 0, sizeof(next));
+    for (uint32_t s = 0; s < A; ++s) {  // ascending symbol within each length
+        const int L = b->len[s];
+        if (!L) continue;
+        const uint32_t rank = next[L]++;
+        b->code[s] = b->first[L] + rank;
+        b->sorted[b->offset[L] + rank] = (uint16_t)s;
+        if (L <= kWideDecBits) {
+            const uint32_t lo = (uint32_t)b->code[s] << (kWideDecBits - L);
+            for (uint32_t i = 0; i < (1u << (kWideDecBits - L)); ++i) b->dec[lo + i] = ((uint32_t)L << 16) | s;
+        }
+    }
+    return CO3_OK;
+}
+
 int build_book_host(const uint64_t *w, uint32_t A, BookDev *b)
 {
     std::memset(b, 0, sizeof(*b));

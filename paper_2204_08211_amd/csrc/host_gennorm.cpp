@@ -37,7 +37,7 @@ extern "C" int co3_bias_from_model(co3_format format, double mu, double alpha, d
 {
     if (!bias || !std::isfinite(mu) || !(alpha >= 0.0) || !(beta >= 0.0)) return CO3_ERR_ARG;
     const int E = format.exp_bits, M = format.mant_bits;
-    if (E < 2 || M < 0 || 1 + E + M > 8) return CO3_ERR_FORMAT;
+    if (E < 2 || M < 0 || 1 + E + M > 12) return CO3_ERR_FORMAT;
     *bias = (1 << (E - 1)) - 1;
     if (error) *error = 0.0;
     if (!(alpha > 0.0) || !(beta > 0.0)) return CO3_OK;

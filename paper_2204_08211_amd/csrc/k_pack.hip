@@ -261,6 +261,16 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_chunks(uint64_t nchunks, 
     if (t == 0) { co[nchunks] = running; payload_bits[u] = payload; }
 }
 
+hipError_t launch_scan_chunks(const Layout &lay, const uint32_t *chunk_bits, uint64_t *chunk_offset,
+                              uint64_t *payload_bits, hipStream_t s)
+{
+    if (lay.U == 0) return hipSuccess;
+    ProfScope prof(K_SCAN, s);
+    hipLaunchKernelGGL(k_scan_chunks, dim3(lay.U), dim3(kScanThreads), 0, s, lay.nchunks, chunk_bits, chunk_offset,
+                       payload_bits);
+    return hipGetLastError();
+}
+
 hipError_t launch_pack(const Layout &lay, const co3_encode_args &a, const BookDev *books, const EncodeWs &ws,
                        hipStream_t s)
 {
@@ -276,11 +286,7 @@ hipError_t launch_pack(const Layout &lay, const co3_encode_args &a, const BookDe
             hipLaunchKernelGGL(k_chunk_bits, dim3(gx, lay.U), dim3(kPkThreads), 0, s, lay, a.symbols, sym_stride, books,
                                ws.chunk_bits);
     }
-    {
-        ProfScope prof(K_SCAN, s);
-        hipLaunchKernelGGL(k_scan_chunks, dim3(lay.U), dim3(kScanThreads), 0, s, lay.nchunks, ws.chunk_bits,
-                           a.chunk_offset, a.payload_bits);
-    }
+    if (launch_scan_chunks(lay, ws.chunk_bits, a.chunk_offset, a.payload_bits, s) != hipSuccess) return hipGetLastError();
     if (lay.nchunks) {
         ProfScope prof(K_PACK, s);
         hipLaunchKernelGGL(k_pack_chunk, dim3(gx, lay.U), dim3(kPkThreads), 0, s, lay, a.symbols, sym_stride, books,

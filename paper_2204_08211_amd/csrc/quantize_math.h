@@ -35,7 +35,7 @@ __device__ __host__ inline QConst make_qconst(int E, int M, int bias)
 // normal fp32 numbers, and the rounding constant C stays finite.
 __device__ __host__ inline bool format_supported(int E, int M, int bias)
 {
-    if (E < 2 || M < 0 || 1 + E + M > 8) return false;
+    if (E < 2 || M < 0 || 1 + E + M > 12) return false;   // up to 8 bits: byte symbols; 9 to 12: 16-bit symbols
     const int emin = 1 - bias;
     const int emax = ((1 << E) - 2) - bias;
     return emin >= -126 && emax <= 100;

@@ -21,6 +21,12 @@ def special_values(E, M, bias, rng, n):
     return rng.choice(pts, n).astype(np.float32)
 
 
+def _sym_numpy(t):
+    """Symbols as the oracle holds them: uint8, or uint16 for alphabets above 8 bits (torch has them as int16)."""
+    a = t.cpu().numpy()
+    return a.view(np.uint16) if a.dtype == np.int16 else a
+
+
 def gpu_round(plan_kwargs, g, m, gamma, mode, weights=None, words_stride=None, max_code_len=32, want_decode=True,
               books=None, buf=None, single_sweep=False, stochastic_seed=None):
     """One encode (+ decode + aggregate) through the binding.  Returns (dict of numpy arrays, objects).
@@ -46,7 +52,7 @@ def gpu_round(plan_kwargs, g, m, gamma, mode, weights=None, words_stride=None, m
                  stochastic_seed=stochastic_seed)
     torch.cuda.synchronize()
     out = dict(
-        m_new=mt[:, :d].cpu().numpy(), sym=buf.symbols_2d().cpu().numpy(),
+        m_new=mt[:, :d].cpu().numpy(), sym=_sym_numpy(buf.symbols_2d()),
         hist=buf.hist.cpu().numpy().view(np.uint64), chunk_offset=buf.chunk_offset.cpu().numpy().view(np.uint64),
         sub_bits=buf.sub_bits.cpu().numpy().view(np.uint16), payload_bits=buf.payload_bits.cpu().numpy().view(np.uint64),
         words=buf.words.cpu().numpy().view(np.uint32), status_encode=buf.status.cpu().numpy().copy(),
@@ -60,7 +66,7 @@ def gpu_round(plan_kwargs, g, m, gamma, mode, weights=None, words_stride=None, m
         avg = torch.full((d,), float("nan"), dtype=torch.float32, device=dev)
         B.co3_ps_aggregate(plan, books, buf, avg)
         torch.cuda.synchronize()
-        out["dec_sym"] = sym2[:U * plan.sym_stride].view(U, plan.sym_stride)[:, :d].cpu().numpy()
+        out["dec_sym"] = _sym_numpy(B.symbols_2d(plan, sym2))
         out["dec_q"] = q[:, :d].cpu().numpy()
         out["avg"] = avg.cpu().numpy()
         out["status"] = buf.status.cpu().numpy().copy()

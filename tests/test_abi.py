@@ -55,9 +55,9 @@ def test_struct_layouts_match_the_header(tmp_path):
 def test_host_side_argument_checks_need_no_gpu():
     L = binding.lib()
     out = ctypes.c_void_p()
-    # exp_bits = 1 makes the exponent set empty; 1 + exp + mant > 8 does not fit a byte
+    # exp_bits = 1 makes the exponent set empty; 1 + exp + mant > 12 is more than the widest alphabet provided for
     assert L.co3_plan_create(binding.Format(1, 2), 1, 10, 0, None, (ctypes.c_int32 * 1)(3), 0, ctypes.byref(out)) == binding.ERR_FORMAT
-    assert L.co3_plan_create(binding.Format(5, 3), 1, 10, 0, None, (ctypes.c_int32 * 1)(3), 0, ctypes.byref(out)) == binding.ERR_FORMAT
+    assert L.co3_plan_create(binding.Format(6, 6), 1, 10, 0, None, (ctypes.c_int32 * 1)(3), 0, ctypes.byref(out)) == binding.ERR_FORMAT
     # bias outside the supported range
     assert L.co3_plan_create(binding.Format(4, 3), 1, 10, 0, None, (ctypes.c_int32 * 1)(200), 0, ctypes.byref(out)) == binding.ERR_FORMAT
     # segments that do not tile [0, d)

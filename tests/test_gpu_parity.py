@@ -601,3 +601,162 @@ def _gain_case(single_sweep):
 @pytest.mark.parametrize("single_sweep", [False, True])
 def test_real_valued_scale_both_encoders(single_sweep):
     _gain_case(single_sweep)
+
+
+# ---- alphabets wider than one byte (9 to 12 symbol bits, 16-bit symbols) ---------------------------------
+
+@pytest.mark.parametrize("E,M,d", [(5, 6, 4096 * 3 + 77), (4, 5, 4095), (3, 5, 1), (5, 3, 4096 * 2)])
+def test_wide_alphabets_both_encoders(E, M, d):
+    import torch
+    from paper_2204_08211_amd import binding as B
+    U = 3
+    A = 1 << (1 + E + M)
+    seg_len = [d] if d < 5000 else [4097, 0, d - 4097 - 63, 63]
+    seg_book = [0] if d < 5000 else [0, 1, 1, 0]
+    nseg = len(seg_len)
+    rng = np.random.default_rng(1200 + E * 10 + M)
+    bias = rng.integers(12, 18, (U, nseg)).astype(np.int32) + (8 if E == 5 else 0)
+    g = np.empty((U, d), np.float32); m = np.empty((U, d), np.float32)
+    off = 0
+    for k, n in enumerate(seg_len):
+        for u in range(U):
+            top = orc.grid(E, M, int(bias[u, k]))[-1]
+            g[u, off:off + n] = syn.gennorm_numpy(rng, n, 0.9, top / 40)
+            m[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, top / 200)
+        off += n
+    if d > 10:
+        g[0, :5] = [np.nan, np.inf, 1e30, -1e30, 0.0]
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias, seg_len=seg_len, seg_book=seg_book)
+    gamma = 0.9
+    ref = gu.oracle_round(kw, g, m, gamma)
+    assert ref["sym"].dtype == np.uint16
+
+    dev = torch.device("cuda:0")
+    plan = B.Plan(**kw)
+    assert plan.wide and plan.A == A
+    stride = (d + 3) // 4 * 4
+    gt = torch.zeros((U, stride), dtype=torch.float32, device=dev); gt[:, :d] = torch.from_numpy(g).to(dev)
+
+    def run(mode, books, single_sweep):
+        mt = torch.zeros((U, stride), dtype=torch.float32, device=dev); mt[:, :d] = torch.from_numpy(m).to(dev)
+        buf = B.RoundBuffers(plan, dev, max_code_len=40)
+        buf.chunk_offset.fill_(-1); buf.sub_bits.fill_(-1); buf.payload_bits.fill_(-1)
+        B.co3_encode(plan, books, gt, mt, mt, gamma, buf, mode=mode, single_sweep=single_sweep)
+        symd = torch.full((plan.symbols_bytes,), 255, dtype=torch.uint8, device=dev)
+        qd = torch.full((U, stride), float("nan"), dtype=torch.float32, device=dev)
+        avg = torch.full((d,), float("nan"), dtype=torch.float32, device=dev)
+        B.co3_decode(plan, books, buf, symbols=symd, q=qd)
+        B.co3_ps_aggregate(plan, books, buf, avg)
+        torch.cuda.synchronize()
+        gu.assert_bits_equal(mt[:, :d].cpu().numpy(), ref["m_new"], "memory m'")
+        if not single_sweep:
+            gu.assert_bits_equal(buf.symbols_2d().cpu().numpy().view(np.uint16), ref["sym"], "symbols")
+            gu.assert_bits_equal(buf.hist.cpu().numpy().view(np.uint64), ref["hist"], "histogram")
+        for b in range(plan.num_books):
+            lb, cb = books.export(b)
+            assert np.array_equal(lb, ref["lens"][b]) and np.array_equal(cb, ref["codes"][b]), f"code table {b}"
+        gu.assert_bits_equal(buf.chunk_offset.cpu().numpy().view(np.uint64), ref["chunk_offset"], "chunk offsets")
+        gu.assert_bits_equal(buf.sub_bits.cpu().numpy().view(np.uint16), ref["sub_bits"], "sub-chunk bits")
+        gu.assert_bits_equal(buf.payload_bits.cpu().numpy().view(np.uint64), ref["payload_bits"], "payload bits")
+        for u, wds in enumerate(ref["words"]):
+            gu.assert_bits_equal(buf.words[u, :wds.size].cpu().numpy().view(np.uint32), wds, f"bitstream of user {u}")
+        gu.assert_bits_equal(B.symbols_2d(plan, symd).cpu().numpy().view(np.uint16), ref["dec_sym"], "decoded symbols")
+        gu.assert_bits_equal(qd[:, :d].cpu().numpy(), ref["dec_q"], "decoded values")
+        gu.assert_bits_equal(avg.cpu().numpy(), ref["avg"], "PS average")
+        st = buf.status.cpu().numpy()
+        assert int(st[0]) == int(ref["counters"][0]) and int(st[1]) == int(ref["counters"][1])
+        assert not st[2:].any()
+
+    # the code built on the device from this round's counts, then the same code built on the host and held
+    books = B.co3_build_codebook(E, M, plan.num_books, None)
+    run(B.BOOK_EMPIRICAL, books, False)
+    held = B.co3_build_codebook(E, M, plan.num_books, ref["hist"])
+    run(B.BOOK_FIXED, held, True)
+    # not provided for wide alphabets
+    mt = torch.zeros((U, stride), dtype=torch.float32, device=dev)
+    buf = B.RoundBuffers(plan, dev, max_code_len=40)
+    with pytest.raises(B.Co3Error):
+        B.co3_encode(plan, held, gt, mt, mt, gamma, buf, mode=B.BOOK_FIXED, single_sweep=True, stochastic_seed=3)
+
+
+def test_wide_long_codes_per_user_tables_and_device_builder():
+    # weights 1, 1, 2, 4, ... on the symbols that occur give codes of up to 61 bits (both halves of the coder's
+    # 64-bit append, the decoder's search by length); a table per user; the device builder on the same weights
+    import torch
+    from paper_2204_08211_amd import binding as B
+    E, M, U, d = 4, 4, 2, 9000
+    A = 1 << (1 + E + M)
+    rng = np.random.default_rng(1301)
+    bias = np.array([[9], [11]], np.int32)
+    w = np.zeros((U, A), np.uint64)
+    g = np.empty((U, d), np.float32)
+    for u in range(U):
+        grid = orc.grid(E, M, int(bias[u, 0]))
+        mags = rng.choice(np.arange(1, grid.size), 31, replace=False)
+        emit = np.concatenate([mags, mags + (A >> 1)])                     # both signs
+        w[u, emit] = np.array([1] + [1 << i for i in range(emit.size - 1)], np.uint64)[rng.permutation(emit.size)]
+        k = rng.choice(mags, d)
+        g[u] = (grid[k] * rng.choice([-1.0, 1.0], d)).astype(np.float32)
+    m = np.zeros_like(g)
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias, per_user_books=True)
+    ref = gu.oracle_round(kw, g, m, 0.9, weights=w)
+    assert ref["lens"].max() >= 57
+    gpu, (plan, books, buf, gt, mt) = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=w, max_code_len=64, want_decode=False)
+    for key, what in [("m_new", "memory"), ("lens", "code lengths"), ("codes", "codes"), ("chunk_offset", "chunk offsets"),
+                      ("sub_bits", "sub-chunk bits"), ("payload_bits", "payload bits")]:
+        gu.assert_bits_equal(gpu[key], ref[key], what)
+    gu.assert_bits_equal(buf.symbols_2d().cpu().numpy().view(np.uint16), ref["sym"], "symbols")
+    for u, wds in enumerate(ref["words"]):
+        gu.assert_bits_equal(gpu["words"][u, :wds.size], wds, f"bitstream of user {u}")
+    symd = torch.zeros(plan.symbols_bytes, dtype=torch.uint8, device="cuda:0")
+    avg = torch.zeros(d, dtype=torch.float32, device="cuda:0")
+    B.co3_decode(plan, books, buf, symbols=symd)
+    B.co3_ps_aggregate(plan, books, buf, avg)
+    torch.cuda.synchronize()
+    gu.assert_bits_equal(B.symbols_2d(plan, symd).cpu().numpy().view(np.uint16), ref["dec_sym"], "decoded symbols")
+    gu.assert_bits_equal(avg.cpu().numpy(), ref["avg"], "PS average")
+    assert int(buf.status[B.STAT_CORRUPT].item()) == 0
+
+    # the device builder gives the host builder's tables; a table holding the sentinel weight is refused and left empty
+    w3 = np.concatenate([w, np.zeros((1, A), np.uint64)]); w3[2, 7] = 1; w3[2, 9] = np.uint64(0xFFFFFFFFFFFFFFFF)
+    dev_books = B.co3_build_codebook(E, M, 3, None)
+    status = torch.zeros(B.STATUS_WORDS, dtype=torch.int64, device="cuda:0")
+    B.co3_build_codebook_device(dev_books, torch.from_numpy(w3.view(np.int64)).to("cuda:0"), status)
+    torch.cuda.synchronize()
+    assert int(status[B.STAT_CODELEN].item()) == 1
+    for b in range(2):
+        lb, cb = dev_books.export(b)
+        assert np.array_equal(lb, ref["lens"][b]) and np.array_equal(cb, ref["codes"][b])
+    lb, cb = dev_books.export(2)
+    assert not lb.any() and not cb.any()
+    with pytest.raises(B.Co3Error):
+        B.co3_build_codebook(E, M, 3, w3)
+
+
+def test_wide_error_paths_capacity_nocode_corrupt():
+    import torch
+    from paper_2204_08211_amd import binding as B
+    E, M, U, d, bias = 5, 4, 1, 20000, 24
+    rng = np.random.default_rng(1302)
+    g = syn.gennorm_numpy(rng, d, 1.0, 2.0 ** -6)[None, :]
+    m = np.zeros_like(g)
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[bias]])
+    ref = gu.oracle_round(kw, g, m, 0.9)
+    need = ref["words"][0].size
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL, words_stride=need - 1500, want_decode=False)
+    assert int(gpu["status_encode"][B.STAT_CAPACITY]) >= 1
+    gu.assert_bits_equal(gpu["chunk_offset"], ref["chunk_offset"], "offsets still exact")
+    w = ref["hist"][0].copy(); victim = np.argsort(w)[-3]; w[victim] = 0
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=w[None, :], want_decode=False)
+    assert int(gpu["status_encode"][B.STAT_NOCODE]) == int(ref["hist"][0][victim])
+    gpu, (plan, books, buf, gt, mt) = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL, want_decode=False)
+    buf.sub_bits[0, 5] += 3
+    buf.words[0, 100:140] = -1
+    buf.chunk_offset[0, 3] += 32 * (1 << 40)          # an index entry far outside the stream buffer
+    buf.status.zero_()
+    out = torch.zeros(d, dtype=torch.float32, device="cuda:0")
+    symd = torch.zeros(plan.symbols_bytes, dtype=torch.uint8, device="cuda:0")
+    B.co3_ps_aggregate(plan, books, buf, out)
+    B.co3_decode(plan, books, buf, symbols=symd)
+    torch.cuda.synchronize()
+    assert int(buf.status[B.STAT_CORRUPT].item()) >= 2
