@@ -9,7 +9,15 @@ coefficient gamma, the excess loss after T iterations, its ratio to that of unco
 the same noise, and the bits per element sent (Sec. VI discusses the
 choice of gamma; Sec. IV-A (iii) the role of the memory).
 
+With --theorem the loop runs in the setting of Theorem 1 of the appendix instead: memory without decay
+(gamma = 1), step size 1 / sqrt(T), the averaged iterate (1/T) sum_t w_t, for a sweep of T.  Printed per format
+and T: the excess loss of the averaged iterate, the right-hand side of the theorem's bound with its three terms
+(mu = min a_i, L = max a_i, G^2 the largest squared gradient norm met, all for the objective summed over
+coordinates), and the mean squared memory per element in units of the fitted GenNorm scale squared beside the
+2^(4 - 2 mant) + 0.3 of the lemma on the quantization error (stated there for a unit-scale gradient).
+
     python -m paper_2204_08211_amd.examples.closed_loop [--d 1000000] [--users 8] [--iters 200]
+    python -m paper_2204_08211_amd.examples.closed_loop --theorem [--d 200000] [--users 8]
 """
 import argparse
 
@@ -28,6 +36,7 @@ def main():
     p.add_argument("--noise", type=float, default=0.1, help="standard deviation of the noise added to every user gradient")
     p.add_argument("--eta", type=float, default=0.2)
     p.add_argument("--stochastic", action="store_true")
+    p.add_argument("--theorem", action="store_true", help="sweep T in the setting of Theorem 1 (gamma 1, eta 1/sqrt(T), averaged iterate)")
     a = p.parse_args()
     dev = torch.device("cuda:0")
     U, d, T = a.users, a.d, a.iters
@@ -45,6 +54,9 @@ def main():
         out[:, :d] = coef[None, :] * (w[None, :] - centre) + a.noise * torch.randn(U, d, device=dev, generator=ng)
 
     g = torch.zeros((U, stride), device=dev)
+    if a.theorem:
+        theorem_sweep(a, dev, coef, centre, loss, gradients, g)
+        return
     w_plain = torch.zeros(d, device=dev)
     for t in range(T):
         gradients(w_plain, t, g)
@@ -78,6 +90,49 @@ def main():
             ex = loss(w) - l_star
             print(f"{'[1,%d,%d]' % (E, M):>10} {gamma:6.2f} {ex:12.3e} {ex / max(l_plain - l_star, 1e-300):22.3f} "
                   f"{bits / (T * U * d):12.3f} {int(st[B.STAT_CLAMPED]):10d}")
+
+
+def theorem_sweep(a, dev, coef, centre, loss, gradients, g):
+    """Theorem 1 (appendix): E L(w_bar_T) - L* <= (|w_0 - w*|^2 + G^2) / sqrt(T) + (mu + 2 L)(2^(4 - 2 mant) + 0.3) / T."""
+    U, d = a.users, a.d
+    stride = g.shape[1]
+    mean_centre = (coef[None, :] * centre).sum(0) / (U * coef)
+    l_star = loss(mean_centre) * d                                # the objective summed over coordinates
+    mu, L = float(coef.min()), float(coef.max())
+    dist0 = float((mean_centre.double() ** 2).sum())               # w_0 = 0
+    print(f"U={U} d={d} noise={a.noise} mu={mu:.3f} L={L:.3f} |w0-w*|^2={dist0:.4e}, gamma=1, eta=1/sqrt(T), refresh every {a.refresh}")
+    print(f"{'format':>10} {'T':>6} {'excess loss':>12} {'bound':>12} {'= dist/sqrtT':>13} {'+ G^2/sqrtT':>12} {'+ quant/T':>10} "
+          f"{'E m^2/alpha^2':>14} {'lemma':>8} {'bit/element':>12}")
+    for E, M in ((2, 1), (3, 0), (4, 3), (5, 2)):
+        for T in (16, 64, 256, 1024):
+            eta = 1.0 / np.sqrt(T)
+            plan = B.Plan(E, M, U, d, [[(1 << (E - 1)) - 1]] * U)
+            books = B.co3_build_codebook(E, M, plan.num_books, None)
+            buf = B.RoundBuffers(plan, dev, max_code_len=64)
+            w = torch.zeros(d, device=dev)
+            w_bar = torch.zeros(d, device=dev, dtype=torch.float64)
+            m = torch.zeros((U, stride), device=dev)
+            bits = 0.0; g2 = 0.0; mem = 0.0
+            for t in range(T):
+                w_bar += w.double() / T
+                g2 = max(g2, float(((coef * (w - mean_centre)).double() ** 2).sum()))
+                gradients(w, t, g)
+                if t % a.refresh == 0:
+                    params = B.co3_gennorm_fit(plan, g, m, 1.0)
+                    B.co3_model_bias_device(plan, params, install=True)
+                    B.co3_build_codebook_device(books, B.co3_model_weights_device(plan, params), buf.status)
+                    alpha2 = float((params[..., 1].double() ** 2).mean())
+                B.co3_encode(plan, books, g, m, m, 1.0, buf, mode=B.BOOK_FIXED, single_sweep=True)
+                B.co3_ps_aggregate(plan, books, buf, None, model=w, eta=eta)
+                bits += float(buf.payload_bits.sum().item())
+                mem += float((m[:, :d].double() ** 2).mean()) / alpha2 / T
+            st = buf.status.cpu().numpy()
+            assert st[B.STAT_NOCODE] == 0 and st[B.STAT_CORRUPT] == 0 and st[B.STAT_STALLED] == 0 and st[B.STAT_CAPACITY] == 0
+            ex = loss(w_bar.float()) * d - l_star
+            lemma = 2.0 ** (4 - 2 * M) + 0.3
+            terms = (dist0 / np.sqrt(T), g2 / np.sqrt(T), (mu + 2 * L) * lemma / T)
+            print(f"{'[1,%d,%d]' % (E, M):>10} {T:6d} {ex:12.4e} {sum(terms):12.4e} {terms[0]:13.4e} {terms[1]:12.4e} {terms[2]:10.3e} "
+                  f"{mem:14.4f} {lemma:8.3f} {bits / (T * U * d):12.3f}")
 
 
 if __name__ == "__main__":
