@@ -116,26 +116,43 @@ __device__ __noinline__ uint32_t long_code(Src src, const DecLds *T, uint32_t po
     return 0u;
 }
 
-// Sequential bit reader of one lane: the word that holds the next bit, the word after it, and the
-// bit's offset in the first.  Consuming at most 32 bits moves on by at most one word.
+// Sequential bit reader of one lane: two consecutive words w0, w1 of the stream, of which the first c bits of
+// w0 (1 <= c <= 32) are consumed; kept is k = 32 - c, so that the next 32 bits are one v_alignbit of (w0, w1) by
+// k.  Consuming at most 32 bits moves on by at most one word.
 template <class Src>
 struct Reader {
     Src src;
-    uint32_t w0, w1;   // word with the next bit, following word
-    uint32_t sh;       // offset of the next bit in w0, 0..31
+    uint32_t w0, w1;   // word with the next bit (or, with k = 0, the word before it), following word
+    uint32_t k;        // 32 - (consumed bits of w0), 0..31
     uint32_t wi;       // index of the word after w1
     __device__ inline void seek(uint32_t pos)
     {
         uint32_t i = pos >> 5;
         i = i < Src::seek_limit ? i : Src::seek_limit;
-        w0 = src.word(i);
-        w1 = src.word(i + 1);
-        wi = i + 2;
-        sh = pos & 31u;
+        const uint32_t sh = pos & 31u;
+        w0 = sh ? src.word(i) : 0u;        // at a word boundary w0 counts as consumed entirely
+        w1 = src.word(sh ? i + 1u : i);
+        wi = sh ? i + 2u : i + 1u;
+        k = (32u - sh) & 31u;
     }
-    __device__ inline uint32_t pos() const { return (wi - 2u) * 32u + sh; }
-    // the next bits left-aligned: at least 33 are valid, zeros follow
-    __device__ inline uint64_t window() const { return (((uint64_t)w0 << 32) | w1) << sh; }
+    __device__ inline uint32_t pos() const { return (wi - 2u) * 32u + (32u - k); }
+    // the next 32 bits
+    __device__ inline uint32_t window32() const { return __builtin_amdgcn_alignbit(w0, w1, k); }
+    // the next 64 bits, `nextw` being word wi
+    __device__ inline uint64_t window64(uint32_t nextw) const
+    {
+        return ((uint64_t)__builtin_amdgcn_alignbit(w0, w1, k) << 32) | __builtin_amdgcn_alignbit(w1, nextw, k);
+    }
+    // L <= 32 bits consumed; `nextw` is word wi
+    __device__ inline void advance(uint32_t L, uint32_t nextw)
+    {
+        const int32_t t = (int32_t)k - (int32_t)L;
+        const bool take = t < 0;
+        k = (uint32_t)t & 31u;
+        w0 = take ? w1 : w0;
+        w1 = take ? nextw : w1;
+        wi += take ? 1u : 0u;
+    }
 };
 
 // The rare part of decode_symbol, for the lanes whose prefix the direct table does not resolve (L == 0 on
@@ -173,33 +190,37 @@ __device__ inline void decode_symbol_long(Reader<Src> &r, const DecLds *T, uint6
 }
 
 // One symbol; `bad` is set if nothing matched.  The common case is one look-up in the direct table and a
-// branch-free advance; the branch to the rare part is taken by the whole wavefront or not at all.
-template <class Src>
-__device__ inline uint32_t decode_symbol(Reader<Src> &r, const DecLds *T, bool &bad)
+// branch-free advance; the branch to the rare part is taken by the whole wavefront or not at all.  Returned is
+// the symbol in bits 0..7; the bits above are not defined (the direct table's entry is passed on as it is).
+// While the two LDS reads of this symbol are in flight the sink may have one of its own for the symbol before
+// (`pend`, element j): Sink::fetch requests it, Sink::commit uses it, and the wavefront waits once for all three.
+template <bool kCommit, class Src, class Sink>
+__device__ inline uint32_t decode_symbol(Reader<Src> &r, const DecLds *T, bool &bad, Sink &sink, int j, uint32_t pend)
 {
-    const uint64_t win = r.window();
-    uint32_t nextw = r.src.next(r.wi);                       // both LDS reads are requested
-    uint32_t e = T->dec[win >> (64 - kDecBits)];             // before either result is needed
-    asm volatile("" : "+v"(nextw), "+v"(e));
-    uint32_t L = e >> 8, s = e & 0xffu;
-    if (__builtin_expect(__any(L == 0u), 0)) decode_symbol_long(r, T, win, L, s, bad);
-    const uint32_t t = r.sh + L;
-    const bool take = t >= 32u;
-    r.sh = t & 31u;
-    r.w0 = take ? r.w1 : r.w0;
-    r.w1 = take ? nextw : r.w1;
-    r.wi += take ? 1u : 0u;
+    const uint32_t win = r.window32();
+    uint32_t nextw = r.src.next(r.wi);                       // all LDS reads are requested
+    uint32_t e = T->dec[win >> (32 - kDecBits)];             // before any result is needed
+    uint32_t tok = kCommit ? sink.fetch(pend) : 0u;
+    asm volatile("" : "+v"(nextw), "+v"(e), "+v"(tok));
+    if (kCommit) sink.commit(j, pend, tok);
+    uint32_t L = e >> 8, s = e;                              // L == 0: e is 0 or 1 + the prefix's second-level table
+    if (__builtin_expect(__any(L == 0u), 0)) {
+        decode_symbol_long(r, T, r.window64(nextw), L, s, bad);
+        asm volatile("" : "+v"(L), "+v"(s));   // the rare part waits for its own LDS reads: none is left pending for the common path
+    }
+    r.advance(L, nextw);
     return s;
 }
 
-// Where a lane's decoded symbols go.
+// Where a lane's decoded symbols go (bits above bit 7 of a symbol are to be ignored).
 // StageSink: four per word into an LDS row (co3_decode: coalesced stores of symbols and values follow).
 struct StageSink {
     uint32_t *row;
     uint32_t packed;
-    __device__ inline void sym(int j, uint32_t s)
+    __device__ inline uint32_t fetch(uint32_t) const { return 0u; }
+    __device__ inline void commit(int j, uint32_t s, uint32_t)
     {
-        packed |= s << (8 * (j & 3));
+        packed |= (s & 0xffu) << (8 * (j & 3));
         if ((j & 3) == 3) { row[j >> 2] = packed; packed = 0; }
     }
     __device__ inline void finish(int cnt) { if (cnt & 3) row[cnt >> 2] = packed; }
@@ -210,9 +231,10 @@ struct AccSink {
     double *row;            // the lane's 64 accumulators
     const uint32_t *mag;
     uint32_t mag_mask, sign_up;
-    __device__ inline void sym(int j, uint32_t s)
+    __device__ inline uint32_t fetch(uint32_t s) const { return mag[s & mag_mask]; }
+    __device__ inline void commit(int j, uint32_t s, uint32_t m)
     {
-        const uint32_t bits = mag[s & mag_mask] | ((s << sign_up) & 0x80000000u);
+        const uint32_t bits = m | ((s << sign_up) & 0x80000000u);
         __hip_atomic_fetch_add(&row[j], (double)__uint_as_float(bits), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
     __device__ inline void finish(int) {}
@@ -228,12 +250,20 @@ __device__ inline uint32_t decode_subchunk(Src src, uint32_t p0, int cnt, const 
     r.seek(p0);
     bool bad = false;
     if (cnt == kSub) {
-        for (int jj = 0; jj < kSub / 4; ++jj) {
+        // the sink's work for symbol j runs beside the decoding of symbol j + 1
+        uint32_t pend = decode_symbol<false>(r, T, bad, sink, 0, 0u);
+        for (int jj = 0; jj < kSub / 4 - 1; ++jj) {
 #pragma unroll
-            for (int b = 0; b < 4; ++b) sink.sym(4 * jj + b, decode_symbol(r, T, bad));
+            for (int b = 0; b < 4; ++b) pend = decode_symbol<true>(r, T, bad, sink, 4 * jj + b, pend);
         }
+#pragma unroll
+        for (int b = 0; b < 3; ++b) pend = decode_symbol<true>(r, T, bad, sink, kSub - 4 + b, pend);
+        sink.commit(kSub - 1, pend, sink.fetch(pend));
     } else {
-        for (int j = 0; j < cnt; ++j) sink.sym(j, decode_symbol(r, T, bad));
+        for (int j = 0; j < cnt; ++j) {
+            const uint32_t sy = decode_symbol<false>(r, T, bad, sink, 0, 0u);
+            sink.commit(j, sy, sink.fetch(sy));
+        }
         sink.finish(cnt);
     }
     return bad ? ~0u : r.pos() - p0;
@@ -394,7 +424,7 @@ constexpr int kAccWords = kSubsPerChunk * kAccStride;
 // sums are exact and their order does not matter; with exponent biases more than about 45 binades apart the
 // last bit may depend on it).  The wavefronts meet only twice: after the sums are cleared and before they
 // are written out.
-template <int W>
+template <int W, bool kPerUser>
 __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t *__restrict__ words,
                                                       uint64_t words_stride,
                                                       const uint64_t *__restrict__ chunk_offset,
@@ -406,7 +436,7 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
     extern __shared__ uint64_t smem64[];
     double *s_acc = reinterpret_cast<double *>(smem64);                    // [64][kAccStride]
     DecLds *s_tab = reinterpret_cast<DecLds *>(s_acc + kAccWords);         // [per-user books ? W : 1]
-    const uint32_t ntab = lay.per_user_books ? W : 1;
+    const uint32_t ntab = kPerUser ? W : 1;
     uint32_t *s_mag = reinterpret_cast<uint32_t *>(s_tab + ntab);          // [W][kMagEntries] fp32 patterns
     uint32_t *s_pay = s_mag + W * kMagEntries;                             // [W][kPayloadAlloc]
     constexpr int T = 64 * W;
@@ -418,16 +448,16 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
     const uint32_t sign_up = 31u - sign_shift;
 
     for (uint32_t i = t; i < (uint32_t)kAccWords; i += T) s_acc[i] = 0.0;
-    if (!lay.per_user_books) load_dec_tables(s_tab, books[(uint32_t)g.book], t, T);
+    if (!kPerUser) load_dec_tables(s_tab, books[(uint32_t)g.book], t, T);
     __syncthreads();
 
     // wavefront `wave` takes users wave, wave + W, ...; everything it touches besides the sums is its own
     uint32_t *my_mag = s_mag + wave * kMagEntries;
     uint32_t *my_pay = s_pay + wave * kPayloadAlloc;
-    const DecLds *my_tab = lay.per_user_books ? s_tab + wave : s_tab;
+    const DecLds *my_tab = kPerUser ? s_tab + wave : s_tab;
     for (uint32_t u = wave; u < lay.U; u += W) {
         const ChunkIndex ix = read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits);
-        if (lay.per_user_books) load_dec_tables(s_tab + wave, books[u * lay.books_per_user + (uint32_t)g.book], lane, 64);
+        if (kPerUser) load_dec_tables(s_tab + wave, books[u * lay.books_per_user + (uint32_t)g.book], lane, 64);
         const int bias = lay.bias[(uint64_t)u * lay.nseg + g.seg];
         const float inv_gain = lay.gain[2 * ((uint64_t)u * lay.nseg + g.seg) + 1];   // 1 unless the plan carries a scale
         for (uint32_t k = lane; k <= mag_mask; k += 64)
@@ -496,19 +526,27 @@ hipError_t launch_decode(const Layout &lay, const co3_decode_args &a, const Book
     return hipGetLastError();
 }
 
+template <int W, bool kPerUser>
+static hipError_t launch_aggregate_wp(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
+                                      hipStream_t s)
+{
+    const size_t lds = (size_t)kAccWords * sizeof(double) + (size_t)(kPerUser ? W : 1) * sizeof(DecLds) +
+                       (size_t)W * (kMagEntries + kPayloadAlloc) * 4;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_aggregate<W, kPerUser>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    ProfScope prof(K_AGGREGATE, s);
+    hipLaunchKernelGGL((k_aggregate<W, kPerUser>), dim3((uint32_t)lay.nchunks), dim3(64 * W), lds, s, lay, a.words,
+                       a.words_stride, a.chunk_offset, a.sub_bits, books, a.out, a.model, a.eta, a.status);
+    return hipGetLastError();
+}
+
 template <int W>
 static hipError_t launch_aggregate_w(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
                                      hipStream_t s)
 {
-    const size_t lds = (size_t)kAccWords * sizeof(double) + (size_t)(lay.per_user_books ? W : 1) * sizeof(DecLds) +
-                       (size_t)W * (kMagEntries + kPayloadAlloc) * 4;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_aggregate<W>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    ProfScope prof(K_AGGREGATE, s);
-    hipLaunchKernelGGL(k_aggregate<W>, dim3((uint32_t)lay.nchunks), dim3(64 * W), lds, s, lay, a.words,
-                       a.words_stride, a.chunk_offset, a.sub_bits, books, a.out, a.model, a.eta, a.status);
-    return hipGetLastError();
+    return lay.per_user_books ? launch_aggregate_wp<W, true>(lay, a, books, s)
+                              : launch_aggregate_wp<W, false>(lay, a, books, s);
 }
 
 hipError_t launch_aggregate(const Layout &lay, const co3_aggregate_args &a, const BookDev *books, hipStream_t s)
