@@ -418,6 +418,120 @@ constexpr int kMagEntries = kMaxA / 2;  // magnitude codes of a symbol alphabet 
 constexpr int kAccStride = kSub + 1;    // a lane's 64 accumulators + 1 pad: lanes hit different banks
 constexpr int kAccWords = kSubsPerChunk * kAccStride;
 
+// The PS average for few users (U <= 4): W = U wavefronts decode the users' chunks into staged symbol rows (as
+// co3_decode does), then every thread sums its elements over the users in fp64, in user order.  It needs no
+// accumulators in LDS, so that a workgroup of few wavefronts still leaves room for several per CU; with many users
+// k_aggregate below, whose footprint does not grow with W, keeps more wavefronts in flight.
+template <int W>
+__global__ __launch_bounds__(64 * W) void k_aggregate_staged(Layout lay, const uint32_t *__restrict__ words,
+                                                      uint64_t words_stride,
+                                                      const uint64_t *__restrict__ chunk_offset,
+                                                      const uint16_t *__restrict__ sub_bits,
+                                                      const BookDev *__restrict__ books, float *__restrict__ out,
+                                                      float *__restrict__ model, float eta,
+                                                      uint64_t *__restrict__ status)
+{
+    extern __shared__ uint64_t smem64[];
+    DecLds *s_tab = reinterpret_cast<DecLds *>(smem64);   // [per-user books ? W : 1]
+    const uint32_t ntab = lay.per_user_books ? W : 1;
+    uint32_t *s_mag = reinterpret_cast<uint32_t *>(s_tab + ntab);          // [W][kMagEntries] fp32 patterns
+    uint32_t *s_stage = s_mag + W * kMagEntries;                           // [W][kStageWords]
+    uint32_t *s_pay = s_stage + W * kStageWords;                           // [W][kPayloadAlloc]
+    constexpr int T = 64 * W;
+    constexpr int G = (kChunk / 4) / T;  // 4-element groups per thread
+    const uint32_t t = threadIdx.x, wave = t >> 6;
+    const uint64_t c = blockIdx.x;
+    const ChunkGeom g = chunk_geom(lay, c);
+    const uint32_t sign_shift = (uint32_t)(lay.E + lay.M);
+    const uint32_t mag_mask = (1u << sign_shift) - 1u;
+    const uint32_t sign_up = 31u - sign_shift;
+
+    double acc[G][4];
+#pragma unroll
+    for (int i = 0; i < G; ++i)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[i][b] = 0.0;
+
+    for (uint32_t u0 = 0; u0 < lay.U; u0 += W) {
+        const uint32_t u = u0 + wave;
+        const bool active = u < lay.U;
+        ChunkIndex ix;
+        if (active) ix = read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits);
+        const DecLds *my_tab = s_tab;
+        if (lay.per_user_books) {
+            my_tab = s_tab + wave;
+            if (active) load_dec_tables(s_tab + wave, books[u * lay.books_per_user + (uint32_t)g.book], t & 63u, 64);
+        } else if (u0 == 0) {
+            load_dec_tables(s_tab, books[(uint32_t)g.book], t, T);
+        }
+        for (uint32_t i = t; i < (uint32_t)(W * kMagEntries); i += T) {
+            const uint32_t uu = i / kMagEntries, k = i % kMagEntries;
+            if (u0 + uu < lay.U && k <= mag_mask) {
+                const uint64_t pair = (uint64_t)(u0 + uu) * lay.nseg + g.seg;
+                s_mag[i] = __float_as_uint(__fmul_rn(__uint_as_float(symbol_value_bits(k, lay.E, lay.M, lay.bias[pair])),
+                                                     lay.gain[2 * pair + 1]));   // inv_gain: 1 unless the plan carries a scale
+            }
+        }
+        __syncthreads();
+        if (active)
+            decode_user_chunk(g, ix, my_tab, s_pay + wave * kPayloadAlloc,
+                              StageSink{s_stage + wave * kStageWords + (t & 63u) * kStageStride, 0u}, status);
+        __syncthreads();
+        const uint32_t nu = (lay.U - u0 < (uint32_t)W) ? lay.U - u0 : (uint32_t)W;
+        for (uint32_t uu = 0; uu < nu; ++uu) {
+            const uint32_t *mag = s_mag + uu * kMagEntries;
+            const uint32_t *st = s_stage + uu * kStageWords;
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                const uint32_t e4 = t + (uint32_t)i * T;  // group of elements 4*e4 .. 4*e4+3
+                const uint32_t wv = st[(e4 >> 4) * kStageStride + (e4 & 15u)];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const uint32_t s = (wv >> (8 * b)) & 0xffu;
+                    const uint32_t bits = mag[s & mag_mask] | ((s << sign_up) & 0x80000000u);
+                    acc[i][b] += (double)__uint_as_float(bits);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    // average, and with `model` the PS update w - eta * average (eq. (aggregate hat), Algorithm 1
+    // line 14): products and difference in fp64, one rounding
+    const double inv_u = 1.0 / (double)lay.U;
+    const double eta64 = (double)eta;
+    const uintptr_t out_addr = out ? reinterpret_cast<uintptr_t>(out + g.e0) : 0u;
+    const uintptr_t model_addr = model ? reinterpret_cast<uintptr_t>(model + g.e0) : 0u;
+    const bool vec_ok = ((out_addr | model_addr) & 15u) == 0;
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+        const uint32_t e = 4u * (t + (uint32_t)i * T);
+        double avg[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) avg[b] = acc[i][b] * inv_u;
+        if (vec_ok && e + 3 < g.n) {
+            if (out)
+                *reinterpret_cast<float4 *>(out + g.e0 + e) =
+                    make_float4((float)avg[0], (float)avg[1], (float)avg[2], (float)avg[3]);
+            if (model) {
+                float4 w = *reinterpret_cast<const float4 *>(model + g.e0 + e);
+                w.x = (float)((double)w.x - eta64 * avg[0]);
+                w.y = (float)((double)w.y - eta64 * avg[1]);
+                w.z = (float)((double)w.z - eta64 * avg[2]);
+                w.w = (float)((double)w.w - eta64 * avg[3]);
+                *reinterpret_cast<float4 *>(model + g.e0 + e) = w;
+            }
+        } else {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                if (e + b >= g.n) continue;
+                if (out) out[g.e0 + e + b] = (float)avg[b];
+                if (model) model[g.e0 + e + b] = (float)((double)model[g.e0 + e + b] - eta64 * avg[b]);
+            }
+        }
+    }
+}
+
+
 // One workgroup per chunk.  The chunk's 4096 sums live in LDS as fp64; W wavefronts decode W users at a time,
 // lane j of each taking sub-chunk j, and every decoded symbol's value is added to its element's sum with an
 // LDS atomic (the users' values are fp32 numbers whose exponents lie within a few dozen binades, so the fp64
@@ -549,13 +663,28 @@ static hipError_t launch_aggregate_w(const Layout &lay, const co3_aggregate_args
                               : launch_aggregate_wp<W, false>(lay, a, books, s);
 }
 
+template <int W>
+static hipError_t launch_aggregate_staged(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
+                                          hipStream_t s)
+{
+    const size_t lds = (size_t)(lay.per_user_books ? W : 1) * sizeof(DecLds) +
+                       (size_t)W * (kMagEntries + kStageWords + kPayloadAlloc) * 4;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_aggregate_staged<W>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    ProfScope prof(K_AGGREGATE, s);
+    hipLaunchKernelGGL(k_aggregate_staged<W>, dim3((uint32_t)lay.nchunks), dim3(64 * W), lds, s, lay, a.words,
+                       a.words_stride, a.chunk_offset, a.sub_bits, books, a.out, a.model, a.eta, a.status);
+    return hipGetLastError();
+}
+
 hipError_t launch_aggregate(const Layout &lay, const co3_aggregate_args &a, const BookDev *books, hipStream_t s)
 {
     if (lay.U == 0 || lay.nchunks == 0) return hipSuccess;
     if (lay.U >= 5) return launch_aggregate_w<8>(lay, a, books, s);
-    if (lay.U >= 3) return launch_aggregate_w<4>(lay, a, books, s);
-    if (lay.U == 2) return launch_aggregate_w<2>(lay, a, books, s);
-    return launch_aggregate_w<1>(lay, a, books, s);
+    if (lay.U >= 3) return launch_aggregate_staged<4>(lay, a, books, s);
+    if (lay.U == 2) return launch_aggregate_staged<2>(lay, a, books, s);
+    return launch_aggregate_staged<1>(lay, a, books, s);
 }
 
 }  // namespace co3
