@@ -227,8 +227,6 @@ __global__ __launch_bounds__(64 * kCpb, kWaves) void k_encode_fused(
             // first) and the vectors at both ends are partial.
             const float *ga = gu - shift, *ma = mu - shift;
             float *moa = mo - shift;
-            for (uint32_t i = lane; i < (uint32_t)(kFuStage + 1); i += 64) s_stage[wave][i] = 0;
-            tables_to_lds();
             f4 gn[kFuBatch], mn[kFuBatch];
 #pragma unroll
             for (int r = 0; r < kFuBatch; ++r) {
@@ -236,6 +234,8 @@ __global__ __launch_bounds__(64 * kCpb, kWaves) void k_encode_fused(
                 gn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(ga + i));
                 mn[r] = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(ma + i));
             }
+            for (uint32_t i = lane; i < (uint32_t)(kFuStage + 1); i += 64) s_stage[wave][i] = 0;
+            tables_to_lds();
 #pragma unroll 1
             for (int bt = 0; bt < kFuBatches; ++bt) {
                 f4 gc[kFuBatch], mc[kFuBatch];
