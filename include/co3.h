@@ -292,7 +292,11 @@ typedef struct {
  * out[i] = fl32((sum over u = 0..U-1, in fp64, of ghat_i^(u)) * (1.0 / U)).
  * With `model`, also the PS model update of eq. (aggregate hat) / Algorithm 1 line 14 in the same
  * pass: model[i] = fl32(model[i] - eta * ((sum over u) * (1.0 / U))), products and difference in
- * fp64, one rounding.                                                                        */
+ * fp64, one rounding.  With five or more users the fp64 sums are formed by atomic additions in
+ * whatever order the wavefronts arrive.  The addends are representatives, so the sum is exact,
+ * and independent of that order, whenever (2^exp_bits - 2) + mant_bits + 1 + (largest minus
+ * smallest bias of the layer over the users) + log2 U <= 53 (add 23 - mant_bits for a plan that
+ * carries a gain); beyond that the last bit of a sum may depend on the order.                 */
 int co3_ps_aggregate(const co3_plan *plan, const co3_aggregate_args *args, void *stream);
 
 /* ---- measurement aid ---------------------------------------------------------------------
