@@ -4,13 +4,14 @@
 // A wavefront decodes one chunk of one user.  It first copies the chunk's words from HBM into
 // LDS with coalesced loads; then lane j decodes sub-chunk j (64 elements), whose start is the
 // prefix sum of the sub-chunk bit counts.  Codes of up to kDecBits bits are resolved by one LDS
-// table lookup; longer ones by a search over the canonical code's length boundaries.  Decoded
-// symbols are staged in LDS so that global stores (and the accumulation over users) are
-// coalesced.  A chunk whose words do not fit the LDS window is decoded straight from global
-// memory (same code, slower).
+// table lookup, a little longer ones by a second-level table, the rest by a search over the
+// canonical code's length boundaries.  co3_decode and the average for few users stage the decoded
+// symbols in LDS so that global stores (and the sum over users) are coalesced; the average for
+// many users adds every value to fp64 sums in LDS as it is decoded.  A chunk whose words do not
+// fit the LDS window is decoded straight from global memory (same code, slower).
 //
-// The work is bound by the serial integer chain of the decoder (table lookup -> shift -> next
-// lookup), not by HBM: it moves about b/8 + 4/U bytes per element.
+// The work moves about b/8 + 4/U bytes per element and is bound by how many sub-chunk streams a
+// CU keeps in flight (each needs its chunk's words in LDS), not by HBM.
 #include <cstdlib>
 
 #include "co3_internal.h"
@@ -534,10 +535,10 @@ __global__ __launch_bounds__(64 * W) void k_aggregate_staged(Layout lay, const u
 
 // One workgroup per chunk.  The chunk's 4096 sums live in LDS as fp64; W wavefronts decode W users at a time,
 // lane j of each taking sub-chunk j, and every decoded symbol's value is added to its element's sum with an
-// LDS atomic (the users' values are fp32 numbers whose exponents lie within a few dozen binades, so the fp64
-// sums are exact and their order does not matter; with exponent biases more than about 45 binades apart the
-// last bit may depend on it).  The wavefronts meet only twice: after the sums are cleared and before they
-// are written out.
+// LDS atomic.  The addends are representatives, so the fp64 sums are exact and their order does not matter as
+// long as (2^exp - 2) + mant + 1 + (spread of the users' biases) + log2 U <= 53 (23 - mant more with a gain);
+// beyond that the last bit may depend on the order.  The wavefronts meet only twice: after the sums are
+// cleared and before they are written out.
 template <int W, bool kPerUser>
 __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t *__restrict__ words,
                                                       uint64_t words_stride,
