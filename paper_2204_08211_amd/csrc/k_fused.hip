@@ -7,13 +7,12 @@
 // A workgroup of four wavefronts takes four consecutive chunks of one user:
 //   1. wavefront w quantizes chunk w (16 KB of g and of m, requested a quarter at a time with the
 //      next quarter in flight while the current one is computed) and leaves the symbols in LDS,
-//      in the rows of 16 + 1 words the pack step reads without bank conflicts.  A chunk that starts
+//      in the rows of 16 + 1 words the pack step reads without bank conflicts; the code's tables go
+//      to LDS while the first vectors are under way and the code length of every symbol is summed as
+//      it is produced, so the chunk's size is known when the sweep ends.  A chunk that starts
 //      at an element off the 16-byte grid (layers begin anywhere) takes the same vectors from the
 //      boundary below it; only the ragged last chunk of a layer goes element by element;
-//   2. lane j of the wavefront owns sub-chunk j: the wavefront-level coder of pack_core.h concatenates every
-//      lane's codewords in a private LDS row, which also yields the sub-chunk sizes (steps 1 and 2 need
-//      no workgroup barrier);
-//   3. the workgroup's 32-bit-rounded size is published and the sizes of all earlier workgroups of
+//   2. the workgroup's 32-bit-rounded size is published and the sizes of all earlier workgroups of
 //      the user are collected by a decoupled look-back: every workgroup first publishes its own
 //      size, then reads its predecessors' until it meets one that already knows its running total.
 //      Workgroups take their position from a ticket counter, so every predecessor is already
@@ -22,10 +21,12 @@
 //      inherit instead of waiting, writes no stream words and is counted in the status block.
 //      An entry is one 64-bit word (flag and size together) and carries everything a successor
 //      needs, so it is written and read with relaxed device-scope atomics: ordering fences would
-//      make every workgroup write back and invalidate its L2.  While the look-back's answers travel,
-//      every wavefront moves its rows to their bit offsets within the chunk (this needs no stream
-//      offset: chunks are word-aligned);
-//   4. the chunk's words are copied out coalesced.
+//      make every workgroup write back and invalidate its L2;
+//   3. while the look-back's answers travel, lane j of every wavefront codes sub-chunk j: the
+//      wavefront-level coder of pack_core.h concatenates the lane's codewords in a private LDS row
+//      (which also yields the sub-chunk sizes) and moves the rows to their bit offsets within the
+//      chunk (this needs no stream offset: chunks are word-aligned);
+//   4. the chunk's words are copied out coalesced at the offset the look-back gave.
 #include <atomic>
 
 #include "co3_internal.h"
