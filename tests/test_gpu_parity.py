@@ -605,7 +605,7 @@ def test_real_valued_scale_both_encoders(single_sweep):
 
 # ---- alphabets wider than one byte (9 to 12 symbol bits, 16-bit symbols) ---------------------------------
 
-@pytest.mark.parametrize("E,M,d", [(5, 6, 4096 * 3 + 77), (4, 5, 4095), (3, 5, 1), (5, 3, 4096 * 2)])
+@pytest.mark.parametrize("E,M,d", [(5, 6, 4096 * 3 + 77), (4, 5, 4095), (3, 5, 1), (5, 3, 4096 * 2), (5, 6, 3 * 2 ** 20 + 4097)])
 def test_wide_alphabets_both_encoders(E, M, d):
     import torch
     from paper_2204_08211_amd import binding as B
