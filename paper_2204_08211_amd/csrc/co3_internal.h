@@ -32,7 +32,8 @@ struct BookDev {
     uint32_t count[65];          // count[L]: symbols with length L
     uint32_t offset[65];         // offset[L]: index of the first length-L symbol in sorted[]
     uint16_t dec[kDecEntries];   // prefix -> (len << 8) | symbol for len <= 11; else 1 + its second-level table, or 0
-    uint16_t dec2[kDec2Tables << kDec2Bits];  // [table][next kDec2Bits bits] -> (len << 8) | symbol, 0: longer code
+    uint16_t dec2[kDec2Tables << kDec2Bits];  // [table][next kDec2Bits bits] -> (len << 8) | symbol, 0: longer code;
+                                 // directly behind dec[]: the decoders index both as one array
     uint8_t len[kMaxA];          // codeword length, 0 = no code
     uint8_t sorted[kMaxA];       // symbols ordered by (length, symbol)
     uint32_t maxlen;
@@ -41,7 +42,8 @@ struct BookDev {
     // longer than kDecBits has the first listed length with w <= long_last[k]; its symbol is
     // sorted[(uint32_t)(w >> (64 - len)) + long_base[k]].
     uint32_t nlong;
-    uint32_t pad;
+    uint32_t long_prefix0;       // first kDecBits-bit prefix under which only longer codes live (kDecEntries: none);
+                                 // prefix long_prefix0 + j, j < kDec2Tables, has second-level table j
     uint64_t long_last[kLongSlots];   // left-aligned last code of the length, low bits all ones
     uint32_t long_base[kLongSlots];   // offset[len] - first[len] (mod 2^32)
     uint32_t long_len[kLongSlots];

@@ -44,7 +44,7 @@ static void finish_tables(BookDev *b, uint32_t A)
     }
     // search list for codes longer than the direct table
     b->nlong = 0;
-    b->pad = 0;
+    b->long_prefix0 = kDecEntries;
     std::memset(b->long_last, 0, sizeof(b->long_last));
     std::memset(b->long_base, 0, sizeof(b->long_base));
     std::memset(b->long_len, 0, sizeof(b->long_len));
@@ -66,6 +66,7 @@ static void finish_tables(BookDev *b, uint32_t A)
         long_prefix0 = (uint32_t)(b->first[L] >> (L - kDecBits));
         break;
     }
+    b->long_prefix0 = long_prefix0;
     for (uint32_t p = long_prefix0; p < (uint32_t)kDecEntries && p - long_prefix0 < (uint32_t)kDec2Tables; ++p)
         b->dec[p] = (uint16_t)(p - long_prefix0 + 1);  // entries of the second-level tables follow with the symbols
     uint32_t next[65];

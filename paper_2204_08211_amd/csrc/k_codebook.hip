@@ -132,7 +132,6 @@ __global__ __launch_bounds__(kCbThreads) void k_build_books(BookDev *__restrict_
         B.maxlen = mx;
         B.nactive = bad ? 0 : (uint32_t)n;
         B.nlong = nlong;
-        B.pad = 0;
     }
     __syncthreads();
 
@@ -160,6 +159,7 @@ __global__ __launch_bounds__(kCbThreads) void k_build_books(BookDev *__restrict_
     for (int l = kDecBits + 1; l <= 64; ++l) {
         if (cnt[l]) { long_prefix0 = (uint32_t)(first[l] >> (l - kDecBits)); break; }
     }
+    if (t == 0) B.long_prefix0 = long_prefix0;
     for (int idx = t; idx < kDecEntries; idx += kCbThreads) {
         uint16_t e = 0;
         for (int l = 1; l <= kDecBits; ++l) {

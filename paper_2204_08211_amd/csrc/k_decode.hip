@@ -12,6 +12,7 @@
 //
 // The work moves about b/8 + 4/U bytes per element and is bound by how many sub-chunk streams a
 // CU keeps in flight (each needs its chunk's words in LDS), not by HBM.
+#include <cstddef>
 #include <cstdlib>
 
 #include "co3_internal.h"
@@ -36,8 +37,10 @@ struct DecLds {
     uint32_t long_len[kLongSlots];
     uint8_t sorted[kMaxA];
     uint32_t nlong;
-    uint32_t pad;
+    uint32_t long_prefix0;
 };
+static_assert(offsetof(DecLds, dec) == 0 && offsetof(DecLds, dec2) == sizeof(uint16_t) * kDecEntries,
+              "the direct table comes first and the second-level tables directly follow it");
 
 __device__ inline void load_dec_tables(DecLds *T, const BookDev &book, uint32_t t, uint32_t nthreads)
 {
@@ -52,7 +55,7 @@ __device__ inline void load_dec_tables(DecLds *T, const BookDev &book, uint32_t 
     }
     for (uint32_t i = t; i < kMaxA / 4; i += nthreads)
         reinterpret_cast<uint32_t *>(T->sorted)[i] = reinterpret_cast<const uint32_t *>(book.sorted)[i];
-    if (t == 0) { T->nlong = book.nlong; T->pad = 0; }
+    if (t == 0) { T->nlong = book.nlong; T->long_prefix0 = book.long_prefix0; }
 }
 
 __device__ inline uint32_t find_chunk_segment_d(const SegDev *segs, uint32_t nseg, uint64_t chunk)
@@ -156,22 +159,14 @@ struct Reader {
     }
 };
 
-// The rare part of decode_symbol, for the lanes whose prefix the direct table does not resolve (L == 0 on
-// entry; s is then 0 or 1 + the prefix's second-level table): codes a little longer than the direct table take
-// one more look-up; the rest compare the window with the left-aligned last code of every longer length that
-// occurs (they grow with the length).  The window's valid bits decide lengths up to 32; longer ones take the
-// exact path, which repositions the reader itself and leaves L = 0.
+// The rare part of decode_symbol, for the lanes whose look-up found no codeword (L == 0 on entry: a code longer
+// than kDecBits + kDec2Bits bits, or a stream that is not one): the window is compared with the left-aligned
+// last code of every longer length that occurs (they grow with the length).  Lengths up to 32 are consumed by
+// the caller; longer ones take the exact path, which repositions the reader itself and leaves L = 0.
 template <class Src>
 __device__ inline void decode_symbol_long(Reader<Src> &r, const DecLds *T, uint64_t win, uint32_t &L, uint32_t &s, bool &bad)
 {
     if (L != 0u) return;
-    uint32_t e2 = 0;
-    if (s) e2 = T->dec2[((s - 1u) << kDec2Bits) | ((uint32_t)(win >> (64 - kDecBits - kDec2Bits)) & ((1u << kDec2Bits) - 1u))];
-    if (e2) {
-        L = e2 >> 8;
-        s = e2 & 0xffu;
-        return;
-    }
     const uint32_t n = T->nlong;
     uint32_t k = 0;
     while (k < n && win > T->long_last[k]) ++k;
@@ -190,21 +185,29 @@ __device__ inline void decode_symbol_long(Reader<Src> &r, const DecLds *T, uint6
     }
 }
 
-// One symbol; `bad` is set if nothing matched.  The common case is one look-up in the direct table and a
-// branch-free advance; the branch to the rare part is taken by the whole wavefront or not at all.  Returned is
-// the symbol in bits 0..7; the bits above are not defined (the direct table's entry is passed on as it is).
-// While the two LDS reads of this symbol are in flight the sink may have one of its own for the symbol before
-// (`pend`, element j): Sink::fetch requests it, Sink::commit uses it, and the wavefront waits once for all three.
+// One symbol; `bad` is set if nothing matched.  The common case is one look-up and a branch-free advance.  The
+// look-up covers codes of up to kDecBits + kDec2Bits bits: the next kDecBits bits index the direct table, unless
+// they are one of the first kDec2Tables prefixes under which only longer codes live (p0 = the first such prefix;
+// canonical codes grow with their length, so these are the largest prefixes) - then kDec2Bits more bits index that
+// prefix's second-level table, which lies directly behind the direct table.  The branch to the rare part is taken
+// by the whole wavefront or not at all.  Returned is the symbol in bits 0..7; the bits above are not defined (the
+// table's entry is passed on as it is).  While the LDS reads of this symbol are in flight the sink may have one of
+// its own for the symbol before (`pend`, element j): Sink::fetch requests it, Sink::commit uses it, and the
+// wavefront waits once for all of them.
 template <bool kCommit, class Src, class Sink>
-__device__ inline uint32_t decode_symbol(Reader<Src> &r, const DecLds *T, bool &bad, Sink &sink, int j, uint32_t pend)
+__device__ inline uint32_t decode_symbol(Reader<Src> &r, const DecLds *T, uint32_t p0, bool &bad, Sink &sink, int j,
+                                         uint32_t pend)
 {
     const uint32_t win = r.window32();
+    const uint32_t i1 = win >> (32 - kDecBits);
+    const uint32_t i2 = (uint32_t)kDecEntries + (win >> (32 - kDecBits - kDec2Bits)) - (p0 << kDec2Bits);
+    const uint32_t idx = (i1 - p0 < (uint32_t)kDec2Tables) ? i2 : i1;   // unsigned: false below p0
     uint32_t nextw = r.src.next(r.wi);                       // all LDS reads are requested
-    uint32_t e = T->dec[win >> (32 - kDecBits)];             // before any result is needed
+    uint32_t e = reinterpret_cast<const uint16_t *>(T)[idx]; // dec[] and, behind it, dec2[]; before any result is needed
     uint32_t tok = kCommit ? sink.fetch(pend) : 0u;
     asm volatile("" : "+v"(nextw), "+v"(e), "+v"(tok));
     if (kCommit) sink.commit(j, pend, tok);
-    uint32_t L = e >> 8, s = e;                              // L == 0: e is 0 or 1 + the prefix's second-level table
+    uint32_t L = e >> 8, s = e;
     if (__builtin_expect(__any(L == 0u), 0)) {
         decode_symbol_long(r, T, r.window64(nextw), L, s, bad);
         asm volatile("" : "+v"(L), "+v"(s));   // the rare part waits for its own LDS reads: none is left pending for the common path
@@ -250,19 +253,20 @@ __device__ inline uint32_t decode_subchunk(Src src, uint32_t p0, int cnt, const 
     r.src = src;
     r.seek(p0);
     bool bad = false;
+    const uint32_t lp0 = T->long_prefix0;   // read once: the sinks' LDS traffic would make the compiler reload it
     if (cnt == kSub) {
         // the sink's work for symbol j runs beside the decoding of symbol j + 1
-        uint32_t pend = decode_symbol<false>(r, T, bad, sink, 0, 0u);
+        uint32_t pend = decode_symbol<false>(r, T, lp0, bad, sink, 0, 0u);
         for (int jj = 0; jj < kSub / 4 - 1; ++jj) {
 #pragma unroll
-            for (int b = 0; b < 4; ++b) pend = decode_symbol<true>(r, T, bad, sink, 4 * jj + b, pend);
+            for (int b = 0; b < 4; ++b) pend = decode_symbol<true>(r, T, lp0, bad, sink, 4 * jj + b, pend);
         }
 #pragma unroll
-        for (int b = 0; b < 3; ++b) pend = decode_symbol<true>(r, T, bad, sink, kSub - 4 + b, pend);
+        for (int b = 0; b < 3; ++b) pend = decode_symbol<true>(r, T, lp0, bad, sink, kSub - 4 + b, pend);
         sink.commit(kSub - 1, pend, sink.fetch(pend));
     } else {
         for (int j = 0; j < cnt; ++j) {
-            const uint32_t sy = decode_symbol<false>(r, T, bad, sink, 0, 0u);
+            const uint32_t sy = decode_symbol<false>(r, T, lp0, bad, sink, 0, 0u);
             sink.commit(j, sy, sink.fetch(sy));
         }
         sink.finish(cnt);
@@ -315,12 +319,24 @@ __device__ inline ChunkIndex read_index(const Layout &lay, uint64_t c, uint32_t 
     return ix;
 }
 
-// One wavefront: bring the chunk into s_pay (if it fits), decode it into the lanes' sinks.  Every read of
-// the stream stays inside the chunk's words.  Inconsistent sub-chunks are counted in
+// The chunk's words as the wavefront requests them from HBM: word lane + 64 k in tmp[k] (zero beyond the chunk, and
+// nothing is requested for a chunk that does not fit the LDS window).
+__device__ inline void payload_request(const ChunkIndex &ix, uint32_t (&tmp)[kPayloadPerLane])
+{
+    const uint32_t lane = threadIdx.x & 63;
+#pragma unroll
+    for (int k = 0; k < kPayloadPerLane; ++k) {
+        const uint32_t i = lane + 64u * k;
+        tmp[k] = (ix.in_lds && i < ix.nw) ? ix.w[i] : 0u;
+    }
+}
+
+// One wavefront: the requested words go to s_pay (if the chunk fits), the chunk is decoded into the lanes' sinks.
+// Every read of the stream stays inside the chunk's words.  Inconsistent sub-chunks are counted in
 // status[CO3_STAT_CORRUPT].  Contains wave-level synchronisation only.
 template <class Sink>
-__device__ inline void decode_user_chunk(const ChunkGeom &g, const ChunkIndex &ix, const DecLds *T,
-                                         uint32_t *s_pay, Sink sink, uint64_t *status)
+__device__ inline void decode_requested_chunk(const ChunkGeom &g, const ChunkIndex &ix, const DecLds *T, uint32_t *s_pay,
+                                              const uint32_t (&tmp)[kPayloadPerLane], Sink sink, uint64_t *status)
 {
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t p0 = wave_exclusive_scan_u32(ix.sb);
@@ -328,13 +344,6 @@ __device__ inline void decode_user_chunk(const ChunkGeom &g, const ChunkIndex &i
     const int cnt = (int)g.n - first_elem < 0 ? 0 : ((int)g.n - first_elem > kSub ? kSub : (int)g.n - first_elem);
     uint32_t used = 0;
     if (ix.in_lds) {
-        // all loads first, then all LDS stores: one memory latency for the whole chunk
-        uint32_t tmp[kPayloadPerLane];
-#pragma unroll
-        for (int k = 0; k < kPayloadPerLane; ++k) {
-            const uint32_t i = lane + 64u * k;
-            tmp[k] = i < ix.nw ? ix.w[i] : 0u;
-        }
 #pragma unroll
         for (int k = 0; k < kPayloadPerLane; ++k) {
             const uint32_t i = lane + 64u * k;
@@ -349,6 +358,16 @@ __device__ inline void decode_user_chunk(const ChunkGeom &g, const ChunkIndex &i
     }
     if (used != ix.sb || !ix.ok)
         atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CORRUPT), 1ull);
+}
+
+// The two in one go: all loads first, then all LDS stores, one memory latency for the whole chunk.
+template <class Sink>
+__device__ inline void decode_user_chunk(const ChunkGeom &g, const ChunkIndex &ix, const DecLds *T,
+                                         uint32_t *s_pay, Sink sink, uint64_t *status)
+{
+    uint32_t tmp[kPayloadPerLane];
+    payload_request(ix, tmp);
+    decode_requested_chunk(g, ix, T, s_pay, tmp, sink, status);
 }
 
 // co3_decode: a workgroup takes one chunk of kDecWaves consecutive users, a wavefront per user, so
@@ -540,7 +559,7 @@ __global__ __launch_bounds__(64 * W) void k_aggregate_staged(Layout lay, const u
 // beyond that the last bit may depend on the order.  The wavefronts meet only twice: after the sums are
 // cleared and before they are written out.
 template <int W, bool kPerUser>
-__global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t *__restrict__ words,
+__global__ __launch_bounds__(64 * W, 4) void k_aggregate(Layout lay, const uint32_t *__restrict__ words,
                                                       uint64_t words_stride,
                                                       const uint64_t *__restrict__ chunk_offset,
                                                       const uint16_t *__restrict__ sub_bits,
@@ -562,16 +581,27 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
     const uint32_t mag_mask = (1u << sign_shift) - 1u;
     const uint32_t sign_up = 31u - sign_shift;
 
+    // Wavefront `wave` takes users wave, wave + W, ...; everything it touches besides the sums is its own.  The
+    // index entries of a user are requested two users ahead and the chunk's words one user ahead (they wait in
+    // registers while the current user is decoded), so that only the first user's memory latency is exposed -
+    // and that one runs beside the clearing of the sums and the loading of the tables.
+    ChunkIndex ix_cur = {}, ix_next = {};
+    uint32_t pl_cur[kPayloadPerLane], pl_next[kPayloadPerLane];
+    if (wave < lay.U) ix_cur = read_index(lay, c, wave, words, words_stride, chunk_offset, sub_bits);
+    if (wave + W < lay.U) ix_next = read_index(lay, c, wave + W, words, words_stride, chunk_offset, sub_bits);
+    if (wave < lay.U) payload_request(ix_cur, pl_cur);
+
     for (uint32_t i = t; i < (uint32_t)kAccWords; i += T) s_acc[i] = 0.0;
     if (!kPerUser) load_dec_tables(s_tab, books[(uint32_t)g.book], t, T);
     __syncthreads();
 
-    // wavefront `wave` takes users wave, wave + W, ...; everything it touches besides the sums is its own
     uint32_t *my_mag = s_mag + wave * kMagEntries;
     uint32_t *my_pay = s_pay + wave * kPayloadAlloc;
     const DecLds *my_tab = kPerUser ? s_tab + wave : s_tab;
     for (uint32_t u = wave; u < lay.U; u += W) {
-        const ChunkIndex ix = read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits);
+        if (u + W < lay.U) payload_request(ix_next, pl_next);
+        ChunkIndex ix_after = {};
+        if (u + 2 * W < lay.U) ix_after = read_index(lay, c, u + 2 * W, words, words_stride, chunk_offset, sub_bits);
         if (kPerUser) load_dec_tables(s_tab + wave, books[u * lay.books_per_user + (uint32_t)g.book], lane, 64);
         const int bias = lay.bias[(uint64_t)u * lay.nseg + g.seg];
         const float inv_gain = lay.gain[2 * ((uint64_t)u * lay.nseg + g.seg) + 1];   // 1 unless the plan carries a scale
@@ -580,10 +610,15 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        decode_user_chunk(g, ix, my_tab, my_pay, AccSink{s_acc + lane * kAccStride, my_mag, mag_mask, sign_up}, status);
+        decode_requested_chunk(g, ix_cur, my_tab, my_pay, pl_cur, AccSink{s_acc + lane * kAccStride, my_mag, mag_mask, sign_up},
+                               status);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();   // the next user's tables and words overwrite these
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        ix_cur = ix_next;
+        ix_next = ix_after;
+#pragma unroll
+        for (int k = 0; k < kPayloadPerLane; ++k) pl_cur[k] = pl_next[k];
     }
     __syncthreads();
 
