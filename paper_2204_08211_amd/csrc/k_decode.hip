@@ -559,7 +559,7 @@ __global__ __launch_bounds__(64 * W) void k_aggregate_staged(Layout lay, const u
 // beyond that the last bit may depend on the order.  The wavefronts meet only twice: after the sums are
 // cleared and before they are written out.
 template <int W, bool kPerUser>
-__global__ __launch_bounds__(64 * W, 4) void k_aggregate(Layout lay, const uint32_t *__restrict__ words,
+__global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t *__restrict__ words,
                                                       uint64_t words_stride,
                                                       const uint64_t *__restrict__ chunk_offset,
                                                       const uint16_t *__restrict__ sub_bits,
@@ -581,27 +581,16 @@ __global__ __launch_bounds__(64 * W, 4) void k_aggregate(Layout lay, const uint3
     const uint32_t mag_mask = (1u << sign_shift) - 1u;
     const uint32_t sign_up = 31u - sign_shift;
 
-    // Wavefront `wave` takes users wave, wave + W, ...; everything it touches besides the sums is its own.  The
-    // index entries of a user are requested two users ahead and the chunk's words one user ahead (they wait in
-    // registers while the current user is decoded), so that only the first user's memory latency is exposed -
-    // and that one runs beside the clearing of the sums and the loading of the tables.
-    ChunkIndex ix_cur = {}, ix_next = {};
-    uint32_t pl_cur[kPayloadPerLane], pl_next[kPayloadPerLane];
-    if (wave < lay.U) ix_cur = read_index(lay, c, wave, words, words_stride, chunk_offset, sub_bits);
-    if (wave + W < lay.U) ix_next = read_index(lay, c, wave + W, words, words_stride, chunk_offset, sub_bits);
-    if (wave < lay.U) payload_request(ix_cur, pl_cur);
-
     for (uint32_t i = t; i < (uint32_t)kAccWords; i += T) s_acc[i] = 0.0;
     if (!kPerUser) load_dec_tables(s_tab, books[(uint32_t)g.book], t, T);
     __syncthreads();
 
+    // wavefront `wave` takes users wave, wave + W, ...; everything it touches besides the sums is its own
     uint32_t *my_mag = s_mag + wave * kMagEntries;
     uint32_t *my_pay = s_pay + wave * kPayloadAlloc;
     const DecLds *my_tab = kPerUser ? s_tab + wave : s_tab;
     for (uint32_t u = wave; u < lay.U; u += W) {
-        if (u + W < lay.U) payload_request(ix_next, pl_next);
-        ChunkIndex ix_after = {};
-        if (u + 2 * W < lay.U) ix_after = read_index(lay, c, u + 2 * W, words, words_stride, chunk_offset, sub_bits);
+        const ChunkIndex ix = read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits);
         if (kPerUser) load_dec_tables(s_tab + wave, books[u * lay.books_per_user + (uint32_t)g.book], lane, 64);
         const int bias = lay.bias[(uint64_t)u * lay.nseg + g.seg];
         const float inv_gain = lay.gain[2 * ((uint64_t)u * lay.nseg + g.seg) + 1];   // 1 unless the plan carries a scale
@@ -610,15 +599,10 @@ __global__ __launch_bounds__(64 * W, 4) void k_aggregate(Layout lay, const uint3
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        decode_requested_chunk(g, ix_cur, my_tab, my_pay, pl_cur, AccSink{s_acc + lane * kAccStride, my_mag, mag_mask, sign_up},
-                               status);
+        decode_user_chunk(g, ix, my_tab, my_pay, AccSink{s_acc + lane * kAccStride, my_mag, mag_mask, sign_up}, status);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();   // the next user's tables and words overwrite these
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        ix_cur = ix_next;
-        ix_next = ix_after;
-#pragma unroll
-        for (int k = 0; k < kPayloadPerLane; ++k) pl_cur[k] = pl_next[k];
     }
     __syncthreads();
 
