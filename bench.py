@@ -61,6 +61,8 @@ def parse():
                    help="encoder for --book model: the single-sweep kernel (symbols never stored) or the three-step one")
     p.add_argument("--stochastic", action="store_true",
                    help="stochastic fp conversion (dithered Q) instead of the closest representative; a new seed per step")
+    p.add_argument("--sweep-hist", action="store_true",
+                   help="the single-sweep encoder also counts the symbols (histogram output with a held code)")
     p.add_argument("--per-user-books", action="store_true", help="every user its own code tables instead of pooled ones")
     p.add_argument("--graph", action="store_true",
                    help="replay the step from HIP graphs (one per gradient set of the pool) instead of launching eagerly")
@@ -165,7 +167,8 @@ def main():
 
         def eager_step(idx):
             B.co3_encode(plan, books, pool[idx], m, m, gamma, buf, mode=mode, single_sweep=single_sweep,
-                         stochastic_seed=(1000 + counter[0]) if a.stochastic else None)
+                         stochastic_seed=(1000 + counter[0]) if a.stochastic else None,
+                         single_sweep_hist=single_sweep and a.sweep_hist)
             B.co3_ps_aggregate(plan, books, buf, out)
 
         graphs = []

@@ -197,9 +197,11 @@ int co3_bias_from_model(co3_format format, double mu, double alpha, double beta,
  * mode CO3_BOOK_FIXED encodes with `books` as they are (a code designed beforehand, e.g. from
  * the GenNorm model); CO3_BOOK_EMPIRICAL first rebuilds `books` on the device from this
  * round's symbol histogram.
- * In mode CO3_BOOK_FIXED `symbols` and `hist` may both be NULL: neither is produced then, and
- * the library runs the single-sweep encoder, in which the symbols never reach device memory
- * (12 bytes of traffic per element plus the stream).                                        */
+ * In mode CO3_BOOK_FIXED `symbols` may be NULL: the library then runs the single-sweep encoder,
+ * in which the symbols never reach device memory (12 bytes of traffic per element plus the
+ * stream).  `hist` may be NULL too; if it is given, the sweep also counts this round's symbols
+ * per code table (e.g. to design the next round's code from them while this round's is held),
+ * at a lower occupancy of the kernel.                                                         */
 enum { CO3_BOOK_FIXED = 0, CO3_BOOK_EMPIRICAL = 1 };
 /* Q_fp picks the closest representative (Sec. IV-A (i)), or, as the stochastic mapping Sec. II-B
  * (ii) allows (non-subtractive dither), the upper of the two neighbours with probability
@@ -220,7 +222,8 @@ typedef struct {
     uint8_t *symbols;        /* device, co3_plan_symbols_bytes(): [U][d] symbols (out);      */
                              /* uint16_t words for wide alphabets                            */
     uint64_t *hist;          /* device [num_books][A] symbol counts (out; cleared here)      */
-                             /* (symbols, hist: both NULL selects the single-sweep encoder)  */
+                             /* (symbols NULL, fixed code: the single-sweep encoder; hist    */
+                             /* is then optional)                                            */
     uint32_t *words;         /* device [U][words_stride] streams (out)                       */
     uint64_t words_stride;   /* capacity of one user's stream in 32-bit words                */
     uint64_t *chunk_offset;  /* device [U][num_chunks+1] bit offsets of the chunks (out)     */

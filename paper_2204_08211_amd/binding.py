@@ -365,10 +365,11 @@ STATIC_SCRATCH_BYTES = 8 << 20
 
 
 def co3_encode(plan, books, g, m, m_out, gamma, buf, mode=BOOK_EMPIRICAL, stream=None, single_sweep=False,
-               stochastic_seed=None, static=False):
+               stochastic_seed=None, static=False, single_sweep_hist=False):
     """User side of one round for all U users (Algorithm 1 lines 8-10).  g, m, m_out are float32
     device tensors [U][row_stride]; outputs land in `buf` (RoundBuffers).  single_sweep (fixed code
-    only) passes no symbols and no hist buffer, which selects the library's single-sweep encoder.
+    only) passes no symbols and no hist buffer, which selects the library's single-sweep encoder;
+    single_sweep_hist passes the hist buffer all the same (the sweep then also counts the symbols).
     stochastic_seed: None = closest representative, else the stochastic conversion keyed by that seed.
     static: call co3_encode_static (the library's own static workspace, no allocation; buf.workspace is not passed)."""
     assert not single_sweep or mode == BOOK_FIXED
@@ -376,7 +377,7 @@ def co3_encode(plan, books, g, m, m_out, gamma, buf, mode=BOOK_EMPIRICAL, stream
     assert g.stride(0) == m.stride(0) == m_out.stride(0)
     a = EncodeArgs(g.data_ptr(), m.data_ptr(), m_out.data_ptr(), g.stride(0), float(np.float32(gamma)), int(mode),
                    books.handle, None if single_sweep else buf.symbols.data_ptr(),
-                   None if single_sweep else buf.hist.data_ptr(), buf.words.data_ptr(),
+                   None if (single_sweep and not single_sweep_hist) else buf.hist.data_ptr(), buf.words.data_ptr(),
                    buf.words_stride, buf.chunk_offset.data_ptr(), buf.sub_bits.data_ptr(),
                    buf.payload_bits.data_ptr(), buf.status.data_ptr(), None if static else buf.workspace.data_ptr(),
                    0 if static else buf.workspace.numel(), ROUND_NEAREST if stochastic_seed is None else ROUND_STOCHASTIC, 0,

@@ -381,7 +381,9 @@ static int encode_with_workspace(const co3_plan *plan, const co3_encode_args *a,
     if (a->rounding != CO3_ROUND_NEAREST && a->rounding != CO3_ROUND_STOCHASTIC) return CO3_ERR_ARG;
     if (a->rounding == CO3_ROUND_STOCHASTIC && plan->has_gain) return CO3_ERR_ARG;  // defined for the closest representative only
     // symbols and hist come as a pair; without them a fixed code is encoded in a single sweep
-    const bool single_sweep = a->mode == CO3_BOOK_FIXED && !a->symbols && !a->hist;
+    // without a symbol buffer a fixed code is encoded in a single sweep (with or without the symbol counts);
+    // everything else needs both buffers
+    const bool single_sweep = a->mode == CO3_BOOK_FIXED && !a->symbols;
     if (!single_sweep && (!a->symbols || !a->hist)) return CO3_ERR_ARG;
     if (!aligned16(a->g) || !aligned16(a->m) || !aligned16(a->m_out) || !aligned16(a->symbols) ||
         (a->row_stride & 3u) || a->row_stride < lay.d)

@@ -142,6 +142,7 @@ size_t three_step_workspace_full(const Layout &lay);
 EncodeWs three_step_workspace(const Layout &lay, void *workspace, size_t bytes);
 
 hipError_t launch_zero_u64(uint64_t *p, uint64_t n, hipStream_t s);
+hipError_t launch_reduce_hist(const uint64_t *hist_rep, uint64_t *hist, uint64_t n, hipStream_t s);   // hist[i] = sum of the partial tables
 hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, const EncodeWs &ws, hipStream_t s);
 hipError_t launch_build_books(BookDev *books, uint32_t nbooks, uint32_t A, const uint64_t *weights,
                               uint64_t *status, hipStream_t s);

@@ -88,17 +88,20 @@ __device__ inline void fu_lds_barrier()
 // kWaves: wavefronts per SIMD the register budget is cut for.  Five (a few values spill) is what the streaming of
 // whole 16-byte-aligned chunks wants; layers that start at arbitrary elements take the shifted path, which holds
 // more state and runs faster at four without spills, and so does the stochastic conversion (1.05 against 1.29 ms).
-template <bool kSR, int kCpb, int kWaves>
+// kHist: also count the symbols per code table (hist_rep: kHistGlobalRep partial tables, folded afterwards), for
+// callers that hold a code but want this round's histogram, e.g. to design the next round's code from it.
+template <bool kSR, int kCpb, int kWaves, bool kHist>
 __global__ __launch_bounds__(64 * kCpb, kWaves) void k_encode_fused(
     Layout lay, const float *__restrict__ g, const float *m, float *m_out, uint64_t row_stride, float gamma,
     uint64_t seed, const BookDev *__restrict__ books, uint32_t *__restrict__ tickets, uint64_t *lb_state, uint32_t nblk,
     uint32_t spin_limit, uint64_t *__restrict__ chunk_offset, uint16_t *__restrict__ sub_bits,
     uint64_t *__restrict__ payload_bits, uint32_t *__restrict__ words, uint64_t words_stride,
-    uint64_t *__restrict__ status)
+    uint64_t *__restrict__ status, uint64_t *__restrict__ hist_rep)
 {
     __shared__ uint32_t s_stage[kCpb][kPcRegion];     // a wavefront's symbols, then its lanes' rows, then its chunk's words
     __shared__ uint32_t s_fast[kCpb][kMaxA];
     __shared__ uint8_t s_len[kCpb][kMaxA];            // code lengths (0: no code), for the chunk's size
+    __shared__ uint32_t s_hist[kHist ? kCpb : 1][kHist ? kMaxA : 1];   // a wavefront's symbol counts of its chunk
     __shared__ uint64_t s_e0[kCpb];
     __shared__ uint32_t s_n[kCpb], s_book[kCpb], s_cbits[kCpb];
     __shared__ int32_t s_bias[kCpb];
@@ -160,6 +163,10 @@ __global__ __launch_bounds__(64 * kCpb, kWaves) void k_encode_fused(
 #pragma unroll
             for (int r = 0; r < kMaxA / 64; ++r) s_fast[wave][lane + 64 * r] = tab_fast[r];
             reinterpret_cast<uint32_t *>(s_len[wave])[lane] = tab_len;
+            if constexpr (kHist) {
+#pragma unroll
+                for (int r = 0; r < kMaxA / 64; ++r) s_hist[wave][lane + 64 * r] = 0u;
+            }
             fu_wave_sync_lds();
         };
         const uint8_t *len_tab = s_len[wave];
@@ -183,6 +190,9 @@ __global__ __launch_bounds__(64 * kCpb, kWaves) void k_encode_fused(
                 n_nonfinite += flags & ok;
                 n_clamped += (flags >> 1) & ok;
                 len_sum += ok ? (uint32_t)len_tab[s] : 0u;
+                if constexpr (kHist) {
+                    if (ok) atomicAdd(&s_hist[wave][s], 1u);
+                }
                 packed |= s << (8 * j);
             }
         };
@@ -308,6 +318,7 @@ __global__ __launch_bounds__(64 * kCpb, kWaves) void k_encode_fused(
                         n_nonfinite += flags & 1u;
                         n_clamped += (flags >> 1) & 1u;
                         len_sum += (uint32_t)len_tab[s];
+                        if constexpr (kHist) atomicAdd(&s_hist[wave][s], 1u);
                     }
                     s = in ? s : 0u;
                     const uint32_t s4 = s | (__shfl_down(s, 1, 64) << 8) | (__shfl_down(s, 2, 64) << 16) |
@@ -322,6 +333,17 @@ __global__ __launch_bounds__(64 * kCpb, kWaves) void k_encode_fused(
                       (unsigned long long)n_nonfinite);
         if (n_clamped)
             atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CLAMPED), (unsigned long long)n_clamped);
+        if constexpr (kHist) {
+            // the chunk's counts go to one of the partial tables of its code table
+            fu_wave_sync_lds();
+            uint64_t *dst = hist_rep + ((uint64_t)(blockIdx.x % kHistGlobalRep) * lay.nbooks + s_book[wave]) * lay.A;
+#pragma unroll
+            for (int r = 0; r < kMaxA / 64; ++r) {
+                const uint32_t bin = lane + 64u * r;
+                const uint32_t cnt = s_hist[wave][bin];
+                if (cnt && bin < lay.A) atomicAdd(reinterpret_cast<unsigned long long *>(dst + bin), (unsigned long long)cnt);
+            }
+        }
     }
     // the chunk's size: every lane summed the code lengths of the elements it quantized
 #pragma unroll
@@ -473,25 +495,28 @@ size_t fused_workspace_bytes(const Layout &lay)
 {
     const uint64_t cpb = (uint64_t)fused_chunks_per_workgroup(lay);
     const uint64_t nblk = (lay.nchunks + cpb - 1) / cpb;
-    // tickets (one 64-bit slot per user) and the look-back entries, plus alignment slack
-    return (size_t)(((uint64_t)lay.U + (uint64_t)lay.U * nblk) * sizeof(uint64_t) + 512);
+    // tickets (one 64-bit slot per user), the look-back entries, the partial symbol-count tables of the
+    // histogram option, plus alignment slack
+    return (size_t)(((uint64_t)lay.U + (uint64_t)lay.U * nblk + (uint64_t)kHistGlobalRep * lay.nbooks * lay.A) *
+                        sizeof(uint64_t) + 512);
 }
 
-template <bool kSR, int kCpb, int kWaves>
+template <bool kSR, int kCpb, int kWaves, bool kHist>
 static void launch_fused_waves(const Layout &lay, const co3_encode_args &a, const BookDev *books, uint32_t *tickets,
-                               uint64_t *lb_state, uint32_t nblk, hipStream_t s)
+                               uint64_t *lb_state, uint32_t nblk, uint64_t *hist_rep, hipStream_t s)
 {
-    hipLaunchKernelGGL((k_encode_fused<kSR, kCpb, kWaves>), dim3(nblk, lay.U), dim3(64 * kCpb), 0, s, lay, a.g, a.m, a.m_out,
-                       a.row_stride, a.gamma, a.seed, books, tickets, lb_state, nblk, g_spin_limit.load(), a.chunk_offset,
-                       a.sub_bits, a.payload_bits, a.words, a.words_stride, a.status);
+    hipLaunchKernelGGL((k_encode_fused<kSR, kCpb, kWaves, kHist>), dim3(nblk, lay.U), dim3(64 * kCpb), 0, s, lay, a.g, a.m,
+                       a.m_out, a.row_stride, a.gamma, a.seed, books, tickets, lb_state, nblk, g_spin_limit.load(),
+                       a.chunk_offset, a.sub_bits, a.payload_bits, a.words, a.words_stride, a.status, hist_rep);
 }
 
 template <bool kSR, int kCpb>
 static void launch_fused_variant(const Layout &lay, const co3_encode_args &a, const BookDev *books, uint32_t *tickets,
-                                 uint64_t *lb_state, uint32_t nblk, hipStream_t s)
+                                 uint64_t *lb_state, uint32_t nblk, uint64_t *hist_rep, hipStream_t s)
 {
-    if (lay.vec_aligned && !kSR) launch_fused_waves<kSR, kCpb, 5>(lay, a, books, tickets, lb_state, nblk, s);
-    else launch_fused_waves<kSR, kCpb, 4>(lay, a, books, tickets, lb_state, nblk, s);
+    if (a.hist) launch_fused_waves<kSR, kCpb, 4, true>(lay, a, books, tickets, lb_state, nblk, hist_rep, s);
+    else if (lay.vec_aligned && !kSR) launch_fused_waves<kSR, kCpb, 5, false>(lay, a, books, tickets, lb_state, nblk, hist_rep, s);
+    else launch_fused_waves<kSR, kCpb, 4, false>(lay, a, books, tickets, lb_state, nblk, hist_rep, s);
 }
 
 hipError_t launch_encode_fused(const Layout &lay, const co3_encode_args &a, const BookDev *books, hipStream_t s)
@@ -502,7 +527,9 @@ hipError_t launch_encode_fused(const Layout &lay, const co3_encode_args &a, cons
     uint64_t *base = reinterpret_cast<uint64_t *>((reinterpret_cast<uintptr_t>(a.workspace) + 255u) & ~(uintptr_t)255u);
     uint64_t *ticket_slots = base;               // [U], the low 32 bits of each are the counter
     uint64_t *lb_state = base + lay.U;           // [U][nblk]
-    const uint64_t nz = (uint64_t)lay.U + (uint64_t)lay.U * nblk;
+    uint64_t *hist_rep = lb_state + (uint64_t)lay.U * nblk;   // [kHistGlobalRep][nbooks][A], with a.hist only
+    const uint64_t hist_n = (uint64_t)lay.nbooks * lay.A;
+    const uint64_t nz = (uint64_t)lay.U + (uint64_t)lay.U * nblk + (a.hist ? (uint64_t)kHistGlobalRep * hist_n : 0);
     {
         ProfScope prof(K_ZERO, s);
         const uint64_t nmax = nz > lay.U ? nz : lay.U;
@@ -511,21 +538,27 @@ hipError_t launch_encode_fused(const Layout &lay, const co3_encode_args &a, cons
     }
     if (lay.nchunks == 0) {
         // nothing to encode: every user's stream is empty; chunk_offset[u][0] = 0
-        ProfScope prof(K_ZERO, s);
-        hipLaunchKernelGGL(k_zero_fused, dim3((lay.U + 255) / 256), dim3(256), 0, s, a.chunk_offset,
-                           (uint64_t)lay.U, a.chunk_offset, (uint64_t)0);
+        {
+            ProfScope prof(K_ZERO, s);
+            hipLaunchKernelGGL(k_zero_fused, dim3((lay.U + 255) / 256), dim3(256), 0, s, a.chunk_offset,
+                               (uint64_t)lay.U, a.chunk_offset, (uint64_t)0);
+        }
+        if (a.hist) return launch_reduce_hist(hist_rep, a.hist, hist_n, s);   // all-zero counts
         return hipGetLastError();
     }
-    ProfScope prof(K_FUSED, s);
-    uint32_t *tickets = reinterpret_cast<uint32_t *>(ticket_slots);
-    const bool sr = a.rounding == CO3_ROUND_STOCHASTIC;
-    if (cpb == kFuCpb) {
-        if (sr) launch_fused_variant<true, kFuCpb>(lay, a, books, tickets, lb_state, (uint32_t)nblk, s);
-        else launch_fused_variant<false, kFuCpb>(lay, a, books, tickets, lb_state, (uint32_t)nblk, s);
-    } else {
-        if (sr) launch_fused_variant<true, kFuCpbSmall>(lay, a, books, tickets, lb_state, (uint32_t)nblk, s);
-        else launch_fused_variant<false, kFuCpbSmall>(lay, a, books, tickets, lb_state, (uint32_t)nblk, s);
+    {
+        ProfScope prof(K_FUSED, s);
+        uint32_t *tickets = reinterpret_cast<uint32_t *>(ticket_slots);
+        const bool sr = a.rounding == CO3_ROUND_STOCHASTIC;
+        if (cpb == kFuCpb) {
+            if (sr) launch_fused_variant<true, kFuCpb>(lay, a, books, tickets, lb_state, (uint32_t)nblk, hist_rep, s);
+            else launch_fused_variant<false, kFuCpb>(lay, a, books, tickets, lb_state, (uint32_t)nblk, hist_rep, s);
+        } else {
+            if (sr) launch_fused_variant<true, kFuCpbSmall>(lay, a, books, tickets, lb_state, (uint32_t)nblk, hist_rep, s);
+            else launch_fused_variant<false, kFuCpbSmall>(lay, a, books, tickets, lb_state, (uint32_t)nblk, hist_rep, s);
+        }
     }
+    if (a.hist) return launch_reduce_hist(hist_rep, a.hist, hist_n, s);
     return hipGetLastError();
 }
 

@@ -179,6 +179,14 @@ hipError_t launch_zero_u64(uint64_t *p, uint64_t n, hipStream_t s)
     return hipGetLastError();
 }
 
+hipError_t launch_reduce_hist(const uint64_t *hist_rep, uint64_t *hist, uint64_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    ProfScope prof(K_REDUCE_HIST, s);
+    hipLaunchKernelGGL(k_reduce_hist, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0, s, hist_rep, hist, n);
+    return hipGetLastError();
+}
+
 hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, const EncodeWs &ws, hipStream_t s)
 {
     if (lay.U == 0) return hipSuccess;
@@ -194,10 +202,7 @@ hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, const En
             hipLaunchKernelGGL(k_quantize<false>, dim3((uint32_t)ntiles, lay.U), dim3(kQThreads), lds, s, lay, a.g, a.m,
                                a.m_out, a.symbols, sym_stride, a.row_stride, a.gamma, a.seed, ws.hist_rep, ws.chunk_hist, a.status);
     }
-    const uint64_t n = (uint64_t)lay.nbooks * lay.A;
-    ProfScope prof(K_REDUCE_HIST, s);
-    hipLaunchKernelGGL(k_reduce_hist, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0, s, ws.hist_rep, a.hist, n);
-    return hipGetLastError();
+    return launch_reduce_hist(ws.hist_rep, a.hist, (uint64_t)lay.nbooks * lay.A, s);
 }
 
 }  // namespace co3

@@ -28,7 +28,7 @@ def _sym_numpy(t):
 
 
 def gpu_round(plan_kwargs, g, m, gamma, mode, weights=None, words_stride=None, max_code_len=32, want_decode=True,
-              books=None, buf=None, single_sweep=False, stochastic_seed=None):
+              books=None, buf=None, single_sweep=False, stochastic_seed=None, single_sweep_hist=False):
     """One encode (+ decode + aggregate) through the binding.  Returns (dict of numpy arrays, objects).
     single_sweep: fixed code, no symbols and no histogram requested (they stay as they were)."""
     import torch
@@ -48,8 +48,10 @@ def gpu_round(plan_kwargs, g, m, gamma, mode, weights=None, words_stride=None, m
     buf.status.zero_()
     if single_sweep:  # outputs the call must overwrite
         buf.payload_bits.fill_(-1); buf.chunk_offset.fill_(-1); buf.sub_bits.fill_(-1)
+    if single_sweep_hist:
+        buf.hist.fill_(-7)   # the call must overwrite it
     B.co3_encode(plan, books, gt, mt, mt, gamma, buf, mode=mode, single_sweep=single_sweep,
-                 stochastic_seed=stochastic_seed)
+                 stochastic_seed=stochastic_seed, single_sweep_hist=single_sweep_hist)
     torch.cuda.synchronize()
     out = dict(
         m_new=mt[:, :d].cpu().numpy(), sym=_sym_numpy(buf.symbols_2d()),

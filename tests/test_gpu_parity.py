@@ -760,3 +760,59 @@ def test_wide_error_paths_capacity_nocode_corrupt():
     B.co3_decode(plan, books, buf, symbols=symd)
     torch.cuda.synchronize()
     assert int(buf.status[B.STAT_CORRUPT].item()) >= 2
+
+
+# ---- single-sweep encoder that also counts the symbols ------------------------------------------------------
+
+@pytest.mark.parametrize("per_user,seed", [(False, None), (True, None), (False, 77)])
+def test_single_sweep_with_histogram(per_user, seed):
+    # several layers at arbitrary offsets (aligned, shifted and ragged chunks), an empty layer, a shared table
+    E, M, U = 4, 2, 3
+    seg_len = [4096 * 2 + 5, 0, 4096 * 3, 777, 4096 + 4095]
+    seg_book = [0, 1, 1, 2, 0]
+    d = sum(seg_len)
+    rng = np.random.default_rng(1400 + int(per_user))
+    bias = rng.integers(12, 16, (U, len(seg_len))).astype(np.int32)
+    g = np.empty((U, d), np.float32); m = np.empty((U, d), np.float32)
+    off = 0
+    for k, n in enumerate(seg_len):
+        for u in range(U):
+            top = orc.grid(E, M, int(bias[u, k]))[-1]
+            g[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.1, top / 30)
+            m[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, top / 300)
+        off += n
+    g[1, 3:6] = [np.nan, np.inf, -1e30]
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias, seg_len=seg_len, seg_book=seg_book, per_user_books=per_user)
+    weights = gu.oracle_round(kw, g, m, 0.9)["hist"] + 1          # a held code that is not this round's
+    ref = gu.oracle_round(kw, g, m, 0.9, weights=weights, stochastic_seed=seed)
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=weights, single_sweep=True, single_sweep_hist=True,
+                          stochastic_seed=seed)
+    gu.compare_round(gpu, ref, d, single_sweep=True)
+    gu.assert_bits_equal(gpu["hist"], ref["hist"], "histogram of the single sweep")
+
+
+def test_single_sweep_with_histogram_many_workgroups_and_empty():
+    import torch
+    from paper_2204_08211_amd import binding as B
+    # the four-chunks-per-workgroup form (above 2048 workgroups) with whole, aligned chunks
+    E, M, U, d = 4, 3, 4, 4096 * 4 * 600
+    rng = np.random.default_rng(1402)
+    g = (rng.standard_normal((U, d)) * 1e-3).astype(np.float32)
+    m = np.zeros_like(g)
+    bias = 20
+    kw = dict(E=E, M=M, U=U, d=d, bias=[[bias]] * U)
+    sym = np.stack([orc.ef_step(g[u], m[u], 0.9, E, M, bias, want_q=False)[1] for u in range(U)])
+    hist = np.bincount(sym.ravel(), minlength=256).astype(np.uint64)[None, :]
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=hist + 1, single_sweep=True, single_sweep_hist=True,
+                          want_decode=False)
+    gu.assert_bits_equal(gpu["hist"], hist, "histogram of the single sweep")
+    assert int(gpu["status_encode"][6]) == 0
+    # no elements: the counts are cleared
+    plan = B.Plan(E=E, M=M, U=2, d=0, bias=[[bias]] * 2)
+    books = B.co3_build_codebook(E, M, plan.num_books, hist + 1)
+    buf = B.RoundBuffers(plan, "cuda:0")
+    z = torch.zeros((2, 4), dtype=torch.float32, device="cuda:0")
+    buf.hist.fill_(12345); buf.payload_bits.fill_(-1)
+    B.co3_encode(plan, books, z, z, z, 0.9, buf, mode=B.BOOK_FIXED, single_sweep=True, single_sweep_hist=True)
+    torch.cuda.synchronize()
+    assert not buf.hist.cpu().numpy().any() and buf.payload_bits.cpu().numpy().tolist() == [0, 0]
