@@ -191,6 +191,16 @@ int co3_model_bias_device(const co3_plan *plan, const co3_gennorm_params *params
 int co3_plan_set_bias_device(co3_plan *plan, const int32_t *bias, void *stream);
 int co3_bias_from_model(co3_format format, double mu, double alpha, double beta, int32_t *bias,
                         double *error);
+/* eq. (exp bias) of Sec. IV-A (i) with b ranging over the reals, for one parameter triple, on the host: the
+ * integer bias that carries the power-of-two part of c_scale = 2^b and the fp32 pair (gain, inv_gain) for
+ * co3_plan_set_gain that carries the rest, inv_gain = fl32(2^t) with t in [-1/2, 1/2], gain = fl32(1 / inv_gain).
+ * The same closed-form expectation as co3_bias_from_model, scanned in steps of 1/16 binade over one and a half
+ * binades to either side of the integer optimum and refined by a golden-section search.  Where no real scale
+ * lowers the expected error by more than 1e-9 (relative) - formats with many binades, layers without a model -
+ * the integer result is returned with gain = inv_gain = 1.  error (may be NULL): the expected squared error of
+ * the returned triple.                                                                                       */
+int co3_scale_from_model(co3_format format, double mu, double alpha, double beta, int32_t *bias, float *gain,
+                         float *inv_gain, double *error);
 
 /* ---- user side: Algorithm 1 lines 8-10 for all U users -----------------------------------
  * v = g + gamma m (eq. (f_error_fb)), ghat = Q_fp(v), m' = v - ghat, b = h_Hf(ghat).

@@ -26,7 +26,7 @@ EXPORTS = [
     "co3_build_codebook", "co3_build_codebook_device", "co3_codebook_export", "co3_codebook_num_books",
     "co3_codebook_destroy", "co3_encode", "co3_decode", "co3_ps_aggregate", "co3_status_string",
     "co3_profile_begin", "co3_profile_end", "co3_gennorm_weights", "co3_plan_fit_workspace_bytes", "co3_gennorm_fit",
-    "co3_model_weights_device", "co3_model_bias_device", "co3_plan_set_bias_device", "co3_bias_from_model",
+    "co3_model_weights_device", "co3_model_bias_device", "co3_plan_set_bias_device", "co3_bias_from_model", "co3_scale_from_model",
     "co3_plan_bias_workspace_bytes", "co3_set_lookback_polls", "co3_encode_static", "co3_plan_set_gain",
 ]
 
@@ -119,6 +119,8 @@ def lib():
         L.co3_plan_set_bias_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.co3_bias_from_model.argtypes = [Format, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_int32),
                                           C.POINTER(C.c_double)]
+        L.co3_scale_from_model.argtypes = [Format, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_int32),
+                                           C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_double)]
         L.co3_set_lookback_polls.argtypes = [C.c_uint32]
         L.co3_set_lookback_polls.restype = None
         L.co3_status_string.argtypes = [C.c_int]
@@ -317,6 +319,17 @@ def co3_model_bias_device(plan, params, install=True, stream=None):
     if install:
         _check("co3_plan_set_bias_device", lib().co3_plan_set_bias_device(plan.handle, bias.data_ptr(), _stream(stream)))
     return bias, err
+
+
+def co3_scale_from_model(E, M, mu, alpha, beta):
+    """eq. (exp bias) with real b on the host: (bias, gain, inv_gain, expected squared error); the pair is what
+    Plan.set_gain takes."""
+    b = C.c_int32(0)
+    gn, ig = C.c_float(1.0), C.c_float(1.0)
+    e = C.c_double(0.0)
+    _check("co3_scale_from_model", lib().co3_scale_from_model(Format(E, M), float(mu), float(alpha), float(beta),
+                                                            C.byref(b), C.byref(gn), C.byref(ig), C.byref(e)))
+    return int(b.value), float(gn.value), float(ig.value), float(e.value)
 
 
 def co3_bias_from_model(E, M, mu, alpha, beta):

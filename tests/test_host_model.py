@@ -45,3 +45,40 @@ def test_library_bias_from_model_equals_the_oracle(E, M, mu, alpha, beta):
 
 def test_library_bias_from_model_without_a_model():
     assert B.co3_bias_from_model(4, 3, 0.0, 0.0, 0.0) == (7, 0.0)
+
+
+# ---- eq. (exp bias) with real b on the host (co3_scale_from_model) -------------------------------------------
+
+@pytest.mark.parametrize("E,M,beta,sigma", [(2, 1, 1.0, 1.0), (2, 1, 0.7, 3e-3), (3, 0, 1.4, 0.2), (3, 2, 0.8, 1e-3),
+                                            (4, 3, 1.3, 5.0)])
+def test_real_valued_scale_from_model_is_the_oracles_optimum(E, M, beta, sigma):
+    import math
+    from scipy import special
+    from oracle import co3_bias_model as bm
+    alpha = sigma * math.sqrt(math.exp(special.gammaln(1.0 / beta) - special.gammaln(3.0 / beta)))   # variance sigma^2
+    bias, gain, inv_gain, err = B.co3_scale_from_model(E, M, 0.0, alpha, beta)
+    ieee = (1 << (E - 1)) - 1
+    reps = bm.signed_set(E, M, ieee)
+    b_lib = (ieee - bias) + math.log2(inv_gain)
+    # the library's triple, evaluated by the oracle, is the error the library reports ...
+    assert abs(bm.scaled_sq_error(reps, b_lib, 0.0, alpha, beta) / err - 1.0) < 1e-6
+    # ... and it is the oracle's optimum over real b, which is at least as good as the best integer
+    lo = (ieee - bias) - 3.0
+    b_opt, err_opt = bm.best_real_scale(reps, alpha, beta, lo=lo, hi=lo + 6.0)
+    assert abs(err / err_opt - 1.0) < 1e-5, (b_lib, b_opt)
+    b_int, err_int = B.co3_bias_from_model(E, M, 0.0, alpha, beta)
+    assert err <= err_int * (1 + 1e-12)
+    assert 2 ** -0.5 * (1 - 1e-6) <= inv_gain <= 2 ** 0.5 * (1 + 1e-6) and abs(gain * inv_gain - 1.0) < 1e-6
+    # the split the oracle takes for the same b gives the same integer part
+    ob, og, oi = bm.split_real_scale(E, b_lib)
+    assert ob == bias and abs(float(oi) / inv_gain - 1.0) < 1e-6
+
+
+def test_real_valued_scale_keeps_the_integer_result_where_nothing_is_gained():
+    # [1,5,2] has a plateau of biases for a narrow source; no model at all gives the IEEE bias
+    bias, gain, inv_gain, err = B.co3_scale_from_model(5, 2, 0.0, 1e-3, 1.0)
+    b_int, err_int = B.co3_bias_from_model(5, 2, 0.0, 1e-3, 1.0)
+    assert err <= err_int
+    if (gain, inv_gain) == (1.0, 1.0):
+        assert bias == b_int
+    assert B.co3_scale_from_model(4, 3, 0.0, 0.0, 0.0) == (7, 1.0, 1.0, 0.0)
