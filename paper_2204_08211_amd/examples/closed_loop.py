@@ -6,7 +6,8 @@ GenNorm model, the exponent bias (eq. (exp bias)) and the Huffman code are refre
 every `--refresh` iterations and held in between, as the paper holds them for several epochs
 (Sec. VI).  The users' gradients carry seeded noise.  Prints, per format and memory-decay
 coefficient gamma, the excess loss after T iterations, its ratio to that of uncompressed SGD on
-the same noise, and the bits per element sent (Sec. VI discusses the
+the same noise, and the bits per element sent (--real-scale: with the real-valued scale of eq. (exp bias)
+instead of the integer bias) (Sec. VI discusses the
 choice of gamma; Sec. IV-A (iii) the role of the memory).
 
 With --theorem the loop runs in the setting of Theorem 1 of the appendix instead: memory without decay
@@ -36,6 +37,8 @@ def main():
     p.add_argument("--noise", type=float, default=0.1, help="standard deviation of the noise added to every user gradient")
     p.add_argument("--eta", type=float, default=0.2)
     p.add_argument("--stochastic", action="store_true")
+    p.add_argument("--real-scale", action="store_true",
+                   help="eq. (exp bias) with real b: bias and gain of every user from co3_scale_from_model (host) at each refresh")
     p.add_argument("--theorem", action="store_true", help="sweep T in the setting of Theorem 1 (gamma 1, eta 1/sqrt(T), averaged iterate)")
     a = p.parse_args()
     dev = torch.device("cuda:0")
@@ -79,7 +82,13 @@ def main():
                 gradients(w, t, g)
                 if t % a.refresh == 0:                                  # fit -> bias -> weights -> code, all on the device
                     params = B.co3_gennorm_fit(plan, g, m, gamma)
-                    B.co3_model_bias_device(plan, params, install=True)
+                    if a.real_scale:                                    # the U argmins over real b run on the host
+                        ph = params.cpu().numpy()
+                        tr = [B.co3_scale_from_model(E, M, *ph[u, 0, :3])[:3] for u in range(U)]
+                        plan.set_bias(np.array([[x[0]] for x in tr], np.int32))
+                        plan.set_gain(np.array([[x[1]] for x in tr], np.float32), np.array([[x[2]] for x in tr], np.float32))
+                    else:
+                        B.co3_model_bias_device(plan, params, install=True)
                     B.co3_build_codebook_device(books, B.co3_model_weights_device(plan, params), buf.status)
                 B.co3_encode(plan, books, g, m, m, gamma, buf, mode=B.BOOK_FIXED, single_sweep=True,
                              stochastic_seed=(t + 1) if a.stochastic else None)
