@@ -180,6 +180,24 @@ def test_matches_float8_e5m2_cast():
     assert np.array_equal(q, ref)
 
 
+@pytest.mark.parametrize("E,bias", [(3, 3), (5, 15), (4, 9)])
+def test_m0_tie_rule_matches_the_e8m0_cast(E, bias):
+    # mant = 0: every representative is a power of two, every midpoint a tie between two one-digit significands.
+    # torch's float8_e8m0fnu (exponent-only, 2^-127 .. 2^127) is a library cast to the nearest power of two that
+    # sends those ties to the larger magnitude, the rule of reading R3.  Compared on positive inputs inside the
+    # format's normal range (e8m0 has neither sign nor zero).
+    import torch
+    if not hasattr(torch, "float8_e8m0fnu"):
+        pytest.skip("this torch has no e8m0 cast")
+    g = orc.grid(E, 0, bias)
+    x = ties_and_randoms(E, 0, bias, np.random.default_rng(40 + E), n=50000)
+    x = x[(x >= g[1]) & (x <= g[-1])]
+    assert np.isin(((g[1:-1] + g[2:]) / 2).astype(np.float32), x).all()      # every tie between two powers of two is there
+    q, _ = orc.quantize_wide(x, E, 0, bias)
+    ref = torch.from_numpy(x).to(torch.float8_e8m0fnu).to(torch.float32).numpy()
+    assert np.array_equal(q, ref)
+
+
 def test_power_of_two_bias_is_a_pure_scaling():
     # c_scale = 2^b: changing the bias by k scales every representative by 2^-k (Sec. V-B)
     x = ties_and_randoms(5, 2, 15, np.random.default_rng(4), n=20000)
