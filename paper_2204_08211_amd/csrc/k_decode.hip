@@ -58,6 +58,40 @@ __device__ inline void load_dec_tables(DecLds *T, const BookDev &book, uint32_t 
     if (t == 0) { T->nlong = book.nlong; T->long_prefix0 = book.long_prefix0; }
 }
 
+// The PS average with tables shared by the users reads one table: per prefix (direct table, then the second-level
+// tables, as one array) the code length in bits 16.. and, below, the top 16 bits of the fp32 pattern of the
+// symbol's value at exponent bias 0 (sign, exponent and 7 mantissa bits: a representative of a format of up to
+// 8 bits has at most 5).  The value for a user is that number times 2^-bias (exact), times the user's scale.
+// 0: no codeword of up to kDecBits + kDec2Bits bits under this prefix.
+constexpr int kValEntries = kDecEntries + (kDec2Tables << kDec2Bits);
+// What the rare decode path needs of a code.
+struct LongLds {
+    uint64_t long_last[kLongSlots];
+    uint32_t long_base[kLongSlots];
+    uint32_t long_len[kLongSlots];
+    uint8_t sorted[kMaxA];
+    uint32_t nlong;
+    uint32_t long_prefix0;
+};
+
+__device__ inline void load_value_tables(LongLds *T, uint32_t *val, const BookDev &book, int E, int M, uint32_t t,
+                                         uint32_t nthreads)
+{
+    for (uint32_t i = t; i < (uint32_t)kValEntries; i += nthreads) {
+        const uint32_t e = i < (uint32_t)kDecEntries ? book.dec[i] : book.dec2[i - kDecEntries];
+        const uint32_t L = e >> 8;
+        val[i] = L ? (L << 16) | (symbol_value_bits(e & 0xffu, E, M, 0) >> 16) : 0u;
+    }
+    for (uint32_t i = t; i < (uint32_t)kLongSlots; i += nthreads) {
+        T->long_last[i] = book.long_last[i];
+        T->long_base[i] = book.long_base[i];
+        T->long_len[i] = book.long_len[i];
+    }
+    for (uint32_t i = t; i < kMaxA / 4; i += nthreads)
+        reinterpret_cast<uint32_t *>(T->sorted)[i] = reinterpret_cast<const uint32_t *>(book.sorted)[i];
+    if (t == 0) { T->nlong = book.nlong; T->long_prefix0 = book.long_prefix0; }
+}
+
 __device__ inline uint32_t find_chunk_segment_d(const SegDev *segs, uint32_t nseg, uint64_t chunk)
 {
     uint32_t lo = 0, hi = nseg;
@@ -103,8 +137,8 @@ struct GlobalWords {
 // (length << 8) | symbol of the code longer than kDecBits that starts at bit `pos` of the chunk,
 // 0 if none matches.  Left-aligned canonical codes grow with their length, so the code's length
 // is the first listed one whose last code is not below the window.
-template <class Src>
-__device__ __noinline__ uint32_t long_code(Src src, const DecLds *T, uint32_t pos)
+template <class Src, class Tab>
+__device__ __noinline__ uint32_t long_code(Src src, const Tab *T, uint32_t pos)
 {
     const uint32_t i0 = pos >> 5, s0 = pos & 31u;
     uint64_t full = (((uint64_t)src.word(i0) << 32) | src.word(i0 + 1)) << s0;
@@ -163,8 +197,8 @@ struct Reader {
 // than kDecBits + kDec2Bits bits, or a stream that is not one): the window is compared with the left-aligned
 // last code of every longer length that occurs (they grow with the length).  Lengths up to 32 are consumed by
 // the caller; longer ones take the exact path, which repositions the reader itself and leaves L = 0.
-template <class Src>
-__device__ inline void decode_symbol_long(Reader<Src> &r, const DecLds *T, uint64_t win, uint32_t &L, uint32_t &s, bool &bad)
+template <class Src, class Tab>
+__device__ inline void decode_symbol_long(Reader<Src> &r, const Tab *T, uint64_t win, uint32_t &L, uint32_t &s, bool &bad)
 {
     if (L != 0u) return;
     const uint32_t n = T->nlong;
@@ -270,6 +304,48 @@ __device__ inline uint32_t decode_subchunk(Src src, uint32_t p0, int cnt, const 
             sink.commit(j, sy, sink.fetch(sy));
         }
         sink.finish(cnt);
+    }
+    return bad ? ~0u : r.pos() - p0;
+}
+
+// The PS average's decoder for tables shared by the users: one look-up per symbol gives its length and its value
+// (see kValEntries), which goes straight to the element's fp64 sum in LDS.  nbias = -bias of the user and layer.
+template <class Src>
+__device__ inline uint32_t decode_subchunk_acc(Src src, uint32_t p0, int cnt, const LongLds *T, const uint32_t *val,
+                                               int E, int M, int nbias, float inv_gain, double *row)
+{
+    Reader<Src> r;
+    r.src = src;
+    r.seek(p0);
+    bool bad = false;
+    const uint32_t lp0 = T->long_prefix0;   // read once: the LDS atomics would make the compiler reload it
+    auto one = [&](int j) {
+        const uint32_t win = r.window32();
+        const uint32_t i1 = win >> (32 - kDecBits);
+        const uint32_t i2 = (uint32_t)kDecEntries + (win >> (32 - kDecBits - kDec2Bits)) - (lp0 << kDec2Bits);
+        const uint32_t idx = (i1 - lp0 < (uint32_t)kDec2Tables) ? i2 : i1;   // unsigned: false below lp0
+        uint32_t nextw = r.src.next(r.wi);
+        uint32_t e = val[idx];
+        asm volatile("" : "+v"(nextw), "+v"(e));
+        uint32_t L = e >> 16;
+        float v = __fmul_rn(ldexpf(__uint_as_float(e << 16), nbias), inv_gain);
+        if (__builtin_expect(__any(L == 0u), 0)) {
+            const bool mine = L == 0u;
+            uint32_t sy = 0;
+            decode_symbol_long(r, T, r.window64(nextw), L, sy, bad);
+            if (mine) v = __fmul_rn(__uint_as_float(symbol_value_bits(sy & 0xffu, E, M, -nbias)), inv_gain);
+            asm volatile("" : "+v"(L), "+v"(v));   // the rare part waits for its own LDS reads
+        }
+        __hip_atomic_fetch_add(&row[j], (double)v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        r.advance(L, nextw);
+    };
+    if (cnt == kSub) {
+        for (int jj = 0; jj < kSub / 4; ++jj) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) one(4 * jj + b);
+        }
+    } else {
+        for (int j = 0; j < cnt; ++j) one(j);
     }
     return bad ? ~0u : r.pos() - p0;
 }
@@ -569,40 +645,80 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
 {
     extern __shared__ uint64_t smem64[];
     double *s_acc = reinterpret_cast<double *>(smem64);                    // [64][kAccStride]
-    DecLds *s_tab = reinterpret_cast<DecLds *>(s_acc + kAccWords);         // [per-user books ? W : 1]
-    const uint32_t ntab = kPerUser ? W : 1;
-    uint32_t *s_mag = reinterpret_cast<uint32_t *>(s_tab + ntab);          // [W][kMagEntries] fp32 patterns
-    uint32_t *s_pay = s_mag + W * kMagEntries;                             // [W][kPayloadAlloc]
     constexpr int T = 64 * W;
     const uint32_t t = threadIdx.x, wave = t >> 6, lane = t & 63u;
     const uint64_t c = blockIdx.x;
     const ChunkGeom g = chunk_geom(lay, c);
-    const uint32_t sign_shift = (uint32_t)(lay.E + lay.M);
-    const uint32_t mag_mask = (1u << sign_shift) - 1u;
-    const uint32_t sign_up = 31u - sign_shift;
 
     for (uint32_t i = t; i < (uint32_t)kAccWords; i += T) s_acc[i] = 0.0;
-    if (!kPerUser) load_dec_tables(s_tab, books[(uint32_t)g.book], t, T);
-    __syncthreads();
-
-    // wavefront `wave` takes users wave, wave + W, ...; everything it touches besides the sums is its own
-    uint32_t *my_mag = s_mag + wave * kMagEntries;
-    uint32_t *my_pay = s_pay + wave * kPayloadAlloc;
-    const DecLds *my_tab = kPerUser ? s_tab + wave : s_tab;
-    for (uint32_t u = wave; u < lay.U; u += W) {
-        const ChunkIndex ix = read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits);
-        if (kPerUser) load_dec_tables(s_tab + wave, books[u * lay.books_per_user + (uint32_t)g.book], lane, 64);
-        const int bias = lay.bias[(uint64_t)u * lay.nseg + g.seg];
-        const float inv_gain = lay.gain[2 * ((uint64_t)u * lay.nseg + g.seg) + 1];   // 1 unless the plan carries a scale
-        for (uint32_t k = lane; k <= mag_mask; k += 64)
-            my_mag[k] = __float_as_uint(__fmul_rn(__uint_as_float(symbol_value_bits(k, lay.E, lay.M, bias)), inv_gain));
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        decode_user_chunk(g, ix, my_tab, my_pay, AccSink{s_acc + lane * kAccStride, my_mag, mag_mask, sign_up}, status);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();   // the next user's tables and words overwrite these
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if constexpr (kPerUser) {
+        // every user its own code: per-wavefront decode tables and a per-user table of values
+        DecLds *s_tab = reinterpret_cast<DecLds *>(s_acc + kAccWords);         // [W]
+        uint32_t *s_mag = reinterpret_cast<uint32_t *>(s_tab + W);             // [W][kMagEntries] fp32 patterns
+        uint32_t *s_pay = s_mag + W * kMagEntries;                             // [W][kPayloadAlloc]
+        const uint32_t sign_shift = (uint32_t)(lay.E + lay.M);
+        const uint32_t mag_mask = (1u << sign_shift) - 1u;
+        const uint32_t sign_up = 31u - sign_shift;
+        __syncthreads();
+        // wavefront `wave` takes users wave, wave + W, ...; everything it touches besides the sums is its own
+        uint32_t *my_mag = s_mag + wave * kMagEntries;
+        uint32_t *my_pay = s_pay + wave * kPayloadAlloc;
+        const DecLds *my_tab = s_tab + wave;
+        for (uint32_t u = wave; u < lay.U; u += W) {
+            const ChunkIndex ix = read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits);
+            load_dec_tables(s_tab + wave, books[u * lay.books_per_user + (uint32_t)g.book], lane, 64);
+            const int bias = lay.bias[(uint64_t)u * lay.nseg + g.seg];
+            const float inv_gain = lay.gain[2 * ((uint64_t)u * lay.nseg + g.seg) + 1];   // 1 unless the plan carries a scale
+            for (uint32_t k = lane; k <= mag_mask; k += 64)
+                my_mag[k] = __float_as_uint(__fmul_rn(__uint_as_float(symbol_value_bits(k, lay.E, lay.M, bias)), inv_gain));
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            decode_user_chunk(g, ix, my_tab, my_pay, AccSink{s_acc + lane * kAccStride, my_mag, mag_mask, sign_up}, status);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();   // the next user's tables and words overwrite these
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+    } else {
+        // one code for all users: one table of lengths and values (at bias 0) for the workgroup
+        LongLds *s_long = reinterpret_cast<LongLds *>(s_acc + kAccWords);
+        uint32_t *s_val = reinterpret_cast<uint32_t *>(s_long + 1);            // [kValEntries]
+        uint32_t *s_pay = s_val + kValEntries;                                 // [W][kPayloadAlloc]
+        load_value_tables(s_long, s_val, books[(uint32_t)g.book], lay.E, lay.M, t, T);
+        __syncthreads();
+        uint32_t *my_pay = s_pay + wave * kPayloadAlloc;
+        const int first_elem = (int)lane * kSub;
+        const int cnt = (int)g.n - first_elem < 0 ? 0 : ((int)g.n - first_elem > kSub ? kSub : (int)g.n - first_elem);
+        for (uint32_t u = wave; u < lay.U; u += W) {
+            const ChunkIndex ix = read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits);
+            const int bias = lay.bias[(uint64_t)u * lay.nseg + g.seg];
+            const float inv_gain = lay.gain[2 * ((uint64_t)u * lay.nseg + g.seg) + 1];   // 1 unless the plan carries a scale
+            const uint32_t p0 = wave_exclusive_scan_u32(ix.sb);
+            uint32_t used = 0;
+            if (ix.in_lds) {
+                uint32_t tmp[kPayloadPerLane];
+                payload_request(ix, tmp);
+#pragma unroll
+                for (int k = 0; k < kPayloadPerLane; ++k) {
+                    const uint32_t i = lane + 64u * k;
+                    if (i < ix.nw) my_pay[i] = tmp[k];
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                if (cnt > 0)
+                    used = decode_subchunk_acc(LdsWords{my_pay}, p0, cnt, s_long, s_val, lay.E, lay.M, -bias, inv_gain,
+                                               s_acc + lane * kAccStride);
+            } else if (cnt > 0) {
+                used = decode_subchunk_acc(GlobalWords{ix.w, ix.nw}, p0, cnt, s_long, s_val, lay.E, lay.M, -bias, inv_gain,
+                                           s_acc + lane * kAccStride);
+            }
+            if (used != ix.sb || !ix.ok)
+                atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CORRUPT), 1ull);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();   // the next user's words overwrite these
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
     }
     __syncthreads();
 
@@ -664,8 +780,10 @@ template <int W, bool kPerUser>
 static hipError_t launch_aggregate_wp(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
                                       hipStream_t s)
 {
-    const size_t lds = (size_t)kAccWords * sizeof(double) + (size_t)(kPerUser ? W : 1) * sizeof(DecLds) +
-                       (size_t)W * (kMagEntries + kPayloadAlloc) * 4;
+    const size_t lds = kPerUser ? (size_t)kAccWords * sizeof(double) + (size_t)W * sizeof(DecLds) +
+                                      (size_t)W * (kMagEntries + kPayloadAlloc) * 4
+                                : (size_t)kAccWords * sizeof(double) + sizeof(LongLds) +
+                                      ((size_t)kValEntries + (size_t)W * kPayloadAlloc) * 4;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_aggregate<W, kPerUser>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
