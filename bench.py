@@ -61,6 +61,9 @@ def parse():
                    help="encoder for --book model: the single-sweep kernel (symbols never stored) or the three-step one")
     p.add_argument("--stochastic", action="store_true",
                    help="stochastic fp conversion (dithered Q) instead of the closest representative; a new seed per step")
+    p.add_argument("--row-align", type=int, default=32,
+                   help="users' rows of g and m start at multiples of this many elements (the library asks for a multiple "
+                        "of 4; 32 = 128 bytes keeps every 16 KB chunk on cache-line boundaries)")
     p.add_argument("--sweep-hist", action="store_true",
                    help="the single-sweep encoder also counts the symbols (histogram output with a held code)")
     p.add_argument("--per-user-books", action="store_true", help="every user its own code tables instead of pooled ones")
@@ -135,7 +138,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     U, d = w.U, w.d
-    stride = (d + 3) // 4 * 4
+    stride = (d + a.row_align - 1) // a.row_align * a.row_align   # elements between users' rows (the library asks for a multiple of 4)
     nseg = len(w.seg_len)
     seg_book = list(range(nseg)) if nseg > 1 else [0]
     seg_off = np.concatenate([[0], np.cumsum(w.seg_len)]).astype(np.int64)

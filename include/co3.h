@@ -225,7 +225,8 @@ typedef struct {
     const float *g;          /* device [U][row_stride] gradients; 16-byte aligned            */
     const float *m;          /* device [U][row_stride] memory m_{t-1}                        */
     float *m_out;            /* device [U][row_stride] memory m_t; may equal m               */
-    uint64_t row_stride;     /* elements between users, >= d, multiple of 4                  */
+    uint64_t row_stride;     /* elements between users, >= d, multiple of 4 (a multiple of  */
+                             /* 32 keeps the 16 KB chunks on 128-byte lines: a few % faster) */
     float gamma;             /* memory-decay coefficient                                     */
     int32_t mode;            /* CO3_BOOK_FIXED or CO3_BOOK_EMPIRICAL                         */
     co3_codebook *books;     /* set with co3_plan_num_books() tables                         */

@@ -95,7 +95,7 @@ def run_workload(name, full_users, n_random_chunks, full_words_limit=40_000_000,
     dev = torch.device("cuda:0")
     U, d, E, M = w.U, w.d, w.E, w.M
     A = 1 << (1 + E + M)
-    stride = (d + 3) // 4 * 4
+    stride = (d + 31) // 32 * 32     # rows on 128-byte boundaries, as bench.py lays them out
     seg_len = w.seg_len
     nseg = len(seg_len)
     seg_book = list(range(nseg)) if nseg > 1 else [0]
