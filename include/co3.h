@@ -115,7 +115,7 @@ uint64_t co3_plan_num_chunks(const co3_plan *plan);     /* chunks per user      
 uint32_t co3_plan_num_books(const co3_plan *plan);      /* tables in a matching set         */
 uint32_t co3_plan_alphabet(const co3_plan *plan);       /* A = 2^(1+exp_bits+mant_bits)     */
 /* bytes of the `symbols` buffer of co3_encode_args / co3_decode_args: U rows of d symbols, each row
- * padded to a multiple of 16 symbols, plus 16 symbols; one byte per symbol (two for wide alphabets) */
+ * padded to a multiple of 128 symbols, plus 16 symbols; one byte per symbol (two for wide alphabets) */
 size_t co3_plan_symbols_bytes(const co3_plan *plan);
 /* bytes of the `workspace` buffer of co3_encode_args                                       */
 size_t co3_plan_workspace_bytes(const co3_plan *plan);

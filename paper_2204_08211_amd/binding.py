@@ -194,7 +194,7 @@ class Plan:
         self.A = int(lib().co3_plan_alphabet(h))
         self.symbols_bytes = int(lib().co3_plan_symbols_bytes(h))
         self.workspace_bytes = int(lib().co3_plan_workspace_bytes(h))
-        self.sym_stride = (self.d + 15) // 16 * 16
+        self.sym_stride = (self.d + 127) // 128 * 128
         self.wide = self.A > 256          # alphabets above 8 bits: 16-bit symbols
 
     def set_bias(self, bias, stream=None):

@@ -229,7 +229,7 @@ uint32_t co3_plan_alphabet(const co3_plan *plan) { return plan ? plan->lay.A : 0
 size_t co3_plan_symbols_bytes(const co3_plan *plan)
 {
     if (!plan) return 0;
-    const uint64_t stride = (plan->lay.d + 15) & ~(uint64_t)15;
+    const uint64_t stride = symbol_row_stride(plan->lay.d);
     return (size_t)(stride * plan->lay.U + 16) * (plan->lay.wide ? 2u : 1u);   // 16-bit symbols above 8 bits
 }
 

@@ -20,6 +20,10 @@ constexpr int kDecEntries = 1 << kDecBits;
 constexpr int kLongSlots = 64 - kDecBits;  // lengths kDecBits+1 .. 64
 constexpr int kDec2Bits = 3;        // second-level tables resolve codes of up to kDecBits + kDec2Bits bits
 constexpr int kDec2Tables = 40;     // for the first prefixes that hold only longer codes (they are the largest ones)
+// Symbols between two users' rows of a symbol buffer: the row length rounded up to 128 symbols, so that rows
+// start on 128-byte lines (of a 256-byte-aligned buffer).
+inline uint64_t symbol_row_stride(uint64_t d) { return (d + 127) & ~(uint64_t)127; }
+
 constexpr int kHistGlobalRep = 64;   // copies of the global symbol-count table the workgroups spread over
 constexpr int kFastLen = 24;        // longest code held in the 32-bit encode entry
 constexpr uint32_t kFastSlow = 0xFFu;  // length field marking "use the 64-bit table"

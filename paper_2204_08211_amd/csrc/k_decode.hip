@@ -763,7 +763,7 @@ __global__ __launch_bounds__(64 * W) void k_aggregate(Layout lay, const uint32_t
 hipError_t launch_decode(const Layout &lay, const co3_decode_args &a, const BookDev *books, hipStream_t s)
 {
     if (lay.U == 0 || lay.nchunks == 0) return hipSuccess;
-    const uint64_t sym_stride = (lay.d + 15) & ~(uint64_t)15;
+    const uint64_t sym_stride = symbol_row_stride(lay.d);
     const size_t lds = (size_t)(lay.per_user_books ? kDecWaves : 1) * sizeof(DecLds) +
                        (size_t)kDecWaves * (kStageWords + kPayloadAlloc) * 4;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_decode),

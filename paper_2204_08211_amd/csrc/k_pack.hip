@@ -275,7 +275,7 @@ hipError_t launch_pack(const Layout &lay, const co3_encode_args &a, const BookDe
                        hipStream_t s)
 {
     if (lay.U == 0) return hipSuccess;
-    const uint64_t sym_stride = (lay.d + 15) & ~(uint64_t)15;
+    const uint64_t sym_stride = symbol_row_stride(lay.d);
     const uint32_t gx = (uint32_t)((lay.nchunks + kPkWaves - 1) / kPkWaves);
     if (lay.nchunks) {
         ProfScope prof(K_CHUNK_BITS, s);

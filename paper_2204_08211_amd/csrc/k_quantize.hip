@@ -191,7 +191,7 @@ hipError_t launch_quantize(const Layout &lay, const co3_encode_args &a, const En
 {
     if (lay.U == 0) return hipSuccess;
     const uint64_t ntiles = (lay.d + kQTile - 1) / kQTile;
-    const uint64_t sym_stride = (lay.d + 15) & ~(uint64_t)15;
+    const uint64_t sym_stride = symbol_row_stride(lay.d);
     const size_t lds = (size_t)lay.A * kHistRep * sizeof(uint32_t);
     if (lay.d) {  // a vector without elements still gets its (all-zero) symbol counts from the fold below
         ProfScope prof(K_QUANTIZE, s);

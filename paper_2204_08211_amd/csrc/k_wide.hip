@@ -551,7 +551,7 @@ static inline size_t w_up256(size_t x) { return (x + 255) & ~(size_t)255; }
 // partial symbol counts, chunk sizes, and (for a fixed code without a symbol buffer) the symbols and their counts
 size_t wide_workspace_bytes(const Layout &lay)
 {
-    const size_t sym_stride = ((size_t)lay.d + 15) & ~(size_t)15;
+    const size_t sym_stride = (size_t)symbol_row_stride(lay.d);
     return w_up256((size_t)kHistGlobalRep * lay.nbooks * lay.A * sizeof(uint64_t)) +
            w_up256((size_t)lay.U * lay.nchunks * sizeof(uint32_t)) + w_up256((size_t)lay.nbooks * lay.A * sizeof(uint64_t)) +
            w_up256(sym_stride * lay.U * sizeof(uint16_t) + 32) + 512;
@@ -574,7 +574,7 @@ hipError_t launch_encode_wide(const Layout &lay, const co3_encode_args &a, BookW
                               hipStream_t s)
 {
     if (lay.U == 0) return hipSuccess;
-    const uint64_t sym_stride = (lay.d + 15) & ~(uint64_t)15;
+    const uint64_t sym_stride = symbol_row_stride(lay.d);
     const uint64_t hist_n = (uint64_t)lay.nbooks * lay.A, hist_rep_n = (uint64_t)kHistGlobalRep * hist_n;
     uintptr_t p = (reinterpret_cast<uintptr_t>(workspace) + 255u) & ~(uintptr_t)255u;
     uint64_t *hist_rep = reinterpret_cast<uint64_t *>(p);
@@ -622,7 +622,7 @@ hipError_t launch_encode_wide(const Layout &lay, const co3_encode_args &a, BookW
 hipError_t launch_decode_wide(const Layout &lay, const co3_decode_args &a, const BookWide *books, hipStream_t s)
 {
     if (lay.U == 0 || lay.nchunks == 0) return hipSuccess;
-    const uint64_t sym_stride = (lay.d + 15) & ~(uint64_t)15;
+    const uint64_t sym_stride = symbol_row_stride(lay.d);
     ProfScope prof(K_DECODE, s);
     hipLaunchKernelGGL(k_decode_wide, dim3((uint32_t)lay.nchunks, (lay.U + kWWaves - 1) / kWWaves), dim3(kWThreads), 0, s,
                        lay, a.words, a.words_stride, a.chunk_offset, a.sub_bits, books,
