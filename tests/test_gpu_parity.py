@@ -816,3 +816,28 @@ def test_single_sweep_with_histogram_many_workgroups_and_empty():
     B.co3_encode(plan, books, z, z, z, 0.9, buf, mode=B.BOOK_FIXED, single_sweep=True, single_sweep_hist=True)
     torch.cuda.synchronize()
     assert not buf.hist.cpu().numpy().any() and buf.payload_bits.cpu().numpy().tolist() == [0, 0]
+
+
+@pytest.mark.parametrize("U", [5, 9])
+def test_long_codes_through_the_many_user_average(U):
+    # codes of up to 63 bits decoded by the PS kernel for five or more users (rare path: boundary search and the
+    # exact 64-bit window), different biases per user, a ragged last chunk
+    E, M, d = 4, 1, 4096 * 2 + 1500
+    A = 64
+    nm = orc.num_magnitudes(E, M)
+    emit = np.array([s for s in range(A) if (s & 31) < nm and s != 32])
+    w = np.zeros(A, np.uint64)
+    w[emit] = np.array([1] + [1 << i for i in range(emit.size - 1)], np.uint64)
+    rng = np.random.default_rng(1500 + U)
+    bias = rng.integers(12, 20, (U, 1)).astype(np.int32)
+    g = np.empty((U, d), np.float32)
+    for u in range(U):
+        grid = orc.grid(E, M, int(bias[u, 0]))
+        k = rng.integers(0, nm, d)
+        g[u] = (grid[k] * rng.choice([-1.0, 1.0], d)).astype(np.float32)
+    m = np.zeros_like(g)
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias)
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=w[None, :], max_code_len=64)
+    ref = gu.oracle_round(kw, g, m, 0.9, weights=w[None, :])
+    assert ref["lens"].max() >= 57
+    gu.compare_round(gpu, ref, d)
