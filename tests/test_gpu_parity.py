@@ -508,11 +508,11 @@ def test_tiny_vectors_both_encoders(d):
 
 # ---- real-valued scale on top of the integer bias (eq. (exp bias) with b in R) --------------------
 
-def _gain_case(single_sweep):
+def _gain_case(single_sweep, U=3):
     import torch
     from oracle import co3_bias_model as bm
     from paper_2204_08211_amd import binding as B
-    E, M, U = 4, 3, 3
+    E, M = 4, 3
     seg_len = [4096 * 2 + 77, 0, 4096 * 3, 1000]
     seg_book = [0, 1, 1, 0]
     nseg = len(seg_len)
@@ -598,9 +598,10 @@ def _gain_case(single_sweep):
     gu.assert_bits_equal(buf.symbols_2d()[1, :n0].cpu().numpy(), so, "symbols with the scale switched off")
 
 
-@pytest.mark.parametrize("single_sweep", [False, True])
-def test_real_valued_scale_both_encoders(single_sweep):
-    _gain_case(single_sweep)
+@pytest.mark.parametrize("single_sweep,U", [(False, 3), (True, 3), (True, 7)])
+def test_real_valued_scale_both_encoders(single_sweep, U):
+    # U = 7: the PS average takes the kernel for five or more users (values scaled from one table)
+    _gain_case(single_sweep, U)
 
 
 # ---- alphabets wider than one byte (9 to 12 symbol bits, 16-bit symbols) ---------------------------------
