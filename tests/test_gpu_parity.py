@@ -842,3 +842,24 @@ def test_long_codes_through_the_many_user_average(U):
     ref = gu.oracle_round(kw, g, m, 0.9, weights=w[None, :])
     assert ref["lens"].max() >= 57
     gu.compare_round(gpu, ref, d)
+
+
+def test_extreme_biases_through_the_many_user_average():
+    # the PS kernel for five or more users forms a value as (pattern at bias 0) x 2^-bias: at bias 127 the format's
+    # subnormal row lies in fp32's denormal range, at the other end the values reach 2^100; biases of the users a
+    # few apart, so that the fp64 sums stay exact
+    E, M, d = 4, 3, 4096 + 777
+    for base in (127 - 5, (2 ** E - 2) - 100):
+        U = 6
+        rng = np.random.default_rng(1600 + base % 97)
+        bias = (base + rng.integers(0, 6, (U, 1))).astype(np.int32)
+        g = np.empty((U, d), np.float32); m = np.empty((U, d), np.float32)
+        for u in range(U):
+            b = int(bias[u, 0])
+            top = orc.grid(E, M, b)[-1]
+            g[u] = (rng.standard_normal(d) * top / 3).astype(np.float32)
+            g[u, :1500] = gu.special_values(E, M, b, rng, 1500)
+            m[u] = (rng.standard_normal(d) * top / 8).astype(np.float32)
+        kw = dict(E=E, M=M, U=U, d=d, bias=bias)
+        gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL)
+        gu.compare_round(gpu, gu.oracle_round(kw, g, m, 0.9), d)
