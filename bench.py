@@ -66,6 +66,9 @@ def parse():
                         "of 4; 32 = 128 bytes keeps every 16 KB chunk on cache-line boundaries)")
     p.add_argument("--sweep-hist", action="store_true",
                    help="the single-sweep encoder also counts the symbols (histogram output with a held code)")
+    p.add_argument("--format", default=None, metavar="E,M",
+                   help="run the workload in the format [1, E, M] instead of its own; an alphabet of more than 8 bits "
+                        "takes the library's 16-bit-symbol path, which has no model code: empirical tables only")
     p.add_argument("--per-user-books", action="store_true", help="every user its own code tables instead of pooled ones")
     p.add_argument("--graph", action="store_true",
                    help="replay the step from HIP graphs (one per gradient set of the pool) instead of launching eagerly")
@@ -132,6 +135,13 @@ def main():
     w = syn.WORKLOADS[a.workload]
     if a.per_user_books:
         w = dataclasses.replace(w, per_user_books=True)
+    wide = False
+    if a.format:
+        E, M = (int(x) for x in a.format.split(","))
+        w = dataclasses.replace(w, E=E, M=M, name=f"{w.name} in [1,{E},{M}]")
+        wide = 1 + E + M > 8
+        if wide:
+            a.book, a.no_other_book, a.no_gamma_sweep = "empirical", True, True
     sweep_gammas = [] if (a.gamma is not None or a.no_gamma_sweep) else [x for x in w.gammas if x != w.gamma]
     if a.gamma is not None:
         w = dataclasses.replace(w, gamma=a.gamma)
@@ -234,7 +244,7 @@ def main():
         per_launch = {k: v[0] / v[1] for k, v in kt.items()}
         enc_ms = sum(kt[k][0] for k in ENC_KERNELS if k in kt) / ksteps
         dec_ms = kt["k_aggregate"][0] / ksteps
-        enc_alg = (12.0 + bpe / 8.0) * elems
+        enc_alg = (12.0 + bpe / 8.0) * elems   # read g, read m, write m', write codewords
         return dict(ms_per_step=ms_per_step, kt=kt, per_launch=per_launch, bpe=bpe, status=status,
                     summary={
                         "book": label, "ms_per_step": round(ms_per_step, 4),
@@ -310,10 +320,11 @@ def main():
 
     head = runs[a.book]
     kt, per_launch, bpe = head["kt"], head["per_launch"], head["bpe"]
+    sb = 2.0 if wide else 1.0             # bytes of a stored symbol
     alg_bytes = {  # algorithmic bytes per element of each kernel
-        "k_quantize": 13.0,               # read g, read m, write m', write symbol
-        "k_chunk_bits": 1.0,              # read symbol
-        "k_pack": 1.0 + bpe / 8.0,        # read symbol, write codewords
+        "k_quantize": 12.0 + sb,          # read g, read m, write m', write symbol
+        "k_chunk_bits": sb,               # read symbol
+        "k_pack": sb + bpe / 8.0,         # read symbol, write codewords
         "k_aggregate": bpe / 8.0 + 4.0 / U,
         "k_encode_fused": 12.0 + bpe / 8.0,   # read g, read m, write m', write codewords
     }
@@ -345,7 +356,7 @@ def main():
         "metric": "CO3 encode+decode GElem/s and % HBM roofline on 1 MI355X; bits/element",
         "value": head["summary"]["gelem_s"], "unit": "GElem/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": head["summary"]["ms_per_step"],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32+u8",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32+u16" if wide else "f32+u8",
         "data": "synthetic GenNorm gradients (seeded torch device generator; recipe in co3_synth.py)",
         "config": {"workload": f"{w.name}: U={U} d={d} [1,{w.E},{w.M}] gamma={w.gamma} nseg={nseg} book={a.book} "
                                f"({'per-user' if w.per_user_books else 'pooled over users'})",

@@ -7,7 +7,7 @@
 // lane, plain loops.  A fixed code without a symbol buffer ("single sweep" in the byte path) runs the same
 // three steps here with the symbols kept in the workspace.
 //
-//   k_quantize_wide      v = g + gamma m, Q_fp, m' = v - ghat, symbol; symbol counts by global atomics
+//   k_quantize_wide      v = g + gamma m, Q_fp, m' = v - ghat, symbol; symbol counts in an LDS table per workgroup
 //   k_build_books_wide   Huffman code of a table on the device (same tie rule and canonical form as the host's)
 //   k_chunk_bits_wide    code lengths summed per chunk
 //   (k_scan_chunks of k_pack.hip gives the chunk offsets)
@@ -22,12 +22,12 @@
 namespace co3 {
 
 constexpr int kWqThreads = 256;
-constexpr int kWqPer = 4;                        // elements per thread
+constexpr int kWqPer = 8;                        // elements per thread and tile
 constexpr int kWqTile = kWqThreads * kWqPer;
 constexpr int kWWaves = 4;                       // wavefronts per workgroup of the chunk kernels
 constexpr int kWThreads = 64 * kWWaves;
 constexpr int kWSymRow = kSub + 2;               // a sub-chunk's 64 staged symbols + pad (16-bit units)
-constexpr int kWWin = 1024;                      // words of the pack window (8 bit/element per pass)
+constexpr int kWWin = 1536;                      // words of the pack window (12 bit/element per pass)
 constexpr int kWbThreads = 1024;                 // threads of the table builder
 
 __device__ inline uint32_t w_find_segment(const SegDev *segs, uint32_t nseg, uint64_t elem)
@@ -95,14 +95,19 @@ __device__ inline WChunk w_chunk(const Layout &lay, uint64_t c, uint32_t u)
 
 // ---- user side, step 1 ------------------------------------------------------------------------------------
 
+// A workgroup takes kWqTiles consecutive tiles of one user and counts their symbols in an LDS table of the code
+// table in use (A entries), which it adds to one of the global partial tables when the code table changes (a layer
+// with another table begins) and at its end; the few elements of a tile that belong to another table than the
+// tile's first element are counted in global memory directly.
+constexpr int kWqTiles = 32;
 __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const float *__restrict__ g, const float *m,
                                                               float *m_out, uint16_t *__restrict__ sym,
                                                               uint64_t sym_stride, uint64_t row_stride, float gamma,
                                                               uint64_t *__restrict__ hist_rep,
                                                               uint64_t *__restrict__ status)
 {
+    __shared__ uint32_t s_hist[kWideMaxA];
     const uint32_t u = blockIdx.y;
-    const uint64_t base = (uint64_t)blockIdx.x * kWqTile;
     const float *gu = g + (uint64_t)u * row_stride;
     const float *mu = m + (uint64_t)u * row_stride;
     float *mo = m_out + (uint64_t)u * row_stride;
@@ -110,29 +115,61 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
     const uint32_t book_base = lay.per_user_books ? u * lay.books_per_user : 0u;
     uint64_t *hist = hist_rep + (uint64_t)(blockIdx.x % kHistGlobalRep) * lay.nbooks * lay.A;
     const uint32_t sign_shift = lay.E + lay.M;
-    const uint32_t seg0 = w_find_segment(lay.segs, lay.nseg, base);
     uint32_t n_nonfinite = 0, n_clamped = 0;
-    for (int k = 0; k < kWqPer; ++k) {
-        const uint64_t i = base + (uint64_t)k * kWqThreads + threadIdx.x;
-        if (i >= lay.d) break;
-        uint32_t s_i = seg0;
-        while (i >= lay.segs[s_i + 1].offset) ++s_i;   // ends: segs[nseg].offset = d > i
-        const uint64_t pair = (uint64_t)u * lay.nseg + s_i;
-        const int bias = lay.bias[pair];
-        const QConst qc = make_qconst(lay.E, lay.M, bias);
-        const float v = __fadd_rn(gu[i], __fmul_rn(gamma, mu[i]));
-        const float y = __fmul_rn(v, lay.gain[2 * pair]);
-        uint32_t s, flags;
-        float q;
-        quantize(y, qc, sign_shift, s, q, flags);
-        q = __fmul_rn(q, lay.gain[2 * pair + 1]);
-        mo[i] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
-        n_nonfinite += flags & 1u;
-        n_clamped += (flags >> 1) & 1u;
-        su[i] = (uint16_t)s;
-        atomicAdd(reinterpret_cast<unsigned long long *>(hist + (uint64_t)(book_base + lay.segs[s_i].book) * lay.A + s),
-                  1ull);
+    for (uint32_t i = threadIdx.x; i < lay.A; i += kWqThreads) s_hist[i] = 0u;
+    __syncthreads();
+    auto flush = [&](uint32_t book) {   // between two workgroup barriers
+        for (uint32_t i = threadIdx.x; i < lay.A; i += kWqThreads) {
+            const uint32_t c = s_hist[i];
+            if (c) atomicAdd(reinterpret_cast<unsigned long long *>(hist + (uint64_t)book * lay.A + i), (unsigned long long)c);
+            s_hist[i] = 0u;
+        }
+    };
+    uint32_t cur_book = 0xffffffffu;   // workgroup-uniform
+    for (int tile = 0; tile < kWqTiles; ++tile) {
+        const uint64_t base = ((uint64_t)blockIdx.x * kWqTiles + (uint64_t)tile) * kWqTile;
+        if (base >= lay.d) break;      // workgroup-uniform
+        const uint32_t seg0 = w_find_segment(lay.segs, lay.nseg, base);
+        const uint32_t tile_book = book_base + (uint32_t)lay.segs[seg0].book;
+        if (tile_book != cur_book) {
+            __syncthreads();
+            if (cur_book != 0xffffffffu) flush(cur_book);
+            __syncthreads();
+            cur_book = tile_book;
+        }
+        float gv[kWqPer], mv[kWqPer];   // the tile's loads are issued together
+#pragma unroll
+        for (int k = 0; k < kWqPer; ++k) {
+            const uint64_t i = base + (uint64_t)k * kWqThreads + threadIdx.x;
+            gv[k] = i < lay.d ? __builtin_nontemporal_load(gu + i) : 0.0f;
+            mv[k] = i < lay.d ? mu[i] : 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < kWqPer; ++k) {
+            const uint64_t i = base + (uint64_t)k * kWqThreads + threadIdx.x;
+            if (i >= lay.d) break;
+            uint32_t s_i = seg0;
+            while (i >= lay.segs[s_i + 1].offset) ++s_i;   // ends: segs[nseg].offset = d > i
+            const uint64_t pair = (uint64_t)u * lay.nseg + s_i;
+            const int bias = lay.bias[pair];
+            const QConst qc = make_qconst(lay.E, lay.M, bias);
+            const float v = __fadd_rn(gv[k], __fmul_rn(gamma, mv[k]));
+            const float y = __fmul_rn(v, lay.gain[2 * pair]);
+            uint32_t s, flags;
+            float q;
+            quantize(y, qc, sign_shift, s, q, flags);
+            q = __fmul_rn(q, lay.gain[2 * pair + 1]);
+            mo[i] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
+            n_nonfinite += flags & 1u;
+            n_clamped += (flags >> 1) & 1u;
+            su[i] = (uint16_t)s;
+            const uint32_t book = book_base + (uint32_t)lay.segs[s_i].book;
+            if (book == cur_book) atomicAdd(&s_hist[s & (kWideMaxA - 1)], 1u);
+            else atomicAdd(reinterpret_cast<unsigned long long *>(hist + (uint64_t)book * lay.A + s), 1ull);
+        }
     }
+    __syncthreads();
+    if (cur_book != 0xffffffffu) flush(cur_book);
     if (n_nonfinite)
         atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NONFINITE), (unsigned long long)n_nonfinite);
     if (n_clamped)
@@ -289,21 +326,57 @@ __global__ __launch_bounds__(kWbThreads) void k_build_books_wide(BookWide *__res
 
 // ---- user side, steps 2 and 3 -------------------------------------------------------------------------------
 
+// Both chunk kernels give a workgroup kWChunksPerWg consecutive chunks of one user (wavefront w takes chunks
+// w, w + kWWaves, ...) and keep the code table of the workgroup's first chunk in LDS; a chunk of another table
+// (a layer boundary inside the workgroup's range) reads its table from global memory instead.
+constexpr int kWChunksPerWave = 8;
+constexpr int kWChunksPerWg = kWWaves * kWChunksPerWave;
+constexpr uint32_t kWFastCodeBits = 25;   // s_fast entry: length << 25 | codeword, for lengths up to 25
+constexpr int kWSymWave = kSubsPerChunk * kWSymRow + 2;   // 16-bit units of a wavefront's staged chunk: 64 rows + one word
+constexpr int kWSymLoads = (kChunk / 2 + 1 + 63) / 64;    // dword loads per lane to cover a chunk at any 2-byte offset (33)
+constexpr uint32_t kWSymMask2 = (uint32_t)(kWideMaxA - 1) * 0x10001u;
+constexpr size_t kWPackLds = sizeof(uint32_t) * (kWideMaxA + kWWaves * (kWWin + 1)) +
+                             sizeof(uint16_t) * kWWaves * kWSymWave;   // 74.4 KB: two workgroups per CU
+
 __global__ __launch_bounds__(kWThreads) void k_chunk_bits_wide(Layout lay, const uint16_t *__restrict__ sym,
                                                               uint64_t sym_stride, const BookWide *__restrict__ books,
                                                               uint32_t *__restrict__ chunk_bits)
 {
+    __shared__ uint8_t s_len[kWideMaxA];
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint64_t c = (uint64_t)blockIdx.x * kWWaves + wave;
+    const uint64_t c_base = (uint64_t)blockIdx.x * kWChunksPerWg;   // < nchunks by the grid
     const uint32_t u = blockIdx.y;
-    if (c >= lay.nchunks) return;
-    const WChunk k = w_chunk(lay, c, u);
-    const uint8_t *len = books[k.book].len;
-    const uint16_t *src = sym + (uint64_t)u * sym_stride + k.e0;
-    uint32_t total = 0;
-    for (uint32_t e = lane; e < k.n; e += 64) total += len[src[e] & (kWideMaxA - 1)];
-    total = w_wave_sum(total);
-    if (lane == 0) chunk_bits[(uint64_t)u * lay.nchunks + c] = total;
+    const uint32_t wg_book = w_chunk(lay, c_base, u).book;
+    for (uint32_t i = threadIdx.x; i < (uint32_t)kWideMaxA; i += kWThreads)
+        s_len[i] = i < lay.A ? books[wg_book].len[i] : (uint8_t)0;
+    __syncthreads();
+    for (int it = 0; it < kWChunksPerWave; ++it) {
+        const uint64_t c = c_base + (uint64_t)it * kWWaves + wave;
+        if (c >= lay.nchunks) break;   // whole wavefront; no workgroup barriers below
+        const WChunk k = w_chunk(lay, c, u);
+        const uint16_t *src = sym + (uint64_t)u * sym_stride + k.e0;
+        uint32_t total = 0;
+        if (k.book == wg_book) {
+            uint32_t done = 0;
+            if ((reinterpret_cast<uintptr_t>(src) & 15u) == 0) {   // eight symbols per load
+                const uint4 *src8 = reinterpret_cast<const uint4 *>(src);
+                for (uint32_t i = lane; i < (k.n >> 3); i += 64) {
+                    const uint4 v = src8[i];
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        total += (uint32_t)s_len[w[q] & (kWideMaxA - 1)] + (uint32_t)s_len[(w[q] >> 16) & (kWideMaxA - 1)];
+                }
+                done = k.n & ~7u;
+            }
+            for (uint32_t e = done + lane; e < k.n; e += 64) total += s_len[src[e] & (kWideMaxA - 1)];
+        } else {
+            const uint8_t *len = books[k.book].len;
+            for (uint32_t e = lane; e < k.n; e += 64) total += len[src[e] & (kWideMaxA - 1)];
+        }
+        total = w_wave_sum(total);
+        if (lane == 0) chunk_bits[(uint64_t)u * lay.nchunks + c] = total;
+    }
 }
 
 __global__ __launch_bounds__(kWThreads) void k_pack_wide(Layout lay, const uint16_t *__restrict__ sym, uint64_t sym_stride,
@@ -312,76 +385,152 @@ __global__ __launch_bounds__(kWThreads) void k_pack_wide(Layout lay, const uint1
                                                         uint16_t *__restrict__ sub_bits, uint32_t *__restrict__ words,
                                                         uint64_t words_stride, uint64_t *__restrict__ status)
 {
-    __shared__ uint16_t s_sym_all[kWWaves][kSubsPerChunk * kWSymRow];
-    __shared__ uint32_t s_win_all[kWWaves][kWWin + 1];
+    extern __shared__ uint32_t wp_smem[];   // kWPackLds bytes
+    uint32_t *s_fast = wp_smem;                                                          // [kWideMaxA]
+    uint32_t *s_win_all = s_fast + kWideMaxA;                                            // [kWWaves][kWWin + 1]
+    uint16_t *s_sym_all = reinterpret_cast<uint16_t *>(s_win_all + kWWaves * (kWWin + 1));  // [kWWaves][64 rows]
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint64_t c = (uint64_t)blockIdx.x * kWWaves + wave;
+    const uint64_t c_base = (uint64_t)blockIdx.x * kWChunksPerWg;   // < nchunks by the grid
     const uint32_t u = blockIdx.y;
-    if (c >= lay.nchunks) return;  // whole wavefront; no workgroup barriers below
-    uint16_t *s_sym = s_sym_all[wave];
-    uint32_t *win = s_win_all[wave];
-    const WChunk k = w_chunk(lay, c, u);
-    const BookWide &book = books[k.book];
-    const uint16_t *src = sym + (uint64_t)u * sym_stride + k.e0;
-    for (uint32_t r = 0; r < (uint32_t)kSubsPerChunk; ++r) {   // element 64 r + lane -> row r
-        const uint32_t e = lane + 64u * r;
-        s_sym[r * kWSymRow + lane] = e < k.n ? (uint16_t)(src[e] & (kWideMaxA - 1)) : (uint16_t)0;
-    }
-    const uint64_t off = chunk_offset[(uint64_t)u * (lay.nchunks + 1) + c];
-    w_wave_sync_lds();
-    const int first = (int)lane * kSub;
-    const int cnt = (int)k.n - first < 0 ? 0 : ((int)k.n - first > kSub ? kSub : (int)k.n - first);
-    const uint16_t *row = s_sym + lane * kWSymRow;
-    uint32_t bits = 0, nocode = 0;
-    for (int j = 0; j < cnt; ++j) {
-        const uint32_t L = book.len[row[j]];
-        nocode += L == 0u ? 1u : 0u;
-        bits += L;
-    }
-    if (nocode) atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NOCODE), (unsigned long long)nocode);
-    sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane] = (uint16_t)bits;
-    const uint32_t incl = w_wave_inclusive_scan(bits, lane);
-    const uint32_t excl = incl - bits;
-    const uint32_t chunk_total = __shfl(incl, 63, 64);
-    const uint32_t nwords = (chunk_total + 31u) >> 5;
-    const uint64_t off_words = off >> 5;
-    if (off_words + nwords > words_stride) {
-        if (lane == 0) atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CAPACITY), 1ull);
-        return;
-    }
-    uint32_t *dst = words + (uint64_t)u * words_stride + off_words;
-    for (uint32_t wbase = 0; wbase < nwords; wbase += kWWin) {
-        const uint32_t wn = nwords - wbase < (uint32_t)kWWin ? nwords - wbase : (uint32_t)kWWin;
-        for (uint32_t i = lane; i <= wn; i += 64) win[i] = 0u;
-        w_wave_sync_lds();
-        uint32_t wi = (excl >> 5) - wbase;  // window word receiving the next completed 32 bits (may start below the window)
-        uint32_t np = excl & 31u;           // bits pending in acc (the leading np bits belong to earlier lanes)
-        uint64_t acc = 0;
-        auto append = [&](uint64_t code, uint32_t L) {  // L <= 32, np < 32
-            acc = (acc << L) | code;
-            np += L;
-            if (np >= 32u) {
-                np -= 32u;
-                if (wi < wn) atomicOr(&win[wi], (uint32_t)(acc >> np));  // unsigned: false below the window
-                ++wi;
-            }
-        };
-        for (int j = 0; j < cnt; ++j) {
-            const uint32_t s = row[j];
-            uint32_t L = book.len[s];
-            if (!L) continue;
-            uint64_t code = book.code[s];
-            if (L > 32u) {
-                append(code >> 32, L - 32u);
-                code &= 0xffffffffull;
-                L = 32u;
-            }
-            append(code, L);
+    const uint32_t wg_book = w_chunk(lay, c_base, u).book;
+    for (uint32_t i = threadIdx.x; i < (uint32_t)kWideMaxA; i += kWThreads) {
+        uint32_t e = 0;
+        if (i < lay.A) {
+            const uint32_t L = books[wg_book].len[i];
+            e = L << kWFastCodeBits;
+            if (L <= kWFastCodeBits) e |= (uint32_t)books[wg_book].code[i];
         }
-        if (np && wi < wn) atomicOr(&win[wi], (uint32_t)(acc << (32u - np)));
+        s_fast[i] = e;
+    }
+    __syncthreads();
+    uint16_t *s_sym = s_sym_all + wave * kWSymWave;
+    uint32_t *win = s_win_all + wave * (kWWin + 1);
+    for (int it = 0; it < kWChunksPerWave; ++it) {
+        const uint64_t c = c_base + (uint64_t)it * kWWaves + wave;
+        if (c >= lay.nchunks) break;   // whole wavefront; wavefront-level synchronisation only below
+        const WChunk k = w_chunk(lay, c, u);
+        const BookWide &book = books[k.book];
+        const bool in_lds = k.book == wg_book;
+        const uint16_t *src = sym + (uint64_t)u * sym_stride + k.e0;
+        // The chunk's symbols, at any 2-byte offset and of any length: coalesced dwords from the 4-byte boundary
+        // below the chunk go to LDS rows of 32 + 1 words (word i of the chunk at i + i / 32), from which lane l
+        // funnels its 64 symbols (words 32 l .. 32 l + 32) into registers, two per word.
+        const uint32_t shift = (uint32_t)(reinterpret_cast<uintptr_t>(src) >> 1) & 1u;
+        const uint32_t *src32 = reinterpret_cast<const uint32_t *>(src - shift);
+        const uint32_t ndw = (shift + k.n + 1u) >> 1;      // <= kChunk / 2 + 1
+        uint32_t tmp[kWSymLoads];
+#pragma unroll
+        for (int r = 0; r < kWSymLoads; ++r) {
+            const uint32_t i = lane + 64u * r;
+            tmp[r] = i < ndw ? __builtin_nontemporal_load(src32 + i) & kWSymMask2 : 0u;
+        }
+        const uint64_t off = chunk_offset[(uint64_t)u * (lay.nchunks + 1) + c];
+        w_wave_sync_lds();   // the previous chunk's rows and window have been read
+        uint32_t *stage = reinterpret_cast<uint32_t *>(s_sym);
+#pragma unroll
+        for (int r = 0; r < kWSymLoads; ++r) {
+            const uint32_t i = lane + 64u * r;
+            if (i < (uint32_t)kChunk / 2 + 1) stage[i + (i >> 5)] = tmp[r];   // word 2048 lands at 2112
+        }
         w_wave_sync_lds();
-        for (uint32_t i = lane; i < wn; i += 64) dst[wbase + i] = win[i];
-        w_wave_sync_lds();
+        const int first = (int)lane * kSub;
+        const int cnt = (int)k.n - first < 0 ? 0 : ((int)k.n - first > kSub ? kSub : (int)k.n - first);
+        uint32_t *row32 = stage + lane * (kWSymRow / 2);
+        uint32_t symw[kSub / 2];
+        {
+            uint32_t cur = row32[0];
+#pragma unroll
+            for (int jj = 0; jj < kSub / 2; ++jj) {
+                const uint32_t nxt = row32[jj + 1 + (jj == kSub / 2 - 1 ? 1 : 0)];   // row32[32] is the row's pad
+                symw[jj] = shift ? __builtin_amdgcn_alignbit(nxt, cur, 16u) : cur;
+                cur = nxt;
+            }
+        }
+        uint32_t bits = 0, nocode = 0;
+        // With the table in LDS both passes are unrolled so that the table look-ups overlap; codes longer than
+        // kWFastCodeBits send the chunk down the plain loops, which read the symbols from the LDS rows.
+        bool unrolled = in_lds;
+        if (in_lds) {
+            uint32_t maxlen = 0;
+#pragma unroll
+            for (int jj = 0; jj < kSub / 2; ++jj) {
+                const uint32_t l0 = s_fast[symw[jj] & 0xffffu] >> kWFastCodeBits;
+                const uint32_t l1 = s_fast[symw[jj] >> 16] >> kWFastCodeBits;
+                const bool h0 = 2 * jj < cnt, h1 = 2 * jj + 1 < cnt;
+                nocode += (h0 && l0 == 0u ? 1u : 0u) + (h1 && l1 == 0u ? 1u : 0u);
+                bits += (h0 ? l0 : 0u) + (h1 ? l1 : 0u);
+                maxlen = max(maxlen, max(h0 ? l0 : 0u, h1 ? l1 : 0u));
+            }
+            unrolled = !__any(maxlen > kWFastCodeBits);
+        }
+        const uint16_t *row = s_sym + lane * kWSymRow;
+        if (!unrolled) {   // whole wavefront
+            w_wave_sync_lds();   // every lane has read its words, the next row's first word included
+#pragma unroll
+            for (int jj = 0; jj < kSub / 2; ++jj) row32[jj] = symw[jj];
+            w_wave_sync_lds();
+            bits = 0; nocode = 0;
+            for (int j = 0; j < cnt; ++j) {
+                const uint32_t L = book.len[row[j]];
+                nocode += L == 0u ? 1u : 0u;
+                bits += L;
+            }
+        }
+        if (nocode) atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NOCODE), (unsigned long long)nocode);
+        sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane] = (uint16_t)bits;
+        const uint32_t incl = w_wave_inclusive_scan(bits, lane);
+        const uint32_t excl = incl - bits;
+        const uint32_t chunk_total = __shfl(incl, 63, 64);
+        const uint32_t nwords = (chunk_total + 31u) >> 5;
+        const uint64_t off_words = off >> 5;
+        if (off_words + nwords > words_stride) {   // whole wavefront
+            if (lane == 0) atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CAPACITY), 1ull);
+            continue;
+        }
+        uint32_t *dst = words + (uint64_t)u * words_stride + off_words;
+        for (uint32_t wbase = 0; wbase < nwords; wbase += kWWin) {
+            const uint32_t wn = nwords - wbase < (uint32_t)kWWin ? nwords - wbase : (uint32_t)kWWin;
+            for (uint32_t i = lane; i <= wn; i += 64) win[i] = 0u;
+            w_wave_sync_lds();
+            uint32_t wi = (excl >> 5) - wbase;  // window word receiving the next completed 32 bits (may start below the window)
+            uint32_t np = excl & 31u;           // bits pending in acc (the leading np bits belong to earlier lanes)
+            uint64_t acc = 0;
+            auto append = [&](uint64_t code, uint32_t L) {  // L <= 32, np < 32
+                acc = (acc << L) | code;
+                np += L;
+                if (np >= 32u) {
+                    np -= 32u;
+                    if (wi < wn) atomicOr(&win[wi], (uint32_t)(acc >> np));  // unsigned: false below the window
+                    ++wi;
+                }
+            };
+            // a lane whose bits all lie outside this window has nothing to add
+            const bool overlaps = excl + bits > wbase * 32u && excl < (wbase + wn) * 32u;
+            if (unrolled) {   // whole wavefront; every code has at most kWFastCodeBits bits
+#pragma unroll
+                for (int jj = 0; jj < kSub / 2; ++jj) {
+                    const uint32_t e0 = s_fast[symw[jj] & 0xffffu], e1 = s_fast[symw[jj] >> 16];
+                    if (overlaps && 2 * jj < cnt) append(e0 & ((1u << kWFastCodeBits) - 1u), e0 >> kWFastCodeBits);
+                    if (overlaps && 2 * jj + 1 < cnt) append(e1 & ((1u << kWFastCodeBits) - 1u), e1 >> kWFastCodeBits);
+                }
+            }
+            for (int j = 0; !unrolled && overlaps && j < cnt; ++j) {
+                const uint32_t s = row[j];
+                uint32_t L = book.len[s];
+                uint64_t code = book.code[s];
+                if (!L) continue;
+                if (L > 32u) {
+                    append(code >> 32, L - 32u);
+                    code &= 0xffffffffull;
+                    L = 32u;
+                }
+                append(code, L);
+            }
+            if (overlaps && np && wi < wn) atomicOr(&win[wi], (uint32_t)(acc << (32u - np)));
+            w_wave_sync_lds();
+            for (uint32_t i = lane; i < wn; i += 64) dst[wbase + i] = win[i];
+            w_wave_sync_lds();
+        }
     }
 }
 
@@ -391,39 +540,132 @@ __global__ __launch_bounds__(kWThreads) void k_pack_wide(Layout lay, const uint1
 struct WideTabs {
     uint32_t dec[1 << kWideDecBits];
     uint64_t first[65];
+    uint64_t upper[65];    // (first[L] + count[L]) left-aligned in 64 bits: every code of L or fewer bits lies below
     uint32_t count[65];
     uint32_t offset[65];
     uint32_t maxlen;
     uint32_t pad;
+    uint16_t sorted[kWideMaxA];
 };
 
 __device__ inline void w_load_tabs(WideTabs *T, const BookWide &book, uint32_t t, uint32_t nthreads)
 {
+#pragma unroll 8
     for (uint32_t i = t; i < (1u << kWideDecBits); i += nthreads) T->dec[i] = book.dec[i];
-    for (uint32_t i = t; i < 65u; i += nthreads) { T->first[i] = book.first[i]; T->count[i] = book.count[i]; T->offset[i] = book.offset[i]; }
+#pragma unroll 8
+    for (uint32_t i = t; i < (uint32_t)kWideMaxA; i += nthreads) T->sorted[i] = book.sorted[i];
+#pragma unroll 1
+    for (uint32_t i = t; i < 65u; i += nthreads) {
+        const uint64_t f = book.first[i];
+        const uint32_t c = book.count[i];
+        T->first[i] = f;
+        T->count[i] = c;
+        T->offset[i] = book.offset[i];
+        uint64_t up = ~0ull;   // lengths 0 and 64, and sums that leave L bits, bound nothing
+        if (i >= 1u && i < 64u && ((f + c) >> i) == 0) up = (f + c) << (64u - i);
+        T->upper[i] = up;
+    }
     if (t == 0) { T->maxlen = book.maxlen > 64u ? 64u : book.maxlen; T->pad = 0; }
 }
 
-// The symbol whose codeword starts at bit `pos` of the chunk's nw words; len = 0 if none matches.  Reads nothing
-// outside w[0 .. nw).
-__device__ inline uint32_t w_decode_one(const uint32_t *__restrict__ w, uint32_t nw, uint32_t pos, const WideTabs *T,
-                                        const uint16_t *__restrict__ sorted, uint32_t &len)
+// Where a chunk's payload words are read from: global memory, or the wavefront's copy of them in LDS.
+// Neither reads outside w[0 .. nw).
+struct WGlobalWords {
+    const uint32_t *w;
+    uint32_t nw;
+    __device__ inline uint32_t word(uint32_t i) const { return i < nw ? w[i] : 0u; }
+};
+struct WLdsWords {
+    const uint32_t *w;   // LDS
+    uint32_t nw;
+    __device__ inline uint32_t word(uint32_t i) const { return i < nw ? w[i] : 0u; }
+};
+
+constexpr int kWStage = 1792;   // payload words a wavefront stages in LDS (14 bit/element); longer chunks are read in place
+
+// The chunk's nw <= kWStage words copied to the wavefront's LDS buffer, eight loads in flight per lane.
+__device__ inline void w_stage_payload(uint32_t *stage, const uint32_t *__restrict__ w, uint32_t nw, uint32_t lane)
 {
-    const uint32_t i0 = pos >> 5, s0 = pos & 31u;
-    const uint32_t w0 = i0 < nw ? w[i0] : 0u, w1 = i0 + 1u < nw ? w[i0 + 1u] : 0u, w2 = i0 + 2u < nw ? w[i0 + 2u] : 0u;
-    uint64_t full = (((uint64_t)w0 << 32) | w1) << s0;
-    if (s0) full |= (uint64_t)(w2 >> (32u - s0));
-    const uint32_t e = T->dec[full >> (64 - kWideDecBits)];
-    if (e) { len = e >> 16; return e & 0xffffu; }
-    for (uint32_t L = kWideDecBits + 1; L <= T->maxlen; ++L) {
-        const uint64_t cde = full >> (64u - L);
-        if (T->count[L] && cde >= T->first[L] && cde - T->first[L] < (uint64_t)T->count[L]) {
-            len = L;
-            return sorted[(T->offset[L] + (uint32_t)(cde - T->first[L])) & (kWideMaxA - 1)];
+    for (uint32_t base = 0; base < nw; base += 8u * 64u) {
+        uint32_t tmp[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint32_t i = base + 64u * r + lane;
+            tmp[r] = i < nw ? __builtin_nontemporal_load(w + i) : 0u;
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint32_t i = base + 64u * r + lane;
+            if (i < nw) stage[i] = tmp[r];
         }
     }
+}
+
+// The three words of a chunk's payload at the read position, and the one after them, which is requested when the
+// position enters a new word and first used when it enters the next one: the load has the symbols in between
+// to complete.
+template <class Src>
+struct WReader {
+    Src src;
+    uint32_t i0, w0, w1, w2, w3;
+    __device__ inline void seek(uint32_t pos)
+    {
+        i0 = pos >> 5;
+        w0 = src.word(i0);
+        w1 = src.word(i0 + 1u);
+        w2 = src.word(i0 + 2u);
+        w3 = src.word(i0 + 3u);
+    }
+    // the 64 bits from bit `pos` on; pos never decreases between calls
+    __device__ inline uint64_t window(uint32_t pos)
+    {
+        const uint32_t i = pos >> 5, s0 = pos & 31u;
+        if (i == i0 + 1u) { w0 = w1; w1 = w2; w2 = w3; w3 = src.word(i + 3u); i0 = i; }
+        else if (i != i0) seek(pos);
+        uint64_t full = (((uint64_t)w0 << 32) | w1) << s0;
+        if (s0) full |= (uint64_t)(w2 >> (32u - s0));
+        return full;
+    }
+};
+
+constexpr int kWUpRegs = 12;   // lengths kWideDecBits + 1 .. kWideDecBits + 12 have their bound in a register
+
+// The bounds of lengths kWideDecBits + 1 .. kWideDecBits + kWUpRegs, top 32 bits (exact: a bound of length
+// l <= 32 has no lower bits); lengths from maxlen on bound nothing.
+struct WUpper32 {
+    uint32_t up[kWUpRegs];
+    __device__ inline void load(const WideTabs *T)
+    {
+#pragma unroll
+        for (int t = 0; t < kWUpRegs; ++t) {
+            const uint32_t l = kWideDecBits + 1 + t;
+            up[t] = l < T->maxlen ? (uint32_t)(T->upper[l] >> 32) : 0xffffffffu;
+        }
+    }
+};
+
+template <class Src>
+__device__ inline uint32_t w_decode_one(WReader<Src> &r, uint32_t pos, const WideTabs *T, const WUpper32 &U32, uint32_t &len)
+{
+    const uint64_t full = r.window(pos);
+    const uint32_t e = T->dec[full >> (64 - kWideDecBits)];
+    if (e) { len = e >> 16; return e & 0xffffu; }
+    const uint32_t maxlen = T->maxlen;   // <= 64
     len = 0;
-    return 0u;
+    if (maxlen <= (uint32_t)kWideDecBits) return 0u;   // every code is in the prefix table
+    const uint32_t hi = (uint32_t)(full >> 32);
+    uint32_t L = kWideDecBits + 1;
+#pragma unroll
+    for (int t = 0; t < kWUpRegs; ++t) L += hi >= U32.up[t] ? 1u : 0u;
+    if (L == kWideDecBits + 1 + kWUpRegs)   // longer than the registers cover
+        for (uint32_t l = L; l < maxlen; ++l) L += full >= T->upper[l] ? 1u : 0u;
+    L = min(L, maxlen);   // a window of ones passes the bounds that bound nothing, too
+    const uint64_t cde = full >> (64u - L);
+    const uint64_t f = T->first[L];
+    const uint32_t c = T->count[L];
+    if (cde < f || cde - f >= (uint64_t)c) return 0u;
+    len = L;
+    return T->sorted[(T->offset[L] + (uint32_t)(cde - f)) & (kWideMaxA - 1)];
 }
 
 // Index entries of chunk c of user u, checked as in the byte decoder.
@@ -456,17 +698,30 @@ __global__ __launch_bounds__(kWThreads) void k_decode_wide(Layout lay, const uin
                                                           uint64_t sym_stride, float *__restrict__ q, uint64_t q_stride,
                                                           uint64_t *__restrict__ status)
 {
-    __shared__ WideTabs s_tabs[kWWaves];
+    // The wavefronts of a workgroup decode the same chunk of four users: with one set of code tables for all
+    // users they share one copy of the chunk's table, else each keeps its own.
+    extern __shared__ uint64_t wd_smem[];
+    uint32_t *s_stage = reinterpret_cast<uint32_t *>(wd_smem);                    // [kWWaves][kWStage]
+    WideTabs *s_tabs = reinterpret_cast<WideTabs *>(s_stage + kWWaves * kWStage);  // [1 or kWWaves]
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint64_t c = blockIdx.x;
     const uint32_t u = blockIdx.y * kWWaves + wave;
+    if (!lay.per_user_books) {
+        w_load_tabs(&s_tabs[0], books[w_chunk(lay, c, 0).book], threadIdx.x, kWThreads);
+        __syncthreads();
+    }
     if (u >= lay.U) return;  // whole wavefront; wavefront-level synchronisation only below
     const WChunk k = w_chunk(lay, c, u);
     const BookWide &book = books[k.book];
-    WideTabs *T = &s_tabs[wave];
-    w_load_tabs(T, book, lane, 64);
+    WideTabs *T = &s_tabs[lay.per_user_books ? wave : 0u];
+    uint32_t *stage = s_stage + wave * kWStage;
     const WIndex ix = w_read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits, lane);
+    const bool staged = ix.nw <= (uint32_t)kWStage;   // whole wavefront
+    if (staged) w_stage_payload(stage, ix.w, ix.nw, lane);
+    if (lay.per_user_books) w_load_tabs(T, book, lane, 64);
     w_wave_sync_lds();
+    WUpper32 U32;
+    U32.load(T);
     const uint32_t p0 = w_wave_inclusive_scan(ix.sb, lane) - ix.sb;
     const int first = (int)lane * kSub;
     const int cnt = (int)k.n - first < 0 ? 0 : ((int)k.n - first > kSub ? kSub : (int)k.n - first);
@@ -475,45 +730,66 @@ __global__ __launch_bounds__(kWThreads) void k_decode_wide(Layout lay, const uin
     const float inv_gain = lay.gain[2 * pair + 1];
     uint32_t pos = p0;
     bool bad = false;
-    for (int j = 0; j < cnt; ++j) {
-        uint32_t len;
-        const uint32_t s = w_decode_one(ix.w, ix.nw, pos, T, book.sorted, len);
-        if (len == 0u) { bad = true; len = 1u; }
-        pos += len;
-        const uint64_t e = k.e0 + (uint64_t)first + (uint64_t)j;
-        if (sym) sym[(uint64_t)u * sym_stride + e] = (uint16_t)s;
-        if (q) q[(uint64_t)u * q_stride + e] = __fmul_rn(__uint_as_float(symbol_value_bits(s, lay.E, lay.M, bias)), inv_gain);
-    }
+    auto run = [&](auto src) {
+        WReader<decltype(src)> rd{src, 0u, 0u, 0u, 0u, 0u};
+        rd.seek(p0);
+        for (int j = 0; j < cnt; ++j) {
+            uint32_t len;
+            const uint32_t s = w_decode_one(rd, pos, T, U32, len);
+            if (len == 0u) { bad = true; len = 1u; }
+            pos += len;
+            const uint64_t e = k.e0 + (uint64_t)first + (uint64_t)j;
+            if (sym) sym[(uint64_t)u * sym_stride + e] = (uint16_t)s;
+            if (q) q[(uint64_t)u * q_stride + e] = __fmul_rn(__uint_as_float(symbol_value_bits(s, lay.E, lay.M, bias)), inv_gain);
+        }
+    };
+    if (staged) run(WLdsWords{stage, ix.nw});
+    else run(WGlobalWords{ix.w, ix.nw});
     if (bad || pos - p0 != ix.sb || !ix.ok)
         atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CORRUPT), 1ull);
 }
 
 constexpr int kWAccStride = kSub + 1;
 constexpr int kWAccWords = kSubsPerChunk * kWAccStride;
+constexpr int kWAggWaves = 8;          // wavefronts of a workgroup with one set of code tables for all users
+constexpr int kWAggWavesPerUser = 4;   // and with a set per user (a table per wavefront in LDS)
+constexpr int kWAggThreads = 64 * kWAggWaves;
 
-__global__ __launch_bounds__(kWThreads) void k_aggregate_wide(Layout lay, const uint32_t *__restrict__ words,
-                                                             uint64_t words_stride,
-                                                             const uint64_t *__restrict__ chunk_offset,
-                                                             const uint16_t *__restrict__ sub_bits,
-                                                             const BookWide *__restrict__ books, float *__restrict__ out,
-                                                             float *__restrict__ model, float eta,
-                                                             uint64_t *__restrict__ status)
+// One workgroup per chunk; wavefront w of n decodes users w, w + n, ... and adds their values to the chunk's fp64
+// sums in LDS.  With one set of code tables for all users the workgroup keeps a single copy of the chunk's table,
+// else one per wavefront.
+template <bool kPerUser>
+__global__ __launch_bounds__(kWAggThreads, kPerUser ? 2 : 6) void k_aggregate_wide(Layout lay, const uint32_t *__restrict__ words,
+                                                                uint64_t words_stride,
+                                                                const uint64_t *__restrict__ chunk_offset,
+                                                                const uint16_t *__restrict__ sub_bits,
+                                                                const BookWide *__restrict__ books, float *__restrict__ out,
+                                                                float *__restrict__ model, float eta,
+                                                                uint64_t *__restrict__ status)
 {
     extern __shared__ uint64_t wa_smem[];
     double *s_acc = reinterpret_cast<double *>(wa_smem);                      // [64][kWAccStride]
-    WideTabs *s_tabs = reinterpret_cast<WideTabs *>(s_acc + kWAccWords);      // [kWWaves]
+    WideTabs *s_tabs = reinterpret_cast<WideTabs *>(s_acc + kWAccWords);      // [tabs_per_wg]
     const uint32_t t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const uint64_t c = blockIdx.x;
     const WChunk k0 = w_chunk(lay, c, 0);
-    for (uint32_t i = t; i < (uint32_t)kWAccWords; i += kWThreads) s_acc[i] = 0.0;
+    const uint32_t nthreads = blockDim.x, nwaves = blockDim.x >> 6;
+    for (uint32_t i = t; i < (uint32_t)kWAccWords; i += nthreads) s_acc[i] = 0.0;
+    if (!kPerUser) w_load_tabs(&s_tabs[0], books[k0.book], t, nthreads);
     __syncthreads();
-    WideTabs *T = &s_tabs[wave];
-    for (uint32_t u = wave; u < lay.U; u += kWWaves) {
+    WideTabs *T = &s_tabs[kPerUser ? wave : 0u];
+    WUpper32 U32;
+    if (!kPerUser) U32.load(T);
+    for (uint32_t u = wave; u < lay.U; u += nwaves) {
         const WChunk k = w_chunk(lay, c, u);
         const BookWide &book = books[k.book];
-        if (u == wave || lay.per_user_books) { w_wave_sync_lds(); w_load_tabs(T, book, lane, 64); }
         const WIndex ix = w_read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits, lane);
-        w_wave_sync_lds();
+        if (kPerUser) {
+            w_wave_sync_lds();   // the previous user's table has been read
+            w_load_tabs(T, book, lane, 64);
+            w_wave_sync_lds();
+            U32.load(T);
+        }
         const uint32_t p0 = w_wave_inclusive_scan(ix.sb, lane) - ix.sb;
         const int first = (int)lane * kSub;
         const int cnt = (int)k.n - first < 0 ? 0 : ((int)k.n - first > kSub ? kSub : (int)k.n - first);
@@ -523,9 +799,11 @@ __global__ __launch_bounds__(kWThreads) void k_aggregate_wide(Layout lay, const 
         double *acc = s_acc + lane * kWAccStride;
         uint32_t pos = p0;
         bool bad = false;
+        WReader<WGlobalWords> rd{WGlobalWords{ix.w, ix.nw}, 0u, 0u, 0u, 0u, 0u};
+        rd.seek(p0);
         for (int j = 0; j < cnt; ++j) {
             uint32_t len;
-            const uint32_t s = w_decode_one(ix.w, ix.nw, pos, T, book.sorted, len);
+            const uint32_t s = w_decode_one(rd, pos, T, U32, len);
             if (len == 0u) { bad = true; len = 1u; }
             pos += len;
             const float val = __fmul_rn(__uint_as_float(symbol_value_bits(s, lay.E, lay.M, bias)), inv_gain);
@@ -537,7 +815,7 @@ __global__ __launch_bounds__(kWThreads) void k_aggregate_wide(Layout lay, const 
     __syncthreads();
     const double inv_u = 1.0 / (double)lay.U;
     const double eta64 = (double)eta;
-    for (uint32_t e = t; e < k0.n; e += kWThreads) {
+    for (uint32_t e = t; e < k0.n; e += nthreads) {
         const double avg = s_acc[(e >> 6) * kWAccStride + (e & 63u)] * inv_u;
         if (out) out[k0.e0 + e] = (float)avg;
         if (model) model[k0.e0 + e] = (float)((double)model[k0.e0 + e] - eta64 * avg);
@@ -593,7 +871,8 @@ hipError_t launch_encode_wide(const Layout &lay, const co3_encode_args &a, BookW
     }
     if (lay.d) {
         ProfScope prof(K_QUANTIZE, s);
-        hipLaunchKernelGGL(k_quantize_wide, dim3((uint32_t)((lay.d + kWqTile - 1) / kWqTile), lay.U), dim3(kWqThreads), 0, s,
+        hipLaunchKernelGGL(k_quantize_wide, dim3((uint32_t)((lay.d + (uint64_t)kWqTile * kWqTiles - 1) / ((uint64_t)kWqTile * kWqTiles)), lay.U),
+                           dim3(kWqThreads), 0, s,
                            lay, a.g, a.m, a.m_out, sym, sym_stride, a.row_stride, a.gamma, hist_rep, a.status);
     }
     {
@@ -604,7 +883,7 @@ hipError_t launch_encode_wide(const Layout &lay, const co3_encode_args &a, BookW
         hipError_t e = launch_build_books_wide(books, lay.nbooks, lay.A, hist, a.status, s);
         if (e != hipSuccess) return e;
     }
-    const uint32_t gx = (uint32_t)((lay.nchunks + kWWaves - 1) / kWWaves);
+    const uint32_t gx = (uint32_t)((lay.nchunks + kWChunksPerWg - 1) / kWChunksPerWg);
     if (lay.nchunks) {
         ProfScope prof(K_CHUNK_BITS, s);
         hipLaunchKernelGGL(k_chunk_bits_wide, dim3(gx, lay.U), dim3(kWThreads), 0, s, lay, sym, sym_stride, books, chunk_bits);
@@ -612,8 +891,11 @@ hipError_t launch_encode_wide(const Layout &lay, const co3_encode_args &a, BookW
     hipError_t e = launch_scan_chunks(lay, chunk_bits, a.chunk_offset, a.payload_bits, s);   // the byte path's scan
     if (e != hipSuccess) return e;
     if (lay.nchunks) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_pack_wide), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)kWPackLds);
+        if (e != hipSuccess) return e;
         ProfScope prof(K_PACK, s);
-        hipLaunchKernelGGL(k_pack_wide, dim3(gx, lay.U), dim3(kWThreads), 0, s, lay, sym, sym_stride, books,
+        hipLaunchKernelGGL(k_pack_wide, dim3(gx, lay.U), dim3(kWThreads), kWPackLds, s, lay, sym, sym_stride, books,
                            a.chunk_offset, a.sub_bits, a.words, a.words_stride, a.status);
     }
     return hipGetLastError();
@@ -623,8 +905,14 @@ hipError_t launch_decode_wide(const Layout &lay, const co3_decode_args &a, const
 {
     if (lay.U == 0 || lay.nchunks == 0) return hipSuccess;
     const uint64_t sym_stride = symbol_row_stride(lay.d);
+    const size_t lds_fixed = (size_t)kWWaves * kWStage * sizeof(uint32_t);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_decode_wide),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)(lds_fixed + (size_t)kWWaves * sizeof(WideTabs)));   // 98 KB at most
+    if (e != hipSuccess) return e;
+    const size_t lds_used = lds_fixed + (lay.per_user_books ? (size_t)kWWaves : 1u) * sizeof(WideTabs);
     ProfScope prof(K_DECODE, s);
-    hipLaunchKernelGGL(k_decode_wide, dim3((uint32_t)lay.nchunks, (lay.U + kWWaves - 1) / kWWaves), dim3(kWThreads), 0, s,
+    hipLaunchKernelGGL(k_decode_wide, dim3((uint32_t)lay.nchunks, (lay.U + kWWaves - 1) / kWWaves), dim3(kWThreads), lds_used, s,
                        lay, a.words, a.words_stride, a.chunk_offset, a.sub_bits, books,
                        reinterpret_cast<uint16_t *>(a.symbols), sym_stride, a.q, a.q_stride, a.status);
     return hipGetLastError();
@@ -633,13 +921,19 @@ hipError_t launch_decode_wide(const Layout &lay, const co3_decode_args &a, const
 hipError_t launch_aggregate_wide(const Layout &lay, const co3_aggregate_args &a, const BookWide *books, hipStream_t s)
 {
     if (lay.U == 0 || lay.nchunks == 0) return hipSuccess;
-    const size_t lds = (size_t)kWAccWords * sizeof(double) + (size_t)kWWaves * sizeof(WideTabs);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_aggregate_wide),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const uint32_t nwaves = lay.per_user_books ? kWAggWavesPerUser : kWAggWaves;
+    const size_t lds = (size_t)kWAccWords * sizeof(double) + (lay.per_user_books ? (size_t)nwaves : 1u) * sizeof(WideTabs);
+    const void *fn = lay.per_user_books ? reinterpret_cast<const void *>(&k_aggregate_wide<true>)
+                                        : reinterpret_cast<const void *>(&k_aggregate_wide<false>);
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);   // 103 KB or 50 KB
     if (e != hipSuccess) return e;
     ProfScope prof(K_AGGREGATE, s);
-    hipLaunchKernelGGL(k_aggregate_wide, dim3((uint32_t)lay.nchunks), dim3(kWThreads), lds, s, lay, a.words,
-                       a.words_stride, a.chunk_offset, a.sub_bits, books, a.out, a.model, a.eta, a.status);
+    if (lay.per_user_books)
+        hipLaunchKernelGGL(k_aggregate_wide<true>, dim3((uint32_t)lay.nchunks), dim3(64 * nwaves), lds, s, lay, a.words,
+                           a.words_stride, a.chunk_offset, a.sub_bits, books, a.out, a.model, a.eta, a.status);
+    else
+        hipLaunchKernelGGL(k_aggregate_wide<false>, dim3((uint32_t)lay.nchunks), dim3(64 * nwaves), lds, s, lay, a.words,
+                           a.words_stride, a.chunk_offset, a.sub_bits, books, a.out, a.model, a.eta, a.status);
     return hipGetLastError();
 }
 
