@@ -2,19 +2,20 @@
 //
 // The steps are those of the byte path (Algorithm 1 lines 8-10 and 13-14; Sec. IV-A (i)-(iii), Sec. II-B (iv))
 // and the container is the same; symbols are 16-bit words and a code table has up to 4096 entries, too many
-// for the per-wavefront LDS tables the byte kernels are built around.  These kernels keep the tables in
-// device memory (they stay in the caches) and trade speed for simplicity: one element or one sub-chunk per
-// lane, plain loops.  A fixed code without a symbol buffer ("single sweep" in the byte path) runs the same
-// three steps here with the symbols kept in the workspace.
+// for the per-wavefront LDS tables the byte kernels are built around: here a workgroup shares one copy of the
+// table of the layer it works on, and falls back to the table in device memory where its range of the vector
+// crosses into a layer with another table.  A fixed code without a symbol buffer ("single sweep" in the byte
+// path) runs the same three steps here with the symbols kept in the workspace.
 //
 //   k_quantize_wide      v = g + gamma m, Q_fp, m' = v - ghat, symbol; symbol counts in an LDS table per workgroup
-//   k_build_books_wide   Huffman code of a table on the device (same tie rule and canonical form as the host's)
-//   k_chunk_bits_wide    code lengths summed per chunk
+//   k_build_books_wide   Huffman code of a table on the device (same tie rule and canonical form as the host's):
+//                        bitonic sort, two-queue merge, depths, canonical ranks from ballots
+//   k_chunk_bits_wide    code lengths summed per chunk, lengths in LDS
 //   (k_scan_chunks of k_pack.hip gives the chunk offsets)
-//   k_pack_wide          wavefront per chunk, lane per sub-chunk: lengths, wave prefix sum, codewords ORed into an
-//                        LDS window at their bit offsets, window copied out
-//   k_decode_wide        wavefront per (chunk, user), lane per sub-chunk: direct table for codes of up to 11 bits,
-//                        canonical search by length above
+//   k_pack_wide          wavefront per chunk, lane per sub-chunk with its 64 symbols in registers: lengths, wave
+//                        prefix sum, codewords ORed into an LDS window at their bit offsets, window copied out
+//   k_decode_wide        wavefront per (chunk, user), lane per sub-chunk: prefix table for codes of up to 11 bits,
+//                        longer ones by their value among the per-length bounds of the canonical code
 //   k_aggregate_wide     the same decoder; values added to per-element fp64 sums in LDS, then averaged
 #include "co3_internal.h"
 #include "quantize_math.h"
@@ -194,7 +195,13 @@ __global__ void k_zero_wide(uint64_t *p, uint64_t n)
 
 // ---- code tables ------------------------------------------------------------------------------------------
 
-// One workgroup per table.  Dynamic LDS: node weights (2 A x 8 bytes) and parents (2 A x 4 bytes).
+// One workgroup per table.  A is a power of two (512 .. 4096).  Dynamic LDS: node weights (2 A x 8 bytes),
+// parents (2 A x 4 bytes), the leaves' symbols (A x 2 bytes).  Steps: bitonic sort of the symbols by
+// (weight, symbol) with the unused ones last; the two-queue merge by one thread, which keeps the heads of both
+// queues in registers and requests a queue's next entry when its head is taken, so that no step waits for LDS;
+// depth of every leaf; canonical order, the rank of a symbol among those of its length from wavefront ballots
+// (wavefront w owns symbols w A/16 .. (w + 1) A/16 - 1, in order).
+constexpr int kWbWaves = kWbThreads / 64;
 __global__ __launch_bounds__(kWbThreads) void k_build_books_wide(BookWide *__restrict__ books, uint32_t A,
                                                                 const uint64_t *__restrict__ weights,
                                                                 uint64_t *__restrict__ status)
@@ -202,25 +209,30 @@ __global__ __launch_bounds__(kWbThreads) void k_build_books_wide(BookWide *__res
     extern __shared__ uint64_t wb_smem[];
     uint64_t *nw = wb_smem;                                        // [2 A] sorted leaves, then internal nodes
     int *parent = reinterpret_cast<int *>(nw + 2 * (size_t)A);      // [2 A]
+    uint16_t *leaf_sym = reinterpret_cast<uint16_t *>(parent + 2 * (size_t)A);   // [A] sorted leaf -> symbol
     __shared__ uint32_t cnt[65], off[65];
     __shared__ uint64_t first[65];
+    __shared__ uint32_t wcnt[kWbWaves][65];   // symbols of each length in a wavefront's range; then running ranks
     __shared__ int err, s_n;
     __shared__ uint32_t s_maxlen;
 
     BookWide &B = books[blockIdx.x];
     const uint64_t *w = weights + (uint64_t)blockIdx.x * A;
-    const uint32_t t = threadIdx.x;
-    uint16_t *leaf_sym = B.sorted;   // sorted leaf -> symbol, until the canonical order replaces it
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint64_t kNone = ~0ull;    // an unused symbol in the sort, an exhausted queue in the merge: refused as a weight
 
     if (t < 65) { cnt[t] = 0; off[t] = 0; first[t] = 0; }
+    for (uint32_t i = t; i < (uint32_t)kWbWaves * 65u; i += kWbThreads) wcnt[i / 65u][i % 65u] = 0;
     if (t == 0) { err = 0; s_maxlen = 0; s_n = 0; }
     for (uint32_t i = t; i < 2 * A; i += kWbThreads) parent[i] = -1;
     __syncthreads();
     int active = 0;
     for (uint32_t s = t; s < A; s += kWbThreads) {
         const uint64_t ws = w[s];
-        if (ws == ~0ull) err = 1;    // 2^64 - 1 marks an exhausted queue in the merge: refused as a weight
+        if (ws == kNone) err = 1;
         active += ws > 0 ? 1 : 0;
+        nw[s] = ws ? ws : kNone;
+        leaf_sym[s] = (uint16_t)s;
         B.len[s] = 0;
         B.code[s] = 0;
     }
@@ -228,34 +240,45 @@ __global__ __launch_bounds__(kWbThreads) void k_build_books_wide(BookWide *__res
     __syncthreads();
     const int nact = s_n;            // number of symbols with a weight
 
-    // rank of every active symbol in (weight, symbol) order
-    for (uint32_t s = t; s < A; s += kWbThreads) {
-        const uint64_t ws = w[s];
-        if (!ws) continue;
-        int rank = 0;
-        for (uint32_t j = 0; j < A; ++j) {
-            const uint64_t wj = w[j];
-            rank += (int)((wj != 0) & ((wj < ws) | ((wj == ws) & (j < s))));
+    // ascending (weight, symbol); the keys are distinct, so the order does not depend on the network
+    for (uint32_t k = 2; k <= A; k <<= 1) {
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            for (uint32_t i = t; i < A; i += kWbThreads) {
+                const uint32_t p = i ^ j;
+                if (p > i) {
+                    const uint64_t wi = nw[i], wp = nw[p];
+                    const uint16_t si = leaf_sym[i], sp = leaf_sym[p];
+                    const bool gt = wi > wp || (wi == wp && si > sp);
+                    if (gt == ((i & k) == 0)) { nw[i] = wp; nw[p] = wi; leaf_sym[i] = sp; leaf_sym[p] = si; }
+                }
+            }
+            __syncthreads();
         }
-        nw[rank] = ws;
-        leaf_sym[rank] = (uint16_t)s;
     }
-    __syncthreads();
 
     if (t == 0 && nact >= 2 && !err) {
-        const uint64_t kNone = ~0ull;
+        auto leaf = [&](int i) { return i < nact ? nw[i] : kNone; };
         int li = 0, ii = nact, made = nact;
+        uint64_t l0 = leaf(0), l1 = leaf(1);   // leaves li, li + 1
+        uint64_t i0 = kNone, i1 = kNone;       // internal nodes ii, ii + 1 where they exist
         for (int step = 0; step < nact - 1; ++step) {
             int pick[2];
             uint64_t pw[2];
+#pragma unroll
             for (int r = 0; r < 2; ++r) {
-                const uint64_t lw = li < nact ? nw[li] : kNone, iw = ii < made ? nw[ii] : kNone;
-                if (lw != kNone && (iw == kNone || lw <= iw)) { pick[r] = li++; pw[r] = lw; }
-                else { pick[r] = ii++; pw[r] = iw; }
+                if (l0 != kNone && (i0 == kNone || l0 <= i0)) {
+                    pick[r] = li++; pw[r] = l0;
+                    l0 = l1; l1 = leaf(li + 1);
+                } else {
+                    pick[r] = ii++; pw[r] = i0;
+                    i0 = i1; i1 = ii + 1 < made ? nw[ii + 1] : kNone;
+                }
             }
             const uint64_t sum = pw[0] + pw[1];
             if (sum < pw[1] || sum == kNone) { err = 1; break; }  // the table's weights sum to 2^64 - 1 or more
             nw[made] = sum;
+            if (made == ii) i0 = sum;
+            else if (made == ii + 1) i1 = sum;
             parent[pick[0]] = made;
             parent[pick[1]] = made;
             ++made;
@@ -277,9 +300,32 @@ __global__ __launch_bounds__(kWbThreads) void k_build_books_wide(BookWide *__res
         if (t == 0) atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CODELEN), 1ull);
     }
     __syncthreads();
-    for (uint32_t s = t; s < A; s += kWbThreads) {
-        const uint32_t L = B.len[s];
-        if (L) { atomicAdd(&cnt[L], 1u); atomicMax(&s_maxlen, L); }
+
+    // lengths present in each wavefront's range of symbols, sub-block of 64 by sub-block
+    const uint32_t per_wave = A / kWbWaves;   // 32 .. 256
+    auto for_each_length_group = [&](uint32_t myL, auto &&body) {   // body(length, lanes with it), once per length
+        uint64_t todo = __ballot(myL != 0u);
+        while (todo) {
+            const int leader = __ffsll((long long)todo) - 1;
+            const uint32_t L0 = (uint32_t)__shfl((int)myL, leader, 64);
+            const uint64_t mask = __ballot(myL == L0);
+            body(L0, mask);
+            todo &= ~mask;
+        }
+    };
+    for (uint32_t sb = 0; sb < per_wave; sb += 64) {
+        const uint32_t i = sb + lane;
+        const uint32_t myL = i < per_wave ? (uint32_t)B.len[wave * per_wave + i] : 0u;
+        for_each_length_group(myL, [&](uint32_t L0, uint64_t mask) {
+            if (lane == 0) wcnt[wave][L0] += (uint32_t)__popcll(mask);
+        });
+    }
+    __syncthreads();
+    if (t < 65) {   // counts per length; a wavefront's entry becomes the rank of its first symbol of that length
+        uint32_t run = 0;
+        for (int wv = 0; wv < kWbWaves; ++wv) { const uint32_t c = wcnt[wv][t]; wcnt[wv][t] = run; run += c; }
+        cnt[t] = run;
+        if (run && t) atomicMax(&s_maxlen, t);
     }
     __syncthreads();
     if (t == 0) {
@@ -294,17 +340,21 @@ __global__ __launch_bounds__(kWbThreads) void k_build_books_wide(BookWide *__res
     }
     __syncthreads();
     // canonical order: rank among the symbols of the same length, ascending symbol
-    for (uint32_t s = t; s < A; s += kWbThreads) {
-        const uint32_t L = B.len[s];
-        if (!L) continue;
-        uint32_t rank = 0;
-        for (uint32_t j = 0; j < s; ++j) rank += B.len[j] == L ? 1u : 0u;
-        B.code[s] = first[L] + rank;
-    }
-    __syncthreads();  // every leaf_sym entry has been read (depths above); sorted[] may now take the canonical order
-    for (uint32_t s = t; s < A; s += kWbThreads) {
-        const uint32_t L = B.len[s];
-        if (L) B.sorted[off[L] + (uint32_t)(B.code[s] - first[L])] = (uint16_t)s;
+    for (uint32_t sb = 0; sb < per_wave; sb += 64) {
+        const uint32_t i = sb + lane;
+        const uint32_t s_i = wave * per_wave + i;
+        const uint32_t myL = i < per_wave ? (uint32_t)B.len[s_i] : 0u;
+        for_each_length_group(myL, [&](uint32_t L0, uint64_t mask) {
+            const uint32_t base = wcnt[wave][L0];
+            if (myL == L0) {
+                const uint32_t rank = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+                B.code[s_i] = first[L0] + rank;
+                B.sorted[off[L0] + rank] = (uint16_t)s_i;
+            }
+            w_wave_sync_lds();   // every lane has read the base
+            if (lane == 0) wcnt[wave][L0] = base + (uint32_t)__popcll(mask);
+            w_wave_sync_lds();
+        });
     }
     for (uint32_t i = (bad ? 0u : (uint32_t)nact) + t; i < A; i += kWbThreads) B.sorted[i] = 0;
     if (t < 65) { B.first[t] = first[t]; B.count[t] = cnt[t]; B.offset[t] = off[t]; }
@@ -839,7 +889,7 @@ hipError_t launch_build_books_wide(BookWide *books, uint32_t nbooks, uint32_t A,
                                    uint64_t *status, hipStream_t s)
 {
     if (nbooks == 0) return hipSuccess;
-    const size_t lds = (size_t)2 * A * (sizeof(uint64_t) + sizeof(int));
+    const size_t lds = (size_t)2 * A * (sizeof(uint64_t) + sizeof(int)) + (size_t)A * sizeof(uint16_t);   // 104 KB at A = 4096
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_build_books_wide),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;

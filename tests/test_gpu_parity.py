@@ -734,6 +734,43 @@ def test_wide_long_codes_per_user_tables_and_device_builder():
         B.co3_build_codebook(E, M, 3, w3)
 
 
+@pytest.mark.parametrize("E,M", [(3, 5), (4, 5), (4, 6), (5, 6)])
+def test_wide_device_builder_against_the_oracle(E, M):
+    # the builder's sort, merge with ties, depths and canonical ranks at every wide alphabet size: tables of many
+    # equal weights, of one and two symbols, of distinct powers of two (a path), of counts as a round gives them,
+    # of few symbols spread over the alphabet, and an empty one
+    import torch
+    from paper_2204_08211_amd import binding as B
+    A = 1 << (1 + E + M)
+    rng = np.random.default_rng(1500 + A)
+    tabs = []
+    tabs.append(rng.integers(0, 4, A).astype(np.uint64))                          # ties everywhere, some unused
+    tabs.append(np.ones(A, np.uint64))                                            # all equal: a full tree
+    one = np.zeros(A, np.uint64); one[A - 3] = 5; tabs.append(one)
+    two = np.zeros(A, np.uint64); two[0] = 7; two[A - 1] = 7; tabs.append(two)
+    path = np.zeros(A, np.uint64); idx = rng.choice(A, 40, replace=False)
+    path[idx] = np.uint64(1) << np.arange(40, dtype=np.uint64); tabs.append(path)
+    geo = np.floor(1e9 * np.exp(-np.abs(np.arange(A) - A / 2) / (A / 40))).astype(np.uint64); tabs.append(geo)
+    few = np.zeros(A, np.uint64); few[rng.choice(A, 100, replace=False)] = rng.integers(1, 1000, 100).astype(np.uint64)
+    tabs.append(few)
+    big = rng.integers(1, 1 << 50, A).astype(np.uint64); tabs.append(big)
+    tabs.append(np.zeros(A, np.uint64))
+    w = np.stack(tabs)
+    books = B.co3_build_codebook(E, M, len(tabs), None)
+    status = torch.zeros(B.STATUS_WORDS, dtype=torch.int64, device="cuda:0")
+    B.co3_build_codebook_device(books, torch.from_numpy(w.view(np.int64)).to("cuda:0"), status)
+    torch.cuda.synchronize()
+    assert int(status[B.STAT_CODELEN].item()) == 0
+    for b, wt in enumerate(tabs):
+        lens, codes = books.export(b)
+        if not wt.any():
+            assert not lens.any() and not codes.any()
+            continue
+        rl, rc = orc.codebook(wt)
+        gu.assert_bits_equal(lens, rl, f"code lengths of table {b}")
+        gu.assert_bits_equal(codes, rc, f"codes of table {b}")
+
+
 def test_wide_error_paths_capacity_nocode_corrupt():
     import torch
     from paper_2204_08211_amd import binding as B
