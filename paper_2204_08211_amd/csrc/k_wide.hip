@@ -28,7 +28,6 @@ constexpr int kWqTile = kWqThreads * kWqPer;
 constexpr int kWWaves = 4;                       // wavefronts per workgroup of the chunk kernels
 constexpr int kWThreads = 64 * kWWaves;
 constexpr int kWSymRow = kSub + 2;               // a sub-chunk's 64 staged symbols + pad (16-bit units)
-constexpr int kWWin = 1536;                      // words of the pack window (12 bit/element per pass)
 constexpr int kWbThreads = 1024;                 // threads of the table builder
 
 __device__ inline uint32_t w_find_segment(const SegDev *segs, uint32_t nseg, uint64_t elem)
@@ -138,6 +137,13 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
             __syncthreads();
             cur_book = tile_book;
         }
+        // the scale and the quantizer's constants of the tile's first layer serve the whole tile unless it
+        // crosses into the next layer
+        const uint64_t tile_end = base + kWqTile < lay.d ? base + kWqTile : lay.d;
+        const bool one_layer = tile_end <= lay.segs[seg0 + 1].offset;
+        const uint64_t pair0 = (uint64_t)u * lay.nseg + seg0;
+        const QConst qc0 = make_qconst(lay.E, lay.M, lay.bias[pair0]);
+        const float gain0 = lay.gain[2 * pair0], inv_gain0 = lay.gain[2 * pair0 + 1];
         float gv[kWqPer], mv[kWqPer];   // the tile's loads are issued together
 #pragma unroll
         for (int k = 0; k < kWqPer; ++k) {
@@ -149,22 +155,28 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
         for (int k = 0; k < kWqPer; ++k) {
             const uint64_t i = base + (uint64_t)k * kWqThreads + threadIdx.x;
             if (i >= lay.d) break;
-            uint32_t s_i = seg0;
-            while (i >= lay.segs[s_i + 1].offset) ++s_i;   // ends: segs[nseg].offset = d > i
-            const uint64_t pair = (uint64_t)u * lay.nseg + s_i;
-            const int bias = lay.bias[pair];
-            const QConst qc = make_qconst(lay.E, lay.M, bias);
+            uint32_t book = tile_book;
+            QConst qc = qc0;
+            float gain = gain0, inv_gain = inv_gain0;
+            if (!one_layer) {   // workgroup-uniform: the tile crosses into another layer
+                uint32_t s_i = seg0;
+                while (i >= lay.segs[s_i + 1].offset) ++s_i;   // ends: segs[nseg].offset = d > i
+                const uint64_t pair = (uint64_t)u * lay.nseg + s_i;
+                qc = make_qconst(lay.E, lay.M, lay.bias[pair]);
+                gain = lay.gain[2 * pair];
+                inv_gain = lay.gain[2 * pair + 1];
+                book = book_base + (uint32_t)lay.segs[s_i].book;
+            }
             const float v = __fadd_rn(gv[k], __fmul_rn(gamma, mv[k]));
-            const float y = __fmul_rn(v, lay.gain[2 * pair]);
+            const float y = __fmul_rn(v, gain);
             uint32_t s, flags;
             float q;
             quantize(y, qc, sign_shift, s, q, flags);
-            q = __fmul_rn(q, lay.gain[2 * pair + 1]);
+            q = __fmul_rn(q, inv_gain);
             mo[i] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
             n_nonfinite += flags & 1u;
             n_clamped += (flags >> 1) & 1u;
             su[i] = (uint16_t)s;
-            const uint32_t book = book_base + (uint32_t)lay.segs[s_i].book;
             if (book == cur_book) atomicAdd(&s_hist[s & (kWideMaxA - 1)], 1u);
             else atomicAdd(reinterpret_cast<unsigned long long *>(hist + (uint64_t)book * lay.A + s), 1ull);
         }
@@ -379,14 +391,92 @@ __global__ __launch_bounds__(kWbThreads) void k_build_books_wide(BookWide *__res
 // Both chunk kernels give a workgroup kWChunksPerWg consecutive chunks of one user (wavefront w takes chunks
 // w, w + kWWaves, ...) and keep the code table of the workgroup's first chunk in LDS; a chunk of another table
 // (a layer boundary inside the workgroup's range) reads its table from global memory instead.
-constexpr int kWChunksPerWave = 8;
+constexpr int kWChunksPerWave = 4;
 constexpr int kWChunksPerWg = kWWaves * kWChunksPerWave;
 constexpr uint32_t kWFastCodeBits = 25;   // s_fast entry: length << 25 | codeword, for lengths up to 25
-constexpr int kWSymWave = kSubsPerChunk * kWSymRow + 2;   // 16-bit units of a wavefront's staged chunk: 64 rows + one word
 constexpr int kWSymLoads = (kChunk / 2 + 1 + 63) / 64;    // dword loads per lane to cover a chunk at any 2-byte offset (33)
 constexpr uint32_t kWSymMask2 = (uint32_t)(kWideMaxA - 1) * 0x10001u;
-constexpr size_t kWPackLds = sizeof(uint32_t) * (kWideMaxA + kWWaves * (kWWin + 1)) +
-                             sizeof(uint16_t) * kWWaves * kWSymWave;   // 74.4 KB: two workgroups per CU
+// A wavefront's LDS words in the coder: 64 rows of 32 + 1 words and one word more.  They hold the staged symbols,
+// then (symbols in registers) every lane's own codewords, then the chunk's words; the plain loops for long codes
+// keep the symbols in the rows and use a small window behind them.
+constexpr int kWRowWords = kWSymRow / 2 - 1;                      // 32
+constexpr int kWRowStride = kWRowWords + 1;                       // odd: no bank conflicts
+constexpr int kWRegion = kSubsPerChunk * kWRowStride + 1;         // 2113
+constexpr int kWWinSlow = 128;
+constexpr int kWWinMedium = 2048;                                // the rows' storage as a window
+constexpr int kWPackWaveWords = kWRegion + kWWinSlow + 1;
+constexpr uint32_t kWFastSlow = 127;                              // length field of a symbol the unrolled coder cannot take
+constexpr size_t kWPackLds = sizeof(uint32_t) * (kWideMaxA + kWWaves * kWPackWaveWords);   // 52 KB: three workgroups per CU
+
+// Step 1 of the coder: every lane concatenates the codewords of its 64 symbols (two per word of sym) from bit 0
+// of its row, without knowing where they will land in the chunk; its bit count falls out at the end.  A
+// codeword enters a 64-bit shift register; it completes at most one 32-bit word, which is stored without a
+// branch (a store of the word still being filled is harmless: the slot is written again; stores beyond the row
+// go to the row's spare slot).  Returns, for the whole wavefront: kRowsOk; kRowsOverflow if a lane's codewords do
+// not fit its row (bits is still every lane's bit count); kRowsSlow if a symbol has a kWFastSlow entry.
+enum { kRowsOk = 0, kRowsOverflow = 1, kRowsSlow = 2 };
+template <bool kFull>
+__device__ inline int w_pack_rows(const uint32_t (&sym)[kSub / 2], int cnt, const uint32_t *fast, uint32_t *region,
+                                   uint32_t lane, uint32_t &bits)
+{
+    uint64_t acc = 0;
+    uint32_t np = 0;                                     // bits of acc not yet stored: < 32 between symbols
+    uint32_t waddr = lane * kWRowStride;
+    const uint32_t wend = waddr + kWRowWords;
+    bool left = false;
+#pragma unroll
+    for (int j = 0; j < kSub; ++j) {
+        uint32_t e = fast[(j & 1) ? sym[j >> 1] >> 16 : sym[j >> 1] & 0xffffu];
+        if (!kFull) e = (j < cnt) ? e : 0u;              // nothing to append beyond the chunk's end
+        const uint32_t L = e >> kWFastCodeBits;          // <= kWFastCodeBits, or kWFastSlow
+        np += L;
+        left = left || np > 63u;                         // exactly the kWFastSlow entries
+        acc = (acc << (L & 63u)) | (e & ((1u << kWFastCodeBits) - 1u));
+        const uint32_t rest = np & 31u;
+        region[waddr < wend ? waddr : wend] = (uint32_t)(acc >> rest);
+        waddr += (np >> 5) & 1u;
+        np = rest;
+    }
+    if (__any(left)) return kRowsSlow;
+    const uint32_t whole = waddr - lane * kWRowStride;   // complete words, counted also beyond the row
+    if (np) region[waddr < wend ? waddr : wend] = (uint32_t)(acc << (32u - np));
+    bits = whole * 32u + np;
+    return __any(whole + (np ? 1u : 0u) > (uint32_t)kWRowWords) ? kRowsOverflow : kRowsOk;
+}
+
+// Step 2: every lane's row holds its `bits` bits; excl: bits of the lanes before it.  The rows go to registers,
+// their storage is cleared and becomes the chunk's words: every lane ORs its words in, shifted by its offset.
+// On return region[0 .. nwords) holds them, nwords = ceil(sum of bits / 32) <= 64 x 32.
+__device__ inline void w_rows_to_window(uint32_t *region, uint32_t lane, uint32_t bits, uint32_t excl, uint32_t nwords)
+{
+    const uint32_t nw = (bits + 31u) >> 5;               // <= kWRowWords
+    uint32_t maxnw = nw;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { const uint32_t y = (uint32_t)__shfl_xor((int)maxnw, o, 64); maxnw = maxnw > y ? maxnw : y; }
+    uint32_t r[kWRowWords];
+    const uint32_t *row = region + lane * kWRowStride;
+#pragma unroll
+    for (int i = 0; i < kWRowWords; ++i) {
+        r[i] = 0u;
+        if ((uint32_t)i < maxnw) r[i] = (uint32_t)i < nw ? row[i] : 0u;
+    }
+    w_wave_sync_lds();                                   // all rows are in registers
+    for (uint32_t i = lane; i <= nwords; i += 64) region[i] = 0u;
+    w_wave_sync_lds();
+    const uint32_t sh = excl & 31u, w0 = excl >> 5;
+    uint32_t prev = 0u;
+#pragma unroll
+    for (int i = 0; i < kWRowWords; ++i) {
+        if ((uint32_t)i < maxnw) {
+            const uint32_t out = __builtin_amdgcn_alignbit(prev, r[i], sh);   // ({prev, r[i]} >> sh), low word
+            if (out) atomicOr(&region[w0 + (uint32_t)i], out);
+            prev = r[i];
+        }
+    }
+    const uint32_t tail = __builtin_amdgcn_alignbit(prev, 0u, sh);   // what the shift pushed out of the last word
+    if (sh && tail && nw) atomicOr(&region[w0 + nw], tail);
+    w_wave_sync_lds();
+}
 
 __global__ __launch_bounds__(kWThreads) void k_chunk_bits_wide(Layout lay, const uint16_t *__restrict__ sym,
                                                               uint64_t sym_stride, const BookWide *__restrict__ books,
@@ -410,9 +500,16 @@ __global__ __launch_bounds__(kWThreads) void k_chunk_bits_wide(Layout lay, const
             uint32_t done = 0;
             if ((reinterpret_cast<uintptr_t>(src) & 15u) == 0) {   // eight symbols per load
                 const uint4 *src8 = reinterpret_cast<const uint4 *>(src);
-                for (uint32_t i = lane; i < (k.n >> 3); i += 64) {
-                    const uint4 v = src8[i];
-                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                uint4 v[kChunk / 8 / 64];   // a whole chunk is eight loads per lane, all requested before the first is used
+#pragma unroll
+                for (int r = 0; r < kChunk / 8 / 64; ++r) {
+                    const uint32_t i = lane + 64u * r;
+                    v[r] = i < (k.n >> 3) ? src8[i] : make_uint4(0u, 0u, 0u, 0u);
+                }
+#pragma unroll
+                for (int r = 0; r < kChunk / 8 / 64; ++r) {
+                    if (lane + 64u * r >= (k.n >> 3)) continue;
+                    const uint32_t w[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
                         total += (uint32_t)s_len[w[q] & (kWideMaxA - 1)] + (uint32_t)s_len[(w[q] >> 16) & (kWideMaxA - 1)];
@@ -429,38 +526,42 @@ __global__ __launch_bounds__(kWThreads) void k_chunk_bits_wide(Layout lay, const
     }
 }
 
-__global__ __launch_bounds__(kWThreads) void k_pack_wide(Layout lay, const uint16_t *__restrict__ sym, uint64_t sym_stride,
+__global__ __launch_bounds__(kWThreads, 3) void k_pack_wide(Layout lay, const uint16_t *__restrict__ sym, uint64_t sym_stride,
                                                         const BookWide *__restrict__ books,
                                                         const uint64_t *__restrict__ chunk_offset,
                                                         uint16_t *__restrict__ sub_bits, uint32_t *__restrict__ words,
                                                         uint64_t words_stride, uint64_t *__restrict__ status)
 {
     extern __shared__ uint32_t wp_smem[];   // kWPackLds bytes
-    uint32_t *s_fast = wp_smem;                                                          // [kWideMaxA]
-    uint32_t *s_win_all = s_fast + kWideMaxA;                                            // [kWWaves][kWWin + 1]
-    uint16_t *s_sym_all = reinterpret_cast<uint16_t *>(s_win_all + kWWaves * (kWWin + 1));  // [kWWaves][64 rows]
+    uint32_t *s_fast = wp_smem;                      // [kWideMaxA]
+    uint32_t *s_wave_all = s_fast + kWideMaxA;       // [kWWaves][kWPackWaveWords]
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint64_t c_base = (uint64_t)blockIdx.x * kWChunksPerWg;   // < nchunks by the grid
     const uint32_t u = blockIdx.y;
     const uint32_t wg_book = w_chunk(lay, c_base, u).book;
-    for (uint32_t i = threadIdx.x; i < (uint32_t)kWideMaxA; i += kWThreads) {
-        uint32_t e = 0;
-        if (i < lay.A) {
-            const uint32_t L = books[wg_book].len[i];
-            e = L << kWFastCodeBits;
-            if (L <= kWFastCodeBits) e |= (uint32_t)books[wg_book].code[i];
+    {
+        const BookWide &tb = books[wg_book];
+        uint32_t tl[kWideMaxA / kWThreads], tc[kWideMaxA / kWThreads];   // the loads are issued together
+#pragma unroll
+        for (int r = 0; r < kWideMaxA / kWThreads; ++r) {
+            const uint32_t i = threadIdx.x + (uint32_t)r * kWThreads;
+            tl[r] = i < lay.A ? (uint32_t)tb.len[i] : 0u;
+            tc[r] = i < lay.A ? (uint32_t)tb.code[i] : 0u;
         }
-        s_fast[i] = e;
+#pragma unroll
+        for (int r = 0; r < kWideMaxA / kWThreads; ++r) {
+            const uint32_t i = threadIdx.x + (uint32_t)r * kWThreads;
+            // no code, or a longer one than an entry holds: kWFastSlow
+            s_fast[i] = (tl[r] >= 1u && tl[r] <= kWFastCodeBits) ? ((tl[r] << kWFastCodeBits) | tc[r]) : (kWFastSlow << kWFastCodeBits);
+        }
     }
     __syncthreads();
-    uint16_t *s_sym = s_sym_all + wave * kWSymWave;
-    uint32_t *win = s_win_all + wave * (kWWin + 1);
+    uint32_t *region = s_wave_all + wave * kWPackWaveWords;
     for (int it = 0; it < kWChunksPerWave; ++it) {
         const uint64_t c = c_base + (uint64_t)it * kWWaves + wave;
         if (c >= lay.nchunks) break;   // whole wavefront; wavefront-level synchronisation only below
         const WChunk k = w_chunk(lay, c, u);
         const BookWide &book = books[k.book];
-        const bool in_lds = k.book == wg_book;
         const uint16_t *src = sym + (uint64_t)u * sym_stride + k.e0;
         // The chunk's symbols, at any 2-byte offset and of any length: coalesced dwords from the 4-byte boundary
         // below the chunk go to LDS rows of 32 + 1 words (word i of the chunk at i + i / 32), from which lane l
@@ -472,61 +573,65 @@ __global__ __launch_bounds__(kWThreads) void k_pack_wide(Layout lay, const uint1
 #pragma unroll
         for (int r = 0; r < kWSymLoads; ++r) {
             const uint32_t i = lane + 64u * r;
-            tmp[r] = i < ndw ? __builtin_nontemporal_load(src32 + i) & kWSymMask2 : 0u;
+            tmp[r] = i < ndw ? __builtin_nontemporal_load(src32 + i) : 0u;   // all requested before the first is used
         }
         const uint64_t off = chunk_offset[(uint64_t)u * (lay.nchunks + 1) + c];
-        w_wave_sync_lds();   // the previous chunk's rows and window have been read
-        uint32_t *stage = reinterpret_cast<uint32_t *>(s_sym);
+        w_wave_sync_lds();   // the previous chunk's words have been copied out
 #pragma unroll
         for (int r = 0; r < kWSymLoads; ++r) {
             const uint32_t i = lane + 64u * r;
-            if (i < (uint32_t)kChunk / 2 + 1) stage[i + (i >> 5)] = tmp[r];   // word 2048 lands at 2112
+            if (i < (uint32_t)kChunk / 2 + 1) region[i + (i >> 5)] = tmp[r];   // word 2048 lands at 2112
         }
         w_wave_sync_lds();
         const int first = (int)lane * kSub;
         const int cnt = (int)k.n - first < 0 ? 0 : ((int)k.n - first > kSub ? kSub : (int)k.n - first);
-        uint32_t *row32 = stage + lane * (kWSymRow / 2);
+        uint32_t *row32 = region + lane * kWRowStride;
         uint32_t symw[kSub / 2];
         {
             uint32_t cur = row32[0];
 #pragma unroll
             for (int jj = 0; jj < kSub / 2; ++jj) {
-                const uint32_t nxt = row32[jj + 1 + (jj == kSub / 2 - 1 ? 1 : 0)];   // row32[32] is the row's pad
-                symw[jj] = shift ? __builtin_amdgcn_alignbit(nxt, cur, 16u) : cur;
+                const uint32_t nxt = row32[jj + 1 + (jj == kSub / 2 - 1 ? 1 : 0)];   // row32[32] is the row's spare slot
+                symw[jj] = (shift ? __builtin_amdgcn_alignbit(nxt, cur, 16u) : cur) & kWSymMask2;   // table indices stay below kWideMaxA
                 cur = nxt;
             }
         }
-        uint32_t bits = 0, nocode = 0;
-        // With the table in LDS both passes are unrolled so that the table look-ups overlap; codes longer than
-        // kWFastCodeBits send the chunk down the plain loops, which read the symbols from the LDS rows.
-        bool unrolled = in_lds;
-        if (in_lds) {
-            uint32_t maxlen = 0;
-#pragma unroll
-            for (int jj = 0; jj < kSub / 2; ++jj) {
-                const uint32_t l0 = s_fast[symw[jj] & 0xffffu] >> kWFastCodeBits;
-                const uint32_t l1 = s_fast[symw[jj] >> 16] >> kWFastCodeBits;
-                const bool h0 = 2 * jj < cnt, h1 = 2 * jj + 1 < cnt;
-                nocode += (h0 && l0 == 0u ? 1u : 0u) + (h1 && l1 == 0u ? 1u : 0u);
-                bits += (h0 ? l0 : 0u) + (h1 ? l1 : 0u);
-                maxlen = max(maxlen, max(h0 ? l0 : 0u, h1 ? l1 : 0u));
-            }
-            unrolled = !__any(maxlen > kWFastCodeBits);
-        }
-        const uint16_t *row = s_sym + lane * kWSymRow;
-        if (!unrolled) {   // whole wavefront
-            w_wave_sync_lds();   // every lane has read its words, the next row's first word included
+        w_wave_sync_lds();   // every lane holds its symbols: the rows are free
+
+        uint32_t bits = 0;
+        const bool in_lds = k.book == wg_book;   // whole wavefront: the table in LDS is this chunk's
+        int rows = kRowsSlow;
+        if (in_lds)
+            rows = k.n == (uint32_t)kChunk ? w_pack_rows<true>(symw, cnt, s_fast, region, lane, bits)
+                                           : w_pack_rows<false>(symw, cnt, s_fast, region, lane, bits);
+        const bool fast_ok = rows == kRowsOk;
+        const uint16_t *row = reinterpret_cast<const uint16_t *>(row32);
+        // what the plain loops know of a symbol: from the table in LDS where that is this chunk's and holds the
+        // symbol's code, else from device memory
+        auto lookup = [&](uint32_t sj, uint32_t &L, uint64_t &code) {
+            const uint32_t e = in_lds ? s_fast[sj] : (kWFastSlow << kWFastCodeBits);
+            L = e >> kWFastCodeBits;
+            code = e & ((1u << kWFastCodeBits) - 1u);
+            if (L == kWFastSlow) { L = book.len[sj]; code = book.code[sj]; }
+        };
+        if (rows == kRowsSlow) {
+            // a long code, a symbol without one, or another table: the symbols go back to the rows, plain loops
+            w_wave_sync_lds();
 #pragma unroll
             for (int jj = 0; jj < kSub / 2; ++jj) row32[jj] = symw[jj];
             w_wave_sync_lds();
-            bits = 0; nocode = 0;
+            uint32_t nocode = 0;
+            bits = 0;
             for (int j = 0; j < cnt; ++j) {
-                const uint32_t L = book.len[row[j]];
+                uint32_t L;
+                uint64_t code;
+                lookup(row[j], L, code);
                 nocode += L == 0u ? 1u : 0u;
                 bits += L;
             }
+            if (nocode)
+                atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NOCODE), (unsigned long long)nocode);
         }
-        if (nocode) atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NOCODE), (unsigned long long)nocode);
         sub_bits[((uint64_t)u * lay.nchunks + c) * kSubsPerChunk + lane] = (uint16_t)bits;
         const uint32_t incl = w_wave_inclusive_scan(bits, lane);
         const uint32_t excl = incl - bits;
@@ -538,8 +643,20 @@ __global__ __launch_bounds__(kWThreads) void k_pack_wide(Layout lay, const uint1
             continue;
         }
         uint32_t *dst = words + (uint64_t)u * words_stride + off_words;
-        for (uint32_t wbase = 0; wbase < nwords; wbase += kWWin) {
-            const uint32_t wn = nwords - wbase < (uint32_t)kWWin ? nwords - wbase : (uint32_t)kWWin;
+        if (fast_ok) {
+            w_rows_to_window(region, lane, bits, excl, nwords);
+            for (uint32_t i = lane; i < nwords; i += 64) __builtin_nontemporal_store(region[i], dst + i);
+            continue;
+        }
+        // Rows too short for some lane (more than 16 bits per symbol on average): the codewords are appended at
+        // their final bit offsets instead, entries from the table in LDS, the rows' storage as the window.  After
+        // the plain loops above: the same from the rows' symbols, a small window behind them.
+        const bool medium = rows == kRowsOverflow;
+        uint32_t *win = medium ? region : region + kWRegion;
+        const uint32_t wcap = medium ? (uint32_t)kWWinMedium : (uint32_t)kWWinSlow;
+        for (uint32_t wbase = 0; wbase < nwords; wbase += wcap) {
+            const uint32_t wn = nwords - wbase < wcap ? nwords - wbase : wcap;
+            w_wave_sync_lds();
             for (uint32_t i = lane; i <= wn; i += 64) win[i] = 0u;
             w_wave_sync_lds();
             uint32_t wi = (excl >> 5) - wbase;  // window word receiving the next completed 32 bits (may start below the window)
@@ -556,18 +673,17 @@ __global__ __launch_bounds__(kWThreads) void k_pack_wide(Layout lay, const uint1
             };
             // a lane whose bits all lie outside this window has nothing to add
             const bool overlaps = excl + bits > wbase * 32u && excl < (wbase + wn) * 32u;
-            if (unrolled) {   // whole wavefront; every code has at most kWFastCodeBits bits
+            if (medium) {   // whole wavefront; every existing symbol has a code of at most kWFastCodeBits bits
 #pragma unroll
-                for (int jj = 0; jj < kSub / 2; ++jj) {
-                    const uint32_t e0 = s_fast[symw[jj] & 0xffffu], e1 = s_fast[symw[jj] >> 16];
-                    if (overlaps && 2 * jj < cnt) append(e0 & ((1u << kWFastCodeBits) - 1u), e0 >> kWFastCodeBits);
-                    if (overlaps && 2 * jj + 1 < cnt) append(e1 & ((1u << kWFastCodeBits) - 1u), e1 >> kWFastCodeBits);
+                for (int j = 0; j < kSub; ++j) {
+                    const uint32_t e = s_fast[(j & 1) ? symw[j >> 1] >> 16 : symw[j >> 1] & 0xffffu];
+                    if (overlaps && j < cnt) append(e & ((1u << kWFastCodeBits) - 1u), e >> kWFastCodeBits);
                 }
             }
-            for (int j = 0; !unrolled && overlaps && j < cnt; ++j) {
-                const uint32_t s = row[j];
-                uint32_t L = book.len[s];
-                uint64_t code = book.code[s];
+            for (int j = 0; !medium && overlaps && j < cnt; ++j) {
+                uint32_t L;
+                uint64_t code;
+                lookup(row[j], L, code);
                 if (!L) continue;
                 if (L > 32u) {
                     append(code >> 32, L - 32u);
@@ -618,38 +734,12 @@ __device__ inline void w_load_tabs(WideTabs *T, const BookWide &book, uint32_t t
     if (t == 0) { T->maxlen = book.maxlen > 64u ? 64u : book.maxlen; T->pad = 0; }
 }
 
-// Where a chunk's payload words are read from: global memory, or the wavefront's copy of them in LDS.
-// Neither reads outside w[0 .. nw).
+// A chunk's payload words in global memory; reads nothing outside w[0 .. nw).
 struct WGlobalWords {
     const uint32_t *w;
     uint32_t nw;
     __device__ inline uint32_t word(uint32_t i) const { return i < nw ? w[i] : 0u; }
 };
-struct WLdsWords {
-    const uint32_t *w;   // LDS
-    uint32_t nw;
-    __device__ inline uint32_t word(uint32_t i) const { return i < nw ? w[i] : 0u; }
-};
-
-constexpr int kWStage = 1792;   // payload words a wavefront stages in LDS (14 bit/element); longer chunks are read in place
-
-// The chunk's nw <= kWStage words copied to the wavefront's LDS buffer, eight loads in flight per lane.
-__device__ inline void w_stage_payload(uint32_t *stage, const uint32_t *__restrict__ w, uint32_t nw, uint32_t lane)
-{
-    for (uint32_t base = 0; base < nw; base += 8u * 64u) {
-        uint32_t tmp[8];
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const uint32_t i = base + 64u * r + lane;
-            tmp[r] = i < nw ? __builtin_nontemporal_load(w + i) : 0u;
-        }
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const uint32_t i = base + 64u * r + lane;
-            if (i < nw) stage[i] = tmp[r];
-        }
-    }
-}
 
 // The three words of a chunk's payload at the read position, and the one after them, which is requested when the
 // position enters a new word and first used when it enters the next one: the load has the symbols in between
@@ -678,6 +768,7 @@ struct WReader {
     }
 };
 
+constexpr int kWRowsWave = kSubsPerChunk * kWSymRow;   // 16-bit units of a wavefront's 64 rows of decoded symbols
 constexpr int kWUpRegs = 12;   // lengths kWideDecBits + 1 .. kWideDecBits + 12 have their bound in a register
 
 // The bounds of lengths kWideDecBits + 1 .. kWideDecBits + kWUpRegs, top 32 bits (exact: a bound of length
@@ -749,10 +840,11 @@ __global__ __launch_bounds__(kWThreads) void k_decode_wide(Layout lay, const uin
                                                           uint64_t *__restrict__ status)
 {
     // The wavefronts of a workgroup decode the same chunk of four users: with one set of code tables for all
-    // users they share one copy of the chunk's table, else each keeps its own.
+    // users they share one copy of the chunk's table, else each keeps its own.  A lane decodes its sub-chunk
+    // into a row of LDS; the rows then go out in element order, 64 consecutive elements per store.
     extern __shared__ uint64_t wd_smem[];
-    uint32_t *s_stage = reinterpret_cast<uint32_t *>(wd_smem);                    // [kWWaves][kWStage]
-    WideTabs *s_tabs = reinterpret_cast<WideTabs *>(s_stage + kWWaves * kWStage);  // [1 or kWWaves]
+    uint16_t *s_rows = reinterpret_cast<uint16_t *>(wd_smem);                                // [kWWaves][64 rows]
+    WideTabs *s_tabs = reinterpret_cast<WideTabs *>(s_rows + kWWaves * kWRowsWave);           // [1 or kWWaves]
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint64_t c = blockIdx.x;
     const uint32_t u = blockIdx.y * kWWaves + wave;
@@ -764,10 +856,8 @@ __global__ __launch_bounds__(kWThreads) void k_decode_wide(Layout lay, const uin
     const WChunk k = w_chunk(lay, c, u);
     const BookWide &book = books[k.book];
     WideTabs *T = &s_tabs[lay.per_user_books ? wave : 0u];
-    uint32_t *stage = s_stage + wave * kWStage;
+    uint16_t *rows = s_rows + wave * kWRowsWave;
     const WIndex ix = w_read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits, lane);
-    const bool staged = ix.nw <= (uint32_t)kWStage;   // whole wavefront
-    if (staged) w_stage_payload(stage, ix.w, ix.nw, lane);
     if (lay.per_user_books) w_load_tabs(T, book, lane, 64);
     w_wave_sync_lds();
     WUpper32 U32;
@@ -780,23 +870,25 @@ __global__ __launch_bounds__(kWThreads) void k_decode_wide(Layout lay, const uin
     const float inv_gain = lay.gain[2 * pair + 1];
     uint32_t pos = p0;
     bool bad = false;
-    auto run = [&](auto src) {
-        WReader<decltype(src)> rd{src, 0u, 0u, 0u, 0u, 0u};
-        rd.seek(p0);
-        for (int j = 0; j < cnt; ++j) {
-            uint32_t len;
-            const uint32_t s = w_decode_one(rd, pos, T, U32, len);
-            if (len == 0u) { bad = true; len = 1u; }
-            pos += len;
-            const uint64_t e = k.e0 + (uint64_t)first + (uint64_t)j;
-            if (sym) sym[(uint64_t)u * sym_stride + e] = (uint16_t)s;
-            if (q) q[(uint64_t)u * q_stride + e] = __fmul_rn(__uint_as_float(symbol_value_bits(s, lay.E, lay.M, bias)), inv_gain);
-        }
-    };
-    if (staged) run(WLdsWords{stage, ix.nw});
-    else run(WGlobalWords{ix.w, ix.nw});
+    WReader<WGlobalWords> rd{WGlobalWords{ix.w, ix.nw}, 0u, 0u, 0u, 0u, 0u};
+    rd.seek(p0);
+    for (int j = 0; j < cnt; ++j) {
+        uint32_t len;
+        const uint32_t s = w_decode_one(rd, pos, T, U32, len);
+        if (len == 0u) { bad = true; len = 1u; }
+        pos += len;
+        rows[lane * kWSymRow + j] = (uint16_t)s;
+    }
     if (bad || pos - p0 != ix.sb || !ix.ok)
         atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CORRUPT), 1ull);
+    w_wave_sync_lds();
+    for (uint32_t r = 0; r < (uint32_t)kSubsPerChunk; ++r) {   // row r = elements 64 r .. 64 r + 63 of the chunk
+        const uint32_t e = 64u * r + lane;
+        if (e >= k.n) break;
+        const uint32_t s = rows[r * kWSymRow + lane];
+        if (sym) sym[(uint64_t)u * sym_stride + k.e0 + e] = (uint16_t)s;
+        if (q) q[(uint64_t)u * q_stride + k.e0 + e] = __fmul_rn(__uint_as_float(symbol_value_bits(s, lay.E, lay.M, bias)), inv_gain);
+    }
 }
 
 constexpr int kWAccStride = kSub + 1;
@@ -955,10 +1047,10 @@ hipError_t launch_decode_wide(const Layout &lay, const co3_decode_args &a, const
 {
     if (lay.U == 0 || lay.nchunks == 0) return hipSuccess;
     const uint64_t sym_stride = symbol_row_stride(lay.d);
-    const size_t lds_fixed = (size_t)kWWaves * kWStage * sizeof(uint32_t);
+    const size_t lds_fixed = (size_t)kWWaves * kWRowsWave * sizeof(uint16_t);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_decode_wide),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)(lds_fixed + (size_t)kWWaves * sizeof(WideTabs)));   // 98 KB at most
+                                       (int)(lds_fixed + (size_t)kWWaves * sizeof(WideTabs)));   // 103 KB at most
     if (e != hipSuccess) return e;
     const size_t lds_used = lds_fixed + (lay.per_user_books ? (size_t)kWWaves : 1u) * sizeof(WideTabs);
     ProfScope prof(K_DECODE, s);

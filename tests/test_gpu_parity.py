@@ -734,6 +734,49 @@ def test_wide_long_codes_per_user_tables_and_device_builder():
         B.co3_build_codebook(E, M, 3, w3)
 
 
+def test_wide_coder_rows_overflow_and_mixed_chunks():
+    # a fixed code whose frequent symbols are not the data's: chunks of 18 bits per element (a lane's codewords
+    # do not fit its LDS row: appended at their final offsets instead), chunks of about 10 (the row coder), a chunk
+    # that mixes both, a ragged last chunk, at an odd element offset so that the symbols start mid-word
+    import torch
+    from paper_2204_08211_amd import binding as B
+    E, M, U = 4, 5, 2
+    A = 1 << (1 + E + M)
+    rng = np.random.default_rng(1600)
+    bias = np.array([[10, 10], [10, 10]], np.int32)
+    grid = orc.grid(E, M, 10)
+    light = rng.choice(np.arange(1, grid.size), 128, replace=False)         # magnitudes the table holds as rare
+    w = np.full(A, 1 << 12, np.uint64)
+    w[light] = 1; w[light + (A >> 1)] = 1
+    heavy = np.setdiff1d(np.arange(1, grid.size), light)
+    seg_len = [4097, 4096 * 3 + 1000]
+    d = sum(seg_len)
+    g = np.empty((U, d), np.float32)
+    for u in range(U):
+        k = rng.choice(heavy, d)
+        k[4097 + 0:4097 + 4096] = rng.choice(light, 4096)                   # a whole chunk of rare symbols
+        k[4097 + 4096 + 2000:4097 + 4096 + 2200] = rng.choice(light, 200)   # a chunk with some lanes of them
+        k[-500:] = rng.choice(light, 500)                                   # the ragged chunk's end
+        g[u] = (grid[k] * rng.choice([-1.0, 1.0], d)).astype(np.float32)
+    m = np.zeros_like(g)
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias, seg_len=seg_len, seg_book=[0, 0])
+    ref = gu.oracle_round(kw, g, m, 0.9, weights=w[None, :])
+    lens = ref["lens"][0]
+    assert lens[light].min() >= 17 and lens.max() <= 25 and lens[heavy].max() <= 11
+    gpu, (plan, books, buf, gt, mt) = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=w[None, :], max_code_len=25,
+                                                   want_decode=False)
+    for key, what in [("m_new", "memory"), ("chunk_offset", "chunk offsets"), ("sub_bits", "sub-chunk bits"),
+                      ("payload_bits", "payload bits")]:
+        gu.assert_bits_equal(gpu[key], ref[key], what)
+    for u, wds in enumerate(ref["words"]):
+        gu.assert_bits_equal(gpu["words"][u, :wds.size], wds, f"bitstream of user {u}")
+    avg = torch.zeros(d, dtype=torch.float32, device="cuda:0")
+    B.co3_ps_aggregate(plan, books, buf, avg)
+    torch.cuda.synchronize()
+    gu.assert_bits_equal(avg.cpu().numpy(), ref["avg"], "PS average")
+    assert int(buf.status[B.STAT_CORRUPT].item()) == 0 and int(gpu["status_encode"][B.STAT_NOCODE]) == 0
+
+
 @pytest.mark.parametrize("E,M", [(3, 5), (4, 5), (4, 6), (5, 6)])
 def test_wide_device_builder_against_the_oracle(E, M):
     # the builder's sort, merge with ties, depths and canonical ranks at every wide alphabet size: tables of many
