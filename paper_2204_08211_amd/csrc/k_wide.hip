@@ -756,15 +756,19 @@ struct WReader {
         w2 = src.word(i0 + 2u);
         w3 = src.word(i0 + 3u);
     }
-    // the 64 bits from bit `pos` on; pos never decreases between calls
-    __device__ inline uint64_t window(uint32_t pos)
+    // the 32 bits from bit `pos` on; pos never decreases between calls
+    __device__ inline uint32_t window32(uint32_t pos)
     {
         const uint32_t i = pos >> 5, s0 = pos & 31u;
         if (i == i0 + 1u) { w0 = w1; w1 = w2; w2 = w3; w3 = src.word(i + 3u); i0 = i; }
         else if (i != i0) seek(pos);
-        uint64_t full = (((uint64_t)w0 << 32) | w1) << s0;
-        if (s0) full |= (uint64_t)(w2 >> (32u - s0));
-        return full;
+        return s0 ? __builtin_amdgcn_alignbit(w0, w1, 32u - s0) : w0;   // ({w0, w1} >> (32 - s0)), low word
+    }
+    // the 32 bits after those, for the same pos
+    __device__ inline uint32_t next32(uint32_t pos) const
+    {
+        const uint32_t s0 = pos & 31u;
+        return s0 ? __builtin_amdgcn_alignbit(w1, w2, 32u - s0) : w1;
     }
 };
 
@@ -788,25 +792,42 @@ struct WUpper32 {
 template <class Src>
 __device__ inline uint32_t w_decode_one(WReader<Src> &r, uint32_t pos, const WideTabs *T, const WUpper32 &U32, uint32_t &len)
 {
-    const uint64_t full = r.window(pos);
-    const uint32_t e = T->dec[full >> (64 - kWideDecBits)];
+    const uint32_t hi = r.window32(pos);
+    const uint32_t e = T->dec[hi >> (32 - kWideDecBits)];
     if (e) { len = e >> 16; return e & 0xffffu; }
     const uint32_t maxlen = T->maxlen;   // <= 64
     len = 0;
     if (maxlen <= (uint32_t)kWideDecBits) return 0u;   // every code is in the prefix table
-    const uint32_t hi = (uint32_t)(full >> 32);
+    // the bounds in two halves: few codes reach the second
     uint32_t L = kWideDecBits + 1;
 #pragma unroll
-    for (int t = 0; t < kWUpRegs; ++t) L += hi >= U32.up[t] ? 1u : 0u;
-    if (L == kWideDecBits + 1 + kWUpRegs)   // longer than the registers cover
+    for (int t = 0; t < kWUpRegs / 2; ++t) L += hi >= U32.up[t] ? 1u : 0u;
+    if (L == kWideDecBits + 1 + kWUpRegs / 2) {
+#pragma unroll
+        for (int t = kWUpRegs / 2; t < kWUpRegs; ++t) L += hi >= U32.up[t] ? 1u : 0u;
+    }
+    uint64_t full = 0;
+    if (L == kWideDecBits + 1 + kWUpRegs) {   // longer than the registers cover
+        full = ((uint64_t)hi << 32) | r.next32(pos);
         for (uint32_t l = L; l < maxlen; ++l) L += full >= T->upper[l] ? 1u : 0u;
+    }
     L = min(L, maxlen);   // a window of ones passes the bounds that bound nothing, too
-    const uint64_t cde = full >> (64u - L);
-    const uint64_t f = T->first[L];
-    const uint32_t c = T->count[L];
-    if (cde < f || cde - f >= (uint64_t)c) return 0u;
+    uint32_t rank;
+    if (L <= 32u) {       // first[L] < 2^L: its low word is all of it
+        const uint32_t cde = hi >> (32u - L);
+        const uint32_t f = (uint32_t)T->first[L];
+        if (cde < f) return 0u;
+        rank = cde - f;
+    } else {
+        if (!full) full = ((uint64_t)hi << 32) | r.next32(pos);
+        const uint64_t cde = full >> (64u - L);
+        const uint64_t f = T->first[L];
+        if (cde < f || cde - f >= (uint64_t)kWideMaxA) return 0u;
+        rank = (uint32_t)(cde - f);
+    }
+    if (rank >= T->count[L]) return 0u;
     len = L;
-    return T->sorted[(T->offset[L] + (uint32_t)(cde - f)) & (kWideMaxA - 1)];
+    return T->sorted[(T->offset[L] + rank) & (kWideMaxA - 1)];
 }
 
 // Index entries of chunk c of user u, checked as in the byte decoder.
