@@ -100,6 +100,8 @@ __device__ inline WChunk w_chunk(const Layout &lay, uint64_t c, uint32_t u)
 // with another table begins) and at its end; the few elements of a tile that belong to another table than the
 // tile's first element are counted in global memory directly.
 constexpr int kWqTiles = 32;
+typedef float wf4 __attribute__((ext_vector_type(4)));
+typedef uint32_t wu2 __attribute__((ext_vector_type(2)));
 __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const float *__restrict__ g, const float *m,
                                                               float *m_out, uint16_t *__restrict__ sym,
                                                               uint64_t sym_stride, uint64_t row_stride, float gamma,
@@ -144,6 +146,43 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
         const uint64_t pair0 = (uint64_t)u * lay.nseg + seg0;
         const QConst qc0 = make_qconst(lay.E, lay.M, lay.bias[pair0]);
         const float gain0 = lay.gain[2 * pair0], inv_gain0 = lay.gain[2 * pair0 + 1];
+        if (one_layer && base + kWqTile <= lay.d) {
+            // a whole tile of one layer (rows and tiles start on 16-byte boundaries): thread t takes elements
+            // 4 t .. 4 t + 3 of each half, 16-byte loads and stores, four symbols per 8-byte store
+            wf4 gq[kWqPer / 4], mq[kWqPer / 4];
+#pragma unroll
+            for (int k = 0; k < kWqPer / 4; ++k) {
+                const uint64_t i = base + (uint64_t)k * (kWqThreads * 4) + threadIdx.x * 4;
+                gq[k] = __builtin_nontemporal_load(reinterpret_cast<const wf4 *>(gu + i));
+                mq[k] = *reinterpret_cast<const wf4 *>(mu + i);
+            }
+#pragma unroll
+            for (int k = 0; k < kWqPer / 4; ++k) {
+                const uint64_t i = base + (uint64_t)k * (kWqThreads * 4) + threadIdx.x * 4;
+                wf4 eo;
+                uint32_t sp[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float v = __fadd_rn(gq[k][j], __fmul_rn(gamma, mq[k][j]));
+                    const float y = __fmul_rn(v, gain0);
+                    uint32_t s, flags;
+                    float q;
+                    quantize(y, qc0, sign_shift, s, q, flags);
+                    q = __fmul_rn(q, inv_gain0);
+                    eo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
+                    n_nonfinite += flags & 1u;
+                    n_clamped += (flags >> 1) & 1u;
+                    sp[j] = s;
+                    atomicAdd(&s_hist[s & (kWideMaxA - 1)], 1u);
+                }
+                __builtin_nontemporal_store(eo, reinterpret_cast<wf4 *>(mo + i));
+                wu2 packed;
+                packed[0] = sp[0] | (sp[1] << 16);
+                packed[1] = sp[2] | (sp[3] << 16);
+                __builtin_nontemporal_store(packed, reinterpret_cast<wu2 *>(su + i));
+            }
+            continue;   // workgroup-uniform
+        }
         float gv[kWqPer], mv[kWqPer];   // the tile's loads are issued together
 #pragma unroll
         for (int k = 0; k < kWqPer; ++k) {
