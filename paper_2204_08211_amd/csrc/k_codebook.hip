@@ -3,6 +3,8 @@
 //
 // Same tie rule and canonical form as the host builder: leaves sorted by (weight, symbol),
 // internal nodes in creation order, merge the two smallest with leaves first on equal weight.
+// The merge runs in rounds that each pair off every node the serial merge would take before any
+// node it has yet to create; a table of 256 symbols takes some twenty rounds.
 #include "co3_internal.h"
 
 namespace co3 {
@@ -25,6 +27,8 @@ __global__ __launch_bounds__(kCbThreads) void k_build_books(BookDev *__restrict_
     __shared__ uint32_t cnt[65], off[65];
     __shared__ uint64_t first[65];
     __shared__ uint32_t sorted[kMaxA];
+    __shared__ uint64_t tmpw[kMaxA];      // a round's nodes in merged order: weight
+    __shared__ int tmpid[kMaxA];          // and node index
     __shared__ int err;
 
     const uint64_t myw = (t < (int)A) ? w[t] : 0;
@@ -53,37 +57,71 @@ __global__ __launch_bounds__(kCbThreads) void k_build_books(BookDev *__restrict_
     }
     __syncthreads();
 
-    if (t == 0 && n >= 2 && !err) {
-        // the two front entries of each queue live in registers, so that the load refilling a queue
-        // is not needed before the pick after next; an exhausted slot shows the sentinel
+    // The two-queue merge in rounds.  With T the sum of the two lightest nodes alive, every internal node alive and
+    // every leaf of weight <= T is taken before any node created from now on (their weights are >= T; on equal
+    // weights a leaf goes before an internal node and an older internal node before a newer one).  So the merged
+    // order of those nodes — a leaf's rank is its own index plus the number of lighter internal nodes, an internal
+    // node's its own plus the number of leaves that are not heavier — pairs off two by two exactly as the serial
+    // merge would; an odd one out stays at the head of its queue.  Every thread keeps the queue positions itself;
+    // a round has at most A <= 256 nodes, one per thread.
+    {
         const uint64_t kNone = ~0ull;
-        int li = 0, ii = n, made = n;
-        uint64_t lw0 = nw[0], lw1 = nw[1], iw0 = kNone, iw1 = kNone;
-        for (int step = 0; step < n - 1; ++step) {
-            int pick[2];
-            uint64_t pw[2];
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                if (lw0 != kNone && (iw0 == kNone || lw0 <= iw0)) {
-                    pick[r] = li; pw[r] = lw0;
-                    ++li;
-                    lw0 = lw1;
-                    lw1 = li + 1 < n ? nw[li + 1] : kNone;
-                } else {
-                    pick[r] = ii; pw[r] = iw0;
-                    ++ii;
-                    iw0 = iw1;
-                    iw1 = ii + 1 < made ? nw[ii + 1] : kNone;
-                }
+        int li = 0, ii = n, made = n;   // next leaf, next internal node, next node to create
+        auto lower_bound = [&](int lo, int hi, uint64_t x) {   // first index in [lo, hi) with nw[index] >= x
+            while (lo < hi) { const int mid = (lo + hi) >> 1; if (nw[mid] < x) lo = mid + 1; else hi = mid; }
+            return lo;
+        };
+        auto upper_bound = [&](int lo, int hi, uint64_t x) {   // first index in [lo, hi) with nw[index] > x
+            while (lo < hi) { const int mid = (lo + hi) >> 1; if (nw[mid] <= x) lo = mid + 1; else hi = mid; }
+            return lo;
+        };
+        while (n >= 2 && !err && (n - li) + (made - ii) > 1) {   // the same in every thread
+            const uint64_t c0 = li < n ? nw[li] : kNone, c1 = li + 1 < n ? nw[li + 1] : kNone;
+            const uint64_t c2 = ii < made ? nw[ii] : kNone, c3 = ii + 1 < made ? nw[ii + 1] : kNone;
+            // the two lightest of two sorted pairs
+            const uint64_t m1 = c0 < c2 ? c0 : c2;
+            const uint64_t r1 = c0 < c2 ? c1 : c0, r2 = c0 < c2 ? c2 : c3;
+            const uint64_t m2 = r1 < r2 ? r1 : r2;
+            const uint64_t T = m1 + m2;
+            if (T < m2 || T == kNone) {   // the weights of this table sum to 2^64 - 1 or more
+                if (t == 0) err = 1;
+                break;
             }
-            const uint64_t s = pw[0] + pw[1];
-            if (s < pw[1] || s == kNone) err = 1;  // the weights of this table sum to 2^64 - 1 or more
-            nw[made] = s;
-            parent[pick[0]] = made;
-            parent[pick[1]] = made;
-            if (ii == made) iw0 = s;            // the internal queue was empty: the new node is its head
-            else if (ii + 1 == made) iw1 = s;   // it held one node: the new one is second
-            ++made;
+            // leaves of weight <= T: they are sorted, so counting them (thread t looks at leaf li + t) gives the end
+            const int bL = __syncthreads_count(li + t < n && nw[li + t] <= T);
+            const int lj = li + bL;
+            const int bI = made - ii, nb = bL + bI;   // 2 <= nb <= 256: the two lightest are among them
+            if (t < nb) {
+                int node, r;
+                if (t < bL) {
+                    node = li + t;
+                    r = t + (lower_bound(ii, made, nw[node]) - ii);
+                } else {
+                    node = ii + (t - bL);
+                    r = (t - bL) + (upper_bound(li, lj, nw[node]) - li);
+                }
+                tmpw[r] = nw[node];
+                tmpid[r] = node;
+            }
+            __syncthreads();
+            const int npair = nb >> 1;
+            if (t < npair) {
+                const uint64_t wa = tmpw[2 * t], wb = tmpw[2 * t + 1];
+                const uint64_t sum = wa + wb;
+                if (sum < wb || sum == kNone) err = 1;
+                nw[made + t] = sum;
+                parent[tmpid[2 * t]] = made + t;
+                parent[tmpid[2 * t + 1]] = made + t;
+            }
+            __syncthreads();
+            int next_li = lj, next_ii = made;
+            if (nb & 1) {   // the heaviest of the batch stays: the last internal node unless a leaf is heavier
+                if (bI > 0 && (bL == 0 || nw[made - 1] >= nw[lj - 1])) next_ii = made - 1;
+                else next_li = lj - 1;
+            }
+            li = next_li;
+            ii = next_ii;
+            made += npair;
         }
     }
     __syncthreads();

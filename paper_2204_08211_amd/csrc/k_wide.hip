@@ -247,9 +247,8 @@ __global__ void k_zero_wide(uint64_t *p, uint64_t n)
 // ---- code tables ------------------------------------------------------------------------------------------
 
 // One workgroup per table.  A is a power of two (512 .. 4096).  Dynamic LDS: node weights (2 A x 8 bytes),
-// parents (2 A x 4 bytes), the leaves' symbols (A x 2 bytes).  Steps: bitonic sort of the symbols by
-// (weight, symbol) with the unused ones last; the two-queue merge by one thread, which keeps the heads of both
-// queues in registers and requests a queue's next entry when its head is taken, so that no step waits for LDS;
+// parents (2 A x 4 bytes), the leaves' symbols (A x 2 bytes), a round's merged nodes (A x 10 bytes).  Steps: bitonic
+// sort of the symbols by (weight, symbol) with the unused ones last; the two-queue merge in rounds of many pairs;
 // depth of every leaf; canonical order, the rank of a symbol among those of its length from wavefront ballots
 // (wavefront w owns symbols w A/16 .. (w + 1) A/16 - 1, in order).
 constexpr int kWbWaves = kWbThreads / 64;
@@ -261,6 +260,8 @@ __global__ __launch_bounds__(kWbThreads) void k_build_books_wide(BookWide *__res
     uint64_t *nw = wb_smem;                                        // [2 A] sorted leaves, then internal nodes
     int *parent = reinterpret_cast<int *>(nw + 2 * (size_t)A);      // [2 A]
     uint16_t *leaf_sym = reinterpret_cast<uint16_t *>(parent + 2 * (size_t)A);   // [A] sorted leaf -> symbol
+    uint64_t *tmpw = reinterpret_cast<uint64_t *>(leaf_sym + A);                 // [A] a round's nodes in merged order: weight
+    uint16_t *tmpid = reinterpret_cast<uint16_t *>(tmpw + A);                    // [A] and node index
     __shared__ uint32_t cnt[65], off[65];
     __shared__ uint64_t first[65];
     __shared__ uint32_t wcnt[kWbWaves][65];   // symbols of each length in a wavefront's range; then running ranks
@@ -307,32 +308,67 @@ __global__ __launch_bounds__(kWbThreads) void k_build_books_wide(BookWide *__res
         }
     }
 
-    if (t == 0 && nact >= 2 && !err) {
-        auto leaf = [&](int i) { return i < nact ? nw[i] : kNone; };
-        int li = 0, ii = nact, made = nact;
-        uint64_t l0 = leaf(0), l1 = leaf(1);   // leaves li, li + 1
-        uint64_t i0 = kNone, i1 = kNone;       // internal nodes ii, ii + 1 where they exist
-        for (int step = 0; step < nact - 1; ++step) {
-            int pick[2];
-            uint64_t pw[2];
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                if (l0 != kNone && (i0 == kNone || l0 <= i0)) {
-                    pick[r] = li++; pw[r] = l0;
-                    l0 = l1; l1 = leaf(li + 1);
-                } else {
-                    pick[r] = ii++; pw[r] = i0;
-                    i0 = i1; i1 = ii + 1 < made ? nw[ii + 1] : kNone;
-                }
+    // The two-queue merge in rounds.  With T the sum of the two lightest nodes alive, every internal node alive and
+    // every leaf of weight <= T is taken before any node created from now on (their weights are >= T; on equal
+    // weights a leaf goes before an internal node and an older internal node before a newer one).  So the merged
+    // order of those nodes — a leaf's rank is its own index plus the number of lighter internal nodes, an internal
+    // node's its own plus the number of leaves that are not heavier — pairs off two by two exactly as the serial
+    // merge would; an odd one out stays at the head of its queue.  Every thread keeps the queue positions itself.
+    {
+        int li = 0, ii = nact, made = nact;   // next leaf, next internal node, next node to create
+        auto lower_bound = [&](int lo, int hi, uint64_t x) {   // first index in [lo, hi) with nw[index] >= x
+            while (lo < hi) { const int mid = (lo + hi) >> 1; if (nw[mid] < x) lo = mid + 1; else hi = mid; }
+            return lo;
+        };
+        auto upper_bound = [&](int lo, int hi, uint64_t x) {   // first index in [lo, hi) with nw[index] > x
+            while (lo < hi) { const int mid = (lo + hi) >> 1; if (nw[mid] <= x) lo = mid + 1; else hi = mid; }
+            return lo;
+        };
+        while (nact >= 2 && !err && (nact - li) + (made - ii) > 1) {   // the same in every thread
+            uint64_t c[4] = {li < nact ? nw[li] : kNone, li + 1 < nact ? nw[li + 1] : kNone,
+                             ii < made ? nw[ii] : kNone, ii + 1 < made ? nw[ii + 1] : kNone};
+            // the two lightest of two sorted pairs
+            const uint64_t m1 = c[0] < c[2] ? c[0] : c[2];
+            const uint64_t r1 = c[0] < c[2] ? c[1] : c[0], r2 = c[0] < c[2] ? c[2] : c[3];
+            const uint64_t m2 = r1 < r2 ? r1 : r2;
+            const uint64_t T = m1 + m2;
+            if (T < m2 || T == kNone) {   // the table's weights sum to 2^64 - 1 or more
+                if (t == 0) err = 1;
+                break;
             }
-            const uint64_t sum = pw[0] + pw[1];
-            if (sum < pw[1] || sum == kNone) { err = 1; break; }  // the table's weights sum to 2^64 - 1 or more
-            nw[made] = sum;
-            if (made == ii) i0 = sum;
-            else if (made == ii + 1) i1 = sum;
-            parent[pick[0]] = made;
-            parent[pick[1]] = made;
-            ++made;
+            const int lj = upper_bound(li, nact, T);
+            const int bL = lj - li, bI = made - ii, nb = bL + bI;   // nb >= 2: the two lightest are among them
+            for (int e = (int)t; e < nb; e += kWbThreads) {
+                int node, r;
+                if (e < bL) {
+                    node = li + e;
+                    r = e + (lower_bound(ii, made, nw[node]) - ii);
+                } else {
+                    node = ii + (e - bL);
+                    r = (e - bL) + (upper_bound(li, lj, nw[node]) - li);
+                }
+                tmpw[r] = nw[node];
+                tmpid[r] = (uint16_t)node;
+            }
+            __syncthreads();
+            const int npair = nb >> 1;
+            for (int k = (int)t; k < npair; k += kWbThreads) {
+                const uint64_t wa = tmpw[2 * k], wb = tmpw[2 * k + 1];
+                const uint64_t sum = wa + wb;
+                if (sum < wb || sum == kNone) err = 1;
+                nw[made + k] = sum;
+                parent[tmpid[2 * k]] = made + k;
+                parent[tmpid[2 * k + 1]] = made + k;
+            }
+            __syncthreads();
+            int next_li = lj, next_ii = made;
+            if (nb & 1) {   // the heaviest of the batch stays: the last internal node unless a leaf is heavier
+                if (bI > 0 && (bL == 0 || nw[made - 1] >= nw[lj - 1])) next_ii = made - 1;
+                else next_li = lj - 1;
+            }
+            li = next_li;
+            ii = next_ii;
+            made += npair;
         }
     }
     __syncthreads();
@@ -1041,7 +1077,7 @@ hipError_t launch_build_books_wide(BookWide *books, uint32_t nbooks, uint32_t A,
                                    uint64_t *status, hipStream_t s)
 {
     if (nbooks == 0) return hipSuccess;
-    const size_t lds = (size_t)2 * A * (sizeof(uint64_t) + sizeof(int)) + (size_t)A * sizeof(uint16_t);   // 104 KB at A = 4096
+    const size_t lds = (size_t)2 * A * (sizeof(uint64_t) + sizeof(int)) + (size_t)A * (2 * sizeof(uint16_t) + sizeof(uint64_t));   // 144 KB at A = 4096
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_build_books_wide),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;

@@ -777,11 +777,11 @@ def test_wide_coder_rows_overflow_and_mixed_chunks():
     assert int(buf.status[B.STAT_CORRUPT].item()) == 0 and int(gpu["status_encode"][B.STAT_NOCODE]) == 0
 
 
-@pytest.mark.parametrize("E,M", [(3, 5), (4, 5), (4, 6), (5, 6)])
+@pytest.mark.parametrize("E,M", [(2, 1), (3, 2), (4, 3), (5, 2), (3, 5), (4, 5), (4, 6), (5, 6)])
 def test_wide_device_builder_against_the_oracle(E, M):
-    # the builder's sort, merge with ties, depths and canonical ranks at every wide alphabet size: tables of many
-    # equal weights, of one and two symbols, of distinct powers of two (a path), of counts as a round gives them,
-    # of few symbols spread over the alphabet, and an empty one
+    # the builders' sort, merge in rounds with ties, depths and canonical ranks at byte and wide alphabet sizes:
+    # tables of many equal weights, of one and two symbols, of distinct powers of two (a path), of counts as a
+    # round gives them, of few symbols spread over the alphabet, and an empty one
     import torch
     from paper_2204_08211_amd import binding as B
     A = 1 << (1 + E + M)
@@ -791,12 +791,18 @@ def test_wide_device_builder_against_the_oracle(E, M):
     tabs.append(np.ones(A, np.uint64))                                            # all equal: a full tree
     one = np.zeros(A, np.uint64); one[A - 3] = 5; tabs.append(one)
     two = np.zeros(A, np.uint64); two[0] = 7; two[A - 1] = 7; tabs.append(two)
-    path = np.zeros(A, np.uint64); idx = rng.choice(A, 40, replace=False)
-    path[idx] = np.uint64(1) << np.arange(40, dtype=np.uint64); tabs.append(path)
+    npath = min(40, A // 2)
+    path = np.zeros(A, np.uint64); idx = rng.choice(A, npath, replace=False)
+    path[idx] = np.uint64(1) << np.arange(npath, dtype=np.uint64); tabs.append(path)
     geo = np.floor(1e9 * np.exp(-np.abs(np.arange(A) - A / 2) / (A / 40))).astype(np.uint64); tabs.append(geo)
-    few = np.zeros(A, np.uint64); few[rng.choice(A, 100, replace=False)] = rng.integers(1, 1000, 100).astype(np.uint64)
+    nfew = min(100, A // 2)
+    few = np.zeros(A, np.uint64); few[rng.choice(A, nfew, replace=False)] = rng.integers(1, 1000, nfew).astype(np.uint64)
     tabs.append(few)
     big = rng.integers(1, 1 << 50, A).astype(np.uint64); tabs.append(big)
+    fib = np.zeros(A, np.uint64); nf = min(A, 60); a_, b_ = 1, 1
+    for i in range(nf):
+        fib[(7 * i) % A if A > 60 else i] = a_; a_, b_ = b_, a_ + b_
+    tabs.append(fib)                                                              # the deepest tree for its weights
     tabs.append(np.zeros(A, np.uint64))
     w = np.stack(tabs)
     books = B.co3_build_codebook(E, M, len(tabs), None)
