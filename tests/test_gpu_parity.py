@@ -778,7 +778,7 @@ def test_wide_coder_rows_overflow_and_mixed_chunks():
 
 
 @pytest.mark.parametrize("E,M", [(2, 1), (3, 2), (4, 3), (5, 2), (3, 5), (4, 5), (4, 6), (5, 6)])
-def test_wide_device_builder_against_the_oracle(E, M):
+def test_device_builders_against_the_oracle(E, M):
     # the builders' sort, merge in rounds with ties, depths and canonical ranks at byte and wide alphabet sizes:
     # tables of many equal weights, of one and two symbols, of distinct powers of two (a path), of counts as a
     # round gives them, of few symbols spread over the alphabet, and an empty one
