@@ -695,9 +695,9 @@ int co3o_aggregate_gain(const uint8_t *sym, uint32_t U, uint64_t d, int nseg,
 /* The sum over u = 0..U-1 and the two products are taken in fp64 (sum, then  */
 /* times 1/U, then times eta), the difference is rounded once to fp32.        */
 /* ------------------------------------------------------------------------- */
-int co3o_model_update(const uint8_t *sym, uint32_t U, uint64_t d, int nseg,
-                      const uint64_t *seg_len, const int32_t *bias,
-                      int exp_bits, int mant_bits, float eta, const float *w, float *w_out)
+static int model_update_any(const void *sym, int wide, uint32_t U, uint64_t d, int nseg,
+                            const uint64_t *seg_len, const int32_t *bias,
+                            int exp_bits, int mant_bits, float eta, const float *w, float *w_out)
 {
     if (U == 0) return CO3O_ERR_ARG;
     double inv_u = 1.0 / (double)U;
@@ -706,11 +706,24 @@ int co3o_model_update(const uint8_t *sym, uint32_t U, uint64_t d, int nseg,
         for (uint64_t i = elem; i < elem + seg_len[k]; ++i) {
             double acc = 0.0;
             for (uint32_t u = 0; u < U; ++u)
-                acc += co3o_value(sym[(size_t)u * d + i], exp_bits, mant_bits,
+                acc += co3o_value(sym_get(sym, wide, (size_t)u * d + i), exp_bits, mant_bits,
                                   bias[(size_t)u * nseg + k]);
             w_out[i] = (float)((double)w[i] - (double)eta * (acc * inv_u));
         }
         elem += seg_len[k];
     }
     return (elem == d) ? CO3O_OK : CO3O_ERR_ARG;
+}
+int co3o_model_update(const uint8_t *sym, uint32_t U, uint64_t d, int nseg,
+                      const uint64_t *seg_len, const int32_t *bias,
+                      int exp_bits, int mant_bits, float eta, const float *w, float *w_out)
+{
+    return model_update_any(sym, 0, U, d, nseg, seg_len, bias, exp_bits, mant_bits, eta, w, w_out);
+}
+/* The same for alphabets of 9 to 12 bits (16-bit symbols). */
+int co3o_model_update_w(const uint16_t *sym, uint32_t U, uint64_t d, int nseg,
+                        const uint64_t *seg_len, const int32_t *bias,
+                        int exp_bits, int mant_bits, float eta, const float *w, float *w_out)
+{
+    return model_update_any(sym, 1, U, d, nseg, seg_len, bias, exp_bits, mant_bits, eta, w, w_out);
 }

@@ -266,16 +266,18 @@ def aggregate(sym, seg_len, bias, E, M):
 
 def model_update(sym, seg_len, bias, E, M, eta, w):
     """PS model update of eq. (aggregate hat), Algorithm 1 line 14: w - (eta / U) sum_u ghat^(u), the sum
-    and products in fp64, one rounding to fp32.  sym [U][d] uint8, bias [U][nseg], w float32 [d]."""
-    sym = np.ascontiguousarray(sym, dtype=np.uint8)
+    and products in fp64, one rounding to fp32.  sym [U][d] uint8 (uint16 for alphabets of more than 8 bits),
+    bias [U][nseg], w float32 [d]."""
+    wide = is_wide(E, M)
+    sym = np.ascontiguousarray(sym, dtype=np.uint16 if wide else np.uint8)
     U, d = sym.shape
     sl = np.ascontiguousarray(seg_len, dtype=np.uint64)
     b = np.ascontiguousarray(np.broadcast_to(np.asarray(bias, np.int32), (U, sl.size)), dtype=np.int32)
     w = np.ascontiguousarray(w, dtype=np.float32)
     out = np.empty(d, dtype=np.float32)
-    rc = lib().co3o_model_update(_p(sym, C.c_uint8), C.c_uint32(U), C.c_uint64(d), C.c_int(sl.size), _p(sl, C.c_uint64),
-                                 _p(b, C.c_int32), C.c_int(E), C.c_int(M), C.c_float(float(np.float32(eta))),
-                                 _p(w, C.c_float), _p(out, C.c_float))
+    rc = (lib().co3o_model_update_w if wide else lib().co3o_model_update)(
+        sym.ctypes.data_as(C.c_void_p), C.c_uint32(U), C.c_uint64(d), C.c_int(sl.size), _p(sl, C.c_uint64),
+        _p(b, C.c_int32), C.c_int(E), C.c_int(M), C.c_float(float(np.float32(eta))), _p(w, C.c_float), _p(out, C.c_float))
     if rc != 0:
         raise ValueError(f"co3o_model_update: {rc}")
     return out

@@ -667,6 +667,13 @@ def test_wide_alphabets_both_encoders(E, M, d):
         st = buf.status.cpu().numpy()
         assert int(st[0]) == int(ref["counters"][0]) and int(st[1]) == int(ref["counters"][1])
         assert not st[2:].any()
+        # the PS update fused into the average (Algorithm 1 line 14)
+        w0 = np.random.default_rng(1250).normal(0, 1e-2, d).astype(np.float32)
+        w_t = torch.from_numpy(w0.copy()).to(dev)
+        B.co3_ps_aggregate(plan, books, buf, None, model=w_t, eta=0.37)
+        torch.cuda.synchronize()
+        gu.assert_bits_equal(w_t.cpu().numpy(), orc.model_update(ref["dec_sym"], seg_len, bias, E, M, 0.37, w0),
+                             "updated model")
 
     # the code built on the device from this round's counts, then the same code built on the host and held
     books = B.co3_build_codebook(E, M, plan.num_books, None)

@@ -80,3 +80,31 @@ def test_wide_hand_stream():
     assert r["rc"] == 0 and r["payload_bits"] == 5 and int(r["words"][0]) == 0b01101 << 27
     rc, back = orc.unpack(r["words"][:1], 5, [5], [0], lens, codes, r["chunk_offset"], r["sub_bits"])
     assert rc == 0 and np.array_equal(back, sym)
+
+
+def test_wide_model_update_against_exact_rationals():
+    # Algorithm 1 line 14 with 16-bit symbols: w - (eta / U) sum of representatives, against exact rational
+    # arithmetic; eta = 0 leaves the model alone; U = 4, eta = 1, w = 0 is minus the (exact) average
+    from fractions import Fraction
+    E, M, U, d = 5, 6, 3, 200
+    rng = np.random.default_rng(1801)
+    nm = orc.num_magnitudes(E, M)
+    sym = (rng.integers(0, nm, (U, d)) | (rng.integers(0, 2, (U, d)) << (E + M))).astype(np.uint16)
+    sym[sym == (1 << (E + M))] = 0                       # no negative zero
+    assert sym.max() > 255                               # beyond what a byte holds
+    bias = rng.integers(18, 26, (U, 1)).astype(np.int32)
+    w = rng.normal(0, 1e-2, d).astype(np.float32)
+    eta = np.float32(0.37)
+    got = orc.model_update(sym, [d], bias, E, M, eta, w)
+    exact_round = np.empty(d, np.float32)
+    for i in range(d):
+        total = sum(Fraction(orc.value(int(sym[u, i]), E, M, int(bias[u, 0]))) for u in range(U))
+        exact = Fraction(float(w[i])) - Fraction(float(eta)) * total / U
+        exact_round[i] = np.float32(float(exact))
+        assert abs(float(got[i]) - float(exact)) <= float(np.spacing(np.abs(exact_round[i]))), i
+    assert np.mean(got == exact_round) > 0.99
+    assert np.array_equal(orc.model_update(sym, [d], bias, E, M, 0.0, w), w)
+    sym4 = np.concatenate([sym, sym[:1]])
+    b4 = np.concatenate([bias, bias[:1]])
+    avg = orc.aggregate(sym4, [d], b4, E, M)
+    assert np.array_equal(orc.model_update(sym4, [d], b4, E, M, 1.0, np.zeros(d, np.float32)), -avg)
