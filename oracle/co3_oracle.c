@@ -267,13 +267,13 @@ int co3o_ef_step_w(const float *g, const float *m, uint64_t n, float gamma,
 /* m' is no longer the exact difference (ghat is itself rounded).  Non-finite  */
 /* y and clamping as R4, decided on y.                                         */
 /* ------------------------------------------------------------------------- */
-int co3o_ef_step_gain(const float *g, const float *m, uint64_t n, float gamma,
-                      int exp_bits, int mant_bits, int bias, float gain, float inv_gain,
-                      float *m_out, uint8_t *sym, float *q_out, uint64_t *counters)
+static int ef_step_gain_any(const float *g, const float *m, uint64_t n, float gamma,
+                            int exp_bits, int mant_bits, int bias, float gain, float inv_gain,
+                            float *m_out, void *sym, int wide, float *q_out, uint64_t *counters)
 {
-    if (1 + exp_bits + mant_bits > 8) return CO3O_ERR_FORMAT;
+    if (1 + exp_bits + mant_bits > (wide ? 12 : 8)) return CO3O_ERR_FORMAT;
     int nmag = co3o_num_magnitudes(exp_bits, mant_bits);
-    double mag[256];
+    double mag[2048];
     int rc = co3o_grid(exp_bits, mant_bits, bias, mag);
     if (rc < 0) return rc;
     for (uint64_t i = 0; i < n; ++i) {
@@ -286,11 +286,24 @@ int co3o_ef_step_gain(const float *g, const float *m, uint64_t n, float gamma,
         volatile float err = v - q;
         if (fl & 1) err = 0.0f;
         if (counters) { counters[0] += (fl & 1); counters[1] += (fl >> 1) & 1; }
-        sym[i] = (uint8_t)c;
+        sym_put(sym, wide, i, c);
         m_out[i] = err;
         if (q_out) q_out[i] = q;
     }
     return CO3O_OK;
+}
+int co3o_ef_step_gain(const float *g, const float *m, uint64_t n, float gamma,
+                      int exp_bits, int mant_bits, int bias, float gain, float inv_gain,
+                      float *m_out, uint8_t *sym, float *q_out, uint64_t *counters)
+{
+    return ef_step_gain_any(g, m, n, gamma, exp_bits, mant_bits, bias, gain, inv_gain, m_out, sym, 0, q_out, counters);
+}
+/* The same for alphabets of 9 to 12 bits (16-bit symbols). */
+int co3o_ef_step_gain_w(const float *g, const float *m, uint64_t n, float gamma,
+                        int exp_bits, int mant_bits, int bias, float gain, float inv_gain,
+                        float *m_out, uint16_t *sym, float *q_out, uint64_t *counters)
+{
+    return ef_step_gain_any(g, m, n, gamma, exp_bits, mant_bits, bias, gain, inv_gain, m_out, sym, 1, q_out, counters);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -666,9 +679,9 @@ int co3o_aggregate_w(const uint16_t *sym, uint32_t U, uint64_t d, int nseg,
 
 /* The same average when the users' representatives carry a real-valued scale */
 /* (reading R16): ghat = fl32(value(sym) c) with c = inv_gain[u][k], fp32.     */
-int co3o_aggregate_gain(const uint8_t *sym, uint32_t U, uint64_t d, int nseg,
-                        const uint64_t *seg_len, const int32_t *bias, const float *inv_gain,
-                        int exp_bits, int mant_bits, float *out)
+static int aggregate_gain_any(const void *sym, int wide, uint32_t U, uint64_t d, int nseg,
+                              const uint64_t *seg_len, const int32_t *bias, const float *inv_gain,
+                              int exp_bits, int mant_bits, float *out)
 {
     if (U == 0) return CO3O_ERR_ARG;
     double inv_u = 1.0 / (double)U;
@@ -677,7 +690,7 @@ int co3o_aggregate_gain(const uint8_t *sym, uint32_t U, uint64_t d, int nseg,
         for (uint64_t i = elem; i < elem + seg_len[k]; ++i) {
             double acc = 0.0;
             for (uint32_t u = 0; u < U; ++u) {
-                volatile float val = (float)co3o_value(sym[(size_t)u * d + i], exp_bits, mant_bits,
+                volatile float val = (float)co3o_value(sym_get(sym, wide, (size_t)u * d + i), exp_bits, mant_bits,
                                                        bias[(size_t)u * nseg + k]);
                 volatile float q = val * inv_gain[(size_t)u * nseg + k];
                 acc += (double)q;
@@ -687,6 +700,18 @@ int co3o_aggregate_gain(const uint8_t *sym, uint32_t U, uint64_t d, int nseg,
         elem += seg_len[k];
     }
     return (elem == d) ? CO3O_OK : CO3O_ERR_ARG;
+}
+int co3o_aggregate_gain(const uint8_t *sym, uint32_t U, uint64_t d, int nseg,
+                        const uint64_t *seg_len, const int32_t *bias, const float *inv_gain,
+                        int exp_bits, int mant_bits, float *out)
+{
+    return aggregate_gain_any(sym, 0, U, d, nseg, seg_len, bias, inv_gain, exp_bits, mant_bits, out);
+}
+int co3o_aggregate_gain_w(const uint16_t *sym, uint32_t U, uint64_t d, int nseg,
+                          const uint64_t *seg_len, const int32_t *bias, const float *inv_gain,
+                          int exp_bits, int mant_bits, float *out)
+{
+    return aggregate_gain_any(sym, 1, U, d, nseg, seg_len, bias, inv_gain, exp_bits, mant_bits, out);
 }
 
 /* ------------------------------------------------------------------------- */

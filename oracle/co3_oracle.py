@@ -107,13 +107,15 @@ def ef_step_gain(g, m, gamma, E, M, bias, gain, inv_gain, want_q=True):
     m = np.ascontiguousarray(m, dtype=np.float32)
     assert g.shape == m.shape and g.ndim == 1
     m_out = np.empty_like(g)
-    sym = np.empty(g.shape, dtype=np.uint8)
+    wide = is_wide(E, M)
+    sym = np.empty(g.shape, dtype=np.uint16 if wide else np.uint8)
     q = np.empty_like(g) if want_q else None
     counters = np.zeros(2, dtype=np.uint64)
-    rc = lib().co3o_ef_step_gain(_p(g, C.c_float), _p(m, C.c_float), C.c_uint64(g.size), C.c_float(np.float32(gamma)),
-                                 C.c_int(E), C.c_int(M), C.c_int(bias), C.c_float(np.float32(gain)),
-                                 C.c_float(np.float32(inv_gain)), _p(m_out, C.c_float), _p(sym, C.c_uint8),
-                                 _p(q, C.c_float) if want_q else None, _p(counters, C.c_uint64))
+    rc = (lib().co3o_ef_step_gain_w if wide else lib().co3o_ef_step_gain)(
+        _p(g, C.c_float), _p(m, C.c_float), C.c_uint64(g.size), C.c_float(np.float32(gamma)),
+        C.c_int(E), C.c_int(M), C.c_int(bias), C.c_float(np.float32(gain)),
+        C.c_float(np.float32(inv_gain)), _p(m_out, C.c_float), sym.ctypes.data_as(C.c_void_p),
+        _p(q, C.c_float) if want_q else None, _p(counters, C.c_uint64))
     if rc < 0:
         raise ValueError(f"co3o_ef_step_gain: {rc}")
     return m_out, sym, q, counters
@@ -121,15 +123,17 @@ def ef_step_gain(g, m, gamma, E, M, bias, gain, inv_gain, want_q=True):
 
 def aggregate_gain(sym, seg_len, bias, inv_gain, E, M):
     """(1/U) sum_u ghat^(u) with ghat = fl32(value(sym) inv_gain[u][layer]) (reading R16)."""
-    sym = np.ascontiguousarray(sym, dtype=np.uint8)
+    wide = is_wide(E, M)
+    sym = np.ascontiguousarray(sym, dtype=np.uint16 if wide else np.uint8)
     U, d = sym.shape
     seg_len = np.ascontiguousarray(seg_len, dtype=np.uint64)
     bias = np.ascontiguousarray(bias, dtype=np.int32).reshape(U, seg_len.size)
     inv_gain = np.ascontiguousarray(inv_gain, dtype=np.float32).reshape(U, seg_len.size)
     out = np.empty(d, dtype=np.float32)
-    rc = lib().co3o_aggregate_gain(_p(sym, C.c_uint8), C.c_uint32(U), C.c_uint64(d), C.c_int(seg_len.size),
-                                   _p(seg_len, C.c_uint64), _p(bias, C.c_int32), _p(inv_gain, C.c_float), C.c_int(E),
-                                   C.c_int(M), _p(out, C.c_float))
+    rc = (lib().co3o_aggregate_gain_w if wide else lib().co3o_aggregate_gain)(
+        sym.ctypes.data_as(C.c_void_p), C.c_uint32(U), C.c_uint64(d), C.c_int(seg_len.size),
+        _p(seg_len, C.c_uint64), _p(bias, C.c_int32), _p(inv_gain, C.c_float), C.c_int(E),
+        C.c_int(M), _p(out, C.c_float))
     if rc < 0:
         raise ValueError(f"co3o_aggregate_gain: {rc}")
     return out

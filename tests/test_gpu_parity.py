@@ -508,11 +508,12 @@ def test_tiny_vectors_both_encoders(d):
 
 # ---- real-valued scale on top of the integer bias (eq. (exp bias) with b in R) --------------------
 
-def _gain_case(single_sweep, U=3):
+def _gain_case(single_sweep, U=3, E=4, M=3):
     import torch
     from oracle import co3_bias_model as bm
     from paper_2204_08211_amd import binding as B
-    E, M = 4, 3
+    A = 1 << (1 + E + M)
+    sym_t = np.uint16 if A > 256 else np.uint8
     seg_len = [4096 * 2 + 77, 0, 4096 * 3, 1000]
     seg_book = [0, 1, 1, 0]
     nseg = len(seg_len)
@@ -525,7 +526,7 @@ def _gain_case(single_sweep, U=3):
     for k, n in enumerate(seg_len):
         for u in range(U):
             beta, alpha = 0.7 + 0.3 * u, 10.0 ** (-3 + 0.5 * k)
-            b, _ = bm.best_real_scale(bm.signed_set(E, M, 7), alpha, beta, lo=-30, hi=10, step=0.25)
+            b, _ = bm.best_real_scale(bm.signed_set(E, M, (1 << (E - 1)) - 1), alpha, beta, lo=-30, hi=10, step=0.25)
             bias[u, k], gain[u, k], inv_gain[u, k] = bm.split_real_scale(E, b)
             g[u, off:off + n] = syn.gennorm_numpy(rng, n, beta, alpha)
             m[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, alpha / 5)
@@ -535,16 +536,16 @@ def _gain_case(single_sweep, U=3):
     kw = dict(E=E, M=M, U=U, d=d, bias=bias, seg_len=seg_len, seg_book=seg_book)
     gamma = 0.9
     # the oracle: Algorithm 1 lines 8-10 with the scaled set, then the code of its own histogram
-    sym = np.empty((U, d), np.uint8); m_ref = np.empty_like(g); q_ref = np.empty_like(g)
+    sym = np.empty((U, d), sym_t); m_ref = np.empty_like(g); q_ref = np.empty_like(g)
     counters = np.zeros(2, np.uint64)
-    hist = np.zeros((2, 256), np.uint64)
+    hist = np.zeros((2, A), np.uint64)
     off = 0
     for k, n in enumerate(seg_len):
         for u in range(U):
             mo, so, qo, cnt = orc.ef_step_gain(g[u, off:off + n], m[u, off:off + n], gamma, E, M, int(bias[u, k]),
                                                gain[u, k], inv_gain[u, k])
             sym[u, off:off + n] = so; m_ref[u, off:off + n] = mo; q_ref[u, off:off + n] = qo; counters += cnt
-            orc.histogram(so, 256, hist[seg_book[k]])
+            orc.histogram(so, A, hist[seg_book[k]])
         off += n
     lens = np.stack([orc.huffman_lengths(hist[b]) for b in range(2)])
     codes = np.stack([orc.canonical_codes(lens[b]) for b in range(2)])
@@ -571,7 +572,7 @@ def _gain_case(single_sweep, U=3):
     torch.cuda.synchronize()
     gu.assert_bits_equal(mt[:, :d].cpu().numpy(), m_ref, "memory m'")
     if not single_sweep:
-        gu.assert_bits_equal(buf.symbols_2d().cpu().numpy(), sym, "symbols")
+        gu.assert_bits_equal(buf.symbols_2d().cpu().numpy().view(sym_t), sym, "symbols")
         gu.assert_bits_equal(buf.hist.cpu().numpy().view(np.uint64), hist, "histogram")
     for b in range(2):
         lb, cb = books.export(b)
@@ -580,7 +581,7 @@ def _gain_case(single_sweep, U=3):
         r = orc.pack(sym[u], seg_len, seg_book, lens, codes)
         nw = int(r["chunk_offset"][-1]) // 32
         gu.assert_bits_equal(buf.words[u, :nw].cpu().numpy().view(np.uint32), r["words"][:nw], f"bitstream of user {u}")
-    gu.assert_bits_equal(symd[:U * plan.sym_stride].view(U, plan.sym_stride)[:, :d].cpu().numpy(), sym, "decoded symbols")
+    gu.assert_bits_equal(B.symbols_2d(plan, symd).cpu().numpy().view(sym_t), sym, "decoded symbols")
     gu.assert_bits_equal(qd[:, :d].cpu().numpy(), q_ref, "decoded values")
     gu.assert_bits_equal(avg.cpu().numpy(), avg_ref, "PS average")
     st = buf.status.cpu().numpy()
@@ -588,6 +589,8 @@ def _gain_case(single_sweep, U=3):
     # not defined together with the stochastic conversion; and switching the scale off restores the plain step
     with pytest.raises(B.Co3Error):
         B.co3_encode(plan, books, gt, mt, mt, gamma, buf, mode=B.BOOK_FIXED, single_sweep=True, stochastic_seed=1)
+    if A > 256:   # the reference loops below use the byte oracle's entry points
+        return
     plan.set_gain(None, None)
     mt[:, :d] = torch.from_numpy(m).to(dev)
     B.co3_encode(plan, books, gt, mt, mt, gamma, buf, mode=B.BOOK_EMPIRICAL)
@@ -595,13 +598,18 @@ def _gain_case(single_sweep, U=3):
     n0 = seg_len[0]
     mo, so, _, _ = orc.ef_step(g[1, :n0], m[1, :n0], gamma, E, M, int(bias[1, 0]), want_q=False)
     gu.assert_bits_equal(mt[1, :n0].cpu().numpy(), mo, "memory m' with the scale switched off")
-    gu.assert_bits_equal(buf.symbols_2d()[1, :n0].cpu().numpy(), so, "symbols with the scale switched off")
+    gu.assert_bits_equal(buf.symbols_2d()[1, :n0].cpu().numpy().view(sym_t), so, "symbols with the scale switched off")
 
 
 @pytest.mark.parametrize("single_sweep,U", [(False, 3), (True, 3), (True, 7)])
 def test_real_valued_scale_both_encoders(single_sweep, U):
     # U = 7: the PS average takes the kernel for five or more users (values scaled from one table)
     _gain_case(single_sweep, U)
+
+
+@pytest.mark.parametrize("single_sweep", [False, True])
+def test_real_valued_scale_wide_alphabet(single_sweep):
+    _gain_case(single_sweep, 3, E=5, M=5)
 
 
 # ---- alphabets wider than one byte (9 to 12 symbol bits, 16-bit symbols) ---------------------------------

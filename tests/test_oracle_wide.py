@@ -108,3 +108,39 @@ def test_wide_model_update_against_exact_rationals():
     b4 = np.concatenate([bias, bias[:1]])
     avg = orc.aggregate(sym4, [d], b4, E, M)
     assert np.array_equal(orc.model_update(sym4, [d], b4, E, M, 1.0, np.zeros(d, np.float32)), -avg)
+
+
+def test_wide_real_scale_special_cases_and_nearest_element():
+    # the scaled conversion with 16-bit symbols: gain 1 is the plain step; a power-of-two gain is a shift of the
+    # bias; for a general scale c every output is the nearest element of {c x} to the scaled input's pre-image,
+    # checked in exact rationals on the representatives next to it; the average with inv_gain 1 is the plain one
+    from fractions import Fraction
+    import co3_synth as syn
+    E, M, bias = 5, 5, 24
+    rng = np.random.default_rng(1802)
+    g = syn.gennorm_numpy(rng, 20_000, 0.9, 2e-3); m = syn.gennorm_numpy(rng, 20_000, 1.0, 5e-4)
+    ref = orc.ef_step(g, m, 0.9, E, M, bias)
+    got = orc.ef_step_gain(g, m, 0.9, E, M, bias, 1.0, 1.0)
+    assert got[1].dtype == np.uint16 and got[1].max() > 255
+    assert np.array_equal(ref[1], got[1]) and np.array_equal(ref[0].view(np.uint32), got[0].view(np.uint32))
+    ref2 = orc.ef_step(g, m, 0.9, E, M, bias + 2)
+    got2 = orc.ef_step_gain(g, m, 0.9, E, M, bias, 4.0, 0.25)
+    assert np.array_equal(ref2[1], got2[1]) and np.array_equal(ref2[0].view(np.uint32), got2[0].view(np.uint32))
+    assert np.array_equal(ref2[2].view(np.uint32), got2[2].view(np.uint32))
+    # general scale: y = fl32(v s); the symbol's representative is the grid point nearest to y
+    s_gain, c = np.float32(1.0 / 1.3), np.float32(1.3)
+    mo, sym, q, _ = orc.ef_step_gain(g[:2000], np.zeros(2000, np.float32), 0.9, E, M, bias, s_gain, c)
+    grid = orc.grid(E, M, bias)
+    for i in range(2000):
+        y = Fraction(float(np.float32(g[i] * s_gain)))
+        k = int(sym[i]) & ((1 << (E + M)) - 1)
+        mine = abs(abs(y) - Fraction(float(grid[k])))
+        for kk in (k - 1, k + 1):
+            if 0 <= kk < grid.size:
+                assert mine <= abs(abs(y) - Fraction(float(grid[kk]))), i
+        assert np.float32(q[i]) == np.float32(np.float32(orc.value(int(sym[i]), E, M, bias)) * c)
+        assert np.float32(mo[i]) == np.float32(np.float32(g[i]) - np.float32(q[i]))
+    two = np.stack([got[1][:500], ref2[1][:500]])
+    b2 = np.array([[bias], [bias + 2]], np.int32)
+    assert np.array_equal(orc.aggregate_gain(two, [500], b2, np.ones((2, 1), np.float32), E, M),
+                          orc.aggregate(two, [500], b2, E, M))
