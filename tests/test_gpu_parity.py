@@ -688,6 +688,16 @@ def test_wide_alphabets_both_encoders(E, M, d):
     run(B.BOOK_EMPIRICAL, books, False)
     held = B.co3_build_codebook(E, M, plan.num_books, ref["hist"])
     run(B.BOOK_FIXED, held, True)
+    # the held code without a symbol buffer, this round's counts asked for as well
+    mt = torch.zeros((U, stride), dtype=torch.float32, device=dev); mt[:, :d] = torch.from_numpy(m).to(dev)
+    buf = B.RoundBuffers(plan, dev, max_code_len=40)
+    buf.hist.fill_(-1)
+    B.co3_encode(plan, held, gt, mt, mt, gamma, buf, mode=B.BOOK_FIXED, single_sweep=True, single_sweep_hist=True)
+    torch.cuda.synchronize()
+    gu.assert_bits_equal(buf.hist.cpu().numpy().view(np.uint64), ref["hist"], "histogram beside the held code")
+    gu.assert_bits_equal(mt[:, :d].cpu().numpy(), ref["m_new"], "memory m'")
+    for u, wds in enumerate(ref["words"]):
+        gu.assert_bits_equal(buf.words[u, :wds.size].cpu().numpy().view(np.uint32), wds, f"bitstream of user {u}")
     # not provided for wide alphabets
     mt = torch.zeros((U, stride), dtype=torch.float32, device=dev)
     buf = B.RoundBuffers(plan, dev, max_code_len=40)
