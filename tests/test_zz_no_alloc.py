@@ -14,12 +14,11 @@ pytestmark = pytest.mark.gpu
 KEYS = ("m", "symbols", "hist", "words", "chunk_offset", "sub_bits", "payload_bits", "status")
 
 
-def one_call(U, d, seed, single_sweep, static):
+def one_call(U, d, seed, single_sweep, static, E=4, M=3):
     """One encode through co3_encode or co3_encode_static on fresh buffers; every output as numpy."""
     import torch
     from paper_2204_08211_amd import binding as B
     dev = torch.device("cuda:0")
-    E, M = 4, 3
     rng = np.random.default_rng(seed)
     g = np.stack([syn.gennorm_numpy(rng, d, 0.9, 1e-3) for _ in range(U)])
     m = np.stack([syn.gennorm_numpy(rng, d, 1.1, 3e-4) for _ in range(U)])
@@ -61,6 +60,20 @@ def test_static_workspace_entry_point_equals_co3_encode(single_sweep):
             assert a[k].shape == b[k].shape and np.array_equal(a[k], b[k]), (U, d, k)
         assert int(a["status"][2:].sum()) == 0
         assert int(a["payload_bits"].sum()) > 0
+
+
+def test_static_workspace_entry_point_with_16_bit_symbols():
+    # the same two calls in a format of 11 bits, whose kernels keep other things in the workspace (partial
+    # histograms of 2048 entries, chunk sizes, and for the held code the symbols themselves)
+    shapes = [(3, 4096 * 40 + 77, 21), (2, 4096 + 905, 22)]
+    for single_sweep in (False, True):
+        static = [one_call(U, d, seed, single_sweep, True, 5, 5) for U, d, seed in shapes]
+        plain = [one_call(U, d, seed, single_sweep, False, 5, 5) for U, d, seed in shapes]
+        for (U, d, _), a, b in zip(shapes, static, plain):
+            for k in KEYS + ("codes",):
+                assert a[k].shape == b[k].shape and np.array_equal(a[k], b[k]), (U, d, k, single_sweep)
+            assert int(a["status"][2:].sum()) == 0
+            assert int(a["payload_bits"].sum()) > 0
 
 
 def test_static_workspace_entry_point_refuses_what_does_not_fit():
