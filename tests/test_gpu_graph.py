@@ -11,17 +11,20 @@ import gpu_util as gu
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("single_sweep", [False, True])
-def test_round_in_a_graph_equals_eager(single_sweep):
+@pytest.mark.parametrize("single_sweep,E,M", [(False, 4, 3), (True, 4, 3), (False, 5, 5)])
+def test_round_in_a_graph_equals_eager(single_sweep, E, M):
+    # (5, 5): 16-bit symbols, the code rebuilt per round (the model code below is for alphabets of up to 8 bits)
     import torch
     from paper_2204_08211_amd import binding as B
-    E, M, U, d = 4, 3, 4, 4096 * 11 + 321
+    U, d = 4, 4096 * 11 + 321
     dev = torch.device("cuda:0")
     rng = np.random.default_rng(77)
     stride = (d + 3) // 4 * 4
-    plan = B.Plan(E, M, U, d, [[16]] * U)
+    bias0 = 16 if E == 4 else 24
+    plan = B.Plan(E, M, U, d, [[bias0]] * U)
     # a model code (every producible symbol has a codeword) for the fixed mode; rebuilt per round otherwise
-    books = B.co3_build_codebook(E, M, plan.num_books, B.co3_gennorm_weights(E, M, 16, 0.0, 5e-3, 1.0)[None, :])
+    books = B.co3_build_codebook(E, M, plan.num_books,
+                                 B.co3_gennorm_weights(E, M, 16, 0.0, 5e-3, 1.0)[None, :] if single_sweep else None)
     buf = B.RoundBuffers(plan, dev, max_code_len=64)
     g = torch.zeros((U, stride), dtype=torch.float32, device=dev)
     m = torch.zeros((U, stride), dtype=torch.float32, device=dev)
