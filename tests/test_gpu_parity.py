@@ -705,6 +705,29 @@ def test_wide_alphabets_both_encoders(E, M, d):
         B.co3_encode(plan, held, gt, mt, mt, gamma, buf, mode=B.BOOK_FIXED, single_sweep=True, stochastic_seed=3)
 
 
+@pytest.mark.parametrize("U,per_user", [(1, False), (17, False), (9, True)])
+def test_wide_user_counts_through_the_average(U, per_user):
+    # one user; more users than a workgroup of the average has wavefronts (several passes per wavefront), with one
+    # set of tables and with a set per user; two layers with their own tables, a ragged last chunk
+    E, M = 4, 5
+    seg_len = [4096 + 9, 4096 * 2 - 1]
+    d = sum(seg_len)
+    rng = np.random.default_rng(1900 + U)
+    bias = rng.integers(10, 14, (U, 2)).astype(np.int32)
+    g = np.empty((U, d), np.float32); m = np.empty((U, d), np.float32)
+    off = 0
+    for k, n in enumerate(seg_len):
+        for u in range(U):
+            top = orc.grid(E, M, int(bias[u, k]))[-1]
+            g[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, top / 50)
+            m[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, top / 300)
+        off += n
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias, seg_len=seg_len, seg_book=[0, 1], per_user_books=per_user)
+    ref = gu.oracle_round(kw, g, m, 0.9)
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_EMPIRICAL, max_code_len=40)
+    gu.compare_round(gpu, ref, d)
+
+
 def test_wide_long_codes_per_user_tables_and_device_builder():
     # weights 1, 1, 2, 4, ... on the symbols that occur give codes of up to 61 bits (both halves of the coder's
     # 64-bit append, the decoder's search by length); a table per user; the device builder on the same weights
