@@ -364,13 +364,13 @@ static float quantize_one_sr(const double *mag, int nmag, int mant_bits, int sig
 
 /* Algorithm 1 lines 8 and 10 with the stochastic conversion.  `user` and     */
 /* `elem0` (index of g[0] within the user's vector) select the random words.  */
-int co3o_ef_step_sr(const float *g, const float *m, uint64_t n, float gamma,
-                    int exp_bits, int mant_bits, int bias, uint32_t user, uint64_t elem0, uint64_t seed,
-                    float *m_out, uint8_t *sym, float *q_out, uint64_t *counters)
+static int ef_step_sr_any(const float *g, const float *m, uint64_t n, float gamma,
+                          int exp_bits, int mant_bits, int bias, uint32_t user, uint64_t elem0, uint64_t seed,
+                          float *m_out, void *sym, int wide, float *q_out, uint64_t *counters)
 {
-    if (1 + exp_bits + mant_bits > 8) return CO3O_ERR_FORMAT;
+    if (1 + exp_bits + mant_bits > (wide ? 12 : 8)) return CO3O_ERR_FORMAT;
     int nmag = co3o_num_magnitudes(exp_bits, mant_bits);
-    double mag[256];
+    double mag[2048];
     int rc = co3o_grid(exp_bits, mant_bits, bias, mag);
     if (rc < 0) return rc;
     uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
@@ -385,11 +385,24 @@ int co3o_ef_step_sr(const float *g, const float *m, uint64_t n, float gamma,
         volatile float err = v - q;
         if (fl & 1) err = 0.0f;
         if (counters) { counters[0] += (fl & 1); counters[1] += (fl >> 1) & 1; }
-        sym[i] = (uint8_t)c;
+        sym_put(sym, wide, i, c);
         m_out[i] = err;
         if (q_out) q_out[i] = q;
     }
     return CO3O_OK;
+}
+int co3o_ef_step_sr(const float *g, const float *m, uint64_t n, float gamma,
+                    int exp_bits, int mant_bits, int bias, uint32_t user, uint64_t elem0, uint64_t seed,
+                    float *m_out, uint8_t *sym, float *q_out, uint64_t *counters)
+{
+    return ef_step_sr_any(g, m, n, gamma, exp_bits, mant_bits, bias, user, elem0, seed, m_out, sym, 0, q_out, counters);
+}
+/* The same for alphabets of 9 to 12 bits (16-bit symbols). */
+int co3o_ef_step_sr_w(const float *g, const float *m, uint64_t n, float gamma,
+                      int exp_bits, int mant_bits, int bias, uint32_t user, uint64_t elem0, uint64_t seed,
+                      float *m_out, uint16_t *sym, float *q_out, uint64_t *counters)
+{
+    return ef_step_sr_any(g, m, n, gamma, exp_bits, mant_bits, bias, user, elem0, seed, m_out, sym, 1, q_out, counters);
 }
 
 /* Symbol counts (the "distribution of the data source" that Huffman coding

@@ -155,13 +155,15 @@ def ef_step_sr(g, m, gamma, E, M, bias, user, elem0, seed, want_q=True):
     m = np.ascontiguousarray(m, dtype=np.float32)
     n = g.size
     m_out = np.empty(n, dtype=np.float32)
-    sym = np.empty(n, dtype=np.uint8)
+    wide = is_wide(E, M)
+    sym = np.empty(n, dtype=np.uint16 if wide else np.uint8)
     q = np.empty(n, dtype=np.float32) if want_q else None
     cnt = np.zeros(2, dtype=np.uint64)
-    rc = lib().co3o_ef_step_sr(_p(g, C.c_float), _p(m, C.c_float), C.c_uint64(n), C.c_float(float(np.float32(gamma))),
-                               C.c_int(E), C.c_int(M), C.c_int(int(bias)), C.c_uint32(int(user)), C.c_uint64(int(elem0)),
-                               C.c_uint64(int(seed)), _p(m_out, C.c_float), _p(sym, C.c_uint8),
-                               _p(q, C.c_float) if want_q else None, _p(cnt, C.c_uint64))
+    rc = (lib().co3o_ef_step_sr_w if wide else lib().co3o_ef_step_sr)(
+        _p(g, C.c_float), _p(m, C.c_float), C.c_uint64(n), C.c_float(float(np.float32(gamma))),
+        C.c_int(E), C.c_int(M), C.c_int(int(bias)), C.c_uint32(int(user)), C.c_uint64(int(elem0)),
+        C.c_uint64(int(seed)), _p(m_out, C.c_float), sym.ctypes.data_as(C.c_void_p),
+        _p(q, C.c_float) if want_q else None, _p(cnt, C.c_uint64))
     if rc != 0:
         raise ValueError(f"co3o_ef_step_sr: {rc}")
     return m_out, sym, q, cnt

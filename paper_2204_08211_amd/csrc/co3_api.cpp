@@ -397,9 +397,7 @@ static int encode_with_workspace(const co3_plan *plan, const co3_encode_args *a,
     args.workspace = workspace;
     args.workspace_bytes = workspace_bytes;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (lay.wide) {   // alphabets above 8 bits: closest representative only; a fixed code without a symbol buffer
-                      // keeps its symbols in the workspace
-        if (a->rounding != CO3_ROUND_NEAREST) return CO3_ERR_ARG;
+    if (lay.wide) {   // alphabets above 8 bits: a fixed code without a symbol buffer keeps its symbols in the workspace
         return launch_encode_wide(lay, args, a->books->d_wide, workspace, s) == hipSuccess ? CO3_OK : CO3_ERR_HIP;
     }
     if (single_sweep)

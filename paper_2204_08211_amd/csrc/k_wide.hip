@@ -102,10 +102,13 @@ __device__ inline WChunk w_chunk(const Layout &lay, uint64_t c, uint32_t u)
 constexpr int kWqTiles = 32;
 typedef float wf4 __attribute__((ext_vector_type(4)));
 typedef uint32_t wu2 __attribute__((ext_vector_type(2)));
+// kSR: the stochastic conversion (dither from Philox words of (element, user, seed)) instead of the closest
+// representative.
+template <bool kSR>
 __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const float *__restrict__ g, const float *m,
                                                               float *m_out, uint16_t *__restrict__ sym,
                                                               uint64_t sym_stride, uint64_t row_stride, float gamma,
-                                                              uint64_t *__restrict__ hist_rep,
+                                                              uint64_t seed, uint64_t *__restrict__ hist_rep,
                                                               uint64_t *__restrict__ status)
 {
     __shared__ uint32_t s_hist[kWideMaxA];
@@ -144,7 +147,8 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
         const uint64_t tile_end = base + kWqTile < lay.d ? base + kWqTile : lay.d;
         const bool one_layer = tile_end <= lay.segs[seg0 + 1].offset;
         const uint64_t pair0 = (uint64_t)u * lay.nseg + seg0;
-        const QConst qc0 = make_qconst(lay.E, lay.M, lay.bias[pair0]);
+        const int bias0 = lay.bias[pair0];
+        const QConst qc0 = make_qconst(lay.E, lay.M, bias0);
         const float gain0 = lay.gain[2 * pair0], inv_gain0 = lay.gain[2 * pair0 + 1];
         if (one_layer && base + kWqTile <= lay.d) {
             // a whole tile of one layer (rows and tiles start on 16-byte boundaries): thread t takes elements
@@ -161,13 +165,16 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
                 const uint64_t i = base + (uint64_t)k * (kWqThreads * 4) + threadIdx.x * 4;
                 wf4 eo;
                 uint32_t sp[4];
+                Philox4 rw;
+                if constexpr (kSR) rw = element_random_words(i, u, seed);   // i is a multiple of 4
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const float v = __fadd_rn(gq[k][j], __fmul_rn(gamma, mq[k][j]));
                     const float y = __fmul_rn(v, gain0);
                     uint32_t s, flags;
                     float q;
-                    quantize(y, qc0, sign_shift, s, q, flags);
+                    if constexpr (kSR) quantize_stochastic(y, qc0, lay.E, lay.M, bias0, sign_shift, rw.w[j], s, q, flags);
+                    else quantize(y, qc0, sign_shift, s, q, flags);
                     q = __fmul_rn(q, inv_gain0);
                     eo[j] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
                     n_nonfinite += flags & 1u;
@@ -196,12 +203,14 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
             if (i >= lay.d) break;
             uint32_t book = tile_book;
             QConst qc = qc0;
+            int bias = bias0;
             float gain = gain0, inv_gain = inv_gain0;
             if (!one_layer) {   // workgroup-uniform: the tile crosses into another layer
                 uint32_t s_i = seg0;
                 while (i >= lay.segs[s_i + 1].offset) ++s_i;   // ends: segs[nseg].offset = d > i
                 const uint64_t pair = (uint64_t)u * lay.nseg + s_i;
-                qc = make_qconst(lay.E, lay.M, lay.bias[pair]);
+                bias = lay.bias[pair];
+                qc = make_qconst(lay.E, lay.M, bias);
                 gain = lay.gain[2 * pair];
                 inv_gain = lay.gain[2 * pair + 1];
                 book = book_base + (uint32_t)lay.segs[s_i].book;
@@ -210,7 +219,10 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
             const float y = __fmul_rn(v, gain);
             uint32_t s, flags;
             float q;
-            quantize(y, qc, sign_shift, s, q, flags);
+            if constexpr (kSR)
+                quantize_stochastic(y, qc, lay.E, lay.M, bias, sign_shift, element_random_words(i, u, seed).w[i & 3u], s, q,
+                                    flags);
+            else quantize(y, qc, sign_shift, s, q, flags);
             q = __fmul_rn(q, inv_gain);
             mo[i] = (flags & 1u) ? 0.0f : __fsub_rn(v, q);
             n_nonfinite += flags & 1u;
@@ -1109,9 +1121,13 @@ hipError_t launch_encode_wide(const Layout &lay, const co3_encode_args &a, BookW
     }
     if (lay.d) {
         ProfScope prof(K_QUANTIZE, s);
-        hipLaunchKernelGGL(k_quantize_wide, dim3((uint32_t)((lay.d + (uint64_t)kWqTile * kWqTiles - 1) / ((uint64_t)kWqTile * kWqTiles)), lay.U),
-                           dim3(kWqThreads), 0, s,
-                           lay, a.g, a.m, a.m_out, sym, sym_stride, a.row_stride, a.gamma, hist_rep, a.status);
+        const dim3 grid((uint32_t)((lay.d + (uint64_t)kWqTile * kWqTiles - 1) / ((uint64_t)kWqTile * kWqTiles)), lay.U);
+        if (a.rounding == CO3_ROUND_STOCHASTIC)
+            hipLaunchKernelGGL(k_quantize_wide<true>, grid, dim3(kWqThreads), 0, s, lay, a.g, a.m, a.m_out, sym, sym_stride,
+                               a.row_stride, a.gamma, a.seed, hist_rep, a.status);
+        else
+            hipLaunchKernelGGL(k_quantize_wide<false>, grid, dim3(kWqThreads), 0, s, lay, a.g, a.m, a.m_out, sym, sym_stride,
+                               a.row_stride, a.gamma, a.seed, hist_rep, a.status);
     }
     {
         ProfScope prof(K_REDUCE_HIST, s);

@@ -24,7 +24,7 @@ def neighbours(grid, a):
     return grid[lo], grid[hi]
 
 
-@pytest.mark.parametrize("E,M,bias", [(2, 1, 1), (3, 0, 5), (4, 3, 14), (5, 2, 20)])
+@pytest.mark.parametrize("E,M,bias", [(2, 1, 1), (3, 0, 5), (4, 3, 14), (5, 2, 20), (5, 5, 22), (4, 7, 12)])
 def test_output_is_a_neighbour_and_representatives_are_fixed_points(E, M, bias):
     rng = np.random.default_rng(E * 10 + M)
     grid = orc.grid(E, M, bias)
@@ -53,7 +53,7 @@ def test_output_is_a_neighbour_and_representatives_are_fixed_points(E, M, bias):
     assert np.array_equal(q2, reps)
 
 
-@pytest.mark.parametrize("E,M,bias", [(3, 0, 5), (4, 3, 14)])
+@pytest.mark.parametrize("E,M,bias", [(3, 0, 5), (4, 3, 14), (4, 5, 14)])
 def test_upper_neighbour_probability_and_unbiasedness(E, M, bias):
     grid = orc.grid(E, M, bias)
     n = 400_000
