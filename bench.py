@@ -68,7 +68,7 @@ def parse():
                    help="the single-sweep encoder also counts the symbols (histogram output with a held code)")
     p.add_argument("--format", default=None, metavar="E,M",
                    help="run the workload in the format [1, E, M] instead of its own; an alphabet of more than 8 bits "
-                        "takes the library's 16-bit-symbol path, which has no model code: empirical tables only")
+                        "takes the library's 16-bit-symbol kernels")
     p.add_argument("--per-user-books", action="store_true", help="every user its own code tables instead of pooled ones")
     p.add_argument("--graph", action="store_true",
                    help="replay the step from HIP graphs (one per gradient set of the pool) instead of launching eagerly")
@@ -140,8 +140,6 @@ def main():
         E, M = (int(x) for x in a.format.split(","))
         w = dataclasses.replace(w, E=E, M=M, name=f"{w.name} in [1,{E},{M}]")
         wide = 1 + E + M > 8
-        if wide:
-            a.book, a.no_other_book, a.no_gamma_sweep = "empirical", True, True
     sweep_gammas = [] if (a.gamma is not None or a.no_gamma_sweep) else [x for x in w.gammas if x != w.gamma]
     if a.gamma is not None:
         w = dataclasses.replace(w, gamma=a.gamma)

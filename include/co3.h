@@ -63,10 +63,9 @@ enum {
  * 1 + exp_bits + mant_bits <= 12.  Up to 8 bits a symbol is one byte.  With 9 to 12 bits ("wide"
  * alphabets) a symbol is a 16-bit word: every `symbols` buffer below then holds uint16_t (its size is
  * co3_plan_symbols_bytes() all the same), the code tables have up to 4096 entries and the library
- * runs kernels of its own for them, in which a workgroup shares one copy of a table.  Not provided
- * for wide alphabets: the model routines co3_model_weights_device and co3_model_bias_device
- * (CO3_ERR_FORMAT); a fixed code without a symbol buffer is coded in the same three steps as with
- * one, the symbols kept in the workspace.                                                      */
+ * runs kernels of its own for them, in which a workgroup shares one copy of a table; a fixed code
+ * without a symbol buffer is coded in the same three steps as with one, the symbols kept in the
+ * workspace.                                                                                    */
 typedef struct {
     int32_t exp_bits;
     int32_t mant_bits;

@@ -453,7 +453,6 @@ int co3_gennorm_fit(const co3_plan *plan, const float *g, const float *m, uint64
 int co3_model_weights_device(const co3_plan *plan, const co3_gennorm_params *params, uint64_t *weights, void *stream)
 {
     if (!plan || !params || !weights) return CO3_ERR_ARG;
-    if (plan->lay.wide) return CO3_ERR_FORMAT;   // the model routines serve alphabets of up to 8 bits
     DeviceGuard guard(plan->device);
     return launch_model_weights(plan->lay, params, weights, static_cast<hipStream_t>(stream)) == hipSuccess
                ? CO3_OK
@@ -466,7 +465,6 @@ int co3_model_bias_device(const co3_plan *plan, const co3_gennorm_params *params
                           void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!plan || !params || !bias || !workspace) return CO3_ERR_ARG;
-    if (plan->lay.wide) return CO3_ERR_FORMAT;
     if (workspace_bytes < bias_workspace_bytes(plan->lay)) return CO3_ERR_CAPACITY;
     if (plan->lay.nseg > 65535u || plan->lay.U > 65535u) return CO3_ERR_ARG;  // grid.y, grid.z
     DeviceGuard guard(plan->device);

@@ -137,38 +137,39 @@ __global__ __launch_bounds__(kFitThreads) void k_fit_params(Layout lay, const do
 __global__ __launch_bounds__(kMaxA) void k_model_weights(Layout lay, const co3_gennorm_params *__restrict__ params,
                                                          uint64_t *__restrict__ weights)
 {
-    const uint32_t b = blockIdx.x, s = threadIdx.x;
-    if (s >= lay.A) return;
+    const uint32_t b = blockIdx.x;
     const uint32_t u_first = lay.per_user_books ? b / lay.books_per_user : 0u;
     const uint32_t u_last = lay.per_user_books ? u_first : lay.U - 1u;
     const int32_t book = (int32_t)(lay.per_user_books ? b % lay.books_per_user : b);
-    double lo, hi;
-    const bool producible = symbol_cell(s, lay.E, lay.M, lay.bias[0], &lo, &hi);  // the same for every bias
-    double mass = 0.0, count = 0.0;
-    if (producible) {
-        for (uint32_t u = u_first; u <= u_last; ++u) {
-            for (uint32_t k = 0; k < lay.nseg; ++k) {
-                const SegDev sd = lay.segs[k];
-                if (sd.book != book || sd.length == 0) continue;
-                const co3_gennorm_params p = params[(uint64_t)u * lay.nseg + k];
-                if (!(p.alpha > 0.0) || !(p.beta > 0.0)) continue;
-                symbol_cell(s, lay.E, lay.M, lay.bias[(uint64_t)u * lay.nseg + k], &lo, &hi);
-                // with a real-valued scale the conversion sees y = v * gain: the model's location and scale times gain
-                const double gn = (double)lay.gain[2 * ((uint64_t)u * lay.nseg + k)];
-                mass += (double)sd.length * gennorm_mass(lo, hi, p.mu * gn, p.alpha * gn, p.beta);
-                count += (double)sd.length;
+    for (uint32_t s = threadIdx.x; s < lay.A; s += kMaxA) {   // one symbol per thread up to 8 bits, up to 16 above
+        double lo, hi;
+        const bool producible = symbol_cell(s, lay.E, lay.M, lay.bias[0], &lo, &hi);  // the same for every bias
+        double mass = 0.0, count = 0.0;
+        if (producible) {
+            for (uint32_t u = u_first; u <= u_last; ++u) {
+                for (uint32_t k = 0; k < lay.nseg; ++k) {
+                    const SegDev sd = lay.segs[k];
+                    if (sd.book != book || sd.length == 0) continue;
+                    const co3_gennorm_params p = params[(uint64_t)u * lay.nseg + k];
+                    if (!(p.alpha > 0.0) || !(p.beta > 0.0)) continue;
+                    symbol_cell(s, lay.E, lay.M, lay.bias[(uint64_t)u * lay.nseg + k], &lo, &hi);
+                    // with a real-valued scale the conversion sees y = v * gain: the model's location and scale times gain
+                    const double gn = (double)lay.gain[2 * ((uint64_t)u * lay.nseg + k)];
+                    mass += (double)sd.length * gennorm_mass(lo, hi, p.mu * gn, p.alpha * gn, p.beta);
+                    count += (double)sd.length;
+                }
             }
         }
-    }
-    uint64_t w = 0;
-    if (producible) {
-        w = 1;
-        if (count > 0.0) {
-            const double x = floor(mass / count * 1099511627776.0);  // 2^40
-            if (x >= 1.0) w = (uint64_t)x;
+        uint64_t w = 0;
+        if (producible) {
+            w = 1;
+            if (count > 0.0) {
+                const double x = floor(mass / count * 1099511627776.0);  // 2^40
+                if (x >= 1.0) w = (uint64_t)x;
+            }
         }
+        weights[(uint64_t)b * lay.A + s] = w;
     }
-    weights[(uint64_t)b * lay.A + s] = w;
 }
 
 // Exponent bias from the model, eq. (exp bias) with integer b.  The expected squared error of a candidate
@@ -235,9 +236,10 @@ __global__ __launch_bounds__(kMaxA) void k_model_bias_ref(Layout lay, const co3_
         s_c0 = c0;
     }
     __syncthreads();
-    double e = 0.0;
-    if (model && t < lay.A)
-        e = sq_error_of_symbol(t, lay.E, lay.M, bias_min_supported(lay.E) + s_c0, p.mu, p.alpha, p.beta);
+    double e = 0.0;   // the shares of symbols t, t + 256, ... in this order (one symbol for alphabets of up to 8 bits)
+    if (model)
+        for (uint32_t sy = t; sy < lay.A; sy += kMaxA)
+            e += sq_error_of_symbol(sy, lay.E, lay.M, bias_min_supported(lay.E) + s_c0, p.mu, p.alpha, p.beta);
     const double total = bias_fold(s_red, t, e);
     if (t == 0) ref[(uint64_t)u * lay.nseg + seg] = model ? total : INFINITY;
 }
@@ -257,8 +259,8 @@ __global__ __launch_bounds__(kMaxA) void k_model_bias_errors(Layout lay, const c
         return;
     }
     double e = 0.0;
-    if (t < lay.A)
-        e = sq_error_of_symbol(t, lay.E, lay.M, bias_min_supported(lay.E) + (int)cand, p.mu, p.alpha, p.beta);
+    for (uint32_t sy = t; sy < lay.A; sy += kMaxA)
+        e += sq_error_of_symbol(sy, lay.E, lay.M, bias_min_supported(lay.E) + (int)cand, p.mu, p.alpha, p.beta);
     const double total = bias_fold(s_red, t, e);
     if (t == 0) errors[pair * kBiasSlots + cand] = total;
 }

@@ -59,10 +59,12 @@ def check_weights(got, ref):
     assert np.all(np.abs(g - r) <= 1.0 + 1e-9 * r), np.abs(g - r).max()
 
 
-@pytest.mark.parametrize("beta,alpha,d", [(0.7, 1e-3, 4096 * 5 + 123), (1.0, 2e-3, 4095), (1.5, 1e-4, 4096 * 33),
-                                          (2.0, 1e-2, 100_000)])
-def test_fit_single_layer(beta, alpha, d):
-    E, M, U = 4, 3, 2
+@pytest.mark.parametrize("beta,alpha,d,E,M", [(0.7, 1e-3, 4096 * 5 + 123, 4, 3), (1.0, 2e-3, 4095, 4, 3),
+                                              (1.5, 1e-4, 4096 * 33, 4, 3), (2.0, 1e-2, 100_000, 4, 3),
+                                              (0.9, 1e-3, 4096 * 3 + 5, 5, 6), (1.3, 3e-3, 9000, 3, 5)])
+def test_fit_single_layer(beta, alpha, d, E, M):
+    # the last two: alphabets of 12 and 9 bits (the model's weights for up to 4096 symbols)
+    U = 2
     rng = np.random.default_rng(int(beta * 100) + d)
     g = np.stack([syn.gennorm_numpy(rng, d, beta, alpha) for _ in range(U)])
     m = np.stack([syn.gennorm_numpy(rng, d, beta, alpha * 0.4) for _ in range(U)])
@@ -158,13 +160,15 @@ def test_fitted_model_code_drives_the_single_sweep_encoder():
     assert ref["payload_bits"].sum() <= 1.01 * emp["payload_bits"].sum()
 
 
-def test_model_bias_on_the_device_and_a_round_with_it():
+@pytest.mark.parametrize("E,M", [(4, 3), (4, 6)])
+def test_model_bias_on_the_device_and_a_round_with_it(E, M):
     # fit -> bias from the model (eq. (exp bias) with integer b) -> installed in the plan -> weights ->
-    # code -> single-sweep encode -> PS average, all without the host; the oracle repeats every step
+    # code -> single-sweep encode -> PS average, all without the host; the oracle repeats every step.
+    # (4, 6): an alphabet of 11 bits
     import torch
     from oracle import co3_bias_model as bm
     from paper_2204_08211_amd import binding as B
-    E, M, U = 4, 3, 3
+    U = 3
     seg_len = [4096 * 2 + 100, 0, 4096 * 3, 777]
     seg_book = [0, 1, 1, 0]
     d = sum(seg_len)
