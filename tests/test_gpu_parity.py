@@ -865,6 +865,33 @@ def test_device_builders_against_the_oracle(E, M):
         gu.assert_bits_equal(codes, rc, f"codes of table {b}")
 
 
+@pytest.mark.parametrize("E,M", [(4, 3), (5, 5)])
+def test_device_builders_weights_that_overflow(E, M):
+    # sums of 2^64 and of 2^64 - 1 (the queues' sentinel) are refused and counted, the table left empty; the
+    # largest sum that fits is coded; tables are independent of each other
+    import torch
+    from paper_2204_08211_amd import binding as B
+    A = 1 << (1 + E + M)
+    w = np.zeros((4, A), np.uint64)
+    w[0, 3] = w[0, A - 2] = np.uint64(1) << np.uint64(63)                       # 2^64
+    w[1, 3] = np.uint64(1) << np.uint64(63); w[1, 9] = (np.uint64(1) << np.uint64(63)) - np.uint64(1)   # 2^64 - 1
+    w[2, 1] = w[2, 5] = w[2, 7] = np.uint64(1) << np.uint64(62)                 # 3 x 2^62: fits
+    w[3, :40] = np.arange(1, 41, dtype=np.uint64)
+    books = B.co3_build_codebook(E, M, 4, None)
+    status = torch.zeros(B.STATUS_WORDS, dtype=torch.int64, device="cuda:0")
+    B.co3_build_codebook_device(books, torch.from_numpy(w.view(np.int64)).to("cuda:0"), status)
+    torch.cuda.synchronize()
+    assert int(status[B.STAT_CODELEN].item()) == 2
+    for b in (0, 1):
+        lens, codes = books.export(b)
+        assert not lens.any() and not codes.any()
+    for b in (2, 3):
+        lens, codes = books.export(b)
+        rl, rc = orc.codebook(w[b])
+        gu.assert_bits_equal(lens, rl, f"code lengths of table {b}")
+        gu.assert_bits_equal(codes, rc, f"codes of table {b}")
+
+
 def test_wide_error_paths_capacity_nocode_corrupt():
     import torch
     from paper_2204_08211_amd import binding as B
