@@ -75,10 +75,12 @@ def main():
                f"    rocprofv3 --kernel-trace --stats --output-format csv -d <dir> -o {wl} -- python3 bench.py {a.bench_args}",
                f"    python3 -m paper_2204_08211_amd.profile_summary --workload {wl} --stats <dir> ...\n",
                "bench.py designs the model code on the device (k_moments, k_fit_params, k_model_bias_*, k_model_weights, "
-               "k_build_books), measures the headline (model code held: k_zero_fused, k_encode_fused, k_aggregate), the "
-               "workload's other memory-decay coefficients, then the path with the code rebuilt every round (k_zero_u64, "
-               "k_quantize, k_reduce_hist, k_build_books, k_chunk_bits, k_scan_chunks, k_pack, k_aggregate) and co3_decode "
-               "(k_decode).  Times in microseconds.\n",
+               "k_build_books), measures the headline (model code held: " +
+               ("k_zero_fused, k_encode_fused, k_aggregate" if "k_encode_fused" in bj["kernel_ms_per_launch"] else
+                "for 16-bit symbols the three coding steps with the symbols in the workspace, then k_aggregate_wide") +
+               "), the workload's other memory-decay coefficients, then the path with the code rebuilt every round (k_zero_u64, "
+               "k_quantize, k_reduce_hist, k_build_books, k_chunk_bits, k_scan_chunks, k_pack, k_aggregate; the *_wide kernels "
+               "for 16-bit symbols) and co3_decode (k_decode).  Times in microseconds.\n",
                "| kernel | calls | average | min | max | share of all GPU time (incl. input generation) |", "|---|---|---|---|---|---|"]
         for r in rows:
             if "co3::" not in r["Name"]:
