@@ -499,17 +499,23 @@ constexpr size_t kWPackLds = sizeof(uint32_t) * (kWideMaxA + kWWaves * kWPackWav
 // of its row, without knowing where they will land in the chunk; its bit count falls out at the end.  A
 // codeword enters a 64-bit shift register; it completes at most one 32-bit word, which is stored without a
 // branch (a store of the word still being filled is harmless: the slot is written again; stores beyond the row
-// go to the row's spare slot).  Returns, for the whole wavefront: kRowsOk; kRowsOverflow if a lane's codewords do
-// not fit its row (bits is still every lane's bit count); kRowsSlow if a symbol has a kWFastSlow entry.
+// go to the row's spare slot).  A lane that met a kWFastSlow entry (a code of more than kWFastCodeBits bits, or
+// a symbol without one: a handful of elements in a round of a large vector) codes its row again by itself in a
+// rolled loop, its symbols parked in `scratch` (32 words), those entries taken from the table in device memory
+// and appended in pieces; nocode counts its symbols without a code.  Returns, for the whole wavefront: kRowsOk;
+// kRowsOverflow if a lane's codewords do not fit its row (bits is still every lane's bit count, and no lane met
+// a kWFastSlow entry); kRowsSlow if more than kWRedoLanes lanes met one, or one did and a row overflowed.
 enum { kRowsOk = 0, kRowsOverflow = 1, kRowsSlow = 2 };
+constexpr int kWRedoLanes = 4;
 template <bool kFull>
-__device__ inline int w_pack_rows(const uint32_t (&sym)[kSub / 2], int cnt, const uint32_t *fast, uint32_t *region,
-                                   uint32_t lane, uint32_t &bits)
+__device__ inline int w_pack_rows(const uint32_t (&sym)[kSub / 2], int cnt, const uint32_t *fast, const BookWide &book,
+                                  uint32_t *region, uint32_t *scratch, uint32_t lane, uint32_t &bits, uint32_t &nocode)
 {
     uint64_t acc = 0;
     uint32_t np = 0;                                     // bits of acc not yet stored: < 32 between symbols
-    uint32_t waddr = lane * kWRowStride;
-    const uint32_t wend = waddr + kWRowWords;
+    const uint32_t row0 = lane * kWRowStride;
+    uint32_t waddr = row0;
+    const uint32_t wend = row0 + kWRowWords;
     bool left = false;
 #pragma unroll
     for (int j = 0; j < kSub; ++j) {
@@ -524,11 +530,50 @@ __device__ inline int w_pack_rows(const uint32_t (&sym)[kSub / 2], int cnt, cons
         waddr += (np >> 5) & 1u;
         np = rest;
     }
-    if (__any(left)) return kRowsSlow;
-    const uint32_t whole = waddr - lane * kWRowStride;   // complete words, counted also beyond the row
+    nocode = 0;
+    const uint64_t slow_lanes = __ballot(left);
+    if (slow_lanes) {
+        if (__popcll(slow_lanes) > kWRedoLanes) return kRowsSlow;
+        for (uint64_t todo = slow_lanes; todo; todo &= todo - 1) {   // the same in every lane
+            const uint32_t l = (uint32_t)__ffsll((long long)todo) - 1u;
+            w_wave_sync_lds();                                       // the scratch words are free
+            if (lane == l) {
+#pragma unroll
+                for (int jj = 0; jj < kSub / 2; ++jj) scratch[jj] = sym[jj];
+            }
+            w_wave_sync_lds();
+            if (lane == l) {
+                const uint16_t *mine = reinterpret_cast<const uint16_t *>(scratch);
+                acc = 0; np = 0; waddr = row0;
+                for (int j = 0; j < (kFull ? kSub : cnt); ++j) {
+                    const uint32_t sj = mine[j];
+                    const uint32_t e = fast[sj];
+                    uint32_t L = e >> kWFastCodeBits;
+                    uint64_t code = e & ((1u << kWFastCodeBits) - 1u);
+                    if (L == kWFastSlow) {
+                        L = book.len[sj];
+                        code = book.code[sj];
+                        nocode += L == 0u ? 1u : 0u;
+                    }
+                    while (L) {   // the codeword's leading bits first, at most kWFastCodeBits at a time
+                        const uint32_t piece = L < kWFastCodeBits ? L : kWFastCodeBits;
+                        L -= piece;
+                        np += piece;
+                        acc = (acc << piece) | ((code >> L) & ((1ull << piece) - 1ull));
+                        const uint32_t rest = np & 31u;
+                        region[waddr < wend ? waddr : wend] = (uint32_t)(acc >> rest);
+                        waddr += (np >> 5) & 1u;
+                        np = rest;
+                    }
+                }
+            }
+        }
+    }
+    const uint32_t whole = waddr - row0;                 // complete words, counted also beyond the row
     if (np) region[waddr < wend ? waddr : wend] = (uint32_t)(acc << (32u - np));
     bits = whole * 32u + np;
-    return __any(whole + (np ? 1u : 0u) > (uint32_t)kWRowWords) ? kRowsOverflow : kRowsOk;
+    if (__any(whole + (np ? 1u : 0u) > (uint32_t)kWRowWords)) return slow_lanes ? kRowsSlow : kRowsOverflow;
+    return kRowsOk;
 }
 
 // Step 2: every lane's row holds its `bits` bits; excl: bits of the lanes before it.  The rows go to registers,
@@ -688,9 +733,14 @@ __global__ __launch_bounds__(kWThreads, 3) void k_pack_wide(Layout lay, const ui
         uint32_t bits = 0;
         const bool in_lds = k.book == wg_book;   // whole wavefront: the table in LDS is this chunk's
         int rows = kRowsSlow;
-        if (in_lds)
-            rows = k.n == (uint32_t)kChunk ? w_pack_rows<true>(symw, cnt, s_fast, region, lane, bits)
-                                           : w_pack_rows<false>(symw, cnt, s_fast, region, lane, bits);
+        if (in_lds) {
+            uint32_t nocode = 0;
+            rows = k.n == (uint32_t)kChunk
+                       ? w_pack_rows<true>(symw, cnt, s_fast, book, region, region + kWRegion, lane, bits, nocode)
+                       : w_pack_rows<false>(symw, cnt, s_fast, book, region, region + kWRegion, lane, bits, nocode);
+            if (rows != kRowsSlow && nocode)   // (the plain loops below count them themselves)
+                atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_NOCODE), (unsigned long long)nocode);
+        }
         const bool fast_ok = rows == kRowsOk;
         const uint16_t *row = reinterpret_cast<const uint16_t *>(row32);
         // what the plain loops know of a symbol: from the table in LDS where that is this chunk's and holds the

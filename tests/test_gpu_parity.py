@@ -822,6 +822,63 @@ def test_wide_coder_rows_overflow_and_mixed_chunks():
     assert int(buf.status[B.STAT_CORRUPT].item()) == 0 and int(gpu["status_encode"][B.STAT_NOCODE]) == 0
 
 
+def test_wide_coder_few_long_codes_in_a_chunk():
+    # a code whose rare symbols have codewords of 26 to 45 bits (beyond what the coder's LDS entries hold), and a
+    # handful of them per chunk: in one lane (first element, last element, two in a row), in lanes at both ends of
+    # the wavefront, in as many lanes as are coded again one by one and in one more (the chunk's plain loops), in the
+    # ragged last chunk; then the same with one of those symbols left without a code: counted, nothing else
+    import torch
+    from paper_2204_08211_amd import binding as B
+    E, M, U = 5, 5, 2
+    A = 1 << (1 + E + M)
+    rng = np.random.default_rng(1700)
+    bias = np.array([[20], [20]], np.int32)
+    grid = orc.grid(E, M, 20)
+    rare = rng.choice(np.arange(1, grid.size), 34, replace=False)
+    w = np.full(A, 1 << 36, np.uint64)
+    w[rare] = np.array([1] + [1 << i for i in range(rare.size - 1)], np.uint64); w[rare + (A >> 1)] = w[rare]
+    common = np.setdiff1d(np.arange(1, grid.size), rare)
+    long_ = rare[np.asarray(orc.huffman_lengths(w))[rare] >= 26]
+    assert long_.size >= 20
+    d = 4096 * 7 + 1500
+    put = {0: [0, 4095],                               # chunk 0: lane 0's first element, lane 63's last
+           1: [64 * 7 + 3, 64 * 7 + 4, 64 * 8],        # chunk 1: two in a row in lane 7, lane 8's first
+           2: [5, 64 * 20 + 63, 64 * 41 + 31, 64 * 63],          # chunk 2: four lanes
+           3: [64 * l + 9 for l in (1, 2, 30, 31, 62)],          # chunk 3: five lanes
+           4: list(range(64 * 13, 64 * 14)),                     # chunk 4: every element of lane 13
+           7: [0, 64 * 23 + 27]}                                 # the ragged chunk: lane 0, and its last element
+    g = np.empty((U, d), np.float32)
+    ks = []
+    for u in range(U):
+        k = rng.choice(common, d)
+        for c, where in put.items():
+            k[4096 * c + np.array(where)] = rng.choice(long_, len(where))
+        ks.append(k)
+        g[u] = (grid[k] * rng.choice([-1.0, 1.0], d)).astype(np.float32)
+    m = np.zeros_like(g)
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias)
+    ref = gu.oracle_round(kw, g, m, 0.9, weights=w[None, :])
+    lens = ref["lens"][0]
+    assert lens[long_].min() >= 26 and lens[long_].max() >= 44 and lens[common].max() <= 12
+    gpu, (plan, books, buf, gt, mt) = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=w[None, :], max_code_len=64,
+                                                   want_decode=False)
+    for key, what in [("m_new", "memory"), ("chunk_offset", "chunk offsets"), ("sub_bits", "sub-chunk bits"),
+                      ("payload_bits", "payload bits")]:
+        gu.assert_bits_equal(gpu[key], ref[key], what)
+    for u, wds in enumerate(ref["words"]):
+        gu.assert_bits_equal(gpu["words"][u, :wds.size], wds, f"bitstream of user {u}")
+    avg = torch.zeros(d, dtype=torch.float32, device="cuda:0")
+    B.co3_ps_aggregate(plan, books, buf, avg)
+    torch.cuda.synchronize()
+    gu.assert_bits_equal(avg.cpu().numpy(), ref["avg"], "PS average")
+    assert int(buf.status[B.STAT_CORRUPT].item()) == 0 and int(gpu["status_encode"][B.STAT_NOCODE]) == 0
+
+    victim = int(ks[0][4096 * 2 + 5])                  # occurs in a chunk whose lanes are coded again one by one
+    w0 = w.copy(); w0[victim] = 0; w0[victim + (A >> 1)] = 0
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=w0[None, :], max_code_len=64, want_decode=False)
+    assert int(gpu["status_encode"][B.STAT_NOCODE]) == sum(int((k == victim).sum()) for k in ks)
+
+
 @pytest.mark.parametrize("E,M", [(2, 1), (3, 2), (4, 3), (5, 2), (3, 5), (4, 5), (4, 6), (5, 6)])
 def test_device_builders_against_the_oracle(E, M):
     # the builders' sort, merge in rounds with ties, depths and canonical ranks at byte and wide alphabet sizes:
