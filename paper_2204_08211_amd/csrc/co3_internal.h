@@ -14,7 +14,9 @@ constexpr int kSub = CO3_SUB;
 constexpr int kSubsPerChunk = CO3_SUBS_PER_CHUNK;
 constexpr int kMaxA = 256;          // alphabets of up to 8 bits: symbols are bytes
 constexpr int kWideMaxA = 4096;     // alphabets of 9 to 12 bits: symbols are 16-bit words (k_wide.hip)
-constexpr int kWideDecBits = 11;    // prefix width of the wide path's direct decode table
+constexpr int kWideDecBits = 12;    // prefix width of the wide path's direct decode table
+constexpr int kWideDec2Bits = 5;    // its second-level tables are indexed by the next bits
+constexpr int kWideDec2Tables = 128;   // number of second-level tables
 constexpr int kDecBits = 11;        // prefix width of the direct decode table
 constexpr int kDecEntries = 1 << kDecBits;
 constexpr int kLongSlots = 64 - kDecBits;  // lengths kDecBits+1 .. 64
@@ -59,7 +61,12 @@ struct BookWide {
     uint64_t first[65];                   // first[L]: first canonical code of length L
     uint32_t count[65];                   // symbols with length L
     uint32_t offset[65];                  // index of the first length-L symbol in sorted[]
-    uint32_t dec[1 << kWideDecBits];      // prefix -> (len << 16) | symbol for len <= kWideDecBits, else 0
+    uint16_t dec[1 << kWideDecBits];      // prefix -> (len << 12) | symbol for len <= kWideDecBits, else 0
+    // the first kWideDec2Tables prefixes that hold only longer codes (the largest prefixes: canonical codes grow
+    // with their length) each have a table over the next kWideDec2Bits bits:
+    // ((len - kWideDecBits) << 12) | symbol for len <= kWideDecBits + kWideDec2Bits, else 0
+    uint16_t dec2[kWideDec2Tables << kWideDec2Bits];
+    uint32_t long_prefix0;                // first prefix that holds only longer codes (1 << kWideDecBits: none)
     uint16_t sorted[kWideMaxA];           // symbols ordered by (length, symbol)
     uint8_t len[kWideMaxA];               // codeword length, 0 = no code
     uint32_t maxlen;

@@ -166,8 +166,23 @@ int build_wide_host(const uint64_t *w, uint32_t A, BookWide *b)
         b->sorted[b->offset[L] + rank] = (uint16_t)s;
         if (L <= kWideDecBits) {
             const uint32_t lo = (uint32_t)b->code[s] << (kWideDecBits - L);
-            for (uint32_t i = 0; i < (1u << (kWideDecBits - L)); ++i) b->dec[lo + i] = ((uint32_t)L << 16) | s;
+            for (uint32_t i = 0; i < (1u << (kWideDecBits - L)); ++i) b->dec[lo + i] = (uint16_t)((L << 12) | s);
         }
+    }
+    // second-level tables under the first prefixes that hold only longer codes
+    b->long_prefix0 = 1u << kWideDecBits;
+    for (int L = kWideDecBits + 1; L <= 64; ++L)
+        if (b->count[L]) { b->long_prefix0 = (uint32_t)(b->first[L] >> (L - kWideDecBits)); break; }
+    for (uint32_t s = 0; s < A; ++s) {
+        const int L = b->len[s];
+        if (L <= kWideDecBits || L > kWideDecBits + kWideDec2Bits) continue;
+        const uint32_t span = kWideDecBits + kWideDec2Bits;
+        const uint32_t lo = (uint32_t)b->code[s] << (span - L);   // the code followed by zeros, span bits
+        const uint32_t tab = (lo >> kWideDec2Bits) - b->long_prefix0;
+        if (tab >= (uint32_t)kWideDec2Tables) continue;
+        for (uint32_t i = 0; i < (1u << (span - L)); ++i)
+            b->dec2[(tab << kWideDec2Bits) | ((lo + i) & ((1u << kWideDec2Bits) - 1u))] =
+                (uint16_t)(((L - kWideDecBits) << 12) | s);
     }
     return CO3_OK;
 }

@@ -14,8 +14,9 @@
 //   (k_scan_chunks of k_pack.hip gives the chunk offsets)
 //   k_pack_wide          wavefront per chunk, lane per sub-chunk with its 64 symbols in registers: lengths, wave
 //                        prefix sum, codewords ORed into an LDS window at their bit offsets, window copied out
-//   k_decode_wide        wavefront per (chunk, user), lane per sub-chunk: prefix table for codes of up to 11 bits,
-//                        longer ones by their value among the per-length bounds of the canonical code
+//   k_decode_wide        wavefront per (chunk, user), lane per sub-chunk: prefix table for codes of up to 12 bits,
+//                        second-level tables over the next 5 bits under the first 128 prefixes of longer codes,
+//                        the rest by their value among the per-length bounds of the canonical code
 //   k_aggregate_wide     the same decoder; values added to per-element fp64 sums in LDS, then averaged
 #include "co3_internal.h"
 #include "quantize_math.h"
@@ -130,12 +131,25 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
             s_hist[i] = 0u;
         }
     };
-    uint32_t cur_book = 0xffffffffu;   // workgroup-uniform
+    uint32_t cur_book = 0xffffffffu;   // workgroup-uniform, like the layer of the tile's first element:
+    uint32_t seg0 = 0, tile_book = 0;
+    uint64_t seg_end = 0;              // where that layer ends (0: none looked up yet)
+    int bias0 = 0;
+    QConst qc0 = make_qconst(lay.E, lay.M, 0);
+    float gain0 = 1.0f, inv_gain0 = 1.0f;
     for (int tile = 0; tile < kWqTiles; ++tile) {
         const uint64_t base = ((uint64_t)blockIdx.x * kWqTiles + (uint64_t)tile) * kWqTile;
         if (base >= lay.d) break;      // workgroup-uniform
-        const uint32_t seg0 = w_find_segment(lay.segs, lay.nseg, base);
-        const uint32_t tile_book = book_base + (uint32_t)lay.segs[seg0].book;
+        if (base >= seg_end) {         // the tile starts in another layer than the last one did: look it up
+            seg0 = w_find_segment(lay.segs, lay.nseg, base);
+            seg_end = lay.segs[seg0 + 1].offset;
+            tile_book = book_base + (uint32_t)lay.segs[seg0].book;
+            const uint64_t pair0 = (uint64_t)u * lay.nseg + seg0;
+            bias0 = lay.bias[pair0];
+            qc0 = make_qconst(lay.E, lay.M, bias0);
+            gain0 = lay.gain[2 * pair0];
+            inv_gain0 = lay.gain[2 * pair0 + 1];
+        }
         if (tile_book != cur_book) {
             __syncthreads();
             if (cur_book != 0xffffffffu) flush(cur_book);
@@ -145,11 +159,7 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
         // the scale and the quantizer's constants of the tile's first layer serve the whole tile unless it
         // crosses into the next layer
         const uint64_t tile_end = base + kWqTile < lay.d ? base + kWqTile : lay.d;
-        const bool one_layer = tile_end <= lay.segs[seg0 + 1].offset;
-        const uint64_t pair0 = (uint64_t)u * lay.nseg + seg0;
-        const int bias0 = lay.bias[pair0];
-        const QConst qc0 = make_qconst(lay.E, lay.M, bias0);
-        const float gain0 = lay.gain[2 * pair0], inv_gain0 = lay.gain[2 * pair0 + 1];
+        const bool one_layer = tile_end <= seg_end;
         if (one_layer && base + kWqTile <= lay.d) {
             // a whole tile of one layer (rows and tiles start on 16-byte boundaries): thread t takes elements
             // 4 t .. 4 t + 3 of each half, 16-byte loads and stores, four symbols per 8-byte store
@@ -158,7 +168,7 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
             for (int k = 0; k < kWqPer / 4; ++k) {
                 const uint64_t i = base + (uint64_t)k * (kWqThreads * 4) + threadIdx.x * 4;
                 gq[k] = __builtin_nontemporal_load(reinterpret_cast<const wf4 *>(gu + i));
-                mq[k] = *reinterpret_cast<const wf4 *>(mu + i);
+                mq[k] = __builtin_nontemporal_load(reinterpret_cast<const wf4 *>(mu + i));
             }
 #pragma unroll
             for (int k = 0; k < kWqPer / 4; ++k) {
@@ -465,11 +475,33 @@ __global__ __launch_bounds__(kWbThreads) void k_build_books_wide(BookWide *__res
             const uint32_t c = idx >> (kWideDecBits - l);
             const uint32_t f = (uint32_t)first[l];
             if (cnt[l] && c >= f && c - f < cnt[l]) {
-                e = ((uint32_t)l << 16) | B.sorted[off[l] + (c - f)];
+                e = ((uint32_t)l << 12) | B.sorted[off[l] + (c - f)];
                 break;
             }
         }
-        B.dec[idx] = e;
+        B.dec[idx] = (uint16_t)e;
+    }
+    // second-level tables under the first prefixes that hold only longer codes
+    uint32_t long_prefix0 = 1u << kWideDecBits;
+    for (int l = kWideDecBits + 1; l <= 64; ++l) {
+        if (cnt[l]) { long_prefix0 = (uint32_t)(first[l] >> (l - kWideDecBits)); break; }
+    }
+    if (t == 0) B.long_prefix0 = long_prefix0;
+    for (uint32_t idx = t; idx < (uint32_t)(kWideDec2Tables << kWideDec2Bits); idx += kWbThreads) {
+        const uint32_t prefix = long_prefix0 + (idx >> kWideDec2Bits);
+        const uint32_t wide = (prefix << kWideDec2Bits) | (idx & ((1u << kWideDec2Bits) - 1u));   // 17 bits
+        uint32_t e = 0;
+        if (prefix < (1u << kWideDecBits)) {
+            for (int l = kWideDecBits + 1; l <= kWideDecBits + kWideDec2Bits; ++l) {
+                const uint32_t c = wide >> (kWideDecBits + kWideDec2Bits - l);
+                const uint32_t f = (uint32_t)first[l];   // first[l] <= 2^l: in 32 bits
+                if (cnt[l] && c >= f && c - f < cnt[l]) {
+                    e = ((uint32_t)(l - kWideDecBits) << 12) | B.sorted[off[l] + (c - f)];
+                    break;
+                }
+            }
+        }
+        B.dec2[idx] = (uint16_t)e;
     }
 }
 
@@ -839,24 +871,29 @@ __global__ __launch_bounds__(kWThreads, 3) void k_pack_wide(Layout lay, const ui
 
 // ---- PS side ----------------------------------------------------------------------------------------------
 
-// What the decoder keeps in LDS of one table.
+// What the decoder keeps in LDS of one table; the symbols in canonical order, which only the search for a code
+// that neither table holds needs, stay in device memory.
 struct WideTabs {
-    uint32_t dec[1 << kWideDecBits];
+    uint16_t dec[1 << kWideDecBits];
+    uint16_t dec2[kWideDec2Tables << kWideDec2Bits];
     uint64_t first[65];
     uint64_t upper[65];    // (first[L] + count[L]) left-aligned in 64 bits: every code of L or fewer bits lies below
     uint32_t count[65];
     uint32_t offset[65];
     uint32_t maxlen;
-    uint32_t pad;
-    uint16_t sorted[kWideMaxA];
+    uint32_t long_prefix0;
 };
 
 __device__ inline void w_load_tabs(WideTabs *T, const BookWide &book, uint32_t t, uint32_t nthreads)
 {
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(book.dec);   // two entries per word
+    uint32_t *dst = reinterpret_cast<uint32_t *>(T->dec);
 #pragma unroll 8
-    for (uint32_t i = t; i < (1u << kWideDecBits); i += nthreads) T->dec[i] = book.dec[i];
+    for (uint32_t i = t; i < (1u << kWideDecBits) / 2; i += nthreads) dst[i] = src[i];
+    src = reinterpret_cast<const uint32_t *>(book.dec2);
+    dst = reinterpret_cast<uint32_t *>(T->dec2);
 #pragma unroll 8
-    for (uint32_t i = t; i < (uint32_t)kWideMaxA; i += nthreads) T->sorted[i] = book.sorted[i];
+    for (uint32_t i = t; i < (uint32_t)(kWideDec2Tables << kWideDec2Bits) / 2; i += nthreads) dst[i] = src[i];
 #pragma unroll 1
     for (uint32_t i = t; i < 65u; i += nthreads) {
         const uint64_t f = book.first[i];
@@ -868,7 +905,7 @@ __device__ inline void w_load_tabs(WideTabs *T, const BookWide &book, uint32_t t
         if (i >= 1u && i < 64u && ((f + c) >> i) == 0) up = (f + c) << (64u - i);
         T->upper[i] = up;
     }
-    if (t == 0) { T->maxlen = book.maxlen > 64u ? 64u : book.maxlen; T->pad = 0; }
+    if (t == 0) { T->maxlen = book.maxlen > 64u ? 64u : book.maxlen; T->long_prefix0 = book.long_prefix0; }
 }
 
 // A chunk's payload words in global memory; reads nothing outside w[0 .. nw).
@@ -927,11 +964,18 @@ struct WUpper32 {
 };
 
 template <class Src>
-__device__ inline uint32_t w_decode_one(WReader<Src> &r, uint32_t pos, const WideTabs *T, const WUpper32 &U32, uint32_t &len)
+__device__ inline uint32_t w_decode_one(WReader<Src> &r, uint32_t pos, const WideTabs *T, const uint16_t *__restrict__ sorted,
+                                        const WUpper32 &U32, uint32_t &len)
 {
     const uint32_t hi = r.window32(pos);
-    const uint32_t e = T->dec[hi >> (32 - kWideDecBits)];
-    if (e) { len = e >> 16; return e & 0xffffu; }
+    const uint32_t prefix = hi >> (32 - kWideDecBits);
+    const uint32_t e = T->dec[prefix];
+    if (e) { len = e >> 12; return e & 0xfffu; }
+    const uint32_t tab = prefix - T->long_prefix0;   // wraps below it: no table
+    if (tab < (uint32_t)kWideDec2Tables) {
+        const uint32_t e2 = T->dec2[(tab << kWideDec2Bits) | ((hi >> (32 - kWideDecBits - kWideDec2Bits)) & ((1u << kWideDec2Bits) - 1u))];
+        if (e2) { len = kWideDecBits + (e2 >> 12); return e2 & 0xfffu; }
+    }
     const uint32_t maxlen = T->maxlen;   // <= 64
     len = 0;
     if (maxlen <= (uint32_t)kWideDecBits) return 0u;   // every code is in the prefix table
@@ -964,7 +1008,7 @@ __device__ inline uint32_t w_decode_one(WReader<Src> &r, uint32_t pos, const Wid
     }
     if (rank >= T->count[L]) return 0u;
     len = L;
-    return T->sorted[(T->offset[L] + rank) & (kWideMaxA - 1)];
+    return sorted[(T->offset[L] + rank) & (kWideMaxA - 1)];
 }
 
 // Index entries of chunk c of user u, checked as in the byte decoder.
@@ -1032,7 +1076,7 @@ __global__ __launch_bounds__(kWThreads) void k_decode_wide(Layout lay, const uin
     rd.seek(p0);
     for (int j = 0; j < cnt; ++j) {
         uint32_t len;
-        const uint32_t s = w_decode_one(rd, pos, T, U32, len);
+        const uint32_t s = w_decode_one(rd, pos, T, book.sorted, U32, len);
         if (len == 0u) { bad = true; len = 1u; }
         pos += len;
         rows[lane * kWSymRow + j] = (uint16_t)s;
@@ -1103,7 +1147,7 @@ __global__ __launch_bounds__(kWAggThreads, kPerUser ? 2 : 6) void k_aggregate_wi
         rd.seek(p0);
         for (int j = 0; j < cnt; ++j) {
             uint32_t len;
-            const uint32_t s = w_decode_one(rd, pos, T, U32, len);
+            const uint32_t s = w_decode_one(rd, pos, T, book.sorted, U32, len);
             if (len == 0u) { bad = true; len = 1u; }
             pos += len;
             const float val = __fmul_rn(__uint_as_float(symbol_value_bits(s, lay.E, lay.M, bias)), inv_gain);

@@ -779,6 +779,58 @@ def test_wide_long_codes_per_user_tables_and_device_builder():
         B.co3_build_codebook(E, M, 3, w3)
 
 
+@pytest.mark.parametrize("per_user", [False, True])
+def test_wide_decoder_second_level_tables(per_user):
+    # a code with 500 magnitudes of about 10 bits, 1400 of 12 to 16 (more 12-bit prefixes hold only longer codes
+    # than the decoder has second-level tables: some of these codes are found there, the rest by search) and 24 of
+    # up to 40 bits; every symbol with a code about equally often in the data; the host's tables and the device's
+    import torch
+    from paper_2204_08211_amd import binding as B
+    E, M, U, d = 5, 6, 3, 4096 * 7 + 300
+    A = 1 << (1 + E + M)
+    rng = np.random.default_rng(1800)
+    bias = np.full((U, 1), 20, np.int32)
+    grid = orc.grid(E, M, 20)
+    perm = rng.permutation(np.arange(1, grid.size))
+    freq, mid, rare = perm[:500], perm[500:1900], perm[1900:1924]
+    w = np.zeros(A, np.uint64)
+    w[freq] = 64 << 24
+    w[mid] = rng.integers(2, 17, mid.size).astype(np.uint64) << 24
+    w[rare] = np.array([1] + [1 << i for i in range(rare.size - 1)], np.uint64)[rng.permutation(rare.size)]
+    w[(A >> 1):] = w[:(A >> 1)]                                            # both signs
+    used = np.concatenate([freq, mid, rare])
+    g = (grid[rng.choice(used, (U, d))] * rng.choice([-1.0, 1.0], (U, d))).astype(np.float32)
+    m = np.zeros_like(g)
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias, per_user_books=per_user)
+    wt = np.repeat(w[None, :], U if per_user else 1, axis=0)
+    ref = gu.oracle_round(kw, g, m, 0.9, weights=wt)
+    lens = ref["lens"][0]
+    n12 = int((np.ldexp(1.0, 12 - lens[(lens > 12)].astype(int))).sum())   # 12-bit prefixes under the longer codes
+    assert n12 > 300 and (lens[mid] >= 13).sum() > 1000 and lens[mid].max() <= 17 and lens[rare].max() >= 36
+    gpu, (plan, books, buf, gt, mt) = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=wt, max_code_len=64, want_decode=False)
+    for u, wds in enumerate(ref["words"]):
+        gu.assert_bits_equal(gpu["words"][u, :wds.size], wds, f"bitstream of user {u}")
+
+    def check(books, what):
+        buf.status.zero_()
+        symd = torch.zeros(plan.symbols_bytes, dtype=torch.uint8, device="cuda:0")
+        avg = torch.zeros(d, dtype=torch.float32, device="cuda:0")
+        B.co3_decode(plan, books, buf, symbols=symd)
+        B.co3_ps_aggregate(plan, books, buf, avg)
+        torch.cuda.synchronize()
+        gu.assert_bits_equal(B.symbols_2d(plan, symd).cpu().numpy().view(np.uint16), ref["dec_sym"], f"decoded symbols, {what}")
+        gu.assert_bits_equal(avg.cpu().numpy(), ref["avg"], f"PS average, {what}")
+        assert int(buf.status[B.STAT_CORRUPT].item()) == 0
+
+    check(books, "tables built on the host")
+    dev_books = B.co3_build_codebook(E, M, plan.num_books, None)
+    status = torch.zeros(B.STATUS_WORDS, dtype=torch.int64, device="cuda:0")
+    B.co3_build_codebook_device(dev_books, torch.from_numpy(wt.view(np.int64)).to("cuda:0"), status)
+    torch.cuda.synchronize()
+    assert not status.cpu().numpy().any()
+    check(dev_books, "tables built on the device")
+
+
 def test_wide_coder_rows_overflow_and_mixed_chunks():
     # a fixed code whose frequent symbols are not the data's: chunks of 18 bits per element (a lane's codewords
     # do not fit its LDS row: appended at their final offsets instead), chunks of about 10 (the row coder), a chunk
