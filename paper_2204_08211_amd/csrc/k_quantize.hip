@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kQThreads) void k_quantize(
                 atomicAdd(&h_lds[s * kHistRep + lane_rep], 1u);
             }
             __builtin_nontemporal_store(eo, reinterpret_cast<f4 *>(mo + i));
-            __builtin_nontemporal_store(packed, reinterpret_cast<uint32_t *>(su + i));
+            *reinterpret_cast<uint32_t *>(su + i) = packed;
         }
         __syncthreads();
         uint64_t *hist_book = hist + (uint64_t)(book_base + lay.segs[seg].book) * lay.A;
