@@ -328,7 +328,7 @@ def main():
     }
     dom = max(per_launch, key=lambda k: kt[k][0])
     ach = alg_bytes.get(dom, 0.0) * elems / (per_launch[dom] * 1e-3) / 1e9
-    counters, counters_note = counter_figures(w.name)
+    counters, counters_note = counter_figures(a.workload + (f"_fp1{w.E}{w.M}" if a.format else ""))
     ck = (counters or {}).get("kernels", {})
     roof = dict(bound="hbm", kernel=dom, achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                 frac=round(ach / HBM_PEAK_GBS, 4), traffic=ck.get(dom, {}).get("traffic_bytes"),

@@ -26,7 +26,11 @@ from paper_2204_08211_amd import build as hip_build
 
 
 # kernels whose name in the library's event timing (co3_profile_end) differs from the function's
-TIMING_NAME = {"k_pack_chunk": "k_pack", "k_chunk_bits_hist": "k_chunk_bits"}
+TIMING_NAME = {"k_pack_chunk": "k_pack", "k_chunk_bits_hist": "k_chunk_bits",
+               # the kernels for 16-bit symbols are timed under the names of the steps they take
+               "k_quantize_wide": "k_quantize", "k_reduce_hist_wide": "k_reduce_hist", "k_build_books_wide": "k_build_books",
+               "k_chunk_bits_wide": "k_chunk_bits", "k_pack_wide": "k_pack", "k_aggregate_wide": "k_aggregate",
+               "k_decode_wide": "k_decode", "k_zero_wide": "k_zero_u64"}
 
 
 def short_name(kernel):
@@ -131,9 +135,11 @@ def main():
             bpe = bj["bits_per_element"]["payload"]
             d = elems // int(bj["config"]["workload"].split("U=")[1].split()[0])
             stream = elems * bpe / 8
-            alg = {"k_encode_fused": (8 * elems, 4 * elems + stream), "k_quantize": (8 * elems, 5 * elems),
-                   "k_chunk_bits": (0, 0), "k_pack": (elems, stream), "k_aggregate": (stream, 4 * d),
-                   "k_decode": (stream, elems), "k_moments": (8 * elems, 0)}
+            sb = 2 if bj.get("dtype", "").endswith("u16") else 1   # bytes of a stored symbol
+            alg = {"k_encode_fused": (8 * elems, 4 * elems + stream), "k_quantize": (8 * elems, (4 + sb) * elems),
+                   "k_chunk_bits": (sb * elems if sb == 2 else 0, 0),   # (the byte path sizes chunks from their counts)
+                   "k_pack": (sb * elems, stream), "k_aggregate": (stream, 4 * d),
+                   "k_decode": (stream, sb * elems), "k_moments": (8 * elems, 0)}
             lines.append(f"Averages per launch; MB = 10^6 bytes; payload {bpe:.3f} bit/element; {elems} elements per launch.  "
                          "Algorithmic bytes: g and m read, m' written, the bitstream written (encoders); symbols written "
                          "(k_quantize) or read (k_pack); the bitstream read and the average written (k_aggregate).\n")
