@@ -201,6 +201,20 @@ int co3_bias_from_model(co3_format format, double mu, double alpha, double beta,
 int co3_scale_from_model(co3_format format, double mu, double alpha, double beta, int32_t *bias, float *gain,
                          float *inv_gain, double *error);
 
+/* The same search on the device for every (user, layer) of a plan, from fitted parameters: first the integer
+ * argmin as in co3_model_bias_device, then scan and golden-section search over the real scale as in
+ * co3_scale_from_model, every expected error summed over the symbols' cells by one workgroup in a fixed order.
+ * bias: device [U][nseg] (out); gain_pairs: device [U][nseg][2] (out), (gain, inv_gain) per pair, (1, 1) where
+ * the integer result stays; error: device [U][nseg] expected squared errors of the returned triples, or NULL;
+ * workspace: device, co3_plan_scale_workspace_bytes().  No synchronisation; no host copy of the results.
+ * co3_plan_set_gain_device installs such a table of pairs in the plan (device-to-device copy on `stream`; the
+ * values must be positive normal numbers, as the ones written here are); the plan then counts as carrying a
+ * scale - the stochastic conversion is refused - until co3_plan_set_gain(plan, NULL, NULL, ...) removes it.   */
+size_t co3_plan_scale_workspace_bytes(const co3_plan *plan);
+int co3_model_scale_device(const co3_plan *plan, const co3_gennorm_params *params, int32_t *bias, float *gain_pairs,
+                           double *error, void *workspace, size_t workspace_bytes, void *stream);
+int co3_plan_set_gain_device(co3_plan *plan, const float *gain_pairs, void *stream);
+
 /* ---- user side: Algorithm 1 lines 8-10 for all U users -----------------------------------
  * v = g + gamma m (eq. (f_error_fb)), ghat = Q_fp(v), m' = v - ghat, b = h_Hf(ghat).
  * mode CO3_BOOK_FIXED encodes with `books` as they are (a code designed beforehand, e.g. from

@@ -27,6 +27,7 @@ EXPORTS = [
     "co3_codebook_destroy", "co3_encode", "co3_decode", "co3_ps_aggregate", "co3_status_string",
     "co3_profile_begin", "co3_profile_end", "co3_gennorm_weights", "co3_plan_fit_workspace_bytes", "co3_gennorm_fit",
     "co3_model_weights_device", "co3_model_bias_device", "co3_plan_set_bias_device", "co3_bias_from_model", "co3_scale_from_model",
+    "co3_plan_scale_workspace_bytes", "co3_model_scale_device", "co3_plan_set_gain_device",
     "co3_plan_bias_workspace_bytes", "co3_set_lookback_polls", "co3_encode_static", "co3_plan_set_gain",
 ]
 
@@ -117,6 +118,11 @@ def lib():
         L.co3_model_bias_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                             C.c_void_p]
         L.co3_plan_set_bias_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.co3_plan_scale_workspace_bytes.argtypes = [C.c_void_p]
+        L.co3_plan_scale_workspace_bytes.restype = C.c_size_t
+        L.co3_model_scale_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_size_t, C.c_void_p]
+        L.co3_plan_set_gain_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.co3_bias_from_model.argtypes = [Format, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_int32),
                                           C.POINTER(C.c_double)]
         L.co3_scale_from_model.argtypes = [Format, C.c_double, C.c_double, C.c_double, C.POINTER(C.c_int32),
@@ -319,6 +325,24 @@ def co3_model_bias_device(plan, params, install=True, stream=None):
     if install:
         _check("co3_plan_set_bias_device", lib().co3_plan_set_bias_device(plan.handle, bias.data_ptr(), _stream(stream)))
     return bias, err
+
+
+def co3_model_scale_device(plan, params, install=True, stream=None):
+    """Exponent bias and real-valued scale per user and layer from fitted parameters (eq. (exp bias) with real b):
+    returns (int32 device tensor [U][nseg], float32 device tensor [U][nseg][2] of (gain, inv_gain), float64 device
+    tensor [U][nseg] of expected squared errors) and, with install, makes them the plan's bias and scale."""
+    import torch
+    bias = torch.zeros((plan.U, plan.nseg), dtype=torch.int32, device=params.device)
+    pairs = torch.ones((plan.U, plan.nseg, 2), dtype=torch.float32, device=params.device)
+    err = torch.zeros((plan.U, plan.nseg), dtype=torch.float64, device=params.device)
+    ws = torch.empty(int(lib().co3_plan_scale_workspace_bytes(plan.handle)), dtype=torch.uint8, device=params.device)
+    _check("co3_model_scale_device",
+           lib().co3_model_scale_device(plan.handle, params.data_ptr(), bias.data_ptr(), pairs.data_ptr(), err.data_ptr(),
+                                        ws.data_ptr(), ws.numel(), _stream(stream)))
+    if install:
+        _check("co3_plan_set_bias_device", lib().co3_plan_set_bias_device(plan.handle, bias.data_ptr(), _stream(stream)))
+        _check("co3_plan_set_gain_device", lib().co3_plan_set_gain_device(plan.handle, pairs.data_ptr(), _stream(stream)))
+    return bias, pairs, err
 
 
 def co3_scale_from_model(E, M, mu, alpha, beta):

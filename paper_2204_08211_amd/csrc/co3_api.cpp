@@ -485,6 +485,33 @@ int co3_plan_set_bias_device(co3_plan *plan, const int32_t *bias, void *stream)
                : CO3_ERR_HIP;
 }
 
+size_t co3_plan_scale_workspace_bytes(const co3_plan *plan) { return plan ? scale_workspace_bytes(plan->lay) : 0; }
+
+int co3_model_scale_device(const co3_plan *plan, const co3_gennorm_params *params, int32_t *bias, float *gain_pairs,
+                           double *error, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!plan || !params || !bias || !gain_pairs || !workspace) return CO3_ERR_ARG;
+    if (workspace_bytes < scale_workspace_bytes(plan->lay)) return CO3_ERR_CAPACITY;
+    if (plan->lay.nseg > 65535u || plan->lay.U > 65535u) return CO3_ERR_ARG;  // grid.y, grid.z
+    DeviceGuard guard(plan->device);
+    double *ws = reinterpret_cast<double *>((reinterpret_cast<uintptr_t>(workspace) + 255u) & ~(uintptr_t)255u);
+    return launch_model_scale(plan->lay, params, bias, gain_pairs, error, ws, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? CO3_OK
+               : CO3_ERR_HIP;
+}
+
+int co3_plan_set_gain_device(co3_plan *plan, const float *gain_pairs, void *stream)
+{
+    if (!plan || !gain_pairs) return CO3_ERR_ARG;
+    DeviceGuard guard(plan->device);
+    const size_t n = (size_t)plan->lay.U * plan->lay.nseg;
+    if (hipMemcpyAsync(plan->d_gain, gain_pairs, sizeof(float) * 2 * n, hipMemcpyDeviceToDevice,
+                       static_cast<hipStream_t>(stream)) != hipSuccess)
+        return CO3_ERR_HIP;
+    plan->has_gain = true;   // the values are not read back: a scale is taken to be there until the host setter says otherwise
+    return CO3_OK;
+}
+
 int co3_decode(const co3_plan *plan, const co3_decode_args *a, void *stream)
 {
     if (!plan || !a) return CO3_ERR_ARG;

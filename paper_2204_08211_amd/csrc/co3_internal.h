@@ -174,6 +174,9 @@ hipError_t launch_model_weights(const Layout &lay, const co3_gennorm_params *par
 size_t bias_workspace_bytes(const Layout &lay);
 hipError_t launch_model_bias(const Layout &lay, const co3_gennorm_params *params, int32_t *bias, double *error,
                              double *errors_ws, hipStream_t s);
+size_t scale_workspace_bytes(const Layout &lay);
+hipError_t launch_model_scale(const Layout &lay, const co3_gennorm_params *params, int32_t *bias, float *gain_pairs,
+                              double *error, double *workspace, hipStream_t s);
 hipError_t launch_decode(const Layout &lay, const co3_decode_args &a, const BookDev *books, hipStream_t s);
 hipError_t launch_aggregate(const Layout &lay, const co3_aggregate_args &a, const BookDev *books,
                             hipStream_t s);

@@ -306,6 +306,103 @@ hipError_t launch_model_bias(const Layout &lay, const co3_gennorm_params *params
     return hipGetLastError();
 }
 
+// eq. (exp bias) with b over the reals, per (user, layer), from the integer optimum found above.  A scale c = 2^t
+// on top of an integer bias turns the representative set into {c x}; its error on GenNorm(mu, alpha, beta) is c^2
+// times the error of the unscaled set on GenNorm(mu / c, alpha / c, beta), so the sum over the symbols' cells
+// serves again.  The logarithm s = t - bias of the whole scale is scanned in steps of 1/16 binade over one and a
+// half binades to either side of the integer optimum and refined by a golden-section search between the scan
+// points next to the best one; bias = -round(s), t = s + bias in [-1/2, 1/2].  One workgroup per (user, layer),
+// thread per symbol, every evaluation folded in the same fixed order: all threads see the same numbers and take
+// the same steps.  A real scale is taken only where it lowers the error by more than kBiasTie (relative).
+__global__ __launch_bounds__(kMaxA) void k_model_scale(Layout lay, const co3_gennorm_params *__restrict__ params,
+                                                       int32_t *bias_io, const double *__restrict__ err_int,
+                                                       float *__restrict__ gain_pairs, double *error_out)
+{
+    __shared__ double s_red[kMaxA];
+    const uint32_t seg = blockIdx.x, u = blockIdx.y, t = threadIdx.x;
+    const uint64_t pair = (uint64_t)u * lay.nseg + seg;
+    const co3_gennorm_params p = params[pair];
+    const int b_int = bias_io[pair];
+    const double e_int = err_int[pair];
+    int b_out = b_int;
+    float gn = 1.0f, ig = 1.0f;
+    double e_out = e_int;
+    __syncthreads();   // every thread has read the integer result before thread 0 replaces it
+    if (p.alpha > 0.0 && p.beta > 0.0) {   // the same in every thread
+        const int bmin = bias_min_supported(lay.E), bmax = kBiasMax;
+        auto split = [&](double sc, int &b, double &tt) {
+            b = (int)lround(-sc);
+            b = b < bmin ? bmin : (b > bmax ? bmax : b);
+            tt = sc + (double)b;
+        };
+        auto err_at = [&](int b, double tt) {
+            const double c = exp2(tt);
+            double e = 0.0;
+            for (uint32_t sy = t; sy < lay.A; sy += kMaxA)
+                e += sq_error_of_symbol(sy, lay.E, lay.M, b, p.mu / c, p.alpha / c, p.beta);
+            return c * c * bias_fold(s_red, t, e);
+        };
+        auto f = [&](double sc) {
+            int b;
+            double tt;
+            split(sc, b, tt);
+            return err_at(b, tt);
+        };
+        const double s0 = -(double)b_int;
+        const int kHalf = 24;
+        double best_s = s0, best_f = e_int;
+        int best_k = 0;
+        for (int k = -kHalf; k <= kHalf; ++k) {
+            const double sc = s0 + (double)k / 16.0, v = f(sc);
+            if (v < best_f) { best_f = v; best_s = sc; best_k = k; }
+        }
+        if (best_k > -kHalf && best_k < kHalf) {
+            const double r = 0.6180339887498949;
+            double a = best_s - 1.0 / 16.0, b = best_s + 1.0 / 16.0;
+            double x1 = b - r * (b - a), x2 = a + r * (b - a), f1 = f(x1), f2 = f(x2);
+            for (int it = 0; it < 60; ++it) {
+                if (f1 < f2) { b = x2; x2 = x1; f2 = f1; x1 = b - r * (b - a); f1 = f(x1); }
+                else { a = x1; x1 = x2; f1 = f2; x2 = a + r * (b - a); f2 = f(x2); }
+            }
+            const double xm = 0.5 * (a + b), fm = f(xm);
+            if (fm < best_f) { best_f = fm; best_s = xm; }
+        }
+        if (best_f < e_int * (1.0 - kBiasTie)) {
+            int b;
+            double tt;
+            split(best_s, b, tt);
+            ig = (float)exp2(tt);
+            gn = 1.0f / ig;
+            b_out = b;
+            e_out = err_at(b, log2((double)ig));   // of the fp32 pair that is returned
+        }
+    }
+    if (t == 0) {
+        bias_io[pair] = b_out;
+        gain_pairs[2 * pair] = gn;
+        gain_pairs[2 * pair + 1] = ig;
+        if (error_out) error_out[pair] = e_out;
+    }
+}
+
+// the integer search's workspace and its expected errors per pair
+size_t scale_workspace_bytes(const Layout &lay) { return bias_workspace_bytes(lay) + (size_t)lay.U * lay.nseg * sizeof(double) + 256; }
+
+hipError_t launch_model_scale(const Layout &lay, const co3_gennorm_params *params, int32_t *bias, float *gain_pairs,
+                              double *error, double *ws, hipStream_t s)
+{
+    if (lay.U == 0 || lay.nseg == 0) return hipSuccess;
+    const uint64_t pairs = (uint64_t)lay.U * lay.nseg;
+    double *err_int = ws;   // [pairs], then the integer search's own workspace (256-byte aligned again)
+    double *ws_int = reinterpret_cast<double *>((reinterpret_cast<uintptr_t>(ws + pairs) + 255u) & ~(uintptr_t)255u);
+    hipError_t e = launch_model_bias(lay, params, bias, err_int, ws_int, s);
+    if (e != hipSuccess) return e;
+    ProfScope prof(K_MODEL_BIAS, s);
+    hipLaunchKernelGGL(k_model_scale, dim3(lay.nseg, lay.U), dim3(kMaxA), 0, s, lay, params, bias, err_int, gain_pairs,
+                       error);
+    return hipGetLastError();
+}
+
 size_t fit_workspace_bytes(const Layout &lay) { return (size_t)lay.U * lay.nchunks * 4 * sizeof(double) + 256; }
 
 hipError_t launch_fit(const Layout &lay, const float *g, const float *m, uint64_t row_stride, float gamma,

@@ -1122,6 +1122,7 @@ __global__ __launch_bounds__(kWAggThreads, kPerUser ? 2 : 6) void k_aggregate_wi
     if (!kPerUser) w_load_tabs(&s_tabs[0], books[k0.book], t, nthreads);
     __syncthreads();
     WideTabs *T = &s_tabs[kPerUser ? wave : 0u];
+    const uint32_t sign_shift = (uint32_t)(lay.E + lay.M), kmask = (1u << sign_shift) - 1u, mshift = 23u - (uint32_t)lay.M;
     WUpper32 U32;
     if (!kPerUser) U32.load(T);
     for (uint32_t u = wave; u < lay.U; u += nwaves) {
@@ -1140,6 +1141,8 @@ __global__ __launch_bounds__(kWAggThreads, kPerUser ? 2 : 6) void k_aggregate_wi
         const uint64_t pair = (uint64_t)u * lay.nseg + k.seg;
         const int bias = lay.bias[pair];
         const float inv_gain = lay.gain[2 * pair + 1];
+        const bool scaled = inv_gain != 1.0f;
+        const uint32_t ebias = (uint32_t)(127 - bias) << 23;
         double *acc = s_acc + lane * kWAccStride;
         uint32_t pos = p0;
         bool bad = false;
@@ -1150,7 +1153,14 @@ __global__ __launch_bounds__(kWAggThreads, kPerUser ? 2 : 6) void k_aggregate_wi
             const uint32_t s = w_decode_one(rd, pos, T, book.sorted, U32, len);
             if (len == 0u) { bad = true; len = 1u; }
             pos += len;
-            const float val = __fmul_rn(__uint_as_float(symbol_value_bits(s, lay.E, lay.M, bias)), inv_gain);
+            // a representative of a normal binade is the symbol's exponent and mantissa fields moved to their fp32
+            // places plus the difference of the biases
+            const uint32_t k = s & kmask;
+            uint32_t vb = (k << mshift) + ebias;
+            if (k < (1u << lay.M)) vb = symbol_value_bits(k, lay.E, lay.M, bias);   // zero and the subnormal row
+            vb |= (s >> sign_shift) << 31;
+            float val = __uint_as_float(vb);
+            if (scaled) val = __fmul_rn(val, inv_gain);   // (the same in every lane)
             __hip_atomic_fetch_add(&acc[j], (double)val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
         if (bad || pos - p0 != ix.sb || !ix.ok)

@@ -38,7 +38,7 @@ def main():
     p.add_argument("--eta", type=float, default=0.2)
     p.add_argument("--stochastic", action="store_true")
     p.add_argument("--real-scale", action="store_true",
-                   help="eq. (exp bias) with real b: bias and gain of every user from co3_scale_from_model (host) at each refresh")
+                   help="eq. (exp bias) with real b: bias and gain of every user from co3_model_scale_device at each refresh")
     p.add_argument("--theorem", action="store_true", help="sweep T in the setting of Theorem 1 (gamma 1, eta 1/sqrt(T), averaged iterate)")
     a = p.parse_args()
     dev = torch.device("cuda:0")
@@ -82,11 +82,8 @@ def main():
                 gradients(w, t, g)
                 if t % a.refresh == 0:                                  # fit -> bias -> weights -> code, all on the device
                     params = B.co3_gennorm_fit(plan, g, m, gamma)
-                    if a.real_scale:                                    # the U argmins over real b run on the host
-                        ph = params.cpu().numpy()
-                        tr = [B.co3_scale_from_model(E, M, *ph[u, 0, :3])[:3] for u in range(U)]
-                        plan.set_bias(np.array([[x[0]] for x in tr], np.int32))
-                        plan.set_gain(np.array([[x[1]] for x in tr], np.float32), np.array([[x[2]] for x in tr], np.float32))
+                    if a.real_scale:                                    # the argmins over real b, on the device as well
+                        B.co3_model_scale_device(plan, params, install=True)
                     else:
                         B.co3_model_bias_device(plan, params, install=True)
                     B.co3_build_codebook_device(books, B.co3_model_weights_device(plan, params), buf.status)
