@@ -162,8 +162,11 @@ int co3_plan_create(co3_format format, uint32_t U, uint64_t d, uint32_t nseg, co
     l.A = 1u << (1 + format.exp_bits + format.mant_bits);
     l.wide = l.A > (uint32_t)kMaxA ? 1u : 0u;
     l.vec_aligned = 1u;
-    for (uint32_t k = 0; k < nseg; ++k)
+    l.tile_aligned = 1u;
+    for (uint32_t k = 0; k < nseg; ++k) {
         if (segs[k].length && (segs[k].offset & 3u)) l.vec_aligned = 0u;
+        if (segs[k].length && (segs[k].offset & 2047u)) l.tile_aligned = 0u;
+    }
     l.books_per_user = (uint32_t)max_book + 1;
     l.per_user_books = per_user_books ? 1u : 0u;
     l.nbooks = l.books_per_user * (per_user_books ? U : 1u);

@@ -95,6 +95,7 @@ struct Layout {
     uint32_t nbooks;           // tables in a set
     uint32_t wide;             // alphabet above 8 bits: 16-bit symbols, the kernels of k_wide.hip
     uint32_t vec_aligned;      // every layer starts at a multiple of 4 elements (16-byte vectors never straddle a layer start)
+    uint32_t tile_aligned;     // every layer starts at a multiple of 2048 elements (a tile of the wide quantizer lies in one chunk)
     const SegDev *segs;        // device [nseg + 1] (last entry: offset = d, chunk_start = nchunks)
     const int32_t *bias;       // device [U][nseg]
     const float *gain;         // device [U][nseg][2]: (gain, inv_gain) of the real-valued scale; (1, 1) when unused

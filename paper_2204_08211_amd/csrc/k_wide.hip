@@ -8,6 +8,7 @@
 // path) runs the same three steps here with the symbols kept in the workspace.
 //
 //   k_quantize_wide      v = g + gamma m, Q_fp, m' = v - ghat, symbol; symbol counts in an LDS table per workgroup
+//                        (and, for a held code on layers that start on its tile grid, the chunks' coded sizes)
 //   k_build_books_wide   Huffman code of a table on the device (same tie rule and canonical form as the host's):
 //                        bitonic sort, two-queue merge, depths, canonical ranks from ballots
 //   k_chunk_bits_wide    code lengths summed per chunk, lengths in LDS
@@ -105,14 +106,21 @@ typedef float wf4 __attribute__((ext_vector_type(4)));
 typedef uint32_t wu2 __attribute__((ext_vector_type(2)));
 // kSR: the stochastic conversion (dither from Philox words of (element, user, seed)) instead of the closest
 // representative.
-template <bool kSR>
+// kBits: the code is known beforehand and every layer starts at a multiple of the tile (lay.tile_aligned), so
+// that a tile lies in one chunk: the chunks' coded sizes are summed here (chunk_bits, zero on entry) and the
+// sweep over the symbols that would count them is not needed.
+template <bool kSR, bool kBits>
 __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const float *__restrict__ g, const float *m,
                                                               float *m_out, uint16_t *__restrict__ sym,
                                                               uint64_t sym_stride, uint64_t row_stride, float gamma,
                                                               uint64_t seed, uint64_t *__restrict__ hist_rep,
+                                                              const BookWide *__restrict__ books,
+                                                              uint32_t *__restrict__ chunk_bits,
                                                               uint64_t *__restrict__ status)
 {
     __shared__ uint32_t s_hist[kWideMaxA];
+    __shared__ uint32_t s_len4[kBits ? kWideMaxA / 4 : 1];   // the code lengths of the table in use, four per word
+    const uint8_t *s_len8 = reinterpret_cast<const uint8_t *>(s_len4);
     const uint32_t u = blockIdx.y;
     const float *gu = g + (uint64_t)u * row_stride;
     const float *mu = m + (uint64_t)u * row_stride;
@@ -134,6 +142,7 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
     uint32_t cur_book = 0xffffffffu;   // workgroup-uniform, like the layer of the tile's first element:
     uint32_t seg0 = 0, tile_book = 0;
     uint64_t seg_end = 0;              // where that layer ends (0: none looked up yet)
+    uint64_t seg_off = 0, seg_chunk0 = 0;   // where it starts, and its first chunk
     int bias0 = 0;
     QConst qc0 = make_qconst(lay.E, lay.M, 0);
     float gain0 = 1.0f, inv_gain0 = 1.0f;
@@ -143,6 +152,8 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
         if (base >= seg_end) {         // the tile starts in another layer than the last one did: look it up
             seg0 = w_find_segment(lay.segs, lay.nseg, base);
             seg_end = lay.segs[seg0 + 1].offset;
+            seg_off = lay.segs[seg0].offset;
+            seg_chunk0 = lay.segs[seg0].chunk_start;
             tile_book = book_base + (uint32_t)lay.segs[seg0].book;
             const uint64_t pair0 = (uint64_t)u * lay.nseg + seg0;
             bias0 = lay.bias[pair0];
@@ -153,9 +164,21 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
         if (tile_book != cur_book) {
             __syncthreads();
             if (cur_book != 0xffffffffu) flush(cur_book);
+            if constexpr (kBits) {
+                const uint32_t *len4 = reinterpret_cast<const uint32_t *>(books[tile_book].len);
+                for (uint32_t i = threadIdx.x; i < (uint32_t)kWideMaxA / 4; i += kWqThreads) s_len4[i] = len4[i];
+            }
             __syncthreads();
             cur_book = tile_book;
         }
+        uint32_t tile_bits = 0;        // code lengths of this thread's elements of the tile
+        auto add_tile_bits = [&]() {   // by every wavefront, once per tile
+            if constexpr (kBits) {
+                const uint32_t sum = w_wave_sum(tile_bits);
+                if ((threadIdx.x & 63u) == 0u && sum)
+                    atomicAdd(&chunk_bits[(uint64_t)u * lay.nchunks + seg_chunk0 + ((base - seg_off) >> 12)], sum);
+            }
+        };
         // the scale and the quantizer's constants of the tile's first layer serve the whole tile unless it
         // crosses into the next layer
         const uint64_t tile_end = base + kWqTile < lay.d ? base + kWqTile : lay.d;
@@ -191,6 +214,7 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
                     n_clamped += (flags >> 1) & 1u;
                     sp[j] = s;
                     atomicAdd(&s_hist[s & (kWideMaxA - 1)], 1u);
+                    if constexpr (kBits) tile_bits += s_len8[s & (kWideMaxA - 1)];
                 }
                 __builtin_nontemporal_store(eo, reinterpret_cast<wf4 *>(mo + i));
                 wu2 packed;
@@ -198,6 +222,7 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
                 packed[1] = sp[2] | (sp[3] << 16);
                 __builtin_nontemporal_store(packed, reinterpret_cast<wu2 *>(su + i));
             }
+            add_tile_bits();
             continue;   // workgroup-uniform
         }
         float gv[kWqPer], mv[kWqPer];   // the tile's loads are issued together
@@ -240,7 +265,9 @@ __global__ __launch_bounds__(kWqThreads) void k_quantize_wide(Layout lay, const 
             su[i] = (uint16_t)s;
             if (book == cur_book) atomicAdd(&s_hist[s & (kWideMaxA - 1)], 1u);
             else atomicAdd(reinterpret_cast<unsigned long long *>(hist + (uint64_t)book * lay.A + s), 1ull);
+            if constexpr (kBits) tile_bits += s_len8[s & (kWideMaxA - 1)];   // (aligned layers: the tile's own table)
         }
+        add_tile_bits();
     }
     __syncthreads();
     if (cur_book != 0xffffffffu) flush(cur_book);
@@ -1219,19 +1246,29 @@ hipError_t launch_encode_wide(const Layout &lay, const co3_encode_args &a, BookW
     // a fixed code without a symbol buffer: the symbols (and their counts, unused) stay in the workspace
     uint16_t *sym = a.symbols ? reinterpret_cast<uint16_t *>(a.symbols) : ws_sym;
     uint64_t *hist = a.hist ? a.hist : ws_hist;
+    // a code that is held and layers on the quantizer's tile grid: the chunks' sizes come out of the first sweep
+    const bool bits_in_sweep = a.mode == CO3_BOOK_FIXED && lay.tile_aligned && lay.nchunks;
     {
+        // the partial counts and, behind them in the workspace, the chunk sizes the sweep adds to
+        const uint64_t zero_n = bits_in_sweep ? (w_up256(hist_rep_n * sizeof(uint64_t)) + w_up256((size_t)lay.U * lay.nchunks * sizeof(uint32_t))) / sizeof(uint64_t)
+                                              : hist_rep_n;
         ProfScope prof(K_ZERO, s);
-        hipLaunchKernelGGL(k_zero_wide, dim3((uint32_t)((hist_rep_n + 255) / 256)), dim3(256), 0, s, hist_rep, hist_rep_n);
+        hipLaunchKernelGGL(k_zero_wide, dim3((uint32_t)((zero_n + 255) / 256)), dim3(256), 0, s, hist_rep, zero_n);
     }
     if (lay.d) {
         ProfScope prof(K_QUANTIZE, s);
         const dim3 grid((uint32_t)((lay.d + (uint64_t)kWqTile * kWqTiles - 1) / ((uint64_t)kWqTile * kWqTiles)), lay.U);
-        if (a.rounding == CO3_ROUND_STOCHASTIC)
-            hipLaunchKernelGGL(k_quantize_wide<true>, grid, dim3(kWqThreads), 0, s, lay, a.g, a.m, a.m_out, sym, sym_stride,
-                               a.row_stride, a.gamma, a.seed, hist_rep, a.status);
-        else
-            hipLaunchKernelGGL(k_quantize_wide<false>, grid, dim3(kWqThreads), 0, s, lay, a.g, a.m, a.m_out, sym, sym_stride,
-                               a.row_stride, a.gamma, a.seed, hist_rep, a.status);
+        auto launch = [&](auto kernel) {
+            hipLaunchKernelGGL(kernel, grid, dim3(kWqThreads), 0, s, lay, a.g, a.m, a.m_out, sym, sym_stride, a.row_stride,
+                               a.gamma, a.seed, hist_rep, static_cast<const BookWide *>(books), chunk_bits, a.status);
+        };
+        if (a.rounding == CO3_ROUND_STOCHASTIC) {
+            if (bits_in_sweep) launch(k_quantize_wide<true, true>);
+            else launch(k_quantize_wide<true, false>);
+        } else {
+            if (bits_in_sweep) launch(k_quantize_wide<false, true>);
+            else launch(k_quantize_wide<false, false>);
+        }
     }
     {
         ProfScope prof(K_REDUCE_HIST, s);
@@ -1242,7 +1279,7 @@ hipError_t launch_encode_wide(const Layout &lay, const co3_encode_args &a, BookW
         if (e != hipSuccess) return e;
     }
     const uint32_t gx = (uint32_t)((lay.nchunks + kWChunksPerWg - 1) / kWChunksPerWg);
-    if (lay.nchunks) {
+    if (lay.nchunks && !bits_in_sweep) {
         ProfScope prof(K_CHUNK_BITS, s);
         hipLaunchKernelGGL(k_chunk_bits_wide, dim3(gx, lay.U), dim3(kWThreads), 0, s, lay, sym, sym_stride, books, chunk_bits);
     }

@@ -702,6 +702,42 @@ def test_wide_alphabets_both_encoders(E, M, d):
         gu.assert_bits_equal(buf.words[u, :wds.size].cpu().numpy().view(np.uint32), wds, f"bitstream of user {u}")
 
 
+@pytest.mark.parametrize("stochastic", [False, True])
+def test_wide_held_code_with_layers_on_the_tile_grid(stochastic):
+    # layers that start at multiples of 2048 elements (the held code's chunk sizes are then summed in the first
+    # sweep): one of two chunks, one of half a chunk, an empty one, one with another table and a ragged end; a
+    # symbol without a code among them
+    import torch
+    from paper_2204_08211_amd import binding as B
+    E, M, U = 4, 5, 3
+    A = 1 << (1 + E + M)
+    seg_len = [4096 * 2, 2048, 0, 4096 + 2048 + 100]
+    seg_book = [0, 1, 0, 1]
+    d = sum(seg_len)
+    rng = np.random.default_rng(2100)
+    bias = rng.integers(10, 14, (U, 4)).astype(np.int32)
+    g = np.empty((U, d), np.float32); m = np.empty((U, d), np.float32)
+    off = 0
+    for k, n in enumerate(seg_len):
+        for u in range(U):
+            top = orc.grid(E, M, int(bias[u, k]))[-1]
+            g[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, top / 50)
+            m[u, off:off + n] = syn.gennorm_numpy(rng, n, 1.0, top / 300)
+        off += n
+    kw = dict(E=E, M=M, U=U, d=d, bias=bias, seg_len=seg_len, seg_book=seg_book)
+    seed = 77 if stochastic else None
+    first = gu.oracle_round(kw, g, m, 0.9, stochastic_seed=seed)            # its histograms are the held code's weights
+    ref = gu.oracle_round(kw, g, m, 0.9, weights=first["hist"], stochastic_seed=seed)
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=first["hist"], max_code_len=40, stochastic_seed=seed)
+    gu.compare_round(gpu, ref, d)
+    assert int(gpu["status_encode"][B.STAT_NOCODE]) == 0
+    w0 = first["hist"].copy()
+    victim = int(np.argsort(w0[1])[-5])
+    w0[1, victim] = 0
+    gpu, _ = gu.gpu_round(kw, g, m, 0.9, BOOK_FIXED, weights=w0, max_code_len=40, want_decode=False, stochastic_seed=seed)
+    assert int(gpu["status_encode"][B.STAT_NOCODE]) == int(first["hist"][1, victim])
+
+
 @pytest.mark.parametrize("U,per_user", [(1, False), (17, False), (9, True)])
 def test_wide_user_counts_through_the_average(U, per_user):
     # one user; more users than a workgroup of the average has wavefronts (several passes per wavefront), with one
