@@ -973,7 +973,6 @@ struct WReader {
     }
 };
 
-constexpr int kWRowsWave = kSubsPerChunk * kWSymRow;   // 16-bit units of a wavefront's 64 rows of decoded symbols
 constexpr int kWUpRegs = 12;   // lengths kWideDecBits + 1 .. kWideDecBits + 12 have their bound in a register
 
 // The bounds of lengths kWideDecBits + 1 .. kWideDecBits + kWUpRegs, top 32 bits (exact: a bound of length
@@ -1060,32 +1059,42 @@ __device__ inline WIndex w_read_index(const Layout &lay, uint64_t c, uint32_t u,
     return ix;
 }
 
-__global__ __launch_bounds__(kWThreads) void k_decode_wide(Layout lay, const uint32_t *__restrict__ words,
-                                                          uint64_t words_stride,
-                                                          const uint64_t *__restrict__ chunk_offset,
-                                                          const uint16_t *__restrict__ sub_bits,
-                                                          const BookWide *__restrict__ books, uint16_t *__restrict__ sym,
-                                                          uint64_t sym_stride, float *__restrict__ q, uint64_t q_stride,
-                                                          uint64_t *__restrict__ status)
+constexpr int kWDecWaves = 8;          // wavefronts of a decode workgroup with one set of code tables for all users
+constexpr int kWDecWavesPerUser = 4;   // and with a set per user (a table per wavefront in LDS)
+constexpr int kWDecBlock = 32;         // symbols a lane decodes between two copies to device memory
+constexpr int kWDecRow = kWDecBlock + 2;                  // 16-bit units of a lane's row: 17 words, odd
+constexpr int kWDecRowsWave = kSubsPerChunk * kWDecRow;   // 16-bit units of a wavefront's 64 rows
+static_assert(kSub % kWDecBlock == 0 && (kWDecRowsWave * sizeof(uint16_t)) % 8 == 0, "blocks per sub-chunk, table alignment");
+
+__global__ __launch_bounds__(64 * kWDecWaves) void k_decode_wide(Layout lay, const uint32_t *__restrict__ words,
+                                                                uint64_t words_stride,
+                                                                const uint64_t *__restrict__ chunk_offset,
+                                                                const uint16_t *__restrict__ sub_bits,
+                                                                const BookWide *__restrict__ books, uint16_t *__restrict__ sym,
+                                                                uint64_t sym_stride, float *__restrict__ q, uint64_t q_stride,
+                                                                uint64_t *__restrict__ status)
 {
-    // The wavefronts of a workgroup decode the same chunk of four users: with one set of code tables for all
+    // The wavefronts of a workgroup decode the same chunk of as many users: with one set of code tables for all
     // users they share one copy of the chunk's table, else each keeps its own.  A lane decodes its sub-chunk
-    // into a row of LDS; the rows then go out in element order, 64 consecutive elements per store.
+    // kWDecBlock symbols at a time into a row of LDS (rows for all 64 symbols would leave room for 12 wavefronts
+    // per CU; blocks of 16 for 32, but store 32 bytes at a time); after each block the rows go out in element
+    // order, 32 consecutive elements per row and 2 rows per store.
     extern __shared__ uint64_t wd_smem[];
-    uint16_t *s_rows = reinterpret_cast<uint16_t *>(wd_smem);                                // [kWWaves][64 rows]
-    WideTabs *s_tabs = reinterpret_cast<WideTabs *>(s_rows + kWWaves * kWRowsWave);           // [1 or kWWaves]
+    const uint32_t nthreads = blockDim.x, nwaves = blockDim.x >> 6;
+    uint16_t *s_rows = reinterpret_cast<uint16_t *>(wd_smem);                                // [nwaves][64 rows]
+    WideTabs *s_tabs = reinterpret_cast<WideTabs *>(s_rows + nwaves * kWDecRowsWave);         // [1 or nwaves]
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint64_t c = blockIdx.x;
-    const uint32_t u = blockIdx.y * kWWaves + wave;
+    const uint32_t u = blockIdx.y * nwaves + wave;
     if (!lay.per_user_books) {
-        w_load_tabs(&s_tabs[0], books[w_chunk(lay, c, 0).book], threadIdx.x, kWThreads);
+        w_load_tabs(&s_tabs[0], books[w_chunk(lay, c, 0).book], threadIdx.x, nthreads);
         __syncthreads();
     }
     if (u >= lay.U) return;  // whole wavefront; wavefront-level synchronisation only below
     const WChunk k = w_chunk(lay, c, u);
     const BookWide &book = books[k.book];
     WideTabs *T = &s_tabs[lay.per_user_books ? wave : 0u];
-    uint16_t *rows = s_rows + wave * kWRowsWave;
+    uint16_t *rows = s_rows + wave * kWDecRowsWave;
     const WIndex ix = w_read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits, lane);
     if (lay.per_user_books) w_load_tabs(T, book, lane, 64);
     w_wave_sync_lds();
@@ -1101,23 +1110,31 @@ __global__ __launch_bounds__(kWThreads) void k_decode_wide(Layout lay, const uin
     bool bad = false;
     WReader<WGlobalWords> rd{WGlobalWords{ix.w, ix.nw}, 0u, 0u, 0u, 0u, 0u};
     rd.seek(p0);
-    for (int j = 0; j < cnt; ++j) {
-        uint32_t len;
-        const uint32_t s = w_decode_one(rd, pos, T, book.sorted, U32, len);
-        if (len == 0u) { bad = true; len = 1u; }
-        pos += len;
-        rows[lane * kWSymRow + j] = (uint16_t)s;
+    const uint32_t col = lane & (uint32_t)(kWDecBlock - 1), rsub = lane / (uint32_t)kWDecBlock;   // of the copy
+    for (int blk = 0; blk < kSub / kWDecBlock; ++blk) {
+        if ((uint32_t)(blk * kWDecBlock) >= k.n) break;   // wavefront-uniform: no lane has a symbol left
+        for (int jj = 0; jj < kWDecBlock; ++jj) {
+            if (blk * kWDecBlock + jj < cnt) {
+                uint32_t len;
+                const uint32_t s = w_decode_one(rd, pos, T, book.sorted, U32, len);
+                if (len == 0u) { bad = true; len = 1u; }
+                pos += len;
+                rows[lane * kWDecRow + jj] = (uint16_t)s;
+            }
+        }
+        w_wave_sync_lds();
+        for (uint32_t r = rsub; r < (uint32_t)kSubsPerChunk; r += 64u / (uint32_t)kWDecBlock) {
+            const uint32_t e = 64u * r + (uint32_t)(blk * kWDecBlock) + col;   // element of the chunk
+            if (e < k.n) {
+                const uint32_t s = rows[r * kWDecRow + col];
+                if (sym) sym[(uint64_t)u * sym_stride + k.e0 + e] = (uint16_t)s;
+                if (q) q[(uint64_t)u * q_stride + k.e0 + e] = __fmul_rn(__uint_as_float(symbol_value_bits(s, lay.E, lay.M, bias)), inv_gain);
+            }
+        }
+        w_wave_sync_lds();   // the rows are free again
     }
     if (bad || pos - p0 != ix.sb || !ix.ok)
         atomicAdd(reinterpret_cast<unsigned long long *>(status + CO3_STAT_CORRUPT), 1ull);
-    w_wave_sync_lds();
-    for (uint32_t r = 0; r < (uint32_t)kSubsPerChunk; ++r) {   // row r = elements 64 r .. 64 r + 63 of the chunk
-        const uint32_t e = 64u * r + lane;
-        if (e >= k.n) break;
-        const uint32_t s = rows[r * kWSymRow + lane];
-        if (sym) sym[(uint64_t)u * sym_stride + k.e0 + e] = (uint16_t)s;
-        if (q) q[(uint64_t)u * q_stride + k.e0 + e] = __fmul_rn(__uint_as_float(symbol_value_bits(s, lay.E, lay.M, bias)), inv_gain);
-    }
 }
 
 constexpr int kWAccStride = kSub + 1;
@@ -1300,14 +1317,14 @@ hipError_t launch_decode_wide(const Layout &lay, const co3_decode_args &a, const
 {
     if (lay.U == 0 || lay.nchunks == 0) return hipSuccess;
     const uint64_t sym_stride = symbol_row_stride(lay.d);
-    const size_t lds_fixed = (size_t)kWWaves * kWRowsWave * sizeof(uint16_t);
+    const uint32_t nwaves = lay.per_user_books ? kWDecWavesPerUser : kWDecWaves;
+    const size_t lds = (size_t)nwaves * kWDecRowsWave * sizeof(uint16_t) +
+                       (lay.per_user_books ? (size_t)nwaves : 1u) * sizeof(WideTabs);   // 52 KB, or 87 KB with a set per user
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_decode_wide),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)(lds_fixed + (size_t)kWWaves * sizeof(WideTabs)));   // 103 KB at most
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    const size_t lds_used = lds_fixed + (lay.per_user_books ? (size_t)kWWaves : 1u) * sizeof(WideTabs);
     ProfScope prof(K_DECODE, s);
-    hipLaunchKernelGGL(k_decode_wide, dim3((uint32_t)lay.nchunks, (lay.U + kWWaves - 1) / kWWaves), dim3(kWThreads), lds_used, s,
+    hipLaunchKernelGGL(k_decode_wide, dim3((uint32_t)lay.nchunks, (lay.U + nwaves - 1) / nwaves), dim3(64 * nwaves), lds, s,
                        lay, a.words, a.words_stride, a.chunk_offset, a.sub_bits, books,
                        reinterpret_cast<uint16_t *>(a.symbols), sym_stride, a.q, a.q_stride, a.status);
     return hipGetLastError();
