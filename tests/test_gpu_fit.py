@@ -224,12 +224,13 @@ def test_model_bias_on_the_device_and_a_round_with_it(E, M):
     assert st[B.STAT_CLAMPED] < 1e-3 * U * d
 
 
-@pytest.mark.parametrize("E,M", [(2, 1), (3, 2), (4, 3), (5, 2), (4, 5)])
+@pytest.mark.parametrize("E,M", [(2, 1), (3, 2), (4, 3), (5, 2), (4, 5), (5, 6)])
 def test_real_valued_scale_on_the_device_and_a_round_with_it(E, M):
     # eq. (exp bias) with real b for every (user, layer) on the device: against the oracle's evaluation of the
     # returned triple, the oracle's own optimum over real b, the library's host routine; a layer without a model;
     # then bias and scale installed from device memory and a whole round under them, against the oracle's
-    # scaled conversion.  (5, 2): many binades, the integer bias stays where no real scale gains.  (4, 5): 10 bits
+    # scaled conversion.  (5, 2): many binades, the integer bias stays where no real scale gains.  (4, 5), (5, 6): 10
+    # and 12 bits
     import math
     import torch
     from scipy import special
