@@ -126,6 +126,18 @@ def test_real_scale_objective_equals_monte_carlo_and_beats_the_integers(E, M, be
     assert abs(bm.expected_sq_error_of_set(rebuilt, 0.0, alpha, beta) / err - 1.0) < 1e-5
 
 
+@pytest.mark.parametrize("E,M,beta,shift", [(2, 1, 1.0, 0.3), (3, 2, 1.4, -0.8)])
+def test_real_scale_objective_with_a_mean_equals_monte_carlo(E, M, beta, shift):
+    # the closed form for a source whose mean is not zero (layers with a bias in their gradients), at two scales
+    alpha = unit_variance_alpha(beta)
+    reps = bm.signed_set(E, M, (1 << (E - 1)) - 1)
+    x = syn.gennorm_numpy(np.random.default_rng(5), 2_000_000, beta, alpha).astype(np.float64) + shift
+    for b in (-1.0, 0.37):
+        assert abs(bm.monte_carlo_sq_error(reps, b, x) / bm.scaled_sq_error(reps, b, shift, alpha, beta) - 1.0) < 0.02
+    # and moving the mean changes it
+    assert abs(bm.scaled_sq_error(reps, 0.37, shift, alpha, beta) / bm.scaled_sq_error(reps, 0.37, 0.0, alpha, beta) - 1.0) > 0.02
+
+
 def test_printed_fp8_polynomial_as_a_gain_lies_on_the_flat_bottom():
     E, M, coef = printed_polynomials()["fp8"]
     reps = bm.signed_set(E, M, (1 << (E - 1)) - 1)
