@@ -899,28 +899,35 @@ __global__ __launch_bounds__(kWThreads, 3) void k_pack_wide(Layout lay, const ui
 // ---- PS side ----------------------------------------------------------------------------------------------
 
 // What the decoder keeps in LDS of one table; the symbols in canonical order, which only the search for a code
-// that neither table holds needs, stay in device memory.
+// that neither table holds needs, stay in device memory.  The second-level tables come last: a wavefront that
+// keeps a table of its own (a set of tables per user) leaves them out - kWTabsShort bytes per table, so that
+// twice as many wavefronts fit a CU - and finds every code of more than kWideDecBits bits by value.
 struct WideTabs {
     uint16_t dec[1 << kWideDecBits];
-    uint16_t dec2[kWideDec2Tables << kWideDec2Bits];
     uint64_t first[65];
     uint64_t upper[65];    // (first[L] + count[L]) left-aligned in 64 bits: every code of L or fewer bits lies below
     uint32_t count[65];
     uint32_t offset[65];
     uint32_t maxlen;
     uint32_t long_prefix0;
+    uint16_t dec2[kWideDec2Tables << kWideDec2Bits];
 };
+constexpr size_t kWTabsShort = offsetof(WideTabs, dec2);
+static_assert(kWTabsShort % 8 == 0 && sizeof(WideTabs) % 8 == 0, "tables follow each other in LDS");
 
+template <bool kDec2>
 __device__ inline void w_load_tabs(WideTabs *T, const BookWide &book, uint32_t t, uint32_t nthreads)
 {
     const uint32_t *src = reinterpret_cast<const uint32_t *>(book.dec);   // two entries per word
     uint32_t *dst = reinterpret_cast<uint32_t *>(T->dec);
 #pragma unroll 8
     for (uint32_t i = t; i < (1u << kWideDecBits) / 2; i += nthreads) dst[i] = src[i];
-    src = reinterpret_cast<const uint32_t *>(book.dec2);
-    dst = reinterpret_cast<uint32_t *>(T->dec2);
+    if constexpr (kDec2) {
+        src = reinterpret_cast<const uint32_t *>(book.dec2);
+        dst = reinterpret_cast<uint32_t *>(T->dec2);
 #pragma unroll 8
-    for (uint32_t i = t; i < (uint32_t)(kWideDec2Tables << kWideDec2Bits) / 2; i += nthreads) dst[i] = src[i];
+        for (uint32_t i = t; i < (uint32_t)(kWideDec2Tables << kWideDec2Bits) / 2; i += nthreads) dst[i] = src[i];
+    }
 #pragma unroll 1
     for (uint32_t i = t; i < 65u; i += nthreads) {
         const uint64_t f = book.first[i];
@@ -989,7 +996,7 @@ struct WUpper32 {
     }
 };
 
-template <class Src>
+template <bool kDec2, class Src>
 __device__ inline uint32_t w_decode_one(WReader<Src> &r, uint32_t pos, const WideTabs *T, const uint16_t *__restrict__ sorted,
                                         const WUpper32 &U32, uint32_t &len)
 {
@@ -997,10 +1004,12 @@ __device__ inline uint32_t w_decode_one(WReader<Src> &r, uint32_t pos, const Wid
     const uint32_t prefix = hi >> (32 - kWideDecBits);
     const uint32_t e = T->dec[prefix];
     if (e) { len = e >> 12; return e & 0xfffu; }
-    const uint32_t tab = prefix - T->long_prefix0;   // wraps below it: no table
-    if (tab < (uint32_t)kWideDec2Tables) {
-        const uint32_t e2 = T->dec2[(tab << kWideDec2Bits) | ((hi >> (32 - kWideDecBits - kWideDec2Bits)) & ((1u << kWideDec2Bits) - 1u))];
-        if (e2) { len = kWideDecBits + (e2 >> 12); return e2 & 0xfffu; }
+    if constexpr (kDec2) {
+        const uint32_t tab = prefix - T->long_prefix0;   // wraps below it: no table
+        if (tab < (uint32_t)kWideDec2Tables) {
+            const uint32_t e2 = T->dec2[(tab << kWideDec2Bits) | ((hi >> (32 - kWideDecBits - kWideDec2Bits)) & ((1u << kWideDec2Bits) - 1u))];
+            if (e2) { len = kWideDecBits + (e2 >> 12); return e2 & 0xfffu; }
+        }
     }
     const uint32_t maxlen = T->maxlen;   // <= 64
     len = 0;
@@ -1066,6 +1075,7 @@ constexpr int kWDecRow = kWDecBlock + 2;                  // 16-bit units of a l
 constexpr int kWDecRowsWave = kSubsPerChunk * kWDecRow;   // 16-bit units of a wavefront's 64 rows
 static_assert(kSub % kWDecBlock == 0 && (kWDecRowsWave * sizeof(uint16_t)) % 8 == 0, "blocks per sub-chunk, table alignment");
 
+template <bool kPerUser>
 __global__ __launch_bounds__(64 * kWDecWaves) void k_decode_wide(Layout lay, const uint32_t *__restrict__ words,
                                                                 uint64_t words_stride,
                                                                 const uint64_t *__restrict__ chunk_offset,
@@ -1082,21 +1092,21 @@ __global__ __launch_bounds__(64 * kWDecWaves) void k_decode_wide(Layout lay, con
     extern __shared__ uint64_t wd_smem[];
     const uint32_t nthreads = blockDim.x, nwaves = blockDim.x >> 6;
     uint16_t *s_rows = reinterpret_cast<uint16_t *>(wd_smem);                                // [nwaves][64 rows]
-    WideTabs *s_tabs = reinterpret_cast<WideTabs *>(s_rows + nwaves * kWDecRowsWave);         // [1 or nwaves]
+    unsigned char *s_tabs = reinterpret_cast<unsigned char *>(s_rows + nwaves * kWDecRowsWave);   // one table, or nwaves short ones
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint64_t c = blockIdx.x;
     const uint32_t u = blockIdx.y * nwaves + wave;
-    if (!lay.per_user_books) {
-        w_load_tabs(&s_tabs[0], books[w_chunk(lay, c, 0).book], threadIdx.x, nthreads);
+    if (!kPerUser) {
+        w_load_tabs<true>(reinterpret_cast<WideTabs *>(s_tabs), books[w_chunk(lay, c, 0).book], threadIdx.x, nthreads);
         __syncthreads();
     }
     if (u >= lay.U) return;  // whole wavefront; wavefront-level synchronisation only below
     const WChunk k = w_chunk(lay, c, u);
     const BookWide &book = books[k.book];
-    WideTabs *T = &s_tabs[lay.per_user_books ? wave : 0u];
+    WideTabs *T = reinterpret_cast<WideTabs *>(s_tabs + (kPerUser ? wave * kWTabsShort : 0u));
     uint16_t *rows = s_rows + wave * kWDecRowsWave;
     const WIndex ix = w_read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits, lane);
-    if (lay.per_user_books) w_load_tabs(T, book, lane, 64);
+    if (kPerUser) w_load_tabs<false>(T, book, lane, 64);
     w_wave_sync_lds();
     WUpper32 U32;
     U32.load(T);
@@ -1116,7 +1126,7 @@ __global__ __launch_bounds__(64 * kWDecWaves) void k_decode_wide(Layout lay, con
         for (int jj = 0; jj < kWDecBlock; ++jj) {
             if (blk * kWDecBlock + jj < cnt) {
                 uint32_t len;
-                const uint32_t s = w_decode_one(rd, pos, T, book.sorted, U32, len);
+                const uint32_t s = w_decode_one<!kPerUser>(rd, pos, T, book.sorted, U32, len);
                 if (len == 0u) { bad = true; len = 1u; }
                 pos += len;
                 rows[lane * kWDecRow + jj] = (uint16_t)s;
@@ -1157,15 +1167,15 @@ __global__ __launch_bounds__(kWAggThreads, kPerUser ? 2 : 6) void k_aggregate_wi
 {
     extern __shared__ uint64_t wa_smem[];
     double *s_acc = reinterpret_cast<double *>(wa_smem);                      // [64][kWAccStride]
-    WideTabs *s_tabs = reinterpret_cast<WideTabs *>(s_acc + kWAccWords);      // [tabs_per_wg]
+    unsigned char *s_tabs = reinterpret_cast<unsigned char *>(s_acc + kWAccWords);   // one table, or a short one per wavefront
     const uint32_t t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const uint64_t c = blockIdx.x;
     const WChunk k0 = w_chunk(lay, c, 0);
     const uint32_t nthreads = blockDim.x, nwaves = blockDim.x >> 6;
     for (uint32_t i = t; i < (uint32_t)kWAccWords; i += nthreads) s_acc[i] = 0.0;
-    if (!kPerUser) w_load_tabs(&s_tabs[0], books[k0.book], t, nthreads);
+    if (!kPerUser) w_load_tabs<true>(reinterpret_cast<WideTabs *>(s_tabs), books[k0.book], t, nthreads);
     __syncthreads();
-    WideTabs *T = &s_tabs[kPerUser ? wave : 0u];
+    WideTabs *T = reinterpret_cast<WideTabs *>(s_tabs + (kPerUser ? wave * kWTabsShort : 0u));
     const uint32_t sign_shift = (uint32_t)(lay.E + lay.M), kmask = (1u << sign_shift) - 1u, mshift = 23u - (uint32_t)lay.M;
     WUpper32 U32;
     if (!kPerUser) U32.load(T);
@@ -1175,7 +1185,7 @@ __global__ __launch_bounds__(kWAggThreads, kPerUser ? 2 : 6) void k_aggregate_wi
         const WIndex ix = w_read_index(lay, c, u, words, words_stride, chunk_offset, sub_bits, lane);
         if (kPerUser) {
             w_wave_sync_lds();   // the previous user's table has been read
-            w_load_tabs(T, book, lane, 64);
+            w_load_tabs<false>(T, book, lane, 64);
             w_wave_sync_lds();
             U32.load(T);
         }
@@ -1194,7 +1204,7 @@ __global__ __launch_bounds__(kWAggThreads, kPerUser ? 2 : 6) void k_aggregate_wi
         rd.seek(p0);
         for (int j = 0; j < cnt; ++j) {
             uint32_t len;
-            const uint32_t s = w_decode_one(rd, pos, T, book.sorted, U32, len);
+            const uint32_t s = w_decode_one<!kPerUser>(rd, pos, T, book.sorted, U32, len);
             if (len == 0u) { bad = true; len = 1u; }
             pos += len;
             // a representative of a normal binade is the symbol's exponent and mantissa fields moved to their fp32
@@ -1319,14 +1329,19 @@ hipError_t launch_decode_wide(const Layout &lay, const co3_decode_args &a, const
     const uint64_t sym_stride = symbol_row_stride(lay.d);
     const uint32_t nwaves = lay.per_user_books ? kWDecWavesPerUser : kWDecWaves;
     const size_t lds = (size_t)nwaves * kWDecRowsWave * sizeof(uint16_t) +
-                       (lay.per_user_books ? (size_t)nwaves : 1u) * sizeof(WideTabs);   // 52 KB, or 87 KB with a set per user
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_decode_wide),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                       (lay.per_user_books ? (size_t)nwaves * kWTabsShort : sizeof(WideTabs));   // 52 KB, or 55 KB with a set per user
+    const void *fn = lay.per_user_books ? reinterpret_cast<const void *>(&k_decode_wide<true>)
+                                        : reinterpret_cast<const void *>(&k_decode_wide<false>);
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     ProfScope prof(K_DECODE, s);
-    hipLaunchKernelGGL(k_decode_wide, dim3((uint32_t)lay.nchunks, (lay.U + nwaves - 1) / nwaves), dim3(64 * nwaves), lds, s,
-                       lay, a.words, a.words_stride, a.chunk_offset, a.sub_bits, books,
-                       reinterpret_cast<uint16_t *>(a.symbols), sym_stride, a.q, a.q_stride, a.status);
+    const dim3 grid((uint32_t)lay.nchunks, (lay.U + nwaves - 1) / nwaves);
+    if (lay.per_user_books)
+        hipLaunchKernelGGL(k_decode_wide<true>, grid, dim3(64 * nwaves), lds, s, lay, a.words, a.words_stride, a.chunk_offset,
+                           a.sub_bits, books, reinterpret_cast<uint16_t *>(a.symbols), sym_stride, a.q, a.q_stride, a.status);
+    else
+        hipLaunchKernelGGL(k_decode_wide<false>, grid, dim3(64 * nwaves), lds, s, lay, a.words, a.words_stride, a.chunk_offset,
+                           a.sub_bits, books, reinterpret_cast<uint16_t *>(a.symbols), sym_stride, a.q, a.q_stride, a.status);
     return hipGetLastError();
 }
 
@@ -1334,10 +1349,10 @@ hipError_t launch_aggregate_wide(const Layout &lay, const co3_aggregate_args &a,
 {
     if (lay.U == 0 || lay.nchunks == 0) return hipSuccess;
     const uint32_t nwaves = lay.per_user_books ? kWAggWavesPerUser : kWAggWaves;
-    const size_t lds = (size_t)kWAccWords * sizeof(double) + (lay.per_user_books ? (size_t)nwaves : 1u) * sizeof(WideTabs);
+    const size_t lds = (size_t)kWAccWords * sizeof(double) + (lay.per_user_books ? (size_t)nwaves * kWTabsShort : sizeof(WideTabs));
     const void *fn = lay.per_user_books ? reinterpret_cast<const void *>(&k_aggregate_wide<true>)
                                         : reinterpret_cast<const void *>(&k_aggregate_wide<false>);
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);   // 103 KB or 50 KB
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);   // 71 KB or 50 KB
     if (e != hipSuccess) return e;
     ProfScope prof(K_AGGREGATE, s);
     if (lay.per_user_books)
